@@ -1,0 +1,273 @@
+"""CPU oracle (float64, numpy) for one T5.1.1-style Transformer block and Adafactor.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference that the HIP
+path is checked against.  It shares no code with the HIP path, imports nothing
+from it, and may be imported only by tests, the smoke check and the bench's
+CPU-baseline leg.  It is never a fallback for the product path.
+
+What it follows.  The paper (Sec. 4, "Example models") ships "T5.1.1" and a
+decoder-only configuration as its models and Sec. 2.3 says they are ordinary
+Flax modules, but it prints no formula for any layer.  Every formula below is
+therefore the public definition of the named layer, written out in full:
+
+  * T5 layer norm: scale-only RMS norm, no mean subtraction, no bias.
+  * Self-attention whose logits get a learned bias looked up from a table by
+    the *bucket* of (key position - query position); no 1/sqrt(d_kv) factor
+    unless the caller asks for one through attn_scale.
+  * T5.1.1 feed-forward: gated GELU (tanh form), no biases.
+  * Pre-norm residual wiring: h = x + Attn(Norm(x)); y = h + MLP(Norm(h)).
+  * Adafactor with factored second moments and update clipping, no momentum.
+
+The result has a plain definition, so the oracle *is* that definition: the
+S x S score matrix is materialised, softmax is the ordinary two-pass form, and
+the backward pass is the hand-derived chain rule written term by term.  The
+only library primitive used as a step is numpy's matmul.
+
+All functions take and return float64 arrays.
+"""
+from __future__ import annotations
+
+import math
+import numpy as np
+
+GELU_KAPPA = math.sqrt(2.0 / math.pi)
+GELU_BETA = 0.044715
+
+
+# --------------------------------------------------------------------------------------
+# Relative-position buckets (integer, exact)
+# --------------------------------------------------------------------------------------
+def relpos_bucket_scalar(rel_pos: int, bidirectional: bool, num_buckets: int = 32,
+                         max_distance: int = 128) -> int:
+    """Bucket of one relative position rel_pos = key_position - query_position.
+
+    T5 definition.  Half of the buckets (per sign when bidirectional) are exact
+    offsets; the other half are logarithmically spaced up to max_distance, and
+    everything beyond shares the last bucket.  In unidirectional (causal) mode
+    only keys at or before the query are distinguished; keys after the query
+    collapse to bucket 0 (they are masked anyway).
+
+    The logarithmic part is floor(L * ln(n/E) / ln(D/E)) with E the number of
+    exact buckets, L the number of logarithmic ones and D = max_distance.  It
+    is evaluated here in exact integer arithmetic: the floor is the largest K
+    with (n/E)^L >= (D/E)^K, i.e. n^L * E^K >= D^K * E^L.  Python integers are
+    unbounded, so no rounding can move a boundary.
+    """
+    rp = int(rel_pos)
+    n_side = num_buckets
+    base = 0
+    if bidirectional:
+        n_side = num_buckets // 2
+        if rp > 0:
+            base = n_side
+        n = abs(rp)
+    else:
+        n = max(-rp, 0)
+    max_exact = n_side // 2
+    if n < max_exact:
+        return base + n
+    n_log = n_side - max_exact
+    big_k = 0
+    # largest K with n^L * E^K >= D^K * E^L ; K can not usefully exceed n_log
+    while big_k + 1 <= n_log and (n ** n_log) * (max_exact ** (big_k + 1)) >= \
+            (max_distance ** (big_k + 1)) * (max_exact ** n_log):
+        big_k += 1
+    return base + min(n_side - 1, max_exact + big_k)
+
+
+def relpos_bucket(rel_pos, bidirectional: bool, num_buckets: int = 32, max_distance: int = 128):
+    """Vectorised wrapper of relpos_bucket_scalar; returns int64 array of the input's shape."""
+    rp = np.asarray(rel_pos)
+    out = np.empty(rp.shape, dtype=np.int64)
+    flat_in, flat_out = rp.reshape(-1), out.reshape(-1)
+    cache = {}
+    for idx in range(flat_in.size):
+        v = int(flat_in[idx])
+        if v not in cache:
+            cache[v] = relpos_bucket_scalar(v, bidirectional, num_buckets, max_distance)
+        flat_out[idx] = cache[v]
+    return out
+
+
+def relpos_bias(rel_table: np.ndarray, seq: int, bidirectional: bool, num_buckets: int,
+                max_distance: int) -> np.ndarray:
+    """bias[h, i, j] = rel_table[bucket(j - i), h]   (query i, key j)."""
+    pos = np.arange(seq)
+    rp = pos[None, :] - pos[:, None]          # rp[i, j] = j - i
+    bucket = relpos_bucket(rp, bidirectional, num_buckets, max_distance)
+    return np.transpose(rel_table[bucket], (2, 0, 1)), bucket
+
+
+# --------------------------------------------------------------------------------------
+# Layer pieces
+# --------------------------------------------------------------------------------------
+def rmsnorm_fwd(x: np.ndarray, g: np.ndarray, eps: float):
+    """n = x * r * g with r = (mean_c x_c^2 + eps)^-1/2 taken over the last axis."""
+    r = 1.0 / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + eps)
+    return x * r * g, r
+
+
+def rmsnorm_bwd(x: np.ndarray, g: np.ndarray, r: np.ndarray, dn: np.ndarray):
+    """Gradient of rmsnorm_fwd.  With xh = x r:  dg = sum_tokens dn*xh,
+    dxh = dn*g,  dx = r * (dxh - xh * mean_c(dxh*xh))."""
+    xh = x * r
+    dg = np.sum((dn * xh).reshape(-1, x.shape[-1]), axis=0)
+    dxh = dn * g
+    dx = r * (dxh - xh * np.mean(dxh * xh, axis=-1, keepdims=True))
+    return dx, dg
+
+
+def gelu(z: np.ndarray) -> np.ndarray:
+    """tanh-form GELU: z/2 * (1 + tanh(kappa (z + beta z^3)))."""
+    return 0.5 * z * (1.0 + np.tanh(GELU_KAPPA * (z + GELU_BETA * z ** 3)))
+
+
+def gelu_grad(z: np.ndarray) -> np.ndarray:
+    t = np.tanh(GELU_KAPPA * (z + GELU_BETA * z ** 3))
+    return 0.5 * (1.0 + t) + 0.5 * z * (1.0 - t * t) * GELU_KAPPA * (1.0 + 3.0 * GELU_BETA * z * z)
+
+
+def softmax_rows(s: np.ndarray) -> np.ndarray:
+    """Two-pass softmax over the last axis; -inf entries get probability exactly 0."""
+    m = np.max(s, axis=-1, keepdims=True)
+    e = np.exp(s - m)
+    return e / np.sum(e, axis=-1, keepdims=True)
+
+
+# --------------------------------------------------------------------------------------
+# Block forward / backward
+# --------------------------------------------------------------------------------------
+def _split_heads(t: np.ndarray, n_heads: int, d_kv: int) -> np.ndarray:
+    b, s, _ = t.shape                          # [B,S,H*k] -> [B,H,S,k]; column h*k+c = head h, channel c
+    return np.transpose(t.reshape(b, s, n_heads, d_kv), (0, 2, 1, 3))
+
+
+def _merge_heads(t: np.ndarray) -> np.ndarray:
+    b, h, s, k = t.shape
+    return np.transpose(t, (0, 2, 1, 3)).reshape(b, s, h * k)
+
+
+def block_fwd(cfg, x: np.ndarray, w: dict):
+    """y = block(x).  x: [B,S,d].  Returns (y, saved) with every intermediate kept for the backward.
+
+    Steps (one sequence at a time is implied by the batched matmuls):
+      n1 = RMSNorm(x; g1);  q,k,v = n1 Wq, n1 Wk, n1 Wv  (split into heads)
+      s[h,i,j] = attn_scale <q_hi, k_hj> + table[bucket(j-i), h];  causal: j>i -> -inf
+      P = softmax_j s;  o = P v;  c = concat_h o;  h = x + c Wo
+      n2 = RMSNorm(h; g2);  u = n2 Wi0;  w = n2 Wi1;  a = gelu(u) * w;  y = h + a Wo_ff
+    """
+    nh, dk = cfg.n_heads, cfg.d_kv
+    n1, r1 = rmsnorm_fwd(x, w["ln1_scale"], cfg.rms_eps)
+    q = _split_heads(n1 @ w["wq"], nh, dk)
+    k = _split_heads(n1 @ w["wk"], nh, dk)
+    v = _split_heads(n1 @ w["wv"], nh, dk)
+    bias, bucket = relpos_bias(w["rel_table"], cfg.seq, not cfg.causal, cfg.num_buckets, cfg.max_distance)
+    s = cfg.attn_scale * (q @ np.swapaxes(k, -1, -2)) + bias[None]
+    if cfg.causal:
+        i = np.arange(cfg.seq)
+        s = np.where(i[None, :] > i[:, None], -np.inf, s)
+    p = softmax_rows(s)
+    o = p @ v
+    c = _merge_heads(o)
+    h = x + c @ w["wo"]
+    n2, r2 = rmsnorm_fwd(h, w["ln2_scale"], cfg.rms_eps)
+    u = n2 @ w["wi0"]
+    wl = n2 @ w["wi1"]
+    a = gelu(u) * wl
+    y = h + a @ w["wo_ff"]
+    saved = dict(x=x, n1=n1, r1=r1, q=q, k=k, v=v, p=p, c=c, h=h, n2=n2, r2=r2, u=u, wl=wl, a=a,
+                 bucket=bucket)
+    return y, saved
+
+
+def block_bwd(cfg, dy: np.ndarray, w: dict, saved: dict):
+    """Gradients of sum(y * dy) w.r.t. x and every weight.  Returns (dx, grads)."""
+    nh, dk = cfg.n_heads, cfg.d_kv
+    d = cfg.d_model
+    x, n1, r1, q, k, v, p, c, h, n2, r2, u, wl, a = (saved[t] for t in
+        ("x", "n1", "r1", "q", "k", "v", "p", "c", "h", "n2", "r2", "u", "wl", "a"))
+    flat = lambda t: t.reshape(-1, t.shape[-1])
+    g = {}
+    # --- MLP
+    g["wo_ff"] = flat(a).T @ flat(dy)
+    da = dy @ w["wo_ff"].T
+    du = da * wl * gelu_grad(u)
+    dwl = da * gelu(u)
+    g["wi0"] = flat(n2).T @ flat(du)
+    g["wi1"] = flat(n2).T @ flat(dwl)
+    dn2 = du @ w["wi0"].T + dwl @ w["wi1"].T
+    dh_norm, g["ln2_scale"] = rmsnorm_bwd(h, w["ln2_scale"], r2, dn2)
+    dh = dy + dh_norm
+    # --- attention
+    g["wo"] = flat(c).T @ flat(dh)
+    dc = dh @ w["wo"].T
+    do = _split_heads(dc, nh, dk)
+    dv = np.swapaxes(p, -1, -2) @ do
+    dp = do @ np.swapaxes(v, -1, -2)
+    ds = p * (dp - np.sum(p * dp, axis=-1, keepdims=True))      # masked entries have p = 0 -> ds = 0
+    dq = cfg.attn_scale * (ds @ k)
+    dk_ = cfg.attn_scale * (np.swapaxes(ds, -1, -2) @ q)
+    # bias table: every (b, i, j) adds ds[b,h,i,j] to row bucket(j-i) of column h
+    dtable = np.zeros_like(w["rel_table"])
+    ds_hij = np.sum(ds, axis=0)                                 # [H,S,S]
+    for hh in range(nh):
+        np.add.at(dtable[:, hh], saved["bucket"].reshape(-1), ds_hij[hh].reshape(-1))
+    g["rel_table"] = dtable
+    dqf, dkf, dvf = _merge_heads(dq), _merge_heads(dk_), _merge_heads(dv)
+    g["wq"] = flat(n1).T @ flat(dqf)
+    g["wk"] = flat(n1).T @ flat(dkf)
+    g["wv"] = flat(n1).T @ flat(dvf)
+    dn1 = dqf @ w["wq"].T + dkf @ w["wk"].T + dvf @ w["wv"].T
+    dx_norm, g["ln1_scale"] = rmsnorm_bwd(x, w["ln1_scale"], r1, dn1)
+    dx = dh + dx_norm
+    assert dx.shape[-1] == d
+    return dx, g
+
+
+# --------------------------------------------------------------------------------------
+# Adafactor
+# --------------------------------------------------------------------------------------
+def adafactor_beta2(step: int, decay_pow: float) -> float:
+    """Second-moment decay at 1-based step t: 1 - t^-decay_pow (0 at t = 1)."""
+    return 1.0 - float(step) ** (-decay_pow)
+
+
+def adafactor_step(param: np.ndarray, grad: np.ndarray, state: dict, *, step: int, lr: float,
+                   factored: bool, decay_pow: float = 0.8, eps1: float = 1e-30, eps2: float = 1e-3,
+                   clip: float = 1.0, scale_by_param: bool = True):
+    """One Adafactor update of a [R,C] tensor.  state holds 'vr' [R] and 'vc' [C] when factored,
+    else 'v' [R,C].  Returns (new_param, new_state); inputs are not modified.
+
+      beta2 = 1 - t^-decay_pow
+      Q = G*G + eps1
+      factored:   vr <- beta2 vr + (1-beta2) mean_j Q;  vc <- beta2 vc + (1-beta2) mean_i Q
+                  vhat_ij = vr_i vc_j / mean_i vr_i
+      otherwise:  v <- beta2 v + (1-beta2) Q;  vhat = v
+      U = G / sqrt(vhat);  U <- U / max(1, RMS(U)/clip)
+      alpha = lr * max(eps2, RMS(W))  (or lr alone);  W <- W - alpha U
+    """
+    b2 = adafactor_beta2(step, decay_pow)
+    qm = grad * grad + eps1
+    new_state = {}
+    if factored:
+        vr = b2 * state["vr"] + (1.0 - b2) * np.mean(qm, axis=1)
+        vc = b2 * state["vc"] + (1.0 - b2) * np.mean(qm, axis=0)
+        vhat = np.outer(vr, vc) / np.mean(vr)
+        new_state["vr"], new_state["vc"] = vr, vc
+    else:
+        vfull = b2 * state["v"] + (1.0 - b2) * qm
+        vhat = vfull
+        new_state["v"] = vfull
+    upd = grad / np.sqrt(vhat)
+    rms_u = math.sqrt(float(np.mean(upd * upd)))
+    upd = upd / max(1.0, rms_u / clip)
+    alpha = lr
+    if scale_by_param:
+        alpha = lr * max(eps2, math.sqrt(float(np.mean(param * param))))
+    return param - alpha * upd, new_state
+
+
+def adafactor_zero_state(rows: int, cols: int, factored: bool) -> dict:
+    if factored:
+        return {"vr": np.zeros(rows), "vc": np.zeros(cols)}
+    return {"v": np.zeros((rows, cols))}
