@@ -1,0 +1,151 @@
+/*
+ * t5mi.h - C ABI of the MI355X (gfx950) implementation of one T5.1.1-style
+ * Transformer block: forward, backward, relative-position buckets and the
+ * Adafactor update of its weights.
+ *
+ * The paper (Sec. 4, "Example models") ships T5.1.1 and a decoder-only model as
+ * its reference architectures and Sec. 2.3 describes them as ordinary layer
+ * stacks; the block below is one layer of those stacks.  The paper prints no
+ * layer formulas, so each entry point states the public definition it computes.
+ *
+ * Conventions for every call
+ *   - returns an int status (T5_OK == 0); never throws, aborts or prints;
+ *   - all tensor pointers are DEVICE pointers owned by the caller, dense
+ *     row-major, no strides, no aliasing between inputs and outputs;
+ *   - config structs are HOST pointers, read during the call only;
+ *   - the library allocates nothing: scratch comes from the caller's workspace,
+ *     whose size is returned by the *_bytes() queries (0 on an invalid config);
+ *   - all device work is enqueued on `stream` (a hipStream_t passed as void*;
+ *     NULL = the default stream) and the call returns without synchronising;
+ *   - arguments are validated before the first HIP call, so error paths can be
+ *     exercised on a host without a GPU.
+ */
+#ifndef T5MI_H
+#define T5MI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  T5_OK = 0,
+  T5_ERR_NULL = 1,        /* a required pointer is NULL */
+  T5_ERR_SHAPE = 2,       /* non-positive or inconsistent dimension / hyper-parameter */
+  T5_ERR_UNSUPPORTED = 3, /* valid problem, but no kernel for this shape/dtype */
+  T5_ERR_WORKSPACE = 4,   /* workspace_bytes smaller than the query result */
+  T5_ERR_DEVICE = 5       /* a HIP call or kernel launch failed */
+};
+
+enum { T5_F32 = 0, T5_BF16 = 1 };
+
+/* One Transformer block (paper Sec. 4: T5.1.1 encoder layer, or a decoder-only layer when
+ * causal != 0):
+ *   n1 = RMSNorm(x; ln1_scale)                      r = (mean_c x_c^2 + rms_eps)^-1/2, no mean subtraction
+ *   q,k,v = n1 Wq, n1 Wk, n1 Wv                     column h*d_kv + c = head h, channel c; no biases
+ *   s[h,i,j] = attn_scale <q_hi,k_hj> + rel_table[bucket(j-i), h];   causal: j > i masked
+ *   h = x + concat_h(softmax_j(s) v) Wo
+ *   n2 = RMSNorm(h; ln2_scale);  y = h + (gelu_tanh(n2 Wi0) * (n2 Wi1)) Wo_ff
+ * bucket() is t5_relpos_bucket() with bidirectional = !causal. */
+typedef struct {
+  int32_t batch, seq, d_model, n_heads, d_kv, d_ff;
+  int32_t num_buckets;  /* 32 in T5 */
+  int32_t max_distance; /* 128 in T5 */
+  int32_t causal;       /* 0: bidirectional buckets, no mask; 1: unidirectional buckets + causal mask */
+  int32_t dtype;        /* T5_F32 or T5_BF16: storage type of x, y, dy, dx and all weights */
+  float rms_eps;        /* 1e-6 in T5 */
+  float attn_scale;     /* 1.0 = T5 convention (scale folded into the initialisation) */
+} t5_block_cfg;
+
+/* Weights, device pointers, element type cfg.dtype, row-major [in, out]. */
+typedef struct {
+  const void* ln1_scale; /* [d_model] */
+  const void* wq;        /* [d_model, n_heads*d_kv] */
+  const void* wk;        /* [d_model, n_heads*d_kv] */
+  const void* wv;        /* [d_model, n_heads*d_kv] */
+  const void* wo;        /* [n_heads*d_kv, d_model] */
+  const void* rel_table; /* [num_buckets, n_heads] */
+  const void* ln2_scale; /* [d_model] */
+  const void* wi0;       /* [d_model, d_ff]; this branch goes through GELU */
+  const void* wi1;       /* [d_model, d_ff]; linear gate */
+  const void* wo_ff;     /* [d_ff, d_model] */
+} t5_block_weights;
+
+/* Weight gradients, device pointers, always float32, same shapes as the weights. */
+typedef struct {
+  float* ln1_scale;
+  float* wq;
+  float* wk;
+  float* wv;
+  float* wo;
+  float* rel_table;
+  float* ln2_scale;
+  float* wi0;
+  float* wi1;
+  float* wo_ff;
+} t5_block_grads;
+
+/* Relative-position bucket of T5 (used by the models of paper Sec. 4), elementwise:
+ * rel_pos = key_position - query_position.  Half of the buckets (per sign when bidirectional)
+ * are exact offsets, the rest are logarithmically spaced up to max_distance; the boundaries are
+ * evaluated in exact integer arithmetic.  rel_pos, bucket: device int32[n].  n == 0 is a no-op.
+ * Errors: NULL pointer with n > 0 -> T5_ERR_NULL; n < 0, num_buckets < 2 (or odd / < 4 when
+ * bidirectional), max_distance <= exact range -> T5_ERR_SHAPE; more than 64 logarithmic
+ * buckets per side -> T5_ERR_UNSUPPORTED. */
+int t5_relpos_bucket(const int32_t* rel_pos, int32_t* bucket, int64_t n, int bidirectional,
+                     int num_buckets, int max_distance, void* stream);
+
+/* Bytes of the saved-for-backward buffer written by t5_block_fwd and read by t5_block_bwd
+ * (opaque layout), and of the scratch workspace (max over forward and backward). */
+size_t t5_block_stash_bytes(const t5_block_cfg* cfg);
+size_t t5_block_workspace_bytes(const t5_block_cfg* cfg);
+
+/* Forward of the block defined at t5_block_cfg.  x, y: [batch, seq, d_model] of cfg.dtype.
+ * stash: t5_block_stash_bytes(cfg) bytes, 256-byte aligned, written here.
+ * Errors: NULL -> T5_ERR_NULL; bad dims -> T5_ERR_SHAPE; shape without a kernel ->
+ * T5_ERR_UNSUPPORTED; small workspace -> T5_ERR_WORKSPACE; launch failure -> T5_ERR_DEVICE. */
+int t5_block_fwd(const t5_block_cfg* cfg, const void* x, const t5_block_weights* w, void* y,
+                 void* stash, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Backward of the same block: given dy = dL/dy, writes dx = dL/dx (cfg.dtype) and the float32
+ * weight gradients (all ten pointers required).  accumulate == 0 overwrites the gradients,
+ * accumulate != 0 adds to them.  x, w and stash must be those of the matching forward call. */
+int t5_block_bwd(const t5_block_cfg* cfg, const void* dy, const void* x, const t5_block_weights* w,
+                 const void* stash, void* dx, const t5_block_grads* dw, int accumulate,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* Adafactor (the optimizer of the T5 models of paper Sec. 4) with factored second moments and
+ * update clipping, no momentum, no weight decay, for one [rows, cols] float32 tensor:
+ *   beta2 = 1 - step^-decay_pow;  Q = G*G + eps1
+ *   factored:  v_row <- beta2 v_row + (1-beta2) mean_j Q;  v_col likewise over rows;
+ *              vhat_ij = v_row_i v_col_j / mean_i v_row_i
+ *   otherwise: v_full <- beta2 v_full + (1-beta2) Q;  vhat = v_full
+ *   U = G / sqrt(vhat);  U <- U / max(1, RMS(U)/clip)
+ *   param <- param - lr * (scale_by_param ? max(eps2, RMS(param)) : 1) * U
+ * param and the state vectors are updated in place.  bf16_copy_out (nullable) receives the new
+ * parameters rounded to bf16.  Unused state pointers may be NULL.
+ * Errors: NULL -> T5_ERR_NULL; rows/cols < 1, step < 1, clip <= 0 -> T5_ERR_SHAPE;
+ * small workspace -> T5_ERR_WORKSPACE. */
+typedef struct {
+  float lr;
+  float decay_pow; /* 0.8 */
+  float eps1;      /* 1e-30 */
+  float eps2;      /* 1e-3 */
+  float clip;      /* 1.0 */
+  int32_t scale_by_param;
+  int32_t step; /* 1-based */
+} adafactor_cfg;
+
+size_t adafactor_workspace_bytes(int64_t rows, int64_t cols, int factored);
+int adafactor_step(float* param, const float* grad, float* v_row, float* v_col, float* v_full,
+                   int64_t rows, int64_t cols, int factored, const adafactor_cfg* cfg,
+                   void* bf16_copy_out, void* workspace, size_t workspace_bytes, void* stream);
+
+const char* t5_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* T5MI_H */

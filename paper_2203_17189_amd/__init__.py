@@ -1,0 +1,19 @@
+"""MI355X (gfx950) implementation of one T5.1.1-style Transformer block: forward, backward,
+relative-position buckets and the Adafactor update, behind the C ABI of include/t5mi.h.
+
+Python here only marshals arguments: every arithmetic step runs in the HIP kernels of libt5mi.so.
+"""
+from .binding import (  # noqa: F401
+    T5Error,
+    WEIGHT_NAMES,
+    adafactor_step,
+    adafactor_workspace_bytes,
+    lib,
+    lib_path,
+    t5_block_bwd,
+    t5_block_fwd,
+    t5_block_stash_bytes,
+    t5_block_workspace_bytes,
+    t5_relpos_bucket,
+    t5_status_string,
+)

@@ -1,0 +1,220 @@
+"""ctypes binding of libt5mi.so.  Argument marshalling only; torch supplies device memory and
+streams.  There is no CPU fallback: a missing library raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+WEIGHT_NAMES = ("ln1_scale", "wq", "wk", "wv", "wo", "rel_table", "ln2_scale", "wi0", "wi1", "wo_ff")
+T5_F32, T5_BF16 = 0, 1
+
+
+class T5Error(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: status {status} ({t5_status_string(status)})")
+        self.status = status
+
+
+class _Cfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("batch", "seq", "d_model", "n_heads", "d_kv", "d_ff", "num_buckets",
+                                         "max_distance", "causal", "dtype")] + \
+               [("rms_eps", C.c_float), ("attn_scale", C.c_float)]
+
+
+class _Weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in WEIGHT_NAMES]
+
+
+class _Grads(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in WEIGHT_NAMES]
+
+
+class _AfCfg(C.Structure):
+    _fields_ = [("lr", C.c_float), ("decay_pow", C.c_float), ("eps1", C.c_float), ("eps2", C.c_float),
+                ("clip", C.c_float), ("scale_by_param", C.c_int32), ("step", C.c_int32)]
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libt5mi.so")
+
+
+def lib() -> C.CDLL:
+    """Load libt5mi.so (building it first if it is not there).  Raises if that fails."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        from . import build as _build
+        _build.build(verbose=False)
+    L = C.CDLL(path)
+    vp, i32, i64, sz = C.c_void_p, C.c_int, C.c_int64, C.c_size_t
+    L.t5_status_string.restype = C.c_char_p
+    L.t5_status_string.argtypes = [i32]
+    L.t5_relpos_bucket.restype = i32
+    L.t5_relpos_bucket.argtypes = [vp, vp, i64, i32, i32, i32, vp]
+    L.t5_block_stash_bytes.restype = sz
+    L.t5_block_stash_bytes.argtypes = [C.POINTER(_Cfg)]
+    L.t5_block_workspace_bytes.restype = sz
+    L.t5_block_workspace_bytes.argtypes = [C.POINTER(_Cfg)]
+    L.t5_block_fwd.restype = i32
+    L.t5_block_fwd.argtypes = [C.POINTER(_Cfg), vp, C.POINTER(_Weights), vp, vp, vp, sz, vp]
+    L.t5_block_bwd.restype = i32
+    L.t5_block_bwd.argtypes = [C.POINTER(_Cfg), vp, vp, C.POINTER(_Weights), vp, vp, C.POINTER(_Grads), i32,
+                               vp, sz, vp]
+    L.adafactor_workspace_bytes.restype = sz
+    L.adafactor_workspace_bytes.argtypes = [i64, i64, i32]
+    L.adafactor_step.restype = i32
+    L.adafactor_step.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, C.POINTER(_AfCfg), vp, vp, sz, vp]
+    _LIB = L
+    return L
+
+
+def t5_status_string(status: int) -> str:
+    return lib().t5_status_string(int(status)).decode()
+
+
+def _cfg_struct(cfg) -> _Cfg:
+    dt = cfg.dtype
+    if isinstance(dt, str):
+        dt = {"f32": T5_F32, "bf16": T5_BF16}[dt]
+    return _Cfg(cfg.batch, cfg.seq, cfg.d_model, cfg.n_heads, cfg.d_kv, cfg.d_ff, cfg.num_buckets,
+                cfg.max_distance, int(bool(cfg.causal)), int(dt), float(cfg.rms_eps), float(cfg.attn_scale))
+
+
+def _torch_dtype(cfg):
+    dt = cfg.dtype
+    return torch.bfloat16 if dt in ("bf16", T5_BF16) else torch.float32
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check_tensor(t, dtype, numel, name):
+    if not t.is_cuda or not t.is_contiguous() or t.dtype != dtype or t.numel() != numel:
+        raise ValueError(f"{name}: need a contiguous cuda tensor of {dtype} with {numel} elements, "
+                         f"got {t.dtype} {tuple(t.shape)} on {t.device}")
+
+
+def t5_relpos_bucket(rel_pos: torch.Tensor, bidirectional: bool, num_buckets: int = 32,
+                     max_distance: int = 128, out: torch.Tensor | None = None) -> torch.Tensor:
+    _check_tensor(rel_pos, torch.int32, rel_pos.numel(), "rel_pos")
+    if out is None:
+        out = torch.empty_like(rel_pos)
+    rc = lib().t5_relpos_bucket(_ptr(rel_pos), _ptr(out), rel_pos.numel(), int(bool(bidirectional)),
+                                int(num_buckets), int(max_distance), _stream())
+    if rc:
+        raise T5Error(rc, "t5_relpos_bucket")
+    return out
+
+
+def t5_block_stash_bytes(cfg) -> int:
+    return int(lib().t5_block_stash_bytes(C.byref(_cfg_struct(cfg))))
+
+
+def t5_block_workspace_bytes(cfg) -> int:
+    return int(lib().t5_block_workspace_bytes(C.byref(_cfg_struct(cfg))))
+
+
+def _weights_struct(cfg, weights) -> _Weights:
+    dt = _torch_dtype(cfg)
+    inner = cfg.n_heads * cfg.d_kv
+    shapes = {"ln1_scale": cfg.d_model, "ln2_scale": cfg.d_model, "wq": cfg.d_model * inner,
+              "wk": cfg.d_model * inner, "wv": cfg.d_model * inner, "wo": inner * cfg.d_model,
+              "rel_table": cfg.num_buckets * cfg.n_heads, "wi0": cfg.d_model * cfg.d_ff,
+              "wi1": cfg.d_model * cfg.d_ff, "wo_ff": cfg.d_ff * cfg.d_model}
+    for n in WEIGHT_NAMES:
+        _check_tensor(weights[n], dt, shapes[n], n)
+    return _Weights(*[weights[n].data_ptr() for n in WEIGHT_NAMES])
+
+
+def _byte_buffer(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def t5_block_fwd(cfg, x, weights, y=None, stash=None, workspace=None):
+    """Returns (y, stash).  stash/workspace are uint8 cuda tensors (allocated here if None)."""
+    cs = _cfg_struct(cfg)
+    dt = _torch_dtype(cfg)
+    n = cfg.batch * cfg.seq * cfg.d_model
+    _check_tensor(x, dt, n, "x")
+    ws = _weights_struct(cfg, weights)
+    if y is None:
+        y = torch.empty_like(x)
+    _check_tensor(y, dt, n, "y")
+    if stash is None:
+        stash = _byte_buffer(lib().t5_block_stash_bytes(C.byref(cs)), x.device)
+    if workspace is None:
+        workspace = _byte_buffer(lib().t5_block_workspace_bytes(C.byref(cs)), x.device)
+    rc = lib().t5_block_fwd(C.byref(cs), _ptr(x), C.byref(ws), _ptr(y), _ptr(stash), _ptr(workspace),
+                            workspace.numel(), _stream())
+    if rc:
+        raise T5Error(rc, "t5_block_fwd")
+    return y, stash
+
+
+def alloc_grads(cfg, weights) -> dict:
+    return {n: torch.zeros(weights[n].shape, dtype=torch.float32, device=weights[n].device) for n in WEIGHT_NAMES}
+
+
+def t5_block_bwd(cfg, dy, x, weights, stash, dx=None, grads=None, accumulate=False, workspace=None):
+    """Returns (dx, grads); grads is a dict of float32 tensors shaped like the weights."""
+    cs = _cfg_struct(cfg)
+    dt = _torch_dtype(cfg)
+    n = cfg.batch * cfg.seq * cfg.d_model
+    _check_tensor(dy, dt, n, "dy")
+    _check_tensor(x, dt, n, "x")
+    ws = _weights_struct(cfg, weights)
+    if dx is None:
+        dx = torch.empty_like(dy)
+    _check_tensor(dx, dt, n, "dx")
+    if grads is None:
+        grads = alloc_grads(cfg, weights)
+    for nme in WEIGHT_NAMES:
+        _check_tensor(grads[nme], torch.float32, weights[nme].numel(), "grad " + nme)
+    gs = _Grads(*[grads[nme].data_ptr() for nme in WEIGHT_NAMES])
+    if workspace is None:
+        workspace = _byte_buffer(lib().t5_block_workspace_bytes(C.byref(cs)), x.device)
+    rc = lib().t5_block_bwd(C.byref(cs), _ptr(dy), _ptr(x), C.byref(ws), _ptr(stash), _ptr(dx), C.byref(gs),
+                            int(bool(accumulate)), _ptr(workspace), workspace.numel(), _stream())
+    if rc:
+        raise T5Error(rc, "t5_block_bwd")
+    return dx, grads
+
+
+def adafactor_workspace_bytes(rows: int, cols: int, factored: bool) -> int:
+    return int(lib().adafactor_workspace_bytes(int(rows), int(cols), int(bool(factored))))
+
+
+def adafactor_step(param, grad, *, step, lr, factored, v_row=None, v_col=None, v_full=None, decay_pow=0.8,
+                   eps1=1e-30, eps2=1e-3, clip=1.0, scale_by_param=True, bf16_copy_out=None, workspace=None):
+    """In-place Adafactor update of a float32 tensor viewed as [rows, cols] (1-D tensors: rows = 1)."""
+    rows, cols = (param.shape[0], param.numel() // param.shape[0]) if param.dim() >= 2 else (1, param.numel())
+    _check_tensor(param, torch.float32, rows * cols, "param")
+    _check_tensor(grad, torch.float32, rows * cols, "grad")
+    if factored:
+        _check_tensor(v_row, torch.float32, rows, "v_row")
+        _check_tensor(v_col, torch.float32, cols, "v_col")
+    else:
+        _check_tensor(v_full, torch.float32, rows * cols, "v_full")
+    if bf16_copy_out is not None:
+        _check_tensor(bf16_copy_out, torch.bfloat16, rows * cols, "bf16_copy_out")
+    if workspace is None:
+        workspace = _byte_buffer(adafactor_workspace_bytes(rows, cols, factored), param.device)
+    cfg = _AfCfg(lr, decay_pow, eps1, eps2, clip, int(bool(scale_by_param)), int(step))
+    rc = lib().adafactor_step(_ptr(param), _ptr(grad), _ptr(v_row), _ptr(v_col), _ptr(v_full), rows, cols,
+                              int(bool(factored)), C.byref(cfg), _ptr(bf16_copy_out), _ptr(workspace),
+                              workspace.numel(), _stream())
+    if rc:
+        raise T5Error(rc, "adafactor_step")
+    return param

@@ -1,0 +1,103 @@
+// Internal helpers shared by the HIP kernels of the T5 block library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/t5mi.h"
+
+namespace t5mi {
+
+typedef __bf16 bf16;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) short short4v;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr int kWave = 64;
+
+// ---- storage-type conversion (round to nearest even for bf16) ----
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16 v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  bf16x2 p;
+  p[0] = (bf16)lo;
+  p[1] = (bf16)hi;
+  return __builtin_bit_cast(uint32_t, p);
+}
+
+// ---- wavefront (64 lanes) and workgroup reductions ----
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+// Sum over a workgroup of NW waves; every thread gets the result.  `red` holds >= NW floats of LDS.
+template <int NW>
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  if (NW == 1) return v;
+  const int w = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NW; ++i) s += red[i];
+  return s;
+}
+
+// tanh-form GELU and its derivative, float32.
+__device__ __forceinline__ float gelu_tanh(float z) {
+  const float kappa = 0.7978845608028654f, beta = 0.044715f;
+  float t = tanhf(kappa * (z + beta * z * z * z));
+  return 0.5f * z * (1.f + t);
+}
+__device__ __forceinline__ void gelu_tanh_both(float z, float& g, float& dg) {
+  const float kappa = 0.7978845608028654f, beta = 0.044715f;
+  float t = tanhf(kappa * (z + beta * z * z * z));
+  g = 0.5f * z * (1.f + t);
+  dg = 0.5f * (1.f + t) + 0.5f * z * (1.f - t * t) * kappa * (1.f + 3.f * beta * z * z);
+}
+
+// Threshold table of the logarithmic relative-position buckets, built on the host in exact
+// integer arithmetic and passed to kernels by value.
+struct RelposLut {
+  int32_t bidirectional;
+  int32_t n_side;     // buckets per side
+  int32_t max_exact;  // offsets below this are their own bucket
+  int32_t n_thr;      // number of thresholds in thr[]
+  int32_t thr[64];    // thr[m] = smallest distance whose logarithmic index is >= m+1
+};
+
+__device__ __forceinline__ int relpos_bucket_dev(int rp, const RelposLut& lut) {
+  int base = 0, n;
+  if (lut.bidirectional) {
+    if (rp > 0) base = lut.n_side;
+    n = rp < 0 ? -rp : rp;
+  } else {
+    n = rp < 0 ? -rp : 0;
+  }
+  if (n < lut.max_exact) return base + n;
+  int k = 0;
+  for (int m = 0; m < lut.n_thr; ++m) k += (n >= lut.thr[m]) ? 1 : 0;
+  int b = lut.max_exact + k;
+  if (b > lut.n_side - 1) b = lut.n_side - 1;
+  return base + b;
+}
+
+inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+}  // namespace t5mi

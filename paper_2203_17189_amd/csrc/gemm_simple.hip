@@ -1,0 +1,181 @@
+// Reference-grade GEMM for the float32 block and for bf16 shapes the MFMA kernel does not take:
+// 64x64 output tile, 16-deep LDS stages, float32 FMA, any shape and either operand orientation.
+// Also: the elementwise gated-GELU of the unfused path and the bf16 weight transpose-pack.
+#include "kernels.h"
+
+namespace t5mi {
+
+namespace {
+
+constexpr int SB = 64;  // tile edge
+constexpr int SK = 16;  // k depth per stage
+
+__device__ __forceinline__ float ld_elem(const void* p, size_t idx, int type) {
+  return type == IN_BF16 ? (float)((const bf16*)p)[idx] : ((const float*)p)[idx];
+}
+__device__ __forceinline__ void st_elem(void* p, size_t idx, int type, float v) {
+  if (type == IN_BF16) ((bf16*)p)[idx] = (bf16)v; else ((float*)p)[idx] = v;
+}
+
+__global__ __launch_bounds__(256) void gemm_simple_kernel(GemmDesc g, GemmEpi e) {
+  __shared__ float As[SK][SB + 1];
+  __shared__ float Bs[SK][SB + 1];
+  const int tid = threadIdx.x;
+  const int tx = tid % 16, ty = tid / 16;
+  const int m0 = blockIdx.y * SB, n0 = blockIdx.x * SB;
+  float acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+
+  for (int s = 0; s < g.nseg; ++s) {
+    const GemmSeg sg = g.seg[s];
+    for (int k0 = 0; k0 < sg.K; k0 += SK) {
+      // 64x16 elements per operand, 256 threads -> 4 each
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int idx = tid + i * 256;
+        int mm, kk;
+        if (g.a_kc) { kk = idx % SK; mm = idx / SK; } else { mm = idx % SB; kk = idx / SB; }
+        float v = 0.f;
+        if (m0 + mm < g.M && k0 + kk < sg.K) {
+          const size_t off = g.a_kc ? (size_t)(m0 + mm) * sg.lda + (k0 + kk)
+                                    : (size_t)(k0 + kk) * sg.lda + (m0 + mm);
+          v = ld_elem(sg.A, off, g.in_type);
+        }
+        As[kk][mm] = v;
+        int nn, kb;
+        if (g.b_kc) { kb = idx % SK; nn = idx / SK; } else { nn = idx % SB; kb = idx / SB; }
+        float u = 0.f;
+        if (n0 + nn < g.N && k0 + kb < sg.K) {
+          const size_t off = g.b_kc ? (size_t)(n0 + nn) * sg.ldb + (k0 + kb)
+                                    : (size_t)(k0 + kb) * sg.ldb + (n0 + nn);
+          u = ld_elem(sg.B, off, g.in_type);
+        }
+        Bs[kb][nn] = u;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int kk = 0; kk < SK; ++kk) {
+        float a[4], b[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; b[i] = Bs[kk][tx * 4 + i]; }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+      }
+      __syncthreads();
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int m = m0 + ty * 4 + i;
+    if (m >= g.M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int n = n0 + tx * 4 + j;
+      if (n >= g.N) continue;
+      const float v = acc[i][j];
+      const size_t o = (size_t)m * e.ld0 + n;
+      switch (e.kind) {
+        case EPI_STORE:
+          st_elem(e.out0, o, e.out_type, v);
+          break;
+        case EPI_RESID:
+          st_elem(e.out0, o, e.out_type, v + ld_elem(e.aux0, o, e.aux_type));
+          break;
+        case EPI_GEGLU_BWD: {
+          const float u = ld_elem(e.aux0, o, e.aux_type), w = ld_elem(e.aux1, o, e.aux_type);
+          float gl, dgl;
+          gelu_tanh_both(u, gl, dgl);
+          st_elem(e.out0, o, e.out_type, v * w * dgl);
+          st_elem(e.out1, o, e.out_type, v * gl);
+          break;
+        }
+        case EPI_SPLIT_F32: {
+          const int which = n / e.split_n, nn = n % e.split_n;
+          float* dst = (float*)(which == 0 ? e.out0 : which == 1 ? e.out1 : e.out2);
+          const size_t oo = (size_t)m * e.ld0 + nn;
+          dst[oo] = e.accumulate ? dst[oo] + v : v;
+          break;
+        }
+        default:
+          break;
+      }
+    }
+  }
+}
+
+template <typename T>
+__global__ void geglu_fwd_kernel(const T* __restrict__ u, const T* __restrict__ w, T* __restrict__ a,
+                                 int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) a[i] = from_f32<T>(gelu_tanh(to_f32(u[i])) * to_f32(w[i]));
+}
+
+// dst[n][k] for a 32x32 tile staged through LDS; see launch_pack_transpose_bf16.
+struct PackSrcs {
+  const bf16* p[3];
+};
+__global__ __launch_bounds__(256) void pack_transpose_kernel(PackSrcs srcs, int nsrc, int K, int n_each,
+                                                            bf16* __restrict__ dst, int interleave) {
+  __shared__ bf16 tile[32][33];
+  const int n_total = nsrc * n_each;
+  const int n0 = blockIdx.x * 32, k0 = blockIdx.y * 32;
+  const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;  // 32 x 8
+  // interleave and n_each are multiples of 32 (or interleave == 0), so a 32-wide tile of packed
+  // rows comes from one source and 32 consecutive source columns.
+  int which, col0;
+  if (interleave > 0) {
+    which = (n0 / interleave) % nsrc;
+    col0 = (n0 / (interleave * nsrc)) * interleave + n0 % interleave;
+  } else {
+    which = n0 / n_each;
+    col0 = n0 % n_each;
+  }
+  const bf16* src = srcs.p[which];
+  for (int r = ty; r < 32; r += 8) {
+    const int k = k0 + r;
+    tile[r][tx] = (k < K && n0 + tx < n_total) ? src[(size_t)k * n_each + col0 + tx] : (bf16)0.f;
+  }
+  __syncthreads();
+  for (int r = ty; r < 32; r += 8) {
+    const int n = n0 + r, k = k0 + tx;
+    if (n < n_total && k < K) dst[(size_t)n * K + k] = tile[tx][r];
+  }
+}
+
+}  // namespace
+
+hipError_t launch_gemm_simple(const GemmDesc& g, const GemmEpi& e, hipStream_t st) {
+  if (e.kind == EPI_GEGLU_FWD) return hipErrorInvalidValue;
+  dim3 grid(ceil_div(g.N, SB), ceil_div(g.M, SB));
+  gemm_simple_kernel<<<grid, 256, 0, st>>>(g, e);
+  return hipGetLastError();
+}
+
+hipError_t launch_geglu_fwd(const void* u, const void* w, void* a, int type, int64_t n, hipStream_t st) {
+  int64_t blocks = (n + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  if (type == IN_BF16)
+    geglu_fwd_kernel<bf16><<<(int)blocks, 256, 0, st>>>((const bf16*)u, (const bf16*)w, (bf16*)a, n);
+  else
+    geglu_fwd_kernel<float><<<(int)blocks, 256, 0, st>>>((const float*)u, (const float*)w, (float*)a, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_pack_transpose_bf16(const void* const* srcs, int nsrc, int K, int n_each, void* dst,
+                                      int interleave, hipStream_t st) {
+  if (nsrc < 1 || nsrc > 3 || n_each % 32 != 0 || (interleave > 0 && interleave % 32 != 0))
+    return hipErrorInvalidValue;
+  PackSrcs ps;
+  for (int i = 0; i < 3; ++i) ps.p[i] = (const bf16*)(i < nsrc ? srcs[i] : nullptr);
+  dim3 grid(nsrc * n_each / 32, ceil_div(K, 32));
+  pack_transpose_kernel<<<grid, 256, 0, st>>>(ps, nsrc, K, n_each, (bf16*)dst, interleave);
+  return hipGetLastError();
+}
+
+}  // namespace t5mi

@@ -1,0 +1,112 @@
+// Internal launcher interface between the C-ABI host layer (block.hip) and the kernel files.
+// Every launcher enqueues on `st` and returns the hipGetLastError() of its launches.
+#pragma once
+#include "common.h"
+
+namespace t5mi {
+
+// ------------------------------------------------------------------ relative positions
+// Fills `lut` for (bidirectional, num_buckets, max_distance); returns a T5_* status.
+int relpos_build_lut(int bidirectional, int num_buckets, int max_distance, RelposLut* lut);
+hipError_t launch_relpos_bucket(const int32_t* rel_pos, int32_t* out, int64_t n, const RelposLut& lut,
+                                hipStream_t st);
+// diag[h][delta + S - 1] = table[bucket(delta)][h] for delta = key - query in [-(S-1), S-1]; float32.
+hipError_t launch_relpos_diag(const void* table, int dtype, float* diag, int S, int H,
+                              const RelposLut& lut, hipStream_t st);
+// dtable[c][h] (+)= sum over delta with bucket(delta) == c of ddiag[h][delta + S - 1]
+hipError_t launch_relpos_diag_bwd(const float* ddiag, float* dtable, int S, int H, int num_buckets,
+                                  const RelposLut& lut, int accumulate, hipStream_t st);
+
+// ------------------------------------------------------------------ RMSNorm
+enum { IN_F32 = 0, IN_BF16 = 1 };
+// n = x * r * g, r = rsqrt(mean(x^2) + eps).  x: [T,d] of x_type; g, n of out_type; r: [T] float32.
+hipError_t launch_rmsnorm_fwd(const void* x, int x_type, const void* g, void* n, int out_type, float* r,
+                              int T, int d, float eps, hipStream_t st);
+// dx_total = resid + r * (dn*g - xh * mean(dn*g*xh)),  xh = x*r;  dg (+)= sum_T dn*xh.
+// x of x_type; g of g_type; dn float32; resid of resid_type; outputs: out_f32 (nullable),
+// out_lp (nullable, lp_type).  dg_partial: workspace float[rmsnorm_bwd_partial_rows(T) * d].
+int rmsnorm_bwd_partial_rows(int T);
+hipError_t launch_rmsnorm_bwd(const void* x, int x_type, const void* g, int g_type, const float* r,
+                              const float* dn, const void* resid, int resid_type, float* out_f32,
+                              void* out_lp, int lp_type, float* dg, float* dg_partial, int accumulate,
+                              int T, int d, hipStream_t st);
+
+// ------------------------------------------------------------------ GEMM
+// C[m,n] = sum over segments s, k < K_s of A_s(m,k) * B_s(n,k), float32 accumulation.
+// a_kc: A_s(m,k) = A[m*lda + k], else A[k*lda + m].  b_kc: B_s(n,k) = B[n*ldb + k], else B[k*ldb + n].
+struct GemmSeg {
+  const void* A;
+  const void* B;
+  int lda, ldb, K;
+};
+enum EpiKind {
+  EPI_STORE = 0,      // out0[m*ld0 + n] = acc                    (out_type)
+  EPI_RESID = 1,      // out0[m*ld0 + n] = acc + aux0[m*ld0 + n]  (aux0 of aux_type)
+  EPI_GEGLU_FWD = 2,  // MFMA path only: B rows interleave wi0/wi1 in groups of 32; writes u, w, a
+  EPI_GEGLU_BWD = 3,  // acc = da; reads u = aux0, w = aux1; out0 = du, out1 = dw   (all ld0)
+  EPI_SPLIT_F32 = 4   // float32 out; column n goes to outs[n / split_n][m*ld0 + n % split_n]; += if accumulate
+};
+struct GemmEpi {
+  int kind;
+  void* out0;
+  void* out1;
+  void* out2;
+  const void* aux0;
+  const void* aux1;
+  int ld0;
+  int out_type;  // IN_F32 / IN_BF16 for out0/out1/out2
+  int aux_type;
+  int split_n;
+  int accumulate;
+};
+struct GemmDesc {
+  int M, N, nseg;
+  GemmSeg seg[3];
+  int a_kc, b_kc;
+  int in_type;  // element type of A and B
+};
+// Simple LDS-tiled FMA kernel: any shape, float32 or bf16 inputs.  Reference-grade speed.
+hipError_t launch_gemm_simple(const GemmDesc& g, const GemmEpi& e, hipStream_t st);
+// bf16 MFMA kernel.  Requires in_type == IN_BF16, every K % 64 == 0, lda/ldb % 8 == 0, N % 64 == 0
+// and 16-byte aligned pointers; gemm_mfma_supported() checks this.
+bool gemm_mfma_supported(const GemmDesc& g, const GemmEpi& e);
+hipError_t launch_gemm_mfma(const GemmDesc& g, const GemmEpi& e, hipStream_t st);
+
+// Transpose-pack for the forward weights (bf16): dst[n][k] = src_j[k][n'] for the concatenation of
+// nsrc matrices [K, n_each] along n.  interleave > 0: packed row n maps to source
+// (n / interleave) % nsrc and column (n / (interleave*nsrc)) * interleave + n % interleave.
+hipError_t launch_pack_transpose_bf16(const void* const* srcs, int nsrc, int K, int n_each, void* dst,
+                                      int interleave, hipStream_t st);
+
+// ------------------------------------------------------------------ elementwise gated GELU (simple path)
+hipError_t launch_geglu_fwd(const void* u, const void* w, void* a, int type, int64_t n, hipStream_t st);
+
+// ------------------------------------------------------------------ attention
+struct AttnDims {
+  int B, S, H, dk;
+  int causal;
+  float scale;
+};
+// qkv: [T, 3*H*dk] (q | k | v per token).  c: [T, H*dk].  lse: [B,H,S] float32.  diag: [H, 2S-1].
+hipError_t launch_attn_fwd_simple(const void* qkv, int type, const float* diag, void* c, float* lse,
+                                  const AttnDims& a, hipStream_t st);
+// dc: [T, H*dk] gradient of c.  Writes dqkv [T, 3*H*dk], dvec [B,H,S] (scratch), ddiag [H, 2S-1]
+// float32 (zeroed inside).
+hipError_t launch_attn_bwd_simple(const void* qkv, const void* c, const void* dc, int type,
+                                  const float* diag, const float* lse, float* dvec, void* dqkv,
+                                  float* ddiag, const AttnDims& a, hipStream_t st);
+bool attn_mfma_supported(const AttnDims& a);
+hipError_t launch_attn_fwd_mfma(const void* qkv, const float* diag, void* c, float* lse, const AttnDims& a,
+                                hipStream_t st);
+size_t attn_bwd_mfma_scratch_bytes(const AttnDims& a);
+hipError_t launch_attn_bwd_mfma(const void* qkv, const void* c, const void* dc, const float* diag,
+                                const float* lse, float* dvec, void* dqkv, float* ddiag, void* scratch,
+                                const AttnDims& a, hipStream_t st);
+
+// ------------------------------------------------------------------ Adafactor
+size_t adafactor_ws_bytes(int64_t rows, int64_t cols, int factored);
+hipError_t launch_adafactor(float* param, const float* grad, float* v_row, float* v_col, float* v_full,
+                            int64_t rows, int64_t cols, int factored, const adafactor_cfg& c,
+                            void* bf16_out, void* ws, hipStream_t st);
+
+}  // namespace t5mi

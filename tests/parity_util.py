@@ -1,0 +1,54 @@
+"""Helpers for the GPU parity tests: upload seeded inputs, run the HIP path through its C-ABI
+binding, and measure the error against the float64 oracle."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import synth_inputs as SI
+
+# Tolerances, keyed by storage dtype: (max, mean) of the per-element error
+#   e_i = |gpu_i - ref_i| / max(|ref_i|, RMS(ref))
+TOL_F32 = (1e-4, 1e-4)
+TOL_BF16_ACT = (2e-2, 2e-3)      # y and dx of the bf16 block (stated target)
+
+
+def rel_err(gpu: np.ndarray, ref: np.ndarray):
+    gpu = np.asarray(gpu, dtype=np.float64).reshape(ref.shape)
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    if rms == 0.0:
+        return float(np.abs(gpu).max()), float(np.abs(gpu).mean())
+    e = np.abs(gpu - ref) / np.maximum(np.abs(ref), rms)
+    return float(e.max()), float(e.mean())
+
+
+def to_dev(a: np.ndarray, dtype: str) -> torch.Tensor:
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    return t.to(torch.bfloat16) if dtype == "bf16" else t
+
+
+def to_np(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def upload_case(cfg, w, x, dy):
+    dw = {k: to_dev(v, cfg.dtype) for k, v in w.items()}
+    return dw, to_dev(x, cfg.dtype), to_dev(dy, cfg.dtype)
+
+
+def run_block_gpu(cfg, w, x, dy):
+    """Returns (y, dx, grads) as float64 numpy arrays, computed by the HIP library."""
+    import paper_2203_17189_amd as P
+    dw, dx_in, ddy = upload_case(cfg, w, x, dy)
+    y, stash = P.t5_block_fwd(cfg, dx_in, dw)
+    dx, grads = P.t5_block_bwd(cfg, ddy, dx_in, dw, stash)
+    torch.cuda.synchronize()
+    return to_np(y), to_np(dx), {k: to_np(v) for k, v in grads.items()}
+
+
+def make_case(cfg, random_scales=True, seed_offset=0):
+    w = SI.make_weights(cfg)
+    if random_scales:
+        w.update(SI.make_random_scales(cfg))
+    x, dy = SI.make_activations(cfg, seed_offset)
+    return w, x, dy

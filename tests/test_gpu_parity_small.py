@@ -1,0 +1,129 @@
+"""GPU parity: HIP path (through the C ABI) against the float64 oracle, element by element, on
+shapes the oracle finishes in seconds."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as SI
+from oracle import t5_oracle as O
+from parity_util import TOL_BF16_ACT, TOL_F32, make_case, rel_err, run_block_gpu, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def _P():
+    import paper_2203_17189_amd as P
+    return P
+
+
+# ------------------------------------------------------------------ relative-position buckets
+@pytest.mark.parametrize("bidir", [True, False])
+@pytest.mark.parametrize("nb,md", [(32, 128), (16, 64), (8, 20), (64, 1000), (128, 4096)])
+def test_relpos_bucket_bit_exact(bidir, nb, md):
+    rp = np.arange(-5000, 5001, dtype=np.int32)
+    got = _P().t5_relpos_bucket(torch.from_numpy(rp).cuda(), bidir, nb, md).cpu().numpy()
+    want = O.relpos_bucket(rp, bidir, nb, md)
+    assert np.array_equal(got.astype(np.int64), want)
+
+
+def test_relpos_bucket_empty_and_large():
+    P = _P()
+    out = P.t5_relpos_bucket(torch.empty(0, dtype=torch.int32, device="cuda"), True)
+    assert out.numel() == 0
+    rng = np.random.default_rng(1)
+    rp = rng.integers(-3000, 3000, size=1 << 20).astype(np.int32)
+    rp[:4] = [-(2 ** 31) + 1, 2 ** 31 - 1, 0, -1]
+    got = P.t5_relpos_bucket(torch.from_numpy(rp).cuda(), False).cpu().numpy()
+    uniq = {int(v): O.relpos_bucket_scalar(int(v), False) for v in np.unique(rp)}
+    want = np.array([uniq[int(v)] for v in rp])
+    assert np.array_equal(got, want)
+
+
+# ------------------------------------------------------------------ float32 block (tiny config)
+C1 = SI.CONFIGS["c1_tiny_f32"]
+
+
+@pytest.mark.parametrize("cfg", [C1, replace(C1, causal=True, index=20),
+                                 replace(C1, name="ragged", index=21, batch=3, seq=37, d_model=72, n_heads=3,
+                                         d_kv=20, d_ff=100, attn_scale=0.25),
+                                 replace(C1, name="long_causal", index=22, batch=1, seq=300, causal=True)])
+def test_block_f32(cfg):
+    w, x, dy = make_case(cfg)
+    y, saved = O.block_fwd(cfg, x, w)
+    dx, g = O.block_bwd(cfg, dy, w, saved)
+    gy, gdx, gg = run_block_gpu(cfg, w, x, dy)
+    assert rel_err(gy, y)[0] <= TOL_F32[0], ("y", rel_err(gy, y))
+    assert rel_err(gdx, dx)[0] <= TOL_F32[0], ("dx", rel_err(gdx, dx))
+    for name in g:
+        assert rel_err(gg[name], g[name])[0] <= TOL_F32[0], (name, rel_err(gg[name], g[name]))
+
+
+def test_block_f32_accumulate_flag():
+    P = _P()
+    from parity_util import upload_case
+    cfg = C1
+    w, x, dy = make_case(cfg)
+    dw, dx_in, ddy = upload_case(cfg, w, x, dy)
+    y, stash = P.t5_block_fwd(cfg, dx_in, dw)
+    _, g1 = P.t5_block_bwd(cfg, ddy, dx_in, dw, stash)
+    g2 = {k: v.clone() for k, v in g1.items()}
+    P.t5_block_bwd(cfg, ddy, dx_in, dw, stash, grads=g2, accumulate=True)
+    torch.cuda.synchronize()
+    for k in g1:
+        np.testing.assert_allclose(to_np(g2[k]), 2 * to_np(g1[k]), rtol=1e-5, atol=1e-6)
+
+
+# ------------------------------------------------------------------ Adafactor
+@pytest.mark.parametrize("rows,cols,factored", [(64, 256, True), (70, 130, True), (513, 1027, True),
+                                                (1, 64, False), (32, 4, False), (33, 7, False)])
+def test_adafactor_three_steps(rows, cols, factored):
+    P = _P()
+    p, _ = SI.make_adafactor_case(rows, cols, seed=5)
+    st = O.adafactor_zero_state(rows, cols, factored)
+    dp = torch.from_numpy(p.astype(np.float32)).cuda()
+    vr = torch.zeros(rows, device="cuda")
+    vc = torch.zeros(cols, device="cuda")
+    vf = torch.zeros(rows, cols, device="cuda")
+    lp = torch.empty(rows, cols, dtype=torch.bfloat16, device="cuda")
+    w = p
+    for t in (1, 2, 3):
+        _, g = SI.make_adafactor_case(rows, cols, seed=30 + t, grad_std=1e-2 * t)
+        w, st = O.adafactor_step(w, g, st, step=t, lr=0.01, factored=factored)
+        P.adafactor_step(dp, torch.from_numpy(g.astype(np.float32)).cuda(), step=t, lr=0.01, factored=factored,
+                         v_row=vr, v_col=vc, v_full=vf, bf16_copy_out=lp)
+        torch.cuda.synchronize()
+        assert rel_err(to_np(dp), w)[0] <= 1e-5, (t, rel_err(to_np(dp), w))
+        if factored:
+            assert rel_err(to_np(vr), st["vr"])[0] <= 1e-5
+            assert rel_err(to_np(vc), st["vc"])[0] <= 1e-5
+        else:
+            assert rel_err(to_np(vf), st["v"])[0] <= 1e-5
+        assert torch.equal(lp, dp.to(torch.bfloat16))
+
+
+# ------------------------------------------------------------------ bf16 block, small shapes
+SMALL_BF16 = [
+    SI.BlockConfig("bf16_enc", 30, batch=2, seq=128, d_model=128, n_heads=2, d_kv=64, d_ff=256,
+                   attn_scale=64 ** -0.5),
+    SI.BlockConfig("bf16_dec", 31, batch=2, seq=192, d_model=128, n_heads=2, d_kv=64, d_ff=256, causal=True,
+                   attn_scale=64 ** -0.5),
+    SI.BlockConfig("bf16_ragged", 32, batch=1, seq=100, d_model=72, n_heads=3, d_kv=24, d_ff=136,
+                   attn_scale=24 ** -0.5),
+]
+
+
+@pytest.mark.parametrize("cfg", SMALL_BF16, ids=[c.name for c in SMALL_BF16])
+def test_block_bf16_small(cfg):
+    w, x, dy = make_case(cfg)
+    y, saved = O.block_fwd(cfg, x, w)
+    dx, g = O.block_bwd(cfg, dy, w, saved)
+    gy, gdx, gg = run_block_gpu(cfg, w, x, dy)
+    ey, edx = rel_err(gy, y), rel_err(gdx, dx)
+    print(cfg.name, "y", ey, "dx", edx, {k: rel_err(gg[k], g[k]) for k in g})
+    assert ey[0] <= TOL_BF16_ACT[0] and ey[1] <= TOL_BF16_ACT[1], ey
+    assert edx[0] <= TOL_BF16_ACT[0] and edx[1] <= TOL_BF16_ACT[1], edx
+    for name in g:
+        e = rel_err(gg[name], g[name])
+        assert e[0] <= 6e-2 and e[1] <= 6e-3, (name, e)
