@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the T5.1.1 block hot path (forward + backward [+ Adafactor]) on one MI355X.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2_small|c3_base|c4_gpt_causal|c5_xl]
+
+Prints ONE JSON line.  A "step" is one pass of the whole hot path over one batch of seeded
+synthetic input already resident in HBM: t5_block_fwd + t5_block_bwd, plus adafactor_step on every
+block weight for the workloads that include the optimizer.  `value` is tokens/s of that step.
+`roofline` describes the step's dominant kernel, timed with HIP events on the launch stream in a
+second, instrumented pass over the same work; `cpu_baseline` is the float64 oracle timed on the host
+cores on a bounded sample (fewer sequences, same shapes).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import synth_inputs as SI  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def gemm_step_flops(cfg) -> dict:
+    """Algorithmic FLOPs of one launch of each MFMA step (2*M*N*K; attention counts the causal half)."""
+    T, d, I, F, S = cfg.tokens, cfg.d_model, cfg.inner, cfg.d_ff, cfg.seq
+    attn_f = 4.0 * T * S * I * (0.5 if cfg.causal else 1.0)
+    return {
+        "gemm_qkv": 2.0 * T * d * 3 * I, "gemm_o": 2.0 * T * I * d, "gemm_wi_geglu": 2.0 * T * d * 2 * F,
+        "gemm_wo": 2.0 * T * F * d, "attn_fwd": attn_f,
+        "gemm_dwo_ff": 2.0 * T * F * d, "gemm_da_geglu_bwd": 2.0 * T * F * d, "gemm_dwi": 2.0 * T * d * F,
+        "gemm_dn2": 2.0 * T * d * 2 * F, "gemm_dwo": 2.0 * T * I * d, "gemm_dc": 2.0 * T * I * d,
+        "attn_bwd": 2.0 * attn_f, "gemm_dwqkv": 2.0 * T * d * 3 * I, "gemm_dn1": 2.0 * T * d * 3 * I,
+    }
+
+
+def cpu_baseline(cfg, sample_batch: int) -> dict:
+    from oracle import t5_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    c = cfg.with_batch(sample_batch)
+    w = SI.make_weights(c)
+    x, dy = SI.make_activations(c)
+    t0 = time.perf_counter()
+    y, saved = O.block_fwd(c, x, w)
+    dx, g = O.block_bwd(c, dy, w, saved)
+    if cfg.adafactor:
+        for name, grad in g.items():
+            p2 = w[name].reshape(-1, w[name].shape[-1]) if w[name].ndim > 1 else w[name].reshape(1, -1)
+            g2 = grad.reshape(p2.shape)
+            fact = min(p2.shape) >= 2 and name not in ("rel_table",)
+            O.adafactor_step(p2, g2, O.adafactor_zero_state(p2.shape[0], p2.shape[1], fact), step=1, lr=1e-2,
+                             factored=fact)
+    dt = time.perf_counter() - t0
+    return {"value": c.tokens / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{cfg.name} at batch {sample_batch} of {cfg.batch} (same seq/width), float64 numpy, "
+                      f"{dt:.2f} s for one fwd+bwd" + ("+adafactor" if cfg.adafactor else "")}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c2_small", choices=[k for k in SI.CONFIGS if k != "c1_tiny_f32"])
+    ap.add_argument("--cpu-sample-batch", type=int, default=0, help="0 = pick about 10-30 s of oracle work")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2203_17189_amd as P
+    from paper_2203_17189_amd import binding as B
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    cfg = SI.CONFIGS[args.workload]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    # ---- seeded synthetic inputs, generated on the host, resident in HBM before timing
+    w_host = SI.make_weights(cfg)
+    dt_t = torch.bfloat16
+    w = {k: torch.from_numpy(v.astype(np.float32)).to(dev).to(dt_t) for k, v in w_host.items()}
+    rng = np.random.default_rng(SI.BASE_SEED + 1000 * cfg.index)
+    shape = (cfg.batch, cfg.seq, cfg.d_model)
+    x = torch.from_numpy(rng.standard_normal(shape, dtype=np.float32)).to(dev).to(dt_t)
+    dy = torch.from_numpy(rng.standard_normal(shape, dtype=np.float32)).to(dev).to(dt_t)
+    y = torch.empty_like(x)
+    dx = torch.empty_like(x)
+    stash = torch.empty(P.t5_block_stash_bytes(cfg), dtype=torch.uint8, device=dev)
+    ws = torch.empty(P.t5_block_workspace_bytes(cfg), dtype=torch.uint8, device=dev)
+    grads = B.alloc_grads(cfg, w)
+    opt = None
+    if cfg.adafactor:
+        opt = {}
+        for name in P.WEIGHT_NAMES:
+            master = w[name].float().contiguous()
+            rows, cols = (master.shape[0], master.shape[1]) if master.dim() == 2 else (1, master.numel())
+            fact = master.dim() == 2 and name != "rel_table"
+            opt[name] = dict(master=master, fact=fact,
+                             vr=torch.zeros(rows, device=dev), vc=torch.zeros(cols, device=dev),
+                             vf=None if fact else torch.zeros(rows, cols, device=dev),
+                             ws=torch.empty(max(P.adafactor_workspace_bytes(rows, cols, fact), 256),
+                                            dtype=torch.uint8, device=dev))
+
+    step_no = [0]
+
+    def step():
+        P.t5_block_fwd(cfg, x, w, y=y, stash=stash, workspace=ws)
+        P.t5_block_bwd(cfg, dy, x, w, stash, dx=dx, grads=grads, workspace=ws)
+        if opt is not None:
+            step_no[0] += 1
+            for name, o in opt.items():
+                P.adafactor_step(o["master"], grads[name], step=step_no[0], lr=1e-2, factored=o["fact"],
+                                 v_row=o["vr"], v_col=o["vc"], v_full=o["vf"], bf16_copy_out=w[name],
+                                 workspace=o["ws"])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    tokens_per_s = cfg.tokens * args.steps / dt
+    model_tflops = cfg.model_flops() / (ms_per_step * 1e-3) / 1e12
+
+    # ---- instrumented pass: per-step HIP-event timing on the launch stream
+    P.t5_step_timing_enable(True)
+    n_prof = max(3, min(args.steps, 10))
+    for _ in range(n_prof):
+        step()
+    torch.cuda.synchronize()
+    timing = P.t5_step_timing_read()
+    P.t5_step_timing_enable(False)
+    flops = gemm_step_flops(cfg)
+    per_kernel = {k: {"avg_ms": v[0] / v[1], "launches_per_step": v[1] / n_prof} for k, v in timing.items()}
+    mfma_steps = {k: v for k, v in per_kernel.items() if k in flops}
+    dom = max(mfma_steps, key=lambda k: mfma_steps[k]["avg_ms"] * mfma_steps[k]["launches_per_step"])
+    dom_tflops = flops[dom] / (per_kernel[dom]["avg_ms"] * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": round(dom_tflops, 2), "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(dom_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "avg_ms": round(per_kernel[dom]["avg_ms"], 4)}
+    for k, v in per_kernel.items():
+        v["avg_ms"] = round(v["avg_ms"], 4)
+        if k in flops:
+            v["tflops"] = round(flops[k] / (v["avg_ms"] * 1e-3) / 1e12, 1) if v["avg_ms"] > 0 else None
+
+    out = {
+        "metric": "T5 block fwd+bwd tokens/s and TFLOP/s (bf16) + % MFMA peak, 1 MI355X",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg.name, "batch": cfg.batch, "seq_len": cfg.seq, "d_model": cfg.d_model,
+                   "n_heads": cfg.n_heads, "d_kv": cfg.d_kv, "d_ff": cfg.d_ff, "causal": cfg.causal,
+                   "adafactor": cfg.adafactor, "passes": "fwd+bwd" + ("+adafactor" if cfg.adafactor else "")},
+        "model_tflops": round(model_tflops, 2), "frac_of_mfma_peak": round(model_tflops / PEAK_BF16_TFLOPS, 4),
+        "roofline": roofline, "per_kernel": per_kernel,
+    }
+    if not args.no_cpu_baseline:
+        sb = args.cpu_sample_batch
+        if sb <= 0:
+            # float64 numpy sustains very roughly 50 GFLOP/s on a handful of cores; aim near 15 s
+            per_seq = cfg.model_flops() / cfg.batch
+            sb = int(max(1, min(cfg.batch, 15.0 * 50e9 / per_seq)))
+        out["cpu_baseline"] = cpu_baseline(cfg, sb)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -143,6 +143,23 @@ int adafactor_step(float* param, const float* grad, float* v_row, float* v_col, 
                    int64_t rows, int64_t cols, int factored, const adafactor_cfg* cfg,
                    void* bf16_copy_out, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Building block of the block's projections (paper Sec. 4 models are stacks of such matmuls):
+ * C[m,n] = sum_k A(m,k) B(n,k), bf16 operands, float32 accumulation on the MFMA units, float32 C
+ * [M, ldc].  a_kc != 0: A(m,k) = A[m*lda + k], else A[k*lda + m]; b_kc likewise for B(n,k).
+ * Only a_kc == b_kc is implemented.  Exposed for unit tests and per-kernel timing.
+ * Errors: NULL -> T5_ERR_NULL; M,N,K < 1 -> T5_ERR_SHAPE; K % 64, lda/ldb % 8, pointers not
+ * 16-byte aligned, (m-contiguous case) M or N % 8 -> T5_ERR_UNSUPPORTED. */
+int t5_gemm_bf16(const void* A, const void* B, float* C, int M, int N, int K, int lda, int ldb, int ldc,
+                 int a_kc, int b_kc, void* stream);
+
+/* Per-step device timing of t5_block_fwd / t5_block_bwd for roofline reports.  While enabled, every
+ * step of the block is bracketed by HIP events on the caller's stream; t5_step_timing_read()
+ * synchronises those events and returns, per step, the summed milliseconds and the number of
+ * launches since the last t5_step_timing_enable(1).  names/ms/calls hold up to `cap` entries; the
+ * return value is the number of steps recorded.  Name pointers stay valid for the process. */
+void t5_step_timing_enable(int enable);
+int t5_step_timing_read(const char** names, float* ms, int* calls, int cap);
+
 const char* t5_status_string(int status);
 
 #ifdef __cplusplus

@@ -14,6 +14,9 @@ from .binding import (  # noqa: F401
     t5_block_fwd,
     t5_block_stash_bytes,
     t5_block_workspace_bytes,
+    t5_gemm_bf16,
     t5_relpos_bucket,
+    t5_step_timing_enable,
+    t5_step_timing_read,
     t5_status_string,
 )

@@ -71,6 +71,12 @@ def lib() -> C.CDLL:
     L.adafactor_workspace_bytes.argtypes = [i64, i64, i32]
     L.adafactor_step.restype = i32
     L.adafactor_step.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, C.POINTER(_AfCfg), vp, vp, sz, vp]
+    L.t5_gemm_bf16.restype = i32
+    L.t5_gemm_bf16.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp]
+    L.t5_step_timing_enable.restype = None
+    L.t5_step_timing_enable.argtypes = [i32]
+    L.t5_step_timing_read.restype = i32
+    L.t5_step_timing_read.argtypes = [C.POINTER(C.c_char_p), C.POINTER(C.c_float), C.POINTER(i32), i32]
     _LIB = L
     return L
 
@@ -218,3 +224,31 @@ def adafactor_step(param, grad, *, step, lr, factored, v_row=None, v_col=None, v
     if rc:
         raise T5Error(rc, "adafactor_step")
     return param
+
+
+def t5_gemm_bf16(a: torch.Tensor, b: torch.Tensor, a_kc: bool, b_kc: bool, out: torch.Tensor | None = None):
+    """C[m,n] = sum_k A(m,k) B(n,k) in float32.  a: [M,K] if a_kc else [K,M]; b: [N,K] if b_kc else [K,N]."""
+    for t, nme in ((a, "a"), (b, "b")):
+        _check_tensor(t, torch.bfloat16, t.numel(), nme)
+    M, K = (a.shape[0], a.shape[1]) if a_kc else (a.shape[1], a.shape[0])
+    N = b.shape[0] if b_kc else b.shape[1]
+    if out is None:
+        out = torch.empty(M, N, dtype=torch.float32, device=a.device)
+    rc = lib().t5_gemm_bf16(_ptr(a), _ptr(b), _ptr(out), M, N, K, a.shape[1], b.shape[1], N, int(a_kc), int(b_kc),
+                            _stream())
+    if rc:
+        raise T5Error(rc, "t5_gemm_bf16")
+    return out
+
+
+def t5_step_timing_enable(enable: bool) -> None:
+    lib().t5_step_timing_enable(int(bool(enable)))
+
+
+def t5_step_timing_read(cap: int = 64) -> dict:
+    """{step name: (total ms, launches)} since timing was enabled."""
+    names = (C.c_char_p * cap)()
+    ms = (C.c_float * cap)()
+    calls = (C.c_int * cap)()
+    n = lib().t5_step_timing_read(names, ms, calls, cap)
+    return {names[i].decode(): (float(ms[i]), int(calls[i])) for i in range(n)}

@@ -2,6 +2,8 @@
 // All validation happens before the first HIP call.
 #include <cmath>
 #include <cstring>
+#include <string>
+#include <vector>
 #include "kernels.h"
 
 using namespace t5mi;
@@ -140,6 +142,36 @@ hipError_t run_gemm(const GemmDesc& g, const GemmEpi& e, hipStream_t st) {
     if ((expr) != hipSuccess) return T5_ERR_DEVICE; \
   } while (0)
 
+// ---- optional per-step device timing (see t5_step_timing_enable in the header)
+struct StepRec {
+  const char* name;
+  hipEvent_t e0, e1;
+};
+bool g_timing = false;
+std::vector<StepRec> g_recs;
+
+struct StepScope {
+  hipStream_t st;
+  bool on;
+  StepRec rec;
+  StepScope(const char* name, hipStream_t s) : st(s), on(g_timing) {
+    if (!on) return;
+    rec.name = name;
+    if (hipEventCreate(&rec.e0) != hipSuccess || hipEventCreate(&rec.e1) != hipSuccess) { on = false; return; }
+    (void)hipEventRecord(rec.e0, st);
+  }
+  ~StepScope() {
+    if (!on) return;
+    (void)hipEventRecord(rec.e1, st);
+    g_recs.push_back(rec);
+  }
+};
+#define T5_STEP(name, expr)                           \
+  do {                                                \
+    StepScope scope_(name, st);                       \
+    if ((expr) != hipSuccess) return T5_ERR_DEVICE;   \
+  } while (0)
+
 bool fused_fwd_ok(const Dims& D) {
   // The packed-weight MFMA forward needs the MFMA GEMM for every projection of this shape; the
   // fused gated-GELU GEMM is the most demanding one, so probe it with placeholder pointers.
@@ -213,65 +245,65 @@ int t5_block_fwd(const t5_block_cfg* cfg, const void* x, const t5_block_weights*
   const AttnDims ad{D.B, D.S, D.H, D.dk, cfg->causal ? 1 : 0, cfg->attn_scale};
   const bool fused = fused_fwd_ok(D);
 
-  T5_TRY(launch_relpos_diag(w->rel_table, cfg->dtype, S.diag, D.S, D.H, lut, st));
-  T5_TRY(launch_rmsnorm_fwd(x, ty, w->ln1_scale, S.n1, ty, S.r1, T, D.d, cfg->rms_eps, st));
+  T5_STEP("relpos_diag", launch_relpos_diag(w->rel_table, cfg->dtype, S.diag, D.S, D.H, lut, st));
+  T5_STEP("rmsnorm_fwd", launch_rmsnorm_fwd(x, ty, w->ln1_scale, S.n1, ty, S.r1, T, D.d, cfg->rms_eps, st));
   if (fused) {
     const void* qkv_src[3] = {w->wq, w->wk, w->wv};
-    T5_TRY(launch_pack_transpose_bf16(qkv_src, 3, D.d, D.I, W.wqkv_t, 0, st));
+    T5_STEP("pack_weights", launch_pack_transpose_bf16(qkv_src, 3, D.d, D.I, W.wqkv_t, 0, st));
     GemmDesc g = gemm1(T, 3 * D.I, D.d, S.n1, D.d, 1, W.wqkv_t, D.d, 1, ty);
-    T5_TRY(run_gemm(g, epi(EPI_STORE, S.qkv, 3 * D.I, ty), st));
+    T5_STEP("gemm_qkv", run_gemm(g, epi(EPI_STORE, S.qkv, 3 * D.I, ty), st));
   } else {
     const void* ws3[3] = {w->wq, w->wk, w->wv};
     for (int j = 0; j < 3; ++j) {
       GemmDesc g = gemm1(T, D.I, D.d, S.n1, D.d, 1, ws3[j], D.I, 0, ty);
-      T5_TRY(run_gemm(g, epi(EPI_STORE, at(S.qkv, (size_t)j * D.I, es), 3 * D.I, ty), st));
+      T5_STEP("gemm_qkv", run_gemm(g, epi(EPI_STORE, at(S.qkv, (size_t)j * D.I, es), 3 * D.I, ty), st));
     }
   }
   if (ty == IN_BF16 && attn_mfma_supported(ad))
-    T5_TRY(launch_attn_fwd_mfma(S.qkv, S.diag, S.c, S.lse, ad, st));
+    T5_STEP("attn_fwd", launch_attn_fwd_mfma(S.qkv, S.diag, S.c, S.lse, ad, st));
   else
-    T5_TRY(launch_attn_fwd_simple(S.qkv, ty, S.diag, S.c, S.lse, ad, st));
+    T5_STEP("attn_fwd", launch_attn_fwd_simple(S.qkv, ty, S.diag, S.c, S.lse, ad, st));
   {  // h = x + c Wo  (float32 residual stream)
     GemmDesc g;
     if (fused) {
       const void* src[1] = {w->wo};
-      T5_TRY(launch_pack_transpose_bf16(src, 1, D.I, D.d, W.wo_t, 0, st));
+      T5_STEP("pack_weights", launch_pack_transpose_bf16(src, 1, D.I, D.d, W.wo_t, 0, st));
       g = gemm1(T, D.d, D.I, S.c, D.I, 1, W.wo_t, D.I, 1, ty);
     } else {
       g = gemm1(T, D.d, D.I, S.c, D.I, 1, w->wo, D.d, 0, ty);
     }
     GemmEpi e = epi(EPI_RESID, S.h, D.d, IN_F32);
     e.aux0 = x; e.aux_type = ty;
-    T5_TRY(run_gemm(g, e, st));
+    T5_STEP("gemm_o", run_gemm(g, e, st));
   }
-  T5_TRY(launch_rmsnorm_fwd(S.h, IN_F32, w->ln2_scale, S.n2, ty, S.r2, T, D.d, cfg->rms_eps, st));
+  T5_STEP("rmsnorm_fwd", launch_rmsnorm_fwd(S.h, IN_F32, w->ln2_scale, S.n2, ty, S.r2, T, D.d, cfg->rms_eps, st));
   if (fused) {
     const void* src[2] = {w->wi0, w->wi1};
-    T5_TRY(launch_pack_transpose_bf16(src, 2, D.d, D.F, W.wi_t, 32, st));
+    T5_STEP("pack_weights", launch_pack_transpose_bf16(src, 2, D.d, D.F, W.wi_t, 32, st));
     GemmDesc g = gemm1(T, 2 * D.F, D.d, S.n2, D.d, 1, W.wi_t, D.d, 1, ty);
     GemmEpi e = epi(EPI_GEGLU_FWD, S.u, D.F, ty);
     e.out1 = S.w; e.out2 = S.a;
     if (!gemm_mfma_supported(g, e)) return T5_ERR_UNSUPPORTED;
-    T5_TRY(launch_gemm_mfma(g, e, st));
+    T5_STEP("gemm_wi_geglu", launch_gemm_mfma(g, e, st));
   } else {
     GemmDesc g0 = gemm1(T, D.F, D.d, S.n2, D.d, 1, w->wi0, D.F, 0, ty);
-    T5_TRY(run_gemm(g0, epi(EPI_STORE, S.u, D.F, ty), st));
+    T5_STEP("gemm_wi", run_gemm(g0, epi(EPI_STORE, S.u, D.F, ty), st));
     GemmDesc g1 = gemm1(T, D.F, D.d, S.n2, D.d, 1, w->wi1, D.F, 0, ty);
-    T5_TRY(run_gemm(g1, epi(EPI_STORE, S.w, D.F, ty), st));
-    T5_TRY(launch_geglu_fwd(S.u, S.w, S.a, ty, (int64_t)D.T * D.F, st));
+    T5_STEP("gemm_wi", run_gemm(g1, epi(EPI_STORE, S.w, D.F, ty), st));
+    T5_STEP("geglu_fwd", launch_geglu_fwd(S.u, S.w, S.a, ty, (int64_t)D.T * D.F, st));
   }
   {  // y = h + a Wo_ff
     GemmDesc g;
     if (fused) {
       const void* src[1] = {w->wo_ff};
-      T5_TRY(launch_pack_transpose_bf16(src, 1, D.F, D.d, W.woff_t, 0, st));
+      T5_STEP("pack_weights", launch_pack_transpose_bf16(src, 1, D.F, D.d, W.woff_t, 0, st));
       g = gemm1(T, D.d, D.F, S.a, D.F, 1, W.woff_t, D.F, 1, ty);
     } else {
       g = gemm1(T, D.d, D.F, S.a, D.F, 1, w->wo_ff, D.d, 0, ty);
     }
     GemmEpi e = epi(EPI_RESID, y, D.d, ty);
     e.aux0 = S.h; e.aux_type = IN_F32;
-    T5_TRY(run_gemm(g, e, st));
+    T5_STEP("gemm_wo", run_gemm(g, e, st));
   }
   return T5_OK;
 }
@@ -304,32 +336,32 @@ int t5_block_bwd(const t5_block_cfg* cfg, const void* dy, const void* x, const t
     GemmDesc g = gemm1(D.F, D.d, T, S.a, D.F, 0, dy, D.d, 0, ty);
     GemmEpi e = epi(EPI_SPLIT_F32, dw->wo_ff, D.d, IN_F32);
     e.accumulate = acc;
-    T5_TRY(run_gemm(g, e, st));
+    T5_STEP("gemm_dwo_ff", run_gemm(g, e, st));
   }
   {  // da = dy Wo_ff^T, fused with the gated-GELU backward: du = da w gelu'(u), dw = da gelu(u)
     GemmDesc g = gemm1(T, D.F, D.d, dy, D.d, 1, w->wo_ff, D.d, 1, ty);
     GemmEpi e = epi(EPI_GEGLU_BWD, W.du, D.F, ty);
     e.out1 = W.dw; e.aux0 = S.u; e.aux1 = S.w; e.aux_type = ty;
-    T5_TRY(run_gemm(g, e, st));
+    T5_STEP("gemm_da_geglu_bwd", run_gemm(g, e, st));
   }
   {  // dWi0 = n2^T du, dWi1 = n2^T dw
     GemmDesc g0 = gemm1(D.d, D.F, T, S.n2, D.d, 0, W.du, D.F, 0, ty);
     GemmEpi e0 = epi(EPI_SPLIT_F32, dw->wi0, D.F, IN_F32);
     e0.accumulate = acc;
-    T5_TRY(run_gemm(g0, e0, st));
+    T5_STEP("gemm_dwi", run_gemm(g0, e0, st));
     GemmDesc g1 = gemm1(D.d, D.F, T, S.n2, D.d, 0, W.dw, D.F, 0, ty);
     GemmEpi e1 = epi(EPI_SPLIT_F32, dw->wi1, D.F, IN_F32);
     e1.accumulate = acc;
-    T5_TRY(run_gemm(g1, e1, st));
+    T5_STEP("gemm_dwi", run_gemm(g1, e1, st));
   }
   {  // dn2 = du Wi0^T + dw Wi1^T
     GemmDesc g = gemm1(T, D.d, D.F, W.du, D.F, 1, w->wi0, D.F, 1, ty);
     g.nseg = 2;
     g.seg[1] = GemmSeg{W.dw, w->wi1, D.F, D.F, D.F};
-    T5_TRY(run_gemm(g, epi(EPI_STORE, W.dn, D.d, IN_F32), st));
+    T5_STEP("gemm_dn2", run_gemm(g, epi(EPI_STORE, W.dn, D.d, IN_F32), st));
   }
   // dh = dy + RMSNormBwd(h, g2, dn2)
-  T5_TRY(launch_rmsnorm_bwd(S.h, IN_F32, w->ln2_scale, ty, S.r2, W.dn, dy, ty, W.dh,
+  T5_STEP("rmsnorm_bwd", launch_rmsnorm_bwd(S.h, IN_F32, w->ln2_scale, ty, S.r2, W.dn, dy, ty, W.dh,
                             ty == IN_BF16 ? W.dh_lp : nullptr, ty, dw->ln2_scale, W.dg_partial, acc, T, D.d,
                             st));
   const void* dh_op = ty == IN_BF16 ? (const void*)W.dh_lp : (const void*)W.dh;
@@ -337,35 +369,71 @@ int t5_block_bwd(const t5_block_cfg* cfg, const void* dy, const void* x, const t
     GemmDesc g = gemm1(D.I, D.d, T, S.c, D.I, 0, dh_op, D.d, 0, ty);
     GemmEpi e = epi(EPI_SPLIT_F32, dw->wo, D.d, IN_F32);
     e.accumulate = acc;
-    T5_TRY(run_gemm(g, e, st));
+    T5_STEP("gemm_dwo", run_gemm(g, e, st));
   }
   {  // dc = dh Wo^T
     GemmDesc g = gemm1(T, D.I, D.d, dh_op, D.d, 1, w->wo, D.d, 1, ty);
-    T5_TRY(run_gemm(g, epi(EPI_STORE, W.dc, D.I, ty), st));
+    T5_STEP("gemm_dc", run_gemm(g, epi(EPI_STORE, W.dc, D.I, ty), st));
   }
   if (ty == IN_BF16 && attn_mfma_supported(ad))
-    T5_TRY(launch_attn_bwd_mfma(S.qkv, S.c, W.dc, S.diag, S.lse, W.dvec, W.dqkv, W.ddiag, W.attn_scratch, ad,
+    T5_STEP("attn_bwd", launch_attn_bwd_mfma(S.qkv, S.c, W.dc, S.diag, S.lse, W.dvec, W.dqkv, W.ddiag, W.attn_scratch, ad,
                                 st));
   else
-    T5_TRY(launch_attn_bwd_simple(S.qkv, S.c, W.dc, ty, S.diag, S.lse, W.dvec, W.dqkv, W.ddiag, ad, st));
-  T5_TRY(launch_relpos_diag_bwd(W.ddiag, dw->rel_table, D.S, D.H, cfg->num_buckets, lut, acc, st));
+    T5_STEP("attn_bwd", launch_attn_bwd_simple(S.qkv, S.c, W.dc, ty, S.diag, S.lse, W.dvec, W.dqkv, W.ddiag, ad, st));
+  T5_STEP("relpos_diag_bwd", launch_relpos_diag_bwd(W.ddiag, dw->rel_table, D.S, D.H, cfg->num_buckets, lut, acc, st));
   {  // dWq | dWk | dWv = n1^T dqkv
     GemmDesc g = gemm1(D.d, 3 * D.I, T, S.n1, D.d, 0, W.dqkv, 3 * D.I, 0, ty);
     GemmEpi e = epi(EPI_SPLIT_F32, dw->wq, D.I, IN_F32);
     e.out1 = dw->wk; e.out2 = dw->wv; e.split_n = D.I; e.accumulate = acc;
-    T5_TRY(run_gemm(g, e, st));
+    T5_STEP("gemm_dwqkv", run_gemm(g, e, st));
   }
   {  // dn1 = dq Wq^T + dk Wk^T + dv Wv^T
     GemmDesc g = gemm1(T, D.d, D.I, W.dqkv, 3 * D.I, 1, w->wq, D.I, 1, ty);
     g.nseg = 3;
     g.seg[1] = GemmSeg{at(W.dqkv, (size_t)D.I, es), w->wk, 3 * D.I, D.I, D.I};
     g.seg[2] = GemmSeg{at(W.dqkv, (size_t)2 * D.I, es), w->wv, 3 * D.I, D.I, D.I};
-    T5_TRY(run_gemm(g, epi(EPI_STORE, W.dn, D.d, IN_F32), st));
+    T5_STEP("gemm_dn1", run_gemm(g, epi(EPI_STORE, W.dn, D.d, IN_F32), st));
   }
   // dx = dh + RMSNormBwd(x, g1, dn1)
-  T5_TRY(launch_rmsnorm_bwd(x, ty, w->ln1_scale, ty, S.r1, W.dn, W.dh, IN_F32, ty == IN_F32 ? (float*)dx : nullptr,
+  T5_STEP("rmsnorm_bwd", launch_rmsnorm_bwd(x, ty, w->ln1_scale, ty, S.r1, W.dn, W.dh, IN_F32, ty == IN_F32 ? (float*)dx : nullptr,
                             ty == IN_BF16 ? dx : nullptr, ty, dw->ln1_scale, W.dg_partial, acc, T, D.d, st));
   return T5_OK;
+}
+
+int t5_gemm_bf16(const void* A, const void* B, float* C, int M, int N, int K, int lda, int ldb, int ldc, int a_kc,
+                 int b_kc, void* stream) {
+  if (M < 1 || N < 1 || K < 1 || lda < 1 || ldb < 1 || ldc < N) return T5_ERR_SHAPE;
+  if (!A || !B || !C) return T5_ERR_NULL;
+  GemmDesc g = gemm1(M, N, K, A, lda, a_kc ? 1 : 0, B, ldb, b_kc ? 1 : 0, IN_BF16);
+  GemmEpi e = a_kc ? epi(EPI_STORE, C, ldc, IN_F32) : epi(EPI_SPLIT_F32, C, ldc, IN_F32);
+  if (!gemm_mfma_supported(g, e)) return T5_ERR_UNSUPPORTED;
+  hipStream_t st = (hipStream_t)stream;
+  T5_STEP("gemm_bf16", launch_gemm_mfma(g, e, st));
+  return T5_OK;
+}
+
+void t5_step_timing_enable(int enable) {
+  for (auto& r : g_recs) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
+  g_recs.clear();
+  g_timing = enable != 0;
+}
+
+int t5_step_timing_read(const char** names, float* ms, int* calls, int cap) {
+  int n = 0;
+  for (auto& r : g_recs) {
+    if (hipEventSynchronize(r.e1) != hipSuccess) continue;
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, r.e0, r.e1) != hipSuccess) continue;
+    int k = 0;
+    while (k < n && std::strcmp(names[k], r.name) != 0) ++k;
+    if (k == n) {
+      if (n >= cap) continue;
+      names[n] = r.name; ms[n] = 0.f; calls[n] = 0; ++n;
+    }
+    ms[k] += t;
+    calls[k] += 1;
+  }
+  return n;
 }
 
 size_t adafactor_workspace_bytes(int64_t rows, int64_t cols, int factored) {

@@ -1,0 +1,108 @@
+"""Host-only checks of the C ABI: the library loads, exports every function the header declares,
+and rejects bad arguments before touching the GPU (so these run on a machine without one)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import synth_inputs as SI
+import paper_2203_17189_amd as P
+from paper_2203_17189_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    src = open(os.path.join(ROOT, "include", "t5mi.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    names = re.findall(r"\b([a-z0-9_]+)\s*\([^;{}]*\)\s*;", src)
+    return sorted(set(names))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared_functions()
+    assert {"t5_relpos_bucket", "t5_block_fwd", "t5_block_bwd", "adafactor_step"} <= set(names)
+    lib = P.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings():
+    assert P.t5_status_string(0) == "ok"
+    assert "workspace" in P.t5_status_string(4)
+
+
+def test_size_queries():
+    for cfg in SI.CONFIGS.values():
+        assert P.t5_block_stash_bytes(cfg) > 0 and P.t5_block_workspace_bytes(cfg) > 0
+    bad = SI.CONFIGS["c1_tiny_f32"].with_batch(0)
+    assert P.t5_block_stash_bytes(bad) == 0 and P.t5_block_workspace_bytes(bad) == 0
+    assert P.adafactor_workspace_bytes(0, 5, True) == 0
+    assert P.adafactor_workspace_bytes(64, 64, True) > 0
+
+
+def test_relpos_validation():
+    lib = P.lib()
+    one = C.c_int32(0)
+    p = C.cast(C.pointer(one), C.c_void_p)   # never dereferenced: every case fails validation first
+    assert lib.t5_relpos_bucket(p, p, -1, 1, 32, 128, None) == 2
+    assert lib.t5_relpos_bucket(p, p, 1, 1, 31, 128, None) == 2      # odd buckets, bidirectional
+    assert lib.t5_relpos_bucket(p, p, 1, 1, 32, 8, None) == 2        # max_distance inside exact range
+    assert lib.t5_relpos_bucket(p, p, 1, 0, 1, 128, None) == 2
+    assert lib.t5_relpos_bucket(p, p, 1, 0, 512, 100000, None) == 3  # too many logarithmic buckets
+    assert lib.t5_relpos_bucket(None, p, 1, 1, 32, 128, None) == 1
+    assert lib.t5_relpos_bucket(None, None, 0, 1, 32, 128, None) == 0  # empty input is a no-op
+
+
+def test_block_validation():
+    lib = P.lib()
+    cfg = B._cfg_struct(SI.CONFIGS["c1_tiny_f32"])
+    dummy = C.c_void_p(4096)                  # non-null placeholder; validation fails before any use
+    w = B._Weights(*([4096] * 10))
+    g = B._Grads(*([4096] * 10))
+    assert lib.t5_block_fwd(None, dummy, C.byref(w), dummy, dummy, dummy, 1 << 30, None) == 1
+    assert lib.t5_block_fwd(C.byref(cfg), None, C.byref(w), dummy, dummy, dummy, 1 << 30, None) == 1
+    w_missing = B._Weights(*([4096] * 9 + [None]))
+    assert lib.t5_block_fwd(C.byref(cfg), dummy, C.byref(w_missing), dummy, dummy, dummy, 1 << 30, None) == 1
+    assert lib.t5_block_fwd(C.byref(cfg), dummy, C.byref(w), dummy, dummy, dummy, 16, None) == 4
+    assert lib.t5_block_bwd(C.byref(cfg), dummy, dummy, C.byref(w), dummy, dummy, C.byref(g), 0, dummy, 16,
+                            None) == 4
+    g_missing = B._Grads(*([None] + [4096] * 9))
+    assert lib.t5_block_bwd(C.byref(cfg), dummy, dummy, C.byref(w), dummy, dummy, C.byref(g_missing), 0,
+                            dummy, 1 << 30, None) == 1
+    bad = B._cfg_struct(SI.CONFIGS["c1_tiny_f32"])
+    bad.d_kv = 0
+    assert lib.t5_block_fwd(C.byref(bad), dummy, C.byref(w), dummy, dummy, dummy, 1 << 30, None) == 2
+    bad = B._cfg_struct(SI.CONFIGS["c1_tiny_f32"])
+    bad.dtype = 7
+    assert lib.t5_block_fwd(C.byref(bad), dummy, C.byref(w), dummy, dummy, dummy, 1 << 30, None) == 3
+    bad = B._cfg_struct(SI.CONFIGS["c1_tiny_f32"])
+    bad.num_buckets = 33
+    assert lib.t5_block_fwd(C.byref(bad), dummy, C.byref(w), dummy, dummy, dummy, 1 << 30, None) == 2
+
+
+def test_adafactor_validation():
+    lib = P.lib()
+    dummy = C.c_void_p(4096)
+    ok = B._AfCfg(0.01, 0.8, 1e-30, 1e-3, 1.0, 1, 1)
+    assert lib.adafactor_step(dummy, dummy, dummy, dummy, None, 8, 8, 1, None, None, dummy, 1 << 20, None) == 1
+    assert lib.adafactor_step(dummy, dummy, dummy, dummy, None, 0, 8, 1, C.byref(ok), None, dummy, 1 << 20,
+                              None) == 2
+    step0 = B._AfCfg(0.01, 0.8, 1e-30, 1e-3, 1.0, 1, 0)
+    assert lib.adafactor_step(dummy, dummy, dummy, dummy, None, 8, 8, 1, C.byref(step0), None, dummy, 1 << 20,
+                              None) == 2
+    assert lib.adafactor_step(dummy, dummy, None, dummy, None, 8, 8, 1, C.byref(ok), None, dummy, 1 << 20,
+                              None) == 1
+    assert lib.adafactor_step(dummy, dummy, None, None, None, 8, 8, 0, C.byref(ok), None, dummy, 1 << 20,
+                              None) == 1
+    assert lib.adafactor_step(dummy, dummy, dummy, dummy, None, 8, 8, 1, C.byref(ok), None, dummy, 8, None) == 4
+
+
+def test_gemm_validation():
+    lib = P.lib()
+    dummy = C.c_void_p(4096)
+    assert lib.t5_gemm_bf16(dummy, dummy, dummy, 0, 64, 64, 64, 64, 64, 1, 1, None) == 2
+    assert lib.t5_gemm_bf16(None, dummy, dummy, 64, 64, 64, 64, 64, 64, 1, 1, None) == 1
+    assert lib.t5_gemm_bf16(dummy, dummy, dummy, 64, 64, 72, 72, 72, 64, 1, 1, None) == 3   # K % 64
+    assert lib.t5_gemm_bf16(dummy, dummy, dummy, 64, 64, 64, 64, 64, 64, 1, 0, None) == 3   # mixed layouts
