@@ -1,7 +1,556 @@
+// Fused self-attention with the T5 relative-position bias for gfx950 (bf16 MFMA 32x32x16,
+// float32 online softmax).  The S x S scores never leave registers.
+//
+// Forward and the dq kernel give each lane one query: scores are computed transposed,
+// S^T = K Q^T, so the MFMA result layout puts a query in lane%32 and 16 keys of a 32-key tile in
+// the lane's registers.  Row maxima and sums are then register reductions plus one exchange between
+// the two lane halves, and the probabilities feed the second matmul (O^T = V^T P^T) straight from
+// the result registers: the contraction index of an MFMA may be permuted freely as long as both
+// operands use the same permutation, and the V^T operand is fetched with that permutation by the
+// LDS transpose load.  The dk/dv kernel mirrors this with one key per lane (S = Q K^T).
+//
+// The bias is Toeplitz: bias[h,i,j] = diag[h][j - i + S - 1].  Each workgroup stages the slice of
+// the per-head diagonal vector it can touch (S + tile - 1 floats) in LDS.
 #include "kernels.h"
+
 namespace t5mi {
-bool attn_mfma_supported(const AttnDims&) { return false; }
-hipError_t launch_attn_fwd_mfma(const void*, const float*, void*, float*, const AttnDims&, hipStream_t) { return hipErrorInvalidValue; }
-size_t attn_bwd_mfma_scratch_bytes(const AttnDims&) { return 0; }
-hipError_t launch_attn_bwd_mfma(const void*, const void*, const void*, const float*, const float*, float*, void*, float*, void*, const AttnDims&, hipStream_t) { return hipErrorInvalidValue; }
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+typedef __attribute__((address_space(3))) short4v lds_short4;
+typedef __attribute__((ext_vector_type(8))) short short8v;
+
+// Row-dependent XOR applied to the 16-byte chunk index of a [rows][DK] bf16 tile.  Chosen so that
+// both access patterns are bank-conflict free: 16 consecutive rows x one chunk (ds_read_b128
+// operand reads) and 4 consecutive rows x 4 consecutive chunks (transpose reads).
+template <int DK>
+__device__ __forceinline__ int row_swz(int row) {
+  if constexpr (DK == 64)
+    return (((row >> 1) & 1) << 2) | (((row >> 2) & 1) << 1) | ((row >> 3) & 1);
+  else
+    return ((row & 1) << 2) | (((row >> 1) & 1) << 3) | ((row >> 2) & 1) | (((row >> 3) & 1) << 1);
 }
+template <int DK>
+__device__ __forceinline__ int tile_off(int row, int chunk) {
+  return row * (DK * 2) + ((chunk ^ row_swz<DK>(row)) << 4);
+}
+
+// Cooperative copy of `rows` rows of DK bf16 (row r at src + r*ld) into a swizzled LDS tile.
+// Rows at or beyond `valid` are clamped to the last valid row (their results are never used).
+template <int DK, int NT>
+__device__ __forceinline__ void load_tile(char* dst, const bf16* __restrict__ src, size_t ld, int rows,
+                                          int valid, int tid) {
+  constexpr int CPR = DK / 8;
+  for (int q = tid; q < rows * CPR; q += NT) {
+    const int row = q / CPR, ch = q % CPR;
+    const int rs = row < valid ? row : valid - 1;
+    *reinterpret_cast<u32x4*>(dst + tile_off<DK>(row, ch)) =
+        *reinterpret_cast<const u32x4*>(src + (size_t)rs * ld + ch * 8);
+  }
+}
+
+// Operand with 8 consecutive channels of row (base + lane%32): k-step kk covers channels kk*16..+15.
+template <int DK>
+__device__ __forceinline__ bf16x8 frag_rows(const char* tile, int base, int kk, int lane) {
+  return *reinterpret_cast<const bf16x8*>(tile + tile_off<DK>(base + (lane & 31), kk * 2 + (lane >> 5)));
+}
+
+// Transposed operand: MFMA row = channel (cbase + lane%32), contraction over tile rows.  Slot jj of
+// lane half g holds tile row  rbase + 8*(jj/4) + 4*g + jj%4  -- the order in which the 32x32 result
+// layout keeps rows 8*(r/4) + 4*g + r%4 in consecutive registers.
+template <int DK>
+__device__ __forceinline__ bf16x8 frag_cols_tr(const char* tile, int rbase, int cbase, int lane) {
+  const int i16 = lane & 15;
+  const int ch_e = cbase + (((lane >> 4) & 1) << 4) + ((i16 & 3) << 2);  // first of 4 channels addressed
+  const int row0 = rbase + ((lane >> 5) << 2) + (i16 >> 2);
+  const int row1 = row0 + 8;
+  const int o0 = tile_off<DK>(row0, ch_e >> 3) + ((ch_e & 7) << 1);
+  const int o1 = tile_off<DK>(row1, ch_e >> 3) + ((ch_e & 7) << 1);
+  short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(tile + o0));
+  short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(tile + o1));
+  short8v r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+__device__ __forceinline__ bf16x8 pack8(const f32x16& v, int first) {
+  bf16x8 o;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) o[i] = (bf16)v[first + i];
+  return o;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// ------------------------------------------------------------------------------------------------
+// Forward.  grid (ceil(S/128), H, B), 256 threads; wave w owns queries i0 + 32w + lane%32.
+// ------------------------------------------------------------------------------------------------
+template <int DK, bool CAUSAL>
+__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv,
+                                                            const float* __restrict__ diag,
+                                                            bf16* __restrict__ c, float* __restrict__ lse,
+                                                            AttnDims a) {
+  constexpr int BR = 128, BC = 64, KS = DK / 16, CT = DK / 32;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  char* Kt = smem;
+  char* Vt = smem + BC * DK * 2;
+  float* dg = reinterpret_cast<float*>(smem + 2 * BC * DK * 2);  // [S + BR - 1], log2 units
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
+  const int S = a.S, I = a.H * DK;
+  const size_t ld = (size_t)3 * I;
+  const int qt = CAUSAL ? (gridDim.x - 1 - blockIdx.x) : blockIdx.x;  // heavy causal tiles first
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int i0 = qt * BR;
+  const int i_loc = wave * 32 + (lane & 31);
+  const int i = i0 + i_loc;
+  const int i_ld = i < S ? i : S - 1;
+  const bf16* base = qkv + (size_t)b * S * ld + h * DK;
+
+  bf16x8 qf[KS];
+  {
+    const bf16* qrow = base + (size_t)i_ld * ld;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qrow + kk * 16 + g * 8);
+  }
+  {
+    const float* dgh = diag + (size_t)h * (2 * S - 1);
+    for (int t = tid; t < S + BR - 1; t += 256) {
+      int idx = t - (i0 + BR - 1) + (S - 1);  // delta + S - 1
+      idx = idx < 0 ? 0 : idx;                // only reachable by clamped (unused) queries
+      dg[t] = dgh[idx] * kLog2e;
+    }
+  }
+  const float sc = a.scale * kLog2e;
+  const int dg_base = BR - 1 - i_loc;  // dg[dg_base + j] = bias(j - i)
+
+  f32x16 oT[CT];
+#pragma unroll
+  for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oT[ct][r] = 0.f;
+  float m = -INFINITY, l = 0.f;
+
+  int n_kv = S / BC;
+  if (CAUSAL) {
+    const int last = (i0 + BR < S ? i0 + BR : S);
+    n_kv = (last + BC - 1) / BC;
+  }
+  for (int jt = 0; jt < n_kv; ++jt) {
+    const int j0 = jt * BC;
+    __syncthreads();
+    load_tile<DK, 256>(Kt, base + (size_t)j0 * ld + I, ld, BC, BC, tid);
+    load_tile<DK, 256>(Vt, base + (size_t)j0 * ld + 2 * I, ld, BC, BC, tid);
+    __syncthreads();
+
+    f32x16 sT[BC / 32];
+#pragma unroll
+    for (int kt = 0; kt < BC / 32; ++kt) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sT[kt][r] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk)
+        sT[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Kt, kt * 32, kk, lane), qf[kk], sT[kt],
+                                                        0, 0, 0);
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < BC / 32; ++kt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int j = j0 + kt * 32 + ((r >> 2) << 3) + (g << 2) + (r & 3);
+        float s = fmaf(sT[kt][r], sc, dg[dg_base + j]);
+        if (CAUSAL && j > i) s = -INFINITY;
+        sT[kt][r] = s;
+        mx = fmaxf(mx, s);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m, mx);
+    const float alpha = fast_exp2(m - m_new);
+    m = m_new;
+    float ls = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < BC / 32; ++kt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = fast_exp2(sT[kt][r] - m_new);
+        sT[kt][r] = p;
+        ls += p;
+      }
+    l = l * alpha + ls;
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oT[ct][r] *= alpha;
+#pragma unroll
+    for (int kt = 0; kt < BC / 32; ++kt)
+#pragma unroll
+      for (int mm = 0; mm < 2; ++mm) {
+        const bf16x8 pf = pack8(sT[kt], mm * 8);
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+          oT[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_tr<DK>(Vt, kt * 32 + mm * 16, ct * 32, lane),
+                                                          pf, oT[ct], 0, 0, 0);
+      }
+  }
+  const float l_tot = l + __shfl_xor(l, 32, 64);
+  if (i < S) {
+    const float inv = 1.f / l_tot;
+    bf16* crow = c + ((size_t)b * S + i) * I + h * DK;
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        bf16x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (bf16)(oT[ct][rq * 4 + e] * inv);
+        *reinterpret_cast<bf16x4*>(crow + ct * 32 + rq * 8 + g * 4) = o;
+      }
+    if (g == 0) lse[((size_t)b * a.H + h) * S + i] = (m + __builtin_amdgcn_logf(l_tot)) * kLn2;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// dvec[b,h,i] = sum_c dO[b,i,h,c] * O[b,i,h,c].  One wave per 64/DK*... rows: lane handles 8 channels.
+// ------------------------------------------------------------------------------------------------
+template <int DK>
+__global__ __launch_bounds__(256) void attn_dvec_kernel(const bf16* __restrict__ o, const bf16* __restrict__ dout,
+                                                        float* __restrict__ dvec, AttnDims a) {
+  constexpr int LPR = DK / 8;  // lanes per (token, head) row
+  const int64_t rows = (int64_t)a.B * a.S * a.H;
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t row = gid / LPR;
+  const int part = (int)(gid % LPR);
+  float s = 0.f;
+  if (row < rows) {
+    const bf16x8 x = *reinterpret_cast<const bf16x8*>(o + row * DK + part * 8);
+    const bf16x8 y = *reinterpret_cast<const bf16x8*>(dout + row * DK + part * 8);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s += (float)x[e] * (float)y[e];
+  }
+#pragma unroll
+  for (int off = LPR / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+  if (row < rows && part == 0) {
+    const int64_t tok = row / a.H;
+    const int hh = (int)(row % a.H);
+    const int64_t bb = tok / a.S, ii = tok % a.S;
+    dvec[(bb * a.H + hh) * a.S + ii] = s;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// dq and the per-diagonal bias gradient.  Same ownership as the forward (lane = query).
+// ------------------------------------------------------------------------------------------------
+template <int DK, bool CAUSAL>
+__global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv,
+                                                               const bf16* __restrict__ dout,
+                                                               const float* __restrict__ diag,
+                                                               const float* __restrict__ lse,
+                                                               const float* __restrict__ dvec,
+                                                               bf16* __restrict__ dqkv, float* __restrict__ ddiag,
+                                                               AttnDims a) {
+  constexpr int BR = 128, BC = 64, KS = DK / 16, CT = DK / 32;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  char* Kt = smem;
+  char* Vt = smem + BC * DK * 2;
+  float* dg = reinterpret_cast<float*>(smem + 2 * BC * DK * 2);  // [S + BR - 1] bias, log2 units
+  float* ddg = dg + (a.S + BR - 1);                              // [S + BR - 1] gradient accumulators
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
+  const int S = a.S, I = a.H * DK;
+  const size_t ld = (size_t)3 * I;
+  const int qt = CAUSAL ? (gridDim.x - 1 - blockIdx.x) : blockIdx.x;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int i0 = qt * BR;
+  const int i_loc = wave * 32 + (lane & 31);
+  const int i = i0 + i_loc;
+  const int i_ld = i < S ? i : S - 1;
+  const bf16* base = qkv + (size_t)b * S * ld + h * DK;
+
+  bf16x8 qf[KS], dof[KS];
+  {
+    const bf16* qrow = base + (size_t)i_ld * ld;
+    const bf16* drow = dout + ((size_t)b * S + i_ld) * I + h * DK;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+      qf[kk] = *reinterpret_cast<const bf16x8*>(qrow + kk * 16 + g * 8);
+      dof[kk] = *reinterpret_cast<const bf16x8*>(drow + kk * 16 + g * 8);
+    }
+  }
+  const size_t srow = ((size_t)b * a.H + h) * S + i_ld;
+  const float lse2 = lse[srow] * kLog2e;
+  const float dv_i = dvec[srow];
+  {
+    const float* dgh = diag + (size_t)h * (2 * S - 1);
+    for (int t = tid; t < S + BR - 1; t += 256) {
+      int idx = t - (i0 + BR - 1) + (S - 1);
+      idx = idx < 0 ? 0 : idx;
+      dg[t] = dgh[idx] * kLog2e;
+      ddg[t] = 0.f;
+    }
+  }
+  const float sc = a.scale * kLog2e;
+  const int dg_base = BR - 1 - i_loc;
+
+  f32x16 dqT[CT];
+#pragma unroll
+  for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dqT[ct][r] = 0.f;
+
+  int n_kv = S / BC;
+  if (CAUSAL) {
+    const int last = (i0 + BR < S ? i0 + BR : S);
+    n_kv = (last + BC - 1) / BC;
+  }
+  for (int jt = 0; jt < n_kv; ++jt) {
+    const int j0 = jt * BC;
+    __syncthreads();
+    load_tile<DK, 256>(Kt, base + (size_t)j0 * ld + I, ld, BC, BC, tid);
+    load_tile<DK, 256>(Vt, base + (size_t)j0 * ld + 2 * I, ld, BC, BC, tid);
+    __syncthreads();
+#pragma unroll
+    for (int kt = 0; kt < BC / 32; ++kt) {
+      f32x16 sT, dpT;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sT[r] = 0.f; dpT[r] = 0.f; }
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk) {
+        sT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Kt, kt * 32, kk, lane), qf[kk], sT, 0, 0, 0);
+        dpT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Vt, kt * 32, kk, lane), dof[kk], dpT, 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int j = j0 + kt * 32 + ((r >> 2) << 3) + (g << 2) + (r & 3);
+        float p = fast_exp2(fmaf(sT[r], sc, dg[dg_base + j]) - lse2);
+        if (CAUSAL && j > i) p = 0.f;
+        const float ds = (i < S) ? p * (dpT[r] - dv_i) : 0.f;
+        sT[r] = ds;
+        atomicAdd(&ddg[dg_base + j], ds);
+      }
+#pragma unroll
+      for (int mm = 0; mm < 2; ++mm) {
+        const bf16x8 dsf = pack8(sT, mm * 8);
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+          dqT[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              frag_cols_tr<DK>(Kt, kt * 32 + mm * 16, ct * 32, lane), dsf, dqT[ct], 0, 0, 0);
+      }
+    }
+  }
+  if (i < S) {
+    bf16* qrow = dqkv + ((size_t)b * S + i) * ld + h * DK;
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        bf16x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (bf16)(dqT[ct][rq * 4 + e] * a.scale);
+        *reinterpret_cast<bf16x4*>(qrow + ct * 32 + rq * 8 + g * 4) = o;
+      }
+  }
+  __syncthreads();
+  {
+    float* ddh = ddiag + (size_t)h * (2 * S - 1);
+    for (int t = tid; t < S + BR - 1; t += 256) {
+      const int idx = t - (i0 + BR - 1) + (S - 1);
+      const float v = ddg[t];
+      if (idx >= 0 && idx < 2 * S - 1 && v != 0.f) unsafeAtomicAdd(&ddh[idx], v);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// dk and dv.  grid (ceil(S/128), H, B); wave w owns keys j0 + 32w + lane%32; loops over query tiles.
+// ------------------------------------------------------------------------------------------------
+template <int DK, bool CAUSAL>
+__global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __restrict__ qkv,
+                                                                const bf16* __restrict__ dout,
+                                                                const float* __restrict__ diag,
+                                                                const float* __restrict__ lse,
+                                                                const float* __restrict__ dvec,
+                                                                bf16* __restrict__ dqkv, AttnDims a) {
+  constexpr int BCK = 128, BQ = 64, KS = DK / 16, CT = DK / 32;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  char* Qt = smem;
+  char* Dt = smem + BQ * DK * 2;
+  float* lse_s = reinterpret_cast<float*>(smem + 2 * BQ * DK * 2);  // [BQ] log2 units
+  float* dv_s = lse_s + BQ;                                         // [BQ]
+  float* dg = dv_s + BQ;                                            // [S + BCK - 1] log2 units
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
+  const int S = a.S, I = a.H * DK;
+  const size_t ld = (size_t)3 * I;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int j0 = blockIdx.x * BCK;
+  const int j_loc = wave * 32 + (lane & 31);
+  const int j = j0 + j_loc;
+  const int j_ld = j < S ? j : S - 1;
+  const bf16* base = qkv + (size_t)b * S * ld + h * DK;
+  const bf16* dobase = dout + (size_t)b * S * I + h * DK;
+
+  bf16x8 kf[KS], vf[KS];
+  {
+    const bf16* krow = base + (size_t)j_ld * ld + I;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+      kf[kk] = *reinterpret_cast<const bf16x8*>(krow + kk * 16 + g * 8);
+      vf[kk] = *reinterpret_cast<const bf16x8*>(krow + I + kk * 16 + g * 8);
+    }
+  }
+  {
+    // dg[t] = bias(delta) for delta = t + j0 - (S - 1), t in [0, S + BCK - 1)
+    const float* dgh = diag + (size_t)h * (2 * S - 1);
+    for (int t = tid; t < S + BCK - 1; t += 256) {
+      int idx = t + j0;  // delta + S - 1
+      idx = idx > 2 * S - 2 ? 2 * S - 2 : idx;
+      dg[t] = dgh[idx] * kLog2e;
+    }
+  }
+  const float sc = a.scale * kLog2e;
+  // dg index of (query i, key j): (j - i) - (j0 - (S-1)) = j_loc + (S - 1 - i)
+  f32x16 dkT[CT], dvT[CT];
+#pragma unroll
+  for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dkT[ct][r] = 0.f; dvT[ct][r] = 0.f; }
+
+  const int it_begin = CAUSAL ? (j0 / BQ) : 0;
+  const size_t srow = ((size_t)b * a.H + h) * S;
+  for (int it = it_begin; it < S / BQ; ++it) {
+    const int q0 = it * BQ;
+    __syncthreads();
+    load_tile<DK, 256>(Qt, base + (size_t)q0 * ld, ld, BQ, BQ, tid);
+    load_tile<DK, 256>(Dt, dobase + (size_t)q0 * I, (size_t)I, BQ, BQ, tid);
+    if (tid < BQ) {
+      lse_s[tid] = lse[srow + q0 + tid] * kLog2e;
+      dv_s[tid] = dvec[srow + q0 + tid];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int qb = 0; qb < BQ / 32; ++qb) {
+      f32x16 s, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk) {
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Qt, qb * 32, kk, lane), kf[kk], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Dt, qb * 32, kk, lane), vf[kk], dp, 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int il = qb * 32 + ((r >> 2) << 3) + (g << 2) + (r & 3);
+        const int i = q0 + il;
+        float p = fast_exp2(fmaf(s[r], sc, dg[j_loc + (S - 1 - i)]) - lse_s[il]);
+        if (CAUSAL && j > i) p = 0.f;
+        s[r] = p;
+        dp[r] = p * (dp[r] - dv_s[il]);
+      }
+#pragma unroll
+      for (int mm = 0; mm < 2; ++mm) {
+        const bf16x8 pf = pack8(s, mm * 8), dsf = pack8(dp, mm * 8);
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+          dvT[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              frag_cols_tr<DK>(Dt, qb * 32 + mm * 16, ct * 32, lane), pf, dvT[ct], 0, 0, 0);
+          dkT[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              frag_cols_tr<DK>(Qt, qb * 32 + mm * 16, ct * 32, lane), dsf, dkT[ct], 0, 0, 0);
+        }
+      }
+    }
+  }
+  if (j < S) {
+    bf16* krow = dqkv + ((size_t)b * S + j) * ld + I + h * DK;
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        bf16x4 ok, ov;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          ok[e] = (bf16)(dkT[ct][rq * 4 + e] * a.scale);
+          ov[e] = (bf16)dvT[ct][rq * 4 + e];
+        }
+        *reinterpret_cast<bf16x4*>(krow + ct * 32 + rq * 8 + g * 4) = ok;
+        *reinterpret_cast<bf16x4*>(krow + I + ct * 32 + rq * 8 + g * 4) = ov;
+      }
+  }
+}
+
+__global__ void zero_kernel(float* p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0.f;
+}
+
+template <typename K>
+hipError_t set_lds(K kern, size_t bytes) {
+  return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+template <int DK, bool CAUSAL>
+hipError_t fwd_launch(const void* qkv, const float* diag, void* c, float* lse, const AttnDims& a, hipStream_t st) {
+  auto kern = attn_fwd_mfma_kernel<DK, CAUSAL>;
+  const size_t lds = 2 * 64 * DK * 2 + sizeof(float) * (a.S + 127);
+  hipError_t e = set_lds(kern, lds);
+  if (e != hipSuccess) return e;
+  kern<<<dim3(ceil_div(a.S, 128), a.H, a.B), 256, lds, st>>>((const bf16*)qkv, diag, (bf16*)c, lse, a);
+  return hipGetLastError();
+}
+
+template <int DK, bool CAUSAL>
+hipError_t bwd_launch(const void* qkv, const void* c, const void* dc, const float* diag, const float* lse,
+                      float* dvec, void* dqkv, float* ddiag, const AttnDims& a, hipStream_t st) {
+  const int64_t rows = (int64_t)a.B * a.S * a.H;
+  attn_dvec_kernel<DK><<<ceil_div(rows * (DK / 8), 256), 256, 0, st>>>((const bf16*)c, (const bf16*)dc, dvec, a);
+  const int64_t nd = (int64_t)a.H * (2 * a.S - 1);
+  zero_kernel<<<ceil_div(nd, 256), 256, 0, st>>>(ddiag, nd);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const dim3 grid(ceil_div(a.S, 128), a.H, a.B);
+  {
+    auto kern = attn_bwd_dq_mfma_kernel<DK, CAUSAL>;
+    const size_t lds = 2 * 64 * DK * 2 + 2 * sizeof(float) * (a.S + 127);
+    if ((e = set_lds(kern, lds)) != hipSuccess) return e;
+    kern<<<grid, 256, lds, st>>>((const bf16*)qkv, (const bf16*)dc, diag, lse, dvec, (bf16*)dqkv, ddiag, a);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  {
+    auto kern = attn_bwd_dkv_mfma_kernel<DK, CAUSAL>;
+    const size_t lds = 2 * 64 * DK * 2 + sizeof(float) * (128 + a.S + 127);
+    if ((e = set_lds(kern, lds)) != hipSuccess) return e;
+    kern<<<grid, 256, lds, st>>>((const bf16*)qkv, (const bf16*)dc, diag, lse, dvec, (bf16*)dqkv, a);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+}  // namespace
+
+bool attn_mfma_supported(const AttnDims& a) {
+  // S % 128: query/key tiles of 128 without ragged edges; LDS holds the diagonal slice (S + 127 floats)
+  return (a.dk == 64 || a.dk == 128) && a.S % 128 == 0 && a.S <= 8192;
+}
+
+hipError_t launch_attn_fwd_mfma(const void* qkv, const float* diag, void* c, float* lse, const AttnDims& a,
+                                hipStream_t st) {
+  if (a.dk == 64) return a.causal ? fwd_launch<64, true>(qkv, diag, c, lse, a, st)
+                                  : fwd_launch<64, false>(qkv, diag, c, lse, a, st);
+  return a.causal ? fwd_launch<128, true>(qkv, diag, c, lse, a, st)
+                  : fwd_launch<128, false>(qkv, diag, c, lse, a, st);
+}
+
+size_t attn_bwd_mfma_scratch_bytes(const AttnDims&) { return 0; }
+
+hipError_t launch_attn_bwd_mfma(const void* qkv, const void* c, const void* dc, const float* diag,
+                                const float* lse, float* dvec, void* dqkv, float* ddiag, void*,
+                                const AttnDims& a, hipStream_t st) {
+  if (a.dk == 64) return a.causal ? bwd_launch<64, true>(qkv, c, dc, diag, lse, dvec, dqkv, ddiag, a, st)
+                                  : bwd_launch<64, false>(qkv, c, dc, diag, lse, dvec, dqkv, ddiag, a, st);
+  return a.causal ? bwd_launch<128, true>(qkv, c, dc, diag, lse, dvec, dqkv, ddiag, a, st)
+                  : bwd_launch<128, false>(qkv, c, dc, diag, lse, dvec, dqkv, ddiag, a, st);
+}
+
+}  // namespace t5mi

@@ -109,6 +109,14 @@ SMALL_BF16 = [
                    attn_scale=64 ** -0.5),
     SI.BlockConfig("bf16_dec", 31, batch=2, seq=192, d_model=128, n_heads=2, d_kv=64, d_ff=256, causal=True,
                    attn_scale=64 ** -0.5),
+    SI.BlockConfig("bf16_dec_mfma", 33, batch=2, seq=384, d_model=128, n_heads=2, d_kv=64, d_ff=256, causal=True,
+                   attn_scale=64 ** -0.5),
+    SI.BlockConfig("bf16_enc_dk128", 34, batch=1, seq=256, d_model=256, n_heads=2, d_kv=128, d_ff=320,
+                   attn_scale=128 ** -0.5),
+    SI.BlockConfig("bf16_dec_dk128", 35, batch=2, seq=256, d_model=128, n_heads=3, d_kv=128, d_ff=192, causal=True,
+                   attn_scale=128 ** -0.5),
+    SI.BlockConfig("bf16_enc_long", 36, batch=1, seq=1024, d_model=64, n_heads=1, d_kv=64, d_ff=64,
+                   attn_scale=64 ** -0.5),
     SI.BlockConfig("bf16_ragged", 32, batch=1, seq=100, d_model=72, n_heads=3, d_kv=24, d_ff=136,
                    attn_scale=24 ** -0.5),
 ]
