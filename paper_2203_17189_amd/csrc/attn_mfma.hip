@@ -242,6 +242,13 @@ __global__ __launch_bounds__(256) void attn_dvec_kernel(const bf16* __restrict__
 
 // ------------------------------------------------------------------------------------------------
 // dq and the per-diagonal bias gradient.  Same ownership as the forward (lane = query).
+//
+// Bias gradient: ddiag[delta] = sum over (b, i) of ds[i, i + delta].  Each wave reduces the
+// diagonals of its 32x32 ds sub-tile through a private LDS staging block (plain stores, then lane t
+// sums diagonal t - 31) and adds them to a wave-private diagonal array with plain read-modify-write:
+// no LDS atomics.  Sub-tiles whose every offset lies in the saturated last bucket (|delta| >= far)
+// skip all that and add into one scalar per lane; it is credited to the outermost diagonal, which
+// is in the same bucket.
 // ------------------------------------------------------------------------------------------------
 template <int DK, bool CAUSAL>
 __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv,
@@ -250,13 +257,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __res
                                                                const float* __restrict__ lse,
                                                                const float* __restrict__ dvec,
                                                                bf16* __restrict__ dqkv, float* __restrict__ ddiag,
-                                                               AttnDims a) {
-  constexpr int BR = 128, BC = 64, KS = DK / 16, CT = DK / 32;
+                                                               AttnDims a, int far) {
+  constexpr int BR = 128, BC = 64, KS = DK / 16, CT = DK / 32, DSP = 36;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   char* Kt = smem;
   char* Vt = smem + BC * DK * 2;
-  float* dg = reinterpret_cast<float*>(smem + 2 * BC * DK * 2);  // [S + BR - 1] bias, log2 units
-  float* ddg = dg + (a.S + BR - 1);                              // [S + BR - 1] gradient accumulators
+  float* dst_all = reinterpret_cast<float*>(smem + 2 * BC * DK * 2);  // [4 waves][32][DSP] ds staging
+  float* dg = dst_all + 4 * 32 * DSP;                                // [S + BR - 1] bias, log2 units
+  float* ddg_all = dg + (a.S + BR - 1);                              // [4 waves][S + 31]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
   const int S = a.S, I = a.H * DK;
@@ -264,35 +272,35 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __res
   const int qt = CAUSAL ? (gridDim.x - 1 - blockIdx.x) : blockIdx.x;
   const int h = blockIdx.y, b = blockIdx.z;
   const int i0 = qt * BR;
-  const int i_loc = wave * 32 + (lane & 31);
+  const int i_w0 = i0 + wave * 32;         // first query of this wave
+  const int i_lw = lane & 31;              // query index inside the wave
+  const int i_loc = wave * 32 + i_lw;
   const int i = i0 + i_loc;
-  const int i_ld = i < S ? i : S - 1;
   const bf16* base = qkv + (size_t)b * S * ld + h * DK;
+  float* dsw = dst_all + wave * 32 * DSP;
+  float* ddgw = ddg_all + wave * (S + 31);  // ddgw[u], u = j - i_lw + 31
 
   bf16x8 qf[KS], dof[KS];
   {
-    const bf16* qrow = base + (size_t)i_ld * ld;
-    const bf16* drow = dout + ((size_t)b * S + i_ld) * I + h * DK;
+    const bf16* qrow = base + (size_t)i * ld;
+    const bf16* drow = dout + ((size_t)b * S + i) * I + h * DK;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
       qf[kk] = *reinterpret_cast<const bf16x8*>(qrow + kk * 16 + g * 8);
       dof[kk] = *reinterpret_cast<const bf16x8*>(drow + kk * 16 + g * 8);
     }
   }
-  const size_t srow = ((size_t)b * a.H + h) * S + i_ld;
+  const size_t srow = ((size_t)b * a.H + h) * S + i;
   const float lse2 = lse[srow] * kLog2e;
   const float dv_i = dvec[srow];
   {
     const float* dgh = diag + (size_t)h * (2 * S - 1);
-    for (int t = tid; t < S + BR - 1; t += 256) {
-      int idx = t - (i0 + BR - 1) + (S - 1);
-      idx = idx < 0 ? 0 : idx;
-      dg[t] = dgh[idx] * kLog2e;
-      ddg[t] = 0.f;
-    }
+    for (int t = tid; t < S + BR - 1; t += 256) dg[t] = dgh[t - (i0 + BR - 1) + (S - 1)] * kLog2e;
+    for (int t = tid; t < 4 * (S + 31); t += 256) ddg_all[t] = 0.f;
   }
   const float sc = a.scale * kLog2e;
   const int dg_base = BR - 1 - i_loc;
+  float far_neg = 0.f, far_pos = 0.f;
 
   f32x16 dqT[CT];
 #pragma unroll
@@ -300,11 +308,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __res
 #pragma unroll
     for (int r = 0; r < 16; ++r) dqT[ct][r] = 0.f;
 
-  int n_kv = S / BC;
-  if (CAUSAL) {
-    const int last = (i0 + BR < S ? i0 + BR : S);
-    n_kv = (last + BC - 1) / BC;
-  }
+  const int n_kv = CAUSAL ? (i0 + BR) / BC : S / BC;
   for (int jt = 0; jt < n_kv; ++jt) {
     const int j0 = jt * BC;
     __syncthreads();
@@ -313,6 +317,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __res
     __syncthreads();
 #pragma unroll
     for (int kt = 0; kt < BC / 32; ++kt) {
+      const int j0s = j0 + kt * 32;
+      if (CAUSAL && j0s > i_w0 + 31) continue;  // whole sub-tile masked for this wave
       f32x16 sT, dpT;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { sT[r] = 0.f; dpT[r] = 0.f; }
@@ -323,12 +329,41 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __res
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int j = j0 + kt * 32 + ((r >> 2) << 3) + (g << 2) + (r & 3);
+        const int j = j0s + ((r >> 2) << 3) + (g << 2) + (r & 3);
         float p = fast_exp2(fmaf(sT[r], sc, dg[dg_base + j]) - lse2);
         if (CAUSAL && j > i) p = 0.f;
-        const float ds = (i < S) ? p * (dpT[r] - dv_i) : 0.f;
-        sT[r] = ds;
-        atomicAdd(&ddg[dg_base + j], ds);
+        sT[r] = p * (dpT[r] - dv_i);
+      }
+      // ---- bias gradient of this 32x32 sub-tile (wave-uniform branches)
+      if (j0s + 31 - i_w0 <= -far) {
+        float t = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) t += sT[r];
+        far_neg += t;
+      } else if (!CAUSAL && j0s - i_w0 - 31 >= far) {
+        float t = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) t += sT[r];
+        far_pos += t;
+      } else {
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+          f32x4 v = {sT[rq * 4], sT[rq * 4 + 1], sT[rq * 4 + 2], sT[rq * 4 + 3]};
+          *reinterpret_cast<f32x4*>(dsw + i_lw * DSP + rq * 8 + g * 4) = v;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        // lane t < 63 owns diagonal key_local - query_local = t - 31
+        float t = 0.f;
+        const int dl = lane - 31;
+#pragma unroll
+        for (int q = 0; q < 32; ++q) {
+          const int kl = q + dl;
+          if (kl >= 0 && kl < 32) t += dsw[q * DSP + kl];
+        }
+        if (lane < 63) ddgw[j0s + lane] += t;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
       }
 #pragma unroll
       for (int mm = 0; mm < 2; ++mm) {
@@ -340,7 +375,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __res
       }
     }
   }
-  if (i < S) {
+  {
     bf16* qrow = dqkv + ((size_t)b * S + i) * ld + h * DK;
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct)
@@ -352,14 +387,20 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __res
         *reinterpret_cast<bf16x4*>(qrow + ct * 32 + rq * 8 + g * 4) = o;
       }
   }
-  __syncthreads();
-  {
-    float* ddh = ddiag + (size_t)h * (2 * S - 1);
-    for (int t = tid; t < S + BR - 1; t += 256) {
-      const int idx = t - (i0 + BR - 1) + (S - 1);
-      const float v = ddg[t];
-      if (idx >= 0 && idx < 2 * S - 1 && v != 0.f) unsafeAtomicAdd(&ddh[idx], v);
-    }
+  // ---- flush the wave-private diagonal sums: u = j - i_lw + 31  ->  delta = u - 31 - i_w0
+  float* ddh = ddiag + (size_t)h * (2 * S - 1);
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  for (int u = lane; u < S + 31; u += 64) {
+    const float v = ddgw[u];
+    const int idx = u - 31 - i_w0 + (S - 1);
+    if (v != 0.f && idx >= 0 && idx < 2 * S - 1) unsafeAtomicAdd(&ddh[idx], v);
+  }
+  far_neg = wave_sum(far_neg);
+  far_pos = wave_sum(far_pos);
+  if (lane == 0) {
+    if (far_neg != 0.f) unsafeAtomicAdd(&ddh[0], far_neg);
+    if (far_pos != 0.f) unsafeAtomicAdd(&ddh[2 * S - 2], far_pos);
   }
 }
 
@@ -502,7 +543,7 @@ hipError_t fwd_launch(const void* qkv, const float* diag, void* c, float* lse, c
 
 template <int DK, bool CAUSAL>
 hipError_t bwd_launch(const void* qkv, const void* c, const void* dc, const float* diag, const float* lse,
-                      float* dvec, void* dqkv, float* ddiag, const AttnDims& a, hipStream_t st) {
+                      float* dvec, void* dqkv, float* ddiag, const AttnDims& a, int far, hipStream_t st) {
   const int64_t rows = (int64_t)a.B * a.S * a.H;
   attn_dvec_kernel<DK><<<ceil_div(rows * (DK / 8), 256), 256, 0, st>>>((const bf16*)c, (const bf16*)dc, dvec, a);
   const int64_t nd = (int64_t)a.H * (2 * a.S - 1);
@@ -512,9 +553,9 @@ hipError_t bwd_launch(const void* qkv, const void* c, const void* dc, const floa
   const dim3 grid(ceil_div(a.S, 128), a.H, a.B);
   {
     auto kern = attn_bwd_dq_mfma_kernel<DK, CAUSAL>;
-    const size_t lds = 2 * 64 * DK * 2 + 2 * sizeof(float) * (a.S + 127);
+    const size_t lds = 2 * 64 * DK * 2 + sizeof(float) * (4 * 32 * 36 + (a.S + 127) + 4 * (a.S + 31));
     if ((e = set_lds(kern, lds)) != hipSuccess) return e;
-    kern<<<grid, 256, lds, st>>>((const bf16*)qkv, (const bf16*)dc, diag, lse, dvec, (bf16*)dqkv, ddiag, a);
+    kern<<<grid, 256, lds, st>>>((const bf16*)qkv, (const bf16*)dc, diag, lse, dvec, (bf16*)dqkv, ddiag, a, far);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   {
@@ -546,11 +587,14 @@ size_t attn_bwd_mfma_scratch_bytes(const AttnDims&) { return 0; }
 
 hipError_t launch_attn_bwd_mfma(const void* qkv, const void* c, const void* dc, const float* diag,
                                 const float* lse, float* dvec, void* dqkv, float* ddiag, void*,
-                                const AttnDims& a, hipStream_t st) {
-  if (a.dk == 64) return a.causal ? bwd_launch<64, true>(qkv, c, dc, diag, lse, dvec, dqkv, ddiag, a, st)
-                                  : bwd_launch<64, false>(qkv, c, dc, diag, lse, dvec, dqkv, ddiag, a, st);
-  return a.causal ? bwd_launch<128, true>(qkv, c, dc, diag, lse, dvec, dqkv, ddiag, a, st)
-                  : bwd_launch<128, false>(qkv, c, dc, diag, lse, dvec, dqkv, ddiag, a, st);
+                                const AttnDims& a, int far, hipStream_t st) {
+  // `far`: smallest distance that falls in the last (saturated) bucket; such offsets need no
+  // per-diagonal resolution.  Never below 1, so offset 0 always takes the per-diagonal path.
+  if (far < 1) far = 1;
+  if (a.dk == 64) return a.causal ? bwd_launch<64, true>(qkv, c, dc, diag, lse, dvec, dqkv, ddiag, a, far, st)
+                                  : bwd_launch<64, false>(qkv, c, dc, diag, lse, dvec, dqkv, ddiag, a, far, st);
+  return a.causal ? bwd_launch<128, true>(qkv, c, dc, diag, lse, dvec, dqkv, ddiag, a, far, st)
+                  : bwd_launch<128, false>(qkv, c, dc, diag, lse, dvec, dqkv, ddiag, a, far, st);
 }
 
 }  // namespace t5mi

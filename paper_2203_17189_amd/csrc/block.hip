@@ -377,7 +377,7 @@ int t5_block_bwd(const t5_block_cfg* cfg, const void* dy, const void* x, const t
   }
   if (ty == IN_BF16 && attn_mfma_supported(ad))
     T5_STEP("attn_bwd", launch_attn_bwd_mfma(S.qkv, S.c, W.dc, S.diag, S.lse, W.dvec, W.dqkv, W.ddiag, W.attn_scratch, ad,
-                                st));
+                                lut.n_thr > 0 ? lut.thr[lut.n_thr - 1] : lut.max_exact, st));
   else
     T5_STEP("attn_bwd", launch_attn_bwd_simple(S.qkv, S.c, W.dc, ty, S.diag, S.lse, W.dvec, W.dqkv, W.ddiag, ad, st));
   T5_STEP("relpos_diag_bwd", launch_relpos_diag_bwd(W.ddiag, dw->rel_table, D.S, D.H, cfg->num_buckets, lut, acc, st));

@@ -58,17 +58,24 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return s;
 }
 
+// tanh through one exp2 and one reciprocal: tanh(x) = 1 - 2 / (1 + e^(2x)).  Saturates correctly at
+// +-inf; absolute error ~1e-7, which gelu() scales by z/2.
+__device__ __forceinline__ float fast_tanh(float x) {
+  const float e = __builtin_amdgcn_exp2f(x * 2.885390081777927f);  // 2 * log2(e)
+  return 1.f - 2.f * __builtin_amdgcn_rcpf(1.f + e);
+}
 // tanh-form GELU and its derivative, float32.
 __device__ __forceinline__ float gelu_tanh(float z) {
   const float kappa = 0.7978845608028654f, beta = 0.044715f;
-  float t = tanhf(kappa * (z + beta * z * z * z));
+  const float t = fast_tanh(kappa * (z + beta * z * z * z));
   return 0.5f * z * (1.f + t);
 }
 __device__ __forceinline__ void gelu_tanh_both(float z, float& g, float& dg) {
   const float kappa = 0.7978845608028654f, beta = 0.044715f;
-  float t = tanhf(kappa * (z + beta * z * z * z));
+  const float z2 = z * z;
+  const float t = fast_tanh(kappa * (z + beta * z * z2));
   g = 0.5f * z * (1.f + t);
-  dg = 0.5f * (1.f + t) + 0.5f * z * (1.f - t * t) * kappa * (1.f + 3.f * beta * z * z);
+  dg = 0.5f * (1.f + t) + 0.5f * z * (1.f - t * t) * kappa * (1.f + 3.f * beta * z2);
 }
 
 // Threshold table of the logarithmic relative-position buckets, built on the host in exact

@@ -146,13 +146,23 @@ __global__ __launch_bounds__(kNormWaves * 64) void rmsnorm_bwd_kernel(
   }
 }
 
-__global__ void rmsnorm_dg_reduce_kernel(const float* __restrict__ part, int nrows, int d,
-                                         float* __restrict__ dg, int accumulate) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= d) return;
+// 256 threads = 32 columns x 8 row slices; the slices meet in LDS in a fixed order.
+__global__ __launch_bounds__(256) void rmsnorm_dg_reduce_kernel(const float* __restrict__ part, int nrows, int d,
+                                                                float* __restrict__ dg, int accumulate) {
+  __shared__ float red[8][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const int c = blockIdx.x * 32 + tx;
   float s = 0.f;
-  for (int i = 0; i < nrows; ++i) s += part[(size_t)i * d + c];
-  dg[c] = accumulate ? dg[c] + s : s;
+  if (c < d)
+    for (int i = ty; i < nrows; i += 8) s += part[(size_t)i * d + c];
+  red[ty][tx] = s;
+  __syncthreads();
+  if (ty == 0 && c < d) {
+    float t = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) t += red[k][tx];
+    dg[c] = accumulate ? dg[c] + t : t;
+  }
 }
 
 template <typename TX, typename TO>
@@ -239,7 +249,7 @@ hipError_t launch_rmsnorm_bwd(const void* x, int x_type, const void* g, int g_ty
   else
     return hipErrorInvalidValue;
   if (e != hipSuccess) return e;
-  rmsnorm_dg_reduce_kernel<<<ceil_div(d, 256), 256, 0, st>>>(dg_partial, grid, d, dg, accumulate);
+  rmsnorm_dg_reduce_kernel<<<ceil_div(d, 32), 256, 0, st>>>(dg_partial, grid, d, dg, accumulate);
   return hipGetLastError();
 }
 
