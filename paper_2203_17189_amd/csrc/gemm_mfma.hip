@@ -2,13 +2,22 @@
 //
 //   C[m,n] = sum_s sum_k A_s(m,k) B_s(n,k)
 //
-// Tiling: workgroup tile BM x BN x 64, WM x WN wavefronts, each wave owns (BM/WM) x (BN/WN) as
-// 32x32 MFMA tiles.  Operand tiles go global -> registers -> LDS (double buffered, one barrier per
-// k-tile).  Two LDS layouts:
-//   k-contiguous operand (A[m][k]):  rows of 64 k (128 B), 16-byte chunks XOR-swizzled by row, read
-//                                    with ds_read_b128;
-//   m-contiguous operand (A[k][m]):  rows of BM m, 32-byte granules XOR-swizzled by k, read with the
-//                                    LDS transpose load ds_read_b64_tr_b16 (two per MFMA operand).
+// Tiling: workgroup tile BM x BN, k-tiles of 32, WM x WN wavefronts, each wave owns
+// (BM/WM) x (BN/WN) as 32x32 MFMA tiles.
+//
+// Data path: global -> LDS directly (global_load_lds_dwordx4: every lane fetches 16 bytes, a wave
+// fills 1 KB of contiguous LDS), NS stages deep.  Global load latency on this part is on the order
+// of a microsecond under load while one k-tile is ~0.4 us of MFMA work, so several k-tiles must be
+// in flight; keeping them in LDS instead of registers leaves the register file to the accumulators.
+// Because the DMA writes LDS linearly, the bank-conflict swizzle is applied on the global side: the
+// lane that owns LDS slot (row, physical chunk) fetches the logical chunk that belongs there.
+// Two operand layouts:
+//   k-contiguous (A[m][k]):  LDS rows of 32 k (64 B, 4 chunks), read with ds_read_b128;
+//   m-contiguous (A[k][m]):  LDS rows of BM m, 32-byte granules swizzled by k, read with the LDS
+//                            transpose load ds_read_b64_tr_b16 (two per MFMA operand).
+// The compiler does not see these DMA writes; ordering is explicit: s_waitcnt vmcnt(n) + s_barrier
+// before a stage is read, and a stage is refilled only after a barrier that every wave reaches
+// after its last read of that stage.
 // Workgroup ids are remapped so that each XCD (ids are dealt round-robin to the 8 XCDs) works on a
 // compact block of output tiles and shares operand tiles through its own L2.
 #include "kernels.h"
@@ -17,33 +26,22 @@ namespace t5mi {
 
 namespace {
 
-constexpr int BK = 64;
+constexpr int BK = 32;   // k per LDS stage
+constexpr int KQ = 64;   // every segment's K must be a multiple of this
 
 typedef __attribute__((address_space(3))) short4v lds_short4;
+typedef __attribute__((address_space(3))) char lds_char;
 
-__device__ __forceinline__ int swz_row(int row) { return (row ^ (row >> 3)) & 7; }
+// k-contiguous stage: row r (64 B) holds logical chunk c at physical chunk c ^ kc_swz(r).
+__device__ __forceinline__ int kc_swz(int row) { return ((row >> 1) & 3) ^ ((row >> 3) & 1); }
 
-template <int ROWS, bool KC>
-struct TileLds {
-  // byte offset of the 16-byte chunk `chunk` of row `row` (KC: row = m, chunk = k/8;
-  // !KC: row = k, chunk = m/8) inside one stage
-  __device__ static __forceinline__ int chunk_off(int row, int chunk) {
-    if constexpr (KC) {
-      return row * 128 + ((chunk ^ swz_row(row)) << 4);
-    } else {
-      const int g = chunk >> 1, half = chunk & 1;
-      return row * (ROWS * 2) + (((g ^ ((row & 3) << 1))) << 5) + (half << 4);
-    }
-  }
-};
-
-// One MFMA operand (8 bf16 of k for row `mrow` = base + lane%32) for k-step kk of the stage.
+// One MFMA operand (8 bf16 of k for row base + lane%32) for k-step kk (0 or 1) of a stage.
 template <int ROWS, bool KC>
 __device__ __forceinline__ bf16x8 load_frag(const char* stage, int base, int kk, int lane) {
   if constexpr (KC) {
     const int row = base + (lane & 31);
     const int chunk = kk * 2 + (lane >> 5);
-    return *reinterpret_cast<const bf16x8*>(stage + TileLds<ROWS, true>::chunk_off(row, chunk));
+    return *reinterpret_cast<const bf16x8*>(stage + row * 64 + ((chunk ^ kc_swz(row)) << 4));
   } else {
     // 16-lane groups: lanes supply the address of 4 consecutive m at row k; the transpose load hands
     // lane i the 4 k-values of m = group_base + i.
@@ -61,24 +59,29 @@ __device__ __forceinline__ bf16x8 load_frag(const char* stage, int base, int kk,
   }
 }
 
-struct KTile {
-  const bf16* a;
-  const bf16* b;
-  int lda, ldb, k0;
-};
+// 64 lanes x 16 bytes: global (sbase + voff per lane) -> LDS [lds_addr, lds_addr + 1024).
+// lds_addr and sbase are wave-uniform.
+__device__ __forceinline__ void dma_1k(uint32_t lds_addr, const void* sbase, uint32_t voff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff),
+               "s"(sbase));
+}
 
-template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int EPI>
+template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int EPI, int NS>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmDesc g, GemmEpi e, int tiles_m,
                                                                 int tiles_n, int split_k) {
-  constexpr int NT = WM * WN * 64;
+  constexpr int NW = WM * WN;
   constexpr int TMW = BM / WM, TNW = BN / WN;
   constexpr int MI = TMW / 32, NI = TNW / 32;
-  constexpr int A_CH = BM * 8 / NT, B_CH = BN * 8 / NT;  // 16-byte chunks per thread per k-tile
-  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128;
+  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
   constexpr int STAGE = A_BYTES + B_BYTES;
-  extern __shared__ __attribute__((aligned(16))) char smem[];
+  constexpr int A_DMA = A_BYTES / 1024 / NW, B_DMA = B_BYTES / 1024 / NW;  // DMA instructions per wave
+  constexpr int DMA_PER_TILE = A_DMA + B_DMA;
+  static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile vs wave count");
+  static_assert((NS - 1) * DMA_PER_TILE < 64, "vmcnt range");
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;
 
   // ---- XCD-aware tile mapping
@@ -100,80 +103,70 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmDesc g, Gem
   const int tm = first_m + in_g % gsz, tn = in_g / gsz;
   const int m0 = tm * BM, n0 = tn * BN;
 
-  // ---- k-tile range of this workgroup (flattened over segments)
+  // ---- k-tile range of this workgroup (flattened over segments; lda/ldb are equal across segments)
   int nk_total = 0;
   for (int s = 0; s < g.nseg; ++s) nk_total += g.seg[s].K / BK;
   const int per = (nk_total + split_k - 1) / split_k;
   const int kt_begin = ks * per;
   const int kt_end = (kt_begin + per) < nk_total ? (kt_begin + per) : nk_total;
+  const int nk = kt_end - kt_begin;
+  const int lda = g.seg[0].lda, ldb = g.seg[0].ldb;
 
-  auto tile_at = [&](int kt) {
-    KTile t;
-    int s = 0, base = 0;
-    while (s + 1 < g.nseg && kt >= base + g.seg[s].K / BK) { base += g.seg[s].K / BK; ++s; }
-    t.a = (const bf16*)g.seg[s].A;
-    t.b = (const bf16*)g.seg[s].B;
-    t.lda = g.seg[s].lda;
-    t.ldb = g.seg[s].ldb;
-    t.k0 = (kt - base) * BK;
-    return t;
-  };
+  // ---- per-lane byte offsets of this wave's DMA slots (loop invariant)
+  uint32_t a_off[A_DMA], b_off[B_DMA];
+#pragma unroll
+  for (int i = 0; i < A_DMA; ++i) {
+    const int q = wave + i * NW;  // 1 KB block inside the A stage
+    if constexpr (A_KC) {
+      const int row = q * 16 + (lane >> 2);
+      const int chunk = (lane & 3) ^ kc_swz(row);
+      int gr = m0 + row;
+      gr = gr < g.M ? gr : g.M - 1;
+      a_off[i] = (uint32_t)gr * (uint32_t)lda * 2u + (uint32_t)chunk * 16u;
+    } else {
+      constexpr int CPR = BM / 8;  // 16-byte chunks per k-row
+      const int slot = q * 64 + lane;
+      const int krow = slot / CPR, pch = slot % CPR;
+      const int gch = (((pch >> 1) ^ ((krow & 3) << 1)) << 1) | (pch & 1);
+      int mm = m0 + gch * 8;
+      mm = mm < g.M ? mm : g.M - 8;
+      a_off[i] = (uint32_t)krow * (uint32_t)lda * 2u + (uint32_t)mm * 2u;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < B_DMA; ++i) {
+    const int q = wave + i * NW;
+    if constexpr (B_KC) {
+      const int row = q * 16 + (lane >> 2);
+      const int chunk = (lane & 3) ^ kc_swz(row);
+      int gr = n0 + row;
+      gr = gr < g.N ? gr : g.N - 1;
+      b_off[i] = (uint32_t)gr * (uint32_t)ldb * 2u + (uint32_t)chunk * 16u;
+    } else {
+      constexpr int CPR = BN / 8;
+      const int slot = q * 64 + lane;
+      const int krow = slot / CPR, pch = slot % CPR;
+      const int gch = (((pch >> 1) ^ ((krow & 3) << 1)) << 1) | (pch & 1);
+      int nn = n0 + gch * 8;
+      nn = nn < g.N ? nn : g.N - 8;
+      b_off[i] = (uint32_t)krow * (uint32_t)ldb * 2u + (uint32_t)nn * 2u;
+    }
+  }
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)smem;
 
-  u32x4 areg[A_CH], breg[B_CH];
-  auto gload = [&](int kt) {
-    const KTile t = tile_at(kt);
+  // Issue the DMA of k-tile `t` (relative to kt_begin; clamped to the last tile) into stage `st`.
+  auto dma_tile = [&](int t, int st) {
+    int kt = kt_begin + (t < nk ? t : nk - 1);
+    int s = 0;
+    while (s + 1 < g.nseg && kt >= g.seg[s].K / BK) { kt -= g.seg[s].K / BK; ++s; }
+    const size_t k0 = (size_t)kt * BK;
+    const char* abase = (const char*)g.seg[s].A + (A_KC ? k0 * 2 : k0 * (size_t)lda * 2);
+    const char* bbase = (const char*)g.seg[s].B + (B_KC ? k0 * 2 : k0 * (size_t)ldb * 2);
+    const uint32_t sa = lds0 + st * STAGE, sb = sa + A_BYTES;
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i) {
-      const int q = tid + i * NT;
-      const bf16* p;
-      if constexpr (A_KC) {
-        int row = m0 + (q >> 3);
-        row = row < g.M ? row : g.M - 1;
-        p = t.a + (size_t)row * t.lda + t.k0 + ((q & 7) << 3);
-      } else {
-        const int krow = q / (BM / 8), cm = q % (BM / 8);
-        int mm = m0 + cm * 8;
-        mm = mm < g.M ? mm : g.M - 8;
-        p = t.a + (size_t)(t.k0 + krow) * t.lda + mm;
-      }
-      areg[i] = *reinterpret_cast<const u32x4*>(p);
-    }
+    for (int i = 0; i < A_DMA; ++i) dma_1k(sa + (wave + i * NW) * 1024, abase, a_off[i]);
 #pragma unroll
-    for (int i = 0; i < B_CH; ++i) {
-      const int q = tid + i * NT;
-      const bf16* p;
-      if constexpr (B_KC) {
-        int row = n0 + (q >> 3);
-        row = row < g.N ? row : g.N - 1;
-        p = t.b + (size_t)row * t.ldb + t.k0 + ((q & 7) << 3);
-      } else {
-        const int krow = q / (BN / 8), cn = q % (BN / 8);
-        int nn = n0 + cn * 8;
-        nn = nn < g.N ? nn : g.N - 8;
-        p = t.b + (size_t)(t.k0 + krow) * t.ldb + nn;
-      }
-      breg[i] = *reinterpret_cast<const u32x4*>(p);
-    }
-  };
-  auto lstore = [&](int buf) {
-    char* sa = smem + buf * STAGE;
-    char* sb = sa + A_BYTES;
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) {
-      const int q = tid + i * NT;
-      int off;
-      if constexpr (A_KC) off = TileLds<BM, true>::chunk_off(q >> 3, q & 7);
-      else off = TileLds<BM, false>::chunk_off(q / (BM / 8), q % (BM / 8));
-      *reinterpret_cast<u32x4*>(sa + off) = areg[i];
-    }
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) {
-      const int q = tid + i * NT;
-      int off;
-      if constexpr (B_KC) off = TileLds<BN, true>::chunk_off(q >> 3, q & 7);
-      else off = TileLds<BN, false>::chunk_off(q / (BN / 8), q % (BN / 8));
-      *reinterpret_cast<u32x4*>(sb + off) = breg[i];
-    }
+    for (int i = 0; i < B_DMA; ++i) dma_1k(sb + (wave + i * NW) * 1024, bbase, b_off[i]);
   };
 
   f32x16 acc[MI][NI];
@@ -184,35 +177,198 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmDesc g, Gem
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  if (kt_begin < kt_end) {
-    gload(kt_begin);
-    lstore(0);
-    __syncthreads();
-    for (int kt = kt_begin; kt < kt_end; ++kt) {
-      const int buf = (kt - kt_begin) & 1;
-      const bool more = kt + 1 < kt_end;
-      if (more) gload(kt + 1);
-      const char* sa = smem + buf * STAGE;
-      const char* sb = sa + A_BYTES;
+  bf16x8 fa[2][MI], fb[2][NI];
+  auto load_frags = [&](int st, int kk, int slot) {
+    const char* sa = smem + st * STAGE;
+    const char* sb = sa + A_BYTES;
 #pragma unroll
-      for (int kk = 0; kk < BK / 16; ++kk) {
-        bf16x8 af[MI], bfr[NI];
+    for (int i = 0; i < MI; ++i) fa[slot][i] = load_frag<BM, A_KC>(sa, wm * TMW + i * 32, kk, lane);
 #pragma unroll
-        for (int i = 0; i < MI; ++i) af[i] = load_frag<BM, A_KC>(sa, wm * TMW + i * 32, kk, lane);
+    for (int j = 0; j < NI; ++j) fb[slot][j] = load_frag<BN, B_KC>(sb, wn * TNW + j * 32, kk, lane);
+  };
+  auto mfma_all = [&](int slot) {
 #pragma unroll
-        for (int j = 0; j < NI; ++j) bfr[j] = load_frag<BN, B_KC>(sb, wn * TNW + j * 32, kk, lane);
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
+      for (int j = 0; j < NI; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
+  };
+  constexpr int DS_PER_FRAGSET = (A_KC ? MI : 2 * MI) + (B_KC ? NI : 2 * NI);
+  auto interleave = [&]() {  // spread one fragment set's LDS reads between the 16 MFMAs of a k-step
 #pragma unroll
-          for (int j = 0; j < NI; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-      }
-      if (more) lstore(buf ^ 1);
-      __syncthreads();
+    for (int q = 0; q < MI + NI; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x008, (MI * NI) / (MI + NI) > 0 ? (MI * NI) / (MI + NI) : 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, DS_PER_FRAGSET / (MI + NI), 0);
     }
+  };
+
+  if (nk > 0) {
+    // Prologue: fill every stage, wait for tile 0.
+#pragma unroll
+    for (int s = 0; s < NS; ++s) dma_tile(s, s);
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((NS - 1) * DMA_PER_TILE) : "memory");
+    load_frags(0, 0, 0);
+    for (int base = 0; base < nk; base += NS) {
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        const int t = base + s;
+        if (t < nk) {
+          // operands of k-step 1 of tile t, under the MFMAs of k-step 0
+          load_frags(s, 1, 1);
+          mfma_all(0);
+          interleave();
+          // tile t+1 has landed (this wave's part), all of this wave's reads of stage s are done;
+          // after the barrier that holds for every wave, so stage s can be refilled.
+          asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((NS - 2) * DMA_PER_TILE) : "memory");
+          dma_tile(t + NS, s);
+          load_frags((s + 1) % NS, 0, 0);
+          mfma_all(1);
+          interleave();
+        }
+      }
+    }
+    // drain DMA that was issued past the end before LDS is released
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   }
 
   // ---- epilogue.  acc[i][j][r]: row = (r/4)*8 + (lane/32)*4 + r%4, col = lane%32 of the 32x32 tile.
+  // Interior wave tiles (the common case) are transposed through LDS, 64 rows at a time, so that
+  // each lane ends up with 4 consecutive columns of one row: auxiliary loads and the stores are
+  // then 8- or 16-byte vector accesses covering whole rows of the wave tile.  Edge tiles take the
+  // predicated per-element path further down.
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");  // every wave is done with the k-loop stages
+  {
+    constexpr int EP_LD = TNW + 8;  // floats per staged row
+    const int mw = m0 + wm * TMW, nw = n0 + wn * TNW;
+    bool interior = (mw + TMW <= g.M) && (nw + TNW <= g.N) && (e.ld0 % 8 == 0);
+    if constexpr (EPI == EPI_SPLIT_F32)
+      interior = interior && (nw / e.split_n == (nw + TNW - 1) / e.split_n) && (e.split_n % 4 == 0);
+    if constexpr (EPI == EPI_SPLIT_F32) {
+      // split-k partial sums go out as float atomics straight from the accumulator registers
+      // (32 consecutive floats per half-wave and row)
+      if (interior && split_k > 1) {
+        const int cl = lane & 31, rl = (lane >> 5) << 2;
+        const int which = nw / e.split_n;
+        float* dst0 = (float*)(which == 0 ? e.out0 : which == 1 ? e.out1 : e.out2) + (nw - which * e.split_n) + cl;
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            float* rowp = dst0 + (size_t)(mw + i * 32 + ((r >> 2) << 3) + rl + (r & 3)) * e.ld0;
+#pragma unroll
+            for (int j = 0; j < NI; ++j) unsafeAtomicAdd(rowp + j * 32, acc[i][j][r]);
+          }
+        return;
+      }
+    }
+    if (interior) {
+      float* stg = reinterpret_cast<float*>(smem) + wave * (64 * EP_LD);
+      const int cl = lane & 31, rl = (lane >> 5) << 2;
+#pragma unroll
+      for (int half = 0; half < MI / 2; ++half) {
+#pragma unroll
+        for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+          for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              stg[(ii * 32 + ((r >> 2) << 3) + rl + (r & 3)) * EP_LD + j * 32 + cl] = acc[half * 2 + ii][j][r];
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_wave_barrier();
+        const int mh = mw + half * 64;
+        if constexpr (EPI == EPI_GEGLU_FWD) {
+          // staged columns: [u 32 | w 32] pairs; lane takes 4 consecutive f of one row
+          constexpr int LPR = TNW / 8;  // lanes per row
+          const int fl = (lane % LPR) * 4;
+          const int pc = (fl >> 5) * 64 + (fl & 31);  // staged column of u; w is 32 further
+          const int f = (nw >> 1) + fl;
+#pragma unroll
+          for (int it = 0; it < 64 / (64 / LPR); ++it) {
+            const int rloc = it * (64 / LPR) + lane / LPR;
+            const f32x4 uu = *reinterpret_cast<const f32x4*>(stg + rloc * EP_LD + pc);
+            const f32x4 ww = *reinterpret_cast<const f32x4*>(stg + rloc * EP_LD + pc + 32);
+            bf16x4 ub, wb, ab;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              ub[q] = (bf16)uu[q];
+              wb[q] = (bf16)ww[q];
+              ab[q] = (bf16)(gelu_tanh((float)ub[q]) * (float)wb[q]);
+            }
+            const size_t o = (size_t)(mh + rloc) * e.ld0 + f;
+            *reinterpret_cast<bf16x4*>((bf16*)e.out0 + o) = ub;
+            *reinterpret_cast<bf16x4*>((bf16*)e.out1 + o) = wb;
+            *reinterpret_cast<bf16x4*>((bf16*)e.out2 + o) = ab;
+          }
+        } else {
+          constexpr int LPR = TNW / 4;     // lanes per row
+          constexpr int RPI = 64 / LPR;    // rows per wave instruction
+          const int c4 = (lane % LPR) * 4;
+          float* split_dst = nullptr;
+          if constexpr (EPI == EPI_SPLIT_F32) {
+            const int which = nw / e.split_n;
+            split_dst = (float*)(which == 0 ? e.out0 : which == 1 ? e.out1 : e.out2) + (nw - which * e.split_n) + c4;
+          }
+#pragma unroll
+          for (int it = 0; it < 64 / RPI; ++it) {
+            const int rloc = it * RPI + lane / LPR;
+            f32x4 v = *reinterpret_cast<const f32x4*>(stg + rloc * EP_LD + c4);
+            const size_t o = (size_t)(mh + rloc) * e.ld0 + nw + c4;
+            if constexpr (EPI == EPI_SPLIT_F32) {
+              float* d = split_dst + (size_t)(mh + rloc) * e.ld0;
+              if (split_k > 1) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) unsafeAtomicAdd(d + q, v[q]);
+              } else {
+                if (e.accumulate) {
+                  const f32x4 old = *reinterpret_cast<const f32x4*>(d);
+#pragma unroll
+                  for (int q = 0; q < 4; ++q) v[q] += old[q];
+                }
+                *reinterpret_cast<f32x4*>(d) = v;
+              }
+            } else if constexpr (EPI == EPI_GEGLU_BWD) {
+              const bf16x4 ub = *reinterpret_cast<const bf16x4*>((const bf16*)e.aux0 + o);
+              const bf16x4 wb = *reinterpret_cast<const bf16x4*>((const bf16*)e.aux1 + o);
+              bf16x4 du, dw;
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                float gl, dgl;
+                gelu_tanh_both((float)ub[q], gl, dgl);
+                du[q] = (bf16)(v[q] * (float)wb[q] * dgl);
+                dw[q] = (bf16)(v[q] * gl);
+              }
+              *reinterpret_cast<bf16x4*>((bf16*)e.out0 + o) = du;
+              *reinterpret_cast<bf16x4*>((bf16*)e.out1 + o) = dw;
+            } else {  // EPI_STORE, EPI_RESID
+              if constexpr (EPI == EPI_RESID) {
+                if (e.aux_type == IN_BF16) {
+                  const bf16x4 x = *reinterpret_cast<const bf16x4*>((const bf16*)e.aux0 + o);
+#pragma unroll
+                  for (int q = 0; q < 4; ++q) v[q] += (float)x[q];
+                } else {
+                  const f32x4 x = *reinterpret_cast<const f32x4*>((const float*)e.aux0 + o);
+#pragma unroll
+                  for (int q = 0; q < 4; ++q) v[q] += x[q];
+                }
+              }
+              if (e.out_type == IN_BF16) {
+                bf16x4 ob;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) ob[q] = (bf16)v[q];
+                *reinterpret_cast<bf16x4*>((bf16*)e.out0 + o) = ob;
+              } else {
+                *reinterpret_cast<f32x4*>((float*)e.out0 + o) = v;
+              }
+            }
+          }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_wave_barrier();
+      }
+      return;
+    }
+  }
+  // ---- edge tiles: per-element bounds checks
   const int col_l = lane & 31, row_l = (lane >> 5) << 2;
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
@@ -274,8 +430,11 @@ __global__ void zero_split_kernel(GemmEpi e, int M, int N) {
 
 template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int EPI>
 hipError_t launch_cfg(const GemmDesc& g, const GemmEpi& e, int split_k, hipStream_t st) {
-  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, A_KC, B_KC, EPI>;
-  constexpr int lds = 2 * (BM + BN) * 128;
+  constexpr int NS = 4;
+  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, A_KC, B_KC, EPI, NS>;
+  constexpr int lds_loop = NS * (BM + BN) * BK * 2;
+  constexpr int lds_epi = WM * WN * 64 * (BN / WN + 8) * 4;
+  constexpr int lds = lds_loop > lds_epi ? lds_loop : lds_epi;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -290,7 +449,7 @@ hipError_t launch_cfg(const GemmDesc& g, const GemmEpi& e, int split_k, hipStrea
 template <bool A_KC, bool B_KC, int EPI>
 hipError_t launch_layout(const GemmDesc& g, const GemmEpi& e, hipStream_t st) {
   int nk = 0;
-  for (int s = 0; s < g.nseg; ++s) nk += g.seg[s].K / BK;
+  for (int s = 0; s < g.nseg; ++s) nk += g.seg[s].K / KQ;
   const int64_t big_tiles = (int64_t)ceil_div(g.M, 256) * ceil_div(g.N, 256);
   const bool big = big_tiles >= 192 || EPI == EPI_SPLIT_F32;
   int split_k = 1;
@@ -316,10 +475,14 @@ bool gemm_mfma_supported(const GemmDesc& g, const GemmEpi& e) {
   if (g.a_kc != g.b_kc) return false;  // implemented: both k-contiguous, or both m/n-contiguous
   for (int s = 0; s < g.nseg; ++s) {
     const GemmSeg& sg = g.seg[s];
-    if (sg.K < BK || sg.K % BK != 0 || sg.lda % 8 != 0 || sg.ldb % 8 != 0) return false;
+    if (sg.K < KQ || sg.K % KQ != 0 || sg.lda % 8 != 0 || sg.ldb % 8 != 0) return false;
+    if (sg.lda != g.seg[0].lda || sg.ldb != g.seg[0].ldb) return false;
     if (((uintptr_t)sg.A | (uintptr_t)sg.B) & 15) return false;
   }
   if (g.M < 8 || g.N < 8) return false;
+  // per-lane byte offsets are 32-bit
+  if ((uint64_t)(g.a_kc ? g.M : KQ) * g.seg[0].lda * 2 >= (1ull << 32)) return false;
+  if ((uint64_t)(g.b_kc ? g.N : KQ) * g.seg[0].ldb * 2 >= (1ull << 32)) return false;
   if (!g.a_kc && (g.M % 8 != 0 || g.N % 8 != 0)) return false;
   switch (e.kind) {
     case EPI_STORE: case EPI_RESID: case EPI_GEGLU_BWD:
