@@ -52,6 +52,33 @@ __device__ __forceinline__ void load_tile(char* dst, const bf16* __restrict__ sr
   }
 }
 
+// DMA descriptor of one [ROWS][DK] bf16 tile for a 4-wave workgroup: the tile is ROWS*DK*2/1024
+// blocks of 1 KB, wave w copies blocks w, w+4, ...  The swizzle of tile_off() is applied on the
+// global side: the lane that owns LDS slot (row, physical chunk) fetches the logical chunk.
+template <int DK, int ROWS>
+struct TileDma {
+  static constexpr int PER_WAVE = ROWS * DK * 2 / 1024 / 4;
+  uint32_t voff[PER_WAVE];
+  __device__ __forceinline__ void init(int wave, int lane, size_t ld_elems) {
+    constexpr int CPR = DK / 8;
+#pragma unroll
+    for (int i = 0; i < PER_WAVE; ++i) {
+      const int slot = (wave + i * 4) * 64 + lane;
+      const int row = slot / CPR, pch = slot % CPR;
+      voff[i] = (uint32_t)(row * ld_elems * 2) + (uint32_t)((pch ^ row_swz<DK>(row)) << 4);
+    }
+  }
+  __device__ __forceinline__ void issue(uint32_t lds_addr, const void* sbase, int wave) const {
+#pragma unroll
+    for (int i = 0; i < PER_WAVE; ++i) dma_1k(lds_addr + (wave + i * 4) * 1024, sbase, voff[i]);
+  }
+};
+
+// All DMA issued so far has landed, this wave's LDS traffic is complete, and every wave is here.
+__device__ __forceinline__ void dma_wait_barrier() {
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // Operand with 8 consecutive channels of row (base + lane%32): k-step kk covers channels kk*16..+15.
 template <int DK>
 __device__ __forceinline__ bf16x8 frag_rows(const char* tile, int base, int kk, int lane) {
@@ -93,12 +120,12 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restri
                                                             bf16* __restrict__ c, float* __restrict__ lse,
                                                             AttnDims a) {
   constexpr int BR = 128, BC = 64, KS = DK / 16, CT = DK / 32;
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  char* Kt = smem;
-  char* Vt = smem + BC * DK * 2;
-  float* dg = reinterpret_cast<float*>(smem + 2 * BC * DK * 2);  // [S + BR - 1], log2 units
+  constexpr int TILE = BC * DK * 2, STG = 2 * TILE;  // a stage holds a K tile then a V tile
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  float* dg = reinterpret_cast<float*>(smem + 2 * STG);  // [S + BR - 1], log2 units
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int S = a.S, I = a.H * DK;
   const size_t ld = (size_t)3 * I;
   const int qt = CAUSAL ? (gridDim.x - 1 - blockIdx.x) : blockIdx.x;  // heavy causal tiles first
@@ -138,12 +165,22 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restri
     const int last = (i0 + BR < S ? i0 + BR : S);
     n_kv = (last + BC - 1) / BC;
   }
+  // K/V tiles are double buffered: tile jt+1 is in flight (DMA) while tile jt is used.
+  TileDma<DK, BC> td;
+  td.init(wave, lane, ld);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)smem;
+  td.issue(lds0, base + I, wave);
+  td.issue(lds0 + TILE, base + 2 * I, wave);
   for (int jt = 0; jt < n_kv; ++jt) {
     const int j0 = jt * BC;
-    __syncthreads();
-    load_tile<DK, 256>(Kt, base + (size_t)j0 * ld + I, ld, BC, BC, tid);
-    load_tile<DK, 256>(Vt, base + (size_t)j0 * ld + 2 * I, ld, BC, BC, tid);
-    __syncthreads();
+    dma_wait_barrier();  // tile jt landed; every wave is done with the other stage
+    if (jt + 1 < n_kv) {
+      const uint32_t nxt = lds0 + ((jt + 1) & 1) * STG;
+      td.issue(nxt, base + (size_t)(j0 + BC) * ld + I, wave);
+      td.issue(nxt + TILE, base + (size_t)(j0 + BC) * ld + 2 * I, wave);
+    }
+    const char* Kt = smem + (jt & 1) * STG;
+    const char* Vt = Kt + TILE;
 
     f32x16 sT[BC / 32];
 #pragma unroll
@@ -259,14 +296,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __res
                                                                bf16* __restrict__ dqkv, float* __restrict__ ddiag,
                                                                AttnDims a, int far) {
   constexpr int BR = 128, BC = 64, KS = DK / 16, CT = DK / 32, DSP = 36;
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  char* Kt = smem;
-  char* Vt = smem + BC * DK * 2;
-  float* dst_all = reinterpret_cast<float*>(smem + 2 * BC * DK * 2);  // [4 waves][32][DSP] ds staging
-  float* dg = dst_all + 4 * 32 * DSP;                                // [S + BR - 1] bias, log2 units
-  float* ddg_all = dg + (a.S + BR - 1);                              // [4 waves][S + 31]
+  constexpr int TILE = BC * DK * 2, STG = 2 * TILE;  // a stage holds a K tile then a V tile
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  float* dst_all = reinterpret_cast<float*>(smem + 2 * STG);  // [4 waves][32][DSP] ds staging
+  float* dg = dst_all + 4 * 32 * DSP;                        // [S + BR - 1] bias, log2 units
+  float* ddg_all = dg + (a.S + BR - 1);                      // [4 waves][S + 31]
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int S = a.S, I = a.H * DK;
   const size_t ld = (size_t)3 * I;
   const int qt = CAUSAL ? (gridDim.x - 1 - blockIdx.x) : blockIdx.x;
@@ -309,12 +346,21 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __res
     for (int r = 0; r < 16; ++r) dqT[ct][r] = 0.f;
 
   const int n_kv = CAUSAL ? (i0 + BR) / BC : S / BC;
+  TileDma<DK, BC> td;
+  td.init(wave, lane, ld);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)smem;
+  td.issue(lds0, base + I, wave);
+  td.issue(lds0 + TILE, base + 2 * I, wave);
   for (int jt = 0; jt < n_kv; ++jt) {
     const int j0 = jt * BC;
-    __syncthreads();
-    load_tile<DK, 256>(Kt, base + (size_t)j0 * ld + I, ld, BC, BC, tid);
-    load_tile<DK, 256>(Vt, base + (size_t)j0 * ld + 2 * I, ld, BC, BC, tid);
-    __syncthreads();
+    dma_wait_barrier();  // tile jt landed; every wave is done with the other stage
+    if (jt + 1 < n_kv) {
+      const uint32_t nxt = lds0 + ((jt + 1) & 1) * STG;
+      td.issue(nxt, base + (size_t)(j0 + BC) * ld + I, wave);
+      td.issue(nxt + TILE, base + (size_t)(j0 + BC) * ld + 2 * I, wave);
+    }
+    const char* Kt = smem + (jt & 1) * STG;
+    const char* Vt = Kt + TILE;
 #pragma unroll
     for (int kt = 0; kt < BC / 32; ++kt) {
       const int j0s = j0 + kt * 32;
@@ -415,14 +461,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
                                                                 const float* __restrict__ dvec,
                                                                 bf16* __restrict__ dqkv, AttnDims a) {
   constexpr int BCK = 128, BQ = 64, KS = DK / 16, CT = DK / 32;
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  char* Qt = smem;
-  char* Dt = smem + BQ * DK * 2;
-  float* lse_s = reinterpret_cast<float*>(smem + 2 * BQ * DK * 2);  // [BQ] log2 units
-  float* dv_s = lse_s + BQ;                                         // [BQ]
-  float* dg = dv_s + BQ;                                            // [S + BCK - 1] log2 units
+  constexpr int TILE = BQ * DK * 2, STG = 2 * TILE;  // a stage holds a Q tile then a dO tile
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  float* lse_all = reinterpret_cast<float*>(smem + 2 * STG);  // [2 stages][BQ] log2 units
+  float* dv_all = lse_all + 2 * BQ;                           // [2 stages][BQ]
+  float* dg = dv_all + 2 * BQ;                                // [S + BCK - 1] log2 units
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int S = a.S, I = a.H * DK;
   const size_t ld = (size_t)3 * I;
   const int h = blockIdx.y, b = blockIdx.z;
@@ -461,16 +507,37 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
 
   const int it_begin = CAUSAL ? (j0 / BQ) : 0;
   const size_t srow = ((size_t)b * a.H + h) * S;
-  for (int it = it_begin; it < S / BQ; ++it) {
+  // Q/dO tiles (DMA) and the matching lse / dvec slices are double buffered.
+  TileDma<DK, BQ> tq, tdo;
+  tq.init(wave, lane, ld);
+  tdo.init(wave, lane, (size_t)I);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)smem;
+  const int n_it = S / BQ;
+  tq.issue(lds0, base + (size_t)it_begin * BQ * ld, wave);
+  tdo.issue(lds0 + TILE, dobase + (size_t)it_begin * BQ * I, wave);
+  if (tid < BQ) {
+    lse_all[tid] = lse[srow + it_begin * BQ + tid] * kLog2e;
+    dv_all[tid] = dvec[srow + it_begin * BQ + tid];
+  }
+  for (int it = it_begin; it < n_it; ++it) {
     const int q0 = it * BQ;
-    __syncthreads();
-    load_tile<DK, 256>(Qt, base + (size_t)q0 * ld, ld, BQ, BQ, tid);
-    load_tile<DK, 256>(Dt, dobase + (size_t)q0 * I, (size_t)I, BQ, BQ, tid);
-    if (tid < BQ) {
-      lse_s[tid] = lse[srow + q0 + tid] * kLog2e;
-      dv_s[tid] = dvec[srow + q0 + tid];
+    const int st = (it - it_begin) & 1;
+    dma_wait_barrier();  // tile `it` landed, its lse/dvec slice is written; other stage is free
+    float nl = 0.f, nd = 0.f;
+    const bool more = it + 1 < n_it;
+    if (more) {
+      const uint32_t nxt = lds0 + (st ^ 1) * STG;
+      tq.issue(nxt, base + (size_t)(q0 + BQ) * ld, wave);
+      tdo.issue(nxt + TILE, dobase + (size_t)(q0 + BQ) * I, wave);
+      if (tid < BQ) {
+        nl = lse[srow + q0 + BQ + tid] * kLog2e;
+        nd = dvec[srow + q0 + BQ + tid];
+      }
     }
-    __syncthreads();
+    const char* Qt = smem + st * STG;
+    const char* Dt = Qt + TILE;
+    const float* lse_s = lse_all + st * BQ;
+    const float* dv_s = dv_all + st * BQ;
 #pragma unroll
     for (int qb = 0; qb < BQ / 32; ++qb) {
       f32x16 s, dp;
@@ -501,6 +568,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
               frag_cols_tr<DK>(Qt, qb * 32 + mm * 16, ct * 32, lane), dsf, dkT[ct], 0, 0, 0);
         }
       }
+    }
+    if (more && tid < BQ) {
+      lse_all[(st ^ 1) * BQ + tid] = nl;
+      dv_all[(st ^ 1) * BQ + tid] = nd;
     }
   }
   if (j < S) {
@@ -534,7 +605,7 @@ hipError_t set_lds(K kern, size_t bytes) {
 template <int DK, bool CAUSAL>
 hipError_t fwd_launch(const void* qkv, const float* diag, void* c, float* lse, const AttnDims& a, hipStream_t st) {
   auto kern = attn_fwd_mfma_kernel<DK, CAUSAL>;
-  const size_t lds = 2 * 64 * DK * 2 + sizeof(float) * (a.S + 127);
+  const size_t lds = 4 * 64 * DK * 2 + sizeof(float) * (a.S + 127);
   hipError_t e = set_lds(kern, lds);
   if (e != hipSuccess) return e;
   kern<<<dim3(ceil_div(a.S, 128), a.H, a.B), 256, lds, st>>>((const bf16*)qkv, diag, (bf16*)c, lse, a);
@@ -553,14 +624,14 @@ hipError_t bwd_launch(const void* qkv, const void* c, const void* dc, const floa
   const dim3 grid(ceil_div(a.S, 128), a.H, a.B);
   {
     auto kern = attn_bwd_dq_mfma_kernel<DK, CAUSAL>;
-    const size_t lds = 2 * 64 * DK * 2 + sizeof(float) * (4 * 32 * 36 + (a.S + 127) + 4 * (a.S + 31));
+    const size_t lds = 4 * 64 * DK * 2 + sizeof(float) * (4 * 32 * 36 + (a.S + 127) + 4 * (a.S + 31));
     if ((e = set_lds(kern, lds)) != hipSuccess) return e;
     kern<<<grid, 256, lds, st>>>((const bf16*)qkv, (const bf16*)dc, diag, lse, dvec, (bf16*)dqkv, ddiag, a, far);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   {
     auto kern = attn_bwd_dkv_mfma_kernel<DK, CAUSAL>;
-    const size_t lds = 2 * 64 * DK * 2 + sizeof(float) * (128 + a.S + 127);
+    const size_t lds = 4 * 64 * DK * 2 + sizeof(float) * (256 + a.S + 127);
     if ((e = set_lds(kern, lds)) != hipSuccess) return e;
     kern<<<grid, 256, lds, st>>>((const bf16*)qkv, (const bf16*)dc, diag, lse, dvec, (bf16*)dqkv, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;

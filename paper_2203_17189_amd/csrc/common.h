@@ -104,6 +104,17 @@ __device__ __forceinline__ int relpos_bucket_dev(int rp, const RelposLut& lut) {
   return base + b;
 }
 
+typedef __attribute__((address_space(3))) char lds_char;
+
+// Direct global -> LDS copy (global_load_lds_dwordx4).  64 lanes x 16 bytes: lane L fetches 16 bytes at
+// sbase + voff and they land at LDS address lds_addr + 16*L, so a wave fills 1 KB of contiguous LDS.
+// lds_addr and sbase are wave-uniform.  The compiler does not know that this writes LDS: callers
+// order it explicitly with s_waitcnt vmcnt(n) and a barrier before the data is read.
+__device__ __forceinline__ void dma_1k(uint32_t lds_addr, const void* sbase, uint32_t voff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff),
+               "s"(sbase));
+}
+
 inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 

@@ -30,7 +30,6 @@ constexpr int BK = 32;   // k per LDS stage
 constexpr int KQ = 64;   // every segment's K must be a multiple of this
 
 typedef __attribute__((address_space(3))) short4v lds_short4;
-typedef __attribute__((address_space(3))) char lds_char;
 
 // k-contiguous stage: row r (64 B) holds logical chunk c at physical chunk c ^ kc_swz(r).
 __device__ __forceinline__ int kc_swz(int row) { return ((row >> 1) & 3) ^ ((row >> 3) & 1); }
@@ -57,13 +56,6 @@ __device__ __forceinline__ bf16x8 load_frag(const char* stage, int base, int kk,
     short8v r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
     return __builtin_bit_cast(bf16x8, r);
   }
-}
-
-// 64 lanes x 16 bytes: global (sbase + voff per lane) -> LDS [lds_addr, lds_addr + 1024).
-// lds_addr and sbase are wave-uniform.
-__device__ __forceinline__ void dma_1k(uint32_t lds_addr, const void* sbase, uint32_t voff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff),
-               "s"(sbase));
 }
 
 template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int EPI, int NS>
@@ -450,13 +442,25 @@ template <bool A_KC, bool B_KC, int EPI>
 hipError_t launch_layout(const GemmDesc& g, const GemmEpi& e, hipStream_t st) {
   int nk = 0;
   for (int s = 0; s < g.nseg; ++s) nk += g.seg[s].K / KQ;
-  const int64_t big_tiles = (int64_t)ceil_div(g.M, 256) * ceil_div(g.N, 256);
-  const bool big = big_tiles >= 192 || EPI == EPI_SPLIT_F32;
+  const int64_t t256 = (int64_t)ceil_div(g.M, 256) * ceil_div(g.N, 256);
+  const int64_t t128 = (int64_t)ceil_div(g.M, 128) * ceil_div(g.N, 128);
+  bool big = t256 >= 192;
   int split_k = 1;
   if constexpr (EPI == EPI_SPLIT_F32) {
-    // weight-gradient GEMMs: few output tiles, very long k.  Split k so about two workgroups per
-    // compute unit exist; partial sums meet in float32 atomics on a zeroed output.
-    while (big_tiles * split_k < 384 && nk / (split_k * 2) >= 8) split_k *= 2;
+    // Weight-gradient GEMMs: few output tiles, very long k.  Small outputs take 128x128 tiles (fewer
+    // k-slices, hence fewer float atomics per output element); k is split so that the workgroups
+    // fill whole rounds of the 256 compute units.  Partial sums meet in float32 atomics on a zeroed
+    // output.
+    big = t256 >= 64;
+    const int64_t tiles = big ? t256 : t128;
+    const int per_cu = big ? 1 : 2;  // concurrent workgroups per compute unit (LDS-limited)
+    double best = -1.0;
+    for (int sp = 1; sp <= 32; ++sp) {
+      if (sp > 1 && nk / sp < 8) break;
+      const int64_t wgs = tiles * sp, slots = 256 * per_cu;
+      const double eff = (double)wgs / (double)(((wgs + slots - 1) / slots) * slots) - 0.012 * sp;
+      if (eff > best) { best = eff; split_k = sp; }
+    }
     if (split_k > 1 && !e.accumulate) {
       zero_split_kernel<<<ceil_div((int64_t)g.M * g.N, 256), 256, 0, st>>>(e, g.M, g.N);
       hipError_t err = hipGetLastError();

@@ -146,21 +146,29 @@ __global__ __launch_bounds__(kNormWaves * 64) void rmsnorm_bwd_kernel(
   }
 }
 
-// 256 threads = 32 columns x 8 row slices; the slices meet in LDS in a fixed order.
-__global__ __launch_bounds__(256) void rmsnorm_dg_reduce_kernel(const float* __restrict__ part, int nrows, int d,
-                                                                float* __restrict__ dg, int accumulate) {
-  __shared__ float red[8][33];
+// 1024 threads = 32 columns x 32 row slices; the slices meet in LDS in a fixed order.
+__global__ __launch_bounds__(1024) void rmsnorm_dg_reduce_kernel(const float* __restrict__ part, int nrows, int d,
+                                                                 float* __restrict__ dg, int accumulate) {
+  __shared__ float red[32][33];
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
   const int c = blockIdx.x * 32 + tx;
-  float s = 0.f;
-  if (c < d)
-    for (int i = ty; i < nrows; i += 8) s += part[(size_t)i * d + c];
-  red[ty][tx] = s;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  if (c < d) {
+    int i = ty;
+    for (; i + 96 < nrows; i += 128) {
+      s0 += part[(size_t)i * d + c];
+      s1 += part[(size_t)(i + 32) * d + c];
+      s2 += part[(size_t)(i + 64) * d + c];
+      s3 += part[(size_t)(i + 96) * d + c];
+    }
+    for (; i < nrows; i += 32) s0 += part[(size_t)i * d + c];
+  }
+  red[ty][tx] = (s0 + s1) + (s2 + s3);
   __syncthreads();
   if (ty == 0 && c < d) {
     float t = 0.f;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) t += red[k][tx];
+    for (int k = 0; k < 32; ++k) t += red[k][tx];
     dg[c] = accumulate ? dg[c] + t : t;
   }
 }
@@ -249,7 +257,7 @@ hipError_t launch_rmsnorm_bwd(const void* x, int x_type, const void* g, int g_ty
   else
     return hipErrorInvalidValue;
   if (e != hipSuccess) return e;
-  rmsnorm_dg_reduce_kernel<<<ceil_div(d, 32), 256, 0, st>>>(dg_partial, grid, d, dg, accumulate);
+  rmsnorm_dg_reduce_kernel<<<ceil_div(d, 32), 1024, 0, st>>>(dg_partial, grid, d, dg, accumulate);
   return hipGetLastError();
 }
 
