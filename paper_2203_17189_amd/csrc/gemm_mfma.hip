@@ -58,8 +58,8 @@ __device__ __forceinline__ bf16x8 load_frag(const char* stage, int base, int kk,
   }
 }
 
-template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int EPI, int NS>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmDesc g, GemmEpi e, int tiles_m,
+template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int EPI, int NS, int MINW>
+__global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc g, GemmEpi e, int tiles_m,
                                                                 int tiles_n, int split_k) {
   constexpr int NW = WM * WN;
   constexpr int TMW = BM / WM, TNW = BN / WN;
@@ -103,6 +103,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmDesc g, Gem
   const int kt_end = (kt_begin + per) < nk_total ? (kt_begin + per) : nk_total;
   const int nk = kt_end - kt_begin;
   const int lda = g.seg[0].lda, ldb = g.seg[0].ldb;
+  const int k_skew = nk > 0 ? (tm * 4 + tn) % nk : 0;
 
   // ---- per-lane byte offsets of this wave's DMA slots (loop invariant)
   uint32_t a_off[A_DMA], b_off[B_DMA];
@@ -148,7 +149,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmDesc g, Gem
 
   // Issue the DMA of k-tile `t` (relative to kt_begin; clamped to the last tile) into stage `st`.
   auto dma_tile = [&](int t, int st) {
-    int kt = kt_begin + (t < nk ? t : nk - 1);
+    // Workgroups start their k loop at different phases (rotated by a multiple of the tile
+    // coordinates) so that concurrently running tiles do not all stream the same 256-byte-interleaved
+    // L2 channel; tiles past the end wrap around and refetch valid data that is never used.
+    int kt = kt_begin + (t % nk + k_skew) % nk;
     int s = 0;
     while (s + 1 < g.nseg && kt >= g.seg[s].K / BK) { kt -= g.seg[s].K / BK; ++s; }
     const size_t k0 = (size_t)kt * BK;
@@ -420,10 +424,9 @@ __global__ void zero_split_kernel(GemmEpi e, int M, int N) {
   dst[(size_t)m * e.ld0 + nn] = 0.f;
 }
 
-template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int EPI>
+template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int EPI, int NS = 4, int MINW = 1>
 hipError_t launch_cfg(const GemmDesc& g, const GemmEpi& e, int split_k, hipStream_t st) {
-  constexpr int NS = 4;
-  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, A_KC, B_KC, EPI, NS>;
+  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, A_KC, B_KC, EPI, NS, MINW>;
   constexpr int lds_loop = NS * (BM + BN) * BK * 2;
   constexpr int lds_epi = WM * WN * 64 * (BN / WN + 8) * 4;
   constexpr int lds = lds_loop > lds_epi ? lds_loop : lds_epi;
@@ -467,8 +470,12 @@ hipError_t launch_layout(const GemmDesc& g, const GemmEpi& e, hipStream_t st) {
       if (err != hipSuccess) return err;
     }
   }
-  if (big) return launch_cfg<256, 256, 2, 2, A_KC, B_KC, EPI>(g, e, split_k, st);
-  return launch_cfg<128, 128, 2, 2, A_KC, B_KC, EPI>(g, e, split_k, st);
+  if (big) {
+    // short k loops: two 256x128 workgroups per compute unit hide each other's prologue/epilogue
+    if (EPI != EPI_SPLIT_F32 && nk <= 16) return launch_cfg<256, 128, 2, 2, A_KC, B_KC, EPI, 3, 2>(g, e, split_k, st);
+    return launch_cfg<256, 256, 2, 2, A_KC, B_KC, EPI, 5, 1>(g, e, split_k, st);
+  }
+  return launch_cfg<128, 128, 2, 2, A_KC, B_KC, EPI, 4, 1>(g, e, split_k, st);
 }
 
 }  // namespace
