@@ -38,7 +38,9 @@ def gemm_step_flops(cfg) -> dict:
         "gemm_wo": 2.0 * T * F * d, "attn_fwd": attn_f,
         "gemm_dwo_ff": 2.0 * T * F * d, "gemm_da_geglu_bwd": 2.0 * T * F * d, "gemm_dwi": 2.0 * T * d * F,
         "gemm_dn2": 2.0 * T * d * 2 * F, "gemm_dwo": 2.0 * T * I * d, "gemm_dc": 2.0 * T * I * d,
-        "attn_bwd": 2.0 * attn_f, "gemm_dwqkv": 2.0 * T * d * 3 * I, "gemm_dn1": 2.0 * T * d * 3 * I,
+        # attention backward is two kernels; its model FLOPs (4 matmuls) are split evenly: the dq kernel
+        # owns dP and dQ, the dk/dv kernel owns dV and dK (the recomputed scores are overhead, not work)
+        "attn_bwd_dq": attn_f, "attn_bwd_dkv": attn_f, "gemm_dwqkv": 2.0 * T * d * 3 * I, "gemm_dn1": 2.0 * T * d * 3 * I,
     }
 
 
@@ -76,6 +78,8 @@ def main() -> int:
     ap.add_argument("--workload", default="c2_small", choices=[k for k in SI.CONFIGS if k != "c1_tiny_f32"])
     ap.add_argument("--cpu-sample-batch", type=int, default=0, help="0 = pick about 10-30 s of oracle work")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run three 1 GiB device-to-device copies (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -92,6 +96,14 @@ def main() -> int:
     cfg = SI.CONFIGS[args.workload]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).zero_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": 1 << 30, "copies": 3}))
+        return 0
 
     # ---- seeded synthetic inputs, generated on the host, resident in HBM before timing
     w_host = SI.make_weights(cfg)
@@ -156,9 +168,17 @@ def main() -> int:
     mfma_steps = {k: v for k, v in per_kernel.items() if k in flops}
     dom = max(mfma_steps, key=lambda k: mfma_steps[k]["avg_ms"] * mfma_steps[k]["launches_per_step"])
     dom_tflops = flops[dom] / (per_kernel[dom]["avg_ms"] * 1e-3) / 1e12
+    # HBM bytes per launch of that kernel come from committed rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE,
+    # scaled by the same counters on a plain copy); bench.py cannot collect counters itself.
+    traffic = None
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as fh:
+            traffic = json.load(fh).get(cfg.name, {}).get(dom)
+    except (OSError, ValueError):
+        traffic = None
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(dom_tflops, 2), "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(dom_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
-                "avg_ms": round(per_kernel[dom]["avg_ms"], 4)}
+                "unit": "TFLOP/s", "frac": round(dom_tflops / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
+                "avg_ms": round(per_kernel[dom]["avg_ms"], 4), "flop_per_launch": flops[dom]}
     for k, v in per_kernel.items():
         v["avg_ms"] = round(v["avg_ms"], 4)
         if k in flops:

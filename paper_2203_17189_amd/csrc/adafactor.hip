@@ -3,7 +3,7 @@
 //
 // Factored tensor [R,C], tiles of 64 rows x 256 columns:
 //   stats     : per-tile row sums and column sums of G*G          -> rowpart[tc][R], colpart[tr][C]
-//   finalize  : v_row, v_col EMA; rfac_i = rsqrt(v_row_i / mean v_row); cfac_j = rsqrt(v_col_j)
+//   finalize  : v_row, v_col EMA; cfac_j = rsqrt(v_col_j); consumers form rsqrt(v_row_i / mean v_row)
 //   norms     : per-tile sums of U*U (U = G rfac cfac) and of W*W -> part[2][tiles]
 //   coef      : coef = lr * max(eps2, RMS(W)) / max(1, RMS(U)/clip)
 //   apply     : W -= coef * U   (+ optional bf16 copy)
@@ -86,22 +86,18 @@ __global__ __launch_bounds__(256) void af_stats_kernel(const float* __restrict__
   }
 }
 
-// Single workgroup of 1024 threads.
-__global__ __launch_bounds__(1024) void af_finalize_kernel(float* __restrict__ v_row, float* __restrict__ v_col,
-                                                           int64_t R, int64_t C, int ntc, int ntr, float beta2,
-                                                           float eps1, AfWs ws) {
-  __shared__ float red[16];
-  float vsum = 0.f;
-  for (int64_t i = threadIdx.x; i < R; i += 1024) {
+// One thread per row and per column: folds the tile partials into the second-moment vectors.
+// cfac_j = rsqrt(v_col_j); the row factor needs mean(v_row) and is formed by the consumers.
+__global__ __launch_bounds__(256) void af_finalize_kernel(float* __restrict__ v_row, float* __restrict__ v_col,
+                                                          int64_t R, int64_t C, int ntc, int ntr, float beta2,
+                                                          float eps1, AfWs ws) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx < R) {
     float s = 0.f;
-    for (int t = 0; t < ntc; ++t) s += ws.rowpart[(int64_t)t * R + i];
-    const float vr = beta2 * v_row[i] + (1.f - beta2) * (s / (float)C + eps1);
-    v_row[i] = vr;
-    vsum += vr;
-  }
-  const float mean_vr = block_sum<16>(vsum, red) / (float)R;
-  for (int64_t i = threadIdx.x; i < R; i += 1024) ws.rfac[i] = rsqrtf(v_row[i] / mean_vr);
-  for (int64_t j = threadIdx.x; j < C; j += 1024) {
+    for (int t = 0; t < ntc; ++t) s += ws.rowpart[(int64_t)t * R + idx];
+    v_row[idx] = beta2 * v_row[idx] + (1.f - beta2) * (s / (float)C + eps1);
+  } else if (idx < R + C) {
+    const int64_t j = idx - R;
     float s = 0.f;
     for (int t = 0; t < ntr; ++t) s += ws.colpart[(int64_t)t * C + j];
     const float vc = beta2 * v_col[j] + (1.f - beta2) * (s / (float)R + eps1);
@@ -110,12 +106,25 @@ __global__ __launch_bounds__(1024) void af_finalize_kernel(float* __restrict__ v
   }
 }
 
+// mean(v_row) in a fixed order, by a whole workgroup of 256 threads (every workgroup gets the same value).
+__device__ __forceinline__ float af_mean_vrow(const float* __restrict__ v_row, int64_t R, float* red) {
+  float s = 0.f;
+  for (int64_t i = threadIdx.x; i < R; i += 256) s += v_row[i];
+  return block_sum<4>(s, red) / (float)R;
+}
+
 // Per-tile sums of U*U and W*W.  FACT: U = g rfac cfac.  !FACT: updates v_full and U = g rsqrt(v).
 template <int VEC, bool FACT>
 __global__ __launch_bounds__(256) void af_norms_kernel(const float* __restrict__ g, const float* __restrict__ w,
-                                                       float* __restrict__ v_full, int64_t R, int64_t C,
-                                                       float beta2, float eps1, AfWs ws) {
-  __shared__ float red[8];
+                                                       float* __restrict__ v_full, const float* __restrict__ v_row,
+                                                       int64_t R, int64_t C, float beta2, float eps1, AfWs ws) {
+  __shared__ float red[12];
+  float inv_mean = 1.f;
+  if constexpr (FACT) {
+    const float mean_vr = af_mean_vrow(v_row, R, red + 8);
+    inv_mean = 1.f / mean_vr;
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) ws.scal[1] = inv_mean;
+  }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t c0 = (int64_t)blockIdx.x * 64 * VEC + lane * VEC;
   const int64_t r0 = (int64_t)blockIdx.y * TR;
@@ -130,7 +139,7 @@ __global__ __launch_bounds__(256) void af_norms_kernel(const float* __restrict__
       ldv<VEC>(g + r * C + c0, gv);
       ldv<VEC>(w + r * C + c0, wv);
       if constexpr (FACT) {
-        const float rf = ws.rfac[r];
+        const float rf = rsqrtf(v_row[r] * inv_mean);
 #pragma unroll
         for (int i = 0; i < VEC; ++i) {
           const float u = gv[i] * rf * cf[i];
@@ -179,8 +188,8 @@ __global__ __launch_bounds__(1024) void af_coef_kernel(int64_t ntiles, double co
 
 template <int VEC, bool FACT>
 __global__ __launch_bounds__(256) void af_apply_kernel(float* __restrict__ w, const float* __restrict__ g,
-                                                       const float* __restrict__ v_full, bf16* __restrict__ lp,
-                                                       int64_t R, int64_t C, AfWs ws) {
+                                                       const float* __restrict__ v_full, const float* __restrict__ v_row,
+                                                       bf16* __restrict__ lp, int64_t R, int64_t C, AfWs ws) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t c0 = (int64_t)blockIdx.x * 64 * VEC + lane * VEC;
   const int64_t r0 = (int64_t)blockIdx.y * TR;
@@ -195,7 +204,7 @@ __global__ __launch_bounds__(256) void af_apply_kernel(float* __restrict__ w, co
     ldv<VEC>(g + r * C + c0, gv);
     ldv<VEC>(w + r * C + c0, wv);
     if constexpr (FACT) {
-      const float rf = ws.rfac[r] * coef;
+      const float rf = rsqrtf(v_row[r] * ws.scal[1]) * coef;
 #pragma unroll
       for (int i = 0; i < VEC; ++i) wv[i] -= gv[i] * rf * cf[i];
     } else {
@@ -266,18 +275,18 @@ hipError_t launch_adafactor(float* param, const float* grad, float* v_row, float
     if (g.vec == 4) af_stats_kernel<4><<<grid, 256, 0, st>>>(grad, R, C, ws);
     else af_stats_kernel<1><<<grid, 256, 0, st>>>(grad, R, C, ws);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    af_finalize_kernel<<<1, 1024, 0, st>>>(v_row, v_col, R, C, g.ntc, g.ntr, beta2, c.eps1, ws);
+    af_finalize_kernel<<<ceil_div(R + C, 256), 256, 0, st>>>(v_row, v_col, R, C, g.ntc, g.ntr, beta2, c.eps1, ws);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    T5MI_AF(af_norms_kernel, true><<<grid, 256, 0, st>>>(grad, param, nullptr, R, C, beta2, c.eps1, ws));
+    T5MI_AF(af_norms_kernel, true><<<grid, 256, 0, st>>>(grad, param, nullptr, v_row, R, C, beta2, c.eps1, ws));
   } else {
-    T5MI_AF(af_norms_kernel, false><<<grid, 256, 0, st>>>(grad, param, v_full, R, C, beta2, c.eps1, ws));
+    T5MI_AF(af_norms_kernel, false><<<grid, 256, 0, st>>>(grad, param, v_full, nullptr, R, C, beta2, c.eps1, ws));
   }
   af_coef_kernel<<<1, 1024, 0, st>>>(g.ntiles, (double)R * (double)C, c, ws);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (factored)
-    T5MI_AF(af_apply_kernel, true><<<grid, 256, 0, st>>>(param, grad, nullptr, (bf16*)bf16_out, R, C, ws));
+    T5MI_AF(af_apply_kernel, true><<<grid, 256, 0, st>>>(param, grad, nullptr, v_row, (bf16*)bf16_out, R, C, ws));
   else
-    T5MI_AF(af_apply_kernel, false><<<grid, 256, 0, st>>>(param, grad, v_full, (bf16*)bf16_out, R, C, ws));
+    T5MI_AF(af_apply_kernel, false><<<grid, 256, 0, st>>>(param, grad, v_full, nullptr, (bf16*)bf16_out, R, C, ws));
 #undef T5MI_AF
   return hipSuccess;
 }

@@ -109,6 +109,25 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int first) {
   return o;
 }
 
+// Workgroup -> (tile, head, batch).  Workgroup ids are dealt round-robin to the 8 XCDs; the tiles of
+// one (batch, head) share its K/V (or Q/dO) stream, so they are given ids that are congruent mod 8
+// and adjacent in dispatch order: they run on one XCD at about the same time and share its L2.
+__device__ __forceinline__ void decode_block(int n_tiles, int H, int B, int& tile, int& h, int& b) {
+  const int bh_total = H * B;
+  const int id = blockIdx.x;
+  int bh;
+  if ((bh_total & 7) == 0) {
+    const int xcd = id & 7, j = id >> 3;
+    bh = (j / n_tiles) * 8 + xcd;
+    tile = j % n_tiles;
+  } else {
+    bh = id / n_tiles;
+    tile = id % n_tiles;
+  }
+  h = bh % H;
+  b = bh / H;
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // ------------------------------------------------------------------------------------------------
@@ -128,8 +147,9 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restri
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int S = a.S, I = a.H * DK;
   const size_t ld = (size_t)3 * I;
-  const int qt = CAUSAL ? (gridDim.x - 1 - blockIdx.x) : blockIdx.x;  // heavy causal tiles first
-  const int h = blockIdx.y, b = blockIdx.z;
+  int qt, h, b;
+  decode_block(S / BR, a.H, a.B, qt, h, b);
+  if (CAUSAL) qt = S / BR - 1 - qt;  // heavy causal tiles first
   const int i0 = qt * BR;
   const int i_loc = wave * 32 + (lane & 31);
   const int i = i0 + i_loc;
@@ -306,8 +326,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __res
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int S = a.S, I = a.H * DK;
   const size_t ld = (size_t)3 * I;
-  const int qt = CAUSAL ? (gridDim.x - 1 - blockIdx.x) : blockIdx.x;
-  const int h = blockIdx.y, b = blockIdx.z;
+  int qt, h, b;
+  decode_block(S / BR, a.H, a.B, qt, h, b);
+  if (CAUSAL) qt = S / BR - 1 - qt;
   const int i0 = qt * BR;
   const int i_w0 = i0 + wave * 32;         // first query of this wave
   const int i_lw = lane & 31;              // query index inside the wave
@@ -454,7 +475,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __res
 // dk and dv.  grid (ceil(S/128), H, B); wave w owns keys j0 + 32w + lane%32; loops over query tiles.
 // ------------------------------------------------------------------------------------------------
 template <int DK, bool CAUSAL>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __restrict__ qkv,
+__global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kernel(const bf16* __restrict__ qkv,
                                                                 const bf16* __restrict__ dout,
                                                                 const float* __restrict__ diag,
                                                                 const float* __restrict__ lse,
@@ -471,8 +492,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int S = a.S, I = a.H * DK;
   const size_t ld = (size_t)3 * I;
-  const int h = blockIdx.y, b = blockIdx.z;
-  const int j0 = blockIdx.x * BCK;
+  int kt_, h, b;
+  decode_block(S / BCK, a.H, a.B, kt_, h, b);
+  const int j0 = kt_ * BCK;
   const int j_loc = wave * 32 + (lane & 31);
   const int j = j0 + j_loc;
   const int j_ld = j < S ? j : S - 1;
@@ -608,28 +630,30 @@ hipError_t fwd_launch(const void* qkv, const float* diag, void* c, float* lse, c
   const size_t lds = 4 * 64 * DK * 2 + sizeof(float) * (a.S + 127);
   hipError_t e = set_lds(kern, lds);
   if (e != hipSuccess) return e;
-  kern<<<dim3(ceil_div(a.S, 128), a.H, a.B), 256, lds, st>>>((const bf16*)qkv, diag, (bf16*)c, lse, a);
+  kern<<<dim3((a.S / 128) * a.H * a.B), 256, lds, st>>>((const bf16*)qkv, diag, (bf16*)c, lse, a);
   return hipGetLastError();
 }
 
 template <int DK, bool CAUSAL>
 hipError_t bwd_launch(const void* qkv, const void* c, const void* dc, const float* diag, const float* lse,
-                      float* dvec, void* dqkv, float* ddiag, const AttnDims& a, int far, hipStream_t st) {
+                      float* dvec, void* dqkv, float* ddiag, const AttnDims& a, int far, int phase, hipStream_t st) {
+  hipError_t e = hipSuccess;
+  if (phase == 0) {
   const int64_t rows = (int64_t)a.B * a.S * a.H;
   attn_dvec_kernel<DK><<<ceil_div(rows * (DK / 8), 256), 256, 0, st>>>((const bf16*)c, (const bf16*)dc, dvec, a);
   const int64_t nd = (int64_t)a.H * (2 * a.S - 1);
   zero_kernel<<<ceil_div(nd, 256), 256, 0, st>>>(ddiag, nd);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  const dim3 grid(ceil_div(a.S, 128), a.H, a.B);
-  {
+  return hipGetLastError();
+  }
+  const dim3 grid((a.S / 128) * a.H * a.B);
+  if (phase == 1) {
     auto kern = attn_bwd_dq_mfma_kernel<DK, CAUSAL>;
     const size_t lds = 4 * 64 * DK * 2 + sizeof(float) * (4 * 32 * 36 + (a.S + 127) + 4 * (a.S + 31));
     if ((e = set_lds(kern, lds)) != hipSuccess) return e;
     kern<<<grid, 256, lds, st>>>((const bf16*)qkv, (const bf16*)dc, diag, lse, dvec, (bf16*)dqkv, ddiag, a, far);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  {
+  if (phase == 2) {
     auto kern = attn_bwd_dkv_mfma_kernel<DK, CAUSAL>;
     const size_t lds = 4 * 64 * DK * 2 + sizeof(float) * (256 + a.S + 127);
     if ((e = set_lds(kern, lds)) != hipSuccess) return e;
@@ -658,14 +682,15 @@ size_t attn_bwd_mfma_scratch_bytes(const AttnDims&) { return 0; }
 
 hipError_t launch_attn_bwd_mfma(const void* qkv, const void* c, const void* dc, const float* diag,
                                 const float* lse, float* dvec, void* dqkv, float* ddiag, void*,
-                                const AttnDims& a, int far, hipStream_t st) {
+                                const AttnDims& a, int far, int phase, hipStream_t st) {
+  // phase 0: dvec = rowsum(dO * O) and zeroed ddiag; phase 1: dq + bias-gradient diagonals; phase 2: dk, dv.
   // `far`: smallest distance that falls in the last (saturated) bucket; such offsets need no
   // per-diagonal resolution.  Never below 1, so offset 0 always takes the per-diagonal path.
   if (far < 1) far = 1;
-  if (a.dk == 64) return a.causal ? bwd_launch<64, true>(qkv, c, dc, diag, lse, dvec, dqkv, ddiag, a, far, st)
-                                  : bwd_launch<64, false>(qkv, c, dc, diag, lse, dvec, dqkv, ddiag, a, far, st);
-  return a.causal ? bwd_launch<128, true>(qkv, c, dc, diag, lse, dvec, dqkv, ddiag, a, far, st)
-                  : bwd_launch<128, false>(qkv, c, dc, diag, lse, dvec, dqkv, ddiag, a, far, st);
+  if (a.dk == 64) return a.causal ? bwd_launch<64, true>(qkv, c, dc, diag, lse, dvec, dqkv, ddiag, a, far, phase, st)
+                                  : bwd_launch<64, false>(qkv, c, dc, diag, lse, dvec, dqkv, ddiag, a, far, phase, st);
+  return a.causal ? bwd_launch<128, true>(qkv, c, dc, diag, lse, dvec, dqkv, ddiag, a, far, phase, st)
+                  : bwd_launch<128, false>(qkv, c, dc, diag, lse, dvec, dqkv, ddiag, a, far, phase, st);
 }
 
 }  // namespace t5mi

@@ -375,9 +375,15 @@ int t5_block_bwd(const t5_block_cfg* cfg, const void* dy, const void* x, const t
     GemmDesc g = gemm1(T, D.I, D.d, dh_op, D.d, 1, w->wo, D.d, 1, ty);
     T5_STEP("gemm_dc", run_gemm(g, epi(EPI_STORE, W.dc, D.I, ty), st));
   }
-  if (ty == IN_BF16 && attn_mfma_supported(ad))
-    T5_STEP("attn_bwd", launch_attn_bwd_mfma(S.qkv, S.c, W.dc, S.diag, S.lse, W.dvec, W.dqkv, W.ddiag, W.attn_scratch, ad,
-                                lut.n_thr > 0 ? lut.thr[lut.n_thr - 1] : lut.max_exact, st));
+  if (ty == IN_BF16 && attn_mfma_supported(ad)) {
+    const int far = lut.n_thr > 0 ? lut.thr[lut.n_thr - 1] : lut.max_exact;
+    T5_STEP("attn_bwd_prep", launch_attn_bwd_mfma(S.qkv, S.c, W.dc, S.diag, S.lse, W.dvec, W.dqkv, W.ddiag,
+                                                  W.attn_scratch, ad, far, 0, st));
+    T5_STEP("attn_bwd_dq", launch_attn_bwd_mfma(S.qkv, S.c, W.dc, S.diag, S.lse, W.dvec, W.dqkv, W.ddiag,
+                                                W.attn_scratch, ad, far, 1, st));
+    T5_STEP("attn_bwd_dkv", launch_attn_bwd_mfma(S.qkv, S.c, W.dc, S.diag, S.lse, W.dvec, W.dqkv, W.ddiag,
+                                                 W.attn_scratch, ad, far, 2, st));
+  }
   else
     T5_STEP("attn_bwd", launch_attn_bwd_simple(S.qkv, S.c, W.dc, ty, S.diag, S.lse, W.dvec, W.dqkv, W.ddiag, ad, st));
   T5_STEP("relpos_diag_bwd", launch_relpos_diag_bwd(W.ddiag, dw->rel_table, D.S, D.H, cfg->num_buckets, lut, acc, st));

@@ -76,17 +76,20 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;
 
-  // ---- XCD-aware tile mapping
+  // ---- XCD-aware mapping.  Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a
+  // contiguous chunk of the (k-slice, tile) space so that whole k-slices, and compact blocks of
+  // tiles inside them, share operand panels through one L2.
   const int nb = tiles_m * tiles_n;
-  int bid = blockIdx.x;
-  const int ks = bid / nb;  // split-k slice
-  bid -= ks * nb;
   int L;
   {
+    const int total = nb * split_k;
+    const int bid = blockIdx.x;
     const int xcd = bid & 7, idx = bid >> 3;
-    const int nb8 = (nb + 7) >> 3, rem = nb & 7;
+    const int nb8 = (total + 7) >> 3, rem = total & 7;
     if (rem == 0 || xcd < rem) L = xcd * nb8 + idx; else L = rem * nb8 + (xcd - rem) * (nb8 - 1) + idx;
   }
+  const int ks = L / nb;  // split-k slice
+  L -= ks * nb;
   constexpr int GM = 8;
   const int per_group = GM * tiles_n;
   const int group = L / per_group, in_g = L - group * per_group;

@@ -101,7 +101,7 @@ hipError_t launch_attn_fwd_mfma(const void* qkv, const float* diag, void* c, flo
 size_t attn_bwd_mfma_scratch_bytes(const AttnDims& a);
 hipError_t launch_attn_bwd_mfma(const void* qkv, const void* c, const void* dc, const float* diag,
                                 const float* lse, float* dvec, void* dqkv, float* ddiag, void* scratch,
-                                const AttnDims& a, int far, hipStream_t st);
+                                const AttnDims& a, int far, int phase, hipStream_t st);
 
 // ------------------------------------------------------------------ Adafactor
 size_t adafactor_ws_bytes(int64_t rows, int64_t cols, int factored);
