@@ -26,21 +26,24 @@ namespace t5mi {
 
 namespace {
 
-constexpr int BK = 32;   // k per LDS stage
 constexpr int KQ = 64;   // every segment's K must be a multiple of this
 
 typedef __attribute__((address_space(3))) short4v lds_short4;
 
-// k-contiguous stage: row r (64 B) holds logical chunk c at physical chunk c ^ kc_swz(r).
-__device__ __forceinline__ int kc_swz(int row) { return ((row >> 1) & 3) ^ ((row >> 3) & 1); }
+// k-contiguous stage: row r (BK*2 bytes) holds logical 16-byte chunk c at physical chunk c ^ kc_swz(r).
+template <int BK>
+__device__ __forceinline__ int kc_swz(int row) {
+  if constexpr (BK == 32) return ((row >> 1) & 3) ^ ((row >> 3) & 1);
+  else return (row ^ (row >> 3)) & 7;
+}
 
-// One MFMA operand (8 bf16 of k for row base + lane%32) for k-step kk (0 or 1) of a stage.
-template <int ROWS, bool KC>
+// One MFMA operand (8 bf16 of k for row base + lane%32) for k-step kk of a stage.
+template <int ROWS, bool KC, int BK>
 __device__ __forceinline__ bf16x8 load_frag(const char* stage, int base, int kk, int lane) {
   if constexpr (KC) {
     const int row = base + (lane & 31);
     const int chunk = kk * 2 + (lane >> 5);
-    return *reinterpret_cast<const bf16x8*>(stage + row * 64 + ((chunk ^ kc_swz(row)) << 4));
+    return *reinterpret_cast<const bf16x8*>(stage + row * (BK * 2) + ((chunk ^ kc_swz<BK>(row)) << 4));
   } else {
     // 16-lane groups: lanes supply the address of 4 consecutive m at row k; the transpose load hands
     // lane i the 4 k-values of m = group_base + i.
@@ -58,7 +61,7 @@ __device__ __forceinline__ bf16x8 load_frag(const char* stage, int base, int kk,
   }
 }
 
-template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int EPI, int NS, int MINW>
+template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int EPI, int NS, int MINW, int BK>
 __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc g, GemmEpi e, int tiles_m,
                                                                 int tiles_n, int split_k) {
   constexpr int NW = WM * WN;
@@ -70,6 +73,9 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
   constexpr int DMA_PER_TILE = A_DMA + B_DMA;
   static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile vs wave count");
   static_assert((NS - 1) * DMA_PER_TILE < 64, "vmcnt range");
+  constexpr int KSTEPS = BK / 16;
+  constexpr int RPB = 512 / BK;  // rows of a k-contiguous stage per 1 KB block
+  constexpr int CPRK = BK / 8;   // 16-byte chunks per such row
   extern __shared__ __attribute__((aligned(1024))) char smem[];
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -114,8 +120,8 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
   for (int i = 0; i < A_DMA; ++i) {
     const int q = wave + i * NW;  // 1 KB block inside the A stage
     if constexpr (A_KC) {
-      const int row = q * 16 + (lane >> 2);
-      const int chunk = (lane & 3) ^ kc_swz(row);
+      const int row = q * RPB + lane / CPRK;
+      const int chunk = (lane % CPRK) ^ kc_swz<BK>(row);
       int gr = m0 + row;
       gr = gr < g.M ? gr : g.M - 1;
       a_off[i] = (uint32_t)gr * (uint32_t)lda * 2u + (uint32_t)chunk * 16u;
@@ -133,8 +139,8 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
   for (int i = 0; i < B_DMA; ++i) {
     const int q = wave + i * NW;
     if constexpr (B_KC) {
-      const int row = q * 16 + (lane >> 2);
-      const int chunk = (lane & 3) ^ kc_swz(row);
+      const int row = q * RPB + lane / CPRK;
+      const int chunk = (lane % CPRK) ^ kc_swz<BK>(row);
       int gr = n0 + row;
       gr = gr < g.N ? gr : g.N - 1;
       b_off[i] = (uint32_t)gr * (uint32_t)ldb * 2u + (uint32_t)chunk * 16u;
@@ -181,9 +187,9 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
     const char* sa = smem + st * STAGE;
     const char* sb = sa + A_BYTES;
 #pragma unroll
-    for (int i = 0; i < MI; ++i) fa[slot][i] = load_frag<BM, A_KC>(sa, wm * TMW + i * 32, kk, lane);
+    for (int i = 0; i < MI; ++i) fa[slot][i] = load_frag<BM, A_KC, BK>(sa, wm * TMW + i * 32, kk, lane);
 #pragma unroll
-    for (int j = 0; j < NI; ++j) fb[slot][j] = load_frag<BN, B_KC>(sb, wn * TNW + j * 32, kk, lane);
+    for (int j = 0; j < NI; ++j) fb[slot][j] = load_frag<BN, B_KC, BK>(sb, wn * TNW + j * 32, kk, lane);
   };
   auto mfma_all = [&](int slot) {
 #pragma unroll
@@ -212,16 +218,19 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
       for (int s = 0; s < NS; ++s) {
         const int t = base + s;
         if (t < nk) {
-          // operands of k-step 1 of tile t, under the MFMAs of k-step 0
-          load_frags(s, 1, 1);
-          mfma_all(0);
-          interleave();
-          // tile t+1 has landed (this wave's part), all of this wave's reads of stage s are done;
+          // k-steps 0 .. KSTEPS-2: operands of the next k-step are fetched under this step's MFMAs
+#pragma unroll
+          for (int kk = 0; kk + 1 < KSTEPS; ++kk) {
+            load_frags(s, kk + 1, (kk + 1) & 1);
+            mfma_all(kk & 1);
+            interleave();
+          }
+          // tile t+1 has landed (this wave's part) and all of this wave's reads of stage s are done;
           // after the barrier that holds for every wave, so stage s can be refilled.
           asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((NS - 2) * DMA_PER_TILE) : "memory");
           dma_tile(t + NS, s);
           load_frags((s + 1) % NS, 0, 0);
-          mfma_all(1);
+          mfma_all((KSTEPS - 1) & 1);
           interleave();
         }
       }
@@ -427,9 +436,9 @@ __global__ void zero_split_kernel(GemmEpi e, int M, int N) {
   dst[(size_t)m * e.ld0 + nn] = 0.f;
 }
 
-template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int EPI, int NS = 4, int MINW = 1>
+template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int EPI, int NS = 4, int MINW = 1, int BK = 32>
 hipError_t launch_cfg(const GemmDesc& g, const GemmEpi& e, int split_k, hipStream_t st) {
-  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, A_KC, B_KC, EPI, NS, MINW>;
+  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, A_KC, B_KC, EPI, NS, MINW, BK>;
   constexpr int lds_loop = NS * (BM + BN) * BK * 2;
   constexpr int lds_epi = WM * WN * 64 * (BN / WN + 8) * 4;
   constexpr int lds = lds_loop > lds_epi ? lds_loop : lds_epi;
