@@ -484,7 +484,9 @@ hipError_t launch_layout(const GemmDesc& g, const GemmEpi& e, hipStream_t st) {
   }
   if (big) {
     // short k loops: two 256x128 workgroups per compute unit hide each other's prologue/epilogue
-    if (EPI != EPI_SPLIT_F32 && nk <= 16) return launch_cfg<256, 128, 2, 2, A_KC, B_KC, EPI, 3, 2>(g, e, split_k, st);
+    // and so do the epilogue-heavy gated-GELU kernels (three outputs, or two inputs and two outputs)
+    if (EPI != EPI_SPLIT_F32 && (nk <= 16 || EPI == EPI_GEGLU_FWD || EPI == EPI_GEGLU_BWD || (EPI == EPI_RESID && nk <= 32)))
+      return launch_cfg<256, 128, 2, 2, A_KC, B_KC, EPI, 3, 2>(g, e, split_k, st);
     return launch_cfg<256, 256, 2, 2, A_KC, B_KC, EPI, 5, 1>(g, e, split_k, st);
   }
   return launch_cfg<128, 128, 2, 2, A_KC, B_KC, EPI, 4, 1>(g, e, split_k, st);
