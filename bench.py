@@ -171,13 +171,17 @@ def main() -> int:
     # HBM bytes per launch of that kernel come from committed rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE,
     # scaled by the same counters on a plain copy); bench.py cannot collect counters itself.
     traffic = None
+    traffic_detail = None
     try:
         with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as fh:
-            traffic = json.load(fh).get(cfg.name, {}).get(dom)
-    except (OSError, ValueError):
+            traffic_detail = json.load(fh).get(cfg.name, {}).get(dom)
+        if traffic_detail is not None:
+            traffic = int(traffic_detail["read_bytes"]) + int(traffic_detail["write_bytes"])
+    except (OSError, ValueError, KeyError, TypeError):
         traffic = None
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(dom_tflops, 2), "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(dom_tflops / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
+                "traffic_unit": "HBM bytes per launch (read + write)", "traffic_detail": traffic_detail,
                 "avg_ms": round(per_kernel[dom]["avg_ms"], 4), "flop_per_launch": flops[dom]}
     for k, v in per_kernel.items():
         v["avg_ms"] = round(v["avg_ms"], 4)

@@ -156,22 +156,33 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
   }
   const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)smem;
 
-  // Issue the DMA of k-tile `t` (relative to kt_begin; clamped to the last tile) into stage `st`.
-  auto dma_tile = [&](int t, int st) {
-    // Workgroups start their k loop at different phases (rotated by a multiple of the tile
-    // coordinates) so that concurrently running tiles do not all stream the same 256-byte-interleaved
-    // L2 channel; tiles past the end wrap around and refetch valid data that is never used.
+  // Global base addresses of k-tile `t` (relative to kt_begin).
+  // Workgroups start their k loop at different phases (rotated by a multiple of the tile
+  // coordinates) so that concurrently running tiles do not all stream the same 256-byte-interleaved
+  // L2 channel; tiles past the end wrap around and refetch valid data that is never used.
+  auto tile_bases = [&](int t, const char*& abase, const char*& bbase) {
     int kt = kt_begin + (t % nk + k_skew) % nk;
     int s = 0;
     while (s + 1 < g.nseg && kt >= g.seg[s].K / BK) { kt -= g.seg[s].K / BK; ++s; }
     const size_t k0 = (size_t)kt * BK;
-    const char* abase = (const char*)g.seg[s].A + (A_KC ? k0 * 2 : k0 * (size_t)lda * 2);
-    const char* bbase = (const char*)g.seg[s].B + (B_KC ? k0 * 2 : k0 * (size_t)ldb * 2);
+    abase = (const char*)g.seg[s].A + (A_KC ? k0 * 2 : k0 * (size_t)lda * 2);
+    bbase = (const char*)g.seg[s].B + (B_KC ? k0 * 2 : k0 * (size_t)ldb * 2);
+  };
+  // Issue DMA instructions [d0, d1) of a k-tile into stage `st`; a tile's DMA_PER_TILE instructions
+  // per wave are numbered A slots first, then B slots.
+  auto dma_part = [&](const char* abase, const char* bbase, int st, int d0, int d1) {
     const uint32_t sa = lds0 + st * STAGE, sb = sa + A_BYTES;
 #pragma unroll
-    for (int i = 0; i < A_DMA; ++i) dma_1k(sa + (wave + i * NW) * 1024, abase, a_off[i]);
-#pragma unroll
-    for (int i = 0; i < B_DMA; ++i) dma_1k(sb + (wave + i * NW) * 1024, bbase, b_off[i]);
+    for (int d = 0; d < DMA_PER_TILE; ++d) {
+      if (d < d0 || d >= d1) continue;
+      if (d < A_DMA) dma_1k(sa + (wave + d * NW) * 1024, abase, a_off[d < A_DMA ? d : 0]);
+      else dma_1k(sb + (wave + (d - A_DMA) * NW) * 1024, bbase, b_off[d >= A_DMA ? d - A_DMA : 0]);
+    }
+  };
+  auto dma_tile = [&](int t, int st) {
+    const char *ab, *bb;
+    tile_bases(t, ab, bb);
+    dma_part(ab, bb, st, 0, DMA_PER_TILE);
   };
 
   f32x16 acc[MI][NI];
@@ -191,47 +202,55 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
 #pragma unroll
     for (int j = 0; j < NI; ++j) fb[slot][j] = load_frag<BN, B_KC, BK>(sb, wn * TNW + j * 32, kk, lane);
   };
-  auto mfma_all = [&](int slot) {
+  // One k-step in MI chunks.  Chunk i issues its share of `dcount` DMA instructions (numbers dbase..)
+  // of a k-tile into stage dst, fetches its share of the next k-step's fragments (stage ld_st,
+  // k-step ld_kk, into register set nxt) and runs the MFMAs of accumulator row i from register set
+  // cur.  The DMA instructions are spread out because a wave that issues them back to back sits in
+  // the memory pipeline's issue queue instead of feeding the matrix unit.
+  auto kstep = [&](int cur, int ld_st, int ld_kk, int nxt, const char* abase, const char* bbase, int dst,
+                   int dbase, int dcount) {
+    const char* sa = smem + ld_st * STAGE;
+    const char* sb = sa + A_BYTES;
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
+    for (int i = 0; i < MI; ++i) {
+      if (dcount > 0) dma_part(abase, bbase, dst, dbase + i * dcount / MI, dbase + (i + 1) * dcount / MI);
+      fa[nxt][i] = load_frag<BM, A_KC, BK>(sa, wm * TMW + i * 32, ld_kk, lane);
 #pragma unroll
       for (int j = 0; j < NI; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
-  };
-  constexpr int DS_PER_FRAGSET = (A_KC ? MI : 2 * MI) + (B_KC ? NI : 2 * NI);
-  auto interleave = [&]() {  // spread one fragment set's LDS reads between the 16 MFMAs of a k-step
+        if (j >= i * NI / MI && j < (i + 1) * NI / MI)
+          fb[nxt][j] = load_frag<BN, B_KC, BK>(sb, wn * TNW + j * 32, ld_kk, lane);
 #pragma unroll
-    for (int q = 0; q < MI + NI; ++q) {
-      __builtin_amdgcn_sched_group_barrier(0x008, (MI * NI) / (MI + NI) > 0 ? (MI * NI) / (MI + NI) : 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, DS_PER_FRAGSET / (MI + NI), 0);
+      for (int j = 0; j < NI; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
+  constexpr int H0 = NS == 2 ? DMA_PER_TILE : DMA_PER_TILE / 2;  // a tile's DMA is issued in two parts: [0, H0) and [H0, DMA_PER_TILE)
 
   if (nk > 0) {
-    // Prologue: fill every stage, wait for tile 0.
+    // Prologue: fill stages 0 .. NS-2 and the first part of stage NS-1, wait for tile 0.
+    const char *ab, *bb;
 #pragma unroll
-    for (int s = 0; s < NS; ++s) dma_tile(s, s);
-    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((NS - 1) * DMA_PER_TILE) : "memory");
+    for (int s = 0; s + 1 < NS; ++s) dma_tile(s, s);
+    tile_bases(NS - 1, ab, bb);
+    dma_part(ab, bb, NS - 1, 0, H0);
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((NS - 2) * DMA_PER_TILE + H0) : "memory");
     load_frags(0, 0, 0);
     for (int base = 0; base < nk; base += NS) {
 #pragma unroll
       for (int s = 0; s < NS; ++s) {
         const int t = base + s;
         if (t < nk) {
-          // k-steps 0 .. KSTEPS-2: operands of the next k-step are fetched under this step's MFMAs
+          // k-step 0 also issues the second part of tile t+NS-1 (its stage was released at the
+          // previous barrier); k-steps 1 .. KSTEPS-2 issue none
+          kstep(0, s, 1, 1, ab, bb, (s + NS - 1) % NS, H0, DMA_PER_TILE - H0);
 #pragma unroll
-          for (int kk = 0; kk + 1 < KSTEPS; ++kk) {
-            load_frags(s, kk + 1, (kk + 1) & 1);
-            mfma_all(kk & 1);
-            interleave();
-          }
+          for (int kk = 1; kk + 1 < KSTEPS; ++kk) kstep(kk & 1, s, kk + 1, (kk + 1) & 1, ab, bb, 0, 0, 0);
           // tile t+1 has landed (this wave's part) and all of this wave's reads of stage s are done;
           // after the barrier that holds for every wave, so stage s can be refilled.
           asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((NS - 2) * DMA_PER_TILE) : "memory");
-          dma_tile(t + NS, s);
-          load_frags((s + 1) % NS, 0, 0);
-          mfma_all((KSTEPS - 1) & 1);
-          interleave();
+          tile_bases(t + NS, ab, bb);
+          kstep((KSTEPS - 1) & 1, (s + 1) % NS, 0, 0, ab, bb, s, 0, H0);
         }
       }
     }
