@@ -134,7 +134,7 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // Forward.  grid (ceil(S/128), H, B), 256 threads; wave w owns queries i0 + 32w + lane%32.
 // ------------------------------------------------------------------------------------------------
 template <int DK, bool CAUSAL>
-__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv,
+__global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv,
                                                             const float* __restrict__ diag,
                                                             bf16* __restrict__ c, float* __restrict__ lse,
                                                             AttnDims a) {
@@ -308,7 +308,7 @@ __global__ __launch_bounds__(256) void attn_dvec_kernel(const bf16* __restrict__
 // is in the same bucket.
 // ------------------------------------------------------------------------------------------------
 template <int DK, bool CAUSAL>
-__global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv,
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv,
                                                                const bf16* __restrict__ dout,
                                                                const float* __restrict__ diag,
                                                                const float* __restrict__ lse,
