@@ -129,6 +129,7 @@ __device__ __forceinline__ void decode_block(int n_tiles, int H, int B, int& til
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float sc_of(const AttnDims& a) { return a.scale * kLog2e; }
 
 // ------------------------------------------------------------------------------------------------
 // Forward.  grid (ceil(S/128), H, B), 256 threads; wave w owns queries i0 + 32w + lane%32.
@@ -349,8 +350,16 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __
     }
   }
   const size_t srow = ((size_t)b * a.H + h) * S + i;
-  const float lse2 = lse[srow] * kLog2e;
-  const float dv_i = dvec[srow];
+  // The score and dP accumulators start from -lse/scale and -dvec (loop-invariant register
+  // vectors), so that the MFMA results are already (s - lse/scale) and (dP - dvec).
+  // (With 128 channels the register budget has no room for the two seed vectors: the subtraction
+  // is done after the MFMAs there.)
+  constexpr bool SEED = DK == 64;
+  const float nl = -lse[srow] / a.scale, nd = -dvec[srow];
+  f32x16 s_init, dp_init;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) { s_init[r] = SEED ? nl : 0.f; dp_init[r] = SEED ? nd : 0.f; }
+  const float nl2 = SEED ? 0.f : nl * sc_of(a), nd2 = SEED ? 0.f : nd;
   {
     const float* dgh = diag + (size_t)h * (2 * S - 1);
     for (int t = tid; t < S + BR - 1; t += 256) dg[t] = dgh[t - (i0 + BR - 1) + (S - 1)] * kLog2e;
@@ -386,9 +395,11 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __
     for (int kt = 0; kt < BC / 32; ++kt) {
       const int j0s = j0 + kt * 32;
       if (CAUSAL && j0s > i_w0 + 31) continue;  // whole sub-tile masked for this wave
-      f32x16 sT, dpT;
+      float bias[16];  // requested before the MFMAs: the LDS latency hides behind the matrix work
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { sT[r] = 0.f; dpT[r] = 0.f; }
+      for (int r = 0; r < 16; ++r) bias[r] = dg[dg_base + j0s + ((r >> 2) << 3) + (g << 2) + (r & 3)];
+      __builtin_amdgcn_sched_barrier(0);
+      f32x16 sT = s_init, dpT = dp_init;
 #pragma unroll
       for (int kk = 0; kk < KS; ++kk) {
         sT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Kt, kt * 32, kk, lane), qf[kk], sT, 0, 0, 0);
@@ -397,9 +408,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int j = j0s + ((r >> 2) << 3) + (g << 2) + (r & 3);
-        float p = fast_exp2(fmaf(sT[r], sc, dg[dg_base + j]) - lse2);
+        float p = fast_exp2(SEED ? fmaf(sT[r], sc, bias[r]) : fmaf(sT[r], sc, bias[r]) + nl2);
         if (CAUSAL && j > i) p = 0.f;
-        sT[r] = p * (dpT[r] - dv_i);
+        sT[r] = p * (SEED ? dpT[r] : dpT[r] + nd2);
       }
       // ---- bias gradient of this 32x32 sub-tile (wave-uniform branches)
       if (j0s + 31 - i_w0 <= -far) {
@@ -484,8 +495,10 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
   constexpr int BCK = 128, BQ = 64, KS = DK / 16, CT = DK / 32;
   constexpr int TILE = BQ * DK * 2, STG = 2 * TILE;  // a stage holds a Q tile then a dO tile
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  float* lse_all = reinterpret_cast<float*>(smem + 2 * STG);  // [2 stages][BQ] log2 units
-  float* dv_all = lse_all + 2 * BQ;                           // [2 stages][BQ]
+  // The score and dP accumulators start from -lse/scale and -dvec, so that the MFMA results are
+  // already (s - lse/scale) and (dP - dvec): no per-element subtraction afterwards.
+  float* lse_all = reinterpret_cast<float*>(smem + 2 * STG);  // [2 stages][BQ]  -lse / scale
+  float* dv_all = lse_all + 2 * BQ;                           // [2 stages][BQ]  -dvec
   float* dg = dv_all + 2 * BQ;                                // [S + BCK - 1] log2 units
 
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
@@ -537,9 +550,10 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
   const int n_it = S / BQ;
   tq.issue(lds0, base + (size_t)it_begin * BQ * ld, wave);
   tdo.issue(lds0 + TILE, dobase + (size_t)it_begin * BQ * I, wave);
+  const float neg_inv_scale = -1.f / a.scale;
   if (tid < BQ) {
-    lse_all[tid] = lse[srow + it_begin * BQ + tid] * kLog2e;
-    dv_all[tid] = dvec[srow + it_begin * BQ + tid];
+    lse_all[tid] = lse[srow + it_begin * BQ + tid] * neg_inv_scale;
+    dv_all[tid] = -dvec[srow + it_begin * BQ + tid];
   }
   for (int it = it_begin; it < n_it; ++it) {
     const int q0 = it * BQ;
@@ -552,8 +566,8 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
       tq.issue(nxt, base + (size_t)(q0 + BQ) * ld, wave);
       tdo.issue(nxt + TILE, dobase + (size_t)(q0 + BQ) * I, wave);
       if (tid < BQ) {
-        nl = lse[srow + q0 + BQ + tid] * kLog2e;
-        nd = dvec[srow + q0 + BQ + tid];
+        nl = lse[srow + q0 + BQ + tid] * neg_inv_scale;
+        nd = -dvec[srow + q0 + BQ + tid];
       }
     }
     const char* Qt = smem + st * STG;
@@ -562,9 +576,26 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
     const float* dv_s = dv_all + st * BQ;
 #pragma unroll
     for (int qb = 0; qb < BQ / 32; ++qb) {
+      // bias values and accumulator seeds are requested before the MFMAs so that their LDS latency
+      // is hidden behind the matrix work instead of stalling the softmax arithmetic
+      // (done for 128 channels, where one wave per SIMD leaves nothing else to hide it; with 64
+      // channels the extra live registers would cost the third wave per SIMD, which hides more)
+      constexpr bool HOIST = DK == 128;
+      float bias[16];
+      if constexpr (HOIST) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          bias[r] = dg[j_loc + (S - 1 - (q0 + qb * 32 + ((r >> 2) << 3) + (g << 2) + (r & 3)))];
+      }
       f32x16 s, dp;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+      for (int rq = 0; rq < 4; ++rq) {
+        const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_s + qb * 32 + rq * 8 + g * 4);
+        const f32x4 d4 = *reinterpret_cast<const f32x4*>(dv_s + qb * 32 + rq * 8 + g * 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { s[rq * 4 + e] = l4[e]; dp[rq * 4 + e] = d4[e]; }
+      }
+      if constexpr (HOIST) __builtin_amdgcn_sched_group_barrier(0x100, 12, 0);  // 8 bias + 4 seed reads first
 #pragma unroll
       for (int kk = 0; kk < KS; ++kk) {
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Qt, qb * 32, kk, lane), kf[kk], s, 0, 0, 0);
@@ -574,10 +605,10 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
       for (int r = 0; r < 16; ++r) {
         const int il = qb * 32 + ((r >> 2) << 3) + (g << 2) + (r & 3);
         const int i = q0 + il;
-        float p = fast_exp2(fmaf(s[r], sc, dg[j_loc + (S - 1 - i)]) - lse_s[il]);
+        float p = fast_exp2(fmaf(s[r], sc, HOIST ? bias[r] : dg[j_loc + (S - 1 - i)]));
         if (CAUSAL && j > i) p = 0.f;
         s[r] = p;
-        dp[r] = p * (dp[r] - dv_s[il]);
+        dp[r] = p * dp[r];
       }
 #pragma unroll
       for (int mm = 0; mm < 2; ++mm) {
