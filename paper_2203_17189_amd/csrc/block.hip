@@ -55,7 +55,9 @@ struct Carver {
 
 struct Stash {
   float *r1, *r2, *lse, *h, *diag;
-  void *n1, *qkv, *c, *n2, *u, *w, *a;
+  // gp = w * gelu'(u) and gl = gelu(u) are the saved factors of the gated GELU (u, w: the wi_0 / wi_1
+  // projections); the simple path uses the two buffers for u and w first and converts them in place.
+  void *n1, *qkv, *c, *n2, *gp, *gl, *a;
 };
 size_t carve_stash(const Dims& D, void* base, Stash* s) {
   Carver cv(base);
@@ -69,8 +71,8 @@ size_t carve_stash(const Dims& D, void* base, Stash* s) {
   t.qkv = cv.take((size_t)D.T * 3 * D.I * D.es);
   t.c = cv.take((size_t)D.T * D.I * D.es);
   t.n2 = cv.take((size_t)D.T * D.d * D.es);
-  t.u = cv.take((size_t)D.T * D.F * D.es);
-  t.w = cv.take((size_t)D.T * D.F * D.es);
+  t.gp = cv.take((size_t)D.T * D.F * D.es);
+  t.gl = cv.take((size_t)D.T * D.F * D.es);
   t.a = cv.take((size_t)D.T * D.F * D.es);
   if (s) *s = t;
   return cv.off;
@@ -281,16 +283,16 @@ int t5_block_fwd(const t5_block_cfg* cfg, const void* x, const t5_block_weights*
     const void* src[2] = {w->wi0, w->wi1};
     T5_STEP("pack_weights", launch_pack_transpose_bf16(src, 2, D.d, D.F, W.wi_t, 32, st));
     GemmDesc g = gemm1(T, 2 * D.F, D.d, S.n2, D.d, 1, W.wi_t, D.d, 1, ty);
-    GemmEpi e = epi(EPI_GEGLU_FWD, S.u, D.F, ty);
-    e.out1 = S.w; e.out2 = S.a;
+    GemmEpi e = epi(EPI_GEGLU_FWD, S.gp, D.F, ty);
+    e.out1 = S.gl; e.out2 = S.a;
     if (!gemm_mfma_supported(g, e)) return T5_ERR_UNSUPPORTED;
     T5_STEP("gemm_wi_geglu", launch_gemm_mfma(g, e, st));
   } else {
     GemmDesc g0 = gemm1(T, D.F, D.d, S.n2, D.d, 1, w->wi0, D.F, 0, ty);
-    T5_STEP("gemm_wi", run_gemm(g0, epi(EPI_STORE, S.u, D.F, ty), st));
+    T5_STEP("gemm_wi", run_gemm(g0, epi(EPI_STORE, S.gp, D.F, ty), st));
     GemmDesc g1 = gemm1(T, D.F, D.d, S.n2, D.d, 1, w->wi1, D.F, 0, ty);
-    T5_STEP("gemm_wi", run_gemm(g1, epi(EPI_STORE, S.w, D.F, ty), st));
-    T5_STEP("geglu_fwd", launch_geglu_fwd(S.u, S.w, S.a, ty, (int64_t)D.T * D.F, st));
+    T5_STEP("gemm_wi", run_gemm(g1, epi(EPI_STORE, S.gl, D.F, ty), st));
+    T5_STEP("geglu_fwd", launch_geglu_fwd(S.gp, S.gl, S.a, ty, (int64_t)D.T * D.F, st));
   }
   {  // y = h + a Wo_ff
     GemmDesc g;
@@ -341,7 +343,7 @@ int t5_block_bwd(const t5_block_cfg* cfg, const void* dy, const void* x, const t
   {  // da = dy Wo_ff^T, fused with the gated-GELU backward: du = da w gelu'(u), dw = da gelu(u)
     GemmDesc g = gemm1(T, D.F, D.d, dy, D.d, 1, w->wo_ff, D.d, 1, ty);
     GemmEpi e = epi(EPI_GEGLU_BWD, W.du, D.F, ty);
-    e.out1 = W.dw; e.aux0 = S.u; e.aux1 = S.w; e.aux_type = ty;
+    e.out1 = W.dw; e.aux0 = S.gp; e.aux1 = S.gl; e.aux_type = ty;
     T5_STEP("gemm_da_geglu_bwd", run_gemm(g, e, st));
   }
   {  // dWi0 = n2^T du, dWi1 = n2^T dw

@@ -291,8 +291,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
     if (interior) {
       float* stg = reinterpret_cast<float*>(smem) + wave * (64 * EP_LD);
       const int cl = lane & 31, rl = (lane >> 5) << 2;
-#pragma unroll
-      for (int half = 0; half < MI / 2; ++half) {
+      auto stage_half = [&](int half) {
 #pragma unroll
         for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
@@ -302,8 +301,12 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
               stg[(ii * 32 + ((r >> 2) << 3) + rl + (r & 3)) * EP_LD + j * 32 + cl] = acc[half * 2 + ii][j][r];
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_wave_barrier();
-        const int mh = mw + half * 64;
-        if constexpr (EPI == EPI_GEGLU_FWD) {
+      };
+      if constexpr (EPI == EPI_GEGLU_FWD) {
+#pragma unroll
+        for (int half = 0; half < MI / 2; ++half) {
+          stage_half(half);
+          const int mh = mw + half * 64;
           // staged columns: [u 32 | w 32] pairs; lane takes 4 consecutive f of one row
           constexpr int LPR = TNW / 8;  // lanes per row
           const int fl = (lane % LPR) * 4;
@@ -314,83 +317,125 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
             const int rloc = it * (64 / LPR) + lane / LPR;
             const f32x4 uu = *reinterpret_cast<const f32x4*>(stg + rloc * EP_LD + pc);
             const f32x4 ww = *reinterpret_cast<const f32x4*>(stg + rloc * EP_LD + pc + 32);
-            bf16x4 ub, wb, ab;
+            bf16x4 gpb, glb, ab;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-              ub[q] = (bf16)uu[q];
-              wb[q] = (bf16)ww[q];
-              ab[q] = (bf16)(gelu_tanh((float)ub[q]) * (float)wb[q]);
+              float gl, dgl;
+              gelu_tanh_both(uu[q], gl, dgl);
+              gpb[q] = (bf16)(ww[q] * dgl);
+              glb[q] = (bf16)gl;
+              ab[q] = (bf16)(gl * ww[q]);
             }
             const size_t o = (size_t)(mh + rloc) * e.ld0 + f;
-            *reinterpret_cast<bf16x4*>((bf16*)e.out0 + o) = ub;
-            *reinterpret_cast<bf16x4*>((bf16*)e.out1 + o) = wb;
+            *reinterpret_cast<bf16x4*>((bf16*)e.out0 + o) = gpb;
+            *reinterpret_cast<bf16x4*>((bf16*)e.out1 + o) = glb;
             *reinterpret_cast<bf16x4*>((bf16*)e.out2 + o) = ab;
           }
-        } else {
-          constexpr int LPR = TNW / 4;     // lanes per row
-          constexpr int RPI = 64 / LPR;    // rows per wave instruction
-          const int c4 = (lane % LPR) * 4;
-          float* split_dst = nullptr;
-          if constexpr (EPI == EPI_SPLIT_F32) {
-            const int which = nw / e.split_n;
-            split_dst = (float*)(which == 0 ? e.out0 : which == 1 ? e.out1 : e.out2) + (nw - which * e.split_n) + c4;
-          }
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+          __builtin_amdgcn_wave_barrier();
+        }
+      } else {
+        constexpr int LPR = TNW / 4;     // lanes per row
+        constexpr int RPI = 64 / LPR;    // rows per wave instruction
+        constexpr int NIT = 64 / RPI;    // instructions per 64-row half
+        constexpr int BT = 8;            // instructions per batch of auxiliary loads
+        constexpr int NB = NIT / BT, NBT = (MI / 2) * NB;
+        static_assert(NIT % BT == 0, "batching");
+        const int c4 = (lane % LPR) * 4;
+        // element offset of this lane in instruction `it` of half `half`: o0 + (half*64 + it*RPI) * ld0
+        const size_t o0 = (size_t)(mw + lane / LPR) * e.ld0 + nw + c4;
+        float* split_dst = nullptr;
+        if constexpr (EPI == EPI_SPLIT_F32) {
+          const int which = nw / e.split_n;
+          split_dst = (float*)(which == 0 ? e.out0 : which == 1 ? e.out1 : e.out2) + (nw - which * e.split_n) + c4 +
+                      (size_t)(mw + lane / LPR) * e.ld0;
+        }
+        // The auxiliary operands (residual; saved gated-GELU factors) come from HBM with a latency of a
+        // microsecond or more.  They are fetched in batches of BT instructions, one batch ahead of the
+        // arithmetic that uses them, so that many loads are in flight instead of one or two.
+        constexpr bool AUX = EPI == EPI_RESID || EPI == EPI_GEGLU_BWD;
+        bf16x4 xa[2][AUX ? BT : 1], xb[2][EPI == EPI_GEGLU_BWD ? BT : 1];
+        f32x4 xf[2][EPI == EPI_RESID ? BT : 1];
+        const bool aux_f32 = EPI == EPI_RESID && e.aux_type != IN_BF16;
+        auto aux_batch = [&](int bi) {  // bi: batch index over both halves
+          if constexpr (AUX) {
+            const int set = bi & 1;
+            const size_t ob = o0 + (size_t)((bi / NB) * 64 + (bi % NB) * BT * RPI) * e.ld0;
 #pragma unroll
-          for (int it = 0; it < 64 / RPI; ++it) {
-            const int rloc = it * RPI + lane / LPR;
-            f32x4 v = *reinterpret_cast<const f32x4*>(stg + rloc * EP_LD + c4);
-            const size_t o = (size_t)(mh + rloc) * e.ld0 + nw + c4;
-            if constexpr (EPI == EPI_SPLIT_F32) {
-              float* d = split_dst + (size_t)(mh + rloc) * e.ld0;
-              if (split_k > 1) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) unsafeAtomicAdd(d + q, v[q]);
+            for (int q = 0; q < BT; ++q) {
+              const size_t o = ob + (size_t)(q * RPI) * e.ld0;
+              if constexpr (EPI == EPI_GEGLU_BWD) {
+                xa[set][q] = *reinterpret_cast<const bf16x4*>((const bf16*)e.aux0 + o);
+                xb[set][q] = *reinterpret_cast<const bf16x4*>((const bf16*)e.aux1 + o);
               } else {
-                if (e.accumulate) {
-                  const f32x4 old = *reinterpret_cast<const f32x4*>(d);
-#pragma unroll
-                  for (int q = 0; q < 4; ++q) v[q] += old[q];
-                }
-                *reinterpret_cast<f32x4*>(d) = v;
-              }
-            } else if constexpr (EPI == EPI_GEGLU_BWD) {
-              const bf16x4 ub = *reinterpret_cast<const bf16x4*>((const bf16*)e.aux0 + o);
-              const bf16x4 wb = *reinterpret_cast<const bf16x4*>((const bf16*)e.aux1 + o);
-              bf16x4 du, dw;
-#pragma unroll
-              for (int q = 0; q < 4; ++q) {
-                float gl, dgl;
-                gelu_tanh_both((float)ub[q], gl, dgl);
-                du[q] = (bf16)(v[q] * (float)wb[q] * dgl);
-                dw[q] = (bf16)(v[q] * gl);
-              }
-              *reinterpret_cast<bf16x4*>((bf16*)e.out0 + o) = du;
-              *reinterpret_cast<bf16x4*>((bf16*)e.out1 + o) = dw;
-            } else {  // EPI_STORE, EPI_RESID
-              if constexpr (EPI == EPI_RESID) {
-                if (e.aux_type == IN_BF16) {
-                  const bf16x4 x = *reinterpret_cast<const bf16x4*>((const bf16*)e.aux0 + o);
-#pragma unroll
-                  for (int q = 0; q < 4; ++q) v[q] += (float)x[q];
-                } else {
-                  const f32x4 x = *reinterpret_cast<const f32x4*>((const float*)e.aux0 + o);
-#pragma unroll
-                  for (int q = 0; q < 4; ++q) v[q] += x[q];
-                }
-              }
-              if (e.out_type == IN_BF16) {
-                bf16x4 ob;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) ob[q] = (bf16)v[q];
-                *reinterpret_cast<bf16x4*>((bf16*)e.out0 + o) = ob;
-              } else {
-                *reinterpret_cast<f32x4*>((float*)e.out0 + o) = v;
+                if (aux_f32) xf[set][q] = *reinterpret_cast<const f32x4*>((const float*)e.aux0 + o);
+                else xa[set][q] = *reinterpret_cast<const bf16x4*>((const bf16*)e.aux0 + o);
               }
             }
           }
+        };
+        aux_batch(0);
+#pragma unroll
+        for (int half = 0; half < MI / 2; ++half) {
+          stage_half(half);
+#pragma unroll
+          for (int b = 0; b < NB; ++b) {
+            const int bi = half * NB + b;
+            if (bi + 1 < NBT) aux_batch(bi + 1);
+            if constexpr (AUX) __builtin_amdgcn_sched_barrier(0);
+            const int set = bi & 1;
+#pragma unroll
+            for (int q = 0; q < BT; ++q) {
+              const int it = b * BT + q;
+              const int rloc = it * RPI + lane / LPR;
+              f32x4 v = *reinterpret_cast<const f32x4*>(stg + rloc * EP_LD + c4);
+              const size_t o = o0 + (size_t)(half * 64 + it * RPI) * e.ld0;
+              if constexpr (EPI == EPI_SPLIT_F32) {
+                float* d = split_dst + (size_t)(half * 64 + it * RPI) * e.ld0;
+                if (split_k > 1) {
+#pragma unroll
+                  for (int qq = 0; qq < 4; ++qq) unsafeAtomicAdd(d + qq, v[qq]);
+                } else {
+                  if (e.accumulate) {
+                    const f32x4 old = *reinterpret_cast<const f32x4*>(d);
+#pragma unroll
+                    for (int qq = 0; qq < 4; ++qq) v[qq] += old[qq];
+                  }
+                  *reinterpret_cast<f32x4*>(d) = v;
+                }
+              } else if constexpr (EPI == EPI_GEGLU_BWD) {
+                bf16x4 du, dw;
+#pragma unroll
+                for (int qq = 0; qq < 4; ++qq) {
+                  du[qq] = (bf16)(v[qq] * (float)xa[set][q][qq]);
+                  dw[qq] = (bf16)(v[qq] * (float)xb[set][q][qq]);
+                }
+                *reinterpret_cast<bf16x4*>((bf16*)e.out0 + o) = du;
+                *reinterpret_cast<bf16x4*>((bf16*)e.out1 + o) = dw;
+              } else {  // EPI_STORE, EPI_RESID
+                if constexpr (EPI == EPI_RESID) {
+                  if (aux_f32) {
+#pragma unroll
+                    for (int qq = 0; qq < 4; ++qq) v[qq] += xf[set][q][qq];
+                  } else {
+#pragma unroll
+                    for (int qq = 0; qq < 4; ++qq) v[qq] += (float)xa[set][q][qq];
+                  }
+                }
+                if (e.out_type == IN_BF16) {
+                  bf16x4 ob;
+#pragma unroll
+                  for (int qq = 0; qq < 4; ++qq) ob[qq] = (bf16)v[qq];
+                  *reinterpret_cast<bf16x4*>((bf16*)e.out0 + o) = ob;
+                } else {
+                  *reinterpret_cast<f32x4*>((float*)e.out0 + o) = v;
+                }
+              }
+            }
+          }
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+          __builtin_amdgcn_wave_barrier();
         }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        __builtin_amdgcn_wave_barrier();
       }
       return;
     }
@@ -409,12 +454,13 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
           const int n = n0 + wn * TNW + j * 32;  // packed column of the u tile; w tile follows
           if (n >= g.N) continue;
           const int f = (n >> 6) * 32 + col_l;
-          // round u and w to storage precision first so the saved values reproduce `a` in the backward
-          const bf16 ub = (bf16)acc[i][j][r], wb = (bf16)acc[i][j + 1][r];
+          const float uu = acc[i][j][r], ww = acc[i][j + 1][r];
+          float gl, dgl;
+          gelu_tanh_both(uu, gl, dgl);
           const size_t o = (size_t)m * e.ld0 + f;
-          ((bf16*)e.out0)[o] = ub;
-          ((bf16*)e.out1)[o] = wb;
-          ((bf16*)e.out2)[o] = (bf16)(gelu_tanh((float)ub) * (float)wb);
+          ((bf16*)e.out0)[o] = (bf16)(ww * dgl);
+          ((bf16*)e.out1)[o] = (bf16)gl;
+          ((bf16*)e.out2)[o] = (bf16)(gl * ww);
         }
       } else {
 #pragma unroll
@@ -429,10 +475,8 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
             const float a = e.aux_type == IN_BF16 ? (float)((const bf16*)e.aux0)[o] : ((const float*)e.aux0)[o];
             if (e.out_type == IN_BF16) ((bf16*)e.out0)[o] = (bf16)(v + a); else ((float*)e.out0)[o] = v + a;
           } else if constexpr (EPI == EPI_GEGLU_BWD) {
-            const float u = (float)((const bf16*)e.aux0)[o], w = (float)((const bf16*)e.aux1)[o];
-            float gl, dgl;
-            gelu_tanh_both(u, gl, dgl);
-            ((bf16*)e.out0)[o] = (bf16)(v * w * dgl);
+            const float gp = (float)((const bf16*)e.aux0)[o], gl = (float)((const bf16*)e.aux1)[o];
+            ((bf16*)e.out0)[o] = (bf16)(v * gp);
             ((bf16*)e.out1)[o] = (bf16)(v * gl);
           } else {  // EPI_SPLIT_F32
             const int which = n / e.split_n, nn = n - which * e.split_n;

@@ -87,10 +87,8 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(GemmDesc g, GemmEpi e)
           st_elem(e.out0, o, e.out_type, v + ld_elem(e.aux0, o, e.aux_type));
           break;
         case EPI_GEGLU_BWD: {
-          const float u = ld_elem(e.aux0, o, e.aux_type), w = ld_elem(e.aux1, o, e.aux_type);
-          float gl, dgl;
-          gelu_tanh_both(u, gl, dgl);
-          st_elem(e.out0, o, e.out_type, v * w * dgl);
+          const float gp = ld_elem(e.aux0, o, e.aux_type), gl = ld_elem(e.aux1, o, e.aux_type);
+          st_elem(e.out0, o, e.out_type, v * gp);
           st_elem(e.out1, o, e.out_type, v * gl);
           break;
         }
@@ -109,11 +107,17 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(GemmDesc g, GemmEpi e)
 }
 
 template <typename T>
-__global__ void geglu_fwd_kernel(const T* __restrict__ u, const T* __restrict__ w, T* __restrict__ a,
-                                 int64_t n) {
+__global__ void geglu_fwd_kernel(T* __restrict__ u, T* __restrict__ w, T* __restrict__ a, int64_t n) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (; i < n; i += stride) a[i] = from_f32<T>(gelu_tanh(to_f32(u[i])) * to_f32(w[i]));
+  for (; i < n; i += stride) {
+    const float uu = to_f32(u[i]), ww = to_f32(w[i]);
+    float gl, dgl;
+    gelu_tanh_both(uu, gl, dgl);
+    a[i] = from_f32<T>(gl * ww);
+    u[i] = from_f32<T>(ww * dgl);
+    w[i] = from_f32<T>(gl);
+  }
 }
 
 // dst[n][k] for a 32x32 tile staged through LDS; see launch_pack_transpose_bf16.
@@ -157,13 +161,13 @@ hipError_t launch_gemm_simple(const GemmDesc& g, const GemmEpi& e, hipStream_t s
   return hipGetLastError();
 }
 
-hipError_t launch_geglu_fwd(const void* u, const void* w, void* a, int type, int64_t n, hipStream_t st) {
+hipError_t launch_geglu_fwd(void* u, void* w, void* a, int type, int64_t n, hipStream_t st) {
   int64_t blocks = (n + 255) / 256;
   if (blocks > 65536) blocks = 65536;
   if (type == IN_BF16)
-    geglu_fwd_kernel<bf16><<<(int)blocks, 256, 0, st>>>((const bf16*)u, (const bf16*)w, (bf16*)a, n);
+    geglu_fwd_kernel<bf16><<<(int)blocks, 256, 0, st>>>((bf16*)u, (bf16*)w, (bf16*)a, n);
   else
-    geglu_fwd_kernel<float><<<(int)blocks, 256, 0, st>>>((const float*)u, (const float*)w, (float*)a, n);
+    geglu_fwd_kernel<float><<<(int)blocks, 256, 0, st>>>((float*)u, (float*)w, (float*)a, n);
   return hipGetLastError();
 }
 

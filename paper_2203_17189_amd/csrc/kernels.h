@@ -42,8 +42,10 @@ struct GemmSeg {
 enum EpiKind {
   EPI_STORE = 0,      // out0[m*ld0 + n] = acc                    (out_type)
   EPI_RESID = 1,      // out0[m*ld0 + n] = acc + aux0[m*ld0 + n]  (aux0 of aux_type)
-  EPI_GEGLU_FWD = 2,  // MFMA path only: B rows interleave wi0/wi1 in groups of 32; writes u, w, a
-  EPI_GEGLU_BWD = 3,  // acc = da; reads u = aux0, w = aux1; out0 = du, out1 = dw   (all ld0)
+  // Gated GELU, a = gelu(u) * w.  The forward saves the two factors the backward needs instead of
+  // u and w themselves: gp = w * gelu'(u) and gl = gelu(u), so that du = da * gp and dw = da * gl.
+  EPI_GEGLU_FWD = 2,  // MFMA path only: B rows interleave wi0/wi1 in groups of 32; out0 = gp, out1 = gl, out2 = a
+  EPI_GEGLU_BWD = 3,  // acc = da; reads gp = aux0, gl = aux1; out0 = du, out1 = dw   (all ld0)
   EPI_SPLIT_F32 = 4   // float32 out; column n goes to outs[n / split_n][m*ld0 + n % split_n]; += if accumulate
 };
 struct GemmEpi {
@@ -79,7 +81,8 @@ hipError_t launch_pack_transpose_bf16(const void* const* srcs, int nsrc, int K, 
                                       int interleave, hipStream_t st);
 
 // ------------------------------------------------------------------ elementwise gated GELU (simple path)
-hipError_t launch_geglu_fwd(const void* u, const void* w, void* a, int type, int64_t n, hipStream_t st);
+// a = gelu(u) * w; then overwrites u with w * gelu'(u) and w with gelu(u) (the saved backward factors).
+hipError_t launch_geglu_fwd(void* u, void* w, void* a, int type, int64_t n, hipStream_t st);
 
 // ------------------------------------------------------------------ attention
 struct AttnDims {
