@@ -128,6 +128,25 @@ __device__ __forceinline__ void decode_block(int n_tiles, int H, int B, int& til
   b = bh / H;
 }
 
+// dg[t] = src[idx_of(t)] * log2(e) for t in [0, n): 256 threads, four independent loads in flight per
+// thread (the slice is short, so its load latency is all there is to hide).
+template <typename F>
+__device__ __forceinline__ void fill_bias_slice(float* dg, const float* __restrict__ src, int n, int tid, F idx_of) {
+  for (int t0 = tid; t0 < n; t0 += 4 * 256) {
+    float v[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int t = t0 + q * 256;
+      v[q] = src[idx_of(t < n ? t : n - 1)];
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int t = t0 + q * 256;
+      if (t < n) dg[t] = v[q] * kLog2e;
+    }
+  }
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float sc_of(const AttnDims& a) { return a.scale * kLog2e; }
 
@@ -165,11 +184,10 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
   }
   {
     const float* dgh = diag + (size_t)h * (2 * S - 1);
-    for (int t = tid; t < S + BR - 1; t += 256) {
-      int idx = t - (i0 + BR - 1) + (S - 1);  // delta + S - 1
-      idx = idx < 0 ? 0 : idx;                // only reachable by clamped (unused) queries
-      dg[t] = dgh[idx] * kLog2e;
-    }
+    fill_bias_slice(dg, dgh, S + BR - 1, tid, [&](int t) {
+      const int idx = t - (i0 + BR - 1) + (S - 1);  // delta + S - 1
+      return idx < 0 ? 0 : idx;                     // only reachable by clamped (unused) queries
+    });
   }
   const float sc = a.scale * kLog2e;
   const int dg_base = BR - 1 - i_loc;  // dg[dg_base + j] = bias(j - i)
@@ -362,7 +380,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __
   const float nl2 = SEED ? 0.f : nl * sc_of(a), nd2 = SEED ? 0.f : nd;
   {
     const float* dgh = diag + (size_t)h * (2 * S - 1);
-    for (int t = tid; t < S + BR - 1; t += 256) dg[t] = dgh[t - (i0 + BR - 1) + (S - 1)] * kLog2e;
+    fill_bias_slice(dg, dgh, S + BR - 1, tid, [&](int t) { return t - (i0 + BR - 1) + (S - 1); });
     for (int t = tid; t < 4 * (S + 31); t += 256) ddg_all[t] = 0.f;
   }
   const float sc = a.scale * kLog2e;
