@@ -36,7 +36,7 @@ def gemm_step_flops(cfg) -> dict:
     return {
         "gemm_qkv": 2.0 * T * d * 3 * I, "gemm_o": 2.0 * T * I * d, "gemm_wi_geglu": 2.0 * T * d * 2 * F,
         "gemm_wo": 2.0 * T * F * d, "attn_fwd": attn_f,
-        "gemm_dwo_ff": 2.0 * T * F * d, "gemm_da_geglu_bwd": 2.0 * T * F * d, "gemm_dwi": 2.0 * T * d * F,
+        "gemm_dwo_ff": 2.0 * T * F * d, "gemm_da_geglu_bwd": 2.0 * T * F * d, "gemm_dwi": 2.0 * T * d * 2 * F,
         "gemm_dn2": 2.0 * T * d * 2 * F, "gemm_dwo": 2.0 * T * I * d, "gemm_dc": 2.0 * T * I * d,
         # attention backward is two kernels; its model FLOPs (4 matmuls) are split evenly: the dq kernel
         # owns dP and dQ, the dk/dv kernel owns dV and dK (the recomputed scores are overhead, not work)

@@ -94,7 +94,7 @@ size_t carve_fwd(const Dims& D, void* base, FwdWs* w) {
 
 struct BwdWs {
   float *dn, *dh, *dvec, *ddiag, *dg_partial;
-  void *dh_lp, *du, *dw, *dc, *dqkv, *attn_scratch;
+  void *dh_lp, *duw, *dc, *dqkv, *attn_scratch;  // duw: [T][2F], du in columns 0..F-1, dw in F..2F-1
 };
 size_t carve_bwd(const Dims& D, void* base, BwdWs* w) {
   Carver cv(base);
@@ -105,8 +105,7 @@ size_t carve_bwd(const Dims& D, void* base, BwdWs* w) {
   t.ddiag = cv.take<float>((size_t)D.H * (2 * D.S - 1) * 4);
   t.dg_partial = cv.take<float>((size_t)rmsnorm_bwd_partial_rows((int)D.T) * D.d * 4);
   t.dh_lp = cv.take(D.ty == IN_BF16 ? (size_t)D.T * D.d * D.es : 0);
-  t.du = cv.take((size_t)D.T * D.F * D.es);
-  t.dw = cv.take((size_t)D.T * D.F * D.es);
+  t.duw = cv.take((size_t)D.T * 2 * D.F * D.es);
   t.dc = cv.take((size_t)D.T * D.I * D.es);
   t.dqkv = cv.take((size_t)D.T * 3 * D.I * D.es);
   AttnDims ad{D.B, D.S, D.H, D.dk, 0, 1.f};
@@ -334,32 +333,42 @@ int t5_block_bwd(const t5_block_cfg* cfg, const void* dy, const void* x, const t
   const size_t es = D.es;
   const AttnDims ad{D.B, D.S, D.H, D.dk, cfg->causal ? 1 : 0, cfg->attn_scale};
 
+  if (!acc) {
+    // the weight-gradient GEMMs add split-k partial sums: clear all their outputs in one launch
+    ZeroList z;
+    std::memset(&z, 0, sizeof(z));
+    float* ps[7] = {(float*)dw->wq, (float*)dw->wk, (float*)dw->wv, (float*)dw->wo, (float*)dw->wi0,
+                    (float*)dw->wi1, (float*)dw->wo_ff};
+    const int64_t ns[7] = {(int64_t)D.d * D.I, (int64_t)D.d * D.I, (int64_t)D.d * D.I, (int64_t)D.I * D.d,
+                           (int64_t)D.d * D.F, (int64_t)D.d * D.F, (int64_t)D.F * D.d};
+    for (int q = 0; q < 7; ++q) { z.p[q] = ps[q]; z.n[q] = ns[q]; }
+    z.count = 7;
+    T5_STEP("zero_grads", launch_zero_f32(z, st));
+  }
+  void* du_p = W.duw;
+  void* dw_p = at(W.duw, (size_t)D.F, es);
   {  // dWo_ff = a^T dy
     GemmDesc g = gemm1(D.F, D.d, T, S.a, D.F, 0, dy, D.d, 0, ty);
     GemmEpi e = epi(EPI_SPLIT_F32, dw->wo_ff, D.d, IN_F32);
-    e.accumulate = acc;
+    e.accumulate = 1;
     T5_STEP("gemm_dwo_ff", run_gemm(g, e, st));
   }
   {  // da = dy Wo_ff^T, fused with the gated-GELU backward: du = da w gelu'(u), dw = da gelu(u)
     GemmDesc g = gemm1(T, D.F, D.d, dy, D.d, 1, w->wo_ff, D.d, 1, ty);
-    GemmEpi e = epi(EPI_GEGLU_BWD, W.du, D.F, ty);
-    e.out1 = W.dw; e.aux0 = S.gp; e.aux1 = S.gl; e.aux_type = ty;
+    GemmEpi e = epi(EPI_GEGLU_BWD, du_p, 2 * D.F, ty);
+    e.out1 = dw_p; e.aux0 = S.gp; e.aux1 = S.gl; e.aux_type = ty; e.ld_aux = D.F;
     T5_STEP("gemm_da_geglu_bwd", run_gemm(g, e, st));
   }
-  {  // dWi0 = n2^T du, dWi1 = n2^T dw
-    GemmDesc g0 = gemm1(D.d, D.F, T, S.n2, D.d, 0, W.du, D.F, 0, ty);
-    GemmEpi e0 = epi(EPI_SPLIT_F32, dw->wi0, D.F, IN_F32);
-    e0.accumulate = acc;
-    T5_STEP("gemm_dwi", run_gemm(g0, e0, st));
-    GemmDesc g1 = gemm1(D.d, D.F, T, S.n2, D.d, 0, W.dw, D.F, 0, ty);
-    GemmEpi e1 = epi(EPI_SPLIT_F32, dw->wi1, D.F, IN_F32);
-    e1.accumulate = acc;
-    T5_STEP("gemm_dwi", run_gemm(g1, e1, st));
+  {  // dWi0 | dWi1 = n2^T [du | dw]
+    GemmDesc g = gemm1(D.d, 2 * D.F, T, S.n2, D.d, 0, du_p, 2 * D.F, 0, ty);
+    GemmEpi e = epi(EPI_SPLIT_F32, dw->wi0, D.F, IN_F32);
+    e.out1 = dw->wi1; e.split_n = D.F; e.accumulate = 1;
+    T5_STEP("gemm_dwi", run_gemm(g, e, st));
   }
   {  // dn2 = du Wi0^T + dw Wi1^T
-    GemmDesc g = gemm1(T, D.d, D.F, W.du, D.F, 1, w->wi0, D.F, 1, ty);
+    GemmDesc g = gemm1(T, D.d, D.F, du_p, 2 * D.F, 1, w->wi0, D.F, 1, ty);
     g.nseg = 2;
-    g.seg[1] = GemmSeg{W.dw, w->wi1, D.F, D.F, D.F};
+    g.seg[1] = GemmSeg{dw_p, w->wi1, 2 * D.F, D.F, D.F};
     T5_STEP("gemm_dn2", run_gemm(g, epi(EPI_STORE, W.dn, D.d, IN_F32), st));
   }
   // dh = dy + RMSNormBwd(h, g2, dn2)
@@ -370,7 +379,7 @@ int t5_block_bwd(const t5_block_cfg* cfg, const void* dy, const void* x, const t
   {  // dWo = c^T dh
     GemmDesc g = gemm1(D.I, D.d, T, S.c, D.I, 0, dh_op, D.d, 0, ty);
     GemmEpi e = epi(EPI_SPLIT_F32, dw->wo, D.d, IN_F32);
-    e.accumulate = acc;
+    e.accumulate = 1;
     T5_STEP("gemm_dwo", run_gemm(g, e, st));
   }
   {  // dc = dh Wo^T
@@ -392,7 +401,7 @@ int t5_block_bwd(const t5_block_cfg* cfg, const void* dy, const void* x, const t
   {  // dWq | dWk | dWv = n1^T dqkv
     GemmDesc g = gemm1(D.d, 3 * D.I, T, S.n1, D.d, 0, W.dqkv, 3 * D.I, 0, ty);
     GemmEpi e = epi(EPI_SPLIT_F32, dw->wq, D.I, IN_F32);
-    e.out1 = dw->wk; e.out2 = dw->wv; e.split_n = D.I; e.accumulate = acc;
+    e.out1 = dw->wk; e.out2 = dw->wv; e.split_n = D.I; e.accumulate = 1;
     T5_STEP("gemm_dwqkv", run_gemm(g, e, st));
   }
   {  // dn1 = dq Wq^T + dk Wk^T + dv Wv^T

@@ -267,7 +267,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
   {
     constexpr int EP_LD = TNW + 8;  // floats per staged row
     const int mw = m0 + wm * TMW, nw = n0 + wn * TNW;
-    bool interior = (mw + TMW <= g.M) && (nw + TNW <= g.N) && (e.ld0 % 8 == 0);
+    bool interior = (mw + TMW <= g.M) && (nw + TNW <= g.N) && (e.ld0 % 8 == 0) && (e.ld_aux % 8 == 0);
     if constexpr (EPI == EPI_SPLIT_F32)
       interior = interior && (nw / e.split_n == (nw + TNW - 1) / e.split_n) && (e.split_n % 4 == 0);
     if constexpr (EPI == EPI_SPLIT_F32) {
@@ -344,6 +344,8 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
         const int c4 = (lane % LPR) * 4;
         // element offset of this lane in instruction `it` of half `half`: o0 + (half*64 + it*RPI) * ld0
         const size_t o0 = (size_t)(mw + lane / LPR) * e.ld0 + nw + c4;
+        const int ld_aux = e.ld_aux ? e.ld_aux : e.ld0;
+        const size_t a0 = (size_t)(mw + lane / LPR) * ld_aux + nw + c4;  // same, in the auxiliary operands
         float* split_dst = nullptr;
         if constexpr (EPI == EPI_SPLIT_F32) {
           const int which = nw / e.split_n;
@@ -360,10 +362,10 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
         auto aux_batch = [&](int bi) {  // bi: batch index over both halves
           if constexpr (AUX) {
             const int set = bi & 1;
-            const size_t ob = o0 + (size_t)((bi / NB) * 64 + (bi % NB) * BT * RPI) * e.ld0;
+            const size_t ob = a0 + (size_t)((bi / NB) * 64 + (bi % NB) * BT * RPI) * ld_aux;
 #pragma unroll
             for (int q = 0; q < BT; ++q) {
-              const size_t o = ob + (size_t)(q * RPI) * e.ld0;
+              const size_t o = ob + (size_t)(q * RPI) * ld_aux;
               if constexpr (EPI == EPI_GEGLU_BWD) {
                 xa[set][q] = *reinterpret_cast<const bf16x4*>((const bf16*)e.aux0 + o);
                 xb[set][q] = *reinterpret_cast<const bf16x4*>((const bf16*)e.aux1 + o);
@@ -472,10 +474,12 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
           if constexpr (EPI == EPI_STORE) {
             if (e.out_type == IN_BF16) ((bf16*)e.out0)[o] = (bf16)v; else ((float*)e.out0)[o] = v;
           } else if constexpr (EPI == EPI_RESID) {
-            const float a = e.aux_type == IN_BF16 ? (float)((const bf16*)e.aux0)[o] : ((const float*)e.aux0)[o];
+            const size_t oa = (size_t)m * (e.ld_aux ? e.ld_aux : e.ld0) + n;
+            const float a = e.aux_type == IN_BF16 ? (float)((const bf16*)e.aux0)[oa] : ((const float*)e.aux0)[oa];
             if (e.out_type == IN_BF16) ((bf16*)e.out0)[o] = (bf16)(v + a); else ((float*)e.out0)[o] = v + a;
           } else if constexpr (EPI == EPI_GEGLU_BWD) {
-            const float gp = (float)((const bf16*)e.aux0)[o], gl = (float)((const bf16*)e.aux1)[o];
+            const size_t oa = (size_t)m * (e.ld_aux ? e.ld_aux : e.ld0) + n;
+            const float gp = (float)((const bf16*)e.aux0)[oa], gl = (float)((const bf16*)e.aux1)[oa];
             ((bf16*)e.out0)[o] = (bf16)(v * gp);
             ((bf16*)e.out1)[o] = (bf16)(v * gl);
           } else {  // EPI_SPLIT_F32

@@ -2,6 +2,7 @@
 // 64x64 output tile, 16-deep LDS stages, float32 FMA, any shape and either operand orientation.
 // Also: the elementwise gated-GELU of the unfused path and the bf16 weight transpose-pack.
 #include "kernels.h"
+#include <algorithm>
 
 namespace t5mi {
 
@@ -84,10 +85,11 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(GemmDesc g, GemmEpi e)
           st_elem(e.out0, o, e.out_type, v);
           break;
         case EPI_RESID:
-          st_elem(e.out0, o, e.out_type, v + ld_elem(e.aux0, o, e.aux_type));
+          st_elem(e.out0, o, e.out_type, v + ld_elem(e.aux0, (size_t)m * (e.ld_aux ? e.ld_aux : e.ld0) + n, e.aux_type));
           break;
         case EPI_GEGLU_BWD: {
-          const float gp = ld_elem(e.aux0, o, e.aux_type), gl = ld_elem(e.aux1, o, e.aux_type);
+          const size_t oa = (size_t)m * (e.ld_aux ? e.ld_aux : e.ld0) + n;
+          const float gp = ld_elem(e.aux0, oa, e.aux_type), gl = ld_elem(e.aux1, oa, e.aux_type);
           st_elem(e.out0, o, e.out_type, v * gp);
           st_elem(e.out1, o, e.out_type, v * gl);
           break;
@@ -158,6 +160,23 @@ hipError_t launch_gemm_simple(const GemmDesc& g, const GemmEpi& e, hipStream_t s
   if (e.kind == EPI_GEGLU_FWD) return hipErrorInvalidValue;
   dim3 grid(ceil_div(g.N, SB), ceil_div(g.M, SB));
   gemm_simple_kernel<<<grid, 256, 0, st>>>(g, e);
+  return hipGetLastError();
+}
+
+__global__ void zero_f32_kernel(ZeroList z) {
+  const int a = blockIdx.y;
+  float* p = z.p[a];
+  const int64_t n = z.n[a];
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+    p[i] = 0.f;
+}
+
+hipError_t launch_zero_f32(const ZeroList& z, hipStream_t st) {
+  if (z.count <= 0) return hipSuccess;
+  int64_t mx = 0;
+  for (int a = 0; a < z.count; ++a) mx = z.n[a] > mx ? z.n[a] : mx;
+  const int64_t blocks = std::min<int64_t>((mx + 255) / 256, 1024);
+  zero_f32_kernel<<<dim3((unsigned)std::max<int64_t>(blocks, 1), (unsigned)z.count), 256, 0, st>>>(z);
   return hipGetLastError();
 }
 

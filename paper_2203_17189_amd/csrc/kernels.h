@@ -55,7 +55,8 @@ struct GemmEpi {
   void* out2;
   const void* aux0;
   const void* aux1;
-  int ld0;
+  int ld0;       // leading dimension of out0/out1/out2
+  int ld_aux;    // leading dimension of aux0/aux1 (0: same as ld0)
   int out_type;  // IN_F32 / IN_BF16 for out0/out1/out2
   int aux_type;
   int split_n;
@@ -73,6 +74,15 @@ hipError_t launch_gemm_simple(const GemmDesc& g, const GemmEpi& e, hipStream_t s
 // and 16-byte aligned pointers; gemm_mfma_supported() checks this.
 bool gemm_mfma_supported(const GemmDesc& g, const GemmEpi& e);
 hipError_t launch_gemm_mfma(const GemmDesc& g, const GemmEpi& e, hipStream_t st);
+
+// Sets up to 8 float arrays to zero in one launch (the weight gradients, before the split-k GEMMs add
+// their partial sums into them).
+struct ZeroList {
+  float* p[8];
+  int64_t n[8];
+  int count;
+};
+hipError_t launch_zero_f32(const ZeroList& z, hipStream_t st);
 
 // Transpose-pack for the forward weights (bf16): dst[n][k] = src_j[k][n'] for the concatenation of
 // nsrc matrices [K, n_each] along n.  interleave > 0: packed row n maps to source
