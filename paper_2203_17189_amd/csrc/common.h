@@ -58,24 +58,22 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return s;
 }
 
-// tanh through one exp2 and one reciprocal: tanh(x) = 1 - 2 / (1 + e^(2x)).  Saturates correctly at
-// +-inf; absolute error ~1e-7, which gelu() scales by z/2.
-__device__ __forceinline__ float fast_tanh(float x) {
-  const float e = __builtin_amdgcn_exp2f(x * 2.885390081777927f);  // 2 * log2(e)
-  return 1.f - 2.f * __builtin_amdgcn_rcpf(1.f + e);
+// tanh-form GELU, float32.  0.5 (1 + tanh(y)) = 1 / (1 + e^(-2y)), so
+//   gelu(z) = z * s,  s = sigmoid(2 kappa (z + beta z^3)),
+//   gelu'(z) = s + z s (1 - s) * 2 kappa (1 + 3 beta z^2),
+// with one exp2 and one reciprocal (absolute error ~1e-7).  Saturates without NaNs: s -> 0 for
+// large negative z (exp2 -> inf, rcp -> 0), s -> 1 for large positive z.
+__device__ __forceinline__ float gelu_gate(float z, float z2) {
+  const float c = -2.f * 0.7978845608028654f * 1.4426950408889634f;  // -2 kappa log2(e)
+  const float inner = z * fmaf(z2, 0.044715f, 1.f);
+  return __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(c * inner));
 }
-// tanh-form GELU and its derivative, float32.
-__device__ __forceinline__ float gelu_tanh(float z) {
-  const float kappa = 0.7978845608028654f, beta = 0.044715f;
-  const float t = fast_tanh(kappa * (z + beta * z * z * z));
-  return 0.5f * z * (1.f + t);
-}
+__device__ __forceinline__ float gelu_tanh(float z) { return z * gelu_gate(z, z * z); }
 __device__ __forceinline__ void gelu_tanh_both(float z, float& g, float& dg) {
-  const float kappa = 0.7978845608028654f, beta = 0.044715f;
   const float z2 = z * z;
-  const float t = fast_tanh(kappa * (z + beta * z * z2));
-  g = 0.5f * z * (1.f + t);
-  dg = 0.5f * (1.f + t) + 0.5f * z * (1.f - t * t) * kappa * (1.f + 3.f * beta * z2);
+  const float s = gelu_gate(z, z2);
+  g = z * s;
+  dg = fmaf(g * (1.f - s), 2.f * 0.7978845608028654f * fmaf(z2, 3.f * 0.044715f, 1.f), s);
 }
 
 // Threshold table of the logarithmic relative-position buckets, built on the host in exact
