@@ -551,8 +551,11 @@ hipError_t launch_layout(const GemmDesc& g, const GemmEpi& e, hipStream_t st) {
   }
   if (big) {
     // short k loops: two 256x128 workgroups per compute unit hide each other's prologue/epilogue
-    // and so do the epilogue-heavy gated-GELU kernels (three outputs, or two inputs and two outputs)
-    if (EPI != EPI_SPLIT_F32 && (nk <= 16 || EPI == EPI_GEGLU_FWD || EPI == EPI_GEGLU_BWD || (EPI == EPI_RESID && nk <= 32)))
+    // and so do the epilogue-heavy gated-GELU kernels (three outputs, or two inputs and two outputs);
+    // the gated-GELU forward goes back to one 256x256 tile once k is long enough (measured: better
+    // from K = 2048, worse at K = 768) because the smaller tiles re-stream more operand data
+    if (EPI != EPI_SPLIT_F32 && (nk <= 16 || (EPI == EPI_GEGLU_FWD && nk < 24) || EPI == EPI_GEGLU_BWD ||
+                                 (EPI == EPI_RESID && nk <= 32)))
       return launch_cfg<256, 128, 2, 2, A_KC, B_KC, EPI, 3, 2>(g, e, split_k, st);
     return launch_cfg<256, 256, 2, 2, A_KC, B_KC, EPI, 5, 1>(g, e, split_k, st);
   }
