@@ -413,15 +413,39 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __
     for (int kt = 0; kt < BC / 32; ++kt) {
       const int j0s = j0 + kt * 32;
       if (CAUSAL && j0s > i_w0 + 31) continue;  // whole sub-tile masked for this wave
-      float bias[16];  // requested before the MFMAs: the LDS latency hides behind the matrix work
+      // All LDS operands of the sub-tile are requested up front (K and V rows for S and dP, the bias
+      // values, the transposed K operand of the dq update) and the scheduler may not sink them: read
+      // just in time, every MFMA waits out an LDS round trip.
+      // (With 128 channels the operands do not fit the register budget; only the bias goes first.)
+      constexpr bool PRE = DK == 64;
+      bf16x8 kfr[PRE ? KS : 1], vfr[PRE ? KS : 1], ktr[2][PRE ? CT : 1];
+      float bias[16];
+      if constexpr (PRE) {
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) {
+          kfr[kk] = frag_rows<DK>(Kt, kt * 32, kk, lane);
+          vfr[kk] = frag_rows<DK>(Vt, kt * 32, kk, lane);
+        }
+      }
 #pragma unroll
       for (int r = 0; r < 16; ++r) bias[r] = dg[dg_base + j0s + ((r >> 2) << 3) + (g << 2) + (r & 3)];
+      if constexpr (PRE) {
+#pragma unroll
+        for (int mm = 0; mm < 2; ++mm)
+#pragma unroll
+          for (int ct = 0; ct < CT; ++ct) ktr[mm][ct] = frag_cols_tr<DK>(Kt, kt * 32 + mm * 16, ct * 32, lane);
+      }
       __builtin_amdgcn_sched_barrier(0);
       f32x16 sT = s_init, dpT = dp_init;
 #pragma unroll
       for (int kk = 0; kk < KS; ++kk) {
-        sT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Kt, kt * 32, kk, lane), qf[kk], sT, 0, 0, 0);
-        dpT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Vt, kt * 32, kk, lane), dof[kk], dpT, 0, 0, 0);
+        if constexpr (PRE) {
+          sT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[kk], qf[kk], sT, 0, 0, 0);
+          dpT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[kk], dof[kk], dpT, 0, 0, 0);
+        } else {
+          sT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Kt, kt * 32, kk, lane), qf[kk], sT, 0, 0, 0);
+          dpT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Vt, kt * 32, kk, lane), dof[kk], dpT, 0, 0, 0);
+        }
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -467,7 +491,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct)
           dqT[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              frag_cols_tr<DK>(Kt, kt * 32 + mm * 16, ct * 32, lane), dsf, dqT[ct], 0, 0, 0);
+              PRE ? ktr[mm][PRE ? ct : 0] : frag_cols_tr<DK>(Kt, kt * 32 + mm * 16, ct * 32, lane), dsf, dqT[ct], 0, 0, 0);
       }
     }
   }
