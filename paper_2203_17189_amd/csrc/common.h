@@ -104,6 +104,17 @@ __device__ __forceinline__ int relpos_bucket_dev(int rp, const RelposLut& lut) {
 
 typedef __attribute__((address_space(3))) char lds_char;
 
+// Streaming (non-temporal) global accesses for data this kernel touches exactly once: outputs and
+// epilogue operands.  They should not push the operand panels that are being reused out of L2.
+__device__ __forceinline__ void st_stream(bf16x4* p, bf16x4 v) {
+  __builtin_nontemporal_store(__builtin_bit_cast(u32x2, v), reinterpret_cast<u32x2*>(p));
+}
+__device__ __forceinline__ void st_stream(f32x4* p, f32x4 v) { __builtin_nontemporal_store(v, p); }
+__device__ __forceinline__ bf16x4 ld_stream(const bf16x4* p) {
+  return __builtin_bit_cast(bf16x4, __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p)));
+}
+__device__ __forceinline__ f32x4 ld_stream(const f32x4* p) { return __builtin_nontemporal_load(p); }
+
 // Direct global -> LDS copy (global_load_lds_dwordx4).  64 lanes x 16 bytes: lane L fetches 16 bytes at
 // sbase + voff and they land at LDS address lds_addr + 16*L, so a wave fills 1 KB of contiguous LDS.
 // lds_addr and sbase are wave-uniform.  The compiler does not know that this writes LDS: callers

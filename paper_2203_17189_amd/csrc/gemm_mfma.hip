@@ -327,9 +327,9 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
               ab[q] = (bf16)(gl * ww[q]);
             }
             const size_t o = (size_t)(mh + rloc) * e.ld0 + f;
-            *reinterpret_cast<bf16x4*>((bf16*)e.out0 + o) = gpb;
-            *reinterpret_cast<bf16x4*>((bf16*)e.out1 + o) = glb;
-            *reinterpret_cast<bf16x4*>((bf16*)e.out2 + o) = ab;
+            st_stream(reinterpret_cast<bf16x4*>((bf16*)e.out0 + o), gpb);
+            st_stream(reinterpret_cast<bf16x4*>((bf16*)e.out1 + o), glb);
+            st_stream(reinterpret_cast<bf16x4*>((bf16*)e.out2 + o), ab);
           }
           asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
           __builtin_amdgcn_wave_barrier();
@@ -367,11 +367,11 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
             for (int q = 0; q < BT; ++q) {
               const size_t o = ob + (size_t)(q * RPI) * ld_aux;
               if constexpr (EPI == EPI_GEGLU_BWD) {
-                xa[set][q] = *reinterpret_cast<const bf16x4*>((const bf16*)e.aux0 + o);
-                xb[set][q] = *reinterpret_cast<const bf16x4*>((const bf16*)e.aux1 + o);
+                xa[set][q] = ld_stream(reinterpret_cast<const bf16x4*>((const bf16*)e.aux0 + o));
+                xb[set][q] = ld_stream(reinterpret_cast<const bf16x4*>((const bf16*)e.aux1 + o));
               } else {
-                if (aux_f32) xf[set][q] = *reinterpret_cast<const f32x4*>((const float*)e.aux0 + o);
-                else xa[set][q] = *reinterpret_cast<const bf16x4*>((const bf16*)e.aux0 + o);
+                if (aux_f32) xf[set][q] = ld_stream(reinterpret_cast<const f32x4*>((const float*)e.aux0 + o));
+                else xa[set][q] = ld_stream(reinterpret_cast<const bf16x4*>((const bf16*)e.aux0 + o));
               }
             }
           }
@@ -412,8 +412,8 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
                   du[qq] = (bf16)(v[qq] * (float)xa[set][q][qq]);
                   dw[qq] = (bf16)(v[qq] * (float)xb[set][q][qq]);
                 }
-                *reinterpret_cast<bf16x4*>((bf16*)e.out0 + o) = du;
-                *reinterpret_cast<bf16x4*>((bf16*)e.out1 + o) = dw;
+                st_stream(reinterpret_cast<bf16x4*>((bf16*)e.out0 + o), du);
+                st_stream(reinterpret_cast<bf16x4*>((bf16*)e.out1 + o), dw);
               } else {  // EPI_STORE, EPI_RESID
                 if constexpr (EPI == EPI_RESID) {
                   if (aux_f32) {
@@ -428,9 +428,9 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
                   bf16x4 ob;
 #pragma unroll
                   for (int qq = 0; qq < 4; ++qq) ob[qq] = (bf16)v[qq];
-                  *reinterpret_cast<bf16x4*>((bf16*)e.out0 + o) = ob;
+                  st_stream(reinterpret_cast<bf16x4*>((bf16*)e.out0 + o), ob);
                 } else {
-                  *reinterpret_cast<f32x4*>((float*)e.out0 + o) = v;
+                  st_stream(reinterpret_cast<f32x4*>((float*)e.out0 + o), v);
                 }
               }
             }

@@ -122,6 +122,29 @@ SMALL_BF16 = [
 ]
 
 
+def test_block_bf16_accumulate_flag():
+    # weight gradients are cleared once per backward unless accumulate is set; with it, a second
+    # backward adds its split-k partial sums on top of the first result
+    P = _P()
+    from parity_util import upload_case
+    cfg = SMALL_BF16[2]
+    w, x, dy = make_case(cfg)
+    dw, dx_in, ddy = upload_case(cfg, w, x, dy)
+    y, stash = P.t5_block_fwd(cfg, dx_in, dw)
+    _, g1 = P.t5_block_bwd(cfg, ddy, dx_in, dw, stash)
+    g2 = {k: v.clone() for k, v in g1.items()}
+    P.t5_block_bwd(cfg, ddy, dx_in, dw, stash, grads=g2, accumulate=True)
+    torch.cuda.synchronize()
+    twice = {k: to_np(v).copy() for k, v in g2.items()}
+    P.t5_block_bwd(cfg, ddy, dx_in, dw, stash, grads=g2)  # without the flag: overwrites
+    torch.cuda.synchronize()
+    for k in g1:
+        a1 = to_np(g1[k])
+        scale = np.abs(a1).max() + 1e-30
+        assert np.abs(twice[k] - 2 * a1).max() <= 4e-5 * scale, ("accumulate", k)
+        assert np.abs(to_np(g2[k]) - a1).max() <= 2e-5 * scale, ("overwrite", k)
+
+
 @pytest.mark.parametrize("cfg", SMALL_BF16, ids=[c.name for c in SMALL_BF16])
 def test_block_bf16_small(cfg):
     w, x, dy = make_case(cfg)
