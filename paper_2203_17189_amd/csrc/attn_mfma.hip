@@ -687,11 +687,6 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
   }
 }
 
-__global__ void zero_kernel(float* p, int64_t n) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = 0.f;
-}
-
 template <typename K>
 hipError_t set_lds(K kern, size_t bytes) {
   return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
@@ -714,8 +709,6 @@ hipError_t bwd_launch(const void* qkv, const void* c, const void* dc, const floa
   if (phase == 0) {
   const int64_t rows = (int64_t)a.B * a.S * a.H;
   attn_dvec_kernel<DK><<<ceil_div(rows * (DK / 8), 256), 256, 0, st>>>((const bf16*)c, (const bf16*)dc, dvec, a);
-  const int64_t nd = (int64_t)a.H * (2 * a.S - 1);
-  zero_kernel<<<ceil_div(nd, 256), 256, 0, st>>>(ddiag, nd);
   return hipGetLastError();
   }
   const dim3 grid((a.S / 128) * a.H * a.B);
@@ -756,7 +749,7 @@ size_t attn_bwd_mfma_scratch_bytes(const AttnDims&) { return 0; }
 hipError_t launch_attn_bwd_mfma(const void* qkv, const void* c, const void* dc, const float* diag,
                                 const float* lse, float* dvec, void* dqkv, float* ddiag, void*,
                                 const AttnDims& a, int far, int phase, hipStream_t st) {
-  // phase 0: dvec = rowsum(dO * O) and zeroed ddiag; phase 1: dq + bias-gradient diagonals; phase 2: dk, dv.
+  // phase 0: dvec = rowsum(dO * O); phase 1: dq + bias-gradient diagonals (added into ddiag); phase 2: dk, dv.
   // `far`: smallest distance that falls in the last (saturated) bucket; such offsets need no
   // per-diagonal resolution.  Never below 1, so offset 0 always takes the per-diagonal path.
   if (far < 1) far = 1;

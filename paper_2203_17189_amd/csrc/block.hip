@@ -249,8 +249,15 @@ int t5_block_fwd(const t5_block_cfg* cfg, const void* x, const t5_block_weights*
   T5_STEP("relpos_diag", launch_relpos_diag(w->rel_table, cfg->dtype, S.diag, D.S, D.H, lut, st));
   T5_STEP("rmsnorm_fwd", launch_rmsnorm_fwd(x, ty, w->ln1_scale, S.n1, ty, S.r1, T, D.d, cfg->rms_eps, st));
   if (fused) {
-    const void* qkv_src[3] = {w->wq, w->wk, w->wv};
-    T5_STEP("pack_weights", launch_pack_transpose_bf16(qkv_src, 3, D.d, D.I, W.wqkv_t, 0, st));
+    // all four weight packs (transposes to k-contiguous rows) in one launch
+    PackJobs pj;
+    std::memset(&pj, 0, sizeof(pj));
+    pj.j[0] = PackJob{{w->wq, w->wk, w->wv}, 3, D.d, D.I, 0, W.wqkv_t};
+    pj.j[1] = PackJob{{w->wo, nullptr, nullptr}, 1, D.I, D.d, 0, W.wo_t};
+    pj.j[2] = PackJob{{w->wi0, w->wi1, nullptr}, 2, D.d, D.F, 32, W.wi_t};
+    pj.j[3] = PackJob{{w->wo_ff, nullptr, nullptr}, 1, D.F, D.d, 0, W.woff_t};
+    pj.count = 4;
+    T5_STEP("pack_weights", launch_pack_transpose_multi(pj, st));
     GemmDesc g = gemm1(T, 3 * D.I, D.d, S.n1, D.d, 1, W.wqkv_t, D.d, 1, ty);
     T5_STEP("gemm_qkv", run_gemm(g, epi(EPI_STORE, S.qkv, 3 * D.I, ty), st));
   } else {
@@ -267,8 +274,6 @@ int t5_block_fwd(const t5_block_cfg* cfg, const void* x, const t5_block_weights*
   {  // h = x + c Wo  (float32 residual stream)
     GemmDesc g;
     if (fused) {
-      const void* src[1] = {w->wo};
-      T5_STEP("pack_weights", launch_pack_transpose_bf16(src, 1, D.I, D.d, W.wo_t, 0, st));
       g = gemm1(T, D.d, D.I, S.c, D.I, 1, W.wo_t, D.I, 1, ty);
     } else {
       g = gemm1(T, D.d, D.I, S.c, D.I, 1, w->wo, D.d, 0, ty);
@@ -279,8 +284,6 @@ int t5_block_fwd(const t5_block_cfg* cfg, const void* x, const t5_block_weights*
   }
   T5_STEP("rmsnorm_fwd", launch_rmsnorm_fwd(S.h, IN_F32, w->ln2_scale, S.n2, ty, S.r2, T, D.d, cfg->rms_eps, st));
   if (fused) {
-    const void* src[2] = {w->wi0, w->wi1};
-    T5_STEP("pack_weights", launch_pack_transpose_bf16(src, 2, D.d, D.F, W.wi_t, 32, st));
     GemmDesc g = gemm1(T, 2 * D.F, D.d, S.n2, D.d, 1, W.wi_t, D.d, 1, ty);
     GemmEpi e = epi(EPI_GEGLU_FWD, S.gp, D.F, ty);
     e.out1 = S.gl; e.out2 = S.a;
@@ -296,8 +299,6 @@ int t5_block_fwd(const t5_block_cfg* cfg, const void* x, const t5_block_weights*
   {  // y = h + a Wo_ff
     GemmDesc g;
     if (fused) {
-      const void* src[1] = {w->wo_ff};
-      T5_STEP("pack_weights", launch_pack_transpose_bf16(src, 1, D.F, D.d, W.woff_t, 0, st));
       g = gemm1(T, D.d, D.F, S.a, D.F, 1, W.woff_t, D.F, 1, ty);
     } else {
       g = gemm1(T, D.d, D.F, S.a, D.F, 1, w->wo_ff, D.d, 0, ty);
@@ -333,17 +334,23 @@ int t5_block_bwd(const t5_block_cfg* cfg, const void* dy, const void* x, const t
   const size_t es = D.es;
   const AttnDims ad{D.B, D.S, D.H, D.dk, cfg->causal ? 1 : 0, cfg->attn_scale};
 
-  if (!acc) {
-    // the weight-gradient GEMMs add split-k partial sums: clear all their outputs in one launch
+  const bool attn_mfma = ty == IN_BF16 && attn_mfma_supported(ad);
+  {
+    // One launch clears what later kernels add into: the weight gradients (split-k partial sums;
+    // kept when the caller accumulates) and the bias-gradient diagonals of the fused attention.
     ZeroList z;
     std::memset(&z, 0, sizeof(z));
-    float* ps[7] = {(float*)dw->wq, (float*)dw->wk, (float*)dw->wv, (float*)dw->wo, (float*)dw->wi0,
-                    (float*)dw->wi1, (float*)dw->wo_ff};
-    const int64_t ns[7] = {(int64_t)D.d * D.I, (int64_t)D.d * D.I, (int64_t)D.d * D.I, (int64_t)D.I * D.d,
-                           (int64_t)D.d * D.F, (int64_t)D.d * D.F, (int64_t)D.F * D.d};
-    for (int q = 0; q < 7; ++q) { z.p[q] = ps[q]; z.n[q] = ns[q]; }
-    z.count = 7;
-    T5_STEP("zero_grads", launch_zero_f32(z, st));
+    if (attn_mfma) {
+      z.p[z.count] = W.ddiag; z.n[z.count] = (int64_t)D.H * (2 * D.S - 1); ++z.count;
+    }
+    if (!acc) {
+      float* ps[7] = {(float*)dw->wq, (float*)dw->wk, (float*)dw->wv, (float*)dw->wo, (float*)dw->wi0,
+                      (float*)dw->wi1, (float*)dw->wo_ff};
+      const int64_t ns[7] = {(int64_t)D.d * D.I, (int64_t)D.d * D.I, (int64_t)D.d * D.I, (int64_t)D.I * D.d,
+                             (int64_t)D.d * D.F, (int64_t)D.d * D.F, (int64_t)D.F * D.d};
+      for (int q = 0; q < 7; ++q) { z.p[z.count] = ps[q]; z.n[z.count] = ns[q]; ++z.count; }
+    }
+    if (z.count > 0) T5_STEP("zero_grads", launch_zero_f32(z, st));
   }
   void* du_p = W.duw;
   void* dw_p = at(W.duw, (size_t)D.F, es);
@@ -386,7 +393,7 @@ int t5_block_bwd(const t5_block_cfg* cfg, const void* dy, const void* x, const t
     GemmDesc g = gemm1(T, D.I, D.d, dh_op, D.d, 1, w->wo, D.d, 1, ty);
     T5_STEP("gemm_dc", run_gemm(g, epi(EPI_STORE, W.dc, D.I, ty), st));
   }
-  if (ty == IN_BF16 && attn_mfma_supported(ad)) {
+  if (attn_mfma) {
     const int far = lut.n_thr > 0 ? lut.thr[lut.n_thr - 1] : lut.max_exact;
     T5_STEP("attn_bwd_prep", launch_attn_bwd_mfma(S.qkv, S.c, W.dc, S.diag, S.lse, W.dvec, W.dqkv, W.ddiag,
                                                   W.attn_scratch, ad, far, 0, st));

@@ -3,6 +3,7 @@
 // Also: the elementwise gated-GELU of the unfused path and the bf16 weight transpose-pack.
 #include "kernels.h"
 #include <algorithm>
+#include <cstring>
 
 namespace t5mi {
 
@@ -122,15 +123,15 @@ __global__ void geglu_fwd_kernel(T* __restrict__ u, T* __restrict__ w, T* __rest
   }
 }
 
-// dst[n][k] for a 32x32 tile staged through LDS; see launch_pack_transpose_bf16.
-struct PackSrcs {
-  const bf16* p[3];
-};
-__global__ __launch_bounds__(256) void pack_transpose_kernel(PackSrcs srcs, int nsrc, int K, int n_each,
-                                                            bf16* __restrict__ dst, int interleave) {
+// dst[n][k] for a 32x32 tile staged through LDS; see launch_pack_transpose_bf16.  blockIdx.z picks
+// the job; blocks outside a job's tile range leave at once.
+__global__ __launch_bounds__(256) void pack_transpose_kernel(PackJobs jobs) {
   __shared__ bf16 tile[32][33];
+  const PackJob& jb = jobs.j[blockIdx.z];
+  const int nsrc = jb.nsrc, K = jb.K, n_each = jb.n_each, interleave = jb.interleave;
   const int n_total = nsrc * n_each;
   const int n0 = blockIdx.x * 32, k0 = blockIdx.y * 32;
+  if (n0 >= n_total || k0 >= K) return;
   const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;  // 32 x 8
   // interleave and n_each are multiples of 32 (or interleave == 0), so a 32-wide tile of packed
   // rows comes from one source and 32 consecutive source columns.
@@ -142,7 +143,8 @@ __global__ __launch_bounds__(256) void pack_transpose_kernel(PackSrcs srcs, int 
     which = n0 / n_each;
     col0 = n0 % n_each;
   }
-  const bf16* src = srcs.p[which];
+  const bf16* src = (const bf16*)jb.src[which];
+  bf16* dst = (bf16*)jb.dst;
   for (int r = ty; r < 32; r += 8) {
     const int k = k0 + r;
     tile[r][tx] = (k < K && n0 + tx < n_total) ? src[(size_t)k * n_each + col0 + tx] : (bf16)0.f;
@@ -190,15 +192,30 @@ hipError_t launch_geglu_fwd(void* u, void* w, void* a, int type, int64_t n, hipS
   return hipGetLastError();
 }
 
+hipError_t launch_pack_transpose_multi(const PackJobs& jobs, hipStream_t st) {
+  if (jobs.count < 1 || jobs.count > 4) return hipErrorInvalidValue;
+  int gx = 0, gy = 0;
+  for (int q = 0; q < jobs.count; ++q) {
+    const PackJob& jb = jobs.j[q];
+    if (jb.nsrc < 1 || jb.nsrc > 3 || jb.n_each % 32 != 0 || (jb.interleave > 0 && jb.interleave % 32 != 0))
+      return hipErrorInvalidValue;
+    gx = std::max(gx, jb.nsrc * jb.n_each / 32);
+    gy = std::max(gy, ceil_div(jb.K, 32));
+  }
+  pack_transpose_kernel<<<dim3(gx, gy, jobs.count), 256, 0, st>>>(jobs);
+  return hipGetLastError();
+}
+
 hipError_t launch_pack_transpose_bf16(const void* const* srcs, int nsrc, int K, int n_each, void* dst,
                                       int interleave, hipStream_t st) {
-  if (nsrc < 1 || nsrc > 3 || n_each % 32 != 0 || (interleave > 0 && interleave % 32 != 0))
-    return hipErrorInvalidValue;
-  PackSrcs ps;
-  for (int i = 0; i < 3; ++i) ps.p[i] = (const bf16*)(i < nsrc ? srcs[i] : nullptr);
-  dim3 grid(nsrc * n_each / 32, ceil_div(K, 32));
-  pack_transpose_kernel<<<grid, 256, 0, st>>>(ps, nsrc, K, n_each, (bf16*)dst, interleave);
-  return hipGetLastError();
+  if (nsrc < 1 || nsrc > 3) return hipErrorInvalidValue;
+  PackJobs jobs;
+  std::memset(&jobs, 0, sizeof(jobs));
+  for (int i = 0; i < nsrc; ++i) jobs.j[0].src[i] = srcs[i];
+  jobs.j[0].nsrc = nsrc; jobs.j[0].K = K; jobs.j[0].n_each = n_each; jobs.j[0].interleave = interleave;
+  jobs.j[0].dst = dst;
+  jobs.count = 1;
+  return launch_pack_transpose_multi(jobs, st);
 }
 
 }  // namespace t5mi

@@ -76,7 +76,7 @@ bool gemm_mfma_supported(const GemmDesc& g, const GemmEpi& e);
 hipError_t launch_gemm_mfma(const GemmDesc& g, const GemmEpi& e, hipStream_t st);
 
 // Sets up to 8 float arrays to zero in one launch (the weight gradients, before the split-k GEMMs add
-// their partial sums into them).
+// their partial sums into them, and the bias-gradient diagonals).
 struct ZeroList {
   float* p[8];
   int64_t n[8];
@@ -89,6 +89,17 @@ hipError_t launch_zero_f32(const ZeroList& z, hipStream_t st);
 // (n / interleave) % nsrc and column (n / (interleave*nsrc)) * interleave + n % interleave.
 hipError_t launch_pack_transpose_bf16(const void* const* srcs, int nsrc, int K, int n_each, void* dst,
                                       int interleave, hipStream_t st);
+// Up to four such packs in one launch.
+struct PackJob {
+  const void* src[3];
+  int nsrc, K, n_each, interleave;
+  void* dst;
+};
+struct PackJobs {
+  PackJob j[4];
+  int count;
+};
+hipError_t launch_pack_transpose_multi(const PackJobs& jobs, hipStream_t st);
 
 // ------------------------------------------------------------------ elementwise gated GELU (simple path)
 // a = gelu(u) * w; then overwrites u with w * gelu'(u) and w with gelu(u) (the saved backward factors).
@@ -112,6 +123,8 @@ bool attn_mfma_supported(const AttnDims& a);
 hipError_t launch_attn_fwd_mfma(const void* qkv, const float* diag, void* c, float* lse, const AttnDims& a,
                                 hipStream_t st);
 size_t attn_bwd_mfma_scratch_bytes(const AttnDims& a);
+// phase 0: dvec = rowsum(dO * O); phase 1: dq and the bias-gradient diagonals, ADDED into ddiag (the
+// caller clears it); phase 2: dk, dv.
 hipError_t launch_attn_bwd_mfma(const void* qkv, const void* c, const void* dc, const float* diag,
                                 const float* lse, float* dvec, void* dqkv, float* ddiag, void* scratch,
                                 const AttnDims& a, int far, int phase, hipStream_t st);
