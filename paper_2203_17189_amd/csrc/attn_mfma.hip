@@ -147,6 +147,27 @@ __device__ __forceinline__ void fill_bias_slice(float* dg, const float* __restri
   }
 }
 
+// Registers R.. of a 32x32 ds sub-tile (S^T layout), each rotated across the 32 lanes of its half by
+// its key offset, summed into `tot`; `lo` gets the part whose source query did not wrap around
+// (lp = 31 - query index of the receiving lane).  The rotation amount must be an immediate.
+template <int R>
+__device__ __forceinline__ void diag_accum(const f32x16& ds, int lp, float& lo, float& tot) {
+  if constexpr (R < 16) {
+    constexpr int kj0 = ((R >> 2) << 3) + (R & 3);  // key offset of register R (without the half's + 4)
+    const float x = ds[R];  // (a plain float first: bit-casting the vector element itself picks element 0)
+    const float v = __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, x), 0xC000 | (kj0 << 5)));
+    lo += lp >= kj0 ? v : 0.f;
+    tot += v;
+    diag_accum<R + 1>(ds, lp, lo, tot);
+  }
+}
+
+// Number of 32-key blocks on each side of a wave's queries whose diagonals are resolved one by one in
+// the dq kernel: offsets up to far + 30 can fall into a sub-tile that is not entirely saturated.
+__host__ __device__ inline int attn_dq_window_blocks(int S, int far) {
+  const int nb = (far + 30) / 32, cap = S / 32 - 1;
+  return nb < cap ? nb : cap;
+}
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float sc_of(const AttnDims& a) { return a.scale * kLog2e; }
 
@@ -319,12 +340,17 @@ __global__ __launch_bounds__(256) void attn_dvec_kernel(const bf16* __restrict__
 // ------------------------------------------------------------------------------------------------
 // dq and the per-diagonal bias gradient.  Same ownership as the forward (lane = query).
 //
-// Bias gradient: ddiag[delta] = sum over (b, i) of ds[i, i + delta].  Each wave reduces the
-// diagonals of its 32x32 ds sub-tile through a private LDS staging block (plain stores, then lane t
-// sums diagonal t - 31) and adds them to a wave-private diagonal array with plain read-modify-write:
-// no LDS atomics.  Sub-tiles whose every offset lies in the saturated last bucket (|delta| >= far)
-// skip all that and add into one scalar per lane; it is credited to the outermost diagonal, which
-// is in the same bucket.
+// Bias gradient: ddiag[delta] = sum over (b, i) of ds[i, i + delta].  In the MFMA result layout a
+// register holds one key offset for 32 queries, i.e. 32 consecutive diagonals, and a different
+// register holds the same diagonals shifted by its key offset.  Rotating each register across the
+// 32 lanes by its key offset (ds_swizzle rotate mode: a crossbar permute, no LDS memory) lines the
+// diagonals up: after the rotation lane p holds, from every register, a value of diagonal slot
+// 31 - p or 63 - p of the sub-tile's 63 diagonals.  Each lane therefore owns two slots per
+// sub-tile, adds into them in a per-(wave, lane half) window in LDS with plain read-modify-write
+// (the owner of a window entry never changes, so no synchronisation until the final flush), and the
+// workgroup adds the eight windows up and issues one global atomic per diagonal.  Sub-tiles whose
+// every offset lies in the saturated last bucket (|delta| >= far) skip all that and add into one
+// scalar per lane; it is credited to the outermost diagonal, which is in the same bucket.
 // ------------------------------------------------------------------------------------------------
 template <int DK, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv,
@@ -334,12 +360,15 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __
                                                                const float* __restrict__ dvec,
                                                                bf16* __restrict__ dqkv, float* __restrict__ ddiag,
                                                                AttnDims a, int far) {
-  constexpr int BR = 128, BC = 64, KS = DK / 16, CT = DK / 32, DSP = 36;
+  constexpr int BR = 128, BC = 64, KS = DK / 16, CT = DK / 32;
   constexpr int TILE = BC * DK * 2, STG = 2 * TILE;  // a stage holds a K tile then a V tile
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  float* dst_all = reinterpret_cast<float*>(smem + 2 * STG);  // [4 waves][32][DSP] ds staging
-  float* dg = dst_all + 4 * 32 * DSP;                        // [S + BR - 1] bias, log2 units
-  float* ddg_all = dg + (a.S + BR - 1);                      // [4 waves][S + 31]
+  float* dg = reinterpret_cast<float*>(smem + 2 * STG);  // [S + BR - 1] bias, log2 units
+  // Diagonal windows [4 waves][2 lane halves][W].  A sub-tile at key offset j0s - i_w0 = 32 m from
+  // the wave's queries is resolved per diagonal for |m| <= nb; its slot u (0..62) lives at
+  // (m + nb) * 32 + u, which is diagonal delta = 32 m + u - 31 (+ 4 for the upper lane half).
+  const int nb = attn_dq_window_blocks(a.S, far), W = 32 * (2 * nb + 2);
+  float* ddg_all = dg + (a.S + BR - 1);
 
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -354,8 +383,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __
   const int i_loc = wave * 32 + i_lw;
   const int i = i0 + i_loc;
   const bf16* base = qkv + (size_t)b * S * ld + h * DK;
-  float* dsw = dst_all + wave * 32 * DSP;
-  float* ddgw = ddg_all + wave * (S + 31);  // ddgw[u], u = j - i_lw + 31
+  float* ddgw = ddg_all + (wave * 2 + g) * W + (31 - i_lw);  // this lane's first slot of block m = -nb
 
   bf16x8 qf[KS], dof[KS];
   {
@@ -381,7 +409,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __
   {
     const float* dgh = diag + (size_t)h * (2 * S - 1);
     fill_bias_slice(dg, dgh, S + BR - 1, tid, [&](int t) { return t - (i0 + BR - 1) + (S - 1); });
-    for (int t = tid; t < 4 * (S + 31); t += 256) ddg_all[t] = 0.f;
+    for (int t = tid; t < 8 * W; t += 256) ddg_all[t] = 0.f;
   }
   const float sc = a.scale * kLog2e;
   const int dg_base = BR - 1 - i_loc;
@@ -466,24 +494,11 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __
         for (int r = 0; r < 16; ++r) t += sT[r];
         far_pos += t;
       } else {
-#pragma unroll
-        for (int rq = 0; rq < 4; ++rq) {
-          f32x4 v = {sT[rq * 4], sT[rq * 4 + 1], sT[rq * 4 + 2], sT[rq * 4 + 3]};
-          *reinterpret_cast<f32x4*>(dsw + i_lw * DSP + rq * 8 + g * 4) = v;
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        // lane t < 63 owns diagonal key_local - query_local = t - 31
-        float t = 0.f;
-        const int dl = lane - 31;
-#pragma unroll
-        for (int q = 0; q < 32; ++q) {
-          const int kl = q + dl;
-          if (kl >= 0 && kl < 32) t += dsw[q * DSP + kl];
-        }
-        if (lane < 63) ddgw[j0s + lane] += t;
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
+        float lo = 0.f, tot = 0.f;
+        diag_accum<0>(sT, 31 - i_lw, lo, tot);
+        float* slot = ddgw + ((j0s - i_w0) / 32 + nb) * 32;
+        slot[0] += lo;
+        slot[32] += tot - lo;
       }
 #pragma unroll
       for (int mm = 0; mm < 2; ++mm) {
@@ -507,13 +522,21 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __
         *reinterpret_cast<bf16x4*>(qrow + ct * 32 + rq * 8 + g * 4) = o;
       }
   }
-  // ---- flush the wave-private diagonal sums: u = j - i_lw + 31  ->  delta = u - 31 - i_w0
+  // ---- flush: add the eight windows up (the upper lane half's diagonals sit 4 higher) and issue one
+  // global atomic per diagonal of this workgroup
   float* ddh = ddiag + (size_t)h * (2 * S - 1);
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  for (int u = lane; u < S + 31; u += 64) {
-    const float v = ddgw[u];
-    const int idx = u - 31 - i_w0 + (S - 1);
+  __syncthreads();
+  for (int t = tid; t < W + 4; t += 256) {
+    float v = 0.f;
+#pragma unroll
+    for (int wv = 0; wv < 4; ++wv) {
+      if (t < W) v += ddg_all[(wv * 2) * W + t];
+      if (t >= 4) v += ddg_all[(wv * 2 + 1) * W + t - 4];
+    }
+    // window entry t of wave wv: delta = t - 32 nb - 31 relative to that wave's first query, and
+    // the waves' first queries are 32 apart -- but so are their windows' origins (m counts from the
+    // wave's own queries), so the entry means the same diagonal for every wave
+    const int idx = t - 32 * nb - 31 + (S - 1);
     if (v != 0.f && idx >= 0 && idx < 2 * S - 1) unsafeAtomicAdd(&ddh[idx], v);
   }
   far_neg = wave_sum(far_neg);
@@ -687,6 +710,11 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
   }
 }
 
+size_t attn_bwd_dq_lds_bytes(const AttnDims& a, int far) {
+  const int W = 32 * (2 * attn_dq_window_blocks(a.S, far) + 2);
+  return (size_t)4 * 64 * a.dk * 2 + sizeof(float) * ((size_t)(a.S + 127) + 8 * (size_t)W);
+}
+
 template <typename K>
 hipError_t set_lds(K kern, size_t bytes) {
   return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
@@ -714,7 +742,7 @@ hipError_t bwd_launch(const void* qkv, const void* c, const void* dc, const floa
   const dim3 grid((a.S / 128) * a.H * a.B);
   if (phase == 1) {
     auto kern = attn_bwd_dq_mfma_kernel<DK, CAUSAL>;
-    const size_t lds = 4 * 64 * DK * 2 + sizeof(float) * (4 * 32 * 36 + (a.S + 127) + 4 * (a.S + 31));
+    const size_t lds = attn_bwd_dq_lds_bytes(a, far);
     if ((e = set_lds(kern, lds)) != hipSuccess) return e;
     kern<<<grid, 256, lds, st>>>((const bf16*)qkv, (const bf16*)dc, diag, lse, dvec, (bf16*)dqkv, ddiag, a, far);
     if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -730,6 +758,11 @@ hipError_t bwd_launch(const void* qkv, const void* c, const void* dc, const floa
 }
 
 }  // namespace
+
+bool attn_bwd_mfma_fits(const AttnDims& a, int far) {
+  // the dq kernel keeps per-diagonal windows of about 2 * far entries in LDS
+  return attn_bwd_dq_lds_bytes(a, far < 1 ? 1 : far) <= (size_t)150 * 1024;
+}
 
 bool attn_mfma_supported(const AttnDims& a) {
   // S % 128: query/key tiles of 128 without ragged edges; LDS holds the diagonal slice (S + 127 floats)

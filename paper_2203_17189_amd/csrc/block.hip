@@ -334,7 +334,8 @@ int t5_block_bwd(const t5_block_cfg* cfg, const void* dy, const void* x, const t
   const size_t es = D.es;
   const AttnDims ad{D.B, D.S, D.H, D.dk, cfg->causal ? 1 : 0, cfg->attn_scale};
 
-  const bool attn_mfma = ty == IN_BF16 && attn_mfma_supported(ad);
+  const int far = lut.n_thr > 0 ? lut.thr[lut.n_thr - 1] : lut.max_exact;
+  const bool attn_mfma = ty == IN_BF16 && attn_mfma_supported(ad) && attn_bwd_mfma_fits(ad, far);
   {
     // One launch clears what later kernels add into: the weight gradients (split-k partial sums;
     // kept when the caller accumulates) and the bias-gradient diagonals of the fused attention.
@@ -394,7 +395,6 @@ int t5_block_bwd(const t5_block_cfg* cfg, const void* dy, const void* x, const t
     T5_STEP("gemm_dc", run_gemm(g, epi(EPI_STORE, W.dc, D.I, ty), st));
   }
   if (attn_mfma) {
-    const int far = lut.n_thr > 0 ? lut.thr[lut.n_thr - 1] : lut.max_exact;
     T5_STEP("attn_bwd_prep", launch_attn_bwd_mfma(S.qkv, S.c, W.dc, S.diag, S.lse, W.dvec, W.dqkv, W.ddiag,
                                                   W.attn_scratch, ad, far, 0, st));
     T5_STEP("attn_bwd_dq", launch_attn_bwd_mfma(S.qkv, S.c, W.dc, S.diag, S.lse, W.dvec, W.dqkv, W.ddiag,

@@ -123,6 +123,9 @@ bool attn_mfma_supported(const AttnDims& a);
 hipError_t launch_attn_fwd_mfma(const void* qkv, const float* diag, void* c, float* lse, const AttnDims& a,
                                 hipStream_t st);
 size_t attn_bwd_mfma_scratch_bytes(const AttnDims& a);
+// Whether the backward kernels take this problem with `far` (smallest distance in the saturated last
+// bucket); otherwise the simple backward is used (same saved tensors).
+bool attn_bwd_mfma_fits(const AttnDims& a, int far);
 // phase 0: dvec = rowsum(dO * O); phase 1: dq and the bias-gradient diagonals, ADDED into ddiag (the
 // caller clears it); phase 2: dk, dv.
 hipError_t launch_attn_bwd_mfma(const void* qkv, const void* c, const void* dc, const float* diag,
