@@ -169,7 +169,6 @@ __host__ __device__ inline int attn_dq_window_blocks(int S, int far) {
   return nb < cap ? nb : cap;
 }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-__device__ __forceinline__ float sc_of(const AttnDims& a) { return a.scale * kLog2e; }
 
 // ------------------------------------------------------------------------------------------------
 // Forward.  grid (ceil(S/128), H, B), 256 threads; wave w owns queries i0 + 32w + lane%32.
@@ -353,7 +352,7 @@ __global__ __launch_bounds__(256) void attn_dvec_kernel(const bf16* __restrict__
 // scalar per lane; it is credited to the outermost diagonal, which is in the same bucket.
 // ------------------------------------------------------------------------------------------------
 template <int DK, bool CAUSAL>
-__global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv,
+__global__ __launch_bounds__(256, DK == 64 ? 3 : 2) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv,
                                                                const bf16* __restrict__ dout,
                                                                const float* __restrict__ diag,
                                                                const float* __restrict__ lse,
@@ -396,16 +395,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __
     }
   }
   const size_t srow = ((size_t)b * a.H + h) * S + i;
-  // The score and dP accumulators start from -lse/scale and -dvec (loop-invariant register
-  // vectors), so that the MFMA results are already (s - lse/scale) and (dP - dvec).
-  // (With 128 channels the register budget has no room for the two seed vectors: the subtraction
-  // is done after the MFMAs there.)
-  constexpr bool SEED = DK == 64;
-  const float nl = -lse[srow] / a.scale, nd = -dvec[srow];
-  f32x16 s_init, dp_init;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) { s_init[r] = SEED ? nl : 0.f; dp_init[r] = SEED ? nd : 0.f; }
-  const float nl2 = SEED ? 0.f : nl * sc_of(a), nd2 = SEED ? 0.f : nd;
+  const float nlse2 = -lse[srow] * kLog2e, ndv = -dvec[srow];
   {
     const float* dgh = diag + (size_t)h * (2 * S - 1);
     fill_bias_slice(dg, dgh, S + BR - 1, tid, [&](int t) { return t - (i0 + BR - 1) + (S - 1); });
@@ -441,46 +431,28 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __
     for (int kt = 0; kt < BC / 32; ++kt) {
       const int j0s = j0 + kt * 32;
       if (CAUSAL && j0s > i_w0 + 31) continue;  // whole sub-tile masked for this wave
-      // All LDS operands of the sub-tile are requested up front (K and V rows for S and dP, the bias
-      // values, the transposed K operand of the dq update) and the scheduler may not sink them: read
-      // just in time, every MFMA waits out an LDS round trip.
-      // (With 128 channels the operands do not fit the register budget; only the bias goes first.)
-      constexpr bool PRE = DK == 64;
-      bf16x8 kfr[PRE ? KS : 1], vfr[PRE ? KS : 1], ktr[2][PRE ? CT : 1];
+      // The bias values are requested before the MFMAs (and the scheduler may not sink them): read at
+      // first use, each one stalls the softmax arithmetic for an LDS round trip.  Prefetching the
+      // MFMA operands as well, or seeding the accumulators with -lse and -dvec, costs more registers
+      // than the third wave per SIMD they displace is worth (measured).
       float bias[16];
-      if constexpr (PRE) {
-#pragma unroll
-        for (int kk = 0; kk < KS; ++kk) {
-          kfr[kk] = frag_rows<DK>(Kt, kt * 32, kk, lane);
-          vfr[kk] = frag_rows<DK>(Vt, kt * 32, kk, lane);
-        }
-      }
 #pragma unroll
       for (int r = 0; r < 16; ++r) bias[r] = dg[dg_base + j0s + ((r >> 2) << 3) + (g << 2) + (r & 3)];
-      if constexpr (PRE) {
-#pragma unroll
-        for (int mm = 0; mm < 2; ++mm)
-#pragma unroll
-          for (int ct = 0; ct < CT; ++ct) ktr[mm][ct] = frag_cols_tr<DK>(Kt, kt * 32 + mm * 16, ct * 32, lane);
-      }
       __builtin_amdgcn_sched_barrier(0);
-      f32x16 sT = s_init, dpT = dp_init;
+      f32x16 sT, dpT;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sT[r] = 0.f; dpT[r] = 0.f; }
 #pragma unroll
       for (int kk = 0; kk < KS; ++kk) {
-        if constexpr (PRE) {
-          sT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[kk], qf[kk], sT, 0, 0, 0);
-          dpT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[kk], dof[kk], dpT, 0, 0, 0);
-        } else {
-          sT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Kt, kt * 32, kk, lane), qf[kk], sT, 0, 0, 0);
-          dpT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Vt, kt * 32, kk, lane), dof[kk], dpT, 0, 0, 0);
-        }
+        sT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Kt, kt * 32, kk, lane), qf[kk], sT, 0, 0, 0);
+        dpT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Vt, kt * 32, kk, lane), dof[kk], dpT, 0, 0, 0);
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int j = j0s + ((r >> 2) << 3) + (g << 2) + (r & 3);
-        float p = fast_exp2(SEED ? fmaf(sT[r], sc, bias[r]) : fmaf(sT[r], sc, bias[r]) + nl2);
+        float p = fast_exp2(fmaf(sT[r], sc, bias[r]) + nlse2);
         if (CAUSAL && j > i) p = 0.f;
-        sT[r] = p * (SEED ? dpT[r] : dpT[r] + nd2);
+        sT[r] = p * (dpT[r] + ndv);
       }
       // ---- bias gradient of this 32x32 sub-tile (wave-uniform branches)
       if (j0s + 31 - i_w0 <= -far) {
@@ -506,7 +478,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct)
           dqT[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              PRE ? ktr[mm][PRE ? ct : 0] : frag_cols_tr<DK>(Kt, kt * 32 + mm * 16, ct * 32, lane), dsf, dqT[ct], 0, 0, 0);
+              frag_cols_tr<DK>(Kt, kt * 32 + mm * 16, ct * 32, lane), dsf, dqT[ct], 0, 0, 0);
       }
     }
   }
