@@ -119,6 +119,15 @@ SMALL_BF16 = [
                    attn_scale=64 ** -0.5),
     SI.BlockConfig("bf16_ragged", 32, batch=1, seq=100, d_model=72, n_heads=3, d_kv=24, d_ff=136,
                    attn_scale=24 ** -0.5),
+    # other bucket tables: the saturated bucket starts at a small offset (narrow per-diagonal window in
+    # the dq kernel, most sub-tiles take the scalar path) or beyond the sequence (every sub-tile is
+    # resolved per diagonal)
+    SI.BlockConfig("bf16_enc_b8_d20", 37, batch=1, seq=512, d_model=128, n_heads=2, d_kv=64, d_ff=128,
+                   num_buckets=8, max_distance=20, attn_scale=64 ** -0.5),
+    SI.BlockConfig("bf16_dec_b8_d20", 38, batch=1, seq=384, d_model=128, n_heads=2, d_kv=64, d_ff=128, causal=True,
+                   num_buckets=8, max_distance=20, attn_scale=64 ** -0.5),
+    SI.BlockConfig("bf16_enc_b64_d1000", 39, batch=1, seq=384, d_model=128, n_heads=2, d_kv=64, d_ff=128,
+                   num_buckets=64, max_distance=1000, attn_scale=64 ** -0.5),
 ]
 
 
