@@ -4,8 +4,8 @@
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2_small|c3_base|c4_gpt_causal|c5_xl]
 
 Prints ONE JSON line.  A "step" is one pass of the whole hot path over one batch of seeded
-synthetic input already resident in HBM: t5_block_fwd + t5_block_bwd, plus adafactor_step on every
-block weight for the workloads that include the optimizer.  `value` is tokens/s of that step.
+synthetic input already resident in HBM: t5_block_fwd + t5_block_bwd, plus adafactor_step_multi over the
+block weights for the workloads that include the optimizer.  `value` is tokens/s of that step.
 `roofline` describes the step's dominant kernel, timed with HIP events on the launch stream in a
 second, instrumented pass over the same work; `cpu_baseline` is the float64 oracle timed on the host
 cores on a bounded sample (fewer sequences, same shapes).
@@ -127,9 +127,10 @@ def main() -> int:
             fact = master.dim() == 2 and name != "rel_table"
             opt[name] = dict(master=master, fact=fact,
                              vr=torch.zeros(rows, device=dev), vc=torch.zeros(cols, device=dev),
-                             vf=None if fact else torch.zeros(rows, cols, device=dev),
-                             ws=torch.empty(max(P.adafactor_workspace_bytes(rows, cols, fact), 256),
-                                            dtype=torch.uint8, device=dev))
+                             vf=None if fact else torch.zeros(rows, cols, device=dev))
+        opt_tensors = [dict(param=o["master"], grad=grads[name], factored=o["fact"], v_row=o["vr"], v_col=o["vc"],
+                            v_full=o["vf"], bf16_copy_out=w[name]) for name, o in opt.items()]
+        opt_ws = torch.empty(max(P.adafactor_multi_workspace_bytes(opt_tensors), 256), dtype=torch.uint8, device=dev)
 
     step_no = [0]
 
@@ -138,10 +139,7 @@ def main() -> int:
         P.t5_block_bwd(cfg, dy, x, w, stash, dx=dx, grads=grads, workspace=ws)
         if opt is not None:
             step_no[0] += 1
-            for name, o in opt.items():
-                P.adafactor_step(o["master"], grads[name], step=step_no[0], lr=1e-2, factored=o["fact"],
-                                 v_row=o["vr"], v_col=o["vc"], v_full=o["vf"], bf16_copy_out=w[name],
-                                 workspace=o["ws"])
+            P.adafactor_step_multi(opt_tensors, step=step_no[0], lr=1e-2, workspace=opt_ws)
 
     for _ in range(args.warmup):
         step()
@@ -165,6 +163,40 @@ def main() -> int:
     P.t5_step_timing_enable(False)
     flops = gemm_step_flops(cfg)
     per_kernel = {k: {"avg_ms": v[0] / v[1], "launches_per_step": v[1] / n_prof} for k, v in timing.items()}
+    step_ms = {k: v["avg_ms"] * v["launches_per_step"] for k, v in per_kernel.items()}
+    fwd_names = {"relpos_diag", "rmsnorm_fwd", "pack_weights", "gemm_qkv", "attn_fwd", "gemm_o", "gemm_wi_geglu",
+                 "gemm_wi", "geglu_fwd", "gemm_wo"}
+    phase_ms = {"fwd_ms": round(sum(v for k, v in step_ms.items() if k in fwd_names), 4),
+                "bwd_ms": round(sum(v for k, v in step_ms.items() if k not in fwd_names and k != "adafactor"), 4),
+                "adafactor_ms": round(step_ms.get("adafactor", 0.0), 4)}
+    # HBM-bound steps: algorithmic bytes per step (2-byte activations; Adafactor: read G, read W, write W
+    # in float32 plus the refreshed bf16 copy)
+    Tn, dn_ = cfg.tokens, cfg.d_model
+    n_params = sum(int(v.numel()) for v in w.values())
+    hbm_bytes = {"rmsnorm_fwd": 2 * (2.0 * Tn * dn_ * 2 + 4.0 * Tn), "rmsnorm_bwd": 2 * (4.0 * Tn * dn_ * 2),
+                 "adafactor": 14.0 * n_params}
+
+    # ---- what this machine sustains with nothing in the way (context for the fractions below)
+    sink = torch.zeros(256, dtype=torch.float32, device=dev)
+    machine = {}
+    for label, rnd in (("mfma_loop_const_operands_tflops", False), ("mfma_loop_random_operands_tflops", True)):
+        P.t5_mfma_peak_probe(1024, 2000, rnd, sink)
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fl = P.t5_mfma_peak_probe(1024, 4000, rnd, sink)
+        e1.record(); torch.cuda.synchronize()
+        machine[label] = round(fl / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+    src = torch.empty(1 << 29, dtype=torch.uint8, device=dev).zero_()
+    dst = torch.empty_like(src)
+    dst.copy_(src); torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    e1.record(); torch.cuda.synchronize()
+    machine["copy_read_plus_write_gbs"] = round(5 * 2.0 * (1 << 29) / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+    del src, dst
     mfma_steps = {k: v for k, v in per_kernel.items() if k in flops}
     dom = max(mfma_steps, key=lambda k: mfma_steps[k]["avg_ms"] * mfma_steps[k]["launches_per_step"])
     dom_tflops = flops[dom] / (per_kernel[dom]["avg_ms"] * 1e-3) / 1e12
@@ -183,10 +215,17 @@ def main() -> int:
                 "unit": "TFLOP/s", "frac": round(dom_tflops / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
                 "traffic_unit": "HBM bytes per launch (read + write)", "traffic_detail": traffic_detail,
                 "avg_ms": round(per_kernel[dom]["avg_ms"], 4), "flop_per_launch": flops[dom]}
+    roofline["frac_of_measured_mfma_loop"] = round(dom_tflops / machine["mfma_loop_random_operands_tflops"], 4)
     for k, v in per_kernel.items():
+        if k in flops and v["avg_ms"] > 0:
+            v["tflops"] = round(flops[k] / (v["avg_ms"] * 1e-3) / 1e12, 1)
+            v["bound"] = "mfma"
+            v["frac"] = round(v["tflops"] / PEAK_BF16_TFLOPS, 4)
+        elif k in hbm_bytes and step_ms[k] > 0:
+            v["gbs"] = round(hbm_bytes[k] / (step_ms[k] * 1e-3) / 1e9, 1)
+            v["bound"] = "hbm"
+            v["frac"] = round(v["gbs"] / PEAK_HBM_GBS, 4)
         v["avg_ms"] = round(v["avg_ms"], 4)
-        if k in flops:
-            v["tflops"] = round(flops[k] / (v["avg_ms"] * 1e-3) / 1e12, 1) if v["avg_ms"] > 0 else None
 
     out = {
         "metric": "T5 block fwd+bwd tokens/s and TFLOP/s (bf16) + % MFMA peak, 1 MI355X",
@@ -197,7 +236,7 @@ def main() -> int:
                    "n_heads": cfg.n_heads, "d_kv": cfg.d_kv, "d_ff": cfg.d_ff, "causal": cfg.causal,
                    "adafactor": cfg.adafactor, "passes": "fwd+bwd" + ("+adafactor" if cfg.adafactor else "")},
         "model_tflops": round(model_tflops, 2), "frac_of_mfma_peak": round(model_tflops / PEAK_BF16_TFLOPS, 4),
-        "roofline": roofline, "per_kernel": per_kernel,
+        "roofline": roofline, **phase_ms, "machine": machine, "per_kernel": per_kernel,
     }
     if not args.no_cpu_baseline:
         sb = args.cpu_sample_batch

@@ -143,6 +143,27 @@ int adafactor_step(float* param, const float* grad, float* v_row, float* v_col, 
                    int64_t rows, int64_t cols, int factored, const adafactor_cfg* cfg,
                    void* bf16_copy_out, void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same update for several tensors at once (the ten parameter tensors of a block): one sequence
+ * of five launches for the whole set instead of five per tensor, which is what the step costs at
+ * T5.1.1-Small/Base sizes.  Each entry is what adafactor_step takes for one tensor; every tensor
+ * gets the same cfg (paper Sec. 4 trains all parameters with one optimizer setting).  workspace: at
+ * least adafactor_multi_workspace_bytes() (the per-tensor workspaces back to back).  Results are
+ * identical to calling adafactor_step per tensor.
+ * Errors: as adafactor_step; n_tensors < 1 -> T5_ERR_SHAPE, > 16 -> T5_ERR_UNSUPPORTED. */
+typedef struct {
+  float* param;
+  const float* grad;
+  float* v_row;  /* [rows] if factored */
+  float* v_col;  /* [cols] if factored */
+  float* v_full; /* [rows, cols] if not factored */
+  int64_t rows, cols;
+  int32_t factored;
+  void* bf16_copy_out; /* nullable */
+} adafactor_tensor;
+size_t adafactor_multi_workspace_bytes(const adafactor_tensor* tensors, int n_tensors);
+int adafactor_step_multi(const adafactor_tensor* tensors, int n_tensors, const adafactor_cfg* cfg,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
 /* Building block of the block's projections (paper Sec. 4 models are stacks of such matmuls):
  * C[m,n] = sum_k A(m,k) B(n,k), bf16 operands, float32 accumulation on the MFMA units, float32 C
  * [M, ldc].  a_kc != 0: A(m,k) = A[m*lda + k], else A[k*lda + m]; b_kc likewise for B(n,k).
@@ -159,6 +180,14 @@ int t5_gemm_bf16(const void* A, const void* B, float* C, int M, int N, int K, in
  * return value is the number of steps recorded.  Name pointers stay valid for the process. */
 void t5_step_timing_enable(int enable);
 int t5_step_timing_read(const char** names, float* ms, int* calls, int cap);
+
+/* Measurement aid for the roofline report: `workgroups` workgroups of 4 waves each issue
+ * iters * 32 v_mfma_f32_32x32x16_bf16 per wave on register operands (no LDS, no memory traffic):
+ * 2 * 32*32*16 FLOP per instruction.  random_operands != 0 fills the operands with pseudo-random
+ * bf16 values instead of ones: the rate then shows the clock the part sustains under the switching
+ * activity of real data.  sink: device buffer of >= 256 floats (practically never written).  The
+ * caller times it.  Errors: sizes < 1 -> T5_ERR_SHAPE, NULL -> T5_ERR_NULL. */
+int t5_mfma_peak_probe(int workgroups, int iters, int random_operands, float* sink, void* stream);
 
 const char* t5_status_string(int status);
 

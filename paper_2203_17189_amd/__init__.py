@@ -7,6 +7,8 @@ from .binding import (  # noqa: F401
     T5Error,
     WEIGHT_NAMES,
     adafactor_step,
+    adafactor_step_multi,
+    adafactor_multi_workspace_bytes,
     adafactor_workspace_bytes,
     lib,
     lib_path,
@@ -15,6 +17,7 @@ from .binding import (  # noqa: F401
     t5_block_stash_bytes,
     t5_block_workspace_bytes,
     t5_gemm_bf16,
+    t5_mfma_peak_probe,
     t5_relpos_bucket,
     t5_step_timing_enable,
     t5_step_timing_read,

@@ -34,6 +34,12 @@ class _Grads(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in WEIGHT_NAMES]
 
 
+class _AfTensor(C.Structure):
+    _fields_ = [("param", C.c_void_p), ("grad", C.c_void_p), ("v_row", C.c_void_p), ("v_col", C.c_void_p),
+                ("v_full", C.c_void_p), ("rows", C.c_int64), ("cols", C.c_int64), ("factored", C.c_int32),
+                ("bf16_copy_out", C.c_void_p)]
+
+
 class _AfCfg(C.Structure):
     _fields_ = [("lr", C.c_float), ("decay_pow", C.c_float), ("eps1", C.c_float), ("eps2", C.c_float),
                 ("clip", C.c_float), ("scale_by_param", C.c_int32), ("step", C.c_int32)]
@@ -71,10 +77,16 @@ def lib() -> C.CDLL:
     L.adafactor_workspace_bytes.argtypes = [i64, i64, i32]
     L.adafactor_step.restype = i32
     L.adafactor_step.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, C.POINTER(_AfCfg), vp, vp, sz, vp]
+    L.adafactor_multi_workspace_bytes.restype = sz
+    L.adafactor_multi_workspace_bytes.argtypes = [C.POINTER(_AfTensor), i32]
+    L.adafactor_step_multi.restype = i32
+    L.adafactor_step_multi.argtypes = [C.POINTER(_AfTensor), i32, C.POINTER(_AfCfg), vp, sz, vp]
     L.t5_gemm_bf16.restype = i32
     L.t5_gemm_bf16.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp]
     L.t5_step_timing_enable.restype = None
     L.t5_step_timing_enable.argtypes = [i32]
+    L.t5_mfma_peak_probe.restype = i32
+    L.t5_mfma_peak_probe.argtypes = [i32, i32, i32, vp, vp]
     L.t5_step_timing_read.restype = i32
     L.t5_step_timing_read.argtypes = [C.POINTER(C.c_char_p), C.POINTER(C.c_float), C.POINTER(i32), i32]
     _LIB = L
@@ -226,6 +238,48 @@ def adafactor_step(param, grad, *, step, lr, factored, v_row=None, v_col=None, v
     return param
 
 
+def _af_tensor_array(tensors):
+    """tensors: list of dicts with param, grad, factored and v_row/v_col or v_full (+ bf16_copy_out)."""
+    arr = (_AfTensor * len(tensors))()
+    for i, t in enumerate(tensors):
+        p = t["param"]
+        rows, cols = (p.shape[0], p.numel() // p.shape[0]) if p.dim() >= 2 else (1, p.numel())
+        fact = bool(t["factored"])
+        _check_tensor(p, torch.float32, rows * cols, "param")
+        _check_tensor(t["grad"], torch.float32, rows * cols, "grad")
+        if fact:
+            _check_tensor(t["v_row"], torch.float32, rows, "v_row")
+            _check_tensor(t["v_col"], torch.float32, cols, "v_col")
+        else:
+            _check_tensor(t["v_full"], torch.float32, rows * cols, "v_full")
+        lp = t.get("bf16_copy_out")
+        if lp is not None:
+            _check_tensor(lp, torch.bfloat16, rows * cols, "bf16_copy_out")
+        addr = lambda x: None if x is None else x.data_ptr()
+        arr[i] = _AfTensor(addr(p), addr(t["grad"]), addr(t.get("v_row")) if fact else None,
+                           addr(t.get("v_col")) if fact else None, None if fact else addr(t.get("v_full")),
+                           rows, cols, int(fact), addr(lp))
+    return arr
+
+
+def adafactor_multi_workspace_bytes(tensors) -> int:
+    arr = _af_tensor_array(tensors)
+    return int(lib().adafactor_multi_workspace_bytes(arr, len(tensors)))
+
+
+def adafactor_step_multi(tensors, *, step, lr, decay_pow=0.8, eps1=1e-30, eps2=1e-3, clip=1.0,
+                         scale_by_param=True, workspace=None):
+    """In-place Adafactor update of several float32 tensors in one sequence of launches."""
+    arr = _af_tensor_array(tensors)
+    if workspace is None:
+        workspace = _byte_buffer(max(int(lib().adafactor_multi_workspace_bytes(arr, len(tensors))), 256),
+                                 tensors[0]["param"].device)
+    cfg = _AfCfg(lr, decay_pow, eps1, eps2, clip, int(bool(scale_by_param)), int(step))
+    rc = lib().adafactor_step_multi(arr, len(tensors), C.byref(cfg), _ptr(workspace), workspace.numel(), _stream())
+    if rc:
+        raise T5Error(rc, "adafactor_step_multi")
+
+
 def t5_gemm_bf16(a: torch.Tensor, b: torch.Tensor, a_kc: bool, b_kc: bool, out: torch.Tensor | None = None):
     """C[m,n] = sum_k A(m,k) B(n,k) in float32.  a: [M,K] if a_kc else [K,M]; b: [N,K] if b_kc else [K,N]."""
     for t, nme in ((a, "a"), (b, "b")):
@@ -243,6 +297,15 @@ def t5_gemm_bf16(a: torch.Tensor, b: torch.Tensor, a_kc: bool, b_kc: bool, out: 
 
 def t5_step_timing_enable(enable: bool) -> None:
     lib().t5_step_timing_enable(int(bool(enable)))
+
+
+def t5_mfma_peak_probe(workgroups: int, iters: int, random_operands: bool, sink: torch.Tensor) -> float:
+    """Launches the register-only MFMA loop; returns the FLOPs it performs (the caller times it)."""
+    _check_tensor(sink, torch.float32, 256, "sink")
+    rc = lib().t5_mfma_peak_probe(int(workgroups), int(iters), int(bool(random_operands)), _ptr(sink), _stream())
+    if rc:
+        raise T5Error(rc, "t5_mfma_peak_probe")
+    return float(workgroups) * 4 * iters * 32 * 2.0 * 32 * 32 * 16
 
 
 def t5_step_timing_read(cap: int = 64) -> dict:

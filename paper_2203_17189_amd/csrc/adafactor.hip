@@ -8,7 +8,14 @@
 //   coef      : coef = lr * max(eps2, RMS(W)) / max(1, RMS(U)/clip)
 //   apply     : W -= coef * U   (+ optional bf16 copy)
 // Unfactored tensors use the same skeleton with v_full updated elementwise in the first pass.
+//
+// Every kernel works on a batch of up to 16 tensors at once (descriptor table passed by value, a
+// workgroup finds its tensor from a prefix table of tile counts): a whole block's optimizer step is
+// five launches, not five per tensor -- at T5.1.1-Base sizes the per-tensor launches cost more than
+// the memory traffic.
 #include "kernels.h"
+#include <cmath>
+#include <cstring>
 
 namespace t5mi {
 
@@ -49,14 +56,40 @@ __device__ __forceinline__ void stv(float* __restrict__ p, const float (&v)[VEC]
   }
 }
 
-// grid (ntc, ntr), 256 threads.  Wave w takes rows w, w+4, ... of the tile; lanes span the columns.
+struct AfItem {
+  float* w;
+  const float* g;
+  float* v_row;
+  float* v_col;
+  float* v_full;
+  bf16* lp;
+  int64_t R, C;
+  AfWs ws;
+  int vec, ntc, ntr, factored;
+};
+struct AfBatch {
+  AfItem it[AF_MAX_TENSORS];
+  int tile_start[AF_MAX_TENSORS + 1];  // prefix sums of ntc * ntr
+  int fin_start[AF_MAX_TENSORS + 1];   // prefix sums of ceil((R + C) / 256) over factored tensors
+  int count;
+  float beta2, eps1;
+};
+
+// Tensor that owns 1-D block `b` under prefix table `start` (wave-uniform).
+__device__ __forceinline__ int af_find(const int* start, int count, int b) {
+  int t = 0;
+  while (t + 1 < count && b >= start[t + 1]) ++t;
+  return t;
+}
+
+// Wave w takes rows w, w+4, ... of the tile; lanes span the columns.
 template <int VEC>
-__global__ __launch_bounds__(256) void af_stats_kernel(const float* __restrict__ g, int64_t R, int64_t C,
-                                                       AfWs ws) {
-  __shared__ float colred[4][64 * VEC];
+__device__ __forceinline__ void af_stats_tile(const AfItem& it, int bx, int by, float (*colred)[256]) {
+  const float* __restrict__ g = it.g;
+  const int64_t R = it.R, C = it.C;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t c0 = (int64_t)blockIdx.x * 64 * VEC + lane * VEC;
-  const int64_t r0 = (int64_t)blockIdx.y * TR;
+  const int64_t c0 = (int64_t)bx * 64 * VEC + lane * VEC;
+  const int64_t r0 = (int64_t)by * TR;
   float csum[VEC];
 #pragma unroll
   for (int i = 0; i < VEC; ++i) csum[i] = 0.f;
@@ -75,34 +108,48 @@ __global__ __launch_bounds__(256) void af_stats_kernel(const float* __restrict__
       }
     }
     rs = wave_sum(rs);
-    if (lane == 0) ws.rowpart[(int64_t)blockIdx.x * R + r] = rs;
+    if (lane == 0) it.ws.rowpart[(int64_t)bx * R + r] = rs;
   }
 #pragma unroll
   for (int i = 0; i < VEC; ++i) colred[wave][lane * VEC + i] = csum[i];
   __syncthreads();
   for (int t = threadIdx.x; t < 64 * VEC; t += 256) {
-    const int64_t c = (int64_t)blockIdx.x * 64 * VEC + t;
-    if (c < C) ws.colpart[(int64_t)blockIdx.y * C + c] = colred[0][t] + colred[1][t] + colred[2][t] + colred[3][t];
+    const int64_t c = (int64_t)bx * 64 * VEC + t;
+    if (c < C) it.ws.colpart[(int64_t)by * C + c] = colred[0][t] + colred[1][t] + colred[2][t] + colred[3][t];
   }
+}
+
+__global__ __launch_bounds__(256) void af_stats_kernel(AfBatch b) {
+  __shared__ float colred[4][256];
+  const int ti = af_find(b.tile_start, b.count, blockIdx.x);
+  const AfItem& it = b.it[ti];
+  if (!it.factored) return;
+  const int local = blockIdx.x - b.tile_start[ti];
+  const int bx = local % it.ntc, by = local / it.ntc;
+  if (it.vec == 4) af_stats_tile<4>(it, bx, by, colred);
+  else af_stats_tile<1>(it, bx, by, colred);
 }
 
 // One thread per row and per column: folds the tile partials into the second-moment vectors.
 // cfac_j = rsqrt(v_col_j); the row factor needs mean(v_row) and is formed by the consumers.
-__global__ __launch_bounds__(256) void af_finalize_kernel(float* __restrict__ v_row, float* __restrict__ v_col,
-                                                          int64_t R, int64_t C, int ntc, int ntr, float beta2,
-                                                          float eps1, AfWs ws) {
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+__global__ __launch_bounds__(256) void af_finalize_kernel(AfBatch b) {
+  const int ti = af_find(b.fin_start, b.count, blockIdx.x);
+  const AfItem& it = b.it[ti];
+  if (!it.factored) return;
+  const int64_t R = it.R, C = it.C;
+  const float beta2 = b.beta2, eps1 = b.eps1;
+  const int64_t idx = (int64_t)(blockIdx.x - b.fin_start[ti]) * 256 + threadIdx.x;
   if (idx < R) {
     float s = 0.f;
-    for (int t = 0; t < ntc; ++t) s += ws.rowpart[(int64_t)t * R + idx];
-    v_row[idx] = beta2 * v_row[idx] + (1.f - beta2) * (s / (float)C + eps1);
+    for (int t = 0; t < it.ntc; ++t) s += it.ws.rowpart[(int64_t)t * R + idx];
+    it.v_row[idx] = beta2 * it.v_row[idx] + (1.f - beta2) * (s / (float)C + eps1);
   } else if (idx < R + C) {
     const int64_t j = idx - R;
     float s = 0.f;
-    for (int t = 0; t < ntr; ++t) s += ws.colpart[(int64_t)t * C + j];
-    const float vc = beta2 * v_col[j] + (1.f - beta2) * (s / (float)R + eps1);
-    v_col[j] = vc;
-    ws.cfac[j] = rsqrtf(vc);
+    for (int t = 0; t < it.ntr; ++t) s += it.ws.colpart[(int64_t)t * C + j];
+    const float vc = beta2 * it.v_col[j] + (1.f - beta2) * (s / (float)R + eps1);
+    it.v_col[j] = vc;
+    it.ws.cfac[j] = rsqrtf(vc);
   }
 }
 
@@ -115,19 +162,23 @@ __device__ __forceinline__ float af_mean_vrow(const float* __restrict__ v_row, i
 
 // Per-tile sums of U*U and W*W.  FACT: U = g rfac cfac.  !FACT: updates v_full and U = g rsqrt(v).
 template <int VEC, bool FACT>
-__global__ __launch_bounds__(256) void af_norms_kernel(const float* __restrict__ g, const float* __restrict__ w,
-                                                       float* __restrict__ v_full, const float* __restrict__ v_row,
-                                                       int64_t R, int64_t C, float beta2, float eps1, AfWs ws) {
-  __shared__ float red[12];
+__device__ __forceinline__ void af_norms_tile(const AfItem& it, int bx, int by, int tile, float beta2, float eps1,
+                                              float* red) {
+  const float* __restrict__ g = it.g;
+  const float* __restrict__ w = it.w;
+  float* __restrict__ v_full = it.v_full;
+  const float* __restrict__ v_row = it.v_row;
+  const int64_t R = it.R, C = it.C;
+  const AfWs& ws = it.ws;
   float inv_mean = 1.f;
   if constexpr (FACT) {
     const float mean_vr = af_mean_vrow(v_row, R, red + 8);
     inv_mean = 1.f / mean_vr;
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) ws.scal[1] = inv_mean;
+    if (tile == 0 && threadIdx.x == 0) ws.scal[1] = inv_mean;
   }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t c0 = (int64_t)blockIdx.x * 64 * VEC + lane * VEC;
-  const int64_t r0 = (int64_t)blockIdx.y * TR;
+  const int64_t c0 = (int64_t)bx * 64 * VEC + lane * VEC;
+  const int64_t r0 = (int64_t)by * TR;
   float su = 0.f, sw = 0.f;
   if (c0 < C) {
     float cf[VEC];
@@ -163,36 +214,59 @@ __global__ __launch_bounds__(256) void af_norms_kernel(const float* __restrict__
   su = block_sum<4>(su, red);
   sw = block_sum<4>(sw, red + 4);
   if (threadIdx.x == 0) {
-    const int64_t tile = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
     ws.part_u[tile] = su;
     ws.part_w[tile] = sw;
   }
 }
 
-__global__ __launch_bounds__(1024) void af_coef_kernel(int64_t ntiles, double count, adafactor_cfg c, AfWs ws) {
+__global__ __launch_bounds__(256) void af_norms_kernel(AfBatch b) {
+  __shared__ float red[12];
+  const int ti = af_find(b.tile_start, b.count, blockIdx.x);
+  const AfItem& it = b.it[ti];
+  const int local = blockIdx.x - b.tile_start[ti];
+  const int bx = local % it.ntc, by = local / it.ntc;
+  if (it.vec == 4) {
+    if (it.factored) af_norms_tile<4, true>(it, bx, by, local, b.beta2, b.eps1, red);
+    else af_norms_tile<4, false>(it, bx, by, local, b.beta2, b.eps1, red);
+  } else {
+    if (it.factored) af_norms_tile<1, true>(it, bx, by, local, b.beta2, b.eps1, red);
+    else af_norms_tile<1, false>(it, bx, by, local, b.beta2, b.eps1, red);
+  }
+}
+
+// One workgroup per tensor.
+__global__ __launch_bounds__(1024) void af_coef_kernel(AfBatch b, adafactor_cfg c) {
   __shared__ float red[32];
+  const AfItem& it = b.it[blockIdx.x];
+  const int64_t ntiles = (int64_t)it.ntc * it.ntr;
   float su = 0.f, sw = 0.f;
   for (int64_t i = threadIdx.x; i < ntiles; i += 1024) {
-    su += ws.part_u[i];
-    sw += ws.part_w[i];
+    su += it.ws.part_u[i];
+    sw += it.ws.part_w[i];
   }
   su = block_sum<16>(su, red);
   sw = block_sum<16>(sw, red + 16);
   if (threadIdx.x == 0) {
+    const double count = (double)it.R * (double)it.C;
     const float rms_u = sqrtf(su / (float)count), rms_w = sqrtf(sw / (float)count);
     float alpha = c.lr;
     if (c.scale_by_param) alpha *= fmaxf(c.eps2, rms_w);
-    ws.scal[0] = alpha / fmaxf(1.f, rms_u / c.clip);
+    it.ws.scal[0] = alpha / fmaxf(1.f, rms_u / c.clip);
   }
 }
 
 template <int VEC, bool FACT>
-__global__ __launch_bounds__(256) void af_apply_kernel(float* __restrict__ w, const float* __restrict__ g,
-                                                       const float* __restrict__ v_full, const float* __restrict__ v_row,
-                                                       bf16* __restrict__ lp, int64_t R, int64_t C, AfWs ws) {
+__device__ __forceinline__ void af_apply_tile(const AfItem& it, int bx, int by) {
+  float* __restrict__ w = it.w;
+  const float* __restrict__ g = it.g;
+  const float* __restrict__ v_full = it.v_full;
+  const float* __restrict__ v_row = it.v_row;
+  bf16* __restrict__ lp = it.lp;
+  const int64_t R = it.R, C = it.C;
+  const AfWs& ws = it.ws;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t c0 = (int64_t)blockIdx.x * 64 * VEC + lane * VEC;
-  const int64_t r0 = (int64_t)blockIdx.y * TR;
+  const int64_t c0 = (int64_t)bx * 64 * VEC + lane * VEC;
+  const int64_t r0 = (int64_t)by * TR;
   if (c0 >= C) return;
   const float coef = ws.scal[0];
   float cf[VEC];
@@ -218,6 +292,20 @@ __global__ __launch_bounds__(256) void af_apply_kernel(float* __restrict__ w, co
 #pragma unroll
       for (int i = 0; i < VEC; ++i) lp[r * C + c0 + i] = (bf16)wv[i];
     }
+  }
+}
+
+__global__ __launch_bounds__(256) void af_apply_kernel(AfBatch b) {
+  const int ti = af_find(b.tile_start, b.count, blockIdx.x);
+  const AfItem& it = b.it[ti];
+  const int local = blockIdx.x - b.tile_start[ti];
+  const int bx = local % it.ntc, by = local / it.ntc;
+  if (it.vec == 4) {
+    if (it.factored) af_apply_tile<4, true>(it, bx, by);
+    else af_apply_tile<4, false>(it, bx, by);
+  } else {
+    if (it.factored) af_apply_tile<1, true>(it, bx, by);
+    else af_apply_tile<1, false>(it, bx, by);
   }
 }
 
@@ -258,37 +346,52 @@ size_t adafactor_ws_bytes(int64_t R, int64_t C, int factored) {
   return n;
 }
 
+hipError_t launch_adafactor_multi(const AfTensor* t, int n, const adafactor_cfg& c, void* wsp, hipStream_t st) {
+  if (n < 1 || n > AF_MAX_TENSORS) return hipErrorInvalidValue;
+  AfBatch b;
+  std::memset(&b, 0, sizeof(b));
+  b.count = n;
+  b.beta2 = (float)(1.0 - pow((double)c.step, -(double)c.decay_pow));
+  b.eps1 = c.eps1;
+  char* wp = (char*)wsp;
+  int64_t tiles = 0, fins = 0;
+  bool any_factored = false;
+  for (int i = 0; i < n; ++i) {
+    const AfGeom g = geom(t[i].rows, t[i].cols);
+    AfItem& it = b.it[i];
+    it.w = t[i].param; it.g = t[i].grad; it.v_row = t[i].v_row; it.v_col = t[i].v_col; it.v_full = t[i].v_full;
+    it.lp = (bf16*)t[i].bf16_out;
+    it.R = t[i].rows; it.C = t[i].cols;
+    it.ws = carve(wp, it.R, it.C, g);
+    wp += adafactor_ws_bytes(it.R, it.C, t[i].factored);
+    it.vec = g.vec; it.ntc = g.ntc; it.ntr = g.ntr; it.factored = t[i].factored ? 1 : 0;
+    b.tile_start[i] = (int)tiles;
+    b.fin_start[i] = (int)fins;
+    tiles += g.ntiles;
+    if (it.factored) { fins += ceil_div(it.R + it.C, (int64_t)256); any_factored = true; }
+    if (tiles > (int64_t)1 << 30 || fins > (int64_t)1 << 30) return hipErrorInvalidValue;
+  }
+  for (int i = n; i <= AF_MAX_TENSORS; ++i) { b.tile_start[i] = (int)tiles; b.fin_start[i] = (int)fins; }
+  hipError_t e;
+  if (any_factored) {
+    af_stats_kernel<<<(unsigned)tiles, 256, 0, st>>>(b);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    af_finalize_kernel<<<(unsigned)fins, 256, 0, st>>>(b);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  af_norms_kernel<<<(unsigned)tiles, 256, 0, st>>>(b);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  af_coef_kernel<<<n, 1024, 0, st>>>(b, c);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  af_apply_kernel<<<(unsigned)tiles, 256, 0, st>>>(b);
+  return hipGetLastError();
+}
+
 hipError_t launch_adafactor(float* param, const float* grad, float* v_row, float* v_col, float* v_full,
                             int64_t R, int64_t C, int factored, const adafactor_cfg& c, void* bf16_out,
                             void* wsp, hipStream_t st) {
-  const AfGeom g = geom(R, C);
-  const AfWs ws = carve(wsp, R, C, g);
-  const float beta2 = (float)(1.0 - pow((double)c.step, -(double)c.decay_pow));
-  const dim3 grid(g.ntc, g.ntr);
-  hipError_t e;
-#define T5MI_AF(K, ...)                                                   \
-  do {                                                                    \
-    if (g.vec == 4) K<4, __VA_ARGS__; else K<1, __VA_ARGS__;              \
-    if ((e = hipGetLastError()) != hipSuccess) return e;                  \
-  } while (0)
-  if (factored) {
-    if (g.vec == 4) af_stats_kernel<4><<<grid, 256, 0, st>>>(grad, R, C, ws);
-    else af_stats_kernel<1><<<grid, 256, 0, st>>>(grad, R, C, ws);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    af_finalize_kernel<<<ceil_div(R + C, 256), 256, 0, st>>>(v_row, v_col, R, C, g.ntc, g.ntr, beta2, c.eps1, ws);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    T5MI_AF(af_norms_kernel, true><<<grid, 256, 0, st>>>(grad, param, nullptr, v_row, R, C, beta2, c.eps1, ws));
-  } else {
-    T5MI_AF(af_norms_kernel, false><<<grid, 256, 0, st>>>(grad, param, v_full, nullptr, R, C, beta2, c.eps1, ws));
-  }
-  af_coef_kernel<<<1, 1024, 0, st>>>(g.ntiles, (double)R * (double)C, c, ws);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
-  if (factored)
-    T5MI_AF(af_apply_kernel, true><<<grid, 256, 0, st>>>(param, grad, nullptr, v_row, (bf16*)bf16_out, R, C, ws));
-  else
-    T5MI_AF(af_apply_kernel, false><<<grid, 256, 0, st>>>(param, grad, v_full, nullptr, (bf16*)bf16_out, R, C, ws));
-#undef T5MI_AF
-  return hipSuccess;
+  AfTensor t{param, grad, v_row, v_col, v_full, R, C, factored, bf16_out};
+  return launch_adafactor_multi(&t, 1, c, wsp, st);
 }
 
 }  // namespace t5mi

@@ -474,8 +474,51 @@ int adafactor_step(float* param, const float* grad, float* v_row, float* v_col, 
   if (!param || !grad || !workspace) return T5_ERR_NULL;
   if (factored ? (!v_row || !v_col) : !v_full) return T5_ERR_NULL;
   if (workspace_bytes < adafactor_ws_bytes(rows, cols, factored)) return T5_ERR_WORKSPACE;
-  T5_TRY(launch_adafactor(param, grad, v_row, v_col, v_full, rows, cols, factored, *cfg, bf16_copy_out,
-                          workspace, (hipStream_t)stream));
+  hipStream_t st = (hipStream_t)stream;
+  T5_STEP("adafactor", launch_adafactor(param, grad, v_row, v_col, v_full, rows, cols, factored, *cfg, bf16_copy_out,
+                                        workspace, st));
+  return T5_OK;
+}
+
+size_t adafactor_multi_workspace_bytes(const adafactor_tensor* t, int n) {
+  if (!t || n < 1 || n > AF_MAX_TENSORS) return 0;
+  size_t total = 0;
+  for (int i = 0; i < n; ++i) {
+    if (t[i].rows < 1 || t[i].cols < 1) return 0;
+    total += adafactor_ws_bytes(t[i].rows, t[i].cols, t[i].factored);
+  }
+  return total;
+}
+
+int adafactor_step_multi(const adafactor_tensor* t, int n, const adafactor_cfg* cfg, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+  if (!cfg || !t) return T5_ERR_NULL;
+  if (n < 1) return T5_ERR_SHAPE;
+  if (n > AF_MAX_TENSORS) return T5_ERR_UNSUPPORTED;
+  if (cfg->step < 1 || !(cfg->clip > 0.f) || !(cfg->eps1 >= 0.f)) return T5_ERR_SHAPE;
+  AfTensor items[AF_MAX_TENSORS];
+  size_t need = 0;
+  for (int i = 0; i < n; ++i) {
+    if (t[i].rows < 1 || t[i].cols < 1) return T5_ERR_SHAPE;
+    if (t[i].rows > (1 << 24) || t[i].cols > (1 << 24)) return T5_ERR_UNSUPPORTED;
+    if (!t[i].param || !t[i].grad) return T5_ERR_NULL;
+    if (t[i].factored ? (!t[i].v_row || !t[i].v_col) : !t[i].v_full) return T5_ERR_NULL;
+    need += adafactor_ws_bytes(t[i].rows, t[i].cols, t[i].factored);
+    items[i] = AfTensor{t[i].param, t[i].grad, t[i].v_row, t[i].v_col, t[i].v_full, t[i].rows, t[i].cols,
+                        t[i].factored, t[i].bf16_copy_out};
+  }
+  if (!workspace) return T5_ERR_NULL;
+  if (workspace_bytes < need) return T5_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  T5_STEP("adafactor", launch_adafactor_multi(items, n, *cfg, workspace, st));
+  return T5_OK;
+}
+
+int t5_mfma_peak_probe(int workgroups, int iters, int random_operands, float* sink, void* stream) {
+  if (workgroups < 1 || iters < 1 || workgroups > (1 << 20)) return T5_ERR_SHAPE;
+  if (!sink) return T5_ERR_NULL;
+  hipStream_t st = (hipStream_t)stream;
+  T5_STEP("mfma_peak_probe", launch_mfma_peak_probe(workgroups, iters, random_operands, sink, st));
   return T5_OK;
 }
 

@@ -132,10 +132,28 @@ hipError_t launch_attn_bwd_mfma(const void* qkv, const void* c, const void* dc, 
                                 const float* lse, float* dvec, void* dqkv, float* ddiag, void* scratch,
                                 const AttnDims& a, int far, int phase, hipStream_t st);
 
+// ------------------------------------------------------------------ measurement aid
+// Register-only MFMA loop: each of the 4 waves of a workgroup issues iters * 32 v_mfma_f32_32x32x16_bf16.
+hipError_t launch_mfma_peak_probe(int workgroups, int iters, int random_operands, float* sink, hipStream_t st);
+
 // ------------------------------------------------------------------ Adafactor
 size_t adafactor_ws_bytes(int64_t rows, int64_t cols, int factored);
 hipError_t launch_adafactor(float* param, const float* grad, float* v_row, float* v_col, float* v_full,
                             int64_t rows, int64_t cols, int factored, const adafactor_cfg& c,
                             void* bf16_out, void* ws, hipStream_t st);
+// The same update for up to AF_MAX_TENSORS tensors in one sequence of launches.  ws: the tensors'
+// workspaces (adafactor_ws_bytes each) back to back, in order.
+constexpr int AF_MAX_TENSORS = 16;
+struct AfTensor {
+  float* param;
+  const float* grad;
+  float* v_row;
+  float* v_col;
+  float* v_full;
+  int64_t rows, cols;
+  int factored;
+  void* bf16_out;
+};
+hipError_t launch_adafactor_multi(const AfTensor* t, int n, const adafactor_cfg& c, void* ws, hipStream_t st);
 
 }  // namespace t5mi

@@ -99,6 +99,30 @@ def test_adafactor_validation():
     assert lib.adafactor_step(dummy, dummy, dummy, dummy, None, 8, 8, 1, C.byref(ok), None, dummy, 8, None) == 4
 
 
+def test_adafactor_multi_validation():
+    lib = P.lib()
+    ok = B._AfCfg(0.01, 0.8, 1e-30, 1e-3, 1.0, 1, 1)
+    arr = (B._AfTensor * 2)()
+    arr[0] = B._AfTensor(4096, 4096, 4096, 4096, None, 8, 8, 1, None)
+    arr[1] = B._AfTensor(4096, 4096, None, None, 4096, 1, 16, 0, None)
+    need = lib.adafactor_multi_workspace_bytes(arr, 2)
+    assert need == lib.adafactor_workspace_bytes(8, 8, 1) + lib.adafactor_workspace_bytes(1, 16, 0)
+    dummy = C.c_void_p(4096)
+    assert lib.adafactor_step_multi(arr, 2, None, dummy, need, None) == 1
+    assert lib.adafactor_step_multi(None, 2, C.byref(ok), dummy, need, None) == 1
+    assert lib.adafactor_step_multi(arr, 0, C.byref(ok), dummy, need, None) == 2
+    assert lib.adafactor_step_multi(arr, 17, C.byref(ok), dummy, need, None) == 3
+    assert lib.adafactor_step_multi(arr, 2, C.byref(ok), dummy, need - 1, None) == 4
+    assert lib.adafactor_step_multi(arr, 2, C.byref(ok), None, need, None) == 1
+    bad = (B._AfTensor * 1)()
+    bad[0] = B._AfTensor(4096, 4096, None, 4096, None, 8, 8, 1, None)   # factored without v_row
+    assert lib.adafactor_step_multi(bad, 1, C.byref(ok), dummy, 1 << 20, None) == 1
+    bad[0] = B._AfTensor(4096, 4096, 4096, 4096, None, 0, 8, 1, None)
+    assert lib.adafactor_step_multi(bad, 1, C.byref(ok), dummy, 1 << 20, None) == 2
+    assert lib.t5_mfma_peak_probe(0, 1, 0, dummy, None) == 2
+    assert lib.t5_mfma_peak_probe(1, 1, 0, None, None) == 1
+
+
 def test_gemm_validation():
     lib = P.lib()
     dummy = C.c_void_p(4096)

@@ -103,6 +103,41 @@ def test_adafactor_three_steps(rows, cols, factored):
         assert torch.equal(lp, dp.to(torch.bfloat16))
 
 
+def test_adafactor_multi_matches_single_and_oracle():
+    # one batched call over tensors of mixed shapes (vectorised and not, factored and not) gives, bit for
+    # bit, what the per-tensor calls give, and both match the float64 oracle
+    P = _P()
+    shapes = [(64, 256, True), (70, 130, True), (513, 1027, True), (1, 64, False), (32, 4, False), (33, 7, False),
+              (128, 384, True)]
+    single, multi, ref = [], [], []
+    for k, (rows, cols, fact) in enumerate(shapes):
+        p, _ = SI.make_adafactor_case(rows, cols, seed=50 + k)
+        for group in (single, multi):
+            group.append(dict(param=torch.from_numpy(p.astype(np.float32)).cuda(), factored=fact,
+                              v_row=torch.zeros(rows, device="cuda"), v_col=torch.zeros(cols, device="cuda"),
+                              v_full=torch.zeros(rows, cols, device="cuda"),
+                              bf16_copy_out=torch.empty(rows, cols, dtype=torch.bfloat16, device="cuda")))
+        ref.append((p, O.adafactor_zero_state(rows, cols, fact)))
+    for t in (1, 2, 3):
+        gs = []
+        for k, (rows, cols, fact) in enumerate(shapes):
+            _, g = SI.make_adafactor_case(rows, cols, seed=300 + 10 * t + k, grad_std=1e-2 * t)
+            gs.append(g)
+            ref[k] = O.adafactor_step(ref[k][0], g, ref[k][1], step=t, lr=0.01, factored=fact)
+        for k, d in enumerate(single):
+            gd = torch.from_numpy(gs[k].astype(np.float32)).cuda()
+            P.adafactor_step(d["param"], gd, step=t, lr=0.01, factored=d["factored"], v_row=d["v_row"],
+                             v_col=d["v_col"], v_full=d["v_full"], bf16_copy_out=d["bf16_copy_out"])
+        for k, d in enumerate(multi):
+            d["grad"] = torch.from_numpy(gs[k].astype(np.float32)).cuda()
+        P.adafactor_step_multi(multi, step=t, lr=0.01)
+        torch.cuda.synchronize()
+        for k, (a, b) in enumerate(zip(single, multi)):
+            assert torch.equal(a["param"], b["param"]), (t, k)
+            assert torch.equal(a["bf16_copy_out"], b["bf16_copy_out"]), (t, k)
+            assert rel_err(to_np(b["param"]), ref[k][0])[0] <= 1e-5, (t, k)
+
+
 # ------------------------------------------------------------------ bf16 block, small shapes
 SMALL_BF16 = [
     SI.BlockConfig("bf16_enc", 30, batch=2, seq=128, d_model=128, n_heads=2, d_kv=64, d_ff=256,
