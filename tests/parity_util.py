@@ -13,6 +13,10 @@ TOL_F32 = (1e-4, 1e-4)
 TOL_BF16_ACT = (2e-2, 2e-3)      # y of the bf16 block (stated target)
 TOL_BF16_DX = (3e-2, 2.5e-3)     # dx: one more chain of bf16 MFMA-operand roundings than y
 TOL_BF16_DW = (6e-2, 6e-3)       # weight gradients
+# At the shapes of the named workload configurations (thousands of tokens per reduction) the measured
+# errors sit lower, and the mean of dx meets the stated 2e-3:
+TOL_BF16_DX_NAMED = (3e-2, 2e-3)
+TOL_BF16_DW_NAMED = (5e-2, 5e-3)
 
 
 def rel_err(gpu: np.ndarray, ref: np.ndarray):
