@@ -61,6 +61,46 @@ __device__ __forceinline__ bf16x8 load_frag(const char* stage, int base, int kk,
   }
 }
 
+// Position in a workgroup's sequence of k-tiles, in scalar registers: global base addresses of the
+// next tile and the number of tiles left in the current run.  A k-slice is at most three runs of
+// consecutive tiles (one per segment); the runs are kept as a list that is rotated when the first
+// one is used up, so nothing is indexed by a run number.  Advancing costs two adds per tile --
+// recomputing the position from the tile number (a modulo, a segment search through the kernel
+// arguments) cost some forty scalar instructions and a scalar load per k-tile.
+struct KCursor {
+  const char *a, *b;  // bases of the next tile
+  int rem;            // tiles left in the current run, this one included
+  const char *ra0, *rb0, *ra1, *rb1, *ra2, *rb2;
+  int rn0, rn1, rn2, nruns;
+  size_t step_a, step_b;
+};
+__device__ __forceinline__ void cursor_rotate(KCursor& c) {
+  if (c.nruns == 2) {
+    const char* ta = c.ra0; const char* tb = c.rb0; const int tn = c.rn0;
+    c.ra0 = c.ra1; c.rb0 = c.rb1; c.rn0 = c.rn1;
+    c.ra1 = ta; c.rb1 = tb; c.rn1 = tn;
+  } else if (c.nruns == 3) {
+    const char* ta = c.ra0; const char* tb = c.rb0; const int tn = c.rn0;
+    c.ra0 = c.ra1; c.rb0 = c.rb1; c.rn0 = c.rn1;
+    c.ra1 = c.ra2; c.rb1 = c.rb2; c.rn1 = c.rn2;
+    c.ra2 = ta; c.rb2 = tb; c.rn2 = tn;
+  }
+}
+// Returns the bases of the next tile and moves on; the sequence wraps around at the end.
+__device__ __forceinline__ void cursor_next(KCursor& c, const char*& abase, const char*& bbase) {
+  abase = c.a;
+  bbase = c.b;
+  if (--c.rem > 0) {
+    c.a += c.step_a;
+    c.b += c.step_b;
+  } else {
+    cursor_rotate(c);
+    c.a = c.ra0;
+    c.b = c.rb0;
+    c.rem = c.rn0;
+  }
+}
+
 template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int EPI, int NS, int MINW, int BK>
 __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc g, GemmEpi e, int tiles_m,
                                                                 int tiles_n, int split_k) {
@@ -156,18 +196,33 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
   }
   const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)smem;
 
-  // Global base addresses of k-tile `t` (relative to kt_begin).
   // Workgroups start their k loop at different phases (rotated by a multiple of the tile
   // coordinates) so that concurrently running tiles do not all stream the same 256-byte-interleaved
-  // L2 channel; tiles past the end wrap around and refetch valid data that is never used.
-  auto tile_bases = [&](int t, const char*& abase, const char*& bbase) {
-    int kt = kt_begin + (t % nk + k_skew) % nk;
-    int s = 0;
-    while (s + 1 < g.nseg && kt >= g.seg[s].K / BK) { kt -= g.seg[s].K / BK; ++s; }
-    const size_t k0 = (size_t)kt * BK;
-    abase = (const char*)g.seg[s].A + (A_KC ? k0 * 2 : k0 * (size_t)lda * 2);
-    bbase = (const char*)g.seg[s].B + (B_KC ? k0 * 2 : k0 * (size_t)ldb * 2);
-  };
+  // L2 channel; the sequence wraps around, and tiles requested past the end refetch valid data that
+  // is never used.
+  KCursor kc;
+  kc.step_a = A_KC ? (size_t)BK * 2 : (size_t)BK * (size_t)lda * 2;
+  kc.step_b = B_KC ? (size_t)BK * 2 : (size_t)BK * (size_t)ldb * 2;
+  kc.nruns = g.nseg;
+  kc.ra1 = kc.rb1 = kc.ra2 = kc.rb2 = nullptr;
+  kc.rn1 = kc.rn2 = 0;
+  if (g.nseg == 1) {
+    kc.ra0 = (const char*)g.seg[0].A + (size_t)kt_begin * kc.step_a;
+    kc.rb0 = (const char*)g.seg[0].B + (size_t)kt_begin * kc.step_b;
+    kc.rn0 = nk;
+  } else {  // several segments are never split along k
+    kc.ra0 = (const char*)g.seg[0].A; kc.rb0 = (const char*)g.seg[0].B; kc.rn0 = g.seg[0].K / BK;
+    kc.ra1 = (const char*)g.seg[1].A; kc.rb1 = (const char*)g.seg[1].B; kc.rn1 = g.seg[1].K / BK;
+    if (g.nseg > 2) { kc.ra2 = (const char*)g.seg[2].A; kc.rb2 = (const char*)g.seg[2].B; kc.rn2 = g.seg[2].K / BK; }
+  }
+  {
+    int o = k_skew;  // < nk = rn0 + rn1 + rn2
+    if (kc.nruns > 1 && o >= kc.rn0) { o -= kc.rn0; cursor_rotate(kc); }
+    if (kc.nruns > 2 && o >= kc.rn0) { o -= kc.rn0; cursor_rotate(kc); }
+    kc.a = kc.ra0 + (size_t)o * kc.step_a;
+    kc.b = kc.rb0 + (size_t)o * kc.step_b;
+    kc.rem = kc.rn0 - o;
+  }
   // Issue DMA instructions [d0, d1) of a k-tile into stage `st`; a tile's DMA_PER_TILE instructions
   // per wave are numbered A slots first, then B slots.
   auto dma_part = [&](const char* abase, const char* bbase, int st, int d0, int d1) {
@@ -178,11 +233,6 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
       if (d < A_DMA) dma_1k(sa + (wave + d * NW) * 1024, abase, a_off[d < A_DMA ? d : 0]);
       else dma_1k(sb + (wave + (d - A_DMA) * NW) * 1024, bbase, b_off[d >= A_DMA ? d - A_DMA : 0]);
     }
-  };
-  auto dma_tile = [&](int t, int st) {
-    const char *ab, *bb;
-    tile_bases(t, ab, bb);
-    dma_part(ab, bb, st, 0, DMA_PER_TILE);
   };
 
   f32x16 acc[MI][NI];
@@ -231,8 +281,11 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
     // Prologue: fill stages 0 .. NS-2 and the first part of stage NS-1, wait for tile 0.
     const char *ab, *bb;
 #pragma unroll
-    for (int s = 0; s + 1 < NS; ++s) dma_tile(s, s);
-    tile_bases(NS - 1, ab, bb);
+    for (int s = 0; s + 1 < NS; ++s) {
+      cursor_next(kc, ab, bb);
+      dma_part(ab, bb, s, 0, DMA_PER_TILE);
+    }
+    cursor_next(kc, ab, bb);
     dma_part(ab, bb, NS - 1, 0, H0);
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((NS - 2) * DMA_PER_TILE + H0) : "memory");
     load_frags(0, 0, 0);
@@ -249,7 +302,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
           // tile t+1 has landed (this wave's part) and all of this wave's reads of stage s are done;
           // after the barrier that holds for every wave, so stage s can be refilled.
           asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((NS - 2) * DMA_PER_TILE) : "memory");
-          tile_bases(t + NS, ab, bb);
+          cursor_next(kc, ab, bb);  // tile t + NS
           kstep((KSTEPS - 1) & 1, (s + 1) % NS, 0, 0, ab, bb, s, 0, H0);
         }
       }
@@ -585,7 +638,7 @@ bool gemm_mfma_supported(const GemmDesc& g, const GemmEpi& e) {
     case EPI_GEGLU_FWD:
       return g.a_kc == 1 && g.N % 64 == 0 && e.out_type == IN_BF16;
     case EPI_SPLIT_F32:
-      return g.a_kc == 0;
+      return g.a_kc == 0 && g.nseg == 1;  // k may be split into slices: one segment only
     default:
       return false;
   }
