@@ -75,7 +75,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2_small", choices=[k for k in SI.CONFIGS if k != "c1_tiny_f32"])
+    ap.add_argument("--workload", default="c2_small", choices=[k for k in SI.CONFIGS if k != "c1_tiny_f32" and SI.CONFIGS[k].enc_seq == 0])
     ap.add_argument("--cpu-sample-batch", type=int, default=0, help="0 = pick about 10-30 s of oracle work")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",

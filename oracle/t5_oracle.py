@@ -16,6 +16,9 @@ therefore the public definition of the named layer, written out in full:
     unless the caller asks for one through attn_scale.
   * T5.1.1 feed-forward: gated GELU (tanh form), no biases.
   * Pre-norm residual wiring: h = x + Attn(Norm(x)); y = h + MLP(Norm(h)).
+  * Decoder block of the encoder-decoder model: the same, with a cross-attention
+    sublayer (queries from the decoder stream, keys and values from the encoder
+    output, no position bias, no mask) between self-attention and the MLP.
   * Adafactor with factored second moments and update clipping, no momentum.
 
 The result has a plain definition, so the oracle *is* that definition: the
@@ -222,6 +225,110 @@ def block_bwd(cfg, dy: np.ndarray, w: dict, saved: dict):
     dx = dh + dx_norm
     assert dx.shape[-1] == d
     return dx, g
+
+
+# --------------------------------------------------------------------------------------
+# Decoder block: causal self-attention, cross-attention over an encoder output, MLP
+# --------------------------------------------------------------------------------------
+def decoder_block_fwd(cfg, x: np.ndarray, enc: np.ndarray, w: dict):
+    """y = decoder_block(x, enc).  x: [B,S,d] decoder stream, enc: [B,S_enc,d] encoder output.
+
+    The encoder-decoder T5 of the paper (Sec. 4) stacks this layer in its decoder.  Pre-norm
+    residual wiring with three sublayers:
+      h1 = x  + SelfAttn(RMSNorm(x; g1))                 (as in block_fwd: bias table, causal mask)
+      h2 = h1 + CrossAttn(RMSNorm(h1; gx), enc)
+      y  = h2 + MLP(RMSNorm(h2; g2))
+    Cross-attention: queries from the normalised decoder stream, keys and values from the encoder
+    output as it is (it was normalised by the encoder's final norm); no position bias, no mask:
+      q = nx Xq;  k = enc Xk;  v = enc Xv  (split into heads)
+      s[h,i,j] = attn_scale <q_hi, k_hj>;  P = softmax_j s;  o = P v;  cx = concat_h o;  h2 = h1 + cx Xo
+    """
+    nh, dk = cfg.n_heads, cfg.d_kv
+    # --- self-attention sublayer
+    n1, r1 = rmsnorm_fwd(x, w["ln1_scale"], cfg.rms_eps)
+    q = _split_heads(n1 @ w["wq"], nh, dk)
+    k = _split_heads(n1 @ w["wk"], nh, dk)
+    v = _split_heads(n1 @ w["wv"], nh, dk)
+    bias, bucket = relpos_bias(w["rel_table"], cfg.seq, not cfg.causal, cfg.num_buckets, cfg.max_distance)
+    s = cfg.attn_scale * (q @ np.swapaxes(k, -1, -2)) + bias[None]
+    if cfg.causal:
+        i = np.arange(cfg.seq)
+        s = np.where(i[None, :] > i[:, None], -np.inf, s)
+    p = softmax_rows(s)
+    c = _merge_heads(p @ v)
+    h1 = x + c @ w["wo"]
+    # --- cross-attention sublayer
+    nx, rx = rmsnorm_fwd(h1, w["lnx_scale"], cfg.rms_eps)
+    qx = _split_heads(nx @ w["xq"], nh, dk)
+    kx = _split_heads(enc @ w["xk"], nh, dk)
+    vx = _split_heads(enc @ w["xv"], nh, dk)
+    px = softmax_rows(cfg.attn_scale * (qx @ np.swapaxes(kx, -1, -2)))
+    cx = _merge_heads(px @ vx)
+    h2 = h1 + cx @ w["xo"]
+    # --- MLP sublayer
+    n2, r2 = rmsnorm_fwd(h2, w["ln2_scale"], cfg.rms_eps)
+    u = n2 @ w["wi0"]
+    wl = n2 @ w["wi1"]
+    a = gelu(u) * wl
+    y = h2 + a @ w["wo_ff"]
+    saved = dict(x=x, enc=enc, n1=n1, r1=r1, q=q, k=k, v=v, p=p, c=c, h1=h1, nx=nx, rx=rx, qx=qx, kx=kx, vx=vx,
+                 px=px, cx=cx, h2=h2, n2=n2, r2=r2, u=u, wl=wl, a=a, bucket=bucket)
+    return y, saved
+
+
+def decoder_block_bwd(cfg, dy: np.ndarray, w: dict, saved: dict):
+    """Gradients of sum(y * dy) w.r.t. x, enc and every weight.  Returns (dx, denc, grads)."""
+    nh, dk = cfg.n_heads, cfg.d_kv
+    flat = lambda t: t.reshape(-1, t.shape[-1])
+    sv = saved
+    g = {}
+    # --- MLP sublayer
+    g["wo_ff"] = flat(sv["a"]).T @ flat(dy)
+    da = dy @ w["wo_ff"].T
+    du = da * sv["wl"] * gelu_grad(sv["u"])
+    dwl = da * gelu(sv["u"])
+    g["wi0"] = flat(sv["n2"]).T @ flat(du)
+    g["wi1"] = flat(sv["n2"]).T @ flat(dwl)
+    dn2 = du @ w["wi0"].T + dwl @ w["wi1"].T
+    dh2_norm, g["ln2_scale"] = rmsnorm_bwd(sv["h2"], w["ln2_scale"], sv["r2"], dn2)
+    dh2 = dy + dh2_norm
+    # --- cross-attention sublayer
+    g["xo"] = flat(sv["cx"]).T @ flat(dh2)
+    dox = _split_heads(dh2 @ w["xo"].T, nh, dk)
+    px, qx, kx, vx = sv["px"], sv["qx"], sv["kx"], sv["vx"]
+    dvx = np.swapaxes(px, -1, -2) @ dox
+    dpx = dox @ np.swapaxes(vx, -1, -2)
+    dsx = px * (dpx - np.sum(px * dpx, axis=-1, keepdims=True))
+    dqx = _merge_heads(cfg.attn_scale * (dsx @ kx))
+    dkx = _merge_heads(cfg.attn_scale * (np.swapaxes(dsx, -1, -2) @ qx))
+    dvx = _merge_heads(dvx)
+    g["xq"] = flat(sv["nx"]).T @ flat(dqx)
+    g["xk"] = flat(sv["enc"]).T @ flat(dkx)
+    g["xv"] = flat(sv["enc"]).T @ flat(dvx)
+    denc = dkx @ w["xk"].T + dvx @ w["xv"].T
+    dh1_norm, g["lnx_scale"] = rmsnorm_bwd(sv["h1"], w["lnx_scale"], sv["rx"], dqx @ w["xq"].T)
+    dh1 = dh2 + dh1_norm
+    # --- self-attention sublayer
+    g["wo"] = flat(sv["c"]).T @ flat(dh1)
+    do = _split_heads(dh1 @ w["wo"].T, nh, dk)
+    p, q, k, v = sv["p"], sv["q"], sv["k"], sv["v"]
+    dv = np.swapaxes(p, -1, -2) @ do
+    dp = do @ np.swapaxes(v, -1, -2)
+    ds = p * (dp - np.sum(p * dp, axis=-1, keepdims=True))
+    dq = cfg.attn_scale * (ds @ k)
+    dk_ = cfg.attn_scale * (np.swapaxes(ds, -1, -2) @ q)
+    dtable = np.zeros_like(w["rel_table"])
+    ds_hij = np.sum(ds, axis=0)
+    for hh in range(nh):
+        np.add.at(dtable[:, hh], sv["bucket"].reshape(-1), ds_hij[hh].reshape(-1))
+    g["rel_table"] = dtable
+    dqf, dkf, dvf = _merge_heads(dq), _merge_heads(dk_), _merge_heads(dv)
+    g["wq"] = flat(sv["n1"]).T @ flat(dqf)
+    g["wk"] = flat(sv["n1"]).T @ flat(dkf)
+    g["wv"] = flat(sv["n1"]).T @ flat(dvf)
+    dn1 = dqf @ w["wq"].T + dkf @ w["wk"].T + dvf @ w["wv"].T
+    dx_norm, g["ln1_scale"] = rmsnorm_bwd(sv["x"], w["ln1_scale"], sv["r1"], dn1)
+    return dh1 + dx_norm, denc, g
 
 
 # --------------------------------------------------------------------------------------

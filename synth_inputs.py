@@ -22,7 +22,10 @@ import numpy as np
 
 BASE_SEED = 20220331
 TENSOR_ORDER = ("x", "dy", "wq", "wk", "wv", "wo", "rel_table", "wi0", "wi1", "wo_ff",
-                "ln1_scale", "ln2_scale")
+                "ln1_scale", "ln2_scale",
+                # decoder block (cross-attention over an encoder output); appended so that the
+                # seeds of the tensors above never change
+                "enc", "xq", "xk", "xv", "xo", "lnx_scale")
 
 
 @dataclass(frozen=True)
@@ -42,6 +45,8 @@ class BlockConfig:
     rms_eps: float = 1e-6
     attn_scale: float = 1.0   # T5 convention: no 1/sqrt(d_kv) on the logits
     adafactor: bool = False
+    enc_seq: int = 0          # > 0: decoder block, with a cross-attention sublayer over an encoder
+                              # output of this length between self-attention and the MLP
 
     @property
     def inner(self) -> int:
@@ -59,7 +64,12 @@ class BlockConfig:
         attn = 4.0 * s * i
         if self.causal and causal_half:
             attn *= 0.5
-        return 8.0 * d * i + attn + 6.0 * d * f
+        cross = 0.0
+        if self.enc_seq > 0:
+            # per decoder token: q and o projections, scores and values over enc_seq keys; the k, v
+            # projections of the enc_seq encoder tokens are spread over the seq decoder tokens
+            cross = 4.0 * d * i + 4.0 * self.enc_seq * i + 4.0 * d * i * self.enc_seq / s
+        return 8.0 * d * i + attn + cross + 6.0 * d * f
 
     def model_flops(self, causal_half: bool = True) -> float:
         """fwd+bwd model FLOPs (3x forward), whole batch."""
@@ -72,6 +82,8 @@ CONFIGS = {
     "c3_base": BlockConfig("c3_base", 2, 128, 512, 768, 12, 64, 2048, adafactor=True),
     "c4_gpt_causal": BlockConfig("c4_gpt_causal", 3, 16, 2048, 2048, 16, 128, 5120, causal=True),
     "c5_xl": BlockConfig("c5_xl", 4, 32, 1024, 2048, 32, 64, 5120, adafactor=True),
+    # T5.1.1-Base decoder block: causal self-attention, cross-attention over 512 encoder positions, MLP
+    "c6_dec_base": BlockConfig("c6_dec_base", 5, 128, 512, 768, 12, 64, 2048, causal=True, enc_seq=512),
 }
 
 
@@ -105,7 +117,7 @@ def _draw(cfg: BlockConfig, tensor: str, shape, std: float, seed_offset: int = 0
 def make_weights(cfg: BlockConfig) -> dict:
     """Block weights as float64 arrays holding dtype-representable values."""
     d, i, f, h = cfg.d_model, cfg.inner, cfg.d_ff, cfg.n_heads
-    return {
+    w = {
         "ln1_scale": np.ones(d),
         "wq": _draw(cfg, "wq", (d, i), d ** -0.5),
         "wk": _draw(cfg, "wk", (d, i), d ** -0.5),
@@ -117,12 +129,21 @@ def make_weights(cfg: BlockConfig) -> dict:
         "wi1": _draw(cfg, "wi1", (d, f), d ** -0.5),
         "wo_ff": _draw(cfg, "wo_ff", (f, d), f ** -0.5),
     }
+    if cfg.enc_seq > 0:
+        w.update({
+            "lnx_scale": np.ones(d),
+            "xq": _draw(cfg, "xq", (d, i), d ** -0.5),
+            "xk": _draw(cfg, "xk", (d, i), d ** -0.5),
+            "xv": _draw(cfg, "xv", (d, i), d ** -0.5),
+            "xo": _draw(cfg, "xo", (i, d), i ** -0.5),
+        })
+    return w
 
 
 def make_random_scales(cfg: BlockConfig, seed_offset: int = 7) -> dict:
     """Non-trivial RMSNorm scales (1 + 0.1 N(0,1)) for tests that must see the scale's gradient path."""
     out = {}
-    for name in ("ln1_scale", "ln2_scale"):
+    for name in ("ln1_scale", "ln2_scale") + (("lnx_scale",) if cfg.enc_seq > 0 else ()):
         out[name] = round_to_dtype(1.0 + _draw(cfg, name, (cfg.d_model,), 0.1, seed_offset), cfg.dtype)
     return out
 
@@ -131,6 +152,11 @@ def make_activations(cfg: BlockConfig, seed_offset: int = 0) -> tuple:
     """(x, dy), each [batch, seq, d_model] float64 holding dtype-representable values."""
     shape = (cfg.batch, cfg.seq, cfg.d_model)
     return _draw(cfg, "x", shape, 1.0, seed_offset), _draw(cfg, "dy", shape, 1.0, seed_offset)
+
+
+def make_encoder_output(cfg: BlockConfig, seed_offset: int = 0) -> np.ndarray:
+    """Encoder output read by the decoder block's cross-attention: [batch, enc_seq, d_model] ~ N(0, 1)."""
+    return _draw(cfg, "enc", (cfg.batch, cfg.enc_seq, cfg.d_model), 1.0, seed_offset)
 
 
 def make_adafactor_case(rows: int, cols: int, seed: int, grad_std: float = 1e-2) -> tuple:
