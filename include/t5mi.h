@@ -1,7 +1,8 @@
 /*
  * t5mi.h - C ABI of the MI355X (gfx950) implementation of one T5.1.1-style
- * Transformer block: forward, backward, relative-position buckets and the
- * Adafactor update of its weights.
+ * Transformer block (encoder layer, decoder-only layer, or encoder-decoder
+ * decoder layer with cross-attention): forward, backward, relative-position
+ * buckets and the Adafactor update of its weights.
  *
  * The paper (Sec. 4, "Example models") ships T5.1.1 and a decoder-only model as
  * its reference architectures and Sec. 2.3 describes them as ordinary layer
@@ -115,6 +116,50 @@ int t5_block_fwd(const t5_block_cfg* cfg, const void* x, const t5_block_weights*
 int t5_block_bwd(const t5_block_cfg* cfg, const void* dy, const void* x, const t5_block_weights* w,
                  const void* stash, void* dx, const t5_block_grads* dw, int accumulate,
                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* Decoder layer of the encoder-decoder T5.1.1 (paper Sec. 4): the block above with a
+ * cross-attention sublayer between self-attention and the MLP.  With h1 the residual stream after
+ * self-attention (cfg.causal selects the decoder's causal mask and unidirectional buckets) and
+ * enc [batch, enc_seq, d_model] the encoder stack's output:
+ *   nx = RMSNorm(h1; lnx_scale);  q = nx Xq;  k = enc Xk;  v = enc Xv        (heads as above)
+ *   s[h,i,j] = attn_scale <q_hi,k_hj>     no position bias, no mask, i < seq, j < enc_seq
+ *   h2 = h1 + concat_h(softmax_j(s) v) Xo;   then n2 = RMSNorm(h2; ln2_scale), y = h2 + MLP(n2).
+ * Cross-attention weights and gradients; the rest of the layer uses t5_block_weights / _grads. */
+typedef struct {
+  const void* lnx_scale; /* [d_model] */
+  const void* xq;        /* [d_model, n_heads*d_kv] */
+  const void* xk;        /* [d_model, n_heads*d_kv] */
+  const void* xv;        /* [d_model, n_heads*d_kv] */
+  const void* xo;        /* [n_heads*d_kv, d_model] */
+} t5_cross_weights;
+typedef struct {
+  float* lnx_scale;
+  float* xq;
+  float* xk;
+  float* xv;
+  float* xo;
+} t5_cross_grads;
+
+/* Stash / workspace sizes of the decoder layer (0 on an invalid config or enc_seq < 1). */
+size_t t5_decoder_block_stash_bytes(const t5_block_cfg* cfg, int32_t enc_seq);
+size_t t5_decoder_block_workspace_bytes(const t5_block_cfg* cfg, int32_t enc_seq);
+
+/* Forward of the decoder layer.  x, y: [batch, seq, d_model]; enc: [batch, enc_seq, d_model]; all of
+ * cfg.dtype.  stash: t5_decoder_block_stash_bytes() bytes, 256-byte aligned, written here.
+ * Errors as t5_block_fwd; enc_seq < 1 -> T5_ERR_SHAPE. */
+int t5_decoder_block_fwd(const t5_block_cfg* cfg, int32_t enc_seq, const void* x, const void* enc,
+                         const t5_block_weights* w, const t5_cross_weights* xw, void* y, void* stash,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* Backward of the decoder layer: writes dx [batch, seq, d_model] and denc [batch, enc_seq, d_model]
+ * (cfg.dtype; denc is overwritten, a caller with several decoder layers sums them) and the float32
+ * weight gradients of both structs (all fifteen pointers required; accumulate as in t5_block_bwd).
+ * x, enc, w, xw and stash must be those of the matching forward call. */
+int t5_decoder_block_bwd(const t5_block_cfg* cfg, int32_t enc_seq, const void* dy, const void* x,
+                         const void* enc, const t5_block_weights* w, const t5_cross_weights* xw,
+                         const void* stash, void* dx, void* denc, const t5_block_grads* dw,
+                         const t5_cross_grads* dxw, int accumulate, void* workspace,
+                         size_t workspace_bytes, void* stream);
 
 /* Adafactor (the optimizer of the T5 models of paper Sec. 4) with factored second moments and
  * update clipping, no momentum, no weight decay, for one [rows, cols] float32 tensor:

@@ -1,10 +1,12 @@
-"""MI355X (gfx950) implementation of one T5.1.1-style Transformer block: forward, backward,
-relative-position buckets and the Adafactor update, behind the C ABI of include/t5mi.h.
+"""MI355X (gfx950) implementation of one T5.1.1-style Transformer block (encoder layer, decoder-only
+layer, or decoder layer with cross-attention): forward, backward, relative-position buckets and the
+Adafactor update, behind the C ABI of include/t5mi.h.
 
 Python here only marshals arguments: every arithmetic step runs in the HIP kernels of libt5mi.so.
 """
 from .binding import (  # noqa: F401
     T5Error,
+    CROSS_WEIGHT_NAMES,
     WEIGHT_NAMES,
     adafactor_step,
     adafactor_step_multi,
@@ -16,6 +18,10 @@ from .binding import (  # noqa: F401
     t5_block_fwd,
     t5_block_stash_bytes,
     t5_block_workspace_bytes,
+    t5_decoder_block_bwd,
+    t5_decoder_block_fwd,
+    t5_decoder_block_stash_bytes,
+    t5_decoder_block_workspace_bytes,
     t5_gemm_bf16,
     t5_mfma_peak_probe,
     t5_relpos_bucket,

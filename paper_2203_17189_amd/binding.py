@@ -11,6 +11,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
 WEIGHT_NAMES = ("ln1_scale", "wq", "wk", "wv", "wo", "rel_table", "ln2_scale", "wi0", "wi1", "wo_ff")
+CROSS_WEIGHT_NAMES = ("lnx_scale", "xq", "xk", "xv", "xo")
 T5_F32, T5_BF16 = 0, 1
 
 
@@ -32,6 +33,14 @@ class _Weights(C.Structure):
 
 class _Grads(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in WEIGHT_NAMES]
+
+
+class _CrossWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in CROSS_WEIGHT_NAMES]
+
+
+class _CrossGrads(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in CROSS_WEIGHT_NAMES]
 
 
 class _AfTensor(C.Structure):
@@ -73,6 +82,17 @@ def lib() -> C.CDLL:
     L.t5_block_bwd.restype = i32
     L.t5_block_bwd.argtypes = [C.POINTER(_Cfg), vp, vp, C.POINTER(_Weights), vp, vp, C.POINTER(_Grads), i32,
                                vp, sz, vp]
+    L.t5_decoder_block_stash_bytes.restype = sz
+    L.t5_decoder_block_stash_bytes.argtypes = [C.POINTER(_Cfg), C.c_int32]
+    L.t5_decoder_block_workspace_bytes.restype = sz
+    L.t5_decoder_block_workspace_bytes.argtypes = [C.POINTER(_Cfg), C.c_int32]
+    L.t5_decoder_block_fwd.restype = i32
+    L.t5_decoder_block_fwd.argtypes = [C.POINTER(_Cfg), C.c_int32, vp, vp, C.POINTER(_Weights),
+                                       C.POINTER(_CrossWeights), vp, vp, vp, sz, vp]
+    L.t5_decoder_block_bwd.restype = i32
+    L.t5_decoder_block_bwd.argtypes = [C.POINTER(_Cfg), C.c_int32, vp, vp, vp, C.POINTER(_Weights),
+                                       C.POINTER(_CrossWeights), vp, vp, vp, C.POINTER(_Grads),
+                                       C.POINTER(_CrossGrads), i32, vp, sz, vp]
     L.adafactor_workspace_bytes.restype = sz
     L.adafactor_workspace_bytes.argtypes = [i64, i64, i32]
     L.adafactor_step.restype = i32
@@ -208,6 +228,89 @@ def t5_block_bwd(cfg, dy, x, weights, stash, dx=None, grads=None, accumulate=Fal
     if rc:
         raise T5Error(rc, "t5_block_bwd")
     return dx, grads
+
+
+def t5_decoder_block_stash_bytes(cfg) -> int:
+    return int(lib().t5_decoder_block_stash_bytes(C.byref(_cfg_struct(cfg)), int(cfg.enc_seq)))
+
+
+def t5_decoder_block_workspace_bytes(cfg) -> int:
+    return int(lib().t5_decoder_block_workspace_bytes(C.byref(_cfg_struct(cfg)), int(cfg.enc_seq)))
+
+
+def _cross_weights_struct(cfg, weights) -> _CrossWeights:
+    dt = _torch_dtype(cfg)
+    inner = cfg.n_heads * cfg.d_kv
+    shapes = {"lnx_scale": cfg.d_model, "xq": cfg.d_model * inner, "xk": cfg.d_model * inner,
+              "xv": cfg.d_model * inner, "xo": inner * cfg.d_model}
+    for n in CROSS_WEIGHT_NAMES:
+        _check_tensor(weights[n], dt, shapes[n], n)
+    return _CrossWeights(*[weights[n].data_ptr() for n in CROSS_WEIGHT_NAMES])
+
+
+def t5_decoder_block_fwd(cfg, x, enc, weights, y=None, stash=None, workspace=None):
+    """Decoder layer with cross-attention over enc [batch, cfg.enc_seq, d_model].  weights holds the
+    block's ten tensors and the five cross-attention tensors.  Returns (y, stash)."""
+    cs = _cfg_struct(cfg)
+    dt = _torch_dtype(cfg)
+    n = cfg.batch * cfg.seq * cfg.d_model
+    _check_tensor(x, dt, n, "x")
+    _check_tensor(enc, dt, cfg.batch * cfg.enc_seq * cfg.d_model, "enc")
+    ws = _weights_struct(cfg, weights)
+    xs = _cross_weights_struct(cfg, weights)
+    if y is None:
+        y = torch.empty_like(x)
+    _check_tensor(y, dt, n, "y")
+    es = int(cfg.enc_seq)
+    if stash is None:
+        stash = _byte_buffer(lib().t5_decoder_block_stash_bytes(C.byref(cs), es), x.device)
+    if workspace is None:
+        workspace = _byte_buffer(lib().t5_decoder_block_workspace_bytes(C.byref(cs), es), x.device)
+    rc = lib().t5_decoder_block_fwd(C.byref(cs), es, _ptr(x), _ptr(enc), C.byref(ws), C.byref(xs), _ptr(y),
+                                    _ptr(stash), _ptr(workspace), workspace.numel(), _stream())
+    if rc:
+        raise T5Error(rc, "t5_decoder_block_fwd")
+    return y, stash
+
+
+def alloc_decoder_grads(cfg, weights) -> dict:
+    return {n: torch.zeros(weights[n].shape, dtype=torch.float32, device=weights[n].device)
+            for n in WEIGHT_NAMES + CROSS_WEIGHT_NAMES}
+
+
+def t5_decoder_block_bwd(cfg, dy, x, enc, weights, stash, dx=None, denc=None, grads=None, accumulate=False,
+                         workspace=None):
+    """Returns (dx, denc, grads); grads is a dict of float32 tensors shaped like the fifteen weights."""
+    cs = _cfg_struct(cfg)
+    dt = _torch_dtype(cfg)
+    n = cfg.batch * cfg.seq * cfg.d_model
+    ne = cfg.batch * cfg.enc_seq * cfg.d_model
+    _check_tensor(dy, dt, n, "dy")
+    _check_tensor(x, dt, n, "x")
+    _check_tensor(enc, dt, ne, "enc")
+    ws = _weights_struct(cfg, weights)
+    xs = _cross_weights_struct(cfg, weights)
+    if dx is None:
+        dx = torch.empty_like(dy)
+    if denc is None:
+        denc = torch.empty_like(enc)
+    _check_tensor(dx, dt, n, "dx")
+    _check_tensor(denc, dt, ne, "denc")
+    if grads is None:
+        grads = alloc_decoder_grads(cfg, weights)
+    for nme in WEIGHT_NAMES + CROSS_WEIGHT_NAMES:
+        _check_tensor(grads[nme], torch.float32, weights[nme].numel(), "grad " + nme)
+    gs = _Grads(*[grads[nme].data_ptr() for nme in WEIGHT_NAMES])
+    gx = _CrossGrads(*[grads[nme].data_ptr() for nme in CROSS_WEIGHT_NAMES])
+    es = int(cfg.enc_seq)
+    if workspace is None:
+        workspace = _byte_buffer(lib().t5_decoder_block_workspace_bytes(C.byref(cs), es), x.device)
+    rc = lib().t5_decoder_block_bwd(C.byref(cs), es, _ptr(dy), _ptr(x), _ptr(enc), C.byref(ws), C.byref(xs),
+                                    _ptr(stash), _ptr(dx), _ptr(denc), C.byref(gs), C.byref(gx),
+                                    int(bool(accumulate)), _ptr(workspace), workspace.numel(), _stream())
+    if rc:
+        raise T5Error(rc, "t5_decoder_block_bwd")
+    return dx, denc, grads
 
 
 def adafactor_workspace_bytes(rows: int, cols: int, factored: bool) -> int:

@@ -1,5 +1,6 @@
-// Fused self-attention with the T5 relative-position bias for gfx950 (bf16 MFMA 32x32x16,
-// float32 online softmax).  The S x S scores never leave registers.
+// Fused attention for gfx950 (bf16 MFMA 32x32x16, float32 online softmax): self-attention with the
+// T5 relative-position bias (BIAS, optionally CAUSAL), or cross-attention of S queries over Sk keys
+// of another sequence without bias or mask.  The S x Sk scores never leave registers.
 //
 // Forward and the dq kernel give each lane one query: scores are computed transposed,
 // S^T = K Q^T, so the MFMA result layout puts a query in lane%32 and 16 keys of a 32-key tile in
@@ -173,20 +174,19 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // ------------------------------------------------------------------------------------------------
 // Forward.  grid (ceil(S/128), H, B), 256 threads; wave w owns queries i0 + 32w + lane%32.
 // ------------------------------------------------------------------------------------------------
-template <int DK, bool CAUSAL>
-__global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv,
-                                                            const float* __restrict__ diag,
+template <int DK, bool CAUSAL, bool BIAS>
+__global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnIO io, const float* __restrict__ diag,
                                                             bf16* __restrict__ c, float* __restrict__ lse,
                                                             AttnDims a) {
   constexpr int BR = 128, BC = 64, KS = DK / 16, CT = DK / 32;
   constexpr int TILE = BC * DK * 2, STG = 2 * TILE;  // a stage holds a K tile then a V tile
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  float* dg = reinterpret_cast<float*>(smem + 2 * STG);  // [S + BR - 1], log2 units
+  float* dg = reinterpret_cast<float*>(smem + 2 * STG);  // [S + BR - 1], log2 units (BIAS only)
 
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int S = a.S, I = a.H * DK;
-  const size_t ld = (size_t)3 * I;
+  const int S = a.S, Sk = a.Sk, I = a.H * DK;
+  const size_t ldq = (size_t)io.ldq, ld = (size_t)io.ldkv;
   int qt, h, b;
   decode_block(S / BR, a.H, a.B, qt, h, b);
   if (CAUSAL) qt = S / BR - 1 - qt;  // heavy causal tiles first
@@ -194,15 +194,16 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
   const int i_loc = wave * 32 + (lane & 31);
   const int i = i0 + i_loc;
   const int i_ld = i < S ? i : S - 1;
-  const bf16* base = qkv + (size_t)b * S * ld + h * DK;
+  const bf16* kbase = (const bf16*)io.k + (size_t)b * Sk * ld + h * DK;
+  const bf16* vbase = (const bf16*)io.v + (size_t)b * Sk * ld + h * DK;
 
   bf16x8 qf[KS];
   {
-    const bf16* qrow = base + (size_t)i_ld * ld;
+    const bf16* qrow = (const bf16*)io.q + ((size_t)b * S + i_ld) * ldq + h * DK;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qrow + kk * 16 + g * 8);
   }
-  {
+  if constexpr (BIAS) {
     const float* dgh = diag + (size_t)h * (2 * S - 1);
     fill_bias_slice(dg, dgh, S + BR - 1, tid, [&](int t) {
       const int idx = t - (i0 + BR - 1) + (S - 1);  // delta + S - 1
@@ -219,7 +220,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
     for (int r = 0; r < 16; ++r) oT[ct][r] = 0.f;
   float m = -INFINITY, l = 0.f;
 
-  int n_kv = S / BC;
+  int n_kv = Sk / BC;
   if (CAUSAL) {
     const int last = (i0 + BR < S ? i0 + BR : S);
     n_kv = (last + BC - 1) / BC;
@@ -228,15 +229,15 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
   TileDma<DK, BC> td;
   td.init(wave, lane, ld);
   const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)smem;
-  td.issue(lds0, base + I, wave);
-  td.issue(lds0 + TILE, base + 2 * I, wave);
+  td.issue(lds0, kbase, wave);
+  td.issue(lds0 + TILE, vbase, wave);
   for (int jt = 0; jt < n_kv; ++jt) {
     const int j0 = jt * BC;
     dma_wait_barrier();  // tile jt landed; every wave is done with the other stage
     if (jt + 1 < n_kv) {
       const uint32_t nxt = lds0 + ((jt + 1) & 1) * STG;
-      td.issue(nxt, base + (size_t)(j0 + BC) * ld + I, wave);
-      td.issue(nxt + TILE, base + (size_t)(j0 + BC) * ld + 2 * I, wave);
+      td.issue(nxt, kbase + (size_t)(j0 + BC) * ld, wave);
+      td.issue(nxt + TILE, vbase + (size_t)(j0 + BC) * ld, wave);
     }
     const char* Kt = smem + (jt & 1) * STG;
     const char* Vt = Kt + TILE;
@@ -257,7 +258,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int j = j0 + kt * 32 + ((r >> 2) << 3) + (g << 2) + (r & 3);
-        float s = fmaf(sT[kt][r], sc, dg[dg_base + j]);
+        float s = BIAS ? fmaf(sT[kt][r], sc, dg[dg_base + j]) : sT[kt][r] * sc;
         if (CAUSAL && j > i) s = -INFINITY;
         sT[kt][r] = s;
         mx = fmaxf(mx, s);
@@ -351,13 +352,13 @@ __global__ __launch_bounds__(256) void attn_dvec_kernel(const bf16* __restrict__
 // every offset lies in the saturated last bucket (|delta| >= far) skip all that and add into one
 // scalar per lane; it is credited to the outermost diagonal, which is in the same bucket.
 // ------------------------------------------------------------------------------------------------
-template <int DK, bool CAUSAL>
-__global__ __launch_bounds__(256, DK == 64 ? 3 : 2) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv,
+template <int DK, bool CAUSAL, bool BIAS>
+__global__ __launch_bounds__(256, DK == 64 ? 3 : 2) void attn_bwd_dq_mfma_kernel(AttnIO io,
                                                                const bf16* __restrict__ dout,
                                                                const float* __restrict__ diag,
                                                                const float* __restrict__ lse,
                                                                const float* __restrict__ dvec,
-                                                               bf16* __restrict__ dqkv, float* __restrict__ ddiag,
+                                                               float* __restrict__ ddiag,
                                                                AttnDims a, int far) {
   constexpr int BR = 128, BC = 64, KS = DK / 16, CT = DK / 32;
   constexpr int TILE = BC * DK * 2, STG = 2 * TILE;  // a stage holds a K tile then a V tile
@@ -366,13 +367,13 @@ __global__ __launch_bounds__(256, DK == 64 ? 3 : 2) void attn_bwd_dq_mfma_kernel
   // Diagonal windows [4 waves][2 lane halves][W].  A sub-tile at key offset j0s - i_w0 = 32 m from
   // the wave's queries is resolved per diagonal for |m| <= nb; its slot u (0..62) lives at
   // (m + nb) * 32 + u, which is diagonal delta = 32 m + u - 31 (+ 4 for the upper lane half).
-  const int nb = attn_dq_window_blocks(a.S, far), W = 32 * (2 * nb + 2);
+  const int nb = BIAS ? attn_dq_window_blocks(a.S, far) : 0, W = 32 * (2 * nb + 2);
   float* ddg_all = dg + (a.S + BR - 1);
 
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int S = a.S, I = a.H * DK;
-  const size_t ld = (size_t)3 * I;
+  const int S = a.S, Sk = a.Sk, I = a.H * DK;
+  const size_t ldq = (size_t)io.ldq, ld = (size_t)io.ldkv;
   int qt, h, b;
   decode_block(S / BR, a.H, a.B, qt, h, b);
   if (CAUSAL) qt = S / BR - 1 - qt;
@@ -381,12 +382,13 @@ __global__ __launch_bounds__(256, DK == 64 ? 3 : 2) void attn_bwd_dq_mfma_kernel
   const int i_lw = lane & 31;              // query index inside the wave
   const int i_loc = wave * 32 + i_lw;
   const int i = i0 + i_loc;
-  const bf16* base = qkv + (size_t)b * S * ld + h * DK;
+  const bf16* kbase = (const bf16*)io.k + (size_t)b * Sk * ld + h * DK;
+  const bf16* vbase = (const bf16*)io.v + (size_t)b * Sk * ld + h * DK;
   float* ddgw = ddg_all + (wave * 2 + g) * W + (31 - i_lw);  // this lane's first slot of block m = -nb
 
   bf16x8 qf[KS], dof[KS];
   {
-    const bf16* qrow = base + (size_t)i * ld;
+    const bf16* qrow = (const bf16*)io.q + ((size_t)b * S + i) * ldq + h * DK;
     const bf16* drow = dout + ((size_t)b * S + i) * I + h * DK;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
@@ -396,7 +398,7 @@ __global__ __launch_bounds__(256, DK == 64 ? 3 : 2) void attn_bwd_dq_mfma_kernel
   }
   const size_t srow = ((size_t)b * a.H + h) * S + i;
   const float nlse2 = -lse[srow] * kLog2e, ndv = -dvec[srow];
-  {
+  if constexpr (BIAS) {
     const float* dgh = diag + (size_t)h * (2 * S - 1);
     fill_bias_slice(dg, dgh, S + BR - 1, tid, [&](int t) { return t - (i0 + BR - 1) + (S - 1); });
     for (int t = tid; t < 8 * W; t += 256) ddg_all[t] = 0.f;
@@ -411,19 +413,19 @@ __global__ __launch_bounds__(256, DK == 64 ? 3 : 2) void attn_bwd_dq_mfma_kernel
 #pragma unroll
     for (int r = 0; r < 16; ++r) dqT[ct][r] = 0.f;
 
-  const int n_kv = CAUSAL ? (i0 + BR) / BC : S / BC;
+  const int n_kv = CAUSAL ? (i0 + BR) / BC : Sk / BC;
   TileDma<DK, BC> td;
   td.init(wave, lane, ld);
   const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)smem;
-  td.issue(lds0, base + I, wave);
-  td.issue(lds0 + TILE, base + 2 * I, wave);
+  td.issue(lds0, kbase, wave);
+  td.issue(lds0 + TILE, vbase, wave);
   for (int jt = 0; jt < n_kv; ++jt) {
     const int j0 = jt * BC;
     dma_wait_barrier();  // tile jt landed; every wave is done with the other stage
     if (jt + 1 < n_kv) {
       const uint32_t nxt = lds0 + ((jt + 1) & 1) * STG;
-      td.issue(nxt, base + (size_t)(j0 + BC) * ld + I, wave);
-      td.issue(nxt + TILE, base + (size_t)(j0 + BC) * ld + 2 * I, wave);
+      td.issue(nxt, kbase + (size_t)(j0 + BC) * ld, wave);
+      td.issue(nxt + TILE, vbase + (size_t)(j0 + BC) * ld, wave);
     }
     const char* Kt = smem + (jt & 1) * STG;
     const char* Vt = Kt + TILE;
@@ -436,9 +438,11 @@ __global__ __launch_bounds__(256, DK == 64 ? 3 : 2) void attn_bwd_dq_mfma_kernel
       // MFMA operands as well, or seeding the accumulators with -lse and -dvec, costs more registers
       // than the third wave per SIMD they displace is worth (measured).
       float bias[16];
+      if constexpr (BIAS) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) bias[r] = dg[dg_base + j0s + ((r >> 2) << 3) + (g << 2) + (r & 3)];
-      __builtin_amdgcn_sched_barrier(0);
+        for (int r = 0; r < 16; ++r) bias[r] = dg[dg_base + j0s + ((r >> 2) << 3) + (g << 2) + (r & 3)];
+        __builtin_amdgcn_sched_barrier(0);
+      }
       f32x16 sT, dpT;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { sT[r] = 0.f; dpT[r] = 0.f; }
@@ -450,12 +454,13 @@ __global__ __launch_bounds__(256, DK == 64 ? 3 : 2) void attn_bwd_dq_mfma_kernel
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int j = j0s + ((r >> 2) << 3) + (g << 2) + (r & 3);
-        float p = fast_exp2(fmaf(sT[r], sc, bias[r]) + nlse2);
+        float p = BIAS ? fast_exp2(fmaf(sT[r], sc, bias[r]) + nlse2) : fast_exp2(fmaf(sT[r], sc, nlse2));
         if (CAUSAL && j > i) p = 0.f;
         sT[r] = p * (dpT[r] + ndv);
       }
       // ---- bias gradient of this 32x32 sub-tile (wave-uniform branches)
-      if (j0s + 31 - i_w0 <= -far) {
+      if constexpr (!BIAS) {
+      } else if (j0s + 31 - i_w0 <= -far) {
         float t = 0.f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) t += sT[r];
@@ -483,7 +488,7 @@ __global__ __launch_bounds__(256, DK == 64 ? 3 : 2) void attn_bwd_dq_mfma_kernel
     }
   }
   {
-    bf16* qrow = dqkv + ((size_t)b * S + i) * ld + h * DK;
+    bf16* qrow = (bf16*)io.dq + ((size_t)b * S + i) * (size_t)io.lddq + h * DK;
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
@@ -494,6 +499,7 @@ __global__ __launch_bounds__(256, DK == 64 ? 3 : 2) void attn_bwd_dq_mfma_kernel
         *reinterpret_cast<bf16x4*>(qrow + ct * 32 + rq * 8 + g * 4) = o;
       }
   }
+  if constexpr (!BIAS) return;
   // ---- flush: add the eight windows up (the upper lane half's diagonals sit 4 higher) and issue one
   // global atomic per diagonal of this workgroup
   float* ddh = ddiag + (size_t)h * (2 * S - 1);
@@ -520,15 +526,15 @@ __global__ __launch_bounds__(256, DK == 64 ? 3 : 2) void attn_bwd_dq_mfma_kernel
 }
 
 // ------------------------------------------------------------------------------------------------
-// dk and dv.  grid (ceil(S/128), H, B); wave w owns keys j0 + 32w + lane%32; loops over query tiles.
+// dk and dv.  grid (Sk/128) * H * B; wave w owns keys j0 + 32w + lane%32; loops over query tiles.
 // ------------------------------------------------------------------------------------------------
-template <int DK, bool CAUSAL>
-__global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kernel(const bf16* __restrict__ qkv,
+template <int DK, bool CAUSAL, bool BIAS>
+__global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kernel(AttnIO io,
                                                                 const bf16* __restrict__ dout,
                                                                 const float* __restrict__ diag,
                                                                 const float* __restrict__ lse,
                                                                 const float* __restrict__ dvec,
-                                                                bf16* __restrict__ dqkv, AttnDims a) {
+                                                                AttnDims a) {
   constexpr int BCK = 128, BQ = 64, KS = DK / 16, CT = DK / 32;
   constexpr int TILE = BQ * DK * 2, STG = 2 * TILE;  // a stage holds a Q tile then a dO tile
   extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -536,31 +542,32 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
   // already (s - lse/scale) and (dP - dvec): no per-element subtraction afterwards.
   float* lse_all = reinterpret_cast<float*>(smem + 2 * STG);  // [2 stages][BQ]  -lse / scale
   float* dv_all = lse_all + 2 * BQ;                           // [2 stages][BQ]  -dvec
-  float* dg = dv_all + 2 * BQ;                                // [S + BCK - 1] log2 units
+  float* dg = dv_all + 2 * BQ;                                // [S + BCK - 1] log2 units (BIAS only)
 
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int S = a.S, I = a.H * DK;
-  const size_t ld = (size_t)3 * I;
+  const int S = a.S, Sk = a.Sk, I = a.H * DK;
+  const size_t ld = (size_t)io.ldq, ldkv = (size_t)io.ldkv;
   int kt_, h, b;
-  decode_block(S / BCK, a.H, a.B, kt_, h, b);
+  decode_block(Sk / BCK, a.H, a.B, kt_, h, b);
   const int j0 = kt_ * BCK;
   const int j_loc = wave * 32 + (lane & 31);
   const int j = j0 + j_loc;
-  const int j_ld = j < S ? j : S - 1;
-  const bf16* base = qkv + (size_t)b * S * ld + h * DK;
+  const int j_ld = j < Sk ? j : Sk - 1;
+  const bf16* base = (const bf16*)io.q + (size_t)b * S * ld + h * DK;
   const bf16* dobase = dout + (size_t)b * S * I + h * DK;
 
   bf16x8 kf[KS], vf[KS];
   {
-    const bf16* krow = base + (size_t)j_ld * ld + I;
+    const bf16* krow = (const bf16*)io.k + ((size_t)b * Sk + j_ld) * ldkv + h * DK;
+    const bf16* vrow = (const bf16*)io.v + ((size_t)b * Sk + j_ld) * ldkv + h * DK;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
       kf[kk] = *reinterpret_cast<const bf16x8*>(krow + kk * 16 + g * 8);
-      vf[kk] = *reinterpret_cast<const bf16x8*>(krow + I + kk * 16 + g * 8);
+      vf[kk] = *reinterpret_cast<const bf16x8*>(vrow + kk * 16 + g * 8);
     }
   }
-  {
+  if constexpr (BIAS) {
     // dg[t] = bias(delta) for delta = t + j0 - (S - 1), t in [0, S + BCK - 1)
     const float* dgh = diag + (size_t)h * (2 * S - 1);
     for (int t = tid; t < S + BCK - 1; t += 256) {
@@ -617,7 +624,7 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
       // is hidden behind the matrix work instead of stalling the softmax arithmetic
       // (done for 128 channels, where one wave per SIMD leaves nothing else to hide it; with 64
       // channels the extra live registers would cost the third wave per SIMD, which hides more)
-      constexpr bool HOIST = DK == 128;
+      constexpr bool HOIST = BIAS && DK == 128;
       float bias[16];
       if constexpr (HOIST) {
 #pragma unroll
@@ -642,7 +649,7 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
       for (int r = 0; r < 16; ++r) {
         const int il = qb * 32 + ((r >> 2) << 3) + (g << 2) + (r & 3);
         const int i = q0 + il;
-        float p = fast_exp2(fmaf(s[r], sc, HOIST ? bias[r] : dg[j_loc + (S - 1 - i)]));
+        float p = BIAS ? fast_exp2(fmaf(s[r], sc, HOIST ? bias[r] : dg[j_loc + (S - 1 - i)])) : fast_exp2(s[r] * sc);
         if (CAUSAL && j > i) p = 0.f;
         s[r] = p;
         dp[r] = p * dp[r];
@@ -664,8 +671,9 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
       dv_all[(st ^ 1) * BQ + tid] = nd;
     }
   }
-  if (j < S) {
-    bf16* krow = dqkv + ((size_t)b * S + j) * ld + I + h * DK;
+  if (j < Sk) {
+    bf16* krow = (bf16*)io.dk + ((size_t)b * Sk + j) * (size_t)io.lddkv + h * DK;
+    bf16* vrow = (bf16*)io.dv + ((size_t)b * Sk + j) * (size_t)io.lddkv + h * DK;
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
@@ -677,12 +685,13 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
           ov[e] = (bf16)dvT[ct][rq * 4 + e];
         }
         *reinterpret_cast<bf16x4*>(krow + ct * 32 + rq * 8 + g * 4) = ok;
-        *reinterpret_cast<bf16x4*>(krow + I + ct * 32 + rq * 8 + g * 4) = ov;
+        *reinterpret_cast<bf16x4*>(vrow + ct * 32 + rq * 8 + g * 4) = ov;
       }
   }
 }
 
 size_t attn_bwd_dq_lds_bytes(const AttnDims& a, int far) {
+  if (!a.bias) return (size_t)4 * 64 * a.dk * 2;
   const int W = 32 * (2 * attn_dq_window_blocks(a.S, far) + 2);
   return (size_t)4 * 64 * a.dk * 2 + sizeof(float) * ((size_t)(a.S + 127) + 8 * (size_t)W);
 }
@@ -692,42 +701,44 @@ hipError_t set_lds(K kern, size_t bytes) {
   return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
-template <int DK, bool CAUSAL>
-hipError_t fwd_launch(const void* qkv, const float* diag, void* c, float* lse, const AttnDims& a, hipStream_t st) {
-  auto kern = attn_fwd_mfma_kernel<DK, CAUSAL>;
-  const size_t lds = 4 * 64 * DK * 2 + sizeof(float) * (a.S + 127);
+template <int DK, bool CAUSAL, bool BIAS>
+hipError_t fwd_launch(const AttnIO& io, const float* diag, void* c, float* lse, const AttnDims& a, hipStream_t st) {
+  auto kern = attn_fwd_mfma_kernel<DK, CAUSAL, BIAS>;
+  const size_t lds = 4 * 64 * DK * 2 + (BIAS ? sizeof(float) * (a.S + 127) : 0);
   hipError_t e = set_lds(kern, lds);
   if (e != hipSuccess) return e;
-  kern<<<dim3((a.S / 128) * a.H * a.B), 256, lds, st>>>((const bf16*)qkv, diag, (bf16*)c, lse, a);
+  kern<<<dim3((a.S / 128) * a.H * a.B), 256, lds, st>>>(io, diag, (bf16*)c, lse, a);
   return hipGetLastError();
 }
 
-template <int DK, bool CAUSAL>
-hipError_t bwd_launch(const void* qkv, const void* c, const void* dc, const float* diag, const float* lse,
-                      float* dvec, void* dqkv, float* ddiag, const AttnDims& a, int far, int phase, hipStream_t st) {
+template <int DK, bool CAUSAL, bool BIAS>
+hipError_t bwd_launch(const AttnIO& io, const void* c, const void* dc, const float* diag, const float* lse,
+                      float* dvec, float* ddiag, const AttnDims& a, int far, int phase, hipStream_t st) {
   hipError_t e = hipSuccess;
   if (phase == 0) {
-  const int64_t rows = (int64_t)a.B * a.S * a.H;
-  attn_dvec_kernel<DK><<<ceil_div(rows * (DK / 8), 256), 256, 0, st>>>((const bf16*)c, (const bf16*)dc, dvec, a);
-  return hipGetLastError();
+    const int64_t rows = (int64_t)a.B * a.S * a.H;
+    attn_dvec_kernel<DK><<<ceil_div(rows * (DK / 8), 256), 256, 0, st>>>((const bf16*)c, (const bf16*)dc, dvec, a);
+    return hipGetLastError();
   }
-  const dim3 grid((a.S / 128) * a.H * a.B);
   if (phase == 1) {
-    auto kern = attn_bwd_dq_mfma_kernel<DK, CAUSAL>;
+    auto kern = attn_bwd_dq_mfma_kernel<DK, CAUSAL, BIAS>;
     const size_t lds = attn_bwd_dq_lds_bytes(a, far);
     if ((e = set_lds(kern, lds)) != hipSuccess) return e;
-    kern<<<grid, 256, lds, st>>>((const bf16*)qkv, (const bf16*)dc, diag, lse, dvec, (bf16*)dqkv, ddiag, a, far);
+    kern<<<dim3((a.S / 128) * a.H * a.B), 256, lds, st>>>(io, (const bf16*)dc, diag, lse, dvec, ddiag, a, far);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (phase == 2) {
-    auto kern = attn_bwd_dkv_mfma_kernel<DK, CAUSAL>;
-    const size_t lds = 4 * 64 * DK * 2 + sizeof(float) * (256 + a.S + 127);
+    auto kern = attn_bwd_dkv_mfma_kernel<DK, CAUSAL, BIAS>;
+    const size_t lds = 4 * 64 * DK * 2 + sizeof(float) * (256 + (BIAS ? a.S + 127 : 0));
     if ((e = set_lds(kern, lds)) != hipSuccess) return e;
-    kern<<<grid, 256, lds, st>>>((const bf16*)qkv, (const bf16*)dc, diag, lse, dvec, (bf16*)dqkv, a);
+    kern<<<dim3((a.Sk / 128) * a.H * a.B), 256, lds, st>>>(io, (const bf16*)dc, diag, lse, dvec, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   return hipSuccess;
 }
+
+// 0: self-attention with bias, 1: the same with the causal mask, 2: cross-attention (no bias, no mask)
+int attn_mode(const AttnDims& a) { return a.bias ? (a.causal ? 1 : 0) : 2; }
 
 }  // namespace
 
@@ -737,31 +748,44 @@ bool attn_bwd_mfma_fits(const AttnDims& a, int far) {
 }
 
 bool attn_mfma_supported(const AttnDims& a) {
-  // S % 128: query/key tiles of 128 without ragged edges; LDS holds the diagonal slice (S + 127 floats)
-  return (a.dk == 64 || a.dk == 128) && a.S % 128 == 0 && a.S <= 8192;
+  // S, Sk % 128: query/key tiles of 128 without ragged edges; LDS holds the diagonal slice (S + 127
+  // floats).  Without the bias only the unmasked form exists; bias and mask need square scores.
+  if (!(a.dk == 64 || a.dk == 128) || a.S % 128 != 0 || a.Sk % 128 != 0 || a.S > 8192 || a.Sk > 65536) return false;
+  if (a.bias) return a.Sk == a.S;
+  return !a.causal;
 }
 
-hipError_t launch_attn_fwd_mfma(const void* qkv, const float* diag, void* c, float* lse, const AttnDims& a,
+hipError_t launch_attn_fwd_mfma(const AttnIO& io, const float* diag, void* c, float* lse, const AttnDims& a,
                                 hipStream_t st) {
-  if (a.dk == 64) return a.causal ? fwd_launch<64, true>(qkv, diag, c, lse, a, st)
-                                  : fwd_launch<64, false>(qkv, diag, c, lse, a, st);
-  return a.causal ? fwd_launch<128, true>(qkv, diag, c, lse, a, st)
-                  : fwd_launch<128, false>(qkv, diag, c, lse, a, st);
+  if (!attn_mfma_supported(a)) return hipErrorInvalidValue;
+  const int mode = attn_mode(a);
+  if (a.dk == 64) {
+    if (mode == 0) return fwd_launch<64, false, true>(io, diag, c, lse, a, st);
+    if (mode == 1) return fwd_launch<64, true, true>(io, diag, c, lse, a, st);
+    return fwd_launch<64, false, false>(io, diag, c, lse, a, st);
+  }
+  if (mode == 0) return fwd_launch<128, false, true>(io, diag, c, lse, a, st);
+  if (mode == 1) return fwd_launch<128, true, true>(io, diag, c, lse, a, st);
+  return fwd_launch<128, false, false>(io, diag, c, lse, a, st);
 }
 
-size_t attn_bwd_mfma_scratch_bytes(const AttnDims&) { return 0; }
-
-hipError_t launch_attn_bwd_mfma(const void* qkv, const void* c, const void* dc, const float* diag,
-                                const float* lse, float* dvec, void* dqkv, float* ddiag, void*,
-                                const AttnDims& a, int far, int phase, hipStream_t st) {
+hipError_t launch_attn_bwd_mfma(const AttnIO& io, const void* c, const void* dc, const float* diag,
+                                const float* lse, float* dvec, float* ddiag, const AttnDims& a, int far,
+                                int phase, hipStream_t st) {
   // phase 0: dvec = rowsum(dO * O); phase 1: dq + bias-gradient diagonals (added into ddiag); phase 2: dk, dv.
   // `far`: smallest distance that falls in the last (saturated) bucket; such offsets need no
   // per-diagonal resolution.  Never below 1, so offset 0 always takes the per-diagonal path.
+  if (!attn_mfma_supported(a)) return hipErrorInvalidValue;
   if (far < 1) far = 1;
-  if (a.dk == 64) return a.causal ? bwd_launch<64, true>(qkv, c, dc, diag, lse, dvec, dqkv, ddiag, a, far, phase, st)
-                                  : bwd_launch<64, false>(qkv, c, dc, diag, lse, dvec, dqkv, ddiag, a, far, phase, st);
-  return a.causal ? bwd_launch<128, true>(qkv, c, dc, diag, lse, dvec, dqkv, ddiag, a, far, phase, st)
-                  : bwd_launch<128, false>(qkv, c, dc, diag, lse, dvec, dqkv, ddiag, a, far, phase, st);
+  const int mode = attn_mode(a);
+  if (a.dk == 64) {
+    if (mode == 0) return bwd_launch<64, false, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
+    if (mode == 1) return bwd_launch<64, true, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
+    return bwd_launch<64, false, false>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
+  }
+  if (mode == 0) return bwd_launch<128, false, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
+  if (mode == 1) return bwd_launch<128, true, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
+  return bwd_launch<128, false, false>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
 }
 
 }  // namespace t5mi

@@ -193,7 +193,7 @@ hipError_t launch_geglu_fwd(void* u, void* w, void* a, int type, int64_t n, hipS
 }
 
 hipError_t launch_pack_transpose_multi(const PackJobs& jobs, hipStream_t st) {
-  if (jobs.count < 1 || jobs.count > 4) return hipErrorInvalidValue;
+  if (jobs.count < 1 || jobs.count > 8) return hipErrorInvalidValue;
   int gx = 0, gy = 0;
   for (int q = 0; q < jobs.count; ++q) {
     const PackJob& jb = jobs.j[q];

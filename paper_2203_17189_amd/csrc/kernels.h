@@ -75,11 +75,12 @@ hipError_t launch_gemm_simple(const GemmDesc& g, const GemmEpi& e, hipStream_t s
 bool gemm_mfma_supported(const GemmDesc& g, const GemmEpi& e);
 hipError_t launch_gemm_mfma(const GemmDesc& g, const GemmEpi& e, hipStream_t st);
 
-// Sets up to 8 float arrays to zero in one launch (the weight gradients, before the split-k GEMMs add
+// Sets up to 12 float arrays to zero in one launch (the weight gradients, before the split-k GEMMs add
 // their partial sums into them, and the bias-gradient diagonals).
+constexpr int ZERO_MAX = 12;
 struct ZeroList {
-  float* p[8];
-  int64_t n[8];
+  float* p[ZERO_MAX];
+  int64_t n[ZERO_MAX];
   int count;
 };
 hipError_t launch_zero_f32(const ZeroList& z, hipStream_t st);
@@ -89,14 +90,14 @@ hipError_t launch_zero_f32(const ZeroList& z, hipStream_t st);
 // (n / interleave) % nsrc and column (n / (interleave*nsrc)) * interleave + n % interleave.
 hipError_t launch_pack_transpose_bf16(const void* const* srcs, int nsrc, int K, int n_each, void* dst,
                                       int interleave, hipStream_t st);
-// Up to four such packs in one launch.
+// Up to eight such packs in one launch.
 struct PackJob {
   const void* src[3];
   int nsrc, K, n_each, interleave;
   void* dst;
 };
 struct PackJobs {
-  PackJob j[4];
+  PackJob j[8];
   int count;
 };
 hipError_t launch_pack_transpose_multi(const PackJobs& jobs, hipStream_t st);
@@ -106,31 +107,52 @@ hipError_t launch_pack_transpose_multi(const PackJobs& jobs, hipStream_t st);
 hipError_t launch_geglu_fwd(void* u, void* w, void* a, int type, int64_t n, hipStream_t st);
 
 // ------------------------------------------------------------------ attention
+// Queries: S per batch element; keys/values: Sk per batch element (Sk == S for self-attention).
+// bias: add the relative-position bias diag[h][j - i + S - 1] (needs Sk == S); causal needs Sk == S.
 struct AttnDims {
   int B, S, H, dk;
   int causal;
   float scale;
+  int Sk;
+  int bias;
 };
-// qkv: [T, 3*H*dk] (q | k | v per token).  c: [T, H*dk].  lse: [B,H,S] float32.  diag: [H, 2S-1].
-hipError_t launch_attn_fwd_simple(const void* qkv, int type, const float* diag, void* c, float* lse,
+// Operand placement.  Row (b*S + i) of q / dq starts at q + row*ldq, row (b*Sk + j) of k, v / dk, dv at
+// k + row*ldkv; head h occupies channels h*dk .. h*dk + dk - 1 of a row.  Element counts, not bytes.
+struct AttnIO {
+  const void *q, *k, *v;
+  int ldq, ldkv;
+  void *dq, *dk, *dv;
+  int lddq, lddkv;
+};
+// q | k | v packed per token: qkv [T, 3*I], dqkv likewise (either may be null when unused).
+inline AttnIO attn_io_packed(const void* qkv, void* dqkv, int I, size_t es) {
+  AttnIO io;
+  io.q = qkv; io.k = (const char*)qkv + (size_t)I * es; io.v = (const char*)qkv + (size_t)2 * I * es;
+  io.ldq = io.ldkv = 3 * I;
+  io.dq = dqkv; io.dk = dqkv ? (char*)dqkv + (size_t)I * es : nullptr;
+  io.dv = dqkv ? (char*)dqkv + (size_t)2 * I * es : nullptr;
+  io.lddq = io.lddkv = 3 * I;
+  return io;
+}
+// c: [B*S, H*dk].  lse: [B,H,S] float32.  diag: [H, 2S-1] (unused without bias).
+hipError_t launch_attn_fwd_simple(const AttnIO& io, int type, const float* diag, void* c, float* lse,
                                   const AttnDims& a, hipStream_t st);
-// dc: [T, H*dk] gradient of c.  Writes dqkv [T, 3*H*dk], dvec [B,H,S] (scratch), ddiag [H, 2S-1]
-// float32 (zeroed inside).
-hipError_t launch_attn_bwd_simple(const void* qkv, const void* c, const void* dc, int type,
-                                  const float* diag, const float* lse, float* dvec, void* dqkv,
-                                  float* ddiag, const AttnDims& a, hipStream_t st);
+// dc: [B*S, H*dk] gradient of c.  Writes dq, dk, dv, dvec [B,H,S] (scratch) and, with bias,
+// ddiag [H, 2S-1] float32 (zeroed inside).
+hipError_t launch_attn_bwd_simple(const AttnIO& io, const void* c, const void* dc, int type,
+                                  const float* diag, const float* lse, float* dvec, float* ddiag,
+                                  const AttnDims& a, hipStream_t st);
 bool attn_mfma_supported(const AttnDims& a);
-hipError_t launch_attn_fwd_mfma(const void* qkv, const float* diag, void* c, float* lse, const AttnDims& a,
+hipError_t launch_attn_fwd_mfma(const AttnIO& io, const float* diag, void* c, float* lse, const AttnDims& a,
                                 hipStream_t st);
-size_t attn_bwd_mfma_scratch_bytes(const AttnDims& a);
 // Whether the backward kernels take this problem with `far` (smallest distance in the saturated last
 // bucket); otherwise the simple backward is used (same saved tensors).
 bool attn_bwd_mfma_fits(const AttnDims& a, int far);
 // phase 0: dvec = rowsum(dO * O); phase 1: dq and the bias-gradient diagonals, ADDED into ddiag (the
 // caller clears it); phase 2: dk, dv.
-hipError_t launch_attn_bwd_mfma(const void* qkv, const void* c, const void* dc, const float* diag,
-                                const float* lse, float* dvec, void* dqkv, float* ddiag, void* scratch,
-                                const AttnDims& a, int far, int phase, hipStream_t st);
+hipError_t launch_attn_bwd_mfma(const AttnIO& io, const void* c, const void* dc, const float* diag,
+                                const float* lse, float* dvec, float* ddiag, const AttnDims& a, int far,
+                                int phase, hipStream_t st);
 
 // ------------------------------------------------------------------ measurement aid
 // Register-only MFMA loop: each of the 4 waves of a workgroup issues iters * 32 v_mfma_f32_32x32x16_bf16.

@@ -240,6 +240,7 @@ int rmsnorm_bwd_partial_rows(int T) {
 // Supported type combinations: (x, g, resid, lp) =
 //   (f32, bf16, bf16, bf16)  norm 2 of the bf16 block: x = h, resid = dy, outputs dh f32 + bf16
 //   (bf16, bf16, f32, bf16)  norm 1 of the bf16 block: x = x, resid = dh, output dx bf16
+//   (f32, bf16, f32, bf16)   cross-attention norm of the bf16 decoder block: x = h, resid = dh2
 //   (f32, f32, f32, f32)     both norms of the float32 block
 hipError_t launch_rmsnorm_bwd(const void* x, int x_type, const void* g, int g_type, const float* r,
                               const float* dn, const void* resid, int resid_type, float* out_f32,
@@ -251,6 +252,8 @@ hipError_t launch_rmsnorm_bwd(const void* x, int x_type, const void* g, int g_ty
     e = bwd_dispatch<float, bf16, bf16, bf16>(x, g, r, dn, resid, out_f32, out_lp, dg_partial, T, d, grid, st);
   else if (x_type == IN_BF16 && g_type == IN_BF16 && resid_type == IN_F32 && lp_type == IN_BF16)
     e = bwd_dispatch<bf16, bf16, float, bf16>(x, g, r, dn, resid, out_f32, out_lp, dg_partial, T, d, grid, st);
+  else if (x_type == IN_F32 && g_type == IN_BF16 && resid_type == IN_F32 && lp_type == IN_BF16)
+    e = bwd_dispatch<float, bf16, float, bf16>(x, g, r, dn, resid, out_f32, out_lp, dg_partial, T, d, grid, st);
   else if (x_type == IN_F32 && g_type == IN_F32 && resid_type == IN_F32 && lp_type == IN_F32)
     e = bwd_dispatch<float, float, float, float>(x, g, r, dn, resid, out_f32, out_lp, dg_partial, T, d, grid,
                                                  st);

@@ -17,6 +17,17 @@ TOL_BF16_DW = (6e-2, 6e-3)       # weight gradients
 # errors sit lower, and the mean of dx meets the stated 2e-3:
 TOL_BF16_DX_NAMED = (3e-2, 2e-3)
 TOL_BF16_DW_NAMED = (5e-2, 5e-3)
+# denc = dk Xk^T + dv Xv^T has no residual term (dx = dh + ... is dominated by the float32 residual
+# path): all of it passes through the bf16 roundings of P and dS as MFMA operands and of dk, dv as
+# stored, the chain of the weight gradients dWk and dWv, so it gets their bound.
+TOL_BF16_DENC = TOL_BF16_DW
+# The decoder layer adds a third sublayer to the float32 residual stream; each sublayer contributes
+# an independent bf16-rounded term of similar size, so the error of y and dx grows by about
+# sqrt(3/2) over the two-sublayer block.  Mean bounds scaled by that factor, maxima unchanged.
+TOL_BF16_DEC_ACT = (2e-2, 2.5e-3)
+TOL_BF16_DEC_DX = (3e-2, 3.1e-3)
+TOL_BF16_DEC_DX_NAMED = (3e-2, 2.5e-3)   # the named-workload dx bound times sqrt(3/2); y meets the stated 2e-3
+TOL_BF16_DENC_NAMED = TOL_BF16_DW_NAMED
 
 
 def rel_err(gpu: np.ndarray, ref: np.ndarray):
@@ -58,3 +69,19 @@ def make_case(cfg, random_scales=True, seed_offset=0):
         w.update(SI.make_random_scales(cfg))
     x, dy = SI.make_activations(cfg, seed_offset)
     return w, x, dy
+
+
+def make_decoder_case(cfg, seed_offset=0):
+    w, x, dy = make_case(cfg, seed_offset=seed_offset)
+    return w, x, SI.make_encoder_output(cfg, seed_offset), dy
+
+
+def run_decoder_block_gpu(cfg, w, x, enc, dy):
+    """Returns (y, dx, denc, grads) as float64 numpy arrays, computed by the HIP library."""
+    import paper_2203_17189_amd as P
+    dw, dx_in, ddy = upload_case(cfg, w, x, dy)
+    denc_in = to_dev(enc, cfg.dtype)
+    y, stash = P.t5_decoder_block_fwd(cfg, dx_in, denc_in, dw)
+    dx, denc, grads = P.t5_decoder_block_bwd(cfg, ddy, dx_in, denc_in, dw, stash)
+    torch.cuda.synchronize()
+    return to_np(y), to_np(dx), to_np(denc), {k: to_np(v) for k, v in grads.items()}

@@ -82,6 +82,38 @@ def test_block_validation():
     assert lib.t5_block_fwd(C.byref(bad), dummy, C.byref(w), dummy, dummy, dummy, 1 << 30, None) == 2
 
 
+def test_decoder_block_validation():
+    lib = P.lib()
+    cfg = B._cfg_struct(SI.CONFIGS["c1_tiny_f32"])
+    dummy = C.c_void_p(4096)
+    w = B._Weights(*([4096] * 10))
+    g = B._Grads(*([4096] * 10))
+    xw = B._CrossWeights(*([4096] * 5))
+    xg = B._CrossGrads(*([4096] * 5))
+    dec = SI.CONFIGS["c6_dec_base"]
+    assert P.t5_decoder_block_stash_bytes(dec) > P.t5_block_stash_bytes(dec)
+    assert P.t5_decoder_block_workspace_bytes(dec) > P.t5_block_workspace_bytes(dec)
+    assert lib.t5_decoder_block_stash_bytes(C.byref(cfg), 0) == 0
+    assert lib.t5_decoder_block_workspace_bytes(C.byref(cfg), -3) == 0
+    fwd = lambda c, es, x, enc, ww, xx, nbytes: lib.t5_decoder_block_fwd(c, es, x, enc, ww, xx, dummy, dummy, dummy,
+                                                                      nbytes, None)
+    big = 1 << 30
+    assert fwd(None, 8, dummy, dummy, C.byref(w), C.byref(xw), big) == 1
+    assert fwd(C.byref(cfg), 0, dummy, dummy, C.byref(w), C.byref(xw), big) == 2
+    assert fwd(C.byref(cfg), 8, dummy, None, C.byref(w), C.byref(xw), big) == 1
+    assert fwd(C.byref(cfg), 8, dummy, dummy, C.byref(w), None, big) == 1
+    assert fwd(C.byref(cfg), 8, dummy, dummy, C.byref(w), C.byref(B._CrossWeights(*([4096] * 4 + [None]))), big) == 1
+    assert fwd(C.byref(cfg), 8, dummy, dummy, C.byref(w), C.byref(xw), 16) == 4
+    bwd = lambda es, denc, gg, xgg, nbytes: lib.t5_decoder_block_bwd(C.byref(cfg), es, dummy, dummy, dummy, C.byref(w),
+                                                                     C.byref(xw), dummy, dummy, denc, gg, xgg, 0,
+                                                                     dummy, nbytes, None)
+    assert bwd(8, dummy, C.byref(g), C.byref(xg), 16) == 4
+    assert bwd(8, None, C.byref(g), C.byref(xg), big) == 1
+    assert bwd(8, dummy, C.byref(g), None, big) == 1
+    assert bwd(8, dummy, C.byref(g), C.byref(B._CrossGrads(*([None] + [4096] * 4))), big) == 1
+    assert bwd(0, dummy, C.byref(g), C.byref(xg), big) == 2
+
+
 def test_adafactor_validation():
     lib = P.lib()
     dummy = C.c_void_p(4096)
