@@ -1,11 +1,12 @@
 #!/usr/bin/env python3
 """Benchmark of the T5.1.1 block hot path (forward + backward [+ Adafactor]) on one MI355X.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2_small|c3_base|c4_gpt_causal|c5_xl]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2_small|c3_base|c4_gpt_causal|c5_xl|c6_dec_base]
 
 Prints ONE JSON line.  A "step" is one pass of the whole hot path over one batch of seeded
-synthetic input already resident in HBM: t5_block_fwd + t5_block_bwd, plus adafactor_step_multi over the
-block weights for the workloads that include the optimizer.  `value` is tokens/s of that step.
+synthetic input already resident in HBM: t5_block_fwd + t5_block_bwd (t5_decoder_block_fwd/bwd for the
+workload with cross-attention), plus adafactor_step_multi over the block weights for the workloads that
+include the optimizer.  `value` is tokens/s of that step.
 `roofline` describes the step's dominant kernel, timed with HIP events on the launch stream in a
 second, instrumented pass over the same work; `cpu_baseline` is the float64 oracle timed on the host
 cores on a bounded sample (fewer sequences, same shapes).
@@ -33,7 +34,15 @@ def gemm_step_flops(cfg) -> dict:
     """Algorithmic FLOPs of one launch of each MFMA step (2*M*N*K; attention counts the causal half)."""
     T, d, I, F, S = cfg.tokens, cfg.d_model, cfg.inner, cfg.d_ff, cfg.seq
     attn_f = 4.0 * T * S * I * (0.5 if cfg.causal else 1.0)
+    Te, xattn_f = cfg.batch * cfg.enc_seq, 4.0 * T * cfg.enc_seq * I
+    cross = {
+        "gemm_xq": 2.0 * T * d * I, "gemm_xkv": 2.0 * Te * d * 2 * I, "xattn_fwd": xattn_f, "gemm_xo": 2.0 * T * I * d,
+        "gemm_dxo": 2.0 * T * I * d, "gemm_dcx": 2.0 * T * I * d, "xattn_bwd_dq": xattn_f, "xattn_bwd_dkv": xattn_f,
+        "gemm_dxq": 2.0 * T * d * I, "gemm_dxkv": 2.0 * Te * d * 2 * I, "gemm_denc": 2.0 * Te * d * 2 * I,
+        "gemm_dnx": 2.0 * T * d * I,
+    } if cfg.enc_seq > 0 else {}
     return {
+        **cross,
         "gemm_qkv": 2.0 * T * d * 3 * I, "gemm_o": 2.0 * T * I * d, "gemm_wi_geglu": 2.0 * T * d * 2 * F,
         "gemm_wo": 2.0 * T * F * d, "attn_fwd": attn_f,
         "gemm_dwo_ff": 2.0 * T * F * d, "gemm_da_geglu_bwd": 2.0 * T * F * d, "gemm_dwi": 2.0 * T * d * 2 * F,
@@ -54,9 +63,14 @@ def cpu_baseline(cfg, sample_batch: int) -> dict:
     c = cfg.with_batch(sample_batch)
     w = SI.make_weights(c)
     x, dy = SI.make_activations(c)
+    enc = SI.make_encoder_output(c) if c.enc_seq > 0 else None
     t0 = time.perf_counter()
-    y, saved = O.block_fwd(c, x, w)
-    dx, g = O.block_bwd(c, dy, w, saved)
+    if enc is None:
+        y, saved = O.block_fwd(c, x, w)
+        dx, g = O.block_bwd(c, dy, w, saved)
+    else:
+        y, saved = O.decoder_block_fwd(c, x, enc, w)
+        dx, denc, g = O.decoder_block_bwd(c, dy, w, saved)
     if cfg.adafactor:
         for name, grad in g.items():
             p2 = w[name].reshape(-1, w[name].shape[-1]) if w[name].ndim > 1 else w[name].reshape(1, -1)
@@ -75,7 +89,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2_small", choices=[k for k in SI.CONFIGS if k != "c1_tiny_f32" and SI.CONFIGS[k].enc_seq == 0])
+    ap.add_argument("--workload", default="c2_small", choices=[k for k in SI.CONFIGS if k != "c1_tiny_f32"])
     ap.add_argument("--cpu-sample-batch", type=int, default=0, help="0 = pick about 10-30 s of oracle work")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -115,13 +129,21 @@ def main() -> int:
     dy = torch.from_numpy(rng.standard_normal(shape, dtype=np.float32)).to(dev).to(dt_t)
     y = torch.empty_like(x)
     dx = torch.empty_like(x)
-    stash = torch.empty(P.t5_block_stash_bytes(cfg), dtype=torch.uint8, device=dev)
-    ws = torch.empty(P.t5_block_workspace_bytes(cfg), dtype=torch.uint8, device=dev)
-    grads = B.alloc_grads(cfg, w)
+    decoder = cfg.enc_seq > 0
+    if decoder:
+        enc = torch.from_numpy(rng.standard_normal((cfg.batch, cfg.enc_seq, cfg.d_model), dtype=np.float32)).to(dev).to(dt_t)
+        denc = torch.empty_like(enc)
+        stash = torch.empty(P.t5_decoder_block_stash_bytes(cfg), dtype=torch.uint8, device=dev)
+        ws = torch.empty(P.t5_decoder_block_workspace_bytes(cfg), dtype=torch.uint8, device=dev)
+        grads = B.alloc_decoder_grads(cfg, w)
+    else:
+        stash = torch.empty(P.t5_block_stash_bytes(cfg), dtype=torch.uint8, device=dev)
+        ws = torch.empty(P.t5_block_workspace_bytes(cfg), dtype=torch.uint8, device=dev)
+        grads = B.alloc_grads(cfg, w)
     opt = None
     if cfg.adafactor:
         opt = {}
-        for name in P.WEIGHT_NAMES:
+        for name in grads:
             master = w[name].float().contiguous()
             rows, cols = (master.shape[0], master.shape[1]) if master.dim() == 2 else (1, master.numel())
             fact = master.dim() == 2 and name != "rel_table"
@@ -135,8 +157,12 @@ def main() -> int:
     step_no = [0]
 
     def step():
-        P.t5_block_fwd(cfg, x, w, y=y, stash=stash, workspace=ws)
-        P.t5_block_bwd(cfg, dy, x, w, stash, dx=dx, grads=grads, workspace=ws)
+        if decoder:
+            P.t5_decoder_block_fwd(cfg, x, enc, w, y=y, stash=stash, workspace=ws)
+            P.t5_decoder_block_bwd(cfg, dy, x, enc, w, stash, dx=dx, denc=denc, grads=grads, workspace=ws)
+        else:
+            P.t5_block_fwd(cfg, x, w, y=y, stash=stash, workspace=ws)
+            P.t5_block_bwd(cfg, dy, x, w, stash, dx=dx, grads=grads, workspace=ws)
         if opt is not None:
             step_no[0] += 1
             P.adafactor_step_multi(opt_tensors, step=step_no[0], lr=1e-2, workspace=opt_ws)
@@ -165,7 +191,7 @@ def main() -> int:
     per_kernel = {k: {"avg_ms": v[0] / v[1], "launches_per_step": v[1] / n_prof} for k, v in timing.items()}
     step_ms = {k: v["avg_ms"] * v["launches_per_step"] for k, v in per_kernel.items()}
     fwd_names = {"relpos_diag", "rmsnorm_fwd", "pack_weights", "gemm_qkv", "attn_fwd", "gemm_o", "gemm_wi_geglu",
-                 "gemm_wi", "geglu_fwd", "gemm_wo"}
+                 "gemm_wi", "geglu_fwd", "gemm_wo", "gemm_xq", "gemm_xkv", "xattn_fwd", "gemm_xo"}
     phase_ms = {"fwd_ms": round(sum(v for k, v in step_ms.items() if k in fwd_names), 4),
                 "bwd_ms": round(sum(v for k, v in step_ms.items() if k not in fwd_names and k != "adafactor"), 4),
                 "adafactor_ms": round(step_ms.get("adafactor", 0.0), 4)}
@@ -173,7 +199,8 @@ def main() -> int:
     # in float32 plus the refreshed bf16 copy)
     Tn, dn_ = cfg.tokens, cfg.d_model
     n_params = sum(int(v.numel()) for v in w.values())
-    hbm_bytes = {"rmsnorm_fwd": 2 * (2.0 * Tn * dn_ * 2 + 4.0 * Tn), "rmsnorm_bwd": 2 * (4.0 * Tn * dn_ * 2),
+    n_norm = 3 if decoder else 2
+    hbm_bytes = {"rmsnorm_fwd": n_norm * (2.0 * Tn * dn_ * 2 + 4.0 * Tn), "rmsnorm_bwd": n_norm * (4.0 * Tn * dn_ * 2),
                  "adafactor": 14.0 * n_params}
 
     # ---- what this machine sustains with nothing in the way (context for the fractions below)
@@ -234,6 +261,7 @@ def main() -> int:
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": cfg.name, "batch": cfg.batch, "seq_len": cfg.seq, "d_model": cfg.d_model,
                    "n_heads": cfg.n_heads, "d_kv": cfg.d_kv, "d_ff": cfg.d_ff, "causal": cfg.causal,
+                   "enc_seq_len": cfg.enc_seq,
                    "adafactor": cfg.adafactor, "passes": "fwd+bwd" + ("+adafactor" if cfg.adafactor else "")},
         "model_tflops": round(model_tflops, 2), "frac_of_mfma_peak": round(model_tflops / PEAK_BF16_TFLOPS, 4),
         "roofline": roofline, **phase_ms, "machine": machine, "per_kernel": per_kernel,
