@@ -16,6 +16,10 @@ therefore the public definition of the named layer, written out in full:
     unless the caller asks for one through attn_scale.
   * T5.1.1 feed-forward: gated GELU (tanh form), no biases.
   * Pre-norm residual wiring: h = x + Attn(Norm(x)); y = h + MLP(Norm(h)).
+  * Stack: token embedding (no input scaling), N blocks sharing one relative-position
+    table, final RMSNorm, logits (untied output matrix, or the embedding transposed
+    and scaled by d_model^-1/2), softmax cross-entropy plus z_loss * log(Z)^2, mean
+    over the positions whose target is >= 0.
   * Decoder block of the encoder-decoder model: the same, with a cross-attention
     sublayer (queries from the decoder stream, keys and values from the encoder
     output, no position bias, no mask) between self-attention and the MLP.
@@ -329,6 +333,81 @@ def decoder_block_bwd(cfg, dy: np.ndarray, w: dict, saved: dict):
     dn1 = dqf @ w["wq"].T + dkf @ w["wk"].T + dvf @ w["wv"].T
     dx_norm, g["ln1_scale"] = rmsnorm_bwd(sv["x"], w["ln1_scale"], sv["r1"], dn1)
     return dh1 + dx_norm, denc, g
+
+
+# --------------------------------------------------------------------------------------
+# Stack of blocks with token embedding, final norm, logits and loss
+# --------------------------------------------------------------------------------------
+def xent_zloss(logits: np.ndarray, targets: np.ndarray, z_loss: float):
+    """Softmax cross-entropy with the auxiliary z-loss of the T5 training recipe, per position:
+        lse = log sum_v exp(logits_v);   loss = lse - logits[target] + z_loss * lse^2
+    Positions with target < 0 carry no loss.  Returns (mean over the positions that count, lse,
+    number of positions that count).  logits: [..., V], targets: integer [...]"""
+    m = logits.max(axis=-1, keepdims=True)
+    lse = (m + np.log(np.exp(logits - m).sum(axis=-1, keepdims=True)))[..., 0]
+    valid = targets >= 0
+    picked = np.take_along_axis(logits, np.where(valid, targets, 0)[..., None], axis=-1)[..., 0]
+    per = np.where(valid, lse - picked + z_loss * lse * lse, 0.0)
+    n = int(valid.sum())
+    return float(per.sum() / max(n, 1)), lse, n
+
+
+def xent_zloss_grad(logits: np.ndarray, targets: np.ndarray, lse: np.ndarray, z_loss: float, n: int):
+    """d(mean loss)/d(logits): (softmax * (1 + 2 z_loss lse) - onehot(target)) / n on counted positions."""
+    p = np.exp(logits - lse[..., None])
+    g = p * (1.0 + 2.0 * z_loss * lse)[..., None]
+    valid = targets >= 0
+    idx = np.where(valid, targets, 0)[..., None]
+    np.put_along_axis(g, idx, np.take_along_axis(g, idx, axis=-1) - 1.0, axis=-1)
+    return g * (valid[..., None] / max(n, 1))
+
+
+def stack_loss(sc, tokens: np.ndarray, targets: np.ndarray, w: dict):
+    """Training loss of the stack (paper Sec. 4 models as plain layer stacks, Sec. 2.3):
+        x_0 = E[tokens];  x_{l+1} = block_l(x_l)  with ONE relative-position table shared by all layers
+        nf = RMSNorm(x_L; gf);  logits = nf Wout   (tied: logits = d_model^-1/2 nf E^T)
+        loss = mean over positions with target >= 0 of xent_zloss
+    Returns (loss, saved)."""
+    cfg = sc.block
+    x = w["embedding"][tokens]
+    saved_layers = []
+    for lw in w["layers"]:
+        wl = dict(lw, rel_table=w["rel_table"])
+        x, sv = block_fwd(cfg, x, wl)
+        saved_layers.append(sv)
+    nf, rf = rmsnorm_fwd(x, w["final_scale"], cfg.rms_eps)
+    if sc.tied_logits:
+        logits = (nf * cfg.d_model ** -0.5) @ w["embedding"].T
+    else:
+        logits = nf @ w["logits_w"]
+    loss, lse, n = xent_zloss(logits, targets, sc.z_loss)
+    return loss, dict(tokens=tokens, targets=targets, layers=saved_layers, x_last=x, nf=nf, rf=rf, logits=logits,
+                      lse=lse, n=n)
+
+
+def stack_loss_grad(sc, w: dict, saved: dict) -> dict:
+    """Gradient of stack_loss w.r.t. every weight: {"embedding", "rel_table" (summed over layers),
+    "final_scale", "logits_w" (untied), "layers": [block gradient dicts without rel_table]}."""
+    cfg = sc.block
+    flat = lambda t: t.reshape(-1, t.shape[-1])
+    dlogits = xent_zloss_grad(saved["logits"], saved["targets"], saved["lse"], sc.z_loss, saved["n"])
+    g = {"layers": [None] * sc.n_layers, "embedding": np.zeros_like(w["embedding"])}
+    if sc.tied_logits:
+        s = cfg.d_model ** -0.5
+        g["embedding"] += s * (flat(dlogits).T @ flat(saved["nf"]))
+        dnf = s * (dlogits @ w["embedding"])
+    else:
+        g["logits_w"] = flat(saved["nf"]).T @ flat(dlogits)
+        dnf = dlogits @ w["logits_w"].T
+    dx, g["final_scale"] = rmsnorm_bwd(saved["x_last"], w["final_scale"], saved["rf"], dnf)
+    g["rel_table"] = np.zeros_like(w["rel_table"])
+    for l in range(sc.n_layers - 1, -1, -1):
+        wl = dict(w["layers"][l], rel_table=w["rel_table"])
+        dx, gl = block_bwd(cfg, dx, wl, saved["layers"][l])
+        g["rel_table"] += gl.pop("rel_table")
+        g["layers"][l] = gl
+    np.add.at(g["embedding"], saved["tokens"].reshape(-1), flat(dx))
+    return g
 
 
 # --------------------------------------------------------------------------------------

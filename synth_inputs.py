@@ -159,6 +159,79 @@ def make_encoder_output(cfg: BlockConfig, seed_offset: int = 0) -> np.ndarray:
     return _draw(cfg, "enc", (cfg.batch, cfg.enc_seq, cfg.d_model), 1.0, seed_offset)
 
 
+@dataclass(frozen=True)
+class StackConfig:
+    """A stack of n_layers identical blocks with token embedding, final norm, logits and loss
+    (paper Sec. 4: the decoder-only model when block.causal, else an encoder-style stack)."""
+    name: str
+    block: BlockConfig
+    n_layers: int
+    vocab: int
+    tied_logits: bool = False   # False: separate [d_model, vocab] output matrix (T5.1.1)
+    z_loss: float = 1e-4
+    remat: bool = False         # True: keep layer inputs only, recompute each layer in the backward
+
+    def with_batch(self, batch: int) -> "StackConfig":
+        return replace(self, block=self.block.with_batch(batch))
+
+    def model_flops(self) -> float:
+        """fwd+bwd model FLOPs of one step (3x forward; the recompute of remat is not counted)."""
+        b = self.block
+        return 3.0 * b.tokens * (self.n_layers * b.fwd_flops_per_token() + 2.0 * b.d_model * self.vocab)
+
+
+STACK_CONFIGS = {
+    # T5.1.1-Base widths as a 12-layer decoder-only language model over the 32128-entry T5 vocabulary
+    "s1_lm_base": StackConfig("s1_lm_base", BlockConfig("s1_lm_base", 6, 32, 512, 768, 12, 64, 2048, causal=True),
+                              n_layers=12, vocab=32128),
+}
+
+
+def make_stack_weights(sc: StackConfig) -> dict:
+    """{"embedding", "rel_table" (shared by all layers), "final_scale", "logits_w" (absent when tied),
+    "layers": [block weight dicts without rel_table]}; float64 holding dtype-representable values."""
+    b = sc.block
+    rng_seed = BASE_SEED + 1000 * b.index + 500
+    emb = np.random.default_rng(rng_seed).standard_normal((sc.vocab, b.d_model))
+    w = {"embedding": round_to_dtype(emb, b.dtype), "final_scale": np.ones(b.d_model), "layers": []}
+    for l in range(sc.n_layers):
+        lw = make_weights(replace(b, index=b.index + 37 * (l + 1), enc_seq=0))
+        table = lw.pop("rel_table")
+        if l == 0:
+            w["rel_table"] = table
+        w["layers"].append(lw)
+    if not sc.tied_logits:
+        out = np.random.default_rng(rng_seed + 1).standard_normal((b.d_model, sc.vocab)) * b.d_model ** -0.5
+        w["logits_w"] = round_to_dtype(out, b.dtype)
+    return w
+
+
+def make_stack_random_scales(sc: StackConfig, w: dict) -> None:
+    """In place: non-trivial RMSNorm scales for every layer and the final norm."""
+    b = sc.block
+    for l, lw in enumerate(w["layers"]):
+        lw.update(make_random_scales(replace(b, index=b.index + 37 * (l + 1), enc_seq=0)))
+    g = np.random.default_rng(BASE_SEED + 1000 * b.index + 502).standard_normal(b.d_model)
+    w["final_scale"] = round_to_dtype(1.0 + 0.1 * g, b.dtype)
+
+
+def make_tokens(sc: StackConfig, seed_offset: int = 0, ignore_fraction: float = 0.1) -> tuple:
+    """(tokens, targets) int32 [batch, seq].  Token ids follow a Zipf-like law over the vocabulary
+    (probability ~ 1 / (rank + 10)), as natural-language token streams do; targets are the next
+    token of the same stream, and a fraction of them is -1 (padding positions that carry no loss)."""
+    b = sc.block
+    rng = np.random.default_rng(BASE_SEED + 1000 * b.index + 503 + 100000 * seed_offset)
+    p = 1.0 / (np.arange(sc.vocab) + 10.0)
+    p /= p.sum()
+    perm = rng.permutation(sc.vocab)                      # rank -> token id
+    stream = perm[rng.choice(sc.vocab, size=(b.batch, b.seq + 1), p=p)]
+    tokens = stream[:, :-1].astype(np.int32)
+    targets = stream[:, 1:].astype(np.int32)
+    if ignore_fraction > 0:
+        targets = np.where(rng.random(targets.shape) < ignore_fraction, -1, targets).astype(np.int32)
+    return tokens, targets
+
+
 def make_adafactor_case(rows: int, cols: int, seed: int, grad_std: float = 1e-2) -> tuple:
     """(param, grad) float64 arrays holding float32-representable values for a standalone optimizer test."""
     rng = np.random.default_rng(BASE_SEED + 7919 * seed + rows * 31 + cols)
