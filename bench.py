@@ -53,6 +53,25 @@ def gemm_step_flops(cfg) -> dict:
     }
 
 
+def cpu_baseline_stack(sc, sample_batch: int) -> dict:
+    from oracle import t5_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    c = sc.with_batch(sample_batch)
+    w = SI.make_stack_weights(c)
+    tokens, targets = SI.make_tokens(c)
+    t0 = time.perf_counter()
+    loss, saved = O.stack_loss(c, tokens, targets, w)
+    O.stack_loss_grad(c, w, saved)
+    dt = time.perf_counter() - t0
+    return {"value": c.block.tokens / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{sc.name} at batch {sample_batch} of {sc.block.batch} (same depth/seq/width/vocab), float64 "
+                      f"numpy, {dt:.2f} s for one loss + gradient"}
+
+
 def cpu_baseline(cfg, sample_batch: int) -> dict:
     from oracle import t5_oracle as O
     try:
@@ -89,7 +108,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2_small", choices=[k for k in SI.CONFIGS if k != "c1_tiny_f32"])
+    ap.add_argument("--workload", default="c2_small", choices=[k for k in SI.CONFIGS if k != "c1_tiny_f32"] + list(SI.STACK_CONFIGS))
     ap.add_argument("--cpu-sample-batch", type=int, default=0, help="0 = pick about 10-30 s of oracle work")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -107,7 +126,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
-    cfg = SI.CONFIGS[args.workload]
+    sc = SI.STACK_CONFIGS.get(args.workload)
+    cfg = sc.block if sc is not None else SI.CONFIGS[args.workload]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     if args.calibrate_copy:
@@ -120,43 +140,62 @@ def main() -> int:
         return 0
 
     # ---- seeded synthetic inputs, generated on the host, resident in HBM before timing
-    w_host = SI.make_weights(cfg)
     dt_t = torch.bfloat16
-    w = {k: torch.from_numpy(v.astype(np.float32)).to(dev).to(dt_t) for k, v in w_host.items()}
-    rng = np.random.default_rng(SI.BASE_SEED + 1000 * cfg.index)
-    shape = (cfg.batch, cfg.seq, cfg.d_model)
-    x = torch.from_numpy(rng.standard_normal(shape, dtype=np.float32)).to(dev).to(dt_t)
-    dy = torch.from_numpy(rng.standard_normal(shape, dtype=np.float32)).to(dev).to(dt_t)
-    y = torch.empty_like(x)
-    dx = torch.empty_like(x)
-    decoder = cfg.enc_seq > 0
-    if decoder:
-        enc = torch.from_numpy(rng.standard_normal((cfg.batch, cfg.enc_seq, cfg.d_model), dtype=np.float32)).to(dev).to(dt_t)
-        denc = torch.empty_like(enc)
-        stash = torch.empty(P.t5_decoder_block_stash_bytes(cfg), dtype=torch.uint8, device=dev)
-        ws = torch.empty(P.t5_decoder_block_workspace_bytes(cfg), dtype=torch.uint8, device=dev)
-        grads = B.alloc_decoder_grads(cfg, w)
+    up = lambda v: torch.from_numpy(v.astype(np.float32)).to(dev).to(dt_t)
+    if sc is not None:
+        ws_host = SI.make_stack_weights(sc)
+        sw = {k: up(v) for k, v in ws_host.items() if k != "layers"}
+        sw["layers"] = [{k: up(v) for k, v in lw.items()} for lw in ws_host["layers"]]
+        del ws_host
+        tok_h, tgt_h = SI.make_tokens(sc)
+        s_tok, s_tgt = torch.from_numpy(tok_h).to(dev), torch.from_numpy(tgt_h).to(dev)
+        s_grads = B.alloc_stack_grads(sc, sw)
+        s_ws = torch.empty(P.t5_stack_workspace_bytes(sc), dtype=torch.uint8, device=dev)
+        s_loss = torch.zeros(1, dtype=torch.float32, device=dev)
+        w_host = {"rel_table": np.zeros((cfg.num_buckets, cfg.n_heads))}
     else:
-        stash = torch.empty(P.t5_block_stash_bytes(cfg), dtype=torch.uint8, device=dev)
-        ws = torch.empty(P.t5_block_workspace_bytes(cfg), dtype=torch.uint8, device=dev)
-        grads = B.alloc_grads(cfg, w)
+        w_host = SI.make_weights(cfg)
+    w = {k: up(v) for k, v in w_host.items()}
+    decoder = cfg.enc_seq > 0
     opt = None
-    if cfg.adafactor:
-        opt = {}
-        for name in grads:
-            master = w[name].float().contiguous()
-            rows, cols = (master.shape[0], master.shape[1]) if master.dim() == 2 else (1, master.numel())
-            fact = master.dim() == 2 and name != "rel_table"
-            opt[name] = dict(master=master, fact=fact,
-                             vr=torch.zeros(rows, device=dev), vc=torch.zeros(cols, device=dev),
-                             vf=None if fact else torch.zeros(rows, cols, device=dev))
-        opt_tensors = [dict(param=o["master"], grad=grads[name], factored=o["fact"], v_row=o["vr"], v_col=o["vc"],
-                            v_full=o["vf"], bf16_copy_out=w[name]) for name, o in opt.items()]
-        opt_ws = torch.empty(max(P.adafactor_multi_workspace_bytes(opt_tensors), 256), dtype=torch.uint8, device=dev)
+    if sc is None:
+        rng = np.random.default_rng(SI.BASE_SEED + 1000 * cfg.index)
+        shape = (cfg.batch, cfg.seq, cfg.d_model)
+        x = torch.from_numpy(rng.standard_normal(shape, dtype=np.float32)).to(dev).to(dt_t)
+        dy = torch.from_numpy(rng.standard_normal(shape, dtype=np.float32)).to(dev).to(dt_t)
+        y = torch.empty_like(x)
+        dx = torch.empty_like(x)
+        decoder = cfg.enc_seq > 0
+        if decoder:
+            enc = torch.from_numpy(rng.standard_normal((cfg.batch, cfg.enc_seq, cfg.d_model), dtype=np.float32)).to(dev).to(dt_t)
+            denc = torch.empty_like(enc)
+            stash = torch.empty(P.t5_decoder_block_stash_bytes(cfg), dtype=torch.uint8, device=dev)
+            ws = torch.empty(P.t5_decoder_block_workspace_bytes(cfg), dtype=torch.uint8, device=dev)
+            grads = B.alloc_decoder_grads(cfg, w)
+        else:
+            stash = torch.empty(P.t5_block_stash_bytes(cfg), dtype=torch.uint8, device=dev)
+            ws = torch.empty(P.t5_block_workspace_bytes(cfg), dtype=torch.uint8, device=dev)
+            grads = B.alloc_grads(cfg, w)
+        opt = None
+        if cfg.adafactor:
+            opt = {}
+            for name in grads:
+                master = w[name].float().contiguous()
+                rows, cols = (master.shape[0], master.shape[1]) if master.dim() == 2 else (1, master.numel())
+                fact = master.dim() == 2 and name != "rel_table"
+                opt[name] = dict(master=master, fact=fact,
+                                 vr=torch.zeros(rows, device=dev), vc=torch.zeros(cols, device=dev),
+                                 vf=None if fact else torch.zeros(rows, cols, device=dev))
+            opt_tensors = [dict(param=o["master"], grad=grads[name], factored=o["fact"], v_row=o["vr"], v_col=o["vc"],
+                                v_full=o["vf"], bf16_copy_out=w[name]) for name, o in opt.items()]
+            opt_ws = torch.empty(max(P.adafactor_multi_workspace_bytes(opt_tensors), 256), dtype=torch.uint8, device=dev)
 
     step_no = [0]
 
     def step():
+        if sc is not None:
+            P.t5_stack_loss_and_grad(sc, s_tok, s_tgt, sw, grads=s_grads, workspace=s_ws, loss=s_loss)
+            return
         if decoder:
             P.t5_decoder_block_fwd(cfg, x, enc, w, y=y, stash=stash, workspace=ws)
             P.t5_decoder_block_bwd(cfg, dy, x, enc, w, stash, dx=dx, denc=denc, grads=grads, workspace=ws)
@@ -177,7 +216,8 @@ def main() -> int:
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
     tokens_per_s = cfg.tokens * args.steps / dt
-    model_tflops = cfg.model_flops() / (ms_per_step * 1e-3) / 1e12
+    total_model_flops = sc.model_flops() if sc is not None else cfg.model_flops()
+    model_tflops = total_model_flops / (ms_per_step * 1e-3) / 1e12
 
     # ---- instrumented pass: per-step HIP-event timing on the launch stream
     P.t5_step_timing_enable(True)
@@ -188,6 +228,10 @@ def main() -> int:
     timing = P.t5_step_timing_read()
     P.t5_step_timing_enable(False)
     flops = gemm_step_flops(cfg)
+    if sc is not None:
+        chunk = min(cfg.tokens, 8192)
+        for name in ("gemm_logits", "gemm_dnf", "gemm_dlogits_w"):
+            flops[name] = 2.0 * chunk * cfg.d_model * sc.vocab
     per_kernel = {k: {"avg_ms": v[0] / v[1], "launches_per_step": v[1] / n_prof} for k, v in timing.items()}
     step_ms = {k: v["avg_ms"] * v["launches_per_step"] for k, v in per_kernel.items()}
     fwd_names = {"relpos_diag", "rmsnorm_fwd", "pack_weights", "gemm_qkv", "attn_fwd", "gemm_o", "gemm_wi_geglu",
@@ -199,9 +243,15 @@ def main() -> int:
     # in float32 plus the refreshed bf16 copy)
     Tn, dn_ = cfg.tokens, cfg.d_model
     n_params = sum(int(v.numel()) for v in w.values())
-    n_norm = 3 if decoder else 2
+    # launches of each norm kernel per step
+    n_norm = 2 * sc.n_layers + 1 if sc is not None else (3 if decoder else 2)
     hbm_bytes = {"rmsnorm_fwd": n_norm * (2.0 * Tn * dn_ * 2 + 4.0 * Tn), "rmsnorm_bwd": n_norm * (4.0 * Tn * dn_ * 2),
                  "adafactor": 14.0 * n_params}
+    if sc is not None:
+        # the loss reads every logit once and writes its gradient over it; the lookup copies T rows, its
+        # gradient reads T rows and adds them into float32 rows (read + write)
+        hbm_bytes.update({"xent_rows": 2.0 * Tn * sc.vocab * 2, "embed_fwd": 2.0 * Tn * dn_ * 2,
+                          "embed_bwd": Tn * dn_ * (2.0 + 8.0)})
 
     # ---- what this machine sustains with nothing in the way (context for the fractions below)
     sink = torch.zeros(256, dtype=torch.float32, device=dev)
@@ -259,10 +309,12 @@ def main() -> int:
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": cfg.name, "batch": cfg.batch, "seq_len": cfg.seq, "d_model": cfg.d_model,
+        "config": {"workload": args.workload, "batch": cfg.batch, "seq_len": cfg.seq, "d_model": cfg.d_model,
                    "n_heads": cfg.n_heads, "d_kv": cfg.d_kv, "d_ff": cfg.d_ff, "causal": cfg.causal,
                    "enc_seq_len": cfg.enc_seq,
-                   "adafactor": cfg.adafactor, "passes": "fwd+bwd" + ("+adafactor" if cfg.adafactor else "")},
+                   "adafactor": cfg.adafactor, "passes": "fwd+bwd" + ("+adafactor" if cfg.adafactor else ""),
+                   **({"n_layers": sc.n_layers, "vocab": sc.vocab, "tied_logits": sc.tied_logits, "remat": sc.remat,
+                       "z_loss": sc.z_loss} if sc is not None else {})},
         "model_tflops": round(model_tflops, 2), "frac_of_mfma_peak": round(model_tflops / PEAK_BF16_TFLOPS, 4),
         "roofline": roofline, **phase_ms, "machine": machine, "per_kernel": per_kernel,
     }
@@ -270,9 +322,9 @@ def main() -> int:
         sb = args.cpu_sample_batch
         if sb <= 0:
             # float64 numpy sustains very roughly 50 GFLOP/s on a handful of cores; aim near 15 s
-            per_seq = cfg.model_flops() / cfg.batch
+            per_seq = total_model_flops / cfg.batch
             sb = int(max(1, min(cfg.batch, 15.0 * 50e9 / per_seq)))
-        out["cpu_baseline"] = cpu_baseline(cfg, sb)
+        out["cpu_baseline"] = cpu_baseline_stack(sc, sb) if sc is not None else cpu_baseline(cfg, sb)
     print(json.dumps(out))
     return 0
 

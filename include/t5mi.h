@@ -161,6 +161,61 @@ int t5_decoder_block_bwd(const t5_block_cfg* cfg, int32_t enc_seq, const void* d
                          const t5_cross_grads* dxw, int accumulate, void* workspace,
                          size_t workspace_bytes, void* stream);
 
+/* A stack of n_layers identical blocks with its two ends (paper Sec. 4: the decoder-only model when
+ * block.causal != 0, an encoder-style stack otherwise; Sec. 2.3: models are plain layer stacks):
+ *   x_0 = E[tokens]                               token embedding, no input scaling
+ *   x_{l+1} = block_l(x_l)                        the block above; ONE relative-position table serves
+ *                                                 every layer (its gradient is the sum over layers)
+ *   nf = RMSNorm(x_L; final_scale)
+ *   logits = nf Wout                              tied_logits != 0: logits = d_model^-1/2 nf E^T
+ *   loss = mean over positions with 0 <= target < vocab of
+ *          lse - logits[target] + z_loss lse^2,   lse = log sum_v exp(logits_v)
+ * remat == 0 keeps every layer's saved activations between the forward and the backward sweep;
+ * remat != 0 keeps the layer inputs only and recomputes each layer's forward inside the backward
+ * sweep (one extra forward per layer for 1/n_layers of the activation memory). */
+typedef struct {
+  t5_block_cfg block; /* per-layer shapes; block.batch x block.seq tokens per step */
+  int32_t n_layers;
+  int32_t vocab;
+  int32_t tied_logits;
+  int32_t remat;
+  float z_loss; /* 1e-4 in the T5 recipe; 0 gives plain cross-entropy */
+} t5_stack_cfg;
+
+/* Device pointers of cfg.block.dtype.  layers: HOST array of n_layers structs of device pointers;
+ * their rel_table fields are ignored (the stack's shared table is used). */
+typedef struct {
+  const void* embedding;          /* [vocab, d_model] */
+  const void* rel_table;          /* [num_buckets, n_heads], shared by all layers */
+  const t5_block_weights* layers; /* [n_layers] */
+  const void* final_scale;        /* [d_model] */
+  const void* logits_w;           /* [d_model, vocab]; ignored when tied_logits */
+} t5_stack_weights;
+
+/* float32 gradients, same shapes.  layers[l].rel_table is ignored. */
+typedef struct {
+  float* embedding;
+  float* rel_table;
+  const t5_block_grads* layers; /* HOST array [n_layers] */
+  float* final_scale;
+  float* logits_w; /* ignored when tied_logits */
+} t5_stack_grads;
+
+/* Bytes of workspace for t5_stack_loss_and_grad (activations of all layers, or of one with remat,
+ * the logits of one chunk of tokens, scratch).  0 on an invalid config. */
+size_t t5_stack_workspace_bytes(const t5_stack_cfg* cfg);
+
+/* One training step's forward and backward: writes the loss (one float32, device memory) and, unless
+ * grads == NULL (then only the loss is computed), every gradient.  tokens, targets: device int32
+ * [batch, seq]; token ids are clamped into [0, vocab); targets outside [0, vocab) carry no loss (use -1
+ * for padding).  accumulate as in t5_block_bwd.  The logits are produced and consumed a chunk of
+ * tokens at a time (logits GEMM, loss and its gradient over the logits in place, the two gradient
+ * GEMMs), so the [tokens, vocab] matrix never exists in full.
+ * Errors: as t5_block_fwd; n_layers < 1, vocab < 2, z_loss < 0 or not finite -> T5_ERR_SHAPE. */
+int t5_stack_loss_and_grad(const t5_stack_cfg* cfg, const int32_t* tokens, const int32_t* targets,
+                           const t5_stack_weights* w, float* loss, const t5_stack_grads* grads,
+                           int accumulate, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Adafactor (the optimizer of the T5 models of paper Sec. 4) with factored second moments and
  * update clipping, no momentum, no weight decay, for one [rows, cols] float32 tensor:
  *   beta2 = 1 - step^-decay_pow;  Q = G*G + eps1

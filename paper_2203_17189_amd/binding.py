@@ -43,6 +43,21 @@ class _CrossGrads(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in CROSS_WEIGHT_NAMES]
 
 
+class _StackCfg(C.Structure):
+    _fields_ = [("block", _Cfg), ("n_layers", C.c_int32), ("vocab", C.c_int32), ("tied_logits", C.c_int32),
+                ("remat", C.c_int32), ("z_loss", C.c_float)]
+
+
+class _StackWeights(C.Structure):
+    _fields_ = [("embedding", C.c_void_p), ("rel_table", C.c_void_p), ("layers", C.POINTER(_Weights)),
+                ("final_scale", C.c_void_p), ("logits_w", C.c_void_p)]
+
+
+class _StackGrads(C.Structure):
+    _fields_ = [("embedding", C.c_void_p), ("rel_table", C.c_void_p), ("layers", C.POINTER(_Grads)),
+                ("final_scale", C.c_void_p), ("logits_w", C.c_void_p)]
+
+
 class _AfTensor(C.Structure):
     _fields_ = [("param", C.c_void_p), ("grad", C.c_void_p), ("v_row", C.c_void_p), ("v_col", C.c_void_p),
                 ("v_full", C.c_void_p), ("rows", C.c_int64), ("cols", C.c_int64), ("factored", C.c_int32),
@@ -93,6 +108,11 @@ def lib() -> C.CDLL:
     L.t5_decoder_block_bwd.argtypes = [C.POINTER(_Cfg), C.c_int32, vp, vp, vp, C.POINTER(_Weights),
                                        C.POINTER(_CrossWeights), vp, vp, vp, C.POINTER(_Grads),
                                        C.POINTER(_CrossGrads), i32, vp, sz, vp]
+    L.t5_stack_workspace_bytes.restype = sz
+    L.t5_stack_workspace_bytes.argtypes = [C.POINTER(_StackCfg)]
+    L.t5_stack_loss_and_grad.restype = i32
+    L.t5_stack_loss_and_grad.argtypes = [C.POINTER(_StackCfg), vp, vp, C.POINTER(_StackWeights), vp,
+                                         C.POINTER(_StackGrads), i32, vp, sz, vp]
     L.adafactor_workspace_bytes.restype = sz
     L.adafactor_workspace_bytes.argtypes = [i64, i64, i32]
     L.adafactor_step.restype = i32
@@ -311,6 +331,82 @@ def t5_decoder_block_bwd(cfg, dy, x, enc, weights, stash, dx=None, denc=None, gr
     if rc:
         raise T5Error(rc, "t5_decoder_block_bwd")
     return dx, denc, grads
+
+
+LAYER_WEIGHT_NAMES = tuple(n for n in WEIGHT_NAMES if n != "rel_table")
+
+
+def _stack_cfg_struct(sc) -> _StackCfg:
+    return _StackCfg(_cfg_struct(sc.block), int(sc.n_layers), int(sc.vocab), int(bool(sc.tied_logits)),
+                     int(bool(sc.remat)), float(sc.z_loss))
+
+
+def t5_stack_workspace_bytes(sc) -> int:
+    return int(lib().t5_stack_workspace_bytes(C.byref(_stack_cfg_struct(sc))))
+
+
+def alloc_stack_grads(sc, weights) -> dict:
+    """float32 zero tensors shaped like the stack's weights: {"embedding", "rel_table", "final_scale",
+    "logits_w" (untied), "layers": [dict per layer]}."""
+    z = lambda t: torch.zeros(t.shape, dtype=torch.float32, device=t.device)
+    g = {k: z(weights[k]) for k in ("embedding", "rel_table", "final_scale")}
+    if not sc.tied_logits:
+        g["logits_w"] = z(weights["logits_w"])
+    g["layers"] = [{n: z(lw[n]) for n in LAYER_WEIGHT_NAMES} for lw in weights["layers"]]
+    return g
+
+
+def t5_stack_loss_and_grad(sc, tokens, targets, weights, grads=None, want_grads=True, accumulate=False,
+                           workspace=None, loss=None):
+    """Loss (and gradients) of a stack of blocks with embedding, final norm, logits and cross-entropy with
+    z-loss.  weights: {"embedding", "rel_table", "final_scale", "logits_w" (untied), "layers": [dict of the
+    block's tensors without rel_table, per layer]}.  Returns (loss tensor of one float32, grads or None)."""
+    b = sc.block
+    cs = _stack_cfg_struct(sc)
+    dt = _torch_dtype(b)
+    n_tok = b.batch * b.seq
+    _check_tensor(tokens, torch.int32, n_tok, "tokens")
+    _check_tensor(targets, torch.int32, n_tok, "targets")
+    _check_tensor(weights["embedding"], dt, sc.vocab * b.d_model, "embedding")
+    _check_tensor(weights["rel_table"], dt, b.num_buckets * b.n_heads, "rel_table")
+    _check_tensor(weights["final_scale"], dt, b.d_model, "final_scale")
+    if not sc.tied_logits:
+        _check_tensor(weights["logits_w"], dt, sc.vocab * b.d_model, "logits_w")
+    if len(weights["layers"]) != sc.n_layers:
+        raise ValueError("weights['layers'] must hold n_layers dicts")
+    lw = (_Weights * sc.n_layers)()
+    for l, d in enumerate(weights["layers"]):
+        lw[l] = _weights_struct(b, dict(d, rel_table=weights["rel_table"]))
+    ws = _StackWeights(weights["embedding"].data_ptr(), weights["rel_table"].data_ptr(), lw,
+                       weights["final_scale"].data_ptr(),
+                       None if sc.tied_logits else weights["logits_w"].data_ptr())
+    gs_ref = None
+    if want_grads:
+        if grads is None:
+            grads = alloc_stack_grads(sc, weights)
+        names = ["embedding", "rel_table", "final_scale"] + ([] if sc.tied_logits else ["logits_w"])
+        for nme in names:
+            _check_tensor(grads[nme], torch.float32, weights[nme].numel(), "grad " + nme)
+        lg = (_Grads * sc.n_layers)()
+        for l, d in enumerate(grads["layers"]):
+            for nme in LAYER_WEIGHT_NAMES:
+                _check_tensor(d[nme], torch.float32, weights["layers"][l][nme].numel(), f"grad layer {l} {nme}")
+            lg[l] = _Grads(*[(d[nme].data_ptr() if nme != "rel_table" else grads["rel_table"].data_ptr())
+                             for nme in WEIGHT_NAMES])
+        gs = _StackGrads(grads["embedding"].data_ptr(), grads["rel_table"].data_ptr(), lg,
+                         grads["final_scale"].data_ptr(), None if sc.tied_logits else grads["logits_w"].data_ptr())
+        gs_ref = C.byref(gs)
+    else:
+        grads = None
+    if loss is None:
+        loss = torch.zeros(1, dtype=torch.float32, device=tokens.device)
+    if workspace is None:
+        workspace = _byte_buffer(lib().t5_stack_workspace_bytes(C.byref(cs)), tokens.device)
+    rc = lib().t5_stack_loss_and_grad(C.byref(cs), _ptr(tokens), _ptr(targets), C.byref(ws), _ptr(loss), gs_ref,
+                                      int(bool(accumulate)), _ptr(workspace), workspace.numel(), _stream())
+    if rc:
+        raise T5Error(rc, "t5_stack_loss_and_grad")
+    return loss, grads
 
 
 def adafactor_workspace_bytes(rows: int, cols: int, factored: bool) -> int:

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libt5mi.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["relpos.hip", "rmsnorm.hip", "gemm_simple.hip", "gemm_mfma.hip", "attn_simple.hip",
-           "attn_mfma.hip", "adafactor.hip", "probe.hip", "block.hip"]
+           "attn_mfma.hip", "adafactor.hip", "probe.hip", "embed_xent.hip", "block.hip", "stack.hip"]
 # -packed-fp32-ops is switched off: hand-written and compiler-made packed float32 math is avoided on
 # this target.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",

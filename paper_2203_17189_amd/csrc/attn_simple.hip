@@ -177,10 +177,10 @@ hipError_t launch_attn_fwd_simple(const AttnIO& io, int type, const float* diag,
 
 hipError_t launch_attn_bwd_simple(const AttnIO& io, const void* c, const void* dc, int type,
                                   const float* diag, const float* lse, float* dvec, float* ddiag,
-                                  const AttnDims& a, hipStream_t st) {
+                                  const AttnDims& a, int zero_ddiag, hipStream_t st) {
   const int grid_q = ceil_div((int64_t)a.B * a.H * a.S, AW);
   const int grid_k = ceil_div((int64_t)a.B * a.H * a.Sk, AW);
-  if (a.bias) {
+  if (a.bias && zero_ddiag) {
     const int64_t nd = (int64_t)a.H * (2 * a.S - 1);
     zero_diag_kernel<<<ceil_div(nd, 256), 256, 0, st>>>(ddiag, nd);
   }

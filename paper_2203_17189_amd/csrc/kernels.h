@@ -23,7 +23,7 @@ enum { IN_F32 = 0, IN_BF16 = 1 };
 hipError_t launch_rmsnorm_fwd(const void* x, int x_type, const void* g, void* n, int out_type, float* r,
                               int T, int d, float eps, hipStream_t st);
 // dx_total = resid + r * (dn*g - xh * mean(dn*g*xh)),  xh = x*r;  dg (+)= sum_T dn*xh.
-// x of x_type; g of g_type; dn float32; resid of resid_type; outputs: out_f32 (nullable),
+// x of x_type; g of g_type; dn float32; resid of resid_type (nullable: no residual term); outputs: out_f32 (nullable),
 // out_lp (nullable, lp_type).  dg_partial: workspace float[rmsnorm_bwd_partial_rows(T) * d].
 int rmsnorm_bwd_partial_rows(int T);
 hipError_t launch_rmsnorm_bwd(const void* x, int x_type, const void* g, int g_type, const float* r,
@@ -137,11 +137,11 @@ inline AttnIO attn_io_packed(const void* qkv, void* dqkv, int I, size_t es) {
 // c: [B*S, H*dk].  lse: [B,H,S] float32.  diag: [H, 2S-1] (unused without bias).
 hipError_t launch_attn_fwd_simple(const AttnIO& io, int type, const float* diag, void* c, float* lse,
                                   const AttnDims& a, hipStream_t st);
-// dc: [B*S, H*dk] gradient of c.  Writes dq, dk, dv, dvec [B,H,S] (scratch) and, with bias,
-// ddiag [H, 2S-1] float32 (zeroed inside).
+// dc: [B*S, H*dk] gradient of c.  Writes dq, dk, dv, dvec [B,H,S] (scratch) and, with bias, adds the
+// bias gradient into ddiag [H, 2S-1] float32 (cleared first when zero_ddiag is set).
 hipError_t launch_attn_bwd_simple(const AttnIO& io, const void* c, const void* dc, int type,
                                   const float* diag, const float* lse, float* dvec, float* ddiag,
-                                  const AttnDims& a, hipStream_t st);
+                                  const AttnDims& a, int zero_ddiag, hipStream_t st);
 bool attn_mfma_supported(const AttnDims& a);
 hipError_t launch_attn_fwd_mfma(const AttnIO& io, const float* diag, void* c, float* lse, const AttnDims& a,
                                 hipStream_t st);
@@ -153,6 +153,27 @@ bool attn_bwd_mfma_fits(const AttnDims& a, int far);
 hipError_t launch_attn_bwd_mfma(const AttnIO& io, const void* c, const void* dc, const float* diag,
                                 const float* lse, float* dvec, float* ddiag, const AttnDims& a, int far,
                                 int phase, hipStream_t st);
+
+// ------------------------------------------------------------------ ends of the layer stack
+// x[r, :] = E[tokens[r], :] (storage type); ids outside [0, vocab) are clamped into it.
+hipError_t launch_embed_fwd(const int32_t* tokens, const void* E, void* x, int type, int64_t rows, int d, int vocab,
+                            hipStream_t st);
+// dE[tokens[r], :] += dx[r, :] with float32 atomics; the caller clears dE.
+hipError_t launch_embed_bwd(const int32_t* tokens, const void* dx, int type, float* dE, int64_t rows, int d,
+                            int vocab, hipStream_t st);
+// *n_valid = number of rows with 0 <= target < vocab, as a float.
+hipError_t launch_xent_count(const int32_t* targets, int64_t rows, int vocab, float* n_valid, hipStream_t st);
+// Per row of logits [rows, ld] (V used columns): loss_rows[r] = lse - logit[target] + z_loss lse^2 (0 when
+// the row has no target); with want_grad the logits are overwritten by d(mean loss)/d(logits) =
+// (softmax (1 + 2 z_loss lse) - onehot) / max(*n_valid, 1).
+hipError_t launch_xent_rows(void* logits, int type, const int32_t* targets, int64_t rows, int V, int ld, float z_loss,
+                            const float* n_valid, float* loss_rows, int want_grad, hipStream_t st);
+// *loss_out = sum(loss_rows) / max(*n_valid, 1), fixed summation order.
+hipError_t launch_loss_reduce(const float* loss_rows, int64_t rows, const float* n_valid, float* loss_out,
+                              hipStream_t st);
+// out = (accumulate ? out : 0) + alpha * in (float32);  out = alpha * in (storage type)
+hipError_t launch_axpy_f32(float* out, const float* in, float alpha, int n, int accumulate, hipStream_t st);
+hipError_t launch_scale_vec(void* out, const void* in, float alpha, int n, int type, hipStream_t st);
 
 // ------------------------------------------------------------------ measurement aid
 // Register-only MFMA loop: each of the 4 waves of a workgroup issues iters * 32 v_mfma_f32_32x32x16_bf16.

@@ -121,7 +121,12 @@ __global__ __launch_bounds__(kNormWaves * 64) void rmsnorm_bwd_kernel(
         load_vec<TX, VEC>(xr + c, xv);
         load_vec<float, VEC>(dnr + c, dv);
         load_vec<TG, VEC>(g + c, gv);
-        load_vec<TR, VEC>(resid + (size_t)row * d + c, rv);
+        if (resid) {
+          load_vec<TR, VEC>(resid + (size_t)row * d + c, rv);
+        } else {
+#pragma unroll
+          for (int i = 0; i < VEC; ++i) rv[i] = 0.f;
+        }
 #pragma unroll
         for (int i = 0; i < VEC; ++i) o[i] = rv[i] + rr * (dv[i] * gv[i] - xv[i] * rr * dot);
         if (out_f32) store_vec<float, VEC>(out_f32 + (size_t)row * d + c, o);

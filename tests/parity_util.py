@@ -30,9 +30,23 @@ TOL_BF16_DEC_DX_NAMED = (3e-2, 2.5e-3)   # the named-workload dx bound times sqr
 TOL_BF16_DENC_NAMED = TOL_BF16_DW_NAMED
 
 
-def rel_err(gpu: np.ndarray, ref: np.ndarray):
+def stack_bf16_tol(n_layers: int):
+    """Weight-gradient bound of an n_layers-deep bf16 stack.  The gradient that reaches a layer has
+    crossed the bf16-rounded operands of every layer above it (and the activations those of every
+    layer below); the per-layer errors are independent, so they add in quadrature: the block's bound
+    times sqrt(n_layers).  The loss itself is a mean over all positions of values computed from
+    bf16 logits: 5e-4 relative."""
+    f = float(n_layers) ** 0.5
+    return TOL_BF16_DW[0] * f, TOL_BF16_DW[1] * f
+
+
+def rel_err(gpu: np.ndarray, ref: np.ndarray, rms: float | None = None):
+    """(max, mean) of e_i.  rms: scale to use instead of RMS(ref) -- for gradients that are zero or
+    near zero outside a small support (embedding rows of tokens that occur, output-matrix columns of
+    targets that occur) the RMS over the support, so that the empty part does not shrink the scale."""
     gpu = np.asarray(gpu, dtype=np.float64).reshape(ref.shape)
-    rms = float(np.sqrt(np.mean(ref * ref)))
+    if rms is None:
+        rms = float(np.sqrt(np.mean(ref * ref)))
     if rms == 0.0:
         return float(np.abs(gpu).max()), float(np.abs(gpu).mean())
     e = np.abs(gpu - ref) / np.maximum(np.abs(ref), rms)

@@ -114,6 +114,37 @@ def test_decoder_block_validation():
     assert bwd(0, dummy, C.byref(g), C.byref(xg), big) == 2
 
 
+def test_stack_validation():
+    lib = P.lib()
+    sc = SI.STACK_CONFIGS["s1_lm_base"]
+    assert P.t5_stack_workspace_bytes(sc) > sc.n_layers * P.t5_block_stash_bytes(sc.block)
+    from dataclasses import replace
+    assert P.t5_stack_workspace_bytes(replace(sc, remat=True)) < P.t5_stack_workspace_bytes(sc) // 2
+    assert P.t5_stack_workspace_bytes(replace(sc, n_layers=0)) == 0
+    assert P.t5_stack_workspace_bytes(replace(sc, vocab=1)) == 0
+    cs = B._stack_cfg_struct(replace(sc, n_layers=2))
+    dummy = C.c_void_p(4096)
+    lw = (B._Weights * 2)(B._Weights(*([4096] * 10)), B._Weights(*([4096] * 9 + [None])))
+    ok_lw = (B._Weights * 2)(B._Weights(*([4096] * 10)), B._Weights(*([4096] * 10)))
+    mk = lambda layers, emb=4096, out=4096: B._StackWeights(emb, 4096, layers, 4096, out)
+    call = lambda c, tok, wts, loss, grads, nbytes: lib.t5_stack_loss_and_grad(c, tok, dummy, wts, loss, grads, 0,
+                                                                               dummy, nbytes, None)
+    big = 1 << 40
+    assert call(None, dummy, C.byref(mk(ok_lw)), dummy, None, big) == 1
+    assert call(C.byref(cs), None, C.byref(mk(ok_lw)), dummy, None, big) == 1
+    assert call(C.byref(cs), dummy, C.byref(mk(ok_lw)), None, None, big) == 1
+    assert call(C.byref(cs), dummy, C.byref(mk(lw)), dummy, None, big) == 1              # a layer lacks wo_ff
+    assert call(C.byref(cs), dummy, C.byref(mk(ok_lw, out=None)), dummy, None, big) == 1  # untied needs logits_w
+    assert call(C.byref(cs), dummy, C.byref(mk(ok_lw)), dummy, None, 1024) == 4
+    lg = (B._Grads * 2)(B._Grads(*([4096] * 10)), B._Grads(*([4096] * 10)))
+    bad_g = B._StackGrads(None, 4096, lg, 4096, 4096)
+    assert call(C.byref(cs), dummy, C.byref(mk(ok_lw)), dummy, C.byref(bad_g), big) == 1
+    neg = B._stack_cfg_struct(replace(sc, z_loss=-1.0))
+    assert call(C.byref(neg), dummy, C.byref(mk(ok_lw)), dummy, None, big) == 2
+    tied = B._stack_cfg_struct(replace(sc, n_layers=2, tied_logits=True))
+    assert call(C.byref(tied), dummy, C.byref(mk(ok_lw, out=None)), dummy, None, 1024) == 4   # tied: logits_w not needed
+
+
 def test_adafactor_validation():
     lib = P.lib()
     dummy = C.c_void_p(4096)

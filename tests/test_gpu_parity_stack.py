@@ -1,0 +1,149 @@
+"""GPU parity of the layer stack (embedding, N blocks with a shared bias table, final norm, logits,
+cross-entropy with z-loss; forward + backward in one call) through the C ABI against the float64 oracle."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as SI
+from oracle import t5_oracle as O
+from parity_util import TOL_F32, rel_err, stack_bf16_tol, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+BLK = SI.BlockConfig("stack_f32", 60, batch=2, seq=24, d_model=32, n_heads=2, d_kv=8, d_ff=48, dtype="f32", causal=True)
+F32_CASES = [
+    SI.StackConfig("stack_f32", BLK, n_layers=3, vocab=29, z_loss=1e-2),                       # odd vocab: generic loss kernel
+    SI.StackConfig("stack_f32_tied", replace(BLK, index=61, causal=False), n_layers=2, vocab=64, tied_logits=True,
+                   z_loss=1e-3),                                                               # 16-byte rows: register loss kernel
+    SI.StackConfig("stack_f32_remat", replace(BLK, index=62), n_layers=3, vocab=40, remat=True, z_loss=0.0),
+    SI.StackConfig("stack_f32_wide_vocab", replace(BLK, index=63, batch=1, seq=16), n_layers=1, vocab=5000, z_loss=1e-4),
+]
+
+
+def _case(sc, ignore_fraction=0.15):
+    w = SI.make_stack_weights(sc)
+    SI.make_stack_random_scales(sc, w)
+    tokens, targets = SI.make_tokens(sc, ignore_fraction=ignore_fraction)
+    return w, tokens, targets
+
+
+def _upload(sc, w, tokens, targets):
+    dt = sc.block.dtype
+    dw = {k: to_dev(v, dt) for k, v in w.items() if k != "layers"}
+    dw["layers"] = [{k: to_dev(v, dt) for k, v in lw.items()} for lw in w["layers"]]
+    return dw, torch.from_numpy(tokens).cuda(), torch.from_numpy(targets).cuda()
+
+
+def _run(sc, w, tokens, targets, **kw):
+    import paper_2203_17189_amd as P
+    dw, tt, tg = _upload(sc, w, tokens, targets)
+    loss, grads = P.t5_stack_loss_and_grad(sc, tt, tg, dw, **kw)
+    torch.cuda.synchronize()
+    return float(loss.item()), grads
+
+
+def _compare(sc, tol_loss, tol, tol_mean=None, verbose=True):
+    w, tokens, targets = _case(sc)
+    loss, saved = O.stack_loss(sc, tokens, targets, w)
+    g = O.stack_loss_grad(sc, w, saved)
+    gl, gg = _run(sc, w, tokens, targets)
+    errs = {}
+    for name in [k for k in g if k != "layers"]:
+        rms = None
+        if name == "embedding" and not sc.tied_logits:      # nonzero only in the rows of tokens that occur
+            rows = np.unique(tokens)
+            rms = float(np.sqrt(np.mean(g[name][rows] ** 2)))
+            assert np.all(to_np(gg[name])[np.setdiff1d(np.arange(sc.vocab), rows)] == 0)
+        if name == "logits_w":                              # dominated by the columns of targets that occur
+            cols = np.unique(targets[targets >= 0])
+            rms = float(np.sqrt(np.mean(g[name][:, cols] ** 2)))
+        errs[name] = rel_err(to_np(gg[name]), g[name], rms)
+    for l in range(sc.n_layers):
+        for name, val in g["layers"][l].items():
+            errs[f"L{l}.{name}"] = rel_err(to_np(gg["layers"][l][name]), val)
+    if verbose:
+        worst = sorted(errs.items(), key=lambda kv: -kv[1][0])[:6]
+        print(sc.name, "loss", gl, loss, "worst", [(k, tuple(round(x, 5) for x in v)) for k, v in worst])
+    assert abs(gl - loss) <= tol_loss * max(1.0, abs(loss)), (gl, loss)
+    for k, e in errs.items():
+        assert e[0] <= tol, (k, e)
+        if tol_mean is not None:
+            assert e[1] <= tol_mean, (k, e)
+    return errs
+
+
+@pytest.mark.parametrize("sc", F32_CASES, ids=[c.name for c in F32_CASES])
+def test_stack_f32(sc):
+    _compare(sc, 1e-5, TOL_F32[0])
+
+
+def test_stack_loss_only_accumulate_and_no_targets():
+    import paper_2203_17189_amd as P
+    sc = F32_CASES[0]
+    w, tokens, targets = _case(sc)
+    dw, tt, tg = _upload(sc, w, tokens, targets)
+    loss, g1 = P.t5_stack_loss_and_grad(sc, tt, tg, dw)
+    loss_only, none = P.t5_stack_loss_and_grad(sc, tt, tg, dw, want_grads=False)
+    assert none is None and torch.equal(loss, loss_only)
+    clone = lambda g: {k: ([{n: t.clone() for n, t in d.items()} for d in v] if k == "layers" else v.clone())
+                       for k, v in g.items()}
+    g2 = clone(g1)
+    P.t5_stack_loss_and_grad(sc, tt, tg, dw, grads=g2, accumulate=True)
+    torch.cuda.synchronize()
+    for k in ("embedding", "rel_table", "final_scale", "logits_w"):
+        np.testing.assert_allclose(to_np(g2[k]), 2 * to_np(g1[k]), rtol=2e-5, atol=1e-7)
+    for l in range(sc.n_layers):
+        for n in g1["layers"][l]:
+            np.testing.assert_allclose(to_np(g2["layers"][l][n]), 2 * to_np(g1["layers"][l][n]), rtol=2e-5, atol=1e-7)
+    # no position carries a loss: zero loss, zero gradients, no division by zero
+    none_t = torch.full_like(tg, -1)
+    loss0, g0 = P.t5_stack_loss_and_grad(sc, tt, none_t, dw)
+    torch.cuda.synchronize()
+    assert float(loss0.item()) == 0.0
+    assert all(float(g0[k].abs().max()) == 0.0 for k in ("embedding", "rel_table", "final_scale", "logits_w"))
+    # out-of-range targets are ignored like negative ones
+    big_t = torch.where(tg < 0, torch.full_like(tg, sc.vocab + 5), tg)
+    loss_b, _ = P.t5_stack_loss_and_grad(sc, tt, big_t, dw, want_grads=False)
+    assert torch.equal(loss_b, loss)
+
+
+BF_BLK = SI.BlockConfig("stack_bf16", 64, batch=2, seq=128, d_model=128, n_heads=2, d_kv=64, d_ff=256, causal=True,
+                        attn_scale=64 ** -0.5)
+BF16_CASES = [
+    SI.StackConfig("stack_bf16", BF_BLK, n_layers=2, vocab=512),
+    SI.StackConfig("stack_bf16_tied", replace(BF_BLK, index=65, causal=False), n_layers=2, vocab=512, tied_logits=True),
+    SI.StackConfig("stack_bf16_t5_vocab", replace(BF_BLK, index=66, batch=1, d_model=64, n_heads=1, d_ff=128),
+                   n_layers=1, vocab=32128),
+    SI.StackConfig("stack_bf16_ragged", SI.BlockConfig("stack_bf16_ragged", 67, batch=1, seq=50, d_model=72, n_heads=3,
+                                                        d_kv=24, d_ff=136, causal=True, attn_scale=24 ** -0.5),
+                   n_layers=2, vocab=301),
+]
+
+
+@pytest.mark.parametrize("sc", BF16_CASES, ids=[c.name for c in BF16_CASES])
+def test_stack_bf16_small(sc):
+    _compare(sc, 5e-4, *stack_bf16_tol(sc.n_layers))
+
+
+def test_stack_bf16_remat_matches_stashed():
+    """Recomputing each layer inside the backward sweep gives the same loss bit for bit and the same
+    gradients up to the order of the float32 atomic additions."""
+    sc = BF16_CASES[0]
+    w, tokens, targets = _case(sc)
+    l1, g1 = _run(sc, w, tokens, targets)
+    l2, g2 = _run(replace(sc, remat=True), w, tokens, targets)
+    assert l1 == l2
+    for k in ("embedding", "rel_table", "final_scale", "logits_w"):
+        a = to_np(g1[k]); assert np.abs(to_np(g2[k]) - a).max() <= 1e-4 * np.abs(a).max(), k
+    for l in range(sc.n_layers):
+        for n in g1["layers"][l]:
+            a = to_np(g1["layers"][l][n]); assert np.abs(to_np(g2["layers"][l][n]) - a).max() <= 1e-4 * np.abs(a).max(), (l, n)
+
+
+def test_stack_named_config_reduced_batch():
+    """T5.1.1-Base decoder-only stack at its real depth, widths, length and vocabulary, one sequence."""
+    sc = replace(SI.STACK_CONFIGS["s1_lm_base"].with_batch(1), name="s1_lm_base_b1")
+    sc = replace(sc, block=replace(sc.block, attn_scale=64 ** -0.5))
+    _compare(sc, 5e-4, *stack_bf16_tol(sc.n_layers))
