@@ -121,51 +121,72 @@ __global__ __launch_bounds__(256) void xent_rows_vec_kernel(T* __restrict__ logi
   T* x = logits + (size_t)row * ld;
   const int tgt = targets[row];
   const bool counted = tgt >= 0 && tgt < V;
-  VT raw[NV];
+  // The row is kept as raw 16-byte vectors; each pass converts on the fly.  The empty asm statements
+  // make vector i depend on the result of vector i-1, so that the compiler cannot convert the whole row
+  // to float32 first and run all exponentials afterwards (2-4x the registers: one wave per SIMD).
+  // Vectors past the end of the row are loaded from its last vector and replaced by -inf, so that the
+  // passes below need no per-vector branches (exp(-inf - m) = 0).
+  constexpr uint32_t kNegInf = sizeof(T) == 2 ? 0xFF80FF80u : 0xFF800000u;
+  v16 raw[NV];
   float m = -INFINITY;
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     const int c = (i * 256 + threadIdx.x) * EPV;
-    if (c < V) {
-      raw[i] = __builtin_bit_cast(VT, __builtin_nontemporal_load(reinterpret_cast<const v16*>(x + c)));
+    const int cc = c < V ? c : V - EPV;
+    v16 r = __builtin_nontemporal_load(reinterpret_cast<const v16*>(x + cc));
+    if (c >= V) r = v16{kNegInf, kNegInf, kNegInf, kNegInf};
+    raw[i] = r;
+  }
 #pragma unroll
-      for (int k = 0; k < EPV; ++k) m = fmaxf(m, to_f32(raw[i][k]));
-    }
+  for (int i = 0; i < NV; ++i) {
+    const VT v = __builtin_bit_cast(VT, raw[i]);
+#pragma unroll
+    for (int k = 0; k < EPV; ++k) m = fmaxf(m, to_f32(v[k]));
+    __builtin_amdgcn_sched_barrier(0);
   }
   m = block_max<4>(m, red);
+  const int rel0 = tgt - (int)threadIdx.x * EPV;
   float s = 0.f;
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
-    const int c = (i * 256 + threadIdx.x) * EPV;
-    if (c < V) {
+    asm volatile("" : "+v"(raw[i]), "+v"(s), "+v"(m));  // vector i is not touched before vector i-1 is summed
+    const VT v = __builtin_bit_cast(VT, raw[i]);
 #pragma unroll
-      for (int k = 0; k < EPV; ++k) {
-        const float v = to_f32(raw[i][k]);
-        s += __expf(v - m);
-        if (c + k == tgt) tgt_logit = v;  // one thread owns the target's logit; read after the barriers below
-      }
+    for (int k = 0; k < EPV; ++k) s += __expf(to_f32(v[k]) - m);
+    // one thread owns the target's logit; thread 0 reads it after the barriers of block_sum()
+    const int rel = rel0 - i * 256 * EPV;  // position of the target inside this vector, if 0 <= rel < EPV
+    if (counted && (unsigned)rel < (unsigned)EPV) {
+      float f = 0.f;
+#pragma unroll
+      for (int k = 0; k < EPV; ++k) f = (rel == k) ? to_f32(v[k]) : f;
+      tgt_logit = f;
     }
+    __builtin_amdgcn_sched_barrier(0);
   }
   s = block_sum<4>(s, red);
-  const float lse = m + __logf(s);
+  float lse = m + __logf(s);
   if (threadIdx.x == 0) loss_rows[row] = counted ? lse - tgt_logit + z_loss * lse * lse : 0.f;
   if constexpr (GRAD) {
     // each thread overwrites exactly the vectors it read
     const float inv_n = counted ? 1.f / fmaxf(*n_valid, 1.f) : 0.f;
     const float gain = (1.f + 2.f * z_loss * lse) * inv_n;
+    uint32_t chain = 0;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const int c = (i * 256 + threadIdx.x) * EPV;
-      if (c < V) {
-        VT outv;
+      asm volatile("" : "+v"(raw[i]), "+v"(chain), "+v"(lse));  // one vector at a time, as above
+      const int rel = rel0 - i * 256 * EPV;
+      const VT v = __builtin_bit_cast(VT, raw[i]);
+      VT outv;
 #pragma unroll
-        for (int k = 0; k < EPV; ++k) {
-          float gv = __expf(to_f32(raw[i][k]) - lse) * gain;
-          if (c + k == tgt) gv -= inv_n;
-          outv[k] = from_f32<T>(gv);
-        }
-        __builtin_nontemporal_store(__builtin_bit_cast(v16, outv), reinterpret_cast<v16*>(x + c));
+      for (int k = 0; k < EPV; ++k) {
+        float gv = __expf(to_f32(v[k]) - lse) * gain;
+        if (rel == k) gv -= inv_n;
+        outv[k] = from_f32<T>(gv);
       }
+      const v16 ob = __builtin_bit_cast(v16, outv);
+      chain = ob[3];
+      if (c < V) __builtin_nontemporal_store(ob, reinterpret_cast<v16*>(x + c));
     }
   }
 }
