@@ -72,6 +72,26 @@ def cpu_baseline_stack(sc, sample_batch: int) -> dict:
                       f"numpy, {dt:.2f} s for one loss + gradient"}
 
 
+def cpu_baseline_encdec(ec, sample_batch: int) -> dict:
+    from oracle import t5_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    c = ec.with_batch(sample_batch)
+    w = SI.make_encdec_weights(c)
+    et, dtk, tg = SI.make_encdec_tokens(c)
+    t0 = time.perf_counter()
+    loss, saved = O.encdec_loss(c, et, dtk, tg, w)
+    O.encdec_loss_grad(c, w, saved)
+    dt = time.perf_counter() - t0
+    return {"value": (c.enc_block.tokens + c.dec_block.tokens) / dt, "unit": "tokens/s", "cores": int(threads),
+            "kind": "oracle",
+            "sample": f"{ec.name} at batch {sample_batch} of {ec.dec_block.batch} (same depth/lengths/width/vocab), "
+                      f"float64 numpy, {dt:.2f} s for one loss + gradient"}
+
+
 def cpu_baseline(cfg, sample_batch: int) -> dict:
     from oracle import t5_oracle as O
     try:
@@ -108,7 +128,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2_small", choices=[k for k in SI.CONFIGS if k != "c1_tiny_f32"] + list(SI.STACK_CONFIGS))
+    ap.add_argument("--workload", default="c2_small", choices=[k for k in SI.CONFIGS if k != "c1_tiny_f32"] + list(SI.STACK_CONFIGS) + list(SI.ENCDEC_CONFIGS))
     ap.add_argument("--cpu-sample-batch", type=int, default=0, help="0 = pick about 10-30 s of oracle work")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -127,7 +147,8 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     sc = SI.STACK_CONFIGS.get(args.workload)
-    cfg = sc.block if sc is not None else SI.CONFIGS[args.workload]
+    ec = SI.ENCDEC_CONFIGS.get(args.workload)
+    cfg = sc.block if sc is not None else (ec.dec_block if ec is not None else SI.CONFIGS[args.workload])
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     if args.calibrate_copy:
@@ -142,7 +163,19 @@ def main() -> int:
     # ---- seeded synthetic inputs, generated on the host, resident in HBM before timing
     dt_t = torch.bfloat16
     up = lambda v: torch.from_numpy(v.astype(np.float32)).to(dev).to(dt_t)
-    if sc is not None:
+    if ec is not None:
+        ws_host = SI.make_encdec_weights(ec)
+        sw = {k: up(v) for k, v in ws_host.items() if not k.endswith("_layers")}
+        for side in ("enc_layers", "dec_layers"):
+            sw[side] = [{k: up(v) for k, v in lw.items()} for lw in ws_host[side]]
+        del ws_host
+        et_h, dt_h, tg_h = SI.make_encdec_tokens(ec)
+        e_tok, s_tok, s_tgt = (torch.from_numpy(a).to(dev) for a in (et_h, dt_h, tg_h))
+        s_grads = B.alloc_encdec_grads(ec, sw)
+        s_ws = torch.empty(P.t5_encdec_workspace_bytes(ec), dtype=torch.uint8, device=dev)
+        s_loss = torch.zeros(1, dtype=torch.float32, device=dev)
+        w_host = {"rel_table": np.zeros((cfg.num_buckets, cfg.n_heads))}
+    elif sc is not None:
         ws_host = SI.make_stack_weights(sc)
         sw = {k: up(v) for k, v in ws_host.items() if k != "layers"}
         sw["layers"] = [{k: up(v) for k, v in lw.items()} for lw in ws_host["layers"]]
@@ -158,7 +191,7 @@ def main() -> int:
     w = {k: up(v) for k, v in w_host.items()}
     decoder = cfg.enc_seq > 0
     opt = None
-    if sc is None:
+    if sc is None and ec is None:
         rng = np.random.default_rng(SI.BASE_SEED + 1000 * cfg.index)
         shape = (cfg.batch, cfg.seq, cfg.d_model)
         x = torch.from_numpy(rng.standard_normal(shape, dtype=np.float32)).to(dev).to(dt_t)
@@ -193,6 +226,9 @@ def main() -> int:
     step_no = [0]
 
     def step():
+        if ec is not None:
+            P.t5_encdec_loss_and_grad(ec, e_tok, s_tok, s_tgt, sw, grads=s_grads, workspace=s_ws, loss=s_loss)
+            return
         if sc is not None:
             P.t5_stack_loss_and_grad(sc, s_tok, s_tgt, sw, grads=s_grads, workspace=s_ws, loss=s_loss)
             return
@@ -215,8 +251,9 @@ def main() -> int:
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
-    tokens_per_s = cfg.tokens * args.steps / dt
-    total_model_flops = sc.model_flops() if sc is not None else cfg.model_flops()
+    step_tokens = cfg.tokens + (ec.enc_block.tokens if ec is not None else 0)
+    tokens_per_s = step_tokens * args.steps / dt
+    total_model_flops = sc.model_flops() if sc is not None else (ec.model_flops() if ec is not None else cfg.model_flops())
     model_tflops = total_model_flops / (ms_per_step * 1e-3) / 1e12
 
     # ---- instrumented pass: per-step HIP-event timing on the launch stream
@@ -228,10 +265,15 @@ def main() -> int:
     timing = P.t5_step_timing_read()
     P.t5_step_timing_enable(False)
     flops = gemm_step_flops(cfg)
-    if sc is not None:
+    if sc is not None or ec is not None:
         chunk = min(cfg.tokens, 8192)
         for name in ("gemm_logits", "gemm_dnf", "gemm_dlogits_w"):
-            flops[name] = 2.0 * chunk * cfg.d_model * sc.vocab
+            flops[name] = 2.0 * chunk * cfg.d_model * (sc or ec).vocab
+    if ec is not None:
+        # encoder and decoder layers launch the same step names at different token counts: per-step rates
+        # would mix the two, so only the steps that exist on one side keep a FLOP count
+        flops = {k: v for k, v in flops.items() if k.startswith(("gemm_x", "xattn", "gemm_dx", "gemm_dcx", "gemm_denc",
+                                                                 "gemm_dnx", "gemm_logits", "gemm_dnf", "gemm_dlogits"))}
     per_kernel = {k: {"avg_ms": v[0] / v[1], "launches_per_step": v[1] / n_prof} for k, v in timing.items()}
     step_ms = {k: v["avg_ms"] * v["launches_per_step"] for k, v in per_kernel.items()}
     fwd_names = {"relpos_diag", "rmsnorm_fwd", "pack_weights", "gemm_qkv", "attn_fwd", "gemm_o", "gemm_wi_geglu",
@@ -245,8 +287,12 @@ def main() -> int:
     n_params = sum(int(v.numel()) for v in w.values())
     # launches of each norm kernel per step
     n_norm = 2 * sc.n_layers + 1 if sc is not None else (3 if decoder else 2)
+    if ec is not None:
+        n_norm = 0  # encoder and decoder norms differ in size: no per-step byte count
     hbm_bytes = {"rmsnorm_fwd": n_norm * (2.0 * Tn * dn_ * 2 + 4.0 * Tn), "rmsnorm_bwd": n_norm * (4.0 * Tn * dn_ * 2),
                  "adafactor": 14.0 * n_params}
+    if ec is not None:
+        hbm_bytes = {"xent_rows": 2.0 * Tn * ec.vocab * 2}
     if sc is not None:
         # the loss reads every logit once and writes its gradient over it; the lookup copies T rows, its
         # gradient reads T rows and adds them into float32 rows (read + write)
@@ -314,7 +360,10 @@ def main() -> int:
                    "enc_seq_len": cfg.enc_seq,
                    "adafactor": cfg.adafactor, "passes": "fwd+bwd" + ("+adafactor" if cfg.adafactor else ""),
                    **({"n_layers": sc.n_layers, "vocab": sc.vocab, "tied_logits": sc.tied_logits, "remat": sc.remat,
-                       "z_loss": sc.z_loss} if sc is not None else {})},
+                       "z_loss": sc.z_loss} if sc is not None else {}),
+                   **({"n_enc_layers": ec.n_enc_layers, "n_dec_layers": ec.n_dec_layers, "vocab": ec.vocab,
+                       "enc_seq_len": ec.enc_block.seq, "tokens_counted": "encoder + decoder positions",
+                       "tied_logits": ec.tied_logits, "remat": ec.remat, "z_loss": ec.z_loss} if ec is not None else {})},
         "model_tflops": round(model_tflops, 2), "frac_of_mfma_peak": round(model_tflops / PEAK_BF16_TFLOPS, 4),
         "roofline": roofline, **phase_ms, "machine": machine, "per_kernel": per_kernel,
     }
@@ -324,7 +373,8 @@ def main() -> int:
             # float64 numpy sustains very roughly 50 GFLOP/s on a handful of cores; aim near 15 s
             per_seq = total_model_flops / cfg.batch
             sb = int(max(1, min(cfg.batch, 15.0 * 50e9 / per_seq)))
-        out["cpu_baseline"] = cpu_baseline_stack(sc, sb) if sc is not None else cpu_baseline(cfg, sb)
+        out["cpu_baseline"] = (cpu_baseline_stack(sc, sb) if sc is not None else
+                               cpu_baseline_encdec(ec, sb) if ec is not None else cpu_baseline(cfg, sb))
     print(json.dumps(out))
     return 0
 

@@ -216,6 +216,60 @@ int t5_stack_loss_and_grad(const t5_stack_cfg* cfg, const int32_t* tokens, const
                            const t5_stack_weights* w, float* loss, const t5_stack_grads* grads,
                            int accumulate, void* workspace, size_t workspace_bytes, void* stream);
 
+/* The encoder-decoder model (paper Sec. 4: T5.1.1): an encoder stack of bidirectional blocks and a
+ * decoder stack of causal blocks with cross-attention (t5_decoder_block_*), sharing one token
+ * embedding:
+ *   enc_out = RMSNorm(encoder_layers(E[enc_tokens]); enc_final_scale)
+ *   x_{l+1} = decoder_block_l(x_l, enc_out),  x_0 = E[dec_tokens]
+ *   nf = RMSNorm(x_L; dec_final_scale);  logits and loss as for t5_stack_cfg
+ * Each stack has its own shared relative-position table (bidirectional / unidirectional buckets);
+ * cross-attention has none.  The gradient of enc_out is the sum over the decoder layers.
+ * enc_block.causal must be 0, dec_block.causal != 0; batch, d_model and dtype must agree;
+ * enc_block.seq is the encoder length, dec_block.seq the decoder length. */
+typedef struct {
+  t5_block_cfg enc_block;
+  t5_block_cfg dec_block;
+  int32_t n_enc_layers, n_dec_layers;
+  int32_t vocab;
+  int32_t tied_logits;
+  int32_t remat;
+  float z_loss;
+} t5_encdec_cfg;
+
+typedef struct {
+  const void* embedding;              /* [vocab, d_model], shared by encoder and decoder */
+  const void* enc_rel_table;          /* [num_buckets, n_heads] */
+  const t5_block_weights* enc_layers; /* HOST array [n_enc_layers]; rel_table fields ignored */
+  const void* enc_final_scale;        /* [d_model] */
+  const void* dec_rel_table;
+  const t5_block_weights* dec_layers; /* HOST array [n_dec_layers] */
+  const t5_cross_weights* dec_cross;  /* HOST array [n_dec_layers] */
+  const void* dec_final_scale;
+  const void* logits_w;               /* [d_model, vocab]; ignored when tied_logits */
+} t5_encdec_weights;
+
+typedef struct {
+  float* embedding;
+  float* enc_rel_table;
+  const t5_block_grads* enc_layers;
+  float* enc_final_scale;
+  float* dec_rel_table;
+  const t5_block_grads* dec_layers;
+  const t5_cross_grads* dec_cross;
+  float* dec_final_scale;
+  float* logits_w;
+} t5_encdec_grads;
+
+size_t t5_encdec_workspace_bytes(const t5_encdec_cfg* cfg);
+
+/* Loss and gradients of the encoder-decoder model; arguments as t5_stack_loss_and_grad, with
+ * enc_tokens [batch, enc_block.seq] and dec_tokens, targets [batch, dec_block.seq].
+ * Errors: as t5_stack_loss_and_grad; mismatched encoder / decoder configs -> T5_ERR_SHAPE. */
+int t5_encdec_loss_and_grad(const t5_encdec_cfg* cfg, const int32_t* enc_tokens, const int32_t* dec_tokens,
+                            const int32_t* targets, const t5_encdec_weights* w, float* loss,
+                            const t5_encdec_grads* grads, int accumulate, void* workspace,
+                            size_t workspace_bytes, void* stream);
+
 /* Adafactor (the optimizer of the T5 models of paper Sec. 4) with factored second moments and
  * update clipping, no momentum, no weight decay, for one [rows, cols] float32 tensor:
  *   beta2 = 1 - step^-decay_pow;  Q = G*G + eps1

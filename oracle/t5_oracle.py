@@ -410,6 +410,71 @@ def stack_loss_grad(sc, w: dict, saved: dict) -> dict:
     return g
 
 
+def encdec_loss(ec, enc_tokens: np.ndarray, dec_tokens: np.ndarray, targets: np.ndarray, w: dict):
+    """Training loss of the encoder-decoder model (paper Sec. 4, T5.1.1):
+        enc_out = RMSNorm(encoder blocks(E[enc_tokens]); enc_final_scale)    bidirectional, own shared table
+        x_{l+1} = decoder_block_l(x_l, enc_out),  x_0 = E[dec_tokens]        causal, own shared table
+        nf = RMSNorm(x_L; dec_final_scale);  logits, loss as in stack_loss
+    Returns (loss, saved)."""
+    e, d = ec.enc_block, ec.dec_block
+    x = w["embedding"][enc_tokens]
+    enc_saved = []
+    for lw in w["enc_layers"]:
+        x, sv = block_fwd(e, x, dict(lw, rel_table=w["enc_rel_table"]))
+        enc_saved.append(sv)
+    enc_out, enc_rf = rmsnorm_fwd(x, w["enc_final_scale"], e.rms_eps)
+    xe_last = x
+    x = w["embedding"][dec_tokens]
+    dec_saved = []
+    for lw in w["dec_layers"]:
+        x, sv = decoder_block_fwd(d, x, enc_out, dict(lw, rel_table=w["dec_rel_table"]))
+        dec_saved.append(sv)
+    nf, rf = rmsnorm_fwd(x, w["dec_final_scale"], d.rms_eps)
+    if ec.tied_logits:
+        logits = (nf * d.d_model ** -0.5) @ w["embedding"].T
+    else:
+        logits = nf @ w["logits_w"]
+    loss, lse, n = xent_zloss(logits, targets, ec.z_loss)
+    return loss, dict(enc_tokens=enc_tokens, dec_tokens=dec_tokens, targets=targets, enc_layers=enc_saved,
+                      dec_layers=dec_saved, xe_last=xe_last, enc_rf=enc_rf, x_last=x, nf=nf, rf=rf, logits=logits,
+                      lse=lse, n=n)
+
+
+def encdec_loss_grad(ec, w: dict, saved: dict) -> dict:
+    """Gradient of encdec_loss w.r.t. every weight (same nesting as the weights)."""
+    e, d = ec.enc_block, ec.dec_block
+    flat = lambda t: t.reshape(-1, t.shape[-1])
+    dlogits = xent_zloss_grad(saved["logits"], saved["targets"], saved["lse"], ec.z_loss, saved["n"])
+    g = {"embedding": np.zeros_like(w["embedding"]), "enc_layers": [None] * ec.n_enc_layers,
+         "dec_layers": [None] * ec.n_dec_layers}
+    if ec.tied_logits:
+        s = d.d_model ** -0.5
+        g["embedding"] += s * (flat(dlogits).T @ flat(saved["nf"]))
+        dnf = s * (dlogits @ w["embedding"])
+    else:
+        g["logits_w"] = flat(saved["nf"]).T @ flat(dlogits)
+        dnf = dlogits @ w["logits_w"].T
+    dx, g["dec_final_scale"] = rmsnorm_bwd(saved["x_last"], w["dec_final_scale"], saved["rf"], dnf)
+    g["dec_rel_table"] = np.zeros_like(w["dec_rel_table"])
+    denc_out = 0.0
+    for l in range(ec.n_dec_layers - 1, -1, -1):
+        wl = dict(w["dec_layers"][l], rel_table=w["dec_rel_table"])
+        dx, denc_l, gl = decoder_block_bwd(d, dx, wl, saved["dec_layers"][l])
+        denc_out = denc_out + denc_l
+        g["dec_rel_table"] += gl.pop("rel_table")
+        g["dec_layers"][l] = gl
+    np.add.at(g["embedding"], saved["dec_tokens"].reshape(-1), flat(dx))
+    dx, g["enc_final_scale"] = rmsnorm_bwd(saved["xe_last"], w["enc_final_scale"], saved["enc_rf"], denc_out)
+    g["enc_rel_table"] = np.zeros_like(w["enc_rel_table"])
+    for l in range(ec.n_enc_layers - 1, -1, -1):
+        wl = dict(w["enc_layers"][l], rel_table=w["enc_rel_table"])
+        dx, gl = block_bwd(e, dx, wl, saved["enc_layers"][l])
+        g["enc_rel_table"] += gl.pop("rel_table")
+        g["enc_layers"][l] = gl
+    np.add.at(g["embedding"], saved["enc_tokens"].reshape(-1), flat(dx))
+    return g
+
+
 # --------------------------------------------------------------------------------------
 # Adafactor
 # --------------------------------------------------------------------------------------

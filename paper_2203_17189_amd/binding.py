@@ -58,6 +58,23 @@ class _StackGrads(C.Structure):
                 ("final_scale", C.c_void_p), ("logits_w", C.c_void_p)]
 
 
+class _EncDecCfg(C.Structure):
+    _fields_ = [("enc_block", _Cfg), ("dec_block", _Cfg), ("n_enc_layers", C.c_int32), ("n_dec_layers", C.c_int32),
+                ("vocab", C.c_int32), ("tied_logits", C.c_int32), ("remat", C.c_int32), ("z_loss", C.c_float)]
+
+
+class _EncDecWeights(C.Structure):
+    _fields_ = [("embedding", C.c_void_p), ("enc_rel_table", C.c_void_p), ("enc_layers", C.POINTER(_Weights)),
+                ("enc_final_scale", C.c_void_p), ("dec_rel_table", C.c_void_p), ("dec_layers", C.POINTER(_Weights)),
+                ("dec_cross", C.POINTER(_CrossWeights)), ("dec_final_scale", C.c_void_p), ("logits_w", C.c_void_p)]
+
+
+class _EncDecGrads(C.Structure):
+    _fields_ = [("embedding", C.c_void_p), ("enc_rel_table", C.c_void_p), ("enc_layers", C.POINTER(_Grads)),
+                ("enc_final_scale", C.c_void_p), ("dec_rel_table", C.c_void_p), ("dec_layers", C.POINTER(_Grads)),
+                ("dec_cross", C.POINTER(_CrossGrads)), ("dec_final_scale", C.c_void_p), ("logits_w", C.c_void_p)]
+
+
 class _AfTensor(C.Structure):
     _fields_ = [("param", C.c_void_p), ("grad", C.c_void_p), ("v_row", C.c_void_p), ("v_col", C.c_void_p),
                 ("v_full", C.c_void_p), ("rows", C.c_int64), ("cols", C.c_int64), ("factored", C.c_int32),
@@ -113,6 +130,11 @@ def lib() -> C.CDLL:
     L.t5_stack_loss_and_grad.restype = i32
     L.t5_stack_loss_and_grad.argtypes = [C.POINTER(_StackCfg), vp, vp, C.POINTER(_StackWeights), vp,
                                          C.POINTER(_StackGrads), i32, vp, sz, vp]
+    L.t5_encdec_workspace_bytes.restype = sz
+    L.t5_encdec_workspace_bytes.argtypes = [C.POINTER(_EncDecCfg)]
+    L.t5_encdec_loss_and_grad.restype = i32
+    L.t5_encdec_loss_and_grad.argtypes = [C.POINTER(_EncDecCfg), vp, vp, vp, C.POINTER(_EncDecWeights), vp,
+                                          C.POINTER(_EncDecGrads), i32, vp, sz, vp]
     L.adafactor_workspace_bytes.restype = sz
     L.adafactor_workspace_bytes.argtypes = [i64, i64, i32]
     L.adafactor_step.restype = i32
@@ -406,6 +428,98 @@ def t5_stack_loss_and_grad(sc, tokens, targets, weights, grads=None, want_grads=
                                       int(bool(accumulate)), _ptr(workspace), workspace.numel(), _stream())
     if rc:
         raise T5Error(rc, "t5_stack_loss_and_grad")
+    return loss, grads
+
+
+def _encdec_cfg_struct(ec) -> _EncDecCfg:
+    return _EncDecCfg(_cfg_struct(ec.enc_block), _cfg_struct(ec.dec_block), int(ec.n_enc_layers),
+                      int(ec.n_dec_layers), int(ec.vocab), int(bool(ec.tied_logits)), int(bool(ec.remat)),
+                      float(ec.z_loss))
+
+
+def t5_encdec_workspace_bytes(ec) -> int:
+    return int(lib().t5_encdec_workspace_bytes(C.byref(_encdec_cfg_struct(ec))))
+
+
+_ENCDEC_FLAT = ("embedding", "enc_rel_table", "enc_final_scale", "dec_rel_table", "dec_final_scale")
+
+
+def alloc_encdec_grads(ec, weights) -> dict:
+    z = lambda t: torch.zeros(t.shape, dtype=torch.float32, device=t.device)
+    g = {k: z(weights[k]) for k in _ENCDEC_FLAT}
+    if not ec.tied_logits:
+        g["logits_w"] = z(weights["logits_w"])
+    g["enc_layers"] = [{n: z(lw[n]) for n in LAYER_WEIGHT_NAMES} for lw in weights["enc_layers"]]
+    g["dec_layers"] = [{n: z(lw[n]) for n in LAYER_WEIGHT_NAMES + CROSS_WEIGHT_NAMES} for lw in weights["dec_layers"]]
+    return g
+
+
+def t5_encdec_loss_and_grad(ec, enc_tokens, dec_tokens, targets, weights, grads=None, want_grads=True,
+                            accumulate=False, workspace=None, loss=None):
+    """Loss (and gradients) of the encoder-decoder model.  weights: {"embedding", "enc_rel_table",
+    "enc_layers": [block dicts without rel_table], "enc_final_scale", "dec_rel_table", "dec_layers": [block +
+    cross-attention dicts without rel_table], "dec_final_scale", "logits_w" (untied)}.
+    Returns (loss tensor of one float32, grads or None)."""
+    e, d = ec.enc_block, ec.dec_block
+    cs = _encdec_cfg_struct(ec)
+    dt = _torch_dtype(d)
+    _check_tensor(enc_tokens, torch.int32, e.batch * e.seq, "enc_tokens")
+    _check_tensor(dec_tokens, torch.int32, d.batch * d.seq, "dec_tokens")
+    _check_tensor(targets, torch.int32, d.batch * d.seq, "targets")
+    _check_tensor(weights["embedding"], dt, ec.vocab * d.d_model, "embedding")
+    for nme, cfgb in (("enc_rel_table", e), ("dec_rel_table", d)):
+        _check_tensor(weights[nme], dt, cfgb.num_buckets * cfgb.n_heads, nme)
+    for nme in ("enc_final_scale", "dec_final_scale"):
+        _check_tensor(weights[nme], dt, d.d_model, nme)
+    if not ec.tied_logits:
+        _check_tensor(weights["logits_w"], dt, ec.vocab * d.d_model, "logits_w")
+    if len(weights["enc_layers"]) != ec.n_enc_layers or len(weights["dec_layers"]) != ec.n_dec_layers:
+        raise ValueError("layer lists must hold n_enc_layers / n_dec_layers dicts")
+    elw = (_Weights * ec.n_enc_layers)()
+    for l, lw in enumerate(weights["enc_layers"]):
+        elw[l] = _weights_struct(e, dict(lw, rel_table=weights["enc_rel_table"]))
+    dlw = (_Weights * ec.n_dec_layers)()
+    dxw = (_CrossWeights * ec.n_dec_layers)()
+    for l, lw in enumerate(weights["dec_layers"]):
+        dlw[l] = _weights_struct(d, dict(lw, rel_table=weights["dec_rel_table"]))
+        dxw[l] = _cross_weights_struct(d, lw)
+    p = lambda t: t.data_ptr()
+    ws = _EncDecWeights(p(weights["embedding"]), p(weights["enc_rel_table"]), elw, p(weights["enc_final_scale"]),
+                        p(weights["dec_rel_table"]), dlw, dxw, p(weights["dec_final_scale"]),
+                        None if ec.tied_logits else p(weights["logits_w"]))
+    gs_ref = None
+    if want_grads:
+        if grads is None:
+            grads = alloc_encdec_grads(ec, weights)
+        for nme in _ENCDEC_FLAT + (() if ec.tied_logits else ("logits_w",)):
+            _check_tensor(grads[nme], torch.float32, weights[nme].numel(), "grad " + nme)
+        elg = (_Grads * ec.n_enc_layers)()
+        for l, gd in enumerate(grads["enc_layers"]):
+            for nme in LAYER_WEIGHT_NAMES:
+                _check_tensor(gd[nme], torch.float32, weights["enc_layers"][l][nme].numel(), f"grad enc {l} {nme}")
+            elg[l] = _Grads(*[(p(gd[nme]) if nme != "rel_table" else p(grads["enc_rel_table"])) for nme in WEIGHT_NAMES])
+        dlg = (_Grads * ec.n_dec_layers)()
+        dxg = (_CrossGrads * ec.n_dec_layers)()
+        for l, gd in enumerate(grads["dec_layers"]):
+            for nme in LAYER_WEIGHT_NAMES + CROSS_WEIGHT_NAMES:
+                _check_tensor(gd[nme], torch.float32, weights["dec_layers"][l][nme].numel(), f"grad dec {l} {nme}")
+            dlg[l] = _Grads(*[(p(gd[nme]) if nme != "rel_table" else p(grads["dec_rel_table"])) for nme in WEIGHT_NAMES])
+            dxg[l] = _CrossGrads(*[p(gd[nme]) for nme in CROSS_WEIGHT_NAMES])
+        gs = _EncDecGrads(p(grads["embedding"]), p(grads["enc_rel_table"]), elg, p(grads["enc_final_scale"]),
+                          p(grads["dec_rel_table"]), dlg, dxg, p(grads["dec_final_scale"]),
+                          None if ec.tied_logits else p(grads["logits_w"]))
+        gs_ref = C.byref(gs)
+    else:
+        grads = None
+    if loss is None:
+        loss = torch.zeros(1, dtype=torch.float32, device=enc_tokens.device)
+    if workspace is None:
+        workspace = _byte_buffer(lib().t5_encdec_workspace_bytes(C.byref(cs)), enc_tokens.device)
+    rc = lib().t5_encdec_loss_and_grad(C.byref(cs), _ptr(enc_tokens), _ptr(dec_tokens), _ptr(targets), C.byref(ws),
+                                       _ptr(loss), gs_ref, int(bool(accumulate)), _ptr(workspace), workspace.numel(),
+                                       _stream())
+    if rc:
+        raise T5Error(rc, "t5_encdec_loss_and_grad")
     return loss, grads
 
 

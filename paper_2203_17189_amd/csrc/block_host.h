@@ -426,9 +426,11 @@ int bwd_mlp(const Dims& D, const void* dy, const float* hin, const t5_block_weig
 }
 
 // Given W.dh / W.dh_lp (gradient of h2): W.dh1 / W.dh1_lp (gradient of h), denc, and the weight
-// gradients of the cross-attention sublayer.
+// gradients of the cross-attention sublayer.  denc is written in the storage type, or (denc_f32) as
+// float32, optionally added to what it holds (a stack sums the encoder-output gradients of its layers).
 int bwd_cross_attn(const t5_block_cfg* cfg, const Dims& D, const void* enc, const t5_cross_weights* xw,
-                   const Stash& S, const BwdWs& W, void* denc, const t5_cross_grads* dxw, int acc, hipStream_t st) {
+                   const Stash& S, const BwdWs& W, void* denc, const t5_cross_grads* dxw, int acc, hipStream_t st,
+                   bool denc_f32 = false, bool denc_add = false) {
   const int T = (int)D.T, Te = (int)D.Te, ty = D.ty;
   const size_t es = D.es;
   const AttnDims ad = cross_dims(cfg, D);
@@ -467,7 +469,9 @@ int bwd_cross_attn(const t5_block_cfg* cfg, const Dims& D, const void* enc, cons
     GemmDesc g = gemm1(Te, D.d, D.I, W.dkvx, 2 * D.I, 1, xw->xk, D.I, 1, ty);
     g.nseg = 2;
     g.seg[1] = GemmSeg{at(W.dkvx, (size_t)D.I, es), xw->xv, 2 * D.I, D.I, D.I};
-    T5_STEP("gemm_denc", run_gemm(g, epi(EPI_STORE, denc, D.d, ty), st));
+    GemmEpi e = epi(denc_add ? EPI_RESID : EPI_STORE, denc, D.d, denc_f32 ? IN_F32 : ty);
+    if (denc_add) { e.aux0 = denc; e.aux_type = denc_f32 ? IN_F32 : ty; }  // in place: each element is read, then written, by one lane
+    T5_STEP("gemm_denc", run_gemm(g, e, st));
   }
   {  // dnx = dq Xq^T
     GemmDesc g = gemm1(T, D.d, D.I, W.dqx, D.I, 1, xw->xq, D.I, 1, ty);

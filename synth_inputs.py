@@ -232,6 +232,79 @@ def make_tokens(sc: StackConfig, seed_offset: int = 0, ignore_fraction: float = 
     return tokens, targets
 
 
+@dataclass(frozen=True)
+class EncDecConfig:
+    """Encoder-decoder model (paper Sec. 4, T5.1.1): a bidirectional encoder stack and a causal decoder
+    stack whose layers cross-attend to the encoder output; one token embedding for both."""
+    name: str
+    enc_block: BlockConfig     # causal False; seq = encoder length
+    dec_block: BlockConfig     # causal True; seq = decoder length; enc_seq = encoder length
+    n_enc_layers: int
+    n_dec_layers: int
+    vocab: int
+    tied_logits: bool = False
+    z_loss: float = 1e-4
+    remat: bool = False
+
+    def with_batch(self, batch: int) -> "EncDecConfig":
+        return replace(self, enc_block=self.enc_block.with_batch(batch), dec_block=self.dec_block.with_batch(batch))
+
+    def model_flops(self) -> float:
+        e, d = self.enc_block, self.dec_block
+        return 3.0 * (e.tokens * self.n_enc_layers * e.fwd_flops_per_token()
+                      + d.tokens * (self.n_dec_layers * d.fwd_flops_per_token() + 2.0 * d.d_model * self.vocab))
+
+
+def _encdec(name, index, batch, enc_seq, dec_seq, d, h, dk, f, le, ld, vocab, **kw):
+    blk = dict(kw.pop("block", {}))
+    e = BlockConfig(name + "_enc", index, batch, enc_seq, d, h, dk, f, causal=False, **blk)
+    dcd = BlockConfig(name + "_dec", index + 1, batch, dec_seq, d, h, dk, f, causal=True, enc_seq=enc_seq, **blk)
+    return EncDecConfig(name, e, dcd, le, ld, vocab, **kw)
+
+
+ENCDEC_CONFIGS = {
+    # T5.1.1-Base: 12 + 12 layers, 512 encoder positions, 114 decoder positions in pre-training; the decoder
+    # length is rounded to 128 here so that its attention runs on the matrix-unit kernels
+    "e1_t5_base": _encdec("e1_t5_base", 8, 32, 512, 128, 768, 12, 64, 2048, 12, 12, 32128),
+}
+
+
+def make_encdec_weights(ec: EncDecConfig) -> dict:
+    e, d = ec.enc_block, ec.dec_block
+    enc = make_stack_weights(StackConfig("enc", e, ec.n_enc_layers, ec.vocab, tied_logits=True))
+    w = {"embedding": enc["embedding"], "enc_rel_table": enc["rel_table"], "enc_layers": enc["layers"],
+         "enc_final_scale": np.ones(e.d_model), "dec_final_scale": np.ones(d.d_model), "dec_layers": []}
+    for l in range(ec.n_dec_layers):
+        lw = make_weights(replace(d, index=d.index + 37 * (l + 1)))
+        table = lw.pop("rel_table")
+        if l == 0:
+            w["dec_rel_table"] = table
+        w["dec_layers"].append(lw)
+    if not ec.tied_logits:
+        out = np.random.default_rng(BASE_SEED + 1000 * d.index + 501).standard_normal((d.d_model, ec.vocab))
+        w["logits_w"] = round_to_dtype(out * d.d_model ** -0.5, d.dtype)
+    return w
+
+
+def make_encdec_random_scales(ec: EncDecConfig, w: dict) -> None:
+    """In place: non-trivial RMSNorm scales everywhere."""
+    e, d = ec.enc_block, ec.dec_block
+    for l, lw in enumerate(w["enc_layers"]):
+        lw.update(make_random_scales(replace(e, index=e.index + 37 * (l + 1))))
+    for l, lw in enumerate(w["dec_layers"]):
+        lw.update(make_random_scales(replace(d, index=d.index + 37 * (l + 1))))
+    rng = np.random.default_rng(BASE_SEED + 1000 * e.index + 504)
+    w["enc_final_scale"] = round_to_dtype(1.0 + 0.1 * rng.standard_normal(e.d_model), e.dtype)
+    w["dec_final_scale"] = round_to_dtype(1.0 + 0.1 * rng.standard_normal(d.d_model), d.dtype)
+
+
+def make_encdec_tokens(ec: EncDecConfig, seed_offset: int = 0, ignore_fraction: float = 0.1) -> tuple:
+    """(enc_tokens [B, S_enc], dec_tokens [B, S_dec], targets [B, S_dec]) int32, Zipf-like as make_tokens."""
+    enc_tokens, _ = make_tokens(StackConfig("e", ec.enc_block, 1, ec.vocab), seed_offset, 0.0)
+    dec_tokens, targets = make_tokens(StackConfig("d", ec.dec_block, 1, ec.vocab), seed_offset, ignore_fraction)
+    return enc_tokens, dec_tokens, targets
+
+
 def make_adafactor_case(rows: int, cols: int, seed: int, grad_std: float = 1e-2) -> tuple:
     """(param, grad) float64 arrays holding float32-representable values for a standalone optimizer test."""
     rng = np.random.default_rng(BASE_SEED + 7919 * seed + rows * 31 + cols)

@@ -145,6 +145,34 @@ def test_stack_validation():
     assert call(C.byref(tied), dummy, C.byref(mk(ok_lw, out=None)), dummy, None, 1024) == 4   # tied: logits_w not needed
 
 
+def test_encdec_validation():
+    lib = P.lib()
+    from dataclasses import replace
+    ec = SI.ENCDEC_CONFIGS["e1_t5_base"]
+    assert P.t5_encdec_workspace_bytes(ec) > 0
+    assert P.t5_encdec_workspace_bytes(replace(ec, remat=True)) < P.t5_encdec_workspace_bytes(ec)
+    assert P.t5_encdec_workspace_bytes(replace(ec, enc_block=replace(ec.enc_block, causal=True))) == 0
+    assert P.t5_encdec_workspace_bytes(replace(ec, dec_block=replace(ec.dec_block, causal=False))) == 0
+    assert P.t5_encdec_workspace_bytes(replace(ec, enc_block=replace(ec.enc_block, d_model=512))) == 0
+    assert P.t5_encdec_workspace_bytes(replace(ec, n_dec_layers=0)) == 0
+    small = replace(ec, n_enc_layers=1, n_dec_layers=1)
+    cs = B._encdec_cfg_struct(small)
+    dummy = C.c_void_p(4096)
+    lw = (B._Weights * 1)(B._Weights(*([4096] * 10)))
+    xw = (B._CrossWeights * 1)(B._CrossWeights(*([4096] * 5)))
+    wts = B._EncDecWeights(4096, 4096, lw, 4096, 4096, lw, xw, 4096, 4096)
+    call = lambda w_, nbytes: lib.t5_encdec_loss_and_grad(C.byref(cs), dummy, dummy, dummy, w_, dummy, None, 0, dummy,
+                                                          nbytes, None)
+    assert call(C.byref(wts), 1024) == 4
+    no_cross = B._EncDecWeights(4096, 4096, lw, 4096, 4096, lw, None, 4096, 4096)
+    assert call(C.byref(no_cross), 1 << 40) == 1
+    bad_x = (B._CrossWeights * 1)(B._CrossWeights(*([4096] * 4 + [None])))
+    assert call(C.byref(B._EncDecWeights(4096, 4096, lw, 4096, 4096, lw, bad_x, 4096, 4096)), 1 << 40) == 1
+    assert call(C.byref(B._EncDecWeights(4096, None, lw, 4096, 4096, lw, xw, 4096, 4096)), 1 << 40) == 1
+    assert lib.t5_encdec_loss_and_grad(C.byref(cs), None, dummy, dummy, C.byref(wts), dummy, None, 0, dummy, 1 << 40,
+                                       None) == 1
+
+
 def test_adafactor_validation():
     lib = P.lib()
     dummy = C.c_void_p(4096)

@@ -147,3 +147,81 @@ def test_stack_named_config_reduced_batch():
     sc = replace(SI.STACK_CONFIGS["s1_lm_base"].with_batch(1), name="s1_lm_base_b1")
     sc = replace(sc, block=replace(sc.block, attn_scale=64 ** -0.5))
     _compare(sc, 5e-4, *stack_bf16_tol(sc.n_layers))
+
+
+# ---------------------------------------------------------------- encoder-decoder model
+def _ec_upload(ec, w, enc_tokens, dec_tokens, targets):
+    dt = ec.dec_block.dtype
+    dw = {k: to_dev(v, dt) for k, v in w.items() if not k.endswith("_layers")}
+    for side in ("enc_layers", "dec_layers"):
+        dw[side] = [{k: to_dev(v, dt) for k, v in lw.items()} for lw in w[side]]
+    dev = lambda a: torch.from_numpy(a).cuda()
+    return dw, dev(enc_tokens), dev(dec_tokens), dev(targets)
+
+
+def _ec_compare(ec, tol_loss, tol, tol_mean=None):
+    import paper_2203_17189_amd as P
+    w = SI.make_encdec_weights(ec)
+    SI.make_encdec_random_scales(ec, w)
+    enc_tokens, dec_tokens, targets = SI.make_encdec_tokens(ec, ignore_fraction=0.15)
+    loss, saved = O.encdec_loss(ec, enc_tokens, dec_tokens, targets, w)
+    g = O.encdec_loss_grad(ec, w, saved)
+    dw, te, td, tg = _ec_upload(ec, w, enc_tokens, dec_tokens, targets)
+    gl, gg = P.t5_encdec_loss_and_grad(ec, te, td, tg, dw)
+    torch.cuda.synchronize()
+    gl = float(gl.item())
+    errs = {}
+    for name in [k for k in g if not k.endswith("_layers")]:
+        rms = None
+        if name == "embedding" and not ec.tied_logits:
+            rows = np.unique(np.concatenate([enc_tokens.ravel(), dec_tokens.ravel()]))
+            rms = float(np.sqrt(np.mean(g[name][rows] ** 2)))
+        if name == "logits_w":
+            cols = np.unique(targets[targets >= 0])
+            rms = float(np.sqrt(np.mean(g[name][:, cols] ** 2)))
+        errs[name] = rel_err(to_np(gg[name]), g[name], rms)
+    for side in ("enc_layers", "dec_layers"):
+        for l, gl_ in enumerate(g[side]):
+            for name, val in gl_.items():
+                errs[f"{side[:3]}{l}.{name}"] = rel_err(to_np(gg[side][l][name]), val)
+    worst = sorted(errs.items(), key=lambda kv: -kv[1][0])[:6]
+    print(ec.name, "loss", gl, loss, "worst", [(k, tuple(round(x, 5) for x in v)) for k, v in worst])
+    assert abs(gl - loss) <= tol_loss * max(1.0, abs(loss)), (gl, loss)
+    for k, e in errs.items():
+        assert e[0] <= tol, (k, e)
+        if tol_mean is not None:
+            assert e[1] <= tol_mean, (k, e)
+
+
+EC_F32 = [
+    SI._encdec("ec_f32", 70, 2, 20, 12, 32, 2, 8, 48, 2, 2, 37, z_loss=1e-2, block=dict(dtype="f32")),
+    replace(SI._encdec("ec_f32_tied_remat", 72, 1, 9, 17, 32, 2, 8, 48, 1, 3, 64, z_loss=1e-3, block=dict(dtype="f32")),
+            tied_logits=True, remat=True),
+]
+
+
+@pytest.mark.parametrize("ec", EC_F32, ids=[c.name for c in EC_F32])
+def test_encdec_f32(ec):
+    _ec_compare(ec, 1e-5, TOL_F32[0])
+
+
+EC_BF16 = [
+    SI._encdec("ec_bf16", 74, 2, 256, 128, 128, 2, 64, 256, 2, 2, 512, block=dict(attn_scale=64 ** -0.5)),
+    replace(SI._encdec("ec_bf16_remat", 76, 1, 128, 128, 128, 2, 64, 256, 1, 2, 512, block=dict(attn_scale=64 ** -0.5)),
+            remat=True),
+    SI._encdec("ec_bf16_ragged", 78, 1, 70, 33, 72, 3, 24, 136, 2, 1, 301, block=dict(attn_scale=24 ** -0.5)),
+]
+
+
+@pytest.mark.parametrize("ec", EC_BF16, ids=[c.name for c in EC_BF16])
+def test_encdec_bf16_small(ec):
+    # a gradient in the encoder has crossed every decoder layer and the encoder layers above it
+    _ec_compare(ec, 5e-4, *stack_bf16_tol(ec.n_enc_layers + ec.n_dec_layers))
+
+
+def test_encdec_named_config_reduced_batch():
+    """T5.1.1-Base encoder-decoder at its real depth, widths, lengths and vocabulary, one sequence pair."""
+    ec = SI.ENCDEC_CONFIGS["e1_t5_base"].with_batch(1)
+    ec = replace(ec, enc_block=replace(ec.enc_block, attn_scale=64 ** -0.5),
+                 dec_block=replace(ec.dec_block, attn_scale=64 ** -0.5))
+    _ec_compare(ec, 5e-4, *stack_bf16_tol(ec.n_enc_layers + ec.n_dec_layers))

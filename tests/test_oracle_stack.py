@@ -214,3 +214,110 @@ def test_stack_gradients_against_central_differences(sc):
     for l in (0, sc.n_layers - 1):
         for name in ("wq", "wo", "wi1", "ln2_scale"):
             probe(lambda ww, l=l, name=name: ww["layers"][l][name], g["layers"][l][name], 3)
+
+
+# ---------------------------------------------------------------- encoder-decoder model
+EC = SI._encdec("ec_tiny", 18, 2, 9, 7, 16, 2, 4, 24, 2, 2, 31, z_loss=1e-2, block=dict(dtype="f32"))
+EC_TIED = replace(SI._encdec("ec_tiny_tied", 20, 2, 5, 8, 16, 2, 4, 24, 1, 2, 31, z_loss=0.0, block=dict(dtype="f32")),
+                  tied_logits=True)
+
+
+def _ec_case(ec):
+    w = SI.make_encdec_weights(ec)
+    SI.make_encdec_random_scales(ec, w)
+    return (w,) + SI.make_encdec_tokens(ec, ignore_fraction=0.2)
+
+
+def _torch_encdec_loss(ec, enc_tokens, dec_tokens, targets, tw):
+    from test_oracle_decoder import _torch_decoder_block
+    e, d = ec.enc_block, ec.dec_block
+    x = tw["embedding"][torch.from_numpy(enc_tokens).long()]
+    for lw in tw["enc_layers"]:
+        x = _torch_block(e, x, dict(lw, rel_table=tw["enc_rel_table"]))
+    enc_out = F.rms_norm(x, (e.d_model,), tw["enc_final_scale"], eps=e.rms_eps)
+    x = tw["embedding"][torch.from_numpy(dec_tokens).long()]
+    for lw in tw["dec_layers"]:
+        x = _torch_decoder_block(d, x, enc_out, dict(lw, rel_table=tw["dec_rel_table"]))
+    nf = F.rms_norm(x, (d.d_model,), tw["dec_final_scale"], eps=d.rms_eps)
+    logits = (nf * d.d_model ** -0.5) @ tw["embedding"].T if ec.tied_logits else nf @ tw["logits_w"]
+    tt = torch.from_numpy(targets).long()
+    valid = tt >= 0
+    lse = torch.logsumexp(logits, -1)
+    ce = F.cross_entropy(logits.reshape(-1, ec.vocab), tt.reshape(-1), ignore_index=-1, reduction="sum")
+    return (ce + ec.z_loss * (lse[valid] ** 2).sum()) / valid.sum()
+
+
+@pytest.mark.parametrize("ec", [EC, EC_TIED])
+def test_encdec_loss_and_gradients_against_torch_autograd(ec):
+    w, enc_tokens, dec_tokens, targets = _ec_case(ec)
+    loss, saved = O.encdec_loss(ec, enc_tokens, dec_tokens, targets, w)
+    g = O.encdec_loss_grad(ec, w, saved)
+    tw = _to_torch(w)
+    tl = _torch_encdec_loss(ec, enc_tokens, dec_tokens, targets, tw)
+    tl.backward()
+    assert abs(loss - float(tl.detach())) < 1e-12 * max(1.0, abs(loss))
+    scale = lambda a: np.sqrt(np.mean(a * a)) + 1e-300
+    flat_names = [k for k in w if not k.endswith("_layers")]
+    assert set(g) == set(w)
+    for name in flat_names:
+        ref = tw[name].grad.numpy()
+        assert np.abs(g[name] - ref).max() / scale(ref) < 1e-9, name
+    for side in ("enc_layers", "dec_layers"):
+        for l, lw in enumerate(w[side]):
+            assert set(g[side][l]) == set(lw)
+            for name, val in g[side][l].items():
+                ref = tw[side][l][name].grad.numpy()
+                assert np.abs(val - ref).max() / scale(ref) < 1e-9, (side, l, name)
+
+
+def test_encdec_structure():
+    """The decoder sees the encoder only through cross-attention: with every cross-attention output
+    projection at zero the loss is that of the decoder stack alone and no gradient reaches the encoder;
+    the encoder tokens do not enter the loss as targets, only through enc_out."""
+    ec = EC
+    w, enc_tokens, dec_tokens, targets = _ec_case(ec)
+    for lw in w["dec_layers"]:
+        lw["xo"] = np.zeros_like(lw["xo"])
+    loss, saved = O.encdec_loss(ec, enc_tokens, dec_tokens, targets, w)
+    g = O.encdec_loss_grad(ec, w, saved)
+    assert np.all(g["enc_rel_table"] == 0) and np.all(g["enc_final_scale"] == 0)
+    assert all(np.all(v == 0) for gl in g["enc_layers"] for v in gl.values())
+    sc = SI.StackConfig("dec_only", replace(ec.dec_block, enc_seq=0), ec.n_dec_layers, ec.vocab, z_loss=ec.z_loss)
+    strip = lambda lw: {k: v for k, v in lw.items() if k not in ("lnx_scale", "xq", "xk", "xv", "xo")}
+    ws = {"embedding": w["embedding"], "rel_table": w["dec_rel_table"], "final_scale": w["dec_final_scale"],
+          "logits_w": w["logits_w"], "layers": [strip(lw) for lw in w["dec_layers"]]}
+    loss_dec, _ = O.stack_loss(sc, dec_tokens, targets, ws)
+    assert abs(loss - loss_dec) < 1e-12
+    # other encoder tokens, same loss
+    loss2, _ = O.encdec_loss(ec, (enc_tokens + 3) % ec.vocab, dec_tokens, targets, w)
+    assert abs(loss2 - loss) < 1e-12
+
+
+def test_encdec_gradients_against_central_differences():
+    ec = EC
+    w, enc_tokens, dec_tokens, targets = _ec_case(ec)
+    _, saved = O.encdec_loss(ec, enc_tokens, dec_tokens, targets, w)
+    g = O.encdec_loss_grad(ec, w, saved)
+    rng = np.random.default_rng(10)
+    eps = 1e-6
+
+    def probe(arr, grad, n_probe=4):
+        for fi in rng.choice(arr.size, size=min(n_probe, arr.size), replace=False):
+            idx = np.unravel_index(fi, arr.shape)
+            old = arr[idx]
+            arr[idx] = old + eps; lp = O.encdec_loss(ec, enc_tokens, dec_tokens, targets, w)[0]
+            arr[idx] = old - eps; lm = O.encdec_loss(ec, enc_tokens, dec_tokens, targets, w)[0]
+            arr[idx] = old
+            fd = (lp - lm) / (2 * eps)
+            assert abs(fd - grad[idx]) <= 5e-8 * max(1.0, abs(grad[idx]) * 1e2), (idx, fd, grad[idx])
+
+    for name in ("enc_rel_table", "dec_rel_table", "enc_final_scale", "dec_final_scale", "logits_w"):
+        probe(w[name], g[name], 6)
+    both = np.intersect1d(enc_tokens, dec_tokens)
+    for tok in list(both[:2]) + [int(enc_tokens[0, 0]), int(dec_tokens[0, 0])]:
+        probe(w["embedding"][tok], g["embedding"][tok], 3)
+    probe(w["enc_layers"][0]["wk"], g["enc_layers"][0]["wk"])
+    probe(w["enc_layers"][1]["wo_ff"], g["enc_layers"][1]["wo_ff"])
+    for name in ("xq", "xk", "xv", "xo", "lnx_scale", "wq", "wi0"):
+        probe(w["dec_layers"][0][name], g["dec_layers"][0][name], 3)
+        probe(w["dec_layers"][1][name], g["dec_layers"][1][name], 3)
