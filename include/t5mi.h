@@ -277,11 +277,14 @@ int t5_encdec_loss_and_grad(const t5_encdec_cfg* cfg, const int32_t* enc_tokens,
  *              vhat_ij = v_row_i v_col_j / mean_i v_row_i
  *   otherwise: v_full <- beta2 v_full + (1-beta2) Q;  vhat = v_full
  *   U = G / sqrt(vhat);  U <- U / max(1, RMS(U)/clip)
- *   param <- param - lr * (scale_by_param ? max(eps2, RMS(param)) : 1) * U
- * param and the state vectors are updated in place.  bf16_copy_out (nullable) receives the new
+ *   D = lr * (scale_by_param ? max(eps2, RMS(param)) : 1) * U
+ *   beta1 > 0 (adafactor_step_multi only):  m <- beta1 m + (1 - beta1) D;  D = m        (momentum)
+ *   param <- param - D - lr * weight_decay * param                                       (decoupled decay)
+ * beta1 = 0 and weight_decay = 0 give the plain update.  param and the state are updated in place.  bf16_copy_out (nullable) receives the new
  * parameters rounded to bf16.  Unused state pointers may be NULL.
- * Errors: NULL -> T5_ERR_NULL; rows/cols < 1, step < 1, clip <= 0 -> T5_ERR_SHAPE;
- * small workspace -> T5_ERR_WORKSPACE. */
+ * Errors: NULL -> T5_ERR_NULL; rows/cols < 1, step < 1, clip <= 0, beta1 outside [0, 1),
+ * weight_decay < 0 -> T5_ERR_SHAPE; small workspace -> T5_ERR_WORKSPACE; beta1 > 0 through
+ * adafactor_step (which has no momentum buffer) -> T5_ERR_UNSUPPORTED. */
 typedef struct {
   float lr;
   float decay_pow; /* 0.8 */
@@ -290,6 +293,8 @@ typedef struct {
   float clip;      /* 1.0 */
   int32_t scale_by_param;
   int32_t step; /* 1-based */
+  float beta1;        /* 0: no momentum; else in (0, 1) and every tensor needs its m buffer */
+  float weight_decay; /* 0: none; >= 0 */
 } adafactor_cfg;
 
 size_t adafactor_workspace_bytes(int64_t rows, int64_t cols, int factored);
@@ -313,6 +318,7 @@ typedef struct {
   int64_t rows, cols;
   int32_t factored;
   void* bf16_copy_out; /* nullable */
+  float* m;            /* [rows, cols] momentum, required when cfg.beta1 > 0, else ignored */
 } adafactor_tensor;
 size_t adafactor_multi_workspace_bytes(const adafactor_tensor* tensors, int n_tensors);
 int adafactor_step_multi(const adafactor_tensor* tensors, int n_tensors, const adafactor_cfg* cfg,

@@ -485,9 +485,9 @@ def adafactor_beta2(step: int, decay_pow: float) -> float:
 
 def adafactor_step(param: np.ndarray, grad: np.ndarray, state: dict, *, step: int, lr: float,
                    factored: bool, decay_pow: float = 0.8, eps1: float = 1e-30, eps2: float = 1e-3,
-                   clip: float = 1.0, scale_by_param: bool = True):
+                   clip: float = 1.0, scale_by_param: bool = True, beta1: float = 0.0, weight_decay: float = 0.0):
     """One Adafactor update of a [R,C] tensor.  state holds 'vr' [R] and 'vc' [C] when factored,
-    else 'v' [R,C].  Returns (new_param, new_state); inputs are not modified.
+    else 'v' [R,C], and 'm' [R,C] when beta1 > 0.  Returns (new_param, new_state); inputs are not modified.
 
       beta2 = 1 - t^-decay_pow
       Q = G*G + eps1
@@ -495,7 +495,9 @@ def adafactor_step(param: np.ndarray, grad: np.ndarray, state: dict, *, step: in
                   vhat_ij = vr_i vc_j / mean_i vr_i
       otherwise:  v <- beta2 v + (1-beta2) Q;  vhat = v
       U = G / sqrt(vhat);  U <- U / max(1, RMS(U)/clip)
-      alpha = lr * max(eps2, RMS(W))  (or lr alone);  W <- W - alpha U
+      alpha = lr * max(eps2, RMS(W))  (or lr alone);  D = alpha U
+      beta1 > 0:  m <- beta1 m + (1 - beta1) D;  D = m                 (momentum on the scaled update)
+      W <- W - D - lr * weight_decay * W                                (decoupled weight decay)
     """
     b2 = adafactor_beta2(step, decay_pow)
     qm = grad * grad + eps1
@@ -515,10 +517,15 @@ def adafactor_step(param: np.ndarray, grad: np.ndarray, state: dict, *, step: in
     alpha = lr
     if scale_by_param:
         alpha = lr * max(eps2, math.sqrt(float(np.mean(param * param))))
-    return param - alpha * upd, new_state
+    delta = alpha * upd
+    if beta1 > 0.0:
+        new_state["m"] = beta1 * state["m"] + (1.0 - beta1) * delta
+        delta = new_state["m"]
+    return param - delta - lr * weight_decay * param, new_state
 
 
-def adafactor_zero_state(rows: int, cols: int, factored: bool) -> dict:
-    if factored:
-        return {"vr": np.zeros(rows), "vc": np.zeros(cols)}
-    return {"v": np.zeros((rows, cols))}
+def adafactor_zero_state(rows: int, cols: int, factored: bool, momentum: bool = False) -> dict:
+    st = {"vr": np.zeros(rows), "vc": np.zeros(cols)} if factored else {"v": np.zeros((rows, cols))}
+    if momentum:
+        st["m"] = np.zeros((rows, cols))
+    return st

@@ -78,12 +78,13 @@ class _EncDecGrads(C.Structure):
 class _AfTensor(C.Structure):
     _fields_ = [("param", C.c_void_p), ("grad", C.c_void_p), ("v_row", C.c_void_p), ("v_col", C.c_void_p),
                 ("v_full", C.c_void_p), ("rows", C.c_int64), ("cols", C.c_int64), ("factored", C.c_int32),
-                ("bf16_copy_out", C.c_void_p)]
+                ("bf16_copy_out", C.c_void_p), ("m", C.c_void_p)]
 
 
 class _AfCfg(C.Structure):
     _fields_ = [("lr", C.c_float), ("decay_pow", C.c_float), ("eps1", C.c_float), ("eps2", C.c_float),
-                ("clip", C.c_float), ("scale_by_param", C.c_int32), ("step", C.c_int32)]
+                ("clip", C.c_float), ("scale_by_param", C.c_int32), ("step", C.c_int32), ("beta1", C.c_float),
+                ("weight_decay", C.c_float)]
 
 
 def lib_path() -> str:
@@ -528,7 +529,8 @@ def adafactor_workspace_bytes(rows: int, cols: int, factored: bool) -> int:
 
 
 def adafactor_step(param, grad, *, step, lr, factored, v_row=None, v_col=None, v_full=None, decay_pow=0.8,
-                   eps1=1e-30, eps2=1e-3, clip=1.0, scale_by_param=True, bf16_copy_out=None, workspace=None):
+                   eps1=1e-30, eps2=1e-3, clip=1.0, scale_by_param=True, bf16_copy_out=None, workspace=None,
+                   weight_decay=0.0):
     """In-place Adafactor update of a float32 tensor viewed as [rows, cols] (1-D tensors: rows = 1)."""
     rows, cols = (param.shape[0], param.numel() // param.shape[0]) if param.dim() >= 2 else (1, param.numel())
     _check_tensor(param, torch.float32, rows * cols, "param")
@@ -542,7 +544,7 @@ def adafactor_step(param, grad, *, step, lr, factored, v_row=None, v_col=None, v
         _check_tensor(bf16_copy_out, torch.bfloat16, rows * cols, "bf16_copy_out")
     if workspace is None:
         workspace = _byte_buffer(adafactor_workspace_bytes(rows, cols, factored), param.device)
-    cfg = _AfCfg(lr, decay_pow, eps1, eps2, clip, int(bool(scale_by_param)), int(step))
+    cfg = _AfCfg(lr, decay_pow, eps1, eps2, clip, int(bool(scale_by_param)), int(step), 0.0, float(weight_decay))
     rc = lib().adafactor_step(_ptr(param), _ptr(grad), _ptr(v_row), _ptr(v_col), _ptr(v_full), rows, cols,
                               int(bool(factored)), C.byref(cfg), _ptr(bf16_copy_out), _ptr(workspace),
                               workspace.numel(), _stream())
@@ -568,10 +570,13 @@ def _af_tensor_array(tensors):
         lp = t.get("bf16_copy_out")
         if lp is not None:
             _check_tensor(lp, torch.bfloat16, rows * cols, "bf16_copy_out")
+        mom = t.get("m")
+        if mom is not None:
+            _check_tensor(mom, torch.float32, rows * cols, "m")
         addr = lambda x: None if x is None else x.data_ptr()
         arr[i] = _AfTensor(addr(p), addr(t["grad"]), addr(t.get("v_row")) if fact else None,
                            addr(t.get("v_col")) if fact else None, None if fact else addr(t.get("v_full")),
-                           rows, cols, int(fact), addr(lp))
+                           rows, cols, int(fact), addr(lp), addr(mom))
     return arr
 
 
@@ -581,13 +586,15 @@ def adafactor_multi_workspace_bytes(tensors) -> int:
 
 
 def adafactor_step_multi(tensors, *, step, lr, decay_pow=0.8, eps1=1e-30, eps2=1e-3, clip=1.0,
-                         scale_by_param=True, workspace=None):
-    """In-place Adafactor update of several float32 tensors in one sequence of launches."""
+                         scale_by_param=True, workspace=None, beta1=0.0, weight_decay=0.0):
+    """In-place Adafactor update of several float32 tensors in one sequence of launches.  beta1 > 0 adds
+    momentum (each tensor dict then holds its float32 buffer "m"); weight_decay is decoupled."""
     arr = _af_tensor_array(tensors)
     if workspace is None:
         workspace = _byte_buffer(max(int(lib().adafactor_multi_workspace_bytes(arr, len(tensors))), 256),
                                  tensors[0]["param"].device)
-    cfg = _AfCfg(lr, decay_pow, eps1, eps2, clip, int(bool(scale_by_param)), int(step))
+    cfg = _AfCfg(lr, decay_pow, eps1, eps2, clip, int(bool(scale_by_param)), int(step), float(beta1),
+                 float(weight_decay))
     rc = lib().adafactor_step_multi(arr, len(tensors), C.byref(cfg), _ptr(workspace), workspace.numel(), _stream())
     if rc:
         raise T5Error(rc, "adafactor_step_multi")

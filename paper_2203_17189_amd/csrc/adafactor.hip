@@ -63,6 +63,7 @@ struct AfItem {
   float* v_col;
   float* v_full;
   bf16* lp;
+  float* m;  // momentum (nullable)
   int64_t R, C;
   AfWs ws;
   int vec, ntc, ntr, factored;
@@ -73,6 +74,7 @@ struct AfBatch {
   int fin_start[AF_MAX_TENSORS + 1];   // prefix sums of ceil((R + C) / 256) over factored tensors
   int count;
   float beta2, eps1;
+  float beta1, decay;  // momentum coefficient; lr * weight_decay
 };
 
 // Tensor that owns 1-D block `b` under prefix table `start` (wave-uniform).
@@ -255,13 +257,15 @@ __global__ __launch_bounds__(1024) void af_coef_kernel(AfBatch b, adafactor_cfg 
   }
 }
 
+// W <- W - D - decay W,  D = alpha U, or with momentum m <- beta1 m + (1 - beta1) alpha U, D = m
 template <int VEC, bool FACT>
-__device__ __forceinline__ void af_apply_tile(const AfItem& it, int bx, int by) {
+__device__ __forceinline__ void af_apply_tile(const AfItem& it, int bx, int by, float beta1, float decay) {
   float* __restrict__ w = it.w;
   const float* __restrict__ g = it.g;
   const float* __restrict__ v_full = it.v_full;
   const float* __restrict__ v_row = it.v_row;
   bf16* __restrict__ lp = it.lp;
+  float* __restrict__ mom = it.m;
   const int64_t R = it.R, C = it.C;
   const AfWs& ws = it.ws;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -274,19 +278,28 @@ __device__ __forceinline__ void af_apply_tile(const AfItem& it, int bx, int by) 
   for (int rr = wave; rr < TR; rr += 4) {
     const int64_t r = r0 + rr;
     if (r >= R) break;
-    float gv[VEC], wv[VEC];
+    float gv[VEC], wv[VEC], dv[VEC];
     ldv<VEC>(g + r * C + c0, gv);
     ldv<VEC>(w + r * C + c0, wv);
     if constexpr (FACT) {
       const float rf = rsqrtf(v_row[r] * ws.scal[1]) * coef;
 #pragma unroll
-      for (int i = 0; i < VEC; ++i) wv[i] -= gv[i] * rf * cf[i];
+      for (int i = 0; i < VEC; ++i) dv[i] = gv[i] * rf * cf[i];
     } else {
       float vv[VEC];
       ldv<VEC>(v_full + r * C + c0, vv);
 #pragma unroll
-      for (int i = 0; i < VEC; ++i) wv[i] -= coef * gv[i] * rsqrtf(vv[i]);
+      for (int i = 0; i < VEC; ++i) dv[i] = coef * gv[i] * rsqrtf(vv[i]);
     }
+    if (mom) {
+      float mv[VEC];
+      ldv<VEC>(mom + r * C + c0, mv);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) { mv[i] = beta1 * mv[i] + (1.f - beta1) * dv[i]; dv[i] = mv[i]; }
+      stv<VEC>(mom + r * C + c0, mv);
+    }
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) wv[i] = wv[i] - dv[i] - decay * wv[i];
     stv<VEC>(w + r * C + c0, wv);
     if (lp) {
 #pragma unroll
@@ -301,11 +314,11 @@ __global__ __launch_bounds__(256) void af_apply_kernel(AfBatch b) {
   const int local = blockIdx.x - b.tile_start[ti];
   const int bx = local % it.ntc, by = local / it.ntc;
   if (it.vec == 4) {
-    if (it.factored) af_apply_tile<4, true>(it, bx, by);
-    else af_apply_tile<4, false>(it, bx, by);
+    if (it.factored) af_apply_tile<4, true>(it, bx, by, b.beta1, b.decay);
+    else af_apply_tile<4, false>(it, bx, by, b.beta1, b.decay);
   } else {
-    if (it.factored) af_apply_tile<1, true>(it, bx, by);
-    else af_apply_tile<1, false>(it, bx, by);
+    if (it.factored) af_apply_tile<1, true>(it, bx, by, b.beta1, b.decay);
+    else af_apply_tile<1, false>(it, bx, by, b.beta1, b.decay);
   }
 }
 
@@ -353,6 +366,8 @@ hipError_t launch_adafactor_multi(const AfTensor* t, int n, const adafactor_cfg&
   b.count = n;
   b.beta2 = (float)(1.0 - pow((double)c.step, -(double)c.decay_pow));
   b.eps1 = c.eps1;
+  b.beta1 = c.beta1;
+  b.decay = c.lr * c.weight_decay;
   char* wp = (char*)wsp;
   int64_t tiles = 0, fins = 0;
   bool any_factored = false;
@@ -361,6 +376,7 @@ hipError_t launch_adafactor_multi(const AfTensor* t, int n, const adafactor_cfg&
     AfItem& it = b.it[i];
     it.w = t[i].param; it.g = t[i].grad; it.v_row = t[i].v_row; it.v_col = t[i].v_col; it.v_full = t[i].v_full;
     it.lp = (bf16*)t[i].bf16_out;
+    it.m = c.beta1 > 0.f ? t[i].m : nullptr;
     it.R = t[i].rows; it.C = t[i].cols;
     it.ws = carve(wp, it.R, it.C, g);
     wp += adafactor_ws_bytes(it.R, it.C, t[i].factored);
@@ -390,7 +406,7 @@ hipError_t launch_adafactor_multi(const AfTensor* t, int n, const adafactor_cfg&
 hipError_t launch_adafactor(float* param, const float* grad, float* v_row, float* v_col, float* v_full,
                             int64_t R, int64_t C, int factored, const adafactor_cfg& c, void* bf16_out,
                             void* wsp, hipStream_t st) {
-  AfTensor t{param, grad, v_row, v_col, v_full, R, C, factored, bf16_out};
+  AfTensor t{param, grad, v_row, v_col, v_full, R, C, factored, bf16_out, nullptr};
   return launch_adafactor_multi(&t, 1, c, wsp, st);
 }
 

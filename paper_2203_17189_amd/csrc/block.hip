@@ -207,6 +207,8 @@ int adafactor_step(float* param, const float* grad, float* v_row, float* v_col, 
                    size_t workspace_bytes, void* stream) {
   if (!cfg) return T5_ERR_NULL;
   if (rows < 1 || cols < 1 || cfg->step < 1 || !(cfg->clip > 0.f) || !(cfg->eps1 >= 0.f)) return T5_ERR_SHAPE;
+  if (!(cfg->beta1 >= 0.f && cfg->beta1 < 1.f) || !(cfg->weight_decay >= 0.f)) return T5_ERR_SHAPE;
+  if (cfg->beta1 > 0.f) return T5_ERR_UNSUPPORTED;
   if (rows > (1 << 24) || cols > (1 << 24)) return T5_ERR_UNSUPPORTED;
   if (!param || !grad || !workspace) return T5_ERR_NULL;
   if (factored ? (!v_row || !v_col) : !v_full) return T5_ERR_NULL;
@@ -233,6 +235,7 @@ int adafactor_step_multi(const adafactor_tensor* t, int n, const adafactor_cfg* 
   if (n < 1) return T5_ERR_SHAPE;
   if (n > AF_MAX_TENSORS) return T5_ERR_UNSUPPORTED;
   if (cfg->step < 1 || !(cfg->clip > 0.f) || !(cfg->eps1 >= 0.f)) return T5_ERR_SHAPE;
+  if (!(cfg->beta1 >= 0.f && cfg->beta1 < 1.f) || !(cfg->weight_decay >= 0.f)) return T5_ERR_SHAPE;
   AfTensor items[AF_MAX_TENSORS];
   size_t need = 0;
   for (int i = 0; i < n; ++i) {
@@ -240,9 +243,10 @@ int adafactor_step_multi(const adafactor_tensor* t, int n, const adafactor_cfg* 
     if (t[i].rows > (1 << 24) || t[i].cols > (1 << 24)) return T5_ERR_UNSUPPORTED;
     if (!t[i].param || !t[i].grad) return T5_ERR_NULL;
     if (t[i].factored ? (!t[i].v_row || !t[i].v_col) : !t[i].v_full) return T5_ERR_NULL;
+    if (cfg->beta1 > 0.f && !t[i].m) return T5_ERR_NULL;
     need += adafactor_ws_bytes(t[i].rows, t[i].cols, t[i].factored);
     items[i] = AfTensor{t[i].param, t[i].grad, t[i].v_row, t[i].v_col, t[i].v_full, t[i].rows, t[i].cols,
-                        t[i].factored, t[i].bf16_copy_out};
+                        t[i].factored, t[i].bf16_copy_out, t[i].m};
   }
   if (!workspace) return T5_ERR_NULL;
   if (workspace_bytes < need) return T5_ERR_WORKSPACE;

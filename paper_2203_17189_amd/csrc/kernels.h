@@ -196,6 +196,7 @@ struct AfTensor {
   int64_t rows, cols;
   int factored;
   void* bf16_out;
+  float* m;  // momentum [rows, cols], used when cfg.beta1 > 0
 };
 hipError_t launch_adafactor_multi(const AfTensor* t, int n, const adafactor_cfg& c, void* ws, hipStream_t st);
 

@@ -190,6 +190,23 @@ def test_adafactor_validation():
     assert lib.adafactor_step(dummy, dummy, dummy, dummy, None, 8, 8, 1, C.byref(ok), None, dummy, 8, None) == 4
 
 
+def test_adafactor_variant_validation():
+    lib = P.lib()
+    dummy = C.c_void_p(4096)
+    mom = B._AfCfg(0.01, 0.8, 1e-30, 1e-3, 1.0, 1, 1, 0.9, 0.0)
+    assert lib.adafactor_step(dummy, dummy, dummy, dummy, None, 8, 8, 1, C.byref(mom), None, dummy, 1 << 20,
+                              None) == 3      # the single-tensor call has no momentum buffer
+    arr = (B._AfTensor * 1)()
+    arr[0] = B._AfTensor(4096, 4096, 4096, 4096, None, 8, 8, 1, None, None)
+    need = lib.adafactor_multi_workspace_bytes(arr, 1)
+    assert lib.adafactor_step_multi(arr, 1, C.byref(mom), dummy, need, None) == 1     # beta1 > 0 without m
+    for bad in (B._AfCfg(0.01, 0.8, 1e-30, 1e-3, 1.0, 1, 1, 1.0, 0.0), B._AfCfg(0.01, 0.8, 1e-30, 1e-3, 1.0, 1, 1, -0.1, 0.0),
+                B._AfCfg(0.01, 0.8, 1e-30, 1e-3, 1.0, 1, 1, 0.0, -1.0)):
+        assert lib.adafactor_step_multi(arr, 1, C.byref(bad), dummy, need, None) == 2
+        assert lib.adafactor_step(dummy, dummy, dummy, dummy, None, 8, 8, 1, C.byref(bad), None, dummy, 1 << 20,
+                                  None) == 2
+
+
 def test_adafactor_multi_validation():
     lib = P.lib()
     ok = B._AfCfg(0.01, 0.8, 1e-30, 1e-3, 1.0, 1, 1)

@@ -138,6 +138,40 @@ def test_adafactor_multi_matches_single_and_oracle():
             assert rel_err(to_np(b["param"]), ref[k][0])[0] <= 1e-5, (t, k)
 
 
+def test_adafactor_momentum_and_weight_decay():
+    # momentum buffers and decoupled decay through the batched entry point, four steps, against the oracle;
+    # weight decay alone also through the single-tensor entry point
+    P = _P()
+    shapes = [(64, 256, True), (70, 130, True), (1, 64, False), (33, 7, False)]
+    beta1, wd, lr = 0.9, 0.05, 0.02
+    dev, ref, single = [], [], []
+    for k, (rows, cols, fact) in enumerate(shapes):
+        p, _ = SI.make_adafactor_case(rows, cols, seed=80 + k)
+        mk = lambda: dict(param=torch.from_numpy(p.astype(np.float32)).cuda(), factored=fact,
+                          v_row=torch.zeros(rows, device="cuda"), v_col=torch.zeros(cols, device="cuda"),
+                          v_full=torch.zeros(rows, cols, device="cuda"), m=torch.zeros(rows, cols, device="cuda"))
+        dev.append(mk())
+        single.append(mk())
+        ref.append([(p, O.adafactor_zero_state(rows, cols, fact, momentum=True)),
+                    (p, O.adafactor_zero_state(rows, cols, fact))])
+    for t in (1, 2, 3, 4):
+        for k, (rows, cols, fact) in enumerate(shapes):
+            _, g = SI.make_adafactor_case(rows, cols, seed=800 + 10 * t + k, grad_std=1e-2 * t)
+            ref[k][0] = O.adafactor_step(ref[k][0][0], g, ref[k][0][1], step=t, lr=lr, factored=fact, beta1=beta1,
+                                         weight_decay=wd)
+            ref[k][1] = O.adafactor_step(ref[k][1][0], g, ref[k][1][1], step=t, lr=lr, factored=fact, weight_decay=wd)
+            dev[k]["grad"] = torch.from_numpy(g.astype(np.float32)).cuda()
+            d = single[k]
+            P.adafactor_step(d["param"], dev[k]["grad"], step=t, lr=lr, factored=fact, v_row=d["v_row"],
+                             v_col=d["v_col"], v_full=d["v_full"], weight_decay=wd)
+        P.adafactor_step_multi(dev, step=t, lr=lr, beta1=beta1, weight_decay=wd)
+        torch.cuda.synchronize()
+        for k in range(len(shapes)):
+            assert rel_err(to_np(dev[k]["param"]), ref[k][0][0])[0] <= 1e-5, (t, k)
+            assert rel_err(to_np(dev[k]["m"]), ref[k][0][1]["m"])[0] <= 1e-5, (t, k)
+            assert rel_err(to_np(single[k]["param"]), ref[k][1][0])[0] <= 1e-5, (t, k)
+
+
 # ------------------------------------------------------------------ bf16 block, small shapes
 SMALL_BF16 = [
     SI.BlockConfig("bf16_enc", 30, batch=2, seq=128, d_model=128, n_heads=2, d_kv=64, d_ff=256,

@@ -97,3 +97,75 @@ def test_resume_is_bit_identical():
     w2c, st2c = w2.copy(), {k: v.copy() for k, v in st2.items()}
     w3, _ = O.adafactor_step(w2c, grads[2], st2c, step=3, lr=0.01, factored=True)
     assert np.array_equal(w3, w)
+
+
+# ---------------------------------------------------------------- momentum and weight decay
+def test_momentum_closed_form_with_constant_sign_update():
+    """Same rank-one G every step, no parameter scaling: v stays G*G, U = sign(G) and the scaled
+    update D = lr sign(G) is constant, so m_t = (1 - beta1^t) D and
+    W_t = W_0 - lr sign(G) sum_{s<=t} (1 - beta1^s)."""
+    rng = np.random.default_rng(3)
+    g = np.outer(rng.uniform(0.5, 2, 6) * rng.choice([-1, 1], 6), rng.uniform(0.5, 2, 4))
+    w0 = rng.standard_normal((6, 4))
+    beta1, lr = 0.9, 0.02
+    w, st = w0, O.adafactor_zero_state(6, 4, True, momentum=True)
+    acc = 0.0
+    for t in range(1, 6):
+        w, st = O.adafactor_step(w, g, st, step=t, lr=lr, factored=True, scale_by_param=False, beta1=beta1)
+        acc += 1.0 - beta1 ** t
+        np.testing.assert_allclose(st["m"], (1.0 - beta1 ** t) * lr * np.sign(g), rtol=1e-10)
+        np.testing.assert_allclose(w, w0 - lr * np.sign(g) * acc, rtol=1e-10, atol=1e-13)
+
+
+def test_variants_reduce_to_the_plain_update():
+    p, g = SI.make_adafactor_case(9, 12, seed=3)
+    base, _ = O.adafactor_step(p, g, O.adafactor_zero_state(9, 12, True), step=1, lr=0.01, factored=True)
+    same, st = O.adafactor_step(p, g, O.adafactor_zero_state(9, 12, True), step=1, lr=0.01, factored=True,
+                                beta1=0.0, weight_decay=0.0)
+    assert np.array_equal(base, same) and "m" not in st
+    # beta1 -> 0+ : m = D, same parameters
+    near, st = O.adafactor_step(p, g, O.adafactor_zero_state(9, 12, True, momentum=True), step=1, lr=0.01,
+                                factored=True, beta1=1e-12)
+    np.testing.assert_allclose(near, base, rtol=1e-11, atol=1e-14)
+    np.testing.assert_allclose(st["m"], p - base, rtol=1e-9, atol=1e-14)
+
+
+def test_weight_decay_is_decoupled():
+    """The decay term is lr * wd * W whatever the gradient does: it adds to the plain update, and with
+    the parameter-scale factor switched off a vanishing gradient leaves exactly W (1 - lr wd)."""
+    p, g = SI.make_adafactor_case(8, 10, seed=4)
+    lr, wd = 0.05, 0.1
+    plain, _ = O.adafactor_step(p, g, O.adafactor_zero_state(8, 10, False), step=1, lr=lr, factored=False)
+    dec, _ = O.adafactor_step(p, g, O.adafactor_zero_state(8, 10, False), step=1, lr=lr, factored=False,
+                              weight_decay=wd)
+    np.testing.assert_allclose(dec, plain - lr * wd * p, rtol=1e-13, atol=1e-15)
+    zero_g, _ = O.adafactor_step(p, np.zeros_like(g), O.adafactor_zero_state(8, 10, False), step=1, lr=lr,
+                                 factored=False, weight_decay=wd, scale_by_param=False)
+    np.testing.assert_allclose(zero_g, p * (1 - lr * wd), rtol=1e-13)
+    # momentum does not touch the decay term: it acts on D only
+    both, st = O.adafactor_step(p, g, O.adafactor_zero_state(8, 10, False, momentum=True), step=1, lr=lr,
+                                factored=False, weight_decay=wd, beta1=0.5)
+    np.testing.assert_allclose(both, p - 0.5 * (p - plain) - lr * wd * p, rtol=1e-12, atol=1e-15)
+
+
+def test_weight_decay_against_torch_library_adafactor():
+    """torch.optim.Adafactor applies decoupled decay as W (1 - lr_t wd) with its own step size lr_t; fed
+    the same lr_t the oracle's update agrees over three steps (unfactored and factored)."""
+    if not hasattr(torch.optim, "Adafactor"):
+        pytest.skip("torch.optim.Adafactor not available")
+    for rows, cols in ((6, 9), (1, 12)):
+        p0, _ = SI.make_adafactor_case(rows, cols, seed=6)
+        tp = torch.nn.Parameter(torch.from_numpy(p0.copy()).reshape(rows, cols) if rows > 1
+                                else torch.from_numpy(p0.copy()).reshape(cols))
+        opt = torch.optim.Adafactor([tp], lr=0.01, beta2_decay=-0.8, eps=(1e-30, 1e-3), d=1.0, weight_decay=0.2,
+                                    foreach=False)
+        fact = rows > 1
+        w, st = p0, O.adafactor_zero_state(rows, cols, fact)
+        for t in (1, 2, 3):
+            _, g = SI.make_adafactor_case(rows, cols, seed=60 + t, grad_std=1e-2 * t)
+            tp.grad = torch.from_numpy(g.copy()).reshape(tp.shape)
+            opt.step()
+            # torch's relative step: min(lr, 1/sqrt(t)), and its parameter scale multiplies the update only
+            lr_t = min(0.01, 1.0 / math.sqrt(t))
+            w, st = O.adafactor_step(w, g, st, step=t, lr=lr_t, factored=fact, weight_decay=0.2)
+            np.testing.assert_allclose(w.reshape(tp.shape), tp.detach().numpy(), rtol=1e-9, atol=1e-12)
