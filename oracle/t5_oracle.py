@@ -14,7 +14,8 @@ therefore the public definition of the named layer, written out in full:
   * Self-attention whose logits get a learned bias looked up from a table by
     the *bucket* of (key position - query position); no 1/sqrt(d_kv) factor
     unless the caller asks for one through attn_scale.
-  * T5.1.1 feed-forward: gated GELU (tanh form), no biases.
+  * T5.1.1 feed-forward: gated GELU (tanh form), no biases.  Variants: the exact (erf)
+    GELU in the same gated form, and the original T5's ungated ReLU feed-forward.
   * Pre-norm residual wiring: h = x + Attn(Norm(x)); y = h + MLP(Norm(h)).
   * Stack: token embedding (no input scaling), N blocks sharing one relative-position
     table, final RMSNorm, logits (untied output matrix, or the embedding transposed
@@ -134,6 +135,52 @@ def gelu_grad(z: np.ndarray) -> np.ndarray:
     return 0.5 * (1.0 + t) + 0.5 * z * (1.0 - t * t) * GELU_KAPPA * (1.0 + 3.0 * GELU_BETA * z * z)
 
 
+def gelu_erf(z: np.ndarray) -> np.ndarray:
+    """Exact GELU: z * Phi(z), Phi the standard normal distribution function."""
+    erf = np.vectorize(math.erf, otypes=[np.float64])
+    return 0.5 * z * (1.0 + erf(z / math.sqrt(2.0)))
+
+
+def gelu_erf_grad(z: np.ndarray) -> np.ndarray:
+    erf = np.vectorize(math.erf, otypes=[np.float64])
+    return 0.5 * (1.0 + erf(z / math.sqrt(2.0))) + z * np.exp(-0.5 * z * z) / math.sqrt(2.0 * math.pi)
+
+
+def mlp_fwd(cfg, n2: np.ndarray, w: dict):
+    """Feed-forward sublayer without its norm and residual, by cfg.mlp:
+      "geglu_tanh" (T5.1.1): a = gelu_tanh(n2 Wi0) * (n2 Wi1)
+      "geglu_erf":           the same with the exact GELU
+      "relu" (original T5):  a = max(n2 Wi0, 0), no gate and no Wi1
+    Returns (a Wo_ff, saved)."""
+    kind = getattr(cfg, "mlp", "geglu_tanh")
+    u = n2 @ w["wi0"]
+    if kind == "relu":
+        a = np.maximum(u, 0.0)
+        return a @ w["wo_ff"], dict(u=u, a=a)
+    act = gelu if kind == "geglu_tanh" else gelu_erf
+    wl = n2 @ w["wi1"]
+    a = act(u) * wl
+    return a @ w["wo_ff"], dict(u=u, wl=wl, a=a)
+
+
+def mlp_bwd(cfg, dout: np.ndarray, n2: np.ndarray, w: dict, sv: dict):
+    """Given dout = gradient of the sublayer's output: (dn2, {wo_ff, wi0[, wi1]} gradients)."""
+    kind = getattr(cfg, "mlp", "geglu_tanh")
+    flat = lambda t: t.reshape(-1, t.shape[-1])
+    g = {"wo_ff": flat(sv["a"]).T @ flat(dout)}
+    da = dout @ w["wo_ff"].T
+    if kind == "relu":
+        du = da * (sv["u"] > 0.0)
+        g["wi0"] = flat(n2).T @ flat(du)
+        return du @ w["wi0"].T, g
+    act, act_grad = (gelu, gelu_grad) if kind == "geglu_tanh" else (gelu_erf, gelu_erf_grad)
+    du = da * sv["wl"] * act_grad(sv["u"])
+    dwl = da * act(sv["u"])
+    g["wi0"] = flat(n2).T @ flat(du)
+    g["wi1"] = flat(n2).T @ flat(dwl)
+    return du @ w["wi0"].T + dwl @ w["wi1"].T, g
+
+
 def softmax_rows(s: np.ndarray) -> np.ndarray:
     """Two-pass softmax over the last axis; -inf entries get probability exactly 0."""
     m = np.max(s, axis=-1, keepdims=True)
@@ -178,12 +225,9 @@ def block_fwd(cfg, x: np.ndarray, w: dict):
     c = _merge_heads(o)
     h = x + c @ w["wo"]
     n2, r2 = rmsnorm_fwd(h, w["ln2_scale"], cfg.rms_eps)
-    u = n2 @ w["wi0"]
-    wl = n2 @ w["wi1"]
-    a = gelu(u) * wl
-    y = h + a @ w["wo_ff"]
-    saved = dict(x=x, n1=n1, r1=r1, q=q, k=k, v=v, p=p, c=c, h=h, n2=n2, r2=r2, u=u, wl=wl, a=a,
-                 bucket=bucket)
+    mlp_out, mlp_saved = mlp_fwd(cfg, n2, w)
+    y = h + mlp_out
+    saved = dict(x=x, n1=n1, r1=r1, q=q, k=k, v=v, p=p, c=c, h=h, n2=n2, r2=r2, bucket=bucket, **mlp_saved)
     return y, saved
 
 
@@ -191,18 +235,11 @@ def block_bwd(cfg, dy: np.ndarray, w: dict, saved: dict):
     """Gradients of sum(y * dy) w.r.t. x and every weight.  Returns (dx, grads)."""
     nh, dk = cfg.n_heads, cfg.d_kv
     d = cfg.d_model
-    x, n1, r1, q, k, v, p, c, h, n2, r2, u, wl, a = (saved[t] for t in
-        ("x", "n1", "r1", "q", "k", "v", "p", "c", "h", "n2", "r2", "u", "wl", "a"))
+    x, n1, r1, q, k, v, p, c, h, n2, r2 = (saved[t] for t in
+        ("x", "n1", "r1", "q", "k", "v", "p", "c", "h", "n2", "r2"))
     flat = lambda t: t.reshape(-1, t.shape[-1])
-    g = {}
     # --- MLP
-    g["wo_ff"] = flat(a).T @ flat(dy)
-    da = dy @ w["wo_ff"].T
-    du = da * wl * gelu_grad(u)
-    dwl = da * gelu(u)
-    g["wi0"] = flat(n2).T @ flat(du)
-    g["wi1"] = flat(n2).T @ flat(dwl)
-    dn2 = du @ w["wi0"].T + dwl @ w["wi1"].T
+    dn2, g = mlp_bwd(cfg, dy, n2, w, saved)
     dh_norm, g["ln2_scale"] = rmsnorm_bwd(h, w["ln2_scale"], r2, dn2)
     dh = dy + dh_norm
     # --- attention
@@ -271,12 +308,10 @@ def decoder_block_fwd(cfg, x: np.ndarray, enc: np.ndarray, w: dict):
     h2 = h1 + cx @ w["xo"]
     # --- MLP sublayer
     n2, r2 = rmsnorm_fwd(h2, w["ln2_scale"], cfg.rms_eps)
-    u = n2 @ w["wi0"]
-    wl = n2 @ w["wi1"]
-    a = gelu(u) * wl
-    y = h2 + a @ w["wo_ff"]
+    mlp_out, mlp_saved = mlp_fwd(cfg, n2, w)
+    y = h2 + mlp_out
     saved = dict(x=x, enc=enc, n1=n1, r1=r1, q=q, k=k, v=v, p=p, c=c, h1=h1, nx=nx, rx=rx, qx=qx, kx=kx, vx=vx,
-                 px=px, cx=cx, h2=h2, n2=n2, r2=r2, u=u, wl=wl, a=a, bucket=bucket)
+                 px=px, cx=cx, h2=h2, n2=n2, r2=r2, bucket=bucket, **mlp_saved)
     return y, saved
 
 
@@ -285,15 +320,8 @@ def decoder_block_bwd(cfg, dy: np.ndarray, w: dict, saved: dict):
     nh, dk = cfg.n_heads, cfg.d_kv
     flat = lambda t: t.reshape(-1, t.shape[-1])
     sv = saved
-    g = {}
     # --- MLP sublayer
-    g["wo_ff"] = flat(sv["a"]).T @ flat(dy)
-    da = dy @ w["wo_ff"].T
-    du = da * sv["wl"] * gelu_grad(sv["u"])
-    dwl = da * gelu(sv["u"])
-    g["wi0"] = flat(sv["n2"]).T @ flat(du)
-    g["wi1"] = flat(sv["n2"]).T @ flat(dwl)
-    dn2 = du @ w["wi0"].T + dwl @ w["wi1"].T
+    dn2, g = mlp_bwd(cfg, dy, sv["n2"], w, sv)
     dh2_norm, g["ln2_scale"] = rmsnorm_bwd(sv["h2"], w["ln2_scale"], sv["r2"], dn2)
     dh2 = dy + dh2_norm
     # --- cross-attention sublayer

@@ -45,6 +45,7 @@ class BlockConfig:
     rms_eps: float = 1e-6
     attn_scale: float = 1.0   # T5 convention: no 1/sqrt(d_kv) on the logits
     adafactor: bool = False
+    mlp: str = "geglu_tanh"   # feed-forward: "geglu_tanh" (T5.1.1) | "geglu_erf" | "relu" (original T5, no gate)
     enc_seq: int = 0          # > 0: decoder block, with a cross-attention sublayer over an encoder
                               # output of this length between self-attention and the MLP
 
@@ -69,7 +70,7 @@ class BlockConfig:
             # per decoder token: q and o projections, scores and values over enc_seq keys; the k, v
             # projections of the enc_seq encoder tokens are spread over the seq decoder tokens
             cross = 4.0 * d * i + 4.0 * self.enc_seq * i + 4.0 * d * i * self.enc_seq / s
-        return 8.0 * d * i + attn + cross + 6.0 * d * f
+        return 8.0 * d * i + attn + cross + (4.0 if self.mlp == "relu" else 6.0) * d * f
 
     def model_flops(self, causal_half: bool = True) -> float:
         """fwd+bwd model FLOPs (3x forward), whole batch."""
@@ -129,6 +130,8 @@ def make_weights(cfg: BlockConfig) -> dict:
         "wi1": _draw(cfg, "wi1", (d, f), d ** -0.5),
         "wo_ff": _draw(cfg, "wo_ff", (f, d), f ** -0.5),
     }
+    if cfg.mlp == "relu":
+        del w["wi1"]
     if cfg.enc_seq > 0:
         w.update({
             "lnx_scale": np.ones(d),

@@ -209,6 +209,13 @@ def _bucket_from_fixture(rp, causal):
     return base + max(b for b, f in bi.items() if f <= n)
 
 
+def _torch_mlp(cfg, n2, w):
+    if cfg.mlp == "relu":
+        return F.relu(n2 @ w["wi0"]) @ w["wo_ff"]
+    approx = "tanh" if cfg.mlp == "geglu_tanh" else "none"
+    return (F.gelu(n2 @ w["wi0"], approximate=approx) * (n2 @ w["wi1"])) @ w["wo_ff"]
+
+
 def _torch_block(cfg, x, w):
     """Independent forward written with torch library ops (einsum, rms_norm, softmax, gelu)."""
     B, S, H, K = cfg.batch, cfg.seq, cfg.n_heads, cfg.d_kv
@@ -226,8 +233,7 @@ def _torch_block(cfg, x, w):
     o = torch.einsum("bhij,bhjk->bihk", p, v).reshape(B, S, H * K)
     h = x + o @ w["wo"]
     n2 = F.rms_norm(h, (cfg.d_model,), w["ln2_scale"], eps=cfg.rms_eps)
-    a = F.gelu(n2 @ w["wi0"], approximate="tanh") * (n2 @ w["wi1"])
-    return h + a @ w["wo_ff"]
+    return h + _torch_mlp(cfg, n2, w)
 
 
 @pytest.mark.parametrize("cfg", [TINY, TINY_CAUSAL, SI.CONFIGS["c1_tiny_f32"],
@@ -292,3 +298,50 @@ def test_bias_table_gradient_sums_to_zero_per_head(cfg):
         for b in range(32):
             if b not in reach:
                 assert np.all(g["rel_table"][b] == 0.0)
+
+
+# ---------------------------------------------------------------- feed-forward variants
+TINY_RELU = replace(TINY, name="tiny_relu", index=12, mlp="relu")
+TINY_ERF = replace(TINY_CAUSAL, name="tiny_erf", index=13, mlp="geglu_erf")
+
+
+def test_erf_gelu_against_library_and_identities():
+    z = np.linspace(-6, 6, 241)
+    tz = torch.from_numpy(z).requires_grad_()
+    ty = F.gelu(tz, approximate="none")
+    ty.sum().backward()
+    np.testing.assert_allclose(O.gelu_erf(z), ty.detach().numpy(), rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(O.gelu_erf_grad(z), tz.grad.numpy(), rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(O.gelu_erf(z) - O.gelu_erf(-z), z, rtol=0, atol=1e-14)   # Phi(z) + Phi(-z) = 1
+    assert O.gelu_erf(np.array([0.0]))[0] == 0.0 and abs(O.gelu_erf_grad(np.array([0.0]))[0] - 0.5) < 1e-15
+    # the tanh form approximates it to a few 1e-4
+    assert 1e-5 < np.abs(O.gelu(z) - O.gelu_erf(z)).max() < 1e-3
+
+
+def test_relu_feed_forward_is_linear_where_all_preactivations_are_positive():
+    """Original-T5 feed-forward: with u = n2 Wi0 > 0 everywhere, a = u and the sublayer is the product of
+    the two matrices; with u < 0 everywhere it is zero and passes no gradient."""
+    cfg = TINY_RELU
+    w, x, dy = _case(cfg)
+    assert "wi1" not in w
+    n2 = np.abs(np.random.default_rng(0).standard_normal((2, 5, cfg.d_model)))
+    wpos = dict(w, wi0=np.abs(w["wi0"]))
+    out, sv = O.mlp_fwd(cfg, n2, wpos)
+    np.testing.assert_allclose(out, n2 @ wpos["wi0"] @ wpos["wo_ff"], rtol=1e-12)
+    dn2, g = O.mlp_bwd(cfg, np.ones_like(out), n2, wpos, sv)
+    np.testing.assert_allclose(dn2, np.ones_like(out) @ wpos["wo_ff"].T @ wpos["wi0"].T, rtol=1e-12)
+    assert set(g) == {"wo_ff", "wi0"}
+    wneg = dict(w, wi0=-np.abs(w["wi0"]))
+    out, sv = O.mlp_fwd(cfg, n2, wneg)
+    dn2, g = O.mlp_bwd(cfg, np.ones_like(out), n2, wneg, sv)
+    assert np.all(out == 0) and np.all(dn2 == 0) and np.all(g["wi0"] == 0)
+
+
+@pytest.mark.parametrize("cfg", [TINY_RELU, TINY_ERF, replace(TINY_RELU, causal=True, index=14)])
+def test_variants_forward_and_backward_against_torch_autograd(cfg):
+    test_forward_and_backward_against_torch_autograd(cfg)
+
+
+@pytest.mark.parametrize("cfg", [TINY_RELU, TINY_ERF])
+def test_variants_backward_against_central_differences(cfg):
+    test_backward_against_central_differences(cfg)

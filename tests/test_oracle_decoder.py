@@ -132,10 +132,12 @@ def _torch_decoder_block(cfg, x, enc, w):
                                         scale=cfg.attn_scale)
     h2 = h1 + ox.permute(0, 2, 1, 3).reshape(B, S, H * K) @ w["xo"]
     n2 = F.rms_norm(h2, (cfg.d_model,), w["ln2_scale"], eps=cfg.rms_eps)
-    return h2 + (F.gelu(n2 @ w["wi0"], approximate="tanh") * (n2 @ w["wi1"])) @ w["wo_ff"]
+    from test_oracle_block import _torch_mlp
+    return h2 + _torch_mlp(cfg, n2, w)
 
 
 @pytest.mark.parametrize("cfg", [DEC, DEC_LONG_ENC, replace(DEC, causal=False, index=14),
+                                 replace(DEC, mlp="relu", index=16), replace(DEC, mlp="geglu_erf", index=17),
                                  replace(SI.CONFIGS["c1_tiny_f32"], causal=True, enc_seq=96, batch=1, index=15)])
 def test_forward_and_backward_against_torch_autograd(cfg):
     w, x, enc, dy = _case(cfg)
