@@ -42,6 +42,12 @@ enum {
 
 enum { T5_F32 = 0, T5_BF16 = 1 };
 
+/* Feed-forward sublayer of a block (paper Sec. 4 names both T5 generations):
+ *   T5_MLP_GEGLU_TANH  T5.1.1: (gelu_tanh(n2 Wi0) * (n2 Wi1)) Wo_ff
+ *   T5_MLP_RELU        original T5: max(n2 Wi0, 0) Wo_ff; wi1 and its gradient pointer are ignored
+ *   T5_MLP_GEGLU_ERF   the gated form with the exact GELU z Phi(z) */
+enum { T5_MLP_GEGLU_TANH = 0, T5_MLP_RELU = 1, T5_MLP_GEGLU_ERF = 2 };
+
 /* One Transformer block (paper Sec. 4: T5.1.1 encoder layer, or a decoder-only layer when
  * causal != 0):
  *   n1 = RMSNorm(x; ln1_scale)                      r = (mean_c x_c^2 + rms_eps)^-1/2, no mean subtraction
@@ -58,6 +64,7 @@ typedef struct {
   int32_t dtype;        /* T5_F32 or T5_BF16: storage type of x, y, dy, dx and all weights */
   float rms_eps;        /* 1e-6 in T5 */
   float attn_scale;     /* 1.0 = T5 convention (scale folded into the initialisation) */
+  int32_t mlp_kind;     /* T5_MLP_*; 0 = the T5.1.1 gated tanh-GELU */
 } t5_block_cfg;
 
 /* Weights, device pointers, element type cfg.dtype, row-major [in, out]. */

@@ -13,6 +13,7 @@ _LIB = None
 WEIGHT_NAMES = ("ln1_scale", "wq", "wk", "wv", "wo", "rel_table", "ln2_scale", "wi0", "wi1", "wo_ff")
 CROSS_WEIGHT_NAMES = ("lnx_scale", "xq", "xk", "xv", "xo")
 T5_F32, T5_BF16 = 0, 1
+MLP_KINDS = {"geglu_tanh": 0, "relu": 1, "geglu_erf": 2}
 
 
 class T5Error(RuntimeError):
@@ -24,7 +25,7 @@ class T5Error(RuntimeError):
 class _Cfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("batch", "seq", "d_model", "n_heads", "d_kv", "d_ff", "num_buckets",
                                          "max_distance", "causal", "dtype")] + \
-               [("rms_eps", C.c_float), ("attn_scale", C.c_float)]
+               [("rms_eps", C.c_float), ("attn_scale", C.c_float), ("mlp_kind", C.c_int32)]
 
 
 class _Weights(C.Structure):
@@ -165,7 +166,8 @@ def _cfg_struct(cfg) -> _Cfg:
     if isinstance(dt, str):
         dt = {"f32": T5_F32, "bf16": T5_BF16}[dt]
     return _Cfg(cfg.batch, cfg.seq, cfg.d_model, cfg.n_heads, cfg.d_kv, cfg.d_ff, cfg.num_buckets,
-                cfg.max_distance, int(bool(cfg.causal)), int(dt), float(cfg.rms_eps), float(cfg.attn_scale))
+                cfg.max_distance, int(bool(cfg.causal)), int(dt), float(cfg.rms_eps), float(cfg.attn_scale),
+                MLP_KINDS[getattr(cfg, "mlp", "geglu_tanh")])
 
 
 def _torch_dtype(cfg):
@@ -207,6 +209,16 @@ def t5_block_workspace_bytes(cfg) -> int:
     return int(lib().t5_block_workspace_bytes(C.byref(_cfg_struct(cfg))))
 
 
+def _block_names(cfg, names=WEIGHT_NAMES):
+    """Tensor names of a block: the ungated ReLU feed-forward has no wi1."""
+    return tuple(n for n in names if not (n == "wi1" and getattr(cfg, "mlp", "geglu_tanh") == "relu"))
+
+
+def _addr(d, n):
+    t = d.get(n)
+    return None if t is None else t.data_ptr()
+
+
 def _weights_struct(cfg, weights) -> _Weights:
     dt = _torch_dtype(cfg)
     inner = cfg.n_heads * cfg.d_kv
@@ -214,9 +226,10 @@ def _weights_struct(cfg, weights) -> _Weights:
               "wk": cfg.d_model * inner, "wv": cfg.d_model * inner, "wo": inner * cfg.d_model,
               "rel_table": cfg.num_buckets * cfg.n_heads, "wi0": cfg.d_model * cfg.d_ff,
               "wi1": cfg.d_model * cfg.d_ff, "wo_ff": cfg.d_ff * cfg.d_model}
-    for n in WEIGHT_NAMES:
+    names = _block_names(cfg)
+    for n in names:
         _check_tensor(weights[n], dt, shapes[n], n)
-    return _Weights(*[weights[n].data_ptr() for n in WEIGHT_NAMES])
+    return _Weights(*[(_addr(weights, n) if n in names else None) for n in WEIGHT_NAMES])
 
 
 def _byte_buffer(nbytes: int, device) -> torch.Tensor:
@@ -245,7 +258,8 @@ def t5_block_fwd(cfg, x, weights, y=None, stash=None, workspace=None):
 
 
 def alloc_grads(cfg, weights) -> dict:
-    return {n: torch.zeros(weights[n].shape, dtype=torch.float32, device=weights[n].device) for n in WEIGHT_NAMES}
+    return {n: torch.zeros(weights[n].shape, dtype=torch.float32, device=weights[n].device)
+            for n in _block_names(cfg)}
 
 
 def t5_block_bwd(cfg, dy, x, weights, stash, dx=None, grads=None, accumulate=False, workspace=None):
@@ -261,9 +275,9 @@ def t5_block_bwd(cfg, dy, x, weights, stash, dx=None, grads=None, accumulate=Fal
     _check_tensor(dx, dt, n, "dx")
     if grads is None:
         grads = alloc_grads(cfg, weights)
-    for nme in WEIGHT_NAMES:
+    for nme in _block_names(cfg):
         _check_tensor(grads[nme], torch.float32, weights[nme].numel(), "grad " + nme)
-    gs = _Grads(*[grads[nme].data_ptr() for nme in WEIGHT_NAMES])
+    gs = _Grads(*[_addr(grads, nme) for nme in WEIGHT_NAMES])
     if workspace is None:
         workspace = _byte_buffer(lib().t5_block_workspace_bytes(C.byref(cs)), x.device)
     rc = lib().t5_block_bwd(C.byref(cs), _ptr(dy), _ptr(x), C.byref(ws), _ptr(stash), _ptr(dx), C.byref(gs),
@@ -318,7 +332,7 @@ def t5_decoder_block_fwd(cfg, x, enc, weights, y=None, stash=None, workspace=Non
 
 def alloc_decoder_grads(cfg, weights) -> dict:
     return {n: torch.zeros(weights[n].shape, dtype=torch.float32, device=weights[n].device)
-            for n in WEIGHT_NAMES + CROSS_WEIGHT_NAMES}
+            for n in _block_names(cfg) + CROSS_WEIGHT_NAMES}
 
 
 def t5_decoder_block_bwd(cfg, dy, x, enc, weights, stash, dx=None, denc=None, grads=None, accumulate=False,
@@ -341,9 +355,9 @@ def t5_decoder_block_bwd(cfg, dy, x, enc, weights, stash, dx=None, denc=None, gr
     _check_tensor(denc, dt, ne, "denc")
     if grads is None:
         grads = alloc_decoder_grads(cfg, weights)
-    for nme in WEIGHT_NAMES + CROSS_WEIGHT_NAMES:
+    for nme in _block_names(cfg) + CROSS_WEIGHT_NAMES:
         _check_tensor(grads[nme], torch.float32, weights[nme].numel(), "grad " + nme)
-    gs = _Grads(*[grads[nme].data_ptr() for nme in WEIGHT_NAMES])
+    gs = _Grads(*[_addr(grads, nme) for nme in WEIGHT_NAMES])
     gx = _CrossGrads(*[grads[nme].data_ptr() for nme in CROSS_WEIGHT_NAMES])
     es = int(cfg.enc_seq)
     if workspace is None:
@@ -375,7 +389,7 @@ def alloc_stack_grads(sc, weights) -> dict:
     g = {k: z(weights[k]) for k in ("embedding", "rel_table", "final_scale")}
     if not sc.tied_logits:
         g["logits_w"] = z(weights["logits_w"])
-    g["layers"] = [{n: z(lw[n]) for n in LAYER_WEIGHT_NAMES} for lw in weights["layers"]]
+    g["layers"] = [{n: z(lw[n]) for n in _block_names(sc.block, LAYER_WEIGHT_NAMES)} for lw in weights["layers"]]
     return g
 
 
@@ -412,9 +426,9 @@ def t5_stack_loss_and_grad(sc, tokens, targets, weights, grads=None, want_grads=
             _check_tensor(grads[nme], torch.float32, weights[nme].numel(), "grad " + nme)
         lg = (_Grads * sc.n_layers)()
         for l, d in enumerate(grads["layers"]):
-            for nme in LAYER_WEIGHT_NAMES:
+            for nme in _block_names(b, LAYER_WEIGHT_NAMES):
                 _check_tensor(d[nme], torch.float32, weights["layers"][l][nme].numel(), f"grad layer {l} {nme}")
-            lg[l] = _Grads(*[(d[nme].data_ptr() if nme != "rel_table" else grads["rel_table"].data_ptr())
+            lg[l] = _Grads(*[(_addr(d, nme) if nme != "rel_table" else grads["rel_table"].data_ptr())
                              for nme in WEIGHT_NAMES])
         gs = _StackGrads(grads["embedding"].data_ptr(), grads["rel_table"].data_ptr(), lg,
                          grads["final_scale"].data_ptr(), None if sc.tied_logits else grads["logits_w"].data_ptr())
@@ -450,8 +464,9 @@ def alloc_encdec_grads(ec, weights) -> dict:
     g = {k: z(weights[k]) for k in _ENCDEC_FLAT}
     if not ec.tied_logits:
         g["logits_w"] = z(weights["logits_w"])
-    g["enc_layers"] = [{n: z(lw[n]) for n in LAYER_WEIGHT_NAMES} for lw in weights["enc_layers"]]
-    g["dec_layers"] = [{n: z(lw[n]) for n in LAYER_WEIGHT_NAMES + CROSS_WEIGHT_NAMES} for lw in weights["dec_layers"]]
+    names = _block_names(ec.enc_block, LAYER_WEIGHT_NAMES)
+    g["enc_layers"] = [{n: z(lw[n]) for n in names} for lw in weights["enc_layers"]]
+    g["dec_layers"] = [{n: z(lw[n]) for n in names + CROSS_WEIGHT_NAMES} for lw in weights["dec_layers"]]
     return g
 
 
@@ -496,15 +511,15 @@ def t5_encdec_loss_and_grad(ec, enc_tokens, dec_tokens, targets, weights, grads=
             _check_tensor(grads[nme], torch.float32, weights[nme].numel(), "grad " + nme)
         elg = (_Grads * ec.n_enc_layers)()
         for l, gd in enumerate(grads["enc_layers"]):
-            for nme in LAYER_WEIGHT_NAMES:
+            for nme in _block_names(e, LAYER_WEIGHT_NAMES):
                 _check_tensor(gd[nme], torch.float32, weights["enc_layers"][l][nme].numel(), f"grad enc {l} {nme}")
-            elg[l] = _Grads(*[(p(gd[nme]) if nme != "rel_table" else p(grads["enc_rel_table"])) for nme in WEIGHT_NAMES])
+            elg[l] = _Grads(*[(_addr(gd, nme) if nme != "rel_table" else p(grads["enc_rel_table"])) for nme in WEIGHT_NAMES])
         dlg = (_Grads * ec.n_dec_layers)()
         dxg = (_CrossGrads * ec.n_dec_layers)()
         for l, gd in enumerate(grads["dec_layers"]):
-            for nme in LAYER_WEIGHT_NAMES + CROSS_WEIGHT_NAMES:
+            for nme in _block_names(d, LAYER_WEIGHT_NAMES) + CROSS_WEIGHT_NAMES:
                 _check_tensor(gd[nme], torch.float32, weights["dec_layers"][l][nme].numel(), f"grad dec {l} {nme}")
-            dlg[l] = _Grads(*[(p(gd[nme]) if nme != "rel_table" else p(grads["dec_rel_table"])) for nme in WEIGHT_NAMES])
+            dlg[l] = _Grads(*[(_addr(gd, nme) if nme != "rel_table" else p(grads["dec_rel_table"])) for nme in WEIGHT_NAMES])
             dxg[l] = _CrossGrads(*[p(gd[nme]) for nme in CROSS_WEIGHT_NAMES])
         gs = _EncDecGrads(p(grads["embedding"]), p(grads["enc_rel_table"]), elg, p(grads["enc_final_scale"]),
                           p(grads["dec_rel_table"]), dlg, dxg, p(grads["dec_final_scale"]),

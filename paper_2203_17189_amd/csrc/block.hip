@@ -66,7 +66,7 @@ int t5_block_fwd(const t5_block_cfg* cfg, const void* x, const t5_block_weights*
   const int rc = validate_cfg(cfg, &D, &lut);
   if (rc != T5_OK) return rc;
   if (!x || !w || !y || !stash || !workspace) return T5_ERR_NULL;
-  if (!weights_present(w)) return T5_ERR_NULL;
+  if (!weights_present(w, D)) return T5_ERR_NULL;
   if (workspace_bytes < carve_fwd(D, nullptr, nullptr)) return T5_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   Stash S;
@@ -88,7 +88,7 @@ int t5_block_bwd(const t5_block_cfg* cfg, const void* dy, const void* x, const t
   const int rc = validate_cfg(cfg, &D, &lut);
   if (rc != T5_OK) return rc;
   if (!dy || !x || !w || !stash || !dx || !dw || !workspace) return T5_ERR_NULL;
-  if (!weights_present(w) || !grads_present(dw)) return T5_ERR_NULL;
+  if (!weights_present(w, D) || !grads_present(dw, D)) return T5_ERR_NULL;
   if (workspace_bytes < carve_bwd(D, nullptr, nullptr)) return T5_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   Stash S;
@@ -114,7 +114,7 @@ int t5_decoder_block_fwd(const t5_block_cfg* cfg, int32_t enc_seq, const void* x
   const int rc = validate_cfg(cfg, &D, &lut, enc_seq);
   if (rc != T5_OK) return rc;
   if (!x || !enc || !w || !xw || !y || !stash || !workspace) return T5_ERR_NULL;
-  if (!weights_present(w)) return T5_ERR_NULL;
+  if (!weights_present(w, D)) return T5_ERR_NULL;
   if (!xw->lnx_scale || !xw->xq || !xw->xk || !xw->xv || !xw->xo) return T5_ERR_NULL;
   if (workspace_bytes < carve_fwd(D, nullptr, nullptr)) return T5_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
@@ -141,7 +141,7 @@ int t5_decoder_block_bwd(const t5_block_cfg* cfg, int32_t enc_seq, const void* d
   const int rc = validate_cfg(cfg, &D, &lut, enc_seq);
   if (rc != T5_OK) return rc;
   if (!dy || !x || !enc || !w || !xw || !stash || !dx || !denc || !dw || !dxw || !workspace) return T5_ERR_NULL;
-  if (!weights_present(w) || !grads_present(dw)) return T5_ERR_NULL;
+  if (!weights_present(w, D) || !grads_present(dw, D)) return T5_ERR_NULL;
   if (!xw->lnx_scale || !xw->xq || !xw->xk || !xw->xv || !xw->xo) return T5_ERR_NULL;
   if (!dxw->lnx_scale || !dxw->xq || !dxw->xk || !dxw->xv || !dxw->xo) return T5_ERR_NULL;
   if (workspace_bytes < carve_bwd(D, nullptr, nullptr)) return T5_ERR_WORKSPACE;

@@ -26,6 +26,7 @@ struct Dims {
   int64_t T;
   size_t es;  // bytes per stored element
   int ty;     // IN_F32 / IN_BF16
+  int mlp;    // ACT_GELU_TANH / ACT_RELU / ACT_GELU_ERF (the T5_MLP_* values)
   int Sk;     // encoder length of the cross-attention sublayer; 0: block without cross-attention
   int64_t Te; // B * Sk
 };
@@ -35,6 +36,8 @@ int validate_cfg(const t5_block_cfg* c, Dims* o, RelposLut* lut, int enc_seq = 0
   if (c->batch < 1 || c->seq < 1 || c->d_model < 1 || c->n_heads < 1 || c->d_kv < 1 || c->d_ff < 1 || enc_seq < 0)
     return T5_ERR_SHAPE;
   if (c->dtype != T5_F32 && c->dtype != T5_BF16) return T5_ERR_UNSUPPORTED;
+  if (c->mlp_kind != T5_MLP_GEGLU_TANH && c->mlp_kind != T5_MLP_RELU && c->mlp_kind != T5_MLP_GEGLU_ERF)
+    return T5_ERR_UNSUPPORTED;
   if (!(c->rms_eps >= 0.f) || !std::isfinite(c->attn_scale)) return T5_ERR_SHAPE;
   const int64_t T = (int64_t)c->batch * c->seq;
   const int64_t Te = (int64_t)c->batch * enc_seq;
@@ -52,6 +55,9 @@ int validate_cfg(const t5_block_cfg* c, Dims* o, RelposLut* lut, int enc_seq = 0
     o->ty = c->dtype == T5_BF16 ? IN_BF16 : IN_F32;
     o->es = c->dtype == T5_BF16 ? 2 : 4;
     o->Sk = enc_seq; o->Te = Te;
+    o->mlp = c->mlp_kind;
+    static_assert(T5_MLP_GEGLU_TANH == ACT_GELU_TANH && T5_MLP_RELU == ACT_RELU && T5_MLP_GEGLU_ERF == ACT_GELU_ERF,
+                  "the config values are the kernels' activation codes");
   }
   return T5_OK;
 }
@@ -219,19 +225,24 @@ bool fused_fwd_ok(const Dims& D) {
   // fused gated-GELU GEMM is the most demanding one, so probe it with placeholder pointers.
   if (D.ty != IN_BF16 || D.d % 64 != 0 || D.I % 64 != 0 || D.F % 64 != 0) return false;
   static const long long dummy[4] = {0, 0, 0, 0};
+  if (D.mlp == ACT_RELU) {
+    GemmDesc g = gemm1((int)D.T, D.F, D.d, dummy, D.d, 1, dummy, D.d, 1, IN_BF16);
+    return gemm_mfma_supported(g, epi(EPI_STORE, (void*)dummy, D.F, IN_BF16));
+  }
   GemmDesc g = gemm1((int)D.T, 2 * D.F, D.d, dummy, D.d, 1, dummy, D.d, 1, IN_BF16);
   GemmEpi e = epi(EPI_GEGLU_FWD, (void*)dummy, D.F, IN_BF16);
   e.out1 = (void*)dummy; e.out2 = (void*)dummy;
   return gemm_mfma_supported(g, e);
 }
 
-bool weights_present(const t5_block_weights* w) {
-  return w->ln1_scale && w->wq && w->wk && w->wv && w->wo && w->rel_table && w->ln2_scale && w->wi0 && w->wi1 &&
-         w->wo_ff;
+// The ungated feed-forward has no wi1.
+bool weights_present(const t5_block_weights* w, const Dims& D) {
+  return w->ln1_scale && w->wq && w->wk && w->wv && w->wo && w->rel_table && w->ln2_scale && w->wi0 &&
+         (w->wi1 || D.mlp == ACT_RELU) && w->wo_ff;
 }
-bool grads_present(const t5_block_grads* g) {
-  return g->ln1_scale && g->wq && g->wk && g->wv && g->wo && g->rel_table && g->ln2_scale && g->wi0 && g->wi1 &&
-         g->wo_ff;
+bool grads_present(const t5_block_grads* g, const Dims& D) {
+  return g->ln1_scale && g->wq && g->wk && g->wv && g->wo && g->rel_table && g->ln2_scale && g->wi0 &&
+         (g->wi1 || D.mlp == ACT_RELU) && g->wo_ff;
 }
 
 AttnDims self_dims(const t5_block_cfg* cfg, const Dims& D) {
@@ -260,7 +271,8 @@ int fwd_pack_weights(const Dims& D, const t5_block_weights* w, const t5_cross_we
   std::memset(&pj, 0, sizeof(pj));
   pj.j[0] = PackJob{{w->wq, w->wk, w->wv}, 3, D.d, D.I, 0, W.wqkv_t};
   pj.j[1] = PackJob{{w->wo, nullptr, nullptr}, 1, D.I, D.d, 0, W.wo_t};
-  pj.j[2] = PackJob{{w->wi0, w->wi1, nullptr}, 2, D.d, D.F, 32, W.wi_t};
+  if (D.mlp == ACT_RELU) pj.j[2] = PackJob{{w->wi0, nullptr, nullptr}, 1, D.d, D.F, 0, W.wi_t};
+  else pj.j[2] = PackJob{{w->wi0, w->wi1, nullptr}, 2, D.d, D.F, 32, W.wi_t};
   pj.j[3] = PackJob{{w->wo_ff, nullptr, nullptr}, 1, D.F, D.d, 0, W.woff_t};
   pj.count = 4;
   if (xw) {
@@ -346,10 +358,16 @@ int fwd_mlp(const t5_block_cfg* cfg, const Dims& D, const float* hin, const t5_b
             const FwdWs& W, bool fused, void* y, hipStream_t st) {
   const int T = (int)D.T, ty = D.ty;
   T5_STEP("rmsnorm_fwd", launch_rmsnorm_fwd(hin, IN_F32, w->ln2_scale, S.n2, ty, S.r2, T, D.d, cfg->rms_eps, st));
-  if (fused) {
+  if (D.mlp == ACT_RELU) {  // a = max(n2 Wi0, 0); the backward reads the mask off a itself
+    GemmDesc g = fused ? gemm1(T, D.F, D.d, S.n2, D.d, 1, W.wi_t, D.d, 1, ty)
+                       : gemm1(T, D.F, D.d, S.n2, D.d, 1, w->wi0, D.F, 0, ty);
+    GemmEpi e = epi(EPI_STORE, S.a, D.F, ty);
+    e.act = ACT_RELU;
+    T5_STEP("gemm_wi_relu", run_gemm(g, e, st));
+  } else if (fused) {
     GemmDesc g = gemm1(T, 2 * D.F, D.d, S.n2, D.d, 1, W.wi_t, D.d, 1, ty);
     GemmEpi e = epi(EPI_GEGLU_FWD, S.gp, D.F, ty);
-    e.out1 = S.gl; e.out2 = S.a;
+    e.out1 = S.gl; e.out2 = S.a; e.act = D.mlp;
     if (!gemm_mfma_supported(g, e)) return T5_ERR_UNSUPPORTED;
     T5_STEP("gemm_wi_geglu", launch_gemm_mfma(g, e, st));
   } else {
@@ -357,7 +375,7 @@ int fwd_mlp(const t5_block_cfg* cfg, const Dims& D, const float* hin, const t5_b
     T5_STEP("gemm_wi", run_gemm(g0, epi(EPI_STORE, S.gp, D.F, ty), st));
     GemmDesc g1 = gemm1(T, D.F, D.d, S.n2, D.d, 1, w->wi1, D.F, 0, ty);
     T5_STEP("gemm_wi", run_gemm(g1, epi(EPI_STORE, S.gl, D.F, ty), st));
-    T5_STEP("geglu_fwd", launch_geglu_fwd(S.gp, S.gl, S.a, ty, (int64_t)D.T * D.F, st));
+    T5_STEP("geglu_fwd", launch_geglu_fwd(S.gp, S.gl, S.a, ty, (int64_t)D.T * D.F, D.mlp, st));
   }
   GemmDesc g = fused ? gemm1(T, D.d, D.F, S.a, D.F, 1, W.woff_t, D.F, 1, ty)
                      : gemm1(T, D.d, D.F, S.a, D.F, 1, w->wo_ff, D.d, 0, ty);
@@ -379,7 +397,8 @@ int bwd_zero(const Dims& D, const t5_block_grads* dw, const t5_cross_grads* dxw,
   if (!acc) {
     const int64_t dI = (int64_t)D.d * D.I, dF = (int64_t)D.d * D.F;
     add(dw->wq, dI); add(dw->wk, dI); add(dw->wv, dI); add(dw->wo, dI);
-    add(dw->wi0, dF); add(dw->wi1, dF); add(dw->wo_ff, dF);
+    add(dw->wi0, dF); add(dw->wo_ff, dF);
+    if (D.mlp != ACT_RELU) add(dw->wi1, dF);
     if (dxw) { add(dxw->xq, dI); add(dxw->xk, dI); add(dxw->xv, dI); add(dxw->xo, dI); }
   }
   static_assert(ZERO_MAX >= 12, "ddiag + 7 block gradients + 4 cross-attention gradients");
@@ -401,23 +420,42 @@ int bwd_mlp(const Dims& D, const void* dy, const float* hin, const t5_block_weig
     e.accumulate = 1;
     T5_STEP("gemm_dwo_ff", run_gemm(g, e, st));
   }
-  {  // da = dy Wo_ff^T, fused with the gated-GELU backward: du = da w gelu'(u), dw = da gelu(u)
-    GemmDesc g = gemm1(T, D.F, D.d, dy, D.d, 1, w->wo_ff, D.d, 1, ty);
-    GemmEpi e = epi(EPI_GEGLU_BWD, du_p, 2 * D.F, ty);
-    e.out1 = dw_p; e.aux0 = S.gp; e.aux1 = S.gl; e.aux_type = ty; e.ld_aux = D.F;
-    T5_STEP("gemm_da_geglu_bwd", run_gemm(g, e, st));
-  }
-  {  // dWi0 | dWi1 = n2^T [du | dw]
-    GemmDesc g = gemm1(D.d, 2 * D.F, T, S.n2, D.d, 0, du_p, 2 * D.F, 0, ty);
-    GemmEpi e = epi(EPI_SPLIT_F32, dw->wi0, D.F, IN_F32);
-    e.out1 = dw->wi1; e.split_n = D.F; e.accumulate = 1;
-    T5_STEP("gemm_dwi", run_gemm(g, e, st));
-  }
-  {  // dn2 = du Wi0^T + dw Wi1^T
-    GemmDesc g = gemm1(T, D.d, D.F, du_p, 2 * D.F, 1, w->wi0, D.F, 1, ty);
-    g.nseg = 2;
-    g.seg[1] = GemmSeg{dw_p, w->wi1, 2 * D.F, D.F, D.F};
-    T5_STEP("gemm_dn2", run_gemm(g, epi(EPI_STORE, W.dn, D.d, IN_F32), st));
+  if (D.mlp == ACT_RELU) {
+    {  // du = (dy Wo_ff^T) where a > 0
+      GemmDesc g = gemm1(T, D.F, D.d, dy, D.d, 1, w->wo_ff, D.d, 1, ty);
+      GemmEpi e = epi(EPI_RESID, du_p, D.F, ty);
+      e.aux0 = S.a; e.aux_type = ty; e.aux_mask = 1;
+      T5_STEP("gemm_da_relu_bwd", run_gemm(g, e, st));
+    }
+    {  // dWi0 = n2^T du
+      GemmDesc g = gemm1(D.d, D.F, T, S.n2, D.d, 0, du_p, D.F, 0, ty);
+      GemmEpi e = epi(EPI_SPLIT_F32, dw->wi0, D.F, IN_F32);
+      e.accumulate = 1;
+      T5_STEP("gemm_dwi", run_gemm(g, e, st));
+    }
+    {  // dn2 = du Wi0^T
+      GemmDesc g = gemm1(T, D.d, D.F, du_p, D.F, 1, w->wi0, D.F, 1, ty);
+      T5_STEP("gemm_dn2", run_gemm(g, epi(EPI_STORE, W.dn, D.d, IN_F32), st));
+    }
+  } else {
+    {  // da = dy Wo_ff^T, fused with the gated-GELU backward: du = da w gelu'(u), dw = da gelu(u)
+      GemmDesc g = gemm1(T, D.F, D.d, dy, D.d, 1, w->wo_ff, D.d, 1, ty);
+      GemmEpi e = epi(EPI_GEGLU_BWD, du_p, 2 * D.F, ty);
+      e.out1 = dw_p; e.aux0 = S.gp; e.aux1 = S.gl; e.aux_type = ty; e.ld_aux = D.F;
+      T5_STEP("gemm_da_geglu_bwd", run_gemm(g, e, st));
+    }
+    {  // dWi0 | dWi1 = n2^T [du | dw]
+      GemmDesc g = gemm1(D.d, 2 * D.F, T, S.n2, D.d, 0, du_p, 2 * D.F, 0, ty);
+      GemmEpi e = epi(EPI_SPLIT_F32, dw->wi0, D.F, IN_F32);
+      e.out1 = dw->wi1; e.split_n = D.F; e.accumulate = 1;
+      T5_STEP("gemm_dwi", run_gemm(g, e, st));
+    }
+    {  // dn2 = du Wi0^T + dw Wi1^T
+      GemmDesc g = gemm1(T, D.d, D.F, du_p, 2 * D.F, 1, w->wi0, D.F, 1, ty);
+      g.nseg = 2;
+      g.seg[1] = GemmSeg{dw_p, w->wi1, 2 * D.F, D.F, D.F};
+      T5_STEP("gemm_dn2", run_gemm(g, epi(EPI_STORE, W.dn, D.d, IN_F32), st));
+    }
   }
   T5_STEP("rmsnorm_bwd", launch_rmsnorm_bwd(hin, IN_F32, w->ln2_scale, ty, S.r2, W.dn, dy, ty, W.dh,
                             ty == IN_BF16 ? W.dh_lp : nullptr, ty, dw->ln2_scale, W.dg_partial, acc, T, D.d,

@@ -76,6 +76,18 @@ __device__ __forceinline__ void gelu_tanh_both(float z, float& g, float& dg) {
   dg = fmaf(g * (1.f - s), 2.f * 0.7978845608028654f * fmaf(z2, 3.f * 0.044715f, 1.f), s);
 }
 
+// Exact GELU z Phi(z) and its derivative Phi(z) + z phi(z).
+__device__ __forceinline__ void gelu_erf_both(float z, float& g, float& dg) {
+  const float cdf = 0.5f * (1.f + erff(z * 0.7071067811865476f));
+  g = z * cdf;
+  dg = fmaf(z * 0.3989422804014327f, __expf(-0.5f * z * z), cdf);
+}
+enum { ACT_GELU_TANH = 0, ACT_RELU = 1, ACT_GELU_ERF = 2 };
+__device__ __forceinline__ void gelu_both(int act, float z, float& g, float& dg) {
+  if (act == ACT_GELU_ERF) gelu_erf_both(z, g, dg);
+  else gelu_tanh_both(z, g, dg);
+}
+
 // Threshold table of the logarithmic relative-position buckets, built on the host in exact
 // integer arithmetic and passed to kernels by value.
 struct RelposLut {

@@ -374,7 +374,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
               float gl, dgl;
-              gelu_tanh_both(uu[q], gl, dgl);
+              gelu_both(e.act, uu[q], gl, dgl);
               gpb[q] = (bf16)(ww[q] * dgl);
               glb[q] = (bf16)gl;
               ab[q] = (bf16)(gl * ww[q]);
@@ -469,12 +469,24 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
                 st_stream(reinterpret_cast<bf16x4*>((bf16*)e.out1 + o), dw);
               } else {  // EPI_STORE, EPI_RESID
                 if constexpr (EPI == EPI_RESID) {
+                  f32x4 ax;
                   if (aux_f32) {
-#pragma unroll
-                    for (int qq = 0; qq < 4; ++qq) v[qq] += xf[set][q][qq];
+                    ax = xf[set][q];
                   } else {
 #pragma unroll
-                    for (int qq = 0; qq < 4; ++qq) v[qq] += (float)xa[set][q][qq];
+                    for (int qq = 0; qq < 4; ++qq) ax[qq] = (float)xa[set][q][qq];
+                  }
+                  if (e.aux_mask) {
+#pragma unroll
+                    for (int qq = 0; qq < 4; ++qq) v[qq] = ax[qq] > 0.f ? v[qq] : 0.f;
+                  } else {
+#pragma unroll
+                    for (int qq = 0; qq < 4; ++qq) v[qq] += ax[qq];
+                  }
+                } else {
+                  if (e.act == ACT_RELU) {
+#pragma unroll
+                    for (int qq = 0; qq < 4; ++qq) v[qq] = fmaxf(v[qq], 0.f);
                   }
                 }
                 if (e.out_type == IN_BF16) {
@@ -511,7 +523,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
           const int f = (n >> 6) * 32 + col_l;
           const float uu = acc[i][j][r], ww = acc[i][j + 1][r];
           float gl, dgl;
-          gelu_tanh_both(uu, gl, dgl);
+          gelu_both(e.act, uu, gl, dgl);
           const size_t o = (size_t)m * e.ld0 + f;
           ((bf16*)e.out0)[o] = (bf16)(ww * dgl);
           ((bf16*)e.out1)[o] = (bf16)gl;
@@ -522,14 +534,16 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
         for (int j = 0; j < NI; ++j) {
           const int n = n0 + wn * TNW + j * 32 + col_l;
           if (n >= g.N) continue;
-          const float v = acc[i][j][r];
+          float v = acc[i][j][r];
           const size_t o = (size_t)m * e.ld0 + n;
           if constexpr (EPI == EPI_STORE) {
+            if (e.act == ACT_RELU) v = fmaxf(v, 0.f);
             if (e.out_type == IN_BF16) ((bf16*)e.out0)[o] = (bf16)v; else ((float*)e.out0)[o] = v;
           } else if constexpr (EPI == EPI_RESID) {
             const size_t oa = (size_t)m * (e.ld_aux ? e.ld_aux : e.ld0) + n;
             const float a = e.aux_type == IN_BF16 ? (float)((const bf16*)e.aux0)[oa] : ((const float*)e.aux0)[oa];
-            if (e.out_type == IN_BF16) ((bf16*)e.out0)[o] = (bf16)(v + a); else ((float*)e.out0)[o] = v + a;
+            const float r = e.aux_mask ? (a > 0.f ? v : 0.f) : v + a;
+            if (e.out_type == IN_BF16) ((bf16*)e.out0)[o] = (bf16)r; else ((float*)e.out0)[o] = r;
           } else if constexpr (EPI == EPI_GEGLU_BWD) {
             const size_t oa = (size_t)m * (e.ld_aux ? e.ld_aux : e.ld0) + n;
             const float gp = (float)((const bf16*)e.aux0)[oa], gl = (float)((const bf16*)e.aux1)[oa];

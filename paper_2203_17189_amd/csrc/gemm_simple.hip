@@ -83,11 +83,13 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(GemmDesc g, GemmEpi e)
       const size_t o = (size_t)m * e.ld0 + n;
       switch (e.kind) {
         case EPI_STORE:
-          st_elem(e.out0, o, e.out_type, v);
+          st_elem(e.out0, o, e.out_type, e.act == ACT_RELU ? fmaxf(v, 0.f) : v);
           break;
-        case EPI_RESID:
-          st_elem(e.out0, o, e.out_type, v + ld_elem(e.aux0, (size_t)m * (e.ld_aux ? e.ld_aux : e.ld0) + n, e.aux_type));
+        case EPI_RESID: {
+          const float a = ld_elem(e.aux0, (size_t)m * (e.ld_aux ? e.ld_aux : e.ld0) + n, e.aux_type);
+          st_elem(e.out0, o, e.out_type, e.aux_mask ? (a > 0.f ? v : 0.f) : v + a);
           break;
+        }
         case EPI_GEGLU_BWD: {
           const size_t oa = (size_t)m * (e.ld_aux ? e.ld_aux : e.ld0) + n;
           const float gp = ld_elem(e.aux0, oa, e.aux_type), gl = ld_elem(e.aux1, oa, e.aux_type);
@@ -110,13 +112,13 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(GemmDesc g, GemmEpi e)
 }
 
 template <typename T>
-__global__ void geglu_fwd_kernel(T* __restrict__ u, T* __restrict__ w, T* __restrict__ a, int64_t n) {
+__global__ void geglu_fwd_kernel(T* __restrict__ u, T* __restrict__ w, T* __restrict__ a, int64_t n, int act) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (; i < n; i += stride) {
     const float uu = to_f32(u[i]), ww = to_f32(w[i]);
     float gl, dgl;
-    gelu_tanh_both(uu, gl, dgl);
+    gelu_both(act, uu, gl, dgl);
     a[i] = from_f32<T>(gl * ww);
     u[i] = from_f32<T>(ww * dgl);
     w[i] = from_f32<T>(gl);
@@ -182,13 +184,13 @@ hipError_t launch_zero_f32(const ZeroList& z, hipStream_t st) {
   return hipGetLastError();
 }
 
-hipError_t launch_geglu_fwd(void* u, void* w, void* a, int type, int64_t n, hipStream_t st) {
+hipError_t launch_geglu_fwd(void* u, void* w, void* a, int type, int64_t n, int act, hipStream_t st) {
   int64_t blocks = (n + 255) / 256;
   if (blocks > 65536) blocks = 65536;
   if (type == IN_BF16)
-    geglu_fwd_kernel<bf16><<<(int)blocks, 256, 0, st>>>((bf16*)u, (bf16*)w, (bf16*)a, n);
+    geglu_fwd_kernel<bf16><<<(int)blocks, 256, 0, st>>>((bf16*)u, (bf16*)w, (bf16*)a, n, act);
   else
-    geglu_fwd_kernel<float><<<(int)blocks, 256, 0, st>>>((float*)u, (float*)w, (float*)a, n);
+    geglu_fwd_kernel<float><<<(int)blocks, 256, 0, st>>>((float*)u, (float*)w, (float*)a, n, act);
   return hipGetLastError();
 }
 

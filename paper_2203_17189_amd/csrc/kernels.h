@@ -61,6 +61,8 @@ struct GemmEpi {
   int aux_type;
   int split_n;
   int accumulate;
+  int act;       // EPI_STORE: ACT_RELU stores max(acc, 0); EPI_GEGLU_FWD: ACT_GELU_TANH or ACT_GELU_ERF
+  int aux_mask;  // EPI_RESID: != 0 stores acc where aux0 > 0 and 0 elsewhere instead of acc + aux0
 };
 struct GemmDesc {
   int M, N, nseg;
@@ -104,7 +106,7 @@ hipError_t launch_pack_transpose_multi(const PackJobs& jobs, hipStream_t st);
 
 // ------------------------------------------------------------------ elementwise gated GELU (simple path)
 // a = gelu(u) * w; then overwrites u with w * gelu'(u) and w with gelu(u) (the saved backward factors).
-hipError_t launch_geglu_fwd(void* u, void* w, void* a, int type, int64_t n, hipStream_t st);
+hipError_t launch_geglu_fwd(void* u, void* w, void* a, int type, int64_t n, int act, hipStream_t st);
 
 // ------------------------------------------------------------------ attention
 // Queries: S per batch element; keys/values: Sk per batch element (Sk == S for self-attention).

@@ -61,7 +61,7 @@ int bind_layers(Layers& s, const t5_block_weights* layers, const t5_cross_weight
   s.lw.assign(layers, layers + s.L);
   for (auto& w : s.lw) {
     w.rel_table = rel_table;
-    if (!weights_present(&w)) return T5_ERR_NULL;
+    if (!weights_present(&w, s.D)) return T5_ERR_NULL;
   }
   if (dec) {
     s.xw.assign(cross, cross + s.L);
@@ -74,7 +74,7 @@ int bind_layers(Layers& s, const t5_block_weights* layers, const t5_cross_weight
   s.lg.assign(glayers, glayers + s.L);
   for (auto& g : s.lg) {
     g.rel_table = d_rel_table;  // never written per layer: the shared table's gradient is folded once
-    if (!grads_present(&g)) return T5_ERR_NULL;
+    if (!grads_present(&g, s.D)) return T5_ERR_NULL;
   }
   if (dec) {
     s.xg.assign(gcross, gcross + s.L);

@@ -10,7 +10,7 @@ import synth_inputs as SI
 from oracle import t5_oracle as O
 from parity_util import (TOL_BF16_ACT, TOL_BF16_DEC_ACT, TOL_BF16_DEC_DX, TOL_BF16_DEC_DX_NAMED, TOL_BF16_DENC, TOL_BF16_DENC_NAMED, TOL_BF16_DW, TOL_BF16_DW_NAMED,
                          TOL_F32,
-                         make_decoder_case, rel_err, run_decoder_block_gpu, to_dev, to_np)
+                         make_decoder_case, rel_err, relu_aware, run_decoder_block_gpu, to_dev, to_np)
 
 pytestmark = pytest.mark.gpu
 
@@ -22,6 +22,7 @@ F32_CASES = [
     replace(C1, name="dec_f32_one_enc_token", index=42, causal=True, enc_seq=1),
     replace(C1, name="dec_f32_long_enc", index=43, batch=1, seq=20, causal=True, enc_seq=300),
     replace(C1, name="dec_f32_bidirectional_self", index=44, causal=False, enc_seq=70),
+    replace(C1, name="dec_f32_relu", index=51, causal=True, enc_seq=48, mlp="relu"),
 ]
 
 
@@ -61,6 +62,8 @@ SMALL_BF16 = [
     # encoder length not a multiple of 128: the simple cross-attention kernels with MFMA self-attention
     SI.BlockConfig("dec_bf16_ragged_enc", 49, batch=2, seq=128, d_model=128, n_heads=2, d_kv=64, d_ff=256, causal=True,
                    attn_scale=64 ** -0.5, enc_seq=100),
+    SI.BlockConfig("dec_bf16_relu", 52, batch=2, seq=128, d_model=128, n_heads=2, d_kv=64, d_ff=256, causal=True,
+                   attn_scale=64 ** -0.5, enc_seq=128, mlp="relu"),
     # nothing a multiple of anything: simple kernels throughout
     SI.BlockConfig("dec_bf16_ragged", 50, batch=1, seq=100, d_model=72, n_heads=3, d_kv=24, d_ff=136, causal=True,
                    attn_scale=24 ** -0.5, enc_seq=61),
@@ -69,7 +72,8 @@ SMALL_BF16 = [
 
 @pytest.mark.parametrize("cfg", SMALL_BF16, ids=[c.name for c in SMALL_BF16])
 def test_decoder_block_bf16_small(cfg):
-    _check(cfg, TOL_BF16_DEC_ACT, TOL_BF16_DEC_DX, TOL_BF16_DENC, TOL_BF16_DW)
+    _check(cfg, TOL_BF16_DEC_ACT, relu_aware(cfg, TOL_BF16_DEC_DX), relu_aware(cfg, TOL_BF16_DENC),
+           relu_aware(cfg, TOL_BF16_DW))
 
 
 def test_decoder_named_config_reduced_batch():

@@ -8,7 +8,7 @@ import torch
 
 import synth_inputs as SI
 from oracle import t5_oracle as O
-from parity_util import TOL_F32, rel_err, stack_bf16_tol, to_dev, to_np
+from parity_util import TOL_F32, rel_err, relu_aware, stack_bf16_tol, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -18,6 +18,7 @@ F32_CASES = [
     SI.StackConfig("stack_f32_tied", replace(BLK, index=61, causal=False), n_layers=2, vocab=64, tied_logits=True,
                    z_loss=1e-3),                                                               # 16-byte rows: register loss kernel
     SI.StackConfig("stack_f32_remat", replace(BLK, index=62), n_layers=3, vocab=40, remat=True, z_loss=0.0),
+    SI.StackConfig("stack_f32_relu", replace(BLK, index=68, mlp="relu"), n_layers=2, vocab=40, z_loss=1e-3),
     SI.StackConfig("stack_f32_wide_vocab", replace(BLK, index=63, batch=1, seq=16), n_layers=1, vocab=5000, z_loss=1e-4),
 ]
 
@@ -116,6 +117,7 @@ BF16_CASES = [
     SI.StackConfig("stack_bf16_tied", replace(BF_BLK, index=65, causal=False), n_layers=2, vocab=512, tied_logits=True),
     SI.StackConfig("stack_bf16_t5_vocab", replace(BF_BLK, index=66, batch=1, d_model=64, n_heads=1, d_ff=128),
                    n_layers=1, vocab=32128),
+    SI.StackConfig("stack_bf16_relu_tied", replace(BF_BLK, index=69, mlp="relu"), n_layers=2, vocab=512, tied_logits=True),
     SI.StackConfig("stack_bf16_ragged", SI.BlockConfig("stack_bf16_ragged", 67, batch=1, seq=50, d_model=72, n_heads=3,
                                                         d_kv=24, d_ff=136, causal=True, attn_scale=24 ** -0.5),
                    n_layers=2, vocab=301),
@@ -124,7 +126,7 @@ BF16_CASES = [
 
 @pytest.mark.parametrize("sc", BF16_CASES, ids=[c.name for c in BF16_CASES])
 def test_stack_bf16_small(sc):
-    _compare(sc, 5e-4, *stack_bf16_tol(sc.n_layers))
+    _compare(sc, 5e-4, *relu_aware(sc.block, stack_bf16_tol(sc.n_layers)))
 
 
 def test_stack_bf16_remat_matches_stashed():
