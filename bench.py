@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the T5.1.1 block hot path (forward + backward [+ Adafactor]) on one MI355X.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2_small|c3_base|c4_gpt_causal|c5_xl|c6_dec_base|s1_lm_base|e1_t5_base]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2_small|c3_base|c4_gpt_causal|c5_xl|c6_dec_base|c7_xl_tp8_share|s1_lm_base|e1_t5_base]
 
 Prints ONE JSON line.  A "step" is one pass of the whole hot path over one batch of seeded
 synthetic input already resident in HBM: t5_block_fwd + t5_block_bwd (t5_decoder_block_fwd/bwd for the

@@ -83,6 +83,9 @@ CONFIGS = {
     "c3_base": BlockConfig("c3_base", 2, 128, 512, 768, 12, 64, 2048, adafactor=True),
     "c4_gpt_causal": BlockConfig("c4_gpt_causal", 3, 16, 2048, 2048, 16, 128, 5120, causal=True),
     "c5_xl": BlockConfig("c5_xl", 4, 32, 1024, 2048, 32, 64, 5120, adafactor=True),
+    # One GPU's share of c5_xl under the paper's tensor model parallelism (Sec. 2.2) over 8 devices: heads
+    # and feed-forward width split by 8 (4 heads, d_ff 640); the [T, d] outputs would be summed across devices
+    "c7_xl_tp8_share": BlockConfig("c7_xl_tp8_share", 7, 32, 1024, 2048, 4, 64, 640),
     # T5.1.1-Base decoder block: causal self-attention, cross-attention over 512 encoder positions, MLP
     "c6_dec_base": BlockConfig("c6_dec_base", 5, 128, 512, 768, 12, 64, 2048, causal=True, enc_seq=512),
 }

@@ -26,7 +26,7 @@ from parity_util import (TOL_BF16_ACT, TOL_BF16_DW, TOL_BF16_DW_NAMED, TOL_BF16_
 
 pytestmark = pytest.mark.gpu
 
-CASES = [("c2_small", 2), ("c3_base", 2), ("c4_gpt_causal", 1), ("c5_xl", 1)]
+CASES = [("c2_small", 2), ("c3_base", 2), ("c4_gpt_causal", 1), ("c5_xl", 1), ("c7_xl_tp8_share", 1)]
 
 
 def _scaled(cfg):

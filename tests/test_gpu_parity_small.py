@@ -193,6 +193,10 @@ SMALL_BF16 = [
                    attn_scale=64 ** -0.5),
     SI.BlockConfig("bf16_ragged", 32, batch=1, seq=100, d_model=72, n_heads=3, d_kv=24, d_ff=136,
                    attn_scale=24 ** -0.5),
+    # long rows: 32 query tiles and 64 key tiles per head, causal, 128 channels (the largest per-head problem of
+    # the workloads is 2048 x 2048)
+    SI.BlockConfig("bf16_dec_4096_dk128", 29, batch=1, seq=4096, d_model=128, n_heads=1, d_kv=128, d_ff=128, causal=True,
+                   attn_scale=128 ** -0.5),
     # other bucket tables: the saturated bucket starts at a small offset (narrow per-diagonal window in
     # the dq kernel, most sub-tiles take the scalar path) or beyond the sequence (every sub-tile is
     # resolved per diagonal)
