@@ -253,16 +253,30 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnIO io, const 
                                                         0, 0, 0);
     }
     float mx = -INFINITY;
+    // only tiles that reach above the diagonal of this wave's queries pay for the mask (wave-uniform)
+    const bool on_diag = CAUSAL && j0 + BC - 1 > i0 + wave * 32;
+    if (on_diag) {
 #pragma unroll
-    for (int kt = 0; kt < BC / 32; ++kt)
+      for (int kt = 0; kt < BC / 32; ++kt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int j = j0 + kt * 32 + ((r >> 2) << 3) + (g << 2) + (r & 3);
-        float s = BIAS ? fmaf(sT[kt][r], sc, dg[dg_base + j]) : sT[kt][r] * sc;
-        if (CAUSAL && j > i) s = -INFINITY;
-        sT[kt][r] = s;
-        mx = fmaxf(mx, s);
-      }
+        for (int r = 0; r < 16; ++r) {
+          const int j = j0 + kt * 32 + ((r >> 2) << 3) + (g << 2) + (r & 3);
+          float s = BIAS ? fmaf(sT[kt][r], sc, dg[dg_base + j]) : sT[kt][r] * sc;
+          if (j > i) s = -INFINITY;
+          sT[kt][r] = s;
+          mx = fmaxf(mx, s);
+        }
+    } else {
+#pragma unroll
+      for (int kt = 0; kt < BC / 32; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int j = j0 + kt * 32 + ((r >> 2) << 3) + (g << 2) + (r & 3);
+          const float s = BIAS ? fmaf(sT[kt][r], sc, dg[dg_base + j]) : sT[kt][r] * sc;
+          sT[kt][r] = s;
+          mx = fmaxf(mx, s);
+        }
+    }
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m, mx);
     const float alpha = fast_exp2(m - m_new);
@@ -451,12 +465,20 @@ __global__ __launch_bounds__(256, DK == 64 ? 3 : 2) void attn_bwd_dq_mfma_kernel
         sT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Kt, kt * 32, kk, lane), qf[kk], sT, 0, 0, 0);
         dpT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Vt, kt * 32, kk, lane), dof[kk], dpT, 0, 0, 0);
       }
+      if (CAUSAL && j0s + 31 > i_w0) {  // sub-tile reaches above the diagonal (wave-uniform)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int j = j0s + ((r >> 2) << 3) + (g << 2) + (r & 3);
-        float p = BIAS ? fast_exp2(fmaf(sT[r], sc, bias[r]) + nlse2) : fast_exp2(fmaf(sT[r], sc, nlse2));
-        if (CAUSAL && j > i) p = 0.f;
-        sT[r] = p * (dpT[r] + ndv);
+        for (int r = 0; r < 16; ++r) {
+          const int j = j0s + ((r >> 2) << 3) + (g << 2) + (r & 3);
+          float p = BIAS ? fast_exp2(fmaf(sT[r], sc, bias[r]) + nlse2) : fast_exp2(fmaf(sT[r], sc, nlse2));
+          if (j > i) p = 0.f;
+          sT[r] = p * (dpT[r] + ndv);
+        }
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float p = BIAS ? fast_exp2(fmaf(sT[r], sc, bias[r]) + nlse2) : fast_exp2(fmaf(sT[r], sc, nlse2));
+          sT[r] = p * (dpT[r] + ndv);
+        }
       }
       // ---- bias gradient of this 32x32 sub-tile (wave-uniform branches)
       if constexpr (!BIAS) {
@@ -645,14 +667,26 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Qt, qb * 32, kk, lane), kf[kk], s, 0, 0, 0);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Dt, qb * 32, kk, lane), vf[kk], dp, 0, 0, 0);
       }
+      // with 64 channels the second copy of the loop costs a wave per SIMD in registers: mask always
+      if (CAUSAL && (DK == 64 || j0 + wave * 32 + 31 > q0 + qb * 32)) {  // some key here lies after some query
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int il = qb * 32 + ((r >> 2) << 3) + (g << 2) + (r & 3);
-        const int i = q0 + il;
-        float p = BIAS ? fast_exp2(fmaf(s[r], sc, HOIST ? bias[r] : dg[j_loc + (S - 1 - i)])) : fast_exp2(s[r] * sc);
-        if (CAUSAL && j > i) p = 0.f;
-        s[r] = p;
-        dp[r] = p * dp[r];
+        for (int r = 0; r < 16; ++r) {
+          const int il = qb * 32 + ((r >> 2) << 3) + (g << 2) + (r & 3);
+          const int i = q0 + il;
+          float p = BIAS ? fast_exp2(fmaf(s[r], sc, HOIST ? bias[r] : dg[j_loc + (S - 1 - i)])) : fast_exp2(s[r] * sc);
+          if (j > i) p = 0.f;
+          s[r] = p;
+          dp[r] = p * dp[r];
+        }
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int il = qb * 32 + ((r >> 2) << 3) + (g << 2) + (r & 3);
+          const int i = q0 + il;
+          const float p = BIAS ? fast_exp2(fmaf(s[r], sc, HOIST ? bias[r] : dg[j_loc + (S - 1 - i)])) : fast_exp2(s[r] * sc);
+          s[r] = p;
+          dp[r] = p * dp[r];
+        }
       }
 #pragma unroll
       for (int mm = 0; mm < 2; ++mm) {
