@@ -600,7 +600,10 @@ hipError_t launch_layout(const GemmDesc& g, const GemmEpi& e, hipStream_t st) {
     // k-slices, hence fewer float atomics per output element); k is split so that the workgroups
     // fill whole rounds of the 256 compute units.  Partial sums meet in float32 atomics on a zeroed
     // output.
-    big = t256 >= 64;
+    // 256x256 tiles from 48 output tiles on, and from 24 when the reduction is long (measured at d_model 768:
+    // dWi 3x16 tiles -18 % at 65536 and -10 % at 16384 tokens; dWo_ff 8x3 and dWqkv 3x9 tiles -14 % at 65536
+    // tokens but +10..18 % at 16384, where a workgroup's share of k no longer pays for the larger epilogue)
+    big = t256 >= 48 || (t256 >= 24 && nk * KQ >= 49152);
     const int64_t tiles = big ? t256 : t128;
     const int per_cu = big ? 1 : 2;  // concurrent workgroups per compute unit (LDS-limited)
     double best = -1.0;
