@@ -624,11 +624,22 @@ hipError_t launch_layout(const GemmDesc& g, const GemmEpi& e, hipStream_t st) {
     // and so do the epilogue-heavy gated-GELU kernels (three outputs, or two inputs and two outputs);
     // the gated-GELU forward goes back to one 256x256 tile once k is long enough (measured: better
     // from K = 2048, worse at K = 768) because the smaller tiles re-stream more operand data
+    // residual epilogues into a narrow output (N < 1024: T5.1.1-Small/Base widths), measured per shape:
+    // K <= 512 as below (256x128), 128x128 tiles for K up to 768 (-6..15 % at N = 768), 256x256 beyond
+    // (-4..9 %)
+    if (EPI == EPI_RESID && g.N < 1024 && nk > 8) {
+      if (nk <= 12) return launch_cfg<128, 128, 2, 2, A_KC, B_KC, EPI, 4, 1>(g, e, split_k, st);
+      return launch_cfg<256, 256, 2, 2, A_KC, B_KC, EPI, 5, 1>(g, e, split_k, st);
+    }
     if (EPI != EPI_SPLIT_F32 && (nk <= 16 || (EPI == EPI_GEGLU_FWD && nk < 24) || EPI == EPI_GEGLU_BWD ||
                                  (EPI == EPI_RESID && nk <= 32)))
       return launch_cfg<256, 128, 2, 2, A_KC, B_KC, EPI, 3, 2>(g, e, split_k, st);
     return launch_cfg<256, 256, 2, 2, A_KC, B_KC, EPI, 5, 1>(g, e, split_k, st);
   }
+  // too few 256x256 tiles to fill the chip, but a long reduction: 256x128 tiles, two per compute unit
+  // (8192 x 768 x 32128: -11 % against 128x128)
+  if (EPI != EPI_SPLIT_F32 && t256 >= 64 && nk >= 64)
+    return launch_cfg<256, 128, 2, 2, A_KC, B_KC, EPI, 3, 2>(g, e, split_k, st);
   return launch_cfg<128, 128, 2, 2, A_KC, B_KC, EPI, 4, 1>(g, e, split_k, st);
 }
 
