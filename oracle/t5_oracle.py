@@ -146,29 +146,36 @@ def gelu_erf_grad(z: np.ndarray) -> np.ndarray:
     return 0.5 * (1.0 + erf(z / math.sqrt(2.0))) + z * np.exp(-0.5 * z * z) / math.sqrt(2.0 * math.pi)
 
 
-def mlp_fwd(cfg, n2: np.ndarray, w: dict):
+def mlp_fwd(cfg, n2: np.ndarray, w: dict, hidden_scale=None):
     """Feed-forward sublayer without its norm and residual, by cfg.mlp:
       "geglu_tanh" (T5.1.1): a = gelu_tanh(n2 Wi0) * (n2 Wi1)
       "geglu_erf":           the same with the exact GELU
       "relu" (original T5):  a = max(n2 Wi0, 0), no gate and no Wi1
-    Returns (a Wo_ff, saved)."""
+    hidden_scale (dropout on the hidden activation, or None) multiplies a before the output projection.
+    Returns (a Wo_ff, saved); saved["a"] is the activation the output projection saw."""
     kind = getattr(cfg, "mlp", "geglu_tanh")
     u = n2 @ w["wi0"]
     if kind == "relu":
         a = np.maximum(u, 0.0)
+        if hidden_scale is not None:
+            a = a * hidden_scale
         return a @ w["wo_ff"], dict(u=u, a=a)
     act = gelu if kind == "geglu_tanh" else gelu_erf
     wl = n2 @ w["wi1"]
     a = act(u) * wl
+    if hidden_scale is not None:
+        a = a * hidden_scale
     return a @ w["wo_ff"], dict(u=u, wl=wl, a=a)
 
 
-def mlp_bwd(cfg, dout: np.ndarray, n2: np.ndarray, w: dict, sv: dict):
+def mlp_bwd(cfg, dout: np.ndarray, n2: np.ndarray, w: dict, sv: dict, hidden_scale=None):
     """Given dout = gradient of the sublayer's output: (dn2, {wo_ff, wi0[, wi1]} gradients)."""
     kind = getattr(cfg, "mlp", "geglu_tanh")
     flat = lambda t: t.reshape(-1, t.shape[-1])
     g = {"wo_ff": flat(sv["a"]).T @ flat(dout)}
     da = dout @ w["wo_ff"].T
+    if hidden_scale is not None:
+        da = da * hidden_scale
     if kind == "relu":
         du = da * (sv["u"] > 0.0)
         g["wi0"] = flat(n2).T @ flat(du)
@@ -186,6 +193,55 @@ def softmax_rows(s: np.ndarray) -> np.ndarray:
     m = np.max(s, axis=-1, keepdims=True)
     e = np.exp(s - m)
     return e / np.sum(e, axis=-1, keepdims=True)
+
+
+# --------------------------------------------------------------------------------------
+# Dropout with a counter-based generator
+# --------------------------------------------------------------------------------------
+# Sites of a block, as in the T5 models (paper Sec. 4): attention probabilities, the attention sublayer's
+# output, the feed-forward hidden activation and the feed-forward sublayer's output.
+DROP_ATTN_PROBS, DROP_ATTN_OUT, DROP_MLP_HIDDEN, DROP_MLP_OUT = 1, 2, 3, 4
+
+
+def _mix32(x: np.ndarray) -> np.ndarray:
+    """A 32-bit integer finaliser (xor-shift / odd-multiply rounds, the public-domain 'lowbias32'
+    constants) on uint64 arrays holding 32-bit values; every step is reduced mod 2^32."""
+    m = np.uint64(0xFFFFFFFF)
+    x = x & m
+    x = x ^ (x >> np.uint64(16))
+    x = (x * np.uint64(0x7FEB352D)) & m
+    x = x ^ (x >> np.uint64(15))
+    x = (x * np.uint64(0x846CA68B)) & m
+    x = x ^ (x >> np.uint64(16))
+    return x
+
+
+def dropout_keep(seed: int, site: int, n_hi: int, n_lo: int, rate: float) -> np.ndarray:
+    """Boolean keep mask [n_hi, n_lo] of a dropout site.  Element (hi, lo) is a pure function of
+    (seed, site, hi, lo) -- no state, so the forward, the backward and any tiling regenerate it:
+        k0 = mix32(seed_lo ^ (site * 0x9E3779B9 mod 2^32))
+        k1 = mix32(k0 ^ hi ^ seed_hi)            one per row
+        r  = mix32(k1 ^ lo)                      one per element
+        keep = r >= floor(rate * 2^32)
+    hi is the row (token, or (batch*heads + head)*seq + query for attention probabilities), lo the column
+    (channel, hidden unit, or key position)."""
+    m = np.uint64(0xFFFFFFFF)
+    seed_lo, seed_hi = np.uint64(seed & 0xFFFFFFFF), np.uint64((seed >> 32) & 0xFFFFFFFF)
+    k0 = _mix32(np.array([seed_lo ^ np.uint64((site * 0x9E3779B9) & 0xFFFFFFFF)], dtype=np.uint64))[0]
+    hi = np.arange(n_hi, dtype=np.uint64)[:, None]
+    lo = np.arange(n_lo, dtype=np.uint64)[None, :]
+    k1 = _mix32(k0 ^ hi ^ seed_hi)
+    r = _mix32(k1 ^ lo)
+    thr = np.uint64(min(int(math.floor(rate * 4294967296.0)), 0xFFFFFFFF))
+    return r >= thr
+
+
+def dropout_scale(cfg, site: int, n_hi: int, n_lo: int):
+    """Multiplier of a site: 1 / (1 - rate) where kept, 0 where dropped; None when dropout is off."""
+    rate = getattr(cfg, "dropout_rate", 0.0)
+    if rate <= 0.0:
+        return None
+    return dropout_keep(cfg.dropout_seed, site, n_hi, n_lo, rate) / (1.0 - rate)
 
 
 # --------------------------------------------------------------------------------------
@@ -221,13 +277,27 @@ def block_fwd(cfg, x: np.ndarray, w: dict):
         i = np.arange(cfg.seq)
         s = np.where(i[None, :] > i[:, None], -np.inf, s)
     p = softmax_rows(s)
-    o = p @ v
+    # dropout (training only; cfg.dropout_rate = 0 leaves every site untouched)
+    B, S = x.shape[0], cfg.seq
+    drop = {site: dropout_scale(cfg, site, n_hi, n_lo) for site, n_hi, n_lo in
+            ((DROP_ATTN_PROBS, B * nh * S, S), (DROP_ATTN_OUT, B * S, cfg.d_model),
+             (DROP_MLP_HIDDEN, B * S, cfg.d_ff), (DROP_MLP_OUT, B * S, cfg.d_model))}
+    if drop[DROP_ATTN_PROBS] is not None:
+        drop = {DROP_ATTN_PROBS: drop[DROP_ATTN_PROBS].reshape(B, nh, S, S),
+                DROP_ATTN_OUT: drop[DROP_ATTN_OUT].reshape(B, S, -1),
+                DROP_MLP_HIDDEN: drop[DROP_MLP_HIDDEN].reshape(B, S, -1),
+                DROP_MLP_OUT: drop[DROP_MLP_OUT].reshape(B, S, -1)}
+    on = drop[DROP_ATTN_PROBS] is not None
+    pd = p * drop[DROP_ATTN_PROBS] if on else p          # what multiplies v
+    o = pd @ v
     c = _merge_heads(o)
-    h = x + c @ w["wo"]
+    ao = c @ w["wo"]
+    h = x + (ao * drop[DROP_ATTN_OUT] if on else ao)
     n2, r2 = rmsnorm_fwd(h, w["ln2_scale"], cfg.rms_eps)
-    mlp_out, mlp_saved = mlp_fwd(cfg, n2, w)
-    y = h + mlp_out
-    saved = dict(x=x, n1=n1, r1=r1, q=q, k=k, v=v, p=p, c=c, h=h, n2=n2, r2=r2, bucket=bucket, **mlp_saved)
+    mlp_out, mlp_saved = mlp_fwd(cfg, n2, w, drop[DROP_MLP_HIDDEN])
+    y = h + (mlp_out * drop[DROP_MLP_OUT] if on else mlp_out)
+    saved = dict(x=x, n1=n1, r1=r1, q=q, k=k, v=v, p=p, pd=pd, c=c, h=h, n2=n2, r2=r2, bucket=bucket,
+                 drop=drop if on else None, **mlp_saved)
     return y, saved
 
 
@@ -238,16 +308,21 @@ def block_bwd(cfg, dy: np.ndarray, w: dict, saved: dict):
     x, n1, r1, q, k, v, p, c, h, n2, r2 = (saved[t] for t in
         ("x", "n1", "r1", "q", "k", "v", "p", "c", "h", "n2", "r2"))
     flat = lambda t: t.reshape(-1, t.shape[-1])
+    drop = saved.get("drop")
     # --- MLP
-    dn2, g = mlp_bwd(cfg, dy, n2, w, saved)
+    dout = dy * drop[DROP_MLP_OUT] if drop else dy
+    dn2, g = mlp_bwd(cfg, dout, n2, w, saved, drop[DROP_MLP_HIDDEN] if drop else None)
     dh_norm, g["ln2_scale"] = rmsnorm_bwd(h, w["ln2_scale"], r2, dn2)
     dh = dy + dh_norm
     # --- attention
-    g["wo"] = flat(c).T @ flat(dh)
-    dc = dh @ w["wo"].T
+    dao = dh * drop[DROP_ATTN_OUT] if drop else dh
+    g["wo"] = flat(c).T @ flat(dao)
+    dc = dao @ w["wo"].T
     do = _split_heads(dc, nh, dk)
-    dv = np.swapaxes(p, -1, -2) @ do
+    dv = np.swapaxes(saved["pd"], -1, -2) @ do
     dp = do @ np.swapaxes(v, -1, -2)
+    if drop:
+        dp = dp * drop[DROP_ATTN_PROBS]
     ds = p * (dp - np.sum(p * dp, axis=-1, keepdims=True))      # masked entries have p = 0 -> ds = 0
     dq = cfg.attn_scale * (ds @ k)
     dk_ = cfg.attn_scale * (np.swapaxes(ds, -1, -2) @ q)
