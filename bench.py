@@ -133,6 +133,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="record one step into a HIP graph after the warm-up and time K replays of it")
+    ap.add_argument("--dropout", type=float, default=0.0,
+                    help="dropout rate at the block's four sites (block workloads only; 0 = the paper's pre-training)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run three 1 GiB device-to-device copies (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -151,6 +153,12 @@ def main() -> int:
     sc = SI.STACK_CONFIGS.get(args.workload)
     ec = SI.ENCDEC_CONFIGS.get(args.workload)
     cfg = sc.block if sc is not None else (ec.dec_block if ec is not None else SI.CONFIGS[args.workload])
+    if args.dropout > 0.0:
+        if sc is not None or ec is not None or cfg.enc_seq > 0:
+            print("bench.py: --dropout applies to the single-block workloads without cross-attention", file=sys.stderr)
+            return 2
+        import dataclasses
+        cfg = dataclasses.replace(cfg, dropout_rate=float(np.float32(args.dropout)), dropout_seed=0x5EED5EED5EED)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     if args.calibrate_copy:
@@ -370,7 +378,7 @@ def main() -> int:
         "launch": "hip graph replay" if args.graph else "eager",
         "config": {"workload": args.workload, "batch": cfg.batch, "seq_len": cfg.seq, "d_model": cfg.d_model,
                    "n_heads": cfg.n_heads, "d_kv": cfg.d_kv, "d_ff": cfg.d_ff, "causal": cfg.causal,
-                   "enc_seq_len": cfg.enc_seq,
+                   "enc_seq_len": cfg.enc_seq, "dropout_rate": cfg.dropout_rate,
                    "adafactor": cfg.adafactor, "passes": "fwd+bwd" + ("+adafactor" if cfg.adafactor else ""),
                    **({"n_layers": sc.n_layers, "vocab": sc.vocab, "tied_logits": sc.tied_logits, "remat": sc.remat,
                        "z_loss": sc.z_loss} if sc is not None else {}),

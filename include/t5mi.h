@@ -65,6 +65,8 @@ typedef struct {
   float rms_eps;        /* 1e-6 in T5 */
   float attn_scale;     /* 1.0 = T5 convention (scale folded into the initialisation) */
   int32_t mlp_kind;     /* T5_MLP_*; 0 = the T5.1.1 gated tanh-GELU */
+  float dropout_rate;   /* 0 = none (pre-training of T5.1.1); in (0, 1): training-time dropout, see t5_dropout_keep */
+  uint32_t dropout_seed_lo, dropout_seed_hi; /* 64-bit seed; a caller changes it per step and per layer */
 } t5_block_cfg;
 
 /* Weights, device pointers, element type cfg.dtype, row-major [in, out]. */
@@ -104,6 +106,22 @@ typedef struct {
  * buckets per side -> T5_ERR_UNSUPPORTED. */
 int t5_relpos_bucket(const int32_t* rel_pos, int32_t* bucket, int64_t n, int bidirectional,
                      int num_buckets, int max_distance, void* stream);
+
+/* Dropout of the T5 models (paper Sec. 4; used when fine-tuning) at the block's four sites: attention
+ * probabilities (site 1; row = (batch*n_heads + head)*seq + query, column = key), output of the attention
+ * sublayer before the residual add (site 2; row = token, column = channel), feed-forward hidden
+ * activation (site 3; column = hidden unit) and output of the feed-forward sublayer (site 4).  Kept
+ * elements are multiplied by 1/(1 - rate).  The generator is counter-based and stateless: with
+ * mix32(x): x ^= x>>16; x *= 0x7FEB352D; x ^= x>>15; x *= 0x846CA68B; x ^= x>>16 (mod 2^32),
+ *   keep(row, col) = mix32(mix32(k0 ^ row ^ seed_hi) ^ col) >= floor(rate * 2^32),
+ *   k0 = mix32(seed_lo ^ site * 0x9E3779B9),
+ * so the forward and backward kernels regenerate the same mask from (seed, site, row, col) and nothing is
+ * stored.  t5_dropout_keep writes that mask (1 = kept) for inspection and tests: keep is device
+ * uint8 [rows, cols].  Errors: NULL -> T5_ERR_NULL; rows/cols < 0, rate outside [0, 1) -> T5_ERR_SHAPE.
+ * t5_block_fwd / t5_block_bwd apply it when cfg.dropout_rate > 0; the decoder layer and the stacks
+ * do not take dropout yet (T5_ERR_UNSUPPORTED). */
+int t5_dropout_keep(uint64_t seed, int site, float rate, int64_t rows, int64_t cols, uint8_t* keep,
+                    void* stream);
 
 /* Bytes of the saved-for-backward buffer written by t5_block_fwd and read by t5_block_bwd
  * (opaque layout), and of the scratch workspace (max over forward and backward). */

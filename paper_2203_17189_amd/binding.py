@@ -25,7 +25,8 @@ class T5Error(RuntimeError):
 class _Cfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("batch", "seq", "d_model", "n_heads", "d_kv", "d_ff", "num_buckets",
                                          "max_distance", "causal", "dtype")] + \
-               [("rms_eps", C.c_float), ("attn_scale", C.c_float), ("mlp_kind", C.c_int32)]
+               [("rms_eps", C.c_float), ("attn_scale", C.c_float), ("mlp_kind", C.c_int32),
+                ("dropout_rate", C.c_float), ("dropout_seed_lo", C.c_uint32), ("dropout_seed_hi", C.c_uint32)]
 
 
 class _Weights(C.Structure):
@@ -107,6 +108,8 @@ def lib() -> C.CDLL:
     L.t5_status_string.argtypes = [i32]
     L.t5_relpos_bucket.restype = i32
     L.t5_relpos_bucket.argtypes = [vp, vp, i64, i32, i32, i32, vp]
+    L.t5_dropout_keep.restype = i32
+    L.t5_dropout_keep.argtypes = [C.c_uint64, i32, C.c_float, i64, i64, vp, vp]
     L.t5_block_stash_bytes.restype = sz
     L.t5_block_stash_bytes.argtypes = [C.POINTER(_Cfg)]
     L.t5_block_workspace_bytes.restype = sz
@@ -167,7 +170,8 @@ def _cfg_struct(cfg) -> _Cfg:
         dt = {"f32": T5_F32, "bf16": T5_BF16}[dt]
     return _Cfg(cfg.batch, cfg.seq, cfg.d_model, cfg.n_heads, cfg.d_kv, cfg.d_ff, cfg.num_buckets,
                 cfg.max_distance, int(bool(cfg.causal)), int(dt), float(cfg.rms_eps), float(cfg.attn_scale),
-                MLP_KINDS[getattr(cfg, "mlp", "geglu_tanh")])
+                MLP_KINDS[getattr(cfg, "mlp", "geglu_tanh")], float(getattr(cfg, "dropout_rate", 0.0)),
+                int(getattr(cfg, "dropout_seed", 0)) & 0xFFFFFFFF, (int(getattr(cfg, "dropout_seed", 0)) >> 32) & 0xFFFFFFFF)
 
 
 def _torch_dtype(cfg):
@@ -198,6 +202,16 @@ def t5_relpos_bucket(rel_pos: torch.Tensor, bidirectional: bool, num_buckets: in
                                 int(num_buckets), int(max_distance), _stream())
     if rc:
         raise T5Error(rc, "t5_relpos_bucket")
+    return out
+
+
+def t5_dropout_keep(seed: int, site: int, rate: float, rows: int, cols: int) -> torch.Tensor:
+    """uint8 [rows, cols] keep mask (1 = kept) of a dropout site, as the block's kernels regenerate it."""
+    out = torch.empty(rows, cols, dtype=torch.uint8, device="cuda")
+    rc = lib().t5_dropout_keep(C.c_uint64(int(seed) & (2 ** 64 - 1)), int(site), float(rate), int(rows), int(cols),
+                               _ptr(out), _stream())
+    if rc:
+        raise T5Error(rc, "t5_dropout_keep")
     return out
 
 

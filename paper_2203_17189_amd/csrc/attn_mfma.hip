@@ -782,6 +782,7 @@ bool attn_bwd_mfma_fits(const AttnDims& a, int far) {
 }
 
 bool attn_mfma_supported(const AttnDims& a) {
+  if (a.drop.on) return false;  // dropout of the probabilities: the simple kernels
   // S, Sk % 128: query/key tiles of 128 without ragged edges; LDS holds the diagonal slice (S + 127
   // floats).  Without the bias only the unmasked form exists; bias and mask need square scores.
   if (!(a.dk == 64 || a.dk == 128) || a.S % 128 != 0 || a.Sk % 128 != 0 || a.S > 8192 || a.Sk > 65536) return false;

@@ -2,6 +2,9 @@
 // bias, or cross-attention over a second sequence without bias or mask.  Any d_kv and sequence
 // lengths, float32 or bf16 storage, float32 arithmetic.  One wavefront per query row (forward, dq)
 // or per key row (dk, dv); scores live in LDS, never in HBM.
+// With dropout of the attention probabilities (a.drop.on) the multiplier M of element
+// ((b*H + h)*S + i, j) is regenerated wherever it is needed: O = (P o M) V, dV = (P o M)^T dO,
+// dS = P o (M o (dO V^T) - rowsum(dO o O)); the softmax normaliser is that of the undropped P.
 #include "kernels.h"
 
 namespace t5mi {
@@ -53,6 +56,10 @@ __global__ __launch_bounds__(AW * 64) void attn_fwd_simple_kernel(AttnIO io, con
   l = wave_sum(l);
   if (lane == 0) lse[row] = m + __logf(l);
   const float inv_l = 1.f / l;
+  if (a.drop.on) {
+    const uint32_t k1 = drop_row_key(a.drop, (uint32_t)row);
+    for (int j = lane; j < jend; j += 64) p[j] *= drop_mult(a.drop, k1, (uint32_t)j);
+  }
   // LDS writes above are read by other lanes of the same wave below
   __builtin_amdgcn_s_waitcnt(0);
   __builtin_amdgcn_wave_barrier();
@@ -91,11 +98,13 @@ __global__ __launch_bounds__(AW * 64) void attn_bwd_dq_simple_kernel(
   if (lane == 0) dvec[row] = dsum;
   const float l = lse[row];
   const int jend = a.causal ? i + 1 : a.Sk;
+  const uint32_t k1 = drop_row_key(a.drop, (uint32_t)row);
   for (int j = lane; j < jend; j += 64) {
     float s = a.scale * dot_row(q, kbase + (size_t)j * io.ldkv, a.dk);
     if (a.bias) s += dg[j];
     const float p = __expf(s - l);
-    const float dp = dot_row(dor, vbase + (size_t)j * io.ldkv, a.dk);
+    float dp = dot_row(dor, vbase + (size_t)j * io.ldkv, a.dk);
+    if (a.drop.on) dp *= drop_mult(a.drop, k1, (uint32_t)j);
     const float d = p * (dp - dsum);
     ds[j] = d;
     if (a.bias) atomicAdd(ddg + j, d);
@@ -138,8 +147,9 @@ __global__ __launch_bounds__(AW * 64) void attn_bwd_dkv_simple_kernel(
     if (a.bias) s += dg[-i];
     const float p = __expf(s - lse[srow + i]);
     const float dp = dot_row(dobase + (size_t)i * I, vr, a.dk);
-    ps[i] = p;
-    dss[i] = p * (dp - dvec[srow + i]);
+    const float mk = a.drop.on ? drop_mult(a.drop, drop_row_key(a.drop, (uint32_t)(srow + i)), (uint32_t)j) : 1.f;
+    ps[i] = p * mk;
+    dss[i] = p * (dp * mk - dvec[srow + i]);
   }
   __builtin_amdgcn_s_waitcnt(0);
   __builtin_amdgcn_wave_barrier();

@@ -33,6 +33,16 @@ int t5_relpos_bucket(const int32_t* rel_pos, int32_t* bucket, int64_t n, int bid
   return T5_OK;
 }
 
+int t5_dropout_keep(uint64_t seed, int site, float rate, int64_t rows, int64_t cols, uint8_t* keep, void* stream) {
+  if (rows < 0 || cols < 0 || !(rate >= 0.f && rate < 1.f)) return T5_ERR_SHAPE;
+  if (rows > ((int64_t)1 << 32) || cols > ((int64_t)1 << 32)) return T5_ERR_UNSUPPORTED;
+  if (rows == 0 || cols == 0) return T5_OK;
+  if (!keep) return T5_ERR_NULL;
+  hipStream_t st = (hipStream_t)stream;
+  T5_STEP("dropout_keep", launch_dropout_keep(make_drop_site(seed, site, rate), rows, cols, keep, st));
+  return T5_OK;
+}
+
 size_t t5_block_stash_bytes(const t5_block_cfg* cfg) {
   Dims D;
   if (validate_cfg(cfg, &D, nullptr) != T5_OK) return 0;

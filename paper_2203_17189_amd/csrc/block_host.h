@@ -29,7 +29,11 @@ struct Dims {
   int mlp;    // ACT_GELU_TANH / ACT_RELU / ACT_GELU_ERF (the T5_MLP_* values)
   int Sk;     // encoder length of the cross-attention sublayer; 0: block without cross-attention
   int64_t Te; // B * Sk
+  float drop;     // dropout rate; 0: none
+  uint64_t seed;  // dropout seed
 };
+// Generator parameters of one of the block's dropout sites (off when the rate is 0).
+inline DropSite drop_site(const Dims& D, int site) { return make_drop_site(D.seed, site, D.drop); }
 
 int validate_cfg(const t5_block_cfg* c, Dims* o, RelposLut* lut, int enc_seq = 0) {
   if (!c) return T5_ERR_NULL;
@@ -39,6 +43,8 @@ int validate_cfg(const t5_block_cfg* c, Dims* o, RelposLut* lut, int enc_seq = 0
   if (c->mlp_kind != T5_MLP_GEGLU_TANH && c->mlp_kind != T5_MLP_RELU && c->mlp_kind != T5_MLP_GEGLU_ERF)
     return T5_ERR_UNSUPPORTED;
   if (!(c->rms_eps >= 0.f) || !std::isfinite(c->attn_scale)) return T5_ERR_SHAPE;
+  if (!(c->dropout_rate >= 0.f && c->dropout_rate < 1.f)) return T5_ERR_SHAPE;
+  if (c->dropout_rate > 0.f && enc_seq > 0) return T5_ERR_UNSUPPORTED;  // no sites defined for cross-attention yet
   const int64_t T = (int64_t)c->batch * c->seq;
   const int64_t Te = (int64_t)c->batch * enc_seq;
   const int64_t I = (int64_t)c->n_heads * c->d_kv;
@@ -46,6 +52,7 @@ int validate_cfg(const t5_block_cfg* c, Dims* o, RelposLut* lut, int enc_seq = 0
       c->seq > (1 << 16) || enc_seq > (1 << 16))
     return T5_ERR_UNSUPPORTED;
   if (c->d_model > 8192 || (c->d_model % 8 != 0 && c->d_model > 1024)) return T5_ERR_UNSUPPORTED;
+  if (c->dropout_rate > 0.f && T * c->n_heads > ((int64_t)1 << 32)) return T5_ERR_UNSUPPORTED;  // 32-bit row counter
   RelposLut tmp;
   const int rc = relpos_build_lut(c->causal ? 0 : 1, c->num_buckets, c->max_distance, lut ? lut : &tmp);
   if (rc != T5_OK) return rc;
@@ -56,6 +63,8 @@ int validate_cfg(const t5_block_cfg* c, Dims* o, RelposLut* lut, int enc_seq = 0
     o->es = c->dtype == T5_BF16 ? 2 : 4;
     o->Sk = enc_seq; o->Te = Te;
     o->mlp = c->mlp_kind;
+    o->drop = c->dropout_rate;
+    o->seed = ((uint64_t)c->dropout_seed_hi << 32) | c->dropout_seed_lo;
     static_assert(T5_MLP_GEGLU_TANH == ACT_GELU_TANH && T5_MLP_RELU == ACT_RELU && T5_MLP_GEGLU_ERF == ACT_GELU_ERF,
                   "the config values are the kernels' activation codes");
   }
@@ -140,6 +149,7 @@ struct BwdWs {
   // cross-attention sublayer: dh/dh_lp hold the gradient of h2, dh1/dh1_lp that of h
   float* dh1;
   void *dh1_lp, *dqx, *dkvx;  // dqx [T, I]; dkvx [Te, 2I]
+  void* dmask;                // [T, d]: a sublayer's output gradient times its dropout multiplier (dropout only)
 };
 size_t carve_bwd(const Dims& D, void* base, BwdWs* w) {
   Carver cv(base);
@@ -154,6 +164,7 @@ size_t carve_bwd(const Dims& D, void* base, BwdWs* w) {
   t.duw = cv.take((size_t)D.T * 2 * D.F * D.es);
   t.dc = cv.take((size_t)D.T * D.I * D.es);
   t.dqkv = cv.take((size_t)D.T * 3 * D.I * D.es);
+  t.dmask = cv.take(D.drop > 0.f ? (size_t)D.T * D.d * D.es : 0);
   if (D.Sk > 0) {
     t.dh1 = cv.take<float>((size_t)D.T * D.d * 4);
     t.dh1_lp = cv.take(D.ty == IN_BF16 ? (size_t)D.T * D.d * D.es : 0);
@@ -246,10 +257,10 @@ bool grads_present(const t5_block_grads* g, const Dims& D) {
 }
 
 AttnDims self_dims(const t5_block_cfg* cfg, const Dims& D) {
-  return AttnDims{D.B, D.S, D.H, D.dk, cfg->causal ? 1 : 0, cfg->attn_scale, D.S, 1};
+  return AttnDims{D.B, D.S, D.H, D.dk, cfg->causal ? 1 : 0, cfg->attn_scale, D.S, 1, drop_site(D, DROP_ATTN_PROBS)};
 }
 AttnDims cross_dims(const t5_block_cfg* cfg, const Dims& D) {
-  return AttnDims{D.B, D.S, D.H, D.dk, 0, cfg->attn_scale, D.Sk, 0};
+  return AttnDims{D.B, D.S, D.H, D.dk, 0, cfg->attn_scale, D.Sk, 0, make_drop_site(0, 0, 0.f)};
 }
 AttnIO cross_io(const Dims& D, const Stash& S, const BwdWs* W) {
   AttnIO io;
@@ -314,7 +325,7 @@ int fwd_self_attn(const t5_block_cfg* cfg, const Dims& D, const RelposLut& lut, 
   GemmDesc g = fused ? gemm1(T, D.d, D.I, S.c, D.I, 1, W.wo_t, D.I, 1, ty)
                      : gemm1(T, D.d, D.I, S.c, D.I, 1, w->wo, D.d, 0, ty);
   GemmEpi e = epi(EPI_RESID, S.h, D.d, IN_F32);
-  e.aux0 = x; e.aux_type = ty;
+  e.aux0 = x; e.aux_type = ty; e.drop = drop_site(D, DROP_ATTN_OUT);
   T5_STEP("gemm_o", run_gemm(g, e, st));
   return T5_OK;
 }
@@ -362,12 +373,12 @@ int fwd_mlp(const t5_block_cfg* cfg, const Dims& D, const float* hin, const t5_b
     GemmDesc g = fused ? gemm1(T, D.F, D.d, S.n2, D.d, 1, W.wi_t, D.d, 1, ty)
                        : gemm1(T, D.F, D.d, S.n2, D.d, 1, w->wi0, D.F, 0, ty);
     GemmEpi e = epi(EPI_STORE, S.a, D.F, ty);
-    e.act = ACT_RELU;
+    e.act = ACT_RELU; e.drop = drop_site(D, DROP_MLP_HIDDEN);
     T5_STEP("gemm_wi_relu", run_gemm(g, e, st));
   } else if (fused) {
     GemmDesc g = gemm1(T, 2 * D.F, D.d, S.n2, D.d, 1, W.wi_t, D.d, 1, ty);
     GemmEpi e = epi(EPI_GEGLU_FWD, S.gp, D.F, ty);
-    e.out1 = S.gl; e.out2 = S.a; e.act = D.mlp;
+    e.out1 = S.gl; e.out2 = S.a; e.act = D.mlp; e.drop = drop_site(D, DROP_MLP_HIDDEN);
     if (!gemm_mfma_supported(g, e)) return T5_ERR_UNSUPPORTED;
     T5_STEP("gemm_wi_geglu", launch_gemm_mfma(g, e, st));
   } else {
@@ -375,12 +386,13 @@ int fwd_mlp(const t5_block_cfg* cfg, const Dims& D, const float* hin, const t5_b
     T5_STEP("gemm_wi", run_gemm(g0, epi(EPI_STORE, S.gp, D.F, ty), st));
     GemmDesc g1 = gemm1(T, D.F, D.d, S.n2, D.d, 1, w->wi1, D.F, 0, ty);
     T5_STEP("gemm_wi", run_gemm(g1, epi(EPI_STORE, S.gl, D.F, ty), st));
-    T5_STEP("geglu_fwd", launch_geglu_fwd(S.gp, S.gl, S.a, ty, (int64_t)D.T * D.F, D.mlp, st));
+    T5_STEP("geglu_fwd", launch_geglu_fwd(S.gp, S.gl, S.a, ty, (int64_t)D.T * D.F, D.mlp,
+                                          drop_site(D, DROP_MLP_HIDDEN), D.F, st));
   }
   GemmDesc g = fused ? gemm1(T, D.d, D.F, S.a, D.F, 1, W.woff_t, D.F, 1, ty)
                      : gemm1(T, D.d, D.F, S.a, D.F, 1, w->wo_ff, D.d, 0, ty);
   GemmEpi e = epi(EPI_RESID, y, D.d, ty);
-  e.aux0 = hin; e.aux_type = IN_F32;
+  e.aux0 = hin; e.aux_type = IN_F32; e.drop = drop_site(D, DROP_MLP_OUT);
   T5_STEP("gemm_wo", run_gemm(g, e, st));
   return T5_OK;
 }
@@ -414,6 +426,11 @@ int bwd_mlp(const Dims& D, const void* dy, const float* hin, const t5_block_weig
   const size_t es = D.es;
   void* du_p = W.duw;
   void* dw_p = at(W.duw, (size_t)D.F, es);
+  const void* dy_in = dy;  // the residual branch takes dy itself, the sublayer dy times its output multiplier
+  if (D.drop > 0.f) {
+    T5_STEP("dropout_dy", launch_dropout_apply(drop_site(D, DROP_MLP_OUT), dy, W.dmask, ty, T, D.d, st));
+    dy = W.dmask;
+  }
   {  // dWo_ff = a^T dy
     GemmDesc g = gemm1(D.F, D.d, T, S.a, D.F, 0, dy, D.d, 0, ty);
     GemmEpi e = epi(EPI_SPLIT_F32, dw->wo_ff, D.d, IN_F32);
@@ -424,7 +441,7 @@ int bwd_mlp(const Dims& D, const void* dy, const float* hin, const t5_block_weig
     {  // du = (dy Wo_ff^T) where a > 0
       GemmDesc g = gemm1(T, D.F, D.d, dy, D.d, 1, w->wo_ff, D.d, 1, ty);
       GemmEpi e = epi(EPI_RESID, du_p, D.F, ty);
-      e.aux0 = S.a; e.aux_type = ty; e.aux_mask = 1;
+      e.aux0 = S.a; e.aux_type = ty; e.aux_mask = 1; e.drop = drop_site(D, DROP_MLP_HIDDEN);
       T5_STEP("gemm_da_relu_bwd", run_gemm(g, e, st));
     }
     {  // dWi0 = n2^T du
@@ -457,7 +474,7 @@ int bwd_mlp(const Dims& D, const void* dy, const float* hin, const t5_block_weig
       T5_STEP("gemm_dn2", run_gemm(g, epi(EPI_STORE, W.dn, D.d, IN_F32), st));
     }
   }
-  T5_STEP("rmsnorm_bwd", launch_rmsnorm_bwd(hin, IN_F32, w->ln2_scale, ty, S.r2, W.dn, dy, ty, W.dh,
+  T5_STEP("rmsnorm_bwd", launch_rmsnorm_bwd(hin, IN_F32, w->ln2_scale, ty, S.r2, W.dn, dy_in, ty, W.dh,
                             ty == IN_BF16 ? W.dh_lp : nullptr, ty, dw->ln2_scale, W.dg_partial, acc, T, D.d,
                             st));
   return T5_OK;
@@ -531,6 +548,10 @@ int bwd_self_attn(const t5_block_cfg* cfg, const Dims& D, const RelposLut& lut, 
   const size_t es = D.es;
   const AttnDims ad = self_dims(cfg, D);
   const void* dh_op = ty == IN_BF16 ? dh_lp : (const void*)dh;
+  if (D.drop > 0.f) {
+    T5_STEP("dropout_dh", launch_dropout_apply(drop_site(D, DROP_ATTN_OUT), dh_op, W.dmask, ty, T, D.d, st));
+    dh_op = W.dmask;
+  }
   {  // dWo = c^T dh
     GemmDesc g = gemm1(D.I, D.d, T, S.c, D.I, 0, dh_op, D.d, 0, ty);
     GemmEpi e = epi(EPI_SPLIT_F32, dw->wo, D.d, IN_F32);

@@ -88,6 +88,41 @@ __device__ __forceinline__ void gelu_both(int act, float z, float& g, float& dg)
   else gelu_tanh_both(z, g, dg);
 }
 
+// ---- dropout with a counter-based generator ----
+// A 32-bit finaliser (xor-shift / odd-multiply rounds with the public-domain "lowbias32" constants); a
+// bijection on 32 bits.  Element (hi, lo) of a dropout site is kept iff
+//   mix32(mix32(k0 ^ hi ^ seed_hi) ^ lo) >= floor(rate * 2^32),   k0 = mix32(seed_lo ^ site * 0x9E3779B9),
+// a pure function of (seed, site, hi, lo): the forward, the backward and any tiling regenerate it.
+__host__ __device__ inline uint32_t mix32(uint32_t x) {
+  x ^= x >> 16;
+  x *= 0x7FEB352Du;
+  x ^= x >> 15;
+  x *= 0x846CA68Bu;
+  x ^= x >> 16;
+  return x;
+}
+struct DropSite {
+  uint32_t k0, seed_hi, thr;
+  float scale;  // 1 / (1 - rate)
+  int on;       // rate > 0
+};
+inline DropSite make_drop_site(uint64_t seed, int site, float rate) {
+  DropSite d;
+  d.on = rate > 0.f ? 1 : 0;
+  d.k0 = mix32((uint32_t)seed ^ ((uint32_t)site * 0x9E3779B9u));
+  d.seed_hi = (uint32_t)(seed >> 32);
+  const double t = (double)(rate > 0.f ? rate : 0.f) * 4294967296.0;
+  d.thr = t >= 4294967295.0 ? 0xFFFFFFFFu : (uint32_t)t;
+  d.scale = 1.f / (1.f - (rate > 0.f ? rate : 0.f));
+  return d;
+}
+enum { DROP_ATTN_PROBS = 1, DROP_ATTN_OUT = 2, DROP_MLP_HIDDEN = 3, DROP_MLP_OUT = 4 };
+__device__ __forceinline__ uint32_t drop_row_key(const DropSite& d, uint32_t hi) { return mix32(d.k0 ^ hi ^ d.seed_hi); }
+// multiplier of element lo in the row whose key is k1: scale where kept, 0 where dropped
+__device__ __forceinline__ float drop_mult(const DropSite& d, uint32_t k1, uint32_t lo) {
+  return mix32(k1 ^ lo) >= d.thr ? d.scale : 0.f;
+}
+
 // Threshold table of the logarithmic relative-position buckets, built on the host in exact
 // integer arithmetic and passed to kernels by value.
 struct RelposLut {

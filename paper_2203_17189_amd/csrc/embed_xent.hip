@@ -239,6 +239,26 @@ __global__ void scale_vec_kernel(T* __restrict__ out, const T* __restrict__ in, 
   if (i < n) out[i] = from_f32<T>(alpha * to_f32(in[i]));
 }
 
+__global__ __launch_bounds__(256) void dropout_keep_kernel(DropSite d, int64_t rows, int64_t cols,
+                                                            uint8_t* __restrict__ out) {
+  const int64_t n = rows * cols;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const uint32_t r = (uint32_t)(i / cols), c = (uint32_t)(i % cols);
+    out[i] = drop_mult(d, drop_row_key(d, r), c) != 0.f ? 1 : 0;
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void dropout_apply_kernel(DropSite d, const T* __restrict__ in, T* __restrict__ out,
+                                                             int64_t rows, int cols) {
+  const int lane = threadIdx.x & 63;
+  for (int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); r < rows; r += (int64_t)gridDim.x * 4) {
+    const uint32_t k1 = drop_row_key(d, (uint32_t)r);
+    for (int c = lane; c < cols; c += 64)
+      out[r * cols + c] = from_f32<T>(to_f32(in[r * cols + c]) * drop_mult(d, k1, (uint32_t)c));
+  }
+}
+
 template <typename T, bool GRAD>
 hipError_t xent_dispatch(void* logits, const int32_t* targets, int64_t rows, int V, int ld, float z_loss,
                          const float* n_valid, float* loss_rows, hipStream_t st) {
@@ -297,6 +317,23 @@ hipError_t launch_xent_rows(void* logits, int type, const int32_t* targets, int6
 hipError_t launch_loss_reduce(const float* loss_rows, int64_t rows, const float* n_valid, float* loss_out,
                               hipStream_t st) {
   loss_reduce_kernel<<<1, 1024, 0, st>>>(loss_rows, rows, n_valid, loss_out);
+  return hipGetLastError();
+}
+
+hipError_t launch_dropout_keep(const DropSite& d, int64_t rows, int64_t cols, uint8_t* out, hipStream_t st) {
+  const int64_t n = rows * cols;
+  if (n <= 0) return hipSuccess;
+  dropout_keep_kernel<<<(int)std::min<int64_t>((n + 255) / 256, 65536), 256, 0, st>>>(d, rows, cols, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_dropout_apply(const DropSite& d, const void* in, void* out, int type, int64_t rows, int cols,
+                                hipStream_t st) {
+  const int grid = (int)std::min<int64_t>((rows + 3) / 4, 16384);
+  if (type == IN_BF16)
+    dropout_apply_kernel<bf16><<<grid, 256, 0, st>>>(d, (const bf16*)in, (bf16*)out, rows, cols);
+  else
+    dropout_apply_kernel<float><<<grid, 256, 0, st>>>(d, (const float*)in, (float*)out, rows, cols);
   return hipGetLastError();
 }
 

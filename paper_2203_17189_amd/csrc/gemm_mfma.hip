@@ -101,9 +101,14 @@ __device__ __forceinline__ void cursor_next(KCursor& c, const char*& abase, cons
   }
 }
 
-template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int EPI, int NS, int MINW, int BK>
+// EPI_T: the epilogue kind, plus EPI_DROP when the result passes a dropout site (a separate instantiation,
+// so that the kernels without dropout keep their register budget).
+constexpr int EPI_DROP = 8;
+template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int EPI_T, int NS, int MINW, int BK>
 __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc g, GemmEpi e, int tiles_m,
                                                                 int tiles_n, int split_k) {
+  constexpr int EPI = EPI_T & (EPI_DROP - 1);
+  constexpr bool DROP = (EPI_T & EPI_DROP) != 0;
   constexpr int NW = WM * WN;
   constexpr int TMW = BM / WM, TNW = BN / WN;
   constexpr int MI = TMW / 32, NI = TNW / 32;
@@ -371,13 +376,19 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
             const f32x4 uu = *reinterpret_cast<const f32x4*>(stg + rloc * EP_LD + pc);
             const f32x4 ww = *reinterpret_cast<const f32x4*>(stg + rloc * EP_LD + pc + 32);
             bf16x4 gpb, glb, ab;
+            f32x4 mk = {1.f, 1.f, 1.f, 1.f};
+            if constexpr (DROP) {
+              const uint32_t k1 = drop_row_key(e.drop, (uint32_t)(mh + rloc));
+#pragma unroll
+              for (int q = 0; q < 4; ++q) mk[q] = drop_mult(e.drop, k1, (uint32_t)(f + q));
+            }
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
               float gl, dgl;
               gelu_both(e.act, uu[q], gl, dgl);
-              gpb[q] = (bf16)(ww[q] * dgl);
-              glb[q] = (bf16)gl;
-              ab[q] = (bf16)(gl * ww[q]);
+              gpb[q] = (bf16)(ww[q] * dgl * mk[q]);
+              glb[q] = (bf16)(gl * mk[q]);
+              ab[q] = (bf16)(gl * ww[q] * mk[q]);
             }
             const size_t o = (size_t)(mh + rloc) * e.ld0 + f;
             st_stream(reinterpret_cast<bf16x4*>((bf16*)e.out0 + o), gpb);
@@ -468,6 +479,12 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
                 st_stream(reinterpret_cast<bf16x4*>((bf16*)e.out0 + o), du);
                 st_stream(reinterpret_cast<bf16x4*>((bf16*)e.out1 + o), dw);
               } else {  // EPI_STORE, EPI_RESID
+                f32x4 mk = {1.f, 1.f, 1.f, 1.f};
+                if constexpr (DROP) {
+                  const uint32_t k1 = drop_row_key(e.drop, (uint32_t)(mw + half * 64 + rloc));
+#pragma unroll
+                  for (int qq = 0; qq < 4; ++qq) mk[qq] = drop_mult(e.drop, k1, (uint32_t)(nw + c4 + qq));
+                }
                 if constexpr (EPI == EPI_RESID) {
                   f32x4 ax;
                   if (aux_f32) {
@@ -477,16 +494,21 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
                     for (int qq = 0; qq < 4; ++qq) ax[qq] = (float)xa[set][q][qq];
                   }
                   if (e.aux_mask) {
+                    const float sc = DROP ? e.drop.scale : 1.f;
 #pragma unroll
-                    for (int qq = 0; qq < 4; ++qq) v[qq] = ax[qq] > 0.f ? v[qq] : 0.f;
+                    for (int qq = 0; qq < 4; ++qq) v[qq] = ax[qq] > 0.f ? v[qq] * sc : 0.f;
                   } else {
 #pragma unroll
-                    for (int qq = 0; qq < 4; ++qq) v[qq] += ax[qq];
+                    for (int qq = 0; qq < 4; ++qq) v[qq] = fmaf(v[qq], mk[qq], ax[qq]);
                   }
                 } else {
                   if (e.act == ACT_RELU) {
 #pragma unroll
                     for (int qq = 0; qq < 4; ++qq) v[qq] = fmaxf(v[qq], 0.f);
+                  }
+                  if constexpr (DROP) {
+#pragma unroll
+                    for (int qq = 0; qq < 4; ++qq) v[qq] *= mk[qq];
                   }
                 }
                 if (e.out_type == IN_BF16) {
@@ -525,9 +547,10 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
           float gl, dgl;
           gelu_both(e.act, uu, gl, dgl);
           const size_t o = (size_t)m * e.ld0 + f;
-          ((bf16*)e.out0)[o] = (bf16)(ww * dgl);
-          ((bf16*)e.out1)[o] = (bf16)gl;
-          ((bf16*)e.out2)[o] = (bf16)(gl * ww);
+          const float mk = DROP ? drop_mult(e.drop, drop_row_key(e.drop, (uint32_t)m), (uint32_t)f) : 1.f;
+          ((bf16*)e.out0)[o] = (bf16)(ww * dgl * mk);
+          ((bf16*)e.out1)[o] = (bf16)(gl * mk);
+          ((bf16*)e.out2)[o] = (bf16)(gl * ww * mk);
         }
       } else {
 #pragma unroll
@@ -536,13 +559,17 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
           if (n >= g.N) continue;
           float v = acc[i][j][r];
           const size_t o = (size_t)m * e.ld0 + n;
+          float mk = 1.f;
+          if constexpr (EPI == EPI_STORE || EPI == EPI_RESID)
+            if constexpr (DROP) mk = drop_mult(e.drop, drop_row_key(e.drop, (uint32_t)m), (uint32_t)n);
           if constexpr (EPI == EPI_STORE) {
             if (e.act == ACT_RELU) v = fmaxf(v, 0.f);
+            v *= mk;
             if (e.out_type == IN_BF16) ((bf16*)e.out0)[o] = (bf16)v; else ((float*)e.out0)[o] = v;
           } else if constexpr (EPI == EPI_RESID) {
             const size_t oa = (size_t)m * (e.ld_aux ? e.ld_aux : e.ld0) + n;
             const float a = e.aux_type == IN_BF16 ? (float)((const bf16*)e.aux0)[oa] : ((const float*)e.aux0)[oa];
-            const float r = e.aux_mask ? (a > 0.f ? v : 0.f) : v + a;
+            const float r = e.aux_mask ? (a > 0.f ? v * (DROP ? e.drop.scale : 1.f) : 0.f) : fmaf(v, mk, a);
             if (e.out_type == IN_BF16) ((bf16*)e.out0)[o] = (bf16)r; else ((float*)e.out0)[o] = r;
           } else if constexpr (EPI == EPI_GEGLU_BWD) {
             const size_t oa = (size_t)m * (e.ld_aux ? e.ld_aux : e.ld0) + n;
@@ -587,8 +614,9 @@ hipError_t launch_cfg(const GemmDesc& g, const GemmEpi& e, int split_k, hipStrea
   return hipGetLastError();
 }
 
-template <bool A_KC, bool B_KC, int EPI>
+template <bool A_KC, bool B_KC, int EPI_T>
 hipError_t launch_layout(const GemmDesc& g, const GemmEpi& e, hipStream_t st) {
+  constexpr int EPI = EPI_T & (EPI_DROP - 1);
   int nk = 0;
   for (int s = 0; s < g.nseg; ++s) nk += g.seg[s].K / KQ;
   const int64_t t256 = (int64_t)ceil_div(g.M, 256) * ceil_div(g.N, 256);
@@ -627,20 +655,22 @@ hipError_t launch_layout(const GemmDesc& g, const GemmEpi& e, hipStream_t st) {
     // residual epilogues into a narrow output (N < 1024: T5.1.1-Small/Base widths), measured per shape:
     // K <= 512 as below (256x128), 128x128 tiles for K up to 768 (-6..15 % at N = 768), 256x256 beyond
     // (-4..9 %)
-    if (EPI == EPI_RESID && g.N < 1024 && nk > 8) {
-      if (nk <= 12) return launch_cfg<128, 128, 2, 2, A_KC, B_KC, EPI, 4, 1>(g, e, split_k, st);
-      return launch_cfg<256, 256, 2, 2, A_KC, B_KC, EPI, 5, 1>(g, e, split_k, st);
+    if (EPI_T == EPI_RESID && g.N < 1024 && nk > 8) {
+      if (nk <= 12) return launch_cfg<128, 128, 2, 2, A_KC, B_KC, EPI_T, 4, 1>(g, e, split_k, st);
+      return launch_cfg<256, 256, 2, 2, A_KC, B_KC, EPI_T, 5, 1>(g, e, split_k, st);
     }
+    // the residual epilogue with dropout does not fit the 256x256 tile's register budget (it would spill)
+    if (EPI_T == (EPI_RESID | EPI_DROP)) return launch_cfg<256, 128, 2, 2, A_KC, B_KC, EPI_T, 3, 2>(g, e, split_k, st);
     if (EPI != EPI_SPLIT_F32 && (nk <= 16 || (EPI == EPI_GEGLU_FWD && nk < 24) || EPI == EPI_GEGLU_BWD ||
                                  (EPI == EPI_RESID && nk <= 32)))
-      return launch_cfg<256, 128, 2, 2, A_KC, B_KC, EPI, 3, 2>(g, e, split_k, st);
-    return launch_cfg<256, 256, 2, 2, A_KC, B_KC, EPI, 5, 1>(g, e, split_k, st);
+      return launch_cfg<256, 128, 2, 2, A_KC, B_KC, EPI_T, 3, 2>(g, e, split_k, st);
+    return launch_cfg<256, 256, 2, 2, A_KC, B_KC, EPI_T, 5, 1>(g, e, split_k, st);
   }
   // too few 256x256 tiles to fill the chip, but a long reduction: 256x128 tiles, two per compute unit
   // (8192 x 768 x 32128: -11 % against 128x128)
   if (EPI != EPI_SPLIT_F32 && t256 >= 64 && nk >= 64)
-    return launch_cfg<256, 128, 2, 2, A_KC, B_KC, EPI, 3, 2>(g, e, split_k, st);
-  return launch_cfg<128, 128, 2, 2, A_KC, B_KC, EPI, 4, 1>(g, e, split_k, st);
+    return launch_cfg<256, 128, 2, 2, A_KC, B_KC, EPI_T, 3, 2>(g, e, split_k, st);
+  return launch_cfg<128, 128, 2, 2, A_KC, B_KC, EPI_T, 4, 1>(g, e, split_k, st);
 }
 
 }  // namespace
@@ -674,9 +704,15 @@ bool gemm_mfma_supported(const GemmDesc& g, const GemmEpi& e) {
 
 hipError_t launch_gemm_mfma(const GemmDesc& g, const GemmEpi& e, hipStream_t st) {
   switch (e.kind) {
-    case EPI_STORE: return launch_layout<true, true, EPI_STORE>(g, e, st);
-    case EPI_RESID: return launch_layout<true, true, EPI_RESID>(g, e, st);
-    case EPI_GEGLU_FWD: return launch_layout<true, true, EPI_GEGLU_FWD>(g, e, st);
+    case EPI_STORE:
+      return e.drop.on ? launch_layout<true, true, EPI_STORE | EPI_DROP>(g, e, st)
+                       : launch_layout<true, true, EPI_STORE>(g, e, st);
+    case EPI_RESID:
+      return e.drop.on ? launch_layout<true, true, EPI_RESID | EPI_DROP>(g, e, st)
+                       : launch_layout<true, true, EPI_RESID>(g, e, st);
+    case EPI_GEGLU_FWD:
+      return e.drop.on ? launch_layout<true, true, EPI_GEGLU_FWD | EPI_DROP>(g, e, st)
+                       : launch_layout<true, true, EPI_GEGLU_FWD>(g, e, st);
     case EPI_GEGLU_BWD: return launch_layout<true, true, EPI_GEGLU_BWD>(g, e, st);
     case EPI_SPLIT_F32: return launch_layout<false, false, EPI_SPLIT_F32>(g, e, st);
     default: return hipErrorInvalidValue;

@@ -81,13 +81,15 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(GemmDesc g, GemmEpi e)
       if (n >= g.N) continue;
       const float v = acc[i][j];
       const size_t o = (size_t)m * e.ld0 + n;
+      const float mk = e.drop.on ? drop_mult(e.drop, drop_row_key(e.drop, (uint32_t)m), (uint32_t)n) : 1.f;
       switch (e.kind) {
         case EPI_STORE:
-          st_elem(e.out0, o, e.out_type, e.act == ACT_RELU ? fmaxf(v, 0.f) : v);
+          st_elem(e.out0, o, e.out_type, (e.act == ACT_RELU ? fmaxf(v, 0.f) : v) * mk);
           break;
         case EPI_RESID: {
           const float a = ld_elem(e.aux0, (size_t)m * (e.ld_aux ? e.ld_aux : e.ld0) + n, e.aux_type);
-          st_elem(e.out0, o, e.out_type, e.aux_mask ? (a > 0.f ? v : 0.f) : v + a);
+          const float sc = e.drop.on ? e.drop.scale : 1.f;
+          st_elem(e.out0, o, e.out_type, e.aux_mask ? (a > 0.f ? v * sc : 0.f) : v * mk + a);
           break;
         }
         case EPI_GEGLU_BWD: {
@@ -112,16 +114,19 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(GemmDesc g, GemmEpi e)
 }
 
 template <typename T>
-__global__ void geglu_fwd_kernel(T* __restrict__ u, T* __restrict__ w, T* __restrict__ a, int64_t n, int act) {
+__global__ void geglu_fwd_kernel(T* __restrict__ u, T* __restrict__ w, T* __restrict__ a, int64_t n, int act,
+                                 DropSite drop, int cols) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (; i < n; i += stride) {
     const float uu = to_f32(u[i]), ww = to_f32(w[i]);
     float gl, dgl;
     gelu_both(act, uu, gl, dgl);
-    a[i] = from_f32<T>(gl * ww);
-    u[i] = from_f32<T>(ww * dgl);
-    w[i] = from_f32<T>(gl);
+    // the saved factors carry the dropout multiplier of the hidden activation, for the backward
+    const float mk = drop.on ? drop_mult(drop, drop_row_key(drop, (uint32_t)(i / cols)), (uint32_t)(i % cols)) : 1.f;
+    a[i] = from_f32<T>(gl * ww * mk);
+    u[i] = from_f32<T>(ww * dgl * mk);
+    w[i] = from_f32<T>(gl * mk);
   }
 }
 
@@ -184,13 +189,14 @@ hipError_t launch_zero_f32(const ZeroList& z, hipStream_t st) {
   return hipGetLastError();
 }
 
-hipError_t launch_geglu_fwd(void* u, void* w, void* a, int type, int64_t n, int act, hipStream_t st) {
+hipError_t launch_geglu_fwd(void* u, void* w, void* a, int type, int64_t n, int act, const DropSite& drop, int cols,
+                            hipStream_t st) {
   int64_t blocks = (n + 255) / 256;
   if (blocks > 65536) blocks = 65536;
   if (type == IN_BF16)
-    geglu_fwd_kernel<bf16><<<(int)blocks, 256, 0, st>>>((bf16*)u, (bf16*)w, (bf16*)a, n, act);
+    geglu_fwd_kernel<bf16><<<(int)blocks, 256, 0, st>>>((bf16*)u, (bf16*)w, (bf16*)a, n, act, drop, cols);
   else
-    geglu_fwd_kernel<float><<<(int)blocks, 256, 0, st>>>((float*)u, (float*)w, (float*)a, n, act);
+    geglu_fwd_kernel<float><<<(int)blocks, 256, 0, st>>>((float*)u, (float*)w, (float*)a, n, act, drop, cols);
   return hipGetLastError();
 }
 

@@ -63,6 +63,11 @@ struct GemmEpi {
   int accumulate;
   int act;       // EPI_STORE: ACT_RELU stores max(acc, 0); EPI_GEGLU_FWD: ACT_GELU_TANH or ACT_GELU_ERF
   int aux_mask;  // EPI_RESID: != 0 stores acc where aux0 > 0 and 0 elsewhere instead of acc + aux0
+  // Dropout of the GEMM's result (row = m, column = n; for EPI_GEGLU_FWD column = hidden unit), when drop.on:
+  // EPI_RESID stores aux0 + acc * M; EPI_STORE stores act(acc) * M; EPI_GEGLU_FWD multiplies all three
+  // outputs by M (so that the saved factors already carry the mask for the backward); with aux_mask
+  // the kept value is acc * drop.scale (aux0 is then a masked, rescaled activation).
+  DropSite drop;
 };
 struct GemmDesc {
   int M, N, nseg;
@@ -106,7 +111,9 @@ hipError_t launch_pack_transpose_multi(const PackJobs& jobs, hipStream_t st);
 
 // ------------------------------------------------------------------ elementwise gated GELU (simple path)
 // a = gelu(u) * w; then overwrites u with w * gelu'(u) and w with gelu(u) (the saved backward factors).
-hipError_t launch_geglu_fwd(void* u, void* w, void* a, int type, int64_t n, int act, hipStream_t st);
+// With drop.on all three also carry the dropout multiplier of element (i / cols, i % cols).
+hipError_t launch_geglu_fwd(void* u, void* w, void* a, int type, int64_t n, int act, const DropSite& drop, int cols,
+                            hipStream_t st);
 
 // ------------------------------------------------------------------ attention
 // Queries: S per batch element; keys/values: Sk per batch element (Sk == S for self-attention).
@@ -117,6 +124,7 @@ struct AttnDims {
   float scale;
   int Sk;
   int bias;
+  DropSite drop;  // dropout of the probabilities; row = (b*H + h)*S + i, column = j
 };
 // Operand placement.  Row (b*S + i) of q / dq starts at q + row*ldq, row (b*Sk + j) of k, v / dk, dv at
 // k + row*ldkv; head h occupies channels h*dk .. h*dk + dk - 1 of a row.  Element counts, not bytes.
@@ -176,6 +184,14 @@ hipError_t launch_loss_reduce(const float* loss_rows, int64_t rows, const float*
 // out = (accumulate ? out : 0) + alpha * in (float32);  out = alpha * in (storage type)
 hipError_t launch_axpy_f32(float* out, const float* in, float alpha, int n, int accumulate, hipStream_t st);
 hipError_t launch_scale_vec(void* out, const void* in, float alpha, int n, int type, hipStream_t st);
+
+// ------------------------------------------------------------------ dropout
+// out[r * cols + c] = 1 where element (r, c) of the site is kept, 0 where dropped (uint8).
+hipError_t launch_dropout_keep(const DropSite& d, int64_t rows, int64_t cols, uint8_t* out, hipStream_t st);
+// out[r, c] = in[r, c] * multiplier(r, c) (storage type): the masked, rescaled copy of a gradient that
+// feeds the GEMMs of a dropped sublayer output.
+hipError_t launch_dropout_apply(const DropSite& d, const void* in, void* out, int type, int64_t rows, int cols,
+                                hipStream_t st);
 
 // ------------------------------------------------------------------ measurement aid
 // Register-only MFMA loop: each of the 4 waves of a workgroup issues iters * 32 v_mfma_f32_32x32x16_bf16.

@@ -271,6 +271,7 @@ int plan_stack(const t5_stack_cfg* c, StackPlan* p) {
   if (!c) return T5_ERR_NULL;
   int rc = validate_cfg(&c->block, &p->S.D, &p->S.lut);
   if (rc != T5_OK) return rc;
+  if (c->block.dropout_rate > 0.f) return T5_ERR_UNSUPPORTED;  // the stacks do not derive per-layer seeds yet
   if ((rc = validate_ends(c->n_layers, c->vocab, c->z_loss)) != T5_OK) return rc;
   p->S.bc = &c->block; p->S.L = c->n_layers; p->S.remat = c->remat != 0; p->S.fused = fused_fwd_ok(p->S.D);
   p->H.V = c->vocab; p->H.tied = c->tied_logits != 0; p->H.z_loss = c->z_loss;
@@ -302,6 +303,7 @@ int plan_encdec(const t5_encdec_cfg* c, EncDecPlan* p) {
   if (e.batch != d.batch || e.d_model != d.d_model || e.dtype != d.dtype) return T5_ERR_SHAPE;
   int rc = validate_cfg(&e, &p->E.D, &p->E.lut);
   if (rc != T5_OK) return rc;
+  if (e.dropout_rate > 0.f || d.dropout_rate > 0.f) return T5_ERR_UNSUPPORTED;
   if ((rc = validate_cfg(&d, &p->Dc.D, &p->Dc.lut, e.seq)) != T5_OK) return rc;
   if ((rc = validate_ends(c->n_enc_layers, c->vocab, c->z_loss)) != T5_OK) return rc;
   if ((rc = validate_ends(c->n_dec_layers, c->vocab, c->z_loss)) != T5_OK) return rc;

@@ -43,6 +43,16 @@ def relu_aware(cfg, tol):
     return TOL_BF16_RELU_GRAD if getattr(cfg, "mlp", "") == "relu" and cfg.dtype == "bf16" else tol
 
 
+def drop_tol(tol, rate: float, backward: bool):
+    """bf16 bounds of a block with dropout at rate p.  A sublayer's output f carries the bf16 rounding error
+    eps * rms(f); the kept elements (a fraction 1 - p) are multiplied by 1 / (1 - p), so the error that reaches
+    the residual stream has RMS eps * rms(f) / sqrt(1 - p) while the exact skip term is unchanged: forward
+    bounds grow by at most (1 - p)^-1/2.  In the backward the gradient passes the same multiplier once more
+    and meets operands that already carry the forward factor: (1 - p)^-1."""
+    f = (1.0 - rate) ** (-1.0 if backward else -0.5)
+    return tol[0] * f, tol[1] * f
+
+
 def stack_bf16_tol(n_layers: int):
     """Weight-gradient bound of an n_layers-deep bf16 stack.  The gradient that reaches a layer has
     crossed the bf16-rounded operands of every layer above it (and the activations those of every
