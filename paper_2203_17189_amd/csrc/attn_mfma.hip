@@ -10,6 +10,12 @@
 // operands use the same permutation, and the V^T operand is fetched with that permutation by the
 // LDS transpose load.  The dk/dv kernel mirrors this with one key per lane (S = Q K^T).
 //
+// Dropout of the probabilities (DROP; self-attention only): the keep decision of element
+// ((b*H + h)*S + i, j) is regenerated from the counter-based generator where P is formed -- the lane
+// that owns a query (forward, dq) hashes its row key once, the dk/dv kernel stages the row keys of a
+// query tile in LDS beside -lse and -dvec.  The factor 1/(1 - rate) of the kept probabilities is applied
+// to the finished O and dV accumulators, and to dP before dvec is subtracted.
+//
 // The bias is Toeplitz: bias[h,i,j] = diag[h][j - i + S - 1].  Each workgroup stages the slice of
 // the per-head diagonal vector it can touch (S + tile - 1 floats) in LDS.
 #include "kernels.h"
@@ -174,7 +180,7 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // ------------------------------------------------------------------------------------------------
 // Forward.  grid (ceil(S/128), H, B), 256 threads; wave w owns queries i0 + 32w + lane%32.
 // ------------------------------------------------------------------------------------------------
-template <int DK, bool CAUSAL, bool BIAS>
+template <int DK, bool CAUSAL, bool BIAS, bool DROP>
 __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnIO io, const float* __restrict__ diag,
                                                             bf16* __restrict__ c, float* __restrict__ lse,
                                                             AttnDims a) {
@@ -212,6 +218,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnIO io, const 
   }
   const float sc = a.scale * kLog2e;
   const int dg_base = BR - 1 - i_loc;  // dg[dg_base + j] = bias(j - i)
+  uint32_t k1 = 0;  // dropout row key of this lane's query
+  if constexpr (DROP) k1 = drop_row_key(a.drop, (uint32_t)(((size_t)b * a.H + h) * S + i_ld));
 
   f32x16 oT[CT];
 #pragma unroll
@@ -287,8 +295,13 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnIO io, const 
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const float p = fast_exp2(sT[kt][r] - m_new);
-        sT[kt][r] = p;
-        ls += p;
+        ls += p;  // the normaliser is that of the undropped probabilities
+        if constexpr (DROP) {
+          const int j = j0 + kt * 32 + ((r >> 2) << 3) + (g << 2) + (r & 3);
+          sT[kt][r] = mix32(k1 ^ (uint32_t)j) >= a.drop.thr ? p : 0.f;
+        } else {
+          sT[kt][r] = p;
+        }
       }
     l = l * alpha + ls;
 #pragma unroll
@@ -308,7 +321,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnIO io, const 
   }
   const float l_tot = l + __shfl_xor(l, 32, 64);
   if (i < S) {
-    const float inv = 1.f / l_tot;
+    const float inv = (DROP ? a.drop.scale : 1.f) / l_tot;
     bf16* crow = c + ((size_t)b * S + i) * I + h * DK;
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct)
@@ -366,8 +379,8 @@ __global__ __launch_bounds__(256) void attn_dvec_kernel(const bf16* __restrict__
 // every offset lies in the saturated last bucket (|delta| >= far) skip all that and add into one
 // scalar per lane; it is credited to the outermost diagonal, which is in the same bucket.
 // ------------------------------------------------------------------------------------------------
-template <int DK, bool CAUSAL, bool BIAS>
-__global__ __launch_bounds__(256, DK == 64 ? 3 : 2) void attn_bwd_dq_mfma_kernel(AttnIO io,
+template <int DK, bool CAUSAL, bool BIAS, bool DROP>
+__global__ __launch_bounds__(256, DK == 64 && !DROP ? 3 : 2) void attn_bwd_dq_mfma_kernel(AttnIO io,
                                                                const bf16* __restrict__ dout,
                                                                const float* __restrict__ diag,
                                                                const float* __restrict__ lse,
@@ -412,6 +425,13 @@ __global__ __launch_bounds__(256, DK == 64 ? 3 : 2) void attn_bwd_dq_mfma_kernel
   }
   const size_t srow = ((size_t)b * a.H + h) * S + i;
   const float nlse2 = -lse[srow] * kLog2e, ndv = -dvec[srow];
+  uint32_t k1 = 0;  // dropout row key of this lane's query
+  if constexpr (DROP) k1 = drop_row_key(a.drop, (uint32_t)srow);
+  // dP of a kept probability carries the factor 1/(1 - rate); that of a dropped one is zero
+  auto dp_masked = [&](float dp, int j) {
+    if constexpr (DROP) return mix32(k1 ^ (uint32_t)j) >= a.drop.thr ? dp * a.drop.scale : 0.f;
+    else return dp;
+  };
   if constexpr (BIAS) {
     const float* dgh = diag + (size_t)h * (2 * S - 1);
     fill_bias_slice(dg, dgh, S + BR - 1, tid, [&](int t) { return t - (i0 + BR - 1) + (S - 1); });
@@ -471,13 +491,14 @@ __global__ __launch_bounds__(256, DK == 64 ? 3 : 2) void attn_bwd_dq_mfma_kernel
           const int j = j0s + ((r >> 2) << 3) + (g << 2) + (r & 3);
           float p = BIAS ? fast_exp2(fmaf(sT[r], sc, bias[r]) + nlse2) : fast_exp2(fmaf(sT[r], sc, nlse2));
           if (j > i) p = 0.f;
-          sT[r] = p * (dpT[r] + ndv);
+          sT[r] = p * (dp_masked(dpT[r], j) + ndv);
         }
       } else {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
+          const int j = j0s + ((r >> 2) << 3) + (g << 2) + (r & 3);
           const float p = BIAS ? fast_exp2(fmaf(sT[r], sc, bias[r]) + nlse2) : fast_exp2(fmaf(sT[r], sc, nlse2));
-          sT[r] = p * (dpT[r] + ndv);
+          sT[r] = p * (dp_masked(dpT[r], j) + ndv);
         }
       }
       // ---- bias gradient of this 32x32 sub-tile (wave-uniform branches)
@@ -550,7 +571,7 @@ __global__ __launch_bounds__(256, DK == 64 ? 3 : 2) void attn_bwd_dq_mfma_kernel
 // ------------------------------------------------------------------------------------------------
 // dk and dv.  grid (Sk/128) * H * B; wave w owns keys j0 + 32w + lane%32; loops over query tiles.
 // ------------------------------------------------------------------------------------------------
-template <int DK, bool CAUSAL, bool BIAS>
+template <int DK, bool CAUSAL, bool BIAS, bool DROP>
 __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kernel(AttnIO io,
                                                                 const bf16* __restrict__ dout,
                                                                 const float* __restrict__ diag,
@@ -564,7 +585,8 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
   // already (s - lse/scale) and (dP - dvec): no per-element subtraction afterwards.
   float* lse_all = reinterpret_cast<float*>(smem + 2 * STG);  // [2 stages][BQ]  -lse / scale
   float* dv_all = lse_all + 2 * BQ;                           // [2 stages][BQ]  -dvec
-  float* dg = dv_all + 2 * BQ;                                // [S + BCK - 1] log2 units (BIAS only)
+  uint32_t* key_all = reinterpret_cast<uint32_t*>(dv_all + 2 * BQ);  // [2 stages][BQ] dropout row keys (DROP only)
+  float* dg = dv_all + 2 * BQ + (DROP ? 2 * BQ : 0);          // [S + BCK - 1] log2 units (BIAS only)
 
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -620,12 +642,14 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
   if (tid < BQ) {
     lse_all[tid] = lse[srow + it_begin * BQ + tid] * neg_inv_scale;
     dv_all[tid] = -dvec[srow + it_begin * BQ + tid];
+    if constexpr (DROP) key_all[tid] = drop_row_key(a.drop, (uint32_t)(srow + it_begin * BQ + tid));
   }
   for (int it = it_begin; it < n_it; ++it) {
     const int q0 = it * BQ;
     const int st = (it - it_begin) & 1;
     dma_wait_barrier();  // tile `it` landed, its lse/dvec slice is written; other stage is free
     float nl = 0.f, nd = 0.f;
+    uint32_t nkey = 0;
     const bool more = it + 1 < n_it;
     if (more) {
       const uint32_t nxt = lds0 + (st ^ 1) * STG;
@@ -634,12 +658,14 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
       if (tid < BQ) {
         nl = lse[srow + q0 + BQ + tid] * neg_inv_scale;
         nd = -dvec[srow + q0 + BQ + tid];
+        if constexpr (DROP) nkey = drop_row_key(a.drop, (uint32_t)(srow + q0 + BQ + tid));
       }
     }
     const char* Qt = smem + st * STG;
     const char* Dt = Qt + TILE;
     const float* lse_s = lse_all + st * BQ;
     const float* dv_s = dv_all + st * BQ;
+    const uint32_t* key_s = key_all + st * BQ;
 #pragma unroll
     for (int qb = 0; qb < BQ / 32; ++qb) {
       // bias values and accumulator seeds are requested before the MFMAs so that their LDS latency
@@ -659,7 +685,8 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
         const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_s + qb * 32 + rq * 8 + g * 4);
         const f32x4 d4 = *reinterpret_cast<const f32x4*>(dv_s + qb * 32 + rq * 8 + g * 4);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) { s[rq * 4 + e] = l4[e]; dp[rq * 4 + e] = d4[e]; }
+        // with dropout dP is rescaled before dvec is subtracted: it starts from zero
+        for (int e = 0; e < 4; ++e) { s[rq * 4 + e] = l4[e]; dp[rq * 4 + e] = DROP ? 0.f : d4[e]; }
       }
       if constexpr (HOIST) __builtin_amdgcn_sched_group_barrier(0x100, 12, 0);  // 8 bias + 4 seed reads first
 #pragma unroll
@@ -675,8 +702,14 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
           const int i = q0 + il;
           float p = BIAS ? fast_exp2(fmaf(s[r], sc, HOIST ? bias[r] : dg[j_loc + (S - 1 - i)])) : fast_exp2(s[r] * sc);
           if (j > i) p = 0.f;
-          s[r] = p;
-          dp[r] = p * dp[r];
+          if constexpr (DROP) {
+            const bool keep = mix32(key_s[il] ^ (uint32_t)j) >= a.drop.thr;
+            s[r] = keep ? p : 0.f;
+            dp[r] = p * ((keep ? dp[r] * a.drop.scale : 0.f) + dv_s[il]);
+          } else {
+            s[r] = p;
+            dp[r] = p * dp[r];
+          }
         }
       } else {
 #pragma unroll
@@ -684,8 +717,14 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
           const int il = qb * 32 + ((r >> 2) << 3) + (g << 2) + (r & 3);
           const int i = q0 + il;
           const float p = BIAS ? fast_exp2(fmaf(s[r], sc, HOIST ? bias[r] : dg[j_loc + (S - 1 - i)])) : fast_exp2(s[r] * sc);
-          s[r] = p;
-          dp[r] = p * dp[r];
+          if constexpr (DROP) {
+            const bool keep = mix32(key_s[il] ^ (uint32_t)j) >= a.drop.thr;
+            s[r] = keep ? p : 0.f;
+            dp[r] = p * ((keep ? dp[r] * a.drop.scale : 0.f) + dv_s[il]);
+          } else {
+            s[r] = p;
+            dp[r] = p * dp[r];
+          }
         }
       }
 #pragma unroll
@@ -703,6 +742,7 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
     if (more && tid < BQ) {
       lse_all[(st ^ 1) * BQ + tid] = nl;
       dv_all[(st ^ 1) * BQ + tid] = nd;
+      if constexpr (DROP) key_all[(st ^ 1) * BQ + tid] = nkey;
     }
   }
   if (j < Sk) {
@@ -716,7 +756,7 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           ok[e] = (bf16)(dkT[ct][rq * 4 + e] * a.scale);
-          ov[e] = (bf16)dvT[ct][rq * 4 + e];
+          ov[e] = (bf16)(DROP ? dvT[ct][rq * 4 + e] * a.drop.scale : dvT[ct][rq * 4 + e]);
         }
         *reinterpret_cast<bf16x4*>(krow + ct * 32 + rq * 8 + g * 4) = ok;
         *reinterpret_cast<bf16x4*>(vrow + ct * 32 + rq * 8 + g * 4) = ov;
@@ -735,9 +775,9 @@ hipError_t set_lds(K kern, size_t bytes) {
   return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
-template <int DK, bool CAUSAL, bool BIAS>
+template <int DK, bool CAUSAL, bool BIAS, bool DROP = false>
 hipError_t fwd_launch(const AttnIO& io, const float* diag, void* c, float* lse, const AttnDims& a, hipStream_t st) {
-  auto kern = attn_fwd_mfma_kernel<DK, CAUSAL, BIAS>;
+  auto kern = attn_fwd_mfma_kernel<DK, CAUSAL, BIAS, DROP>;
   const size_t lds = 4 * 64 * DK * 2 + (BIAS ? sizeof(float) * (a.S + 127) : 0);
   hipError_t e = set_lds(kern, lds);
   if (e != hipSuccess) return e;
@@ -745,7 +785,7 @@ hipError_t fwd_launch(const AttnIO& io, const float* diag, void* c, float* lse, 
   return hipGetLastError();
 }
 
-template <int DK, bool CAUSAL, bool BIAS>
+template <int DK, bool CAUSAL, bool BIAS, bool DROP = false>
 hipError_t bwd_launch(const AttnIO& io, const void* c, const void* dc, const float* diag, const float* lse,
                       float* dvec, float* ddiag, const AttnDims& a, int far, int phase, hipStream_t st) {
   hipError_t e = hipSuccess;
@@ -755,15 +795,15 @@ hipError_t bwd_launch(const AttnIO& io, const void* c, const void* dc, const flo
     return hipGetLastError();
   }
   if (phase == 1) {
-    auto kern = attn_bwd_dq_mfma_kernel<DK, CAUSAL, BIAS>;
+    auto kern = attn_bwd_dq_mfma_kernel<DK, CAUSAL, BIAS, DROP>;
     const size_t lds = attn_bwd_dq_lds_bytes(a, far);
     if ((e = set_lds(kern, lds)) != hipSuccess) return e;
     kern<<<dim3((a.S / 128) * a.H * a.B), 256, lds, st>>>(io, (const bf16*)dc, diag, lse, dvec, ddiag, a, far);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (phase == 2) {
-    auto kern = attn_bwd_dkv_mfma_kernel<DK, CAUSAL, BIAS>;
-    const size_t lds = 4 * 64 * DK * 2 + sizeof(float) * (256 + (BIAS ? a.S + 127 : 0));
+    auto kern = attn_bwd_dkv_mfma_kernel<DK, CAUSAL, BIAS, DROP>;
+    const size_t lds = 4 * 64 * DK * 2 + sizeof(float) * (256 + (DROP ? 128 : 0) + (BIAS ? a.S + 127 : 0));
     if ((e = set_lds(kern, lds)) != hipSuccess) return e;
     kern<<<dim3((a.Sk / 128) * a.H * a.B), 256, lds, st>>>(io, (const bf16*)dc, diag, lse, dvec, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -782,7 +822,7 @@ bool attn_bwd_mfma_fits(const AttnDims& a, int far) {
 }
 
 bool attn_mfma_supported(const AttnDims& a) {
-  if (a.drop.on) return false;  // dropout of the probabilities: the simple kernels
+  if (a.drop.on && !a.bias) return false;  // dropout of the probabilities: self-attention only
   // S, Sk % 128: query/key tiles of 128 without ragged edges; LDS holds the diagonal slice (S + 127
   // floats).  Without the bias only the unmasked form exists; bias and mask need square scores.
   if (!(a.dk == 64 || a.dk == 128) || a.S % 128 != 0 || a.Sk % 128 != 0 || a.S > 8192 || a.Sk > 65536) return false;
@@ -794,6 +834,13 @@ hipError_t launch_attn_fwd_mfma(const AttnIO& io, const float* diag, void* c, fl
                                 hipStream_t st) {
   if (!attn_mfma_supported(a)) return hipErrorInvalidValue;
   const int mode = attn_mode(a);
+  if (a.drop.on) {
+    if (a.dk == 64)
+      return mode == 0 ? fwd_launch<64, false, true, true>(io, diag, c, lse, a, st)
+                       : fwd_launch<64, true, true, true>(io, diag, c, lse, a, st);
+    return mode == 0 ? fwd_launch<128, false, true, true>(io, diag, c, lse, a, st)
+                     : fwd_launch<128, true, true, true>(io, diag, c, lse, a, st);
+  }
   if (a.dk == 64) {
     if (mode == 0) return fwd_launch<64, false, true>(io, diag, c, lse, a, st);
     if (mode == 1) return fwd_launch<64, true, true>(io, diag, c, lse, a, st);
@@ -813,6 +860,13 @@ hipError_t launch_attn_bwd_mfma(const AttnIO& io, const void* c, const void* dc,
   if (!attn_mfma_supported(a)) return hipErrorInvalidValue;
   if (far < 1) far = 1;
   const int mode = attn_mode(a);
+  if (a.drop.on) {
+    if (a.dk == 64)
+      return mode == 0 ? bwd_launch<64, false, true, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st)
+                       : bwd_launch<64, true, true, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
+    return mode == 0 ? bwd_launch<128, false, true, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st)
+                     : bwd_launch<128, true, true, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
+  }
   if (a.dk == 64) {
     if (mode == 0) return bwd_launch<64, false, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
     if (mode == 1) return bwd_launch<64, true, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);

@@ -110,3 +110,59 @@ def test_block_dropout_bf16(cfg):
         e = rel_err(gg[name], g[name])
         tol = drop_tol(TOL_BF16_DW, p, True) if name == "wo_ff" else tol_dw
         assert e[0] <= tol[0] and e[1] <= tol[1], (name, e)
+
+
+# ------------------------------------------------------------------ workload shapes (matrix-unit kernels)
+def _named(name, b):
+    cfg = SI.CONFIGS[name]
+    return replace(cfg, attn_scale=cfg.d_kv ** -0.5, dropout_rate=RATE, dropout_seed=SEED + 5).with_batch(b)
+
+
+@pytest.mark.parametrize("name,b0", [("c3_base", 2), ("c4_gpt_causal", 1)])
+def test_config_dropout_reduced_batch(name, b0):
+    """Full sequence length, widths and heads of a workload at a reduced batch (sequences are independent
+    through the block): several query and key tiles per head in the fused attention kernels."""
+    from parity_util import TOL_BF16_DW_NAMED, TOL_BF16_DX_NAMED
+    cfg = _named(name, b0)
+    w, x, dy = make_case(cfg)
+    y, saved = O.block_fwd(cfg, x, w)
+    dx, g = O.block_bwd(cfg, dy, w, saved)
+    gy, gdx, gg = run_block_gpu(cfg, w, x, dy)
+    ey, edx = rel_err(gy, y), rel_err(gdx, dx)
+    print(name, "y", ey, "dx", edx, {k: tuple(round(v, 5) for v in rel_err(gg[k], g[k])) for k in g})
+    tol_y, tol_dx = drop_tol(TOL_BF16_ACT, RATE, False), drop_tol(TOL_BF16_DX_NAMED, RATE, True)
+    tol_dw = drop_tol(TOL_BF16_DW_NAMED, RATE, True)
+    assert ey[0] <= tol_y[0] and ey[1] <= tol_y[1], ("y", ey)
+    assert edx[0] <= tol_dx[0] and edx[1] <= tol_dx[1], ("dx", edx)
+    for k in g:
+        e = rel_err(gg[k], g[k])
+        assert e[0] <= tol_dw[0] and e[1] <= tol_dw[1], (k, e)
+
+
+def test_dropout_full_batch_sampled():
+    """c2_small at its full batch with dropout, as bench.py --dropout launches it: the first 2 sequences of y
+    and dx against the oracle (the masks of a sequence depend on its own batch index only), and
+    run-to-run determinism."""
+    from parity_util import TOL_BF16_DX_NAMED, to_dev, to_np
+    P = _P()
+    cfg = _named("c2_small", SI.CONFIGS["c2_small"].batch)
+    b0 = 2
+    w = SI.make_weights(cfg)
+    x, dy = SI.make_activations(cfg)
+    small = cfg.with_batch(b0)
+    y, saved = O.block_fwd(small, x[:b0], w)
+    dx, _ = O.block_bwd(small, dy[:b0], w, saved)
+    dw = {k: to_dev(v, cfg.dtype) for k, v in w.items()}
+    tx, tdy = to_dev(x, cfg.dtype), to_dev(dy, cfg.dtype)
+    gy, stash = P.t5_block_fwd(cfg, tx, dw)
+    gdx, gg = P.t5_block_bwd(cfg, tdy, tx, dw, stash)
+    gy2, stash2 = P.t5_block_fwd(cfg, tx, dw)
+    gdx2, _ = P.t5_block_bwd(cfg, tdy, tx, dw, stash2)
+    torch.cuda.synchronize()
+    ey, edx = rel_err(to_np(gy[:b0]), y), rel_err(to_np(gdx[:b0]), dx)
+    print("full batch sample with dropout: y", ey, "dx", edx)
+    tol_y, tol_dx = drop_tol(TOL_BF16_ACT, RATE, False), drop_tol(TOL_BF16_DX_NAMED, RATE, True)
+    assert ey[0] <= tol_y[0] and ey[1] <= tol_y[1], ey
+    assert edx[0] <= tol_dx[0] and edx[1] <= tol_dx[1], edx
+    assert torch.equal(gy, gy2) and torch.equal(gdx, gdx2)
+    assert all(torch.isfinite(v).all() for v in gg.values())
