@@ -238,3 +238,26 @@ def test_gemm_validation():
     assert lib.t5_gemm_bf16(None, dummy, dummy, 64, 64, 64, 64, 64, 64, 1, 1, None) == 1
     assert lib.t5_gemm_bf16(dummy, dummy, dummy, 64, 64, 72, 72, 72, 64, 1, 1, None) == 3   # K % 64
     assert lib.t5_gemm_bf16(dummy, dummy, dummy, 64, 64, 64, 64, 64, 64, 1, 0, None) == 3   # mixed layouts
+
+
+def test_dropout_validation():
+    lib = P.lib()
+    dummy = C.c_void_p(4096)
+    w = B._Weights(*([4096] * 10))
+    keep = lambda seed, site, rate, rows, cols, out: lib.t5_dropout_keep(C.c_uint64(seed), site, C.c_float(rate), rows,
+                                                                         cols, out, None)
+    assert keep(1, 1, 0.1, 0, 16, None) == 0            # nothing to write
+    assert keep(1, 1, 0.1, 4, 4, None) == 1
+    assert keep(1, 1, 1.0, 4, 4, dummy) == 2
+    assert keep(1, 1, -0.5, 4, 4, dummy) == 2
+    assert keep(1, 1, float("nan"), 4, 4, dummy) == 2
+    assert keep(1, 1, 0.1, -1, 4, dummy) == 2
+    for rate in (1.0, -0.25, float("nan")):
+        bad = B._cfg_struct(SI.CONFIGS["c1_tiny_f32"])
+        bad.dropout_rate = rate
+        assert lib.t5_block_fwd(C.byref(bad), dummy, C.byref(w), dummy, dummy, dummy, 1 << 30, None) == 2
+    # the backward of a block with dropout needs room for the masked gradient copy
+    from dataclasses import replace
+    c1 = SI.CONFIGS["c1_tiny_f32"]
+    assert P.t5_block_workspace_bytes(replace(c1, dropout_rate=0.5)) >= P.t5_block_workspace_bytes(c1)
+    assert P.t5_block_stash_bytes(replace(c1, dropout_rate=0.5)) == P.t5_block_stash_bytes(c1)   # no mask is stored
