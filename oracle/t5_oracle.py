@@ -35,6 +35,7 @@ All functions take and return float64 arrays.
 """
 from __future__ import annotations
 
+import dataclasses
 import math
 import numpy as np
 
@@ -201,6 +202,9 @@ def softmax_rows(s: np.ndarray) -> np.ndarray:
 # Sites of a block, as in the T5 models (paper Sec. 4): attention probabilities, the attention sublayer's
 # output, the feed-forward hidden activation and the feed-forward sublayer's output.
 DROP_ATTN_PROBS, DROP_ATTN_OUT, DROP_MLP_HIDDEN, DROP_MLP_OUT = 1, 2, 3, 4
+# the cross-attention sublayer of a decoder layer, and the two ends of a stack (embedded tokens; output of the
+# final norm); the decoder side of an encoder-decoder pair has its own end sites
+DROP_CROSS_PROBS, DROP_CROSS_OUT, DROP_EMBED, DROP_FINAL, DROP_DEC_EMBED, DROP_DEC_FINAL = 5, 6, 7, 8, 9, 10
 
 
 def _mix32(x: np.ndarray) -> np.ndarray:
@@ -234,6 +238,25 @@ def dropout_keep(seed: int, site: int, n_hi: int, n_lo: int, rate: float) -> np.
     r = _mix32(k1 ^ lo)
     thr = np.uint64(min(int(math.floor(rate * 4294967296.0)), 0xFFFFFFFF))
     return r >= thr
+
+
+def dropout_layer_seed(seed: int, layer: int) -> int:
+    """Seed of layer `layer` (0-based) of a stack whose configuration carries `seed`: the layers must not
+    share masks, so each adds a multiple of an odd 64-bit constant (mod 2^64).  The decoder layers of an
+    encoder-decoder pair count on from the encoder's."""
+    return (seed + (layer + 1) * 0x9E3779B97F4A7C15) & 0xFFFFFFFFFFFFFFFF
+
+
+def _with_layer_seed(cfg, layer: int):
+    if getattr(cfg, "dropout_rate", 0.0) <= 0.0:
+        return cfg
+    return dataclasses.replace(cfg, dropout_seed=dropout_layer_seed(cfg.dropout_seed, layer))
+
+
+def _token_scale(cfg, site: int, shape):
+    """Multiplier of a per-token site for activations of shape [B, S, width]; 1.0 when dropout is off."""
+    m = dropout_scale(cfg, site, shape[0] * shape[1], shape[2])
+    return 1.0 if m is None else m.reshape(shape)
 
 
 def dropout_scale(cfg, site: int, n_hi: int, n_lo: int):
@@ -371,22 +394,36 @@ def decoder_block_fwd(cfg, x: np.ndarray, enc: np.ndarray, w: dict):
         i = np.arange(cfg.seq)
         s = np.where(i[None, :] > i[:, None], -np.inf, s)
     p = softmax_rows(s)
-    c = _merge_heads(p @ v)
-    h1 = x + c @ w["wo"]
+    # dropout: the block's four sites plus the two of the cross-attention sublayer (rows of its probabilities:
+    # (b*H + h)*S + i over the S decoder positions, columns: encoder positions)
+    B, S, Se = x.shape[0], cfg.seq, enc.shape[1]
+    drop = None
+    if getattr(cfg, "dropout_rate", 0.0) > 0.0:
+        drop = {DROP_ATTN_PROBS: dropout_scale(cfg, DROP_ATTN_PROBS, B * nh * S, S).reshape(B, nh, S, S),
+                DROP_ATTN_OUT: dropout_scale(cfg, DROP_ATTN_OUT, B * S, cfg.d_model).reshape(B, S, -1),
+                DROP_CROSS_PROBS: dropout_scale(cfg, DROP_CROSS_PROBS, B * nh * S, Se).reshape(B, nh, S, Se),
+                DROP_CROSS_OUT: dropout_scale(cfg, DROP_CROSS_OUT, B * S, cfg.d_model).reshape(B, S, -1),
+                DROP_MLP_HIDDEN: dropout_scale(cfg, DROP_MLP_HIDDEN, B * S, cfg.d_ff).reshape(B, S, -1),
+                DROP_MLP_OUT: dropout_scale(cfg, DROP_MLP_OUT, B * S, cfg.d_model).reshape(B, S, -1)}
+    one = lambda site: drop[site] if drop else 1.0
+    pd = p * one(DROP_ATTN_PROBS)
+    c = _merge_heads(pd @ v)
+    h1 = x + (c @ w["wo"]) * one(DROP_ATTN_OUT)
     # --- cross-attention sublayer
     nx, rx = rmsnorm_fwd(h1, w["lnx_scale"], cfg.rms_eps)
     qx = _split_heads(nx @ w["xq"], nh, dk)
     kx = _split_heads(enc @ w["xk"], nh, dk)
     vx = _split_heads(enc @ w["xv"], nh, dk)
     px = softmax_rows(cfg.attn_scale * (qx @ np.swapaxes(kx, -1, -2)))
-    cx = _merge_heads(px @ vx)
-    h2 = h1 + cx @ w["xo"]
+    pxd = px * one(DROP_CROSS_PROBS)
+    cx = _merge_heads(pxd @ vx)
+    h2 = h1 + (cx @ w["xo"]) * one(DROP_CROSS_OUT)
     # --- MLP sublayer
     n2, r2 = rmsnorm_fwd(h2, w["ln2_scale"], cfg.rms_eps)
-    mlp_out, mlp_saved = mlp_fwd(cfg, n2, w)
-    y = h2 + mlp_out
-    saved = dict(x=x, enc=enc, n1=n1, r1=r1, q=q, k=k, v=v, p=p, c=c, h1=h1, nx=nx, rx=rx, qx=qx, kx=kx, vx=vx,
-                 px=px, cx=cx, h2=h2, n2=n2, r2=r2, bucket=bucket, **mlp_saved)
+    mlp_out, mlp_saved = mlp_fwd(cfg, n2, w, drop[DROP_MLP_HIDDEN] if drop else None)
+    y = h2 + mlp_out * one(DROP_MLP_OUT)
+    saved = dict(x=x, enc=enc, n1=n1, r1=r1, q=q, k=k, v=v, p=p, pd=pd, c=c, h1=h1, nx=nx, rx=rx, qx=qx, kx=kx,
+                 vx=vx, px=px, pxd=pxd, cx=cx, h2=h2, n2=n2, r2=r2, bucket=bucket, drop=drop, **mlp_saved)
     return y, saved
 
 
@@ -395,16 +432,19 @@ def decoder_block_bwd(cfg, dy: np.ndarray, w: dict, saved: dict):
     nh, dk = cfg.n_heads, cfg.d_kv
     flat = lambda t: t.reshape(-1, t.shape[-1])
     sv = saved
+    drop = sv.get("drop")
+    one = lambda site: drop[site] if drop else 1.0
     # --- MLP sublayer
-    dn2, g = mlp_bwd(cfg, dy, sv["n2"], w, sv)
+    dn2, g = mlp_bwd(cfg, dy * one(DROP_MLP_OUT), sv["n2"], w, sv, drop[DROP_MLP_HIDDEN] if drop else None)
     dh2_norm, g["ln2_scale"] = rmsnorm_bwd(sv["h2"], w["ln2_scale"], sv["r2"], dn2)
     dh2 = dy + dh2_norm
     # --- cross-attention sublayer
-    g["xo"] = flat(sv["cx"]).T @ flat(dh2)
-    dox = _split_heads(dh2 @ w["xo"].T, nh, dk)
+    dxo = dh2 * one(DROP_CROSS_OUT)
+    g["xo"] = flat(sv["cx"]).T @ flat(dxo)
+    dox = _split_heads(dxo @ w["xo"].T, nh, dk)
     px, qx, kx, vx = sv["px"], sv["qx"], sv["kx"], sv["vx"]
-    dvx = np.swapaxes(px, -1, -2) @ dox
-    dpx = dox @ np.swapaxes(vx, -1, -2)
+    dvx = np.swapaxes(sv["pxd"], -1, -2) @ dox
+    dpx = (dox @ np.swapaxes(vx, -1, -2)) * one(DROP_CROSS_PROBS)
     dsx = px * (dpx - np.sum(px * dpx, axis=-1, keepdims=True))
     dqx = _merge_heads(cfg.attn_scale * (dsx @ kx))
     dkx = _merge_heads(cfg.attn_scale * (np.swapaxes(dsx, -1, -2) @ qx))
@@ -416,11 +456,12 @@ def decoder_block_bwd(cfg, dy: np.ndarray, w: dict, saved: dict):
     dh1_norm, g["lnx_scale"] = rmsnorm_bwd(sv["h1"], w["lnx_scale"], sv["rx"], dqx @ w["xq"].T)
     dh1 = dh2 + dh1_norm
     # --- self-attention sublayer
-    g["wo"] = flat(sv["c"]).T @ flat(dh1)
-    do = _split_heads(dh1 @ w["wo"].T, nh, dk)
+    dao = dh1 * one(DROP_ATTN_OUT)
+    g["wo"] = flat(sv["c"]).T @ flat(dao)
+    do = _split_heads(dao @ w["wo"].T, nh, dk)
     p, q, k, v = sv["p"], sv["q"], sv["k"], sv["v"]
-    dv = np.swapaxes(p, -1, -2) @ do
-    dp = do @ np.swapaxes(v, -1, -2)
+    dv = np.swapaxes(sv["pd"], -1, -2) @ do
+    dp = (do @ np.swapaxes(v, -1, -2)) * one(DROP_ATTN_PROBS)
     ds = p * (dp - np.sum(p * dp, axis=-1, keepdims=True))
     dq = cfg.attn_scale * (ds @ k)
     dk_ = cfg.attn_scale * (np.swapaxes(ds, -1, -2) @ q)
@@ -470,22 +511,28 @@ def stack_loss(sc, tokens: np.ndarray, targets: np.ndarray, w: dict):
         x_0 = E[tokens];  x_{l+1} = block_l(x_l)  with ONE relative-position table shared by all layers
         nf = RMSNorm(x_L; gf);  logits = nf Wout   (tied: logits = d_model^-1/2 nf E^T)
         loss = mean over positions with target >= 0 of xent_zloss
+    With dropout (block.dropout_rate > 0): layer l runs with the seed dropout_layer_seed(seed, l), the embedded
+    tokens pass site DROP_EMBED and the output of the final norm site DROP_FINAL (both under the stack's seed).
     Returns (loss, saved)."""
     cfg = sc.block
     x = w["embedding"][tokens]
+    m_embed = _token_scale(cfg, DROP_EMBED, x.shape)
+    x = x * m_embed
     saved_layers = []
-    for lw in w["layers"]:
+    for l, lw in enumerate(w["layers"]):
         wl = dict(lw, rel_table=w["rel_table"])
-        x, sv = block_fwd(cfg, x, wl)
+        x, sv = block_fwd(_with_layer_seed(cfg, l), x, wl)
         saved_layers.append(sv)
     nf, rf = rmsnorm_fwd(x, w["final_scale"], cfg.rms_eps)
+    m_final = _token_scale(cfg, DROP_FINAL, nf.shape)
+    nf = nf * m_final                                    # what the logits see
     if sc.tied_logits:
         logits = (nf * cfg.d_model ** -0.5) @ w["embedding"].T
     else:
         logits = nf @ w["logits_w"]
     loss, lse, n = xent_zloss(logits, targets, sc.z_loss)
     return loss, dict(tokens=tokens, targets=targets, layers=saved_layers, x_last=x, nf=nf, rf=rf, logits=logits,
-                      lse=lse, n=n)
+                      lse=lse, n=n, m_embed=m_embed, m_final=m_final)
 
 
 def stack_loss_grad(sc, w: dict, saved: dict) -> dict:
@@ -502,14 +549,14 @@ def stack_loss_grad(sc, w: dict, saved: dict) -> dict:
     else:
         g["logits_w"] = flat(saved["nf"]).T @ flat(dlogits)
         dnf = dlogits @ w["logits_w"].T
-    dx, g["final_scale"] = rmsnorm_bwd(saved["x_last"], w["final_scale"], saved["rf"], dnf)
+    dx, g["final_scale"] = rmsnorm_bwd(saved["x_last"], w["final_scale"], saved["rf"], dnf * saved["m_final"])
     g["rel_table"] = np.zeros_like(w["rel_table"])
     for l in range(sc.n_layers - 1, -1, -1):
         wl = dict(w["layers"][l], rel_table=w["rel_table"])
-        dx, gl = block_bwd(cfg, dx, wl, saved["layers"][l])
+        dx, gl = block_bwd(_with_layer_seed(cfg, l), dx, wl, saved["layers"][l])
         g["rel_table"] += gl.pop("rel_table")
         g["layers"][l] = gl
-    np.add.at(g["embedding"], saved["tokens"].reshape(-1), flat(dx))
+    np.add.at(g["embedding"], saved["tokens"].reshape(-1), flat(dx * saved["m_embed"]))
     return g
 
 
@@ -518,21 +565,34 @@ def encdec_loss(ec, enc_tokens: np.ndarray, dec_tokens: np.ndarray, targets: np.
         enc_out = RMSNorm(encoder blocks(E[enc_tokens]); enc_final_scale)    bidirectional, own shared table
         x_{l+1} = decoder_block_l(x_l, enc_out),  x_0 = E[dec_tokens]        causal, own shared table
         nf = RMSNorm(x_L; dec_final_scale);  logits, loss as in stack_loss
+    With dropout each side takes rate and seed from its own block configuration: encoder layer l runs with
+    dropout_layer_seed(seed, l), decoder layer l with dropout_layer_seed(seed, n_enc_layers + l); the encoder's
+    ends are sites DROP_EMBED / DROP_FINAL (enc_out is the dropped norm output), the decoder's
+    DROP_DEC_EMBED / DROP_DEC_FINAL.
     Returns (loss, saved)."""
     e, d = ec.enc_block, ec.dec_block
     x = w["embedding"][enc_tokens]
+    me_embed = _token_scale(e, DROP_EMBED, x.shape)
+    x = x * me_embed
     enc_saved = []
-    for lw in w["enc_layers"]:
-        x, sv = block_fwd(e, x, dict(lw, rel_table=w["enc_rel_table"]))
+    for l, lw in enumerate(w["enc_layers"]):
+        x, sv = block_fwd(_with_layer_seed(e, l), x, dict(lw, rel_table=w["enc_rel_table"]))
         enc_saved.append(sv)
     enc_out, enc_rf = rmsnorm_fwd(x, w["enc_final_scale"], e.rms_eps)
+    me_final = _token_scale(e, DROP_FINAL, enc_out.shape)
+    enc_out = enc_out * me_final
     xe_last = x
     x = w["embedding"][dec_tokens]
+    md_embed = _token_scale(d, DROP_DEC_EMBED, x.shape)
+    x = x * md_embed
     dec_saved = []
-    for lw in w["dec_layers"]:
-        x, sv = decoder_block_fwd(d, x, enc_out, dict(lw, rel_table=w["dec_rel_table"]))
+    for l, lw in enumerate(w["dec_layers"]):
+        x, sv = decoder_block_fwd(_with_layer_seed(d, ec.n_enc_layers + l), x, enc_out,
+                                  dict(lw, rel_table=w["dec_rel_table"]))
         dec_saved.append(sv)
     nf, rf = rmsnorm_fwd(x, w["dec_final_scale"], d.rms_eps)
+    md_final = _token_scale(d, DROP_DEC_FINAL, nf.shape)
+    nf = nf * md_final
     if ec.tied_logits:
         logits = (nf * d.d_model ** -0.5) @ w["embedding"].T
     else:
@@ -540,7 +600,7 @@ def encdec_loss(ec, enc_tokens: np.ndarray, dec_tokens: np.ndarray, targets: np.
     loss, lse, n = xent_zloss(logits, targets, ec.z_loss)
     return loss, dict(enc_tokens=enc_tokens, dec_tokens=dec_tokens, targets=targets, enc_layers=enc_saved,
                       dec_layers=dec_saved, xe_last=xe_last, enc_rf=enc_rf, x_last=x, nf=nf, rf=rf, logits=logits,
-                      lse=lse, n=n)
+                      lse=lse, n=n, masks=(me_embed, me_final, md_embed, md_final))
 
 
 def encdec_loss_grad(ec, w: dict, saved: dict) -> dict:
@@ -557,24 +617,26 @@ def encdec_loss_grad(ec, w: dict, saved: dict) -> dict:
     else:
         g["logits_w"] = flat(saved["nf"]).T @ flat(dlogits)
         dnf = dlogits @ w["logits_w"].T
-    dx, g["dec_final_scale"] = rmsnorm_bwd(saved["x_last"], w["dec_final_scale"], saved["rf"], dnf)
+    me_embed, me_final, md_embed, md_final = saved["masks"]
+    dx, g["dec_final_scale"] = rmsnorm_bwd(saved["x_last"], w["dec_final_scale"], saved["rf"], dnf * md_final)
     g["dec_rel_table"] = np.zeros_like(w["dec_rel_table"])
     denc_out = 0.0
     for l in range(ec.n_dec_layers - 1, -1, -1):
         wl = dict(w["dec_layers"][l], rel_table=w["dec_rel_table"])
-        dx, denc_l, gl = decoder_block_bwd(d, dx, wl, saved["dec_layers"][l])
+        dx, denc_l, gl = decoder_block_bwd(_with_layer_seed(d, ec.n_enc_layers + l), dx, wl, saved["dec_layers"][l])
         denc_out = denc_out + denc_l
         g["dec_rel_table"] += gl.pop("rel_table")
         g["dec_layers"][l] = gl
-    np.add.at(g["embedding"], saved["dec_tokens"].reshape(-1), flat(dx))
-    dx, g["enc_final_scale"] = rmsnorm_bwd(saved["xe_last"], w["enc_final_scale"], saved["enc_rf"], denc_out)
+    np.add.at(g["embedding"], saved["dec_tokens"].reshape(-1), flat(dx * md_embed))
+    dx, g["enc_final_scale"] = rmsnorm_bwd(saved["xe_last"], w["enc_final_scale"], saved["enc_rf"],
+                                           denc_out * me_final)
     g["enc_rel_table"] = np.zeros_like(w["enc_rel_table"])
     for l in range(ec.n_enc_layers - 1, -1, -1):
         wl = dict(w["enc_layers"][l], rel_table=w["enc_rel_table"])
-        dx, gl = block_bwd(e, dx, wl, saved["enc_layers"][l])
+        dx, gl = block_bwd(_with_layer_seed(e, l), dx, wl, saved["enc_layers"][l])
         g["enc_rel_table"] += gl.pop("rel_table")
         g["enc_layers"][l] = gl
-    np.add.at(g["embedding"], saved["enc_tokens"].reshape(-1), flat(dx))
+    np.add.at(g["embedding"], saved["enc_tokens"].reshape(-1), flat(dx * me_embed))
     return g
 
 
