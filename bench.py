@@ -134,7 +134,7 @@ def main() -> int:
     ap.add_argument("--graph", action="store_true",
                     help="record one step into a HIP graph after the warm-up and time K replays of it")
     ap.add_argument("--dropout", type=float, default=0.0,
-                    help="dropout rate at the block's four sites (block workloads only; 0 = the paper's pre-training)")
+                    help="dropout rate at every site of the workload (0 = the paper's pre-training recipe)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run three 1 GiB device-to-device copies (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -154,11 +154,13 @@ def main() -> int:
     ec = SI.ENCDEC_CONFIGS.get(args.workload)
     cfg = sc.block if sc is not None else (ec.dec_block if ec is not None else SI.CONFIGS[args.workload])
     if args.dropout > 0.0:
-        if sc is not None or ec is not None or cfg.enc_seq > 0:
-            print("bench.py: --dropout applies to the single-block workloads without cross-attention", file=sys.stderr)
-            return 2
         import dataclasses
-        cfg = dataclasses.replace(cfg, dropout_rate=float(np.float32(args.dropout)), dropout_seed=0x5EED5EED5EED)
+        drop = lambda c: dataclasses.replace(c, dropout_rate=float(np.float32(args.dropout)), dropout_seed=0x5EED5EED5EED)
+        if sc is not None:
+            sc = dataclasses.replace(sc, block=drop(sc.block))
+        if ec is not None:
+            ec = dataclasses.replace(ec, enc_block=drop(ec.enc_block), dec_block=drop(ec.dec_block))
+        cfg = sc.block if sc is not None else (ec.dec_block if ec is not None else drop(cfg))
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     if args.calibrate_copy:

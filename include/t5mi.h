@@ -118,8 +118,13 @@ int t5_relpos_bucket(const int32_t* rel_pos, int32_t* bucket, int64_t n, int bid
  * so the forward and backward kernels regenerate the same mask from (seed, site, row, col) and nothing is
  * stored.  t5_dropout_keep writes that mask (1 = kept) for inspection and tests: keep is device
  * uint8 [rows, cols].  Errors: NULL -> T5_ERR_NULL; rows/cols < 0, rate outside [0, 1) -> T5_ERR_SHAPE.
- * t5_block_fwd / t5_block_bwd apply it when cfg.dropout_rate > 0; the decoder layer and the stacks
- * do not take dropout yet (T5_ERR_UNSUPPORTED). */
+ * Every entry point applies it when its block configuration has dropout_rate > 0.  The decoder layer adds
+ * site 5 (cross-attention probabilities; row = (batch*n_heads + head)*seq + query, column = encoder
+ * position) and site 6 (output of the cross-attention sublayer).  A stack runs layer l (0-based) with the
+ * seed  seed + (l + 1) * 0x9E3779B97F4A7C15 (mod 2^64)  and applies site 7 to the embedded tokens and site
+ * 8 to the output of the final norm, both under the configuration's own seed; in the encoder-decoder pair
+ * each side takes rate and seed from its block configuration, the decoder's layers count on from the
+ * encoder's (l = n_enc_layers + index), and the decoder's ends are sites 9 and 10. */
 int t5_dropout_keep(uint64_t seed, int site, float rate, int64_t rows, int64_t cols, uint8_t* keep,
                     void* stream);
 

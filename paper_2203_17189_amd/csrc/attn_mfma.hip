@@ -10,7 +10,7 @@
 // operands use the same permutation, and the V^T operand is fetched with that permutation by the
 // LDS transpose load.  The dk/dv kernel mirrors this with one key per lane (S = Q K^T).
 //
-// Dropout of the probabilities (DROP; self-attention only): the keep decision of element
+// Dropout of the probabilities (DROP): the keep decision of element
 // ((b*H + h)*S + i, j) is regenerated from the counter-based generator where P is formed -- the lane
 // that owns a query (forward, dq) hashes its row key once, the dk/dv kernel stages the row keys of a
 // query tile in LDS beside -lse and -dvec.  The factor 1/(1 - rate) of the kept probabilities is applied
@@ -822,7 +822,6 @@ bool attn_bwd_mfma_fits(const AttnDims& a, int far) {
 }
 
 bool attn_mfma_supported(const AttnDims& a) {
-  if (a.drop.on && !a.bias) return false;  // dropout of the probabilities: self-attention only
   // S, Sk % 128: query/key tiles of 128 without ragged edges; LDS holds the diagonal slice (S + 127
   // floats).  Without the bias only the unmasked form exists; bias and mask need square scores.
   if (!(a.dk == 64 || a.dk == 128) || a.S % 128 != 0 || a.Sk % 128 != 0 || a.S > 8192 || a.Sk > 65536) return false;
@@ -835,11 +834,14 @@ hipError_t launch_attn_fwd_mfma(const AttnIO& io, const float* diag, void* c, fl
   if (!attn_mfma_supported(a)) return hipErrorInvalidValue;
   const int mode = attn_mode(a);
   if (a.drop.on) {
-    if (a.dk == 64)
-      return mode == 0 ? fwd_launch<64, false, true, true>(io, diag, c, lse, a, st)
-                       : fwd_launch<64, true, true, true>(io, diag, c, lse, a, st);
-    return mode == 0 ? fwd_launch<128, false, true, true>(io, diag, c, lse, a, st)
-                     : fwd_launch<128, true, true, true>(io, diag, c, lse, a, st);
+    if (a.dk == 64) {
+      if (mode == 0) return fwd_launch<64, false, true, true>(io, diag, c, lse, a, st);
+      if (mode == 1) return fwd_launch<64, true, true, true>(io, diag, c, lse, a, st);
+      return fwd_launch<64, false, false, true>(io, diag, c, lse, a, st);
+    }
+    if (mode == 0) return fwd_launch<128, false, true, true>(io, diag, c, lse, a, st);
+    if (mode == 1) return fwd_launch<128, true, true, true>(io, diag, c, lse, a, st);
+    return fwd_launch<128, false, false, true>(io, diag, c, lse, a, st);
   }
   if (a.dk == 64) {
     if (mode == 0) return fwd_launch<64, false, true>(io, diag, c, lse, a, st);
@@ -861,11 +863,14 @@ hipError_t launch_attn_bwd_mfma(const AttnIO& io, const void* c, const void* dc,
   if (far < 1) far = 1;
   const int mode = attn_mode(a);
   if (a.drop.on) {
-    if (a.dk == 64)
-      return mode == 0 ? bwd_launch<64, false, true, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st)
-                       : bwd_launch<64, true, true, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
-    return mode == 0 ? bwd_launch<128, false, true, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st)
-                     : bwd_launch<128, true, true, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
+    if (a.dk == 64) {
+      if (mode == 0) return bwd_launch<64, false, true, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
+      if (mode == 1) return bwd_launch<64, true, true, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
+      return bwd_launch<64, false, false, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
+    }
+    if (mode == 0) return bwd_launch<128, false, true, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
+    if (mode == 1) return bwd_launch<128, true, true, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
+    return bwd_launch<128, false, false, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
   }
   if (a.dk == 64) {
     if (mode == 0) return bwd_launch<64, false, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);

@@ -44,7 +44,6 @@ int validate_cfg(const t5_block_cfg* c, Dims* o, RelposLut* lut, int enc_seq = 0
     return T5_ERR_UNSUPPORTED;
   if (!(c->rms_eps >= 0.f) || !std::isfinite(c->attn_scale)) return T5_ERR_SHAPE;
   if (!(c->dropout_rate >= 0.f && c->dropout_rate < 1.f)) return T5_ERR_SHAPE;
-  if (c->dropout_rate > 0.f && enc_seq > 0) return T5_ERR_UNSUPPORTED;  // no sites defined for cross-attention yet
   const int64_t T = (int64_t)c->batch * c->seq;
   const int64_t Te = (int64_t)c->batch * enc_seq;
   const int64_t I = (int64_t)c->n_heads * c->d_kv;
@@ -260,7 +259,7 @@ AttnDims self_dims(const t5_block_cfg* cfg, const Dims& D) {
   return AttnDims{D.B, D.S, D.H, D.dk, cfg->causal ? 1 : 0, cfg->attn_scale, D.S, 1, drop_site(D, DROP_ATTN_PROBS)};
 }
 AttnDims cross_dims(const t5_block_cfg* cfg, const Dims& D) {
-  return AttnDims{D.B, D.S, D.H, D.dk, 0, cfg->attn_scale, D.Sk, 0, make_drop_site(0, 0, 0.f)};
+  return AttnDims{D.B, D.S, D.H, D.dk, 0, cfg->attn_scale, D.Sk, 0, drop_site(D, DROP_CROSS_PROBS)};
 }
 AttnIO cross_io(const Dims& D, const Stash& S, const BwdWs* W) {
   AttnIO io;
@@ -359,7 +358,7 @@ int fwd_cross_attn(const t5_block_cfg* cfg, const Dims& D, const void* enc, cons
   GemmDesc g = fused ? gemm1(T, D.d, D.I, S.cx, D.I, 1, W.xo_t, D.I, 1, ty)
                      : gemm1(T, D.d, D.I, S.cx, D.I, 1, xw->xo, D.d, 0, ty);
   GemmEpi e = epi(EPI_RESID, S.h2, D.d, IN_F32);
-  e.aux0 = S.h; e.aux_type = IN_F32;
+  e.aux0 = S.h; e.aux_type = IN_F32; e.drop = drop_site(D, DROP_CROSS_OUT);
   T5_STEP("gemm_xo", run_gemm(g, e, st));
   return T5_OK;
 }
@@ -490,6 +489,10 @@ int bwd_cross_attn(const t5_block_cfg* cfg, const Dims& D, const void* enc, cons
   const size_t es = D.es;
   const AttnDims ad = cross_dims(cfg, D);
   const void* dh_op = ty == IN_BF16 ? (const void*)W.dh_lp : (const void*)W.dh;
+  if (D.drop > 0.f) {
+    T5_STEP("dropout_dh", launch_dropout_apply(drop_site(D, DROP_CROSS_OUT), dh_op, W.dmask, ty, T, D.d, st));
+    dh_op = W.dmask;
+  }
   {  // dXo = cx^T dh2
     GemmDesc g = gemm1(D.I, D.d, T, S.cx, D.I, 0, dh_op, D.d, 0, ty);
     GemmEpi e = epi(EPI_SPLIT_F32, dxw->xo, D.d, IN_F32);

@@ -116,7 +116,13 @@ inline DropSite make_drop_site(uint64_t seed, int site, float rate) {
   d.scale = 1.f / (1.f - (rate > 0.f ? rate : 0.f));
   return d;
 }
-enum { DROP_ATTN_PROBS = 1, DROP_ATTN_OUT = 2, DROP_MLP_HIDDEN = 3, DROP_MLP_OUT = 4 };
+// Sites: the block's four; the cross-attention sublayer of a decoder layer (probabilities, output); the ends
+// of a stack (embedded tokens, output of the final norm), with their own numbers on the decoder side of an
+// encoder-decoder pair.
+enum {
+  DROP_ATTN_PROBS = 1, DROP_ATTN_OUT = 2, DROP_MLP_HIDDEN = 3, DROP_MLP_OUT = 4, DROP_CROSS_PROBS = 5,
+  DROP_CROSS_OUT = 6, DROP_EMBED = 7, DROP_FINAL = 8, DROP_DEC_EMBED = 9, DROP_DEC_FINAL = 10
+};
 __device__ __forceinline__ uint32_t drop_row_key(const DropSite& d, uint32_t hi) { return mix32(d.k0 ^ hi ^ d.seed_hi); }
 // multiplier of element lo in the row whose key is k1: scale where kept, 0 where dropped
 __device__ __forceinline__ float drop_mult(const DropSite& d, uint32_t k1, uint32_t lo) {

@@ -18,6 +18,7 @@ struct Layers {
   Dims D;          // D.Sk > 0: decoder layers with cross-attention over an encoder output of that length
   RelposLut lut;
   int L = 0;
+  int layer0 = 0;  // index of the first layer in the model's count of layers (dropout seeds)
   bool remat = false, fused = false;
   std::vector<t5_block_weights> lw;
   std::vector<t5_block_grads> lg;
@@ -84,8 +85,28 @@ int bind_layers(Layers& s, const t5_block_weights* layers, const t5_cross_weight
   return T5_OK;
 }
 
+// Configuration of layer l: the stack's, with the layer's own dropout seed -- the stack's plus a multiple
+// of an odd 64-bit constant, so that no two layers of a model share masks.
+void layer_cfg(const Layers& s, int l, t5_block_cfg* bc, Dims* D) {
+  *bc = *s.bc;
+  *D = s.D;
+  if (s.D.drop > 0.f) {
+    D->seed = s.D.seed + (uint64_t)(s.layer0 + l + 1) * 0x9E3779B97F4A7C15ull;
+    bc->dropout_seed_lo = (uint32_t)D->seed;
+    bc->dropout_seed_hi = (uint32_t)(D->seed >> 32);
+  }
+}
+
+// In-place dropout of [rows, d] activations or gradients at one of the stack's end sites.
+int end_dropout(const Dims& D, int site, void* p, int type, hipStream_t st) {
+  if (D.drop > 0.f) T5_STEP("dropout_end", launch_dropout_apply(drop_site(D, site), p, p, type, D.T, D.d, st));
+  return T5_OK;
+}
+
 int layer_forward(const Layers& s, int l, const void* enc_out, hipStream_t st) {
-  const Dims& D = s.D;
+  t5_block_cfg bc;
+  Dims D;
+  layer_cfg(s, l, &bc, &D);
   Stash S;
   carve_stash(D, s.stash_of(l), &S);
   S.diag = s.diag;
@@ -93,9 +114,9 @@ int layer_forward(const Layers& s, int l, const void* enc_out, hipStream_t st) {
   carve_fwd(D, s.block_ws, &FW);
   const bool dec = D.Sk > 0;
   if (s.fused) T5_SUB(fwd_pack_weights(D, &s.lw[l], dec ? &s.xw[l] : nullptr, FW, st));
-  T5_SUB(fwd_self_attn(s.bc, D, s.lut, s.x_of(l), &s.lw[l], S, FW, s.fused, st, false));
-  if (dec) T5_SUB(fwd_cross_attn(s.bc, D, enc_out, &s.xw[l], S, FW, s.fused, st));
-  T5_SUB(fwd_mlp(s.bc, D, dec ? S.h2 : S.h, &s.lw[l], S, FW, s.fused, s.x_of(l + 1), st));
+  T5_SUB(fwd_self_attn(&bc, D, s.lut, s.x_of(l), &s.lw[l], S, FW, s.fused, st, false));
+  if (dec) T5_SUB(fwd_cross_attn(&bc, D, enc_out, &s.xw[l], S, FW, s.fused, st));
+  T5_SUB(fwd_mlp(&bc, D, dec ? S.h2 : S.h, &s.lw[l], S, FW, s.fused, s.x_of(l + 1), st));
   return T5_OK;
 }
 
@@ -127,6 +148,9 @@ int layers_backward(const Layers& s, const void* enc_out, float* denc_acc, int a
   void* dx = s.dxb;
   for (int l = s.L - 1; l >= 0; --l) {
     if (s.remat) T5_SUB(layer_forward(s, l, enc_out, st));  // rebuilds layer l's saved activations
+    t5_block_cfg bc;
+    Dims D;  // this layer's (its dropout seed differs from the stack's)
+    layer_cfg(s, l, &bc, &D);
     Stash S;
     carve_stash(D, s.stash_of(l), &S);
     S.diag = s.diag;
@@ -134,11 +158,11 @@ int layers_backward(const Layers& s, const void* enc_out, float* denc_acc, int a
     T5_SUB(bwd_mlp(D, dy, dec ? S.h2 : S.h, &s.lw[l], S, BW, &s.lg[l], acc, st));
     if (dec) {
       // the first layer processed stores its denc, the others add theirs to it
-      T5_SUB(bwd_cross_attn(s.bc, D, enc_out, &s.xw[l], S, BW, denc_acc, &s.xg[l], acc, st, true, l != s.L - 1));
-      T5_SUB(bwd_self_attn(s.bc, D, s.lut, s.x_of(l), BW.dh1, BW.dh1_lp, &s.lw[l], S, BW, attn_mfma, far, dx,
+      T5_SUB(bwd_cross_attn(&bc, D, enc_out, &s.xw[l], S, BW, denc_acc, &s.xg[l], acc, st, true, l != s.L - 1));
+      T5_SUB(bwd_self_attn(&bc, D, s.lut, s.x_of(l), BW.dh1, BW.dh1_lp, &s.lw[l], S, BW, attn_mfma, far, dx,
                            &s.lg[l], acc, st, false));
     } else {
-      T5_SUB(bwd_self_attn(s.bc, D, s.lut, s.x_of(l), BW.dh, BW.dh_lp, &s.lw[l], S, BW, attn_mfma, far, dx,
+      T5_SUB(bwd_self_attn(&bc, D, s.lut, s.x_of(l), BW.dh, BW.dh_lp, &s.lw[l], S, BW, attn_mfma, far, dx,
                            &s.lg[l], acc, st, false));
     }
     std::swap(dy, dx);
@@ -157,6 +181,7 @@ struct Head {
   int V = 0, chunk = 0;
   bool tied = false;
   float z_loss = 0.f;
+  int drop_site_final = DROP_FINAL;  // dropout site of the final norm's output
   const void *embedding = nullptr, *final_scale = nullptr, *logits_w = nullptr;
   float *d_embedding = nullptr, *d_final_scale = nullptr, *d_logits_w = nullptr;
   void *nf = nullptr, *logits = nullptr, *wout_t = nullptr, *scale_s = nullptr;
@@ -190,6 +215,7 @@ int head_loss_and_grad(const Head& h, const Dims& D, float rms_eps, const void* 
     gf = h.scale_s;
   }
   T5_STEP("rmsnorm_fwd", launch_rmsnorm_fwd(x_last, ty, gf, h.nf, ty, h.rf, T, D.d, rms_eps, st));
+  T5_SUB(end_dropout(D, h.drop_site_final, h.nf, ty, st));  // the logits (and dW) see the dropped norm output
   // The MFMA GEMMs want the contraction index contiguous in both operands.  logits = nf W contracts over
   // d_model: E [V, d] has it contiguous, Wout [d, V] is transposed once per step.  dnf = dlogits W^T
   // contracts over the vocabulary: Wout has it contiguous, E is transposed once per step.
@@ -239,6 +265,7 @@ int head_loss_and_grad(const Head& h, const Dims& D, float rms_eps, const void* 
   if (!want_grads) return T5_OK;
   // gradient of the stack's last output through the final norm (no residual term)
   float* dg = h.tied ? h.dg_tmp : h.d_final_scale;
+  T5_SUB(end_dropout(D, h.drop_site_final, h.dnf, IN_F32, st));
   T5_STEP("rmsnorm_bwd", launch_rmsnorm_bwd(x_last, ty, gf, ty, h.rf, h.dnf, nullptr, IN_F32,
                                             ty == IN_F32 ? (float*)dx_out : nullptr, ty == IN_BF16 ? dx_out : nullptr,
                                             ty, dg, h.dg_partial, h.tied ? 0 : acc, T, D.d, st));
@@ -271,7 +298,6 @@ int plan_stack(const t5_stack_cfg* c, StackPlan* p) {
   if (!c) return T5_ERR_NULL;
   int rc = validate_cfg(&c->block, &p->S.D, &p->S.lut);
   if (rc != T5_OK) return rc;
-  if (c->block.dropout_rate > 0.f) return T5_ERR_UNSUPPORTED;  // the stacks do not derive per-layer seeds yet
   if ((rc = validate_ends(c->n_layers, c->vocab, c->z_loss)) != T5_OK) return rc;
   p->S.bc = &c->block; p->S.L = c->n_layers; p->S.remat = c->remat != 0; p->S.fused = fused_fwd_ok(p->S.D);
   p->H.V = c->vocab; p->H.tied = c->tied_logits != 0; p->H.z_loss = c->z_loss;
@@ -303,11 +329,12 @@ int plan_encdec(const t5_encdec_cfg* c, EncDecPlan* p) {
   if (e.batch != d.batch || e.d_model != d.d_model || e.dtype != d.dtype) return T5_ERR_SHAPE;
   int rc = validate_cfg(&e, &p->E.D, &p->E.lut);
   if (rc != T5_OK) return rc;
-  if (e.dropout_rate > 0.f || d.dropout_rate > 0.f) return T5_ERR_UNSUPPORTED;
   if ((rc = validate_cfg(&d, &p->Dc.D, &p->Dc.lut, e.seq)) != T5_OK) return rc;
   if ((rc = validate_ends(c->n_enc_layers, c->vocab, c->z_loss)) != T5_OK) return rc;
   if ((rc = validate_ends(c->n_dec_layers, c->vocab, c->z_loss)) != T5_OK) return rc;
   p->E.bc = &c->enc_block; p->E.L = c->n_enc_layers; p->E.remat = c->remat != 0; p->E.fused = fused_fwd_ok(p->E.D);
+  p->Dc.layer0 = c->n_enc_layers;  // the decoder's layers count on from the encoder's
+  p->H.drop_site_final = DROP_DEC_FINAL;
   p->Dc.bc = &c->dec_block; p->Dc.L = c->n_dec_layers; p->Dc.remat = c->remat != 0; p->Dc.fused = fused_fwd_ok(p->Dc.D);
   p->H.V = c->vocab; p->H.tied = c->tied_logits != 0; p->H.z_loss = c->z_loss;
   p->H.chunk = p->Dc.D.T < kLogitChunk ? (int)p->Dc.D.T : kLogitChunk;
@@ -360,6 +387,7 @@ int t5_stack_loss_and_grad(const t5_stack_cfg* cfg, const int32_t* tokens, const
   }
 
   T5_STEP("embed_fwd", launch_embed_fwd(tokens, w->embedding, p.S.x_of(0), D.ty, D.T, D.d, V, st));
+  T5_SUB(end_dropout(D, DROP_EMBED, p.S.x_of(0), D.ty, st));
   T5_SUB(layers_forward(p.S, nullptr, st));
   if (grads && !acc) T5_SUB(zero_end_grads(grads->embedding, p.H.d_logits_w, V, D.d, st));
   T5_SUB(head_loss_and_grad(p.H, D, cfg->block.rms_eps, p.S.x_of(p.S.L), targets, loss, grads != nullptr, acc,
@@ -367,6 +395,7 @@ int t5_stack_loss_and_grad(const t5_stack_cfg* cfg, const int32_t* tokens, const
   if (!grads) return T5_OK;
   void* dx0 = nullptr;
   T5_SUB(layers_backward(p.S, nullptr, nullptr, acc, &dx0, st));
+  T5_SUB(end_dropout(D, DROP_EMBED, dx0, D.ty, st));
   T5_STEP("embed_bwd", launch_embed_bwd(tokens, dx0, D.ty, grads->embedding, D.T, D.d, V, st));
   return T5_OK;
 }
@@ -409,11 +438,14 @@ int t5_encdec_loss_and_grad(const t5_encdec_cfg* cfg, const int32_t* enc_tokens,
 
   // encoder: embedding, layers, final norm -> enc_out
   T5_STEP("embed_fwd", launch_embed_fwd(enc_tokens, w->embedding, p.E.x_of(0), ty, E.T, E.d, V, st));
+  T5_SUB(end_dropout(E, DROP_EMBED, p.E.x_of(0), ty, st));
   T5_SUB(layers_forward(p.E, nullptr, st));
   T5_STEP("rmsnorm_fwd", launch_rmsnorm_fwd(p.E.x_of(p.E.L), ty, w->enc_final_scale, p.enc_out, ty, p.enc_rf, (int)E.T,
                                             E.d, cfg->enc_block.rms_eps, st));
+  T5_SUB(end_dropout(E, DROP_FINAL, p.enc_out, ty, st));
   // decoder: embedding, layers cross-attending to enc_out, head
   T5_STEP("embed_fwd", launch_embed_fwd(dec_tokens, w->embedding, p.Dc.x_of(0), ty, D.T, D.d, V, st));
+  T5_SUB(end_dropout(D, DROP_DEC_EMBED, p.Dc.x_of(0), ty, st));
   T5_SUB(layers_forward(p.Dc, p.enc_out, st));
   if (grads && !acc) T5_SUB(zero_end_grads(grads->embedding, p.H.d_logits_w, V, D.d, st));
   T5_SUB(head_loss_and_grad(p.H, D, cfg->dec_block.rms_eps, p.Dc.x_of(p.Dc.L), targets, loss, grads != nullptr, acc,
@@ -421,13 +453,16 @@ int t5_encdec_loss_and_grad(const t5_encdec_cfg* cfg, const int32_t* enc_tokens,
   if (!grads) return T5_OK;
   void* dx0 = nullptr;
   T5_SUB(layers_backward(p.Dc, p.enc_out, p.denc, acc, &dx0, st));
+  T5_SUB(end_dropout(D, DROP_DEC_EMBED, dx0, ty, st));
   T5_STEP("embed_bwd", launch_embed_bwd(dec_tokens, dx0, ty, grads->embedding, D.T, D.d, V, st));
+  T5_SUB(end_dropout(E, DROP_FINAL, p.denc, IN_F32, st));
   // encoder: final norm backward (no residual term), layers, embedding
   T5_STEP("rmsnorm_bwd", launch_rmsnorm_bwd(p.E.x_of(p.E.L), ty, w->enc_final_scale, ty, p.enc_rf, p.denc, nullptr,
                                             IN_F32, ty == IN_F32 ? (float*)p.E.dxa : nullptr,
                                             ty == IN_BF16 ? p.E.dxa : nullptr, ty, grads->enc_final_scale,
                                             p.enc_dg_partial, acc, (int)E.T, E.d, st));
   T5_SUB(layers_backward(p.E, nullptr, nullptr, acc, &dx0, st));
+  T5_SUB(end_dropout(E, DROP_EMBED, dx0, ty, st));
   T5_STEP("embed_bwd", launch_embed_bwd(enc_tokens, dx0, ty, grads->embedding, E.T, E.d, V, st));
   return T5_OK;
 }

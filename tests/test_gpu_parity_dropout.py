@@ -166,3 +166,101 @@ def test_dropout_full_batch_sampled():
     assert edx[0] <= tol_dx[0] and edx[1] <= tol_dx[1], edx
     assert torch.equal(gy, gy2) and torch.equal(gdx, gdx2)
     assert all(torch.isfinite(v).all() for v in gg.values())
+
+
+# ------------------------------------------------------------------ decoder layer, stacks, encoder-decoder pair
+def _drop_block(cfg, rate=RATE, seed=SEED + 9, **kw):
+    return replace(cfg, dropout_rate=rate, dropout_seed=seed, **kw)
+
+
+def _drop_stack(sc, rate=RATE, seed=SEED + 10, **kw):
+    return replace(sc, block=_drop_block(sc.block, rate, seed), **kw)
+
+
+def _drop_encdec(ec, rate=RATE, seed_e=SEED + 11, seed_d=SEED + 11, **kw):
+    return replace(ec, enc_block=_drop_block(ec.enc_block, rate, seed_e), dec_block=_drop_block(ec.dec_block, rate, seed_d), **kw)
+
+
+def _dec_cases():
+    import test_gpu_parity_decoder as TD
+    f32 = [_drop_block(TD.F32_CASES[0], name="drop_dec_f32", index=80),
+           _drop_block(TD.F32_CASES[1], float(np.float32(0.3)), 5, name="drop_dec_f32_ragged", index=81),
+           _drop_block(TD.F32_CASES[5], name="drop_dec_f32_relu", index=82)]
+    bf = [_drop_block(c, name="drop_" + c.name, index=83 + i) for i, c in enumerate(TD.SMALL_BF16) if
+          c.name in ("dec_bf16", "dec_bf16_dk128", "dec_bf16_ragged_enc", "dec_bf16_ragged")]
+    return f32, bf
+
+
+DEC_F32, DEC_BF16 = _dec_cases()
+
+
+@pytest.mark.parametrize("cfg", DEC_F32, ids=[c.name for c in DEC_F32])
+def test_decoder_block_dropout_f32(cfg):
+    from test_gpu_parity_decoder import _check
+    _check(cfg, TOL_F32, TOL_F32, TOL_F32, TOL_F32)
+
+
+@pytest.mark.parametrize("cfg", DEC_BF16, ids=[c.name for c in DEC_BF16])
+def test_decoder_block_dropout_bf16(cfg):
+    from parity_util import TOL_BF16_DEC_ACT, TOL_BF16_DEC_DX, TOL_BF16_DENC
+    from test_gpu_parity_decoder import _check
+    p = cfg.dropout_rate
+    _check(cfg, drop_tol(TOL_BF16_DEC_ACT, p, False), drop_tol(TOL_BF16_DEC_DX, p, True), drop_tol(TOL_BF16_DENC, p, True),
+           drop_tol(TOL_BF16_DW, p, True))
+
+
+def _stack_cases():
+    import test_gpu_parity_stack as TS
+    f32 = [_drop_stack(TS.F32_CASES[0], name="drop_stack_f32"), _drop_stack(TS.F32_CASES[1], name="drop_stack_f32_tied"),
+           _drop_stack(TS.F32_CASES[2], float(np.float32(0.25)), 3, name="drop_stack_f32_remat")]
+    bf = [_drop_stack(TS.BF16_CASES[0], name="drop_stack_bf16"), _drop_stack(TS.BF16_CASES[1], name="drop_stack_bf16_tied"),
+          _drop_stack(TS.BF16_CASES[5], name="drop_stack_bf16_ragged")]
+    ef32 = [_drop_encdec(TS.EC_F32[0], name="drop_ec_f32"),
+            _drop_encdec(TS.EC_F32[1], float(np.float32(0.2)), 21, 22, name="drop_ec_f32_tied_remat")]
+    ebf = [_drop_encdec(TS.EC_BF16[0], name="drop_ec_bf16"), _drop_encdec(TS.EC_BF16[2], name="drop_ec_bf16_ragged")]
+    return f32, bf, ef32, ebf
+
+
+ST_F32, ST_BF16, EC_F32, EC_BF16 = _stack_cases()
+
+
+@pytest.mark.parametrize("sc", ST_F32, ids=[c.name for c in ST_F32])
+def test_stack_dropout_f32(sc):
+    from test_gpu_parity_stack import _compare
+    _compare(sc, 1e-5, TOL_F32[0])
+
+
+@pytest.mark.parametrize("sc", ST_BF16, ids=[c.name for c in ST_BF16])
+def test_stack_dropout_bf16(sc):
+    from parity_util import stack_bf16_tol
+    from test_gpu_parity_stack import _compare
+    _compare(sc, 5e-4 / (1.0 - RATE), *drop_tol(stack_bf16_tol(sc.n_layers), RATE, True))
+
+
+def test_stack_dropout_remat_replays_the_masks():
+    """Recomputing a layer in the backward regenerates the same masks: gradients equal those of the stashed run
+    (up to the order of the float32 atomic additions of the weight gradients)."""
+    import test_gpu_parity_stack as TS
+    sc = ST_BF16[0]
+    w, tokens, targets = TS._case(sc)
+    l1, g1 = TS._run(sc, w, tokens, targets)
+    l2, g2 = TS._run(replace(sc, remat=True), w, tokens, targets)
+    assert l1 == l2
+    from parity_util import to_np
+    for l in range(sc.n_layers):
+        for name in g1["layers"][l]:
+            a, b = to_np(g1["layers"][l][name]), to_np(g2["layers"][l][name])
+            assert np.abs(a - b).max() <= 1e-4 * (np.abs(a).max() + 1e-30), (l, name)
+
+
+@pytest.mark.parametrize("ec", EC_F32, ids=[c.name for c in EC_F32])
+def test_encdec_dropout_f32(ec):
+    from test_gpu_parity_stack import _ec_compare
+    _ec_compare(ec, 1e-5, TOL_F32[0])
+
+
+@pytest.mark.parametrize("ec", EC_BF16, ids=[c.name for c in EC_BF16])
+def test_encdec_dropout_bf16(ec):
+    from parity_util import stack_bf16_tol
+    from test_gpu_parity_stack import _ec_compare
+    _ec_compare(ec, 5e-4 / (1.0 - RATE), *drop_tol(stack_bf16_tol(ec.n_enc_layers + ec.n_dec_layers), RATE, True))
