@@ -133,6 +133,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="record one step into a HIP graph after the warm-up and time K replays of it")
+    ap.add_argument("--overlap", action="store_true",
+                    help="run the weight-gradient GEMMs of the backward on the library's second stream")
     ap.add_argument("--dropout", type=float, default=0.0,
                     help="dropout rate at every site of the workload (0 = the paper's pre-training recipe)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -254,6 +256,8 @@ def main() -> int:
             step_no[0] += 1
             P.adafactor_step_multi(opt_tensors, step=step_no[0], lr=1e-2, workspace=opt_ws)
 
+    if args.overlap:
+        P.t5_wgrad_overlap_enable(True)
     for _ in range(max(args.warmup, 1 if args.graph else 0)):
         step()
     torch.cuda.synchronize()
@@ -377,7 +381,7 @@ def main() -> int:
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "launch": "hip graph replay" if args.graph else "eager",
+        "launch": ("hip graph replay" if args.graph else "eager") + (", weight gradients on a second stream" if args.overlap else ""),
         "config": {"workload": args.workload, "batch": cfg.batch, "seq_len": cfg.seq, "d_model": cfg.d_model,
                    "n_heads": cfg.n_heads, "d_kv": cfg.d_kv, "d_ff": cfg.d_ff, "causal": cfg.causal,
                    "enc_seq_len": cfg.enc_seq, "dropout_rate": cfg.dropout_rate,

@@ -363,6 +363,17 @@ int adafactor_step_multi(const adafactor_tensor* tensors, int n_tensors, const a
 int t5_gemm_bf16(const void* A, const void* B, float* C, int M, int N, int K, int lda, int ldb, int ldc,
                  int a_kc, int b_kc, void* stream);
 
+/* Opt-in overlap inside the backward passes.  The weight-gradient GEMMs are leaves of the backward's
+ * dependency graph; after t5_wgrad_overlap_enable(1) every backward entry point launches them on a
+ * second stream owned by the library (default priority, created by that call, ordered against the caller's
+ * stream with events: forked after the producers of each GEMM's operands, joined before the call returns
+ * or the next layer starts), so that they run beside the chain that carries the gradient to the input.
+ * Results are identical up to the order of the float32 atomic additions.  The state is per process and
+ * not thread-safe; call it outside stream capture (the forks and joins themselves can be captured).
+ * Passes with dropout stay on one stream.  t5_wgrad_overlap_enable(0) drains and releases the stream.
+ * Returns T5_OK or T5_ERR_DEVICE. */
+int t5_wgrad_overlap_enable(int enable);
+
 /* Per-step device timing of t5_block_fwd / t5_block_bwd for roofline reports.  While enabled, every
  * step of the block is bracketed by HIP events on the caller's stream; t5_step_timing_read()
  * synchronises those events and returns, per step, the summed milliseconds and the number of

@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     t5_decoder_block_stash_bytes,
     t5_decoder_block_workspace_bytes,
     t5_dropout_keep,
+    t5_wgrad_overlap_enable,
     t5_encdec_loss_and_grad,
     t5_encdec_workspace_bytes,
     t5_gemm_bf16,

@@ -150,6 +150,8 @@ def lib() -> C.CDLL:
     L.adafactor_step_multi.argtypes = [C.POINTER(_AfTensor), i32, C.POINTER(_AfCfg), vp, sz, vp]
     L.t5_gemm_bf16.restype = i32
     L.t5_gemm_bf16.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp]
+    L.t5_wgrad_overlap_enable.restype = i32
+    L.t5_wgrad_overlap_enable.argtypes = [i32]
     L.t5_step_timing_enable.restype = None
     L.t5_step_timing_enable.argtypes = [i32]
     L.t5_mfma_peak_probe.restype = i32
@@ -642,6 +644,13 @@ def t5_gemm_bf16(a: torch.Tensor, b: torch.Tensor, a_kc: bool, b_kc: bool, out: 
     if rc:
         raise T5Error(rc, "t5_gemm_bf16")
     return out
+
+
+def t5_wgrad_overlap_enable(enable: bool) -> None:
+    """Run the weight-gradient GEMMs of every backward pass on a second stream owned by the library."""
+    rc = lib().t5_wgrad_overlap_enable(int(bool(enable)))
+    if rc:
+        raise T5Error(rc, "t5_wgrad_overlap_enable")
 
 
 def t5_step_timing_enable(enable: bool) -> None:

@@ -5,6 +5,7 @@
 namespace t5mi {
 bool g_timing = false;
 std::vector<StepRec> g_recs;
+SideStream g_side;
 }  // namespace t5mi
 
 extern "C" {
@@ -109,9 +110,11 @@ int t5_block_bwd(const t5_block_cfg* cfg, const void* dy, const void* x, const t
   const AttnDims ad = self_dims(cfg, D);
   const int far = lut.n_thr > 0 ? lut.thr[lut.n_thr - 1] : lut.max_exact;
   const bool attn_mfma = D.ty == IN_BF16 && attn_mfma_supported(ad) && attn_bwd_mfma_fits(ad, far);
+  W.fork = fork_begin(st, D.drop == 0.f);
   T5_SUB(bwd_zero(D, dw, nullptr, attn_mfma ? W.ddiag : nullptr, acc != 0, st));
   T5_SUB(bwd_mlp(D, dy, S.h, w, S, W, dw, acc, st));
   T5_SUB(bwd_self_attn(cfg, D, lut, x, W.dh, W.dh_lp, w, S, W, attn_mfma, far, dx, dw, acc, st));
+  T5_TRY(fork_join(W.fork));
   return T5_OK;
 }
 
@@ -164,10 +167,12 @@ int t5_decoder_block_bwd(const t5_block_cfg* cfg, int32_t enc_seq, const void* d
   const AttnDims ad = self_dims(cfg, D);
   const int far = lut.n_thr > 0 ? lut.thr[lut.n_thr - 1] : lut.max_exact;
   const bool attn_mfma = D.ty == IN_BF16 && attn_mfma_supported(ad) && attn_bwd_mfma_fits(ad, far);
+  W.fork = fork_begin(st, D.drop == 0.f);
   T5_SUB(bwd_zero(D, dw, dxw, attn_mfma ? W.ddiag : nullptr, acc != 0, st));
   T5_SUB(bwd_mlp(D, dy, S.h2, w, S, W, dw, acc, st));
   T5_SUB(bwd_cross_attn(cfg, D, enc, xw, S, W, denc, dxw, acc, st));
   T5_SUB(bwd_self_attn(cfg, D, lut, x, W.dh1, W.dh1_lp, w, S, W, attn_mfma, far, dx, dw, acc, st));
+  T5_TRY(fork_join(W.fork));
   return T5_OK;
 }
 
@@ -180,6 +185,29 @@ int t5_gemm_bf16(const void* A, const void* B, float* C, int M, int N, int K, in
   if (!gemm_mfma_supported(g, e)) return T5_ERR_UNSUPPORTED;
   hipStream_t st = (hipStream_t)stream;
   T5_STEP("gemm_bf16", launch_gemm_mfma(g, e, st));
+  return T5_OK;
+}
+
+int t5_wgrad_overlap_enable(int enable) {
+  if (!enable) {
+    if (g_side.stream) {
+      (void)hipStreamSynchronize(g_side.stream);
+      (void)hipEventDestroy(g_side.ev_fork);
+      (void)hipEventDestroy(g_side.ev_join);
+      (void)hipStreamDestroy(g_side.stream);
+      g_side = SideStream();
+    }
+    return T5_OK;
+  }
+  if (g_side.stream) return T5_OK;
+  SideStream s;
+  if (hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) != hipSuccess) return T5_ERR_DEVICE;  // default priority
+  if (hipEventCreateWithFlags(&s.ev_fork, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&s.ev_join, hipEventDisableTiming) != hipSuccess) {
+    (void)hipStreamDestroy(s.stream);
+    return T5_ERR_DEVICE;
+  }
+  g_side = s;
   return T5_OK;
 }
 

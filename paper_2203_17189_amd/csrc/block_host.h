@@ -15,6 +15,12 @@ struct StepRec {
 };
 extern bool g_timing;
 extern std::vector<StepRec> g_recs;
+// Second stream for the weight-gradient GEMMs of a backward pass (t5_wgrad_overlap_enable); null when off.
+struct SideStream {
+  hipStream_t stream = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+};
+extern SideStream g_side;
 }  // namespace t5mi
 
 using namespace t5mi;
@@ -142,7 +148,39 @@ size_t carve_fwd(const Dims& D, void* base, FwdWs* w) {
   return cv.off;
 }
 
+// Fork/join of one backward pass.  The weight gradients are leaves of the backward's dependency graph:
+// nothing later in the pass reads them.  With a side stream they run beside the chain that carries the
+// gradient to the layer's input, filling compute units that chain's smaller kernels leave idle.
+// fork_sync() makes the side stream wait for everything launched on the main stream so far (the producers
+// of the GEMM's operands, and the clearing of the gradients); fork_join() makes the main stream wait for
+// the side stream, before buffers the side GEMMs read are written again (the next layer, the next call).
+struct Fork {
+  hipStream_t main = nullptr, side = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  bool on = false;
+};
+inline Fork fork_begin(hipStream_t st, bool allowed) {
+  Fork f;
+  f.main = st;
+  if (!allowed || !t5mi::g_side.stream) return f;
+  f.side = t5mi::g_side.stream; f.ev_fork = t5mi::g_side.ev_fork; f.ev_join = t5mi::g_side.ev_join;
+  f.on = true;
+  return f;
+}
+inline hipError_t fork_sync(const Fork& f) {
+  if (!f.on) return hipSuccess;
+  hipError_t e = hipEventRecord(f.ev_fork, f.main);
+  return e != hipSuccess ? e : hipStreamWaitEvent(f.side, f.ev_fork, 0);
+}
+inline hipError_t fork_join(const Fork& f) {
+  if (!f.on) return hipSuccess;
+  hipError_t e = hipEventRecord(f.ev_join, f.side);
+  return e != hipSuccess ? e : hipStreamWaitEvent(f.main, f.ev_join, 0);
+}
+inline hipStream_t wgrad_stream(const Fork& f) { return f.on ? f.side : f.main; }
+
 struct BwdWs {
+  Fork fork;
   float *dn, *dh, *dvec, *ddiag, *dg_partial;
   void *dh_lp, *duw, *dc, *dqkv;  // duw: [T][2F], du in columns 0..F-1, dw in F..2F-1
   // cross-attention sublayer: dh/dh_lp hold the gradient of h2, dh1/dh1_lp that of h
@@ -152,8 +190,7 @@ struct BwdWs {
 };
 size_t carve_bwd(const Dims& D, void* base, BwdWs* w) {
   Carver cv(base);
-  BwdWs t;
-  std::memset(&t, 0, sizeof(t));
+  BwdWs t = {};
   t.dn = cv.take<float>((size_t)D.T * D.d * 4);
   t.dh = cv.take<float>((size_t)D.T * D.d * 4);
   t.dvec = cv.take<float>((size_t)D.B * D.H * D.S * 4);
@@ -431,6 +468,8 @@ int bwd_mlp(const Dims& D, const void* dy, const float* hin, const t5_block_weig
     dy = W.dmask;
   }
   {  // dWo_ff = a^T dy
+    T5_TRY(fork_sync(W.fork));
+    hipStream_t st = wgrad_stream(W.fork);
     GemmDesc g = gemm1(D.F, D.d, T, S.a, D.F, 0, dy, D.d, 0, ty);
     GemmEpi e = epi(EPI_SPLIT_F32, dw->wo_ff, D.d, IN_F32);
     e.accumulate = 1;
@@ -444,6 +483,8 @@ int bwd_mlp(const Dims& D, const void* dy, const float* hin, const t5_block_weig
       T5_STEP("gemm_da_relu_bwd", run_gemm(g, e, st));
     }
     {  // dWi0 = n2^T du
+      T5_TRY(fork_sync(W.fork));
+      hipStream_t st = wgrad_stream(W.fork);
       GemmDesc g = gemm1(D.d, D.F, T, S.n2, D.d, 0, du_p, D.F, 0, ty);
       GemmEpi e = epi(EPI_SPLIT_F32, dw->wi0, D.F, IN_F32);
       e.accumulate = 1;
@@ -461,6 +502,8 @@ int bwd_mlp(const Dims& D, const void* dy, const float* hin, const t5_block_weig
       T5_STEP("gemm_da_geglu_bwd", run_gemm(g, e, st));
     }
     {  // dWi0 | dWi1 = n2^T [du | dw]
+      T5_TRY(fork_sync(W.fork));
+      hipStream_t st = wgrad_stream(W.fork);
       GemmDesc g = gemm1(D.d, 2 * D.F, T, S.n2, D.d, 0, du_p, 2 * D.F, 0, ty);
       GemmEpi e = epi(EPI_SPLIT_F32, dw->wi0, D.F, IN_F32);
       e.out1 = dw->wi1; e.split_n = D.F; e.accumulate = 1;
@@ -494,6 +537,8 @@ int bwd_cross_attn(const t5_block_cfg* cfg, const Dims& D, const void* enc, cons
     dh_op = W.dmask;
   }
   {  // dXo = cx^T dh2
+    T5_TRY(fork_sync(W.fork));
+    hipStream_t st = wgrad_stream(W.fork);
     GemmDesc g = gemm1(D.I, D.d, T, S.cx, D.I, 0, dh_op, D.d, 0, ty);
     GemmEpi e = epi(EPI_SPLIT_F32, dxw->xo, D.d, IN_F32);
     e.accumulate = 1;
@@ -512,12 +557,15 @@ int bwd_cross_attn(const t5_block_cfg* cfg, const Dims& D, const void* enc, cons
     T5_STEP("xattn_bwd", launch_attn_bwd_simple(io, S.cx, W.dc, ty, nullptr, S.lse_x, W.dvec, nullptr, ad, 0, st));
   }
   {  // dXq = nx^T dq
+    T5_TRY(fork_sync(W.fork));
+    hipStream_t st = wgrad_stream(W.fork);
     GemmDesc g = gemm1(D.d, D.I, T, S.nx, D.d, 0, W.dqx, D.I, 0, ty);
     GemmEpi e = epi(EPI_SPLIT_F32, dxw->xq, D.I, IN_F32);
     e.accumulate = 1;
     T5_STEP("gemm_dxq", run_gemm(g, e, st));
   }
-  {  // dXk | dXv = enc^T [dk | dv]
+  {  // dXk | dXv = enc^T [dk | dv]   (ordered after dXq on the side stream: no new fork point needed)
+    hipStream_t st = wgrad_stream(W.fork);
     GemmDesc g = gemm1(D.d, 2 * D.I, Te, enc, D.d, 0, W.dkvx, 2 * D.I, 0, ty);
     GemmEpi e = epi(EPI_SPLIT_F32, dxw->xk, D.I, IN_F32);
     e.out1 = dxw->xv; e.split_n = D.I; e.accumulate = 1;
@@ -556,6 +604,8 @@ int bwd_self_attn(const t5_block_cfg* cfg, const Dims& D, const RelposLut& lut, 
     dh_op = W.dmask;
   }
   {  // dWo = c^T dh
+    T5_TRY(fork_sync(W.fork));
+    hipStream_t st = wgrad_stream(W.fork);
     GemmDesc g = gemm1(D.I, D.d, T, S.c, D.I, 0, dh_op, D.d, 0, ty);
     GemmEpi e = epi(EPI_SPLIT_F32, dw->wo, D.d, IN_F32);
     e.accumulate = 1;
@@ -578,6 +628,8 @@ int bwd_self_attn(const t5_block_cfg* cfg, const Dims& D, const RelposLut& lut, 
   if (own_table)
     T5_STEP("relpos_diag_bwd", launch_relpos_diag_bwd(W.ddiag, dw->rel_table, D.S, D.H, cfg->num_buckets, lut, acc, st));
   {  // dWq | dWk | dWv = n1^T dqkv
+    T5_TRY(fork_sync(W.fork));
+    hipStream_t st = wgrad_stream(W.fork);
     GemmDesc g = gemm1(D.d, 3 * D.I, T, S.n1, D.d, 0, W.dqkv, 3 * D.I, 0, ty);
     GemmEpi e = epi(EPI_SPLIT_F32, dw->wq, D.I, IN_F32);
     e.out1 = dw->wk; e.out2 = dw->wv; e.split_n = D.I; e.accumulate = 1;

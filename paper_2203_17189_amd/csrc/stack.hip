@@ -135,6 +135,7 @@ int layers_backward(const Layers& s, const void* enc_out, float* denc_acc, int a
   BwdWs BW;
   carve_bwd(D, s.block_ws, &BW);
   BW.ddiag = s.ddiag;
+  BW.fork = fork_begin(st, D.drop == 0.f);
   {
     ZeroList z;
     std::memset(&z, 0, sizeof(z));
@@ -165,6 +166,8 @@ int layers_backward(const Layers& s, const void* enc_out, float* denc_acc, int a
       T5_SUB(bwd_self_attn(&bc, D, s.lut, s.x_of(l), BW.dh, BW.dh_lp, &s.lw[l], S, BW, attn_mfma, far, dx,
                            &s.lg[l], acc, st, false));
     }
+    // the next layer rewrites the workspace (and, with remat, the stash) the side GEMMs read
+    T5_TRY(fork_join(BW.fork));
     std::swap(dy, dx);
   }
   T5_STEP("relpos_diag_bwd",
