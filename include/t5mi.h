@@ -369,8 +369,8 @@ int t5_gemm_bf16(const void* A, const void* B, float* C, int M, int N, int K, in
  * stream with events: forked after the producers of each GEMM's operands, joined before the call returns
  * or the next layer starts), so that they run beside the chain that carries the gradient to the input.
  * Results are identical up to the order of the float32 atomic additions.  The state is per process and
- * not thread-safe; call it outside stream capture (the forks and joins themselves can be captured).
- * Passes with dropout stay on one stream.  t5_wgrad_overlap_enable(0) drains and releases the stream.
+ * not thread-safe; call it outside stream capture.  Passes with dropout, and passes on a stream that is
+ * being captured into a graph, stay on one stream.  t5_wgrad_overlap_enable(0) drains and releases the stream.
  * Returns T5_OK or T5_ERR_DEVICE. */
 int t5_wgrad_overlap_enable(int enable);
 

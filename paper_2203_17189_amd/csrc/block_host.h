@@ -163,6 +163,9 @@ inline Fork fork_begin(hipStream_t st, bool allowed) {
   Fork f;
   f.main = st;
   if (!allowed || !t5mi::g_side.stream) return f;
+  // a pass that is being recorded into a graph stays on the caller's stream
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(st, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) return f;
   f.side = t5mi::g_side.stream; f.ev_fork = t5mi::g_side.ev_fork; f.ev_join = t5mi::g_side.ev_join;
   f.on = true;
   return f;

@@ -85,3 +85,34 @@ def test_stack_overlapped_equals_serial(overlap, remat):
     for l in range(sc.n_layers):
         for k in g0["layers"][l]:
             _close(g1["layers"][l][k], g0["layers"][l][k], (l, k))
+
+
+def test_captured_pass_stays_on_the_callers_stream(overlap):
+    """With the second stream enabled, a backward recorded into a graph runs on the capturing stream alone:
+    the replays match the eager (overlapped) results."""
+    P = overlap
+    from paper_2203_17189_amd import binding as B
+    w, x, dy = make_case(BLK)
+    dw, tx, tdy = upload_case(BLK, w, x, dy)
+    mk = lambda: dict(y=torch.empty_like(tx), dx=torch.empty_like(tx), grads=B.alloc_grads(BLK, dw),
+                      stash=torch.empty(P.t5_block_stash_bytes(BLK), dtype=torch.uint8, device="cuda"),
+                      ws=torch.empty(P.t5_block_workspace_bytes(BLK), dtype=torch.uint8, device="cuda"))
+    eager, graph = mk(), mk()
+
+    def step(b):
+        P.t5_block_fwd(BLK, tx, dw, y=b["y"], stash=b["stash"], workspace=b["ws"])
+        P.t5_block_bwd(BLK, tdy, tx, dw, b["stash"], dx=b["dx"], grads=b["grads"], workspace=b["ws"])
+
+    step(graph)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step(graph)
+    for rep in range(3):
+        graph["dx"].zero_()
+        g.replay()
+        step(eager)
+        torch.cuda.synchronize()
+        assert torch.equal(graph["dx"], eager["dx"]), rep
+        for k in eager["grads"]:
+            _close(graph["grads"][k], eager["grads"][k], (rep, k))
