@@ -133,6 +133,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="record one step into a HIP graph after the warm-up and time K replays of it")
+    ap.add_argument("--optimizer", action="store_true",
+                    help="stack workloads: add the Adafactor update of every tensor of the model to the step")
     ap.add_argument("--overlap", action="store_true",
                     help="run the weight-gradient GEMMs of the backward on the library's second stream")
     ap.add_argument("--dropout", type=float, default=0.0,
@@ -237,14 +239,40 @@ def main() -> int:
                                 v_full=o["vf"], bf16_copy_out=w[name]) for name, o in opt.items()]
             opt_ws = torch.empty(max(P.adafactor_multi_workspace_bytes(opt_tensors), 256), dtype=torch.uint8, device=dev)
 
+    def all_tensors(wt, gt, path=""):
+        """(name, weight, gradient) of every tensor of a nested weight / gradient structure."""
+        if isinstance(wt, dict):
+            return [t for k in gt for t in all_tensors(wt[k], gt[k], f"{path}.{k}")]
+        if isinstance(wt, list):
+            return [t for i in range(len(gt)) for t in all_tensors(wt[i], gt[i], f"{path}[{i}]")]
+        return [(path, wt, gt)]
+
+    model_opt = None
+    if args.optimizer and (sc is not None or ec is not None):
+        # float32 master copies and second-moment state for every tensor; the bf16 weights the model reads are
+        # refreshed by the update itself.  Matrices are factored, except the embedding and the bias tables.
+        model_opt = []
+        for name, wt, gt in all_tensors(sw, s_grads):
+            master = wt.float().contiguous()
+            rows, cols = (master.shape[0], master.shape[1]) if master.dim() == 2 else (1, master.numel())
+            fact = master.dim() == 2 and "rel_table" not in name and "embedding" not in name
+            model_opt.append(dict(param=master, grad=gt, factored=fact,
+                                  v_row=torch.zeros(rows, device=dev) if fact else None,
+                                  v_col=torch.zeros(cols, device=dev) if fact else None,
+                                  v_full=None if fact else torch.zeros(rows, cols, device=dev), bf16_copy_out=wt))
+        model_opt_ws = torch.empty(max(P.adafactor_multi_workspace_bytes(model_opt), 256), dtype=torch.uint8, device=dev)
+
     step_no = [0]
 
     def step():
-        if ec is not None:
-            P.t5_encdec_loss_and_grad(ec, e_tok, s_tok, s_tgt, sw, grads=s_grads, workspace=s_ws, loss=s_loss)
-            return
-        if sc is not None:
-            P.t5_stack_loss_and_grad(sc, s_tok, s_tgt, sw, grads=s_grads, workspace=s_ws, loss=s_loss)
+        if ec is not None or sc is not None:
+            if ec is not None:
+                P.t5_encdec_loss_and_grad(ec, e_tok, s_tok, s_tgt, sw, grads=s_grads, workspace=s_ws, loss=s_loss)
+            else:
+                P.t5_stack_loss_and_grad(sc, s_tok, s_tgt, sw, grads=s_grads, workspace=s_ws, loss=s_loss)
+            if model_opt is not None:
+                step_no[0] += 1
+                P.adafactor_step_multi(model_opt, step=step_no[0], lr=1e-3, workspace=model_opt_ws)
             return
         if decoder:
             P.t5_decoder_block_fwd(cfg, x, enc, w, y=y, stash=stash, workspace=ws)
@@ -311,6 +339,8 @@ def main() -> int:
     # in float32 plus the refreshed bf16 copy)
     Tn, dn_ = cfg.tokens, cfg.d_model
     n_params = sum(int(v.numel()) for v in w.values())
+    if model_opt is not None:  # the whole model's tensors; unfactored ones also read and write their full second moment
+        n_params = sum(int(t["param"].numel()) * (1.0 if t["factored"] else 22.0 / 14.0) for t in model_opt)
     # launches of each norm kernel per step
     n_norm = 2 * sc.n_layers + 1 if sc is not None else (3 if decoder else 2)
     if ec is not None:
@@ -318,7 +348,7 @@ def main() -> int:
     hbm_bytes = {"rmsnorm_fwd": n_norm * (2.0 * Tn * dn_ * 2 + 4.0 * Tn), "rmsnorm_bwd": n_norm * (4.0 * Tn * dn_ * 2),
                  "adafactor": 14.0 * n_params}
     if ec is not None:
-        hbm_bytes = {"xent_rows": 2.0 * Tn * ec.vocab * 2}
+        hbm_bytes = {"xent_rows": 2.0 * Tn * ec.vocab * 2, "adafactor": 14.0 * n_params}
     if sc is not None:
         # the loss reads every logit once and writes its gradient over it; the lookup copies T rows, its
         # gradient reads T rows and adds them into float32 rows (read + write)
@@ -385,7 +415,7 @@ def main() -> int:
         "config": {"workload": args.workload, "batch": cfg.batch, "seq_len": cfg.seq, "d_model": cfg.d_model,
                    "n_heads": cfg.n_heads, "d_kv": cfg.d_kv, "d_ff": cfg.d_ff, "causal": cfg.causal,
                    "enc_seq_len": cfg.enc_seq, "dropout_rate": cfg.dropout_rate,
-                   "adafactor": cfg.adafactor, "passes": "fwd+bwd" + ("+adafactor" if cfg.adafactor else ""),
+                   "adafactor": cfg.adafactor, "passes": "fwd+bwd" + ("+adafactor" if cfg.adafactor or (args.optimizer and (sc is not None or ec is not None)) else ""),
                    **({"n_layers": sc.n_layers, "vocab": sc.vocab, "tied_logits": sc.tied_logits, "remat": sc.remat,
                        "z_loss": sc.z_loss} if sc is not None else {}),
                    **({"n_enc_layers": ec.n_enc_layers, "n_dec_layers": ec.n_dec_layers, "vocab": ec.vocab,

@@ -337,8 +337,10 @@ int adafactor_step(float* param, const float* grad, float* v_row, float* v_col, 
  * T5.1.1-Small/Base sizes.  Each entry is what adafactor_step takes for one tensor; every tensor
  * gets the same cfg (paper Sec. 4 trains all parameters with one optimizer setting).  workspace: at
  * least adafactor_multi_workspace_bytes() (the per-tensor workspaces back to back).  Results are
- * identical to calling adafactor_step per tensor.
- * Errors: as adafactor_step; n_tensors < 1 -> T5_ERR_SHAPE, > 16 -> T5_ERR_UNSUPPORTED. */
+ * identical to calling adafactor_step per tensor.  Longer lists (all tensors of a stack) are processed
+ * 16 consecutive entries at a time, in stream order, the groups sharing the workspace:
+ * adafactor_multi_workspace_bytes() is the largest group's need.
+ * Errors: as adafactor_step; n_tensors < 1 -> T5_ERR_SHAPE, > 65536 -> T5_ERR_UNSUPPORTED. */
 typedef struct {
   float* param;
   const float* grad;

@@ -8,6 +8,10 @@ std::vector<StepRec> g_recs;
 SideStream g_side;
 }  // namespace t5mi
 
+namespace {
+constexpr int kAfMaxListed = 1 << 16;  // tensors one adafactor_step_multi call may list
+}
+
 extern "C" {
 
 const char* t5_status_string(int s) {
@@ -257,39 +261,48 @@ int adafactor_step(float* param, const float* grad, float* v_row, float* v_col, 
   return T5_OK;
 }
 
+// Tensors are processed in groups of AF_MAX_TENSORS consecutive entries (one launch sequence each, in
+// stream order), so the groups share one workspace: the largest group's.
 size_t adafactor_multi_workspace_bytes(const adafactor_tensor* t, int n) {
-  if (!t || n < 1 || n > AF_MAX_TENSORS) return 0;
-  size_t total = 0;
-  for (int i = 0; i < n; ++i) {
-    if (t[i].rows < 1 || t[i].cols < 1) return 0;
-    total += adafactor_ws_bytes(t[i].rows, t[i].cols, t[i].factored);
+  if (!t || n < 1 || n > kAfMaxListed) return 0;
+  size_t need = 0;
+  for (int i0 = 0; i0 < n; i0 += AF_MAX_TENSORS) {
+    size_t total = 0;
+    for (int i = i0; i < n && i < i0 + AF_MAX_TENSORS; ++i) {
+      if (t[i].rows < 1 || t[i].cols < 1) return 0;
+      total += adafactor_ws_bytes(t[i].rows, t[i].cols, t[i].factored);
+    }
+    need = total > need ? total : need;
   }
-  return total;
+  return need;
 }
 
 int adafactor_step_multi(const adafactor_tensor* t, int n, const adafactor_cfg* cfg, void* workspace,
                          size_t workspace_bytes, void* stream) {
   if (!cfg || !t) return T5_ERR_NULL;
   if (n < 1) return T5_ERR_SHAPE;
-  if (n > AF_MAX_TENSORS) return T5_ERR_UNSUPPORTED;
+  if (n > kAfMaxListed) return T5_ERR_UNSUPPORTED;
   if (cfg->step < 1 || !(cfg->clip > 0.f) || !(cfg->eps1 >= 0.f)) return T5_ERR_SHAPE;
   if (!(cfg->beta1 >= 0.f && cfg->beta1 < 1.f) || !(cfg->weight_decay >= 0.f)) return T5_ERR_SHAPE;
-  AfTensor items[AF_MAX_TENSORS];
-  size_t need = 0;
-  for (int i = 0; i < n; ++i) {
+  for (int i = 0; i < n; ++i) {  // every entry is checked before the first launch
     if (t[i].rows < 1 || t[i].cols < 1) return T5_ERR_SHAPE;
     if (t[i].rows > (1 << 24) || t[i].cols > (1 << 24)) return T5_ERR_UNSUPPORTED;
     if (!t[i].param || !t[i].grad) return T5_ERR_NULL;
     if (t[i].factored ? (!t[i].v_row || !t[i].v_col) : !t[i].v_full) return T5_ERR_NULL;
     if (cfg->beta1 > 0.f && !t[i].m) return T5_ERR_NULL;
-    need += adafactor_ws_bytes(t[i].rows, t[i].cols, t[i].factored);
-    items[i] = AfTensor{t[i].param, t[i].grad, t[i].v_row, t[i].v_col, t[i].v_full, t[i].rows, t[i].cols,
-                        t[i].factored, t[i].bf16_copy_out, t[i].m};
   }
   if (!workspace) return T5_ERR_NULL;
-  if (workspace_bytes < need) return T5_ERR_WORKSPACE;
+  if (workspace_bytes < adafactor_multi_workspace_bytes(t, n)) return T5_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
-  T5_STEP("adafactor", launch_adafactor_multi(items, n, *cfg, workspace, st));
+  for (int i0 = 0; i0 < n; i0 += AF_MAX_TENSORS) {
+    AfTensor items[AF_MAX_TENSORS];
+    const int m = n - i0 < AF_MAX_TENSORS ? n - i0 : AF_MAX_TENSORS;
+    for (int i = 0; i < m; ++i) {
+      const adafactor_tensor& a = t[i0 + i];
+      items[i] = AfTensor{a.param, a.grad, a.v_row, a.v_col, a.v_full, a.rows, a.cols, a.factored, a.bf16_copy_out, a.m};
+    }
+    T5_STEP("adafactor", launch_adafactor_multi(items, m, *cfg, workspace, st));
+  }
   return T5_OK;
 }
 

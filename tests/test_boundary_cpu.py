@@ -219,7 +219,9 @@ def test_adafactor_multi_validation():
     assert lib.adafactor_step_multi(arr, 2, None, dummy, need, None) == 1
     assert lib.adafactor_step_multi(None, 2, C.byref(ok), dummy, need, None) == 1
     assert lib.adafactor_step_multi(arr, 0, C.byref(ok), dummy, need, None) == 2
-    assert lib.adafactor_step_multi(arr, 17, C.byref(ok), dummy, need, None) == 3
+    assert lib.adafactor_step_multi(arr, (1 << 16) + 1, C.byref(ok), dummy, need, None) == 3
+    many = (B._AfTensor * 40)(*([arr[0]] * 40))         # groups of 16: the workspace is the largest group's
+    assert lib.adafactor_multi_workspace_bytes(many, 40) == 16 * lib.adafactor_workspace_bytes(8, 8, 1)
     assert lib.adafactor_step_multi(arr, 2, C.byref(ok), dummy, need - 1, None) == 4
     assert lib.adafactor_step_multi(arr, 2, C.byref(ok), None, need, None) == 1
     bad = (B._AfTensor * 1)()

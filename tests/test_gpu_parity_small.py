@@ -143,6 +143,23 @@ def test_adafactor_multi_matches_single_and_oracle():
             assert rel_err(to_np(b["param"]), ref[k][0])[0] <= 1e-5, (t, k)
 
 
+def test_adafactor_multi_long_list():
+    # 37 tensors in one call: three groups of up to 16, sharing the workspace; each equals the oracle
+    P = _P()
+    shapes = [(8 + 3 * k, 24 + 5 * (k % 7), k % 3 != 0) for k in range(37)]
+    items, ref = [], []
+    for k, (rows, cols, fact) in enumerate(shapes):
+        p, g = SI.make_adafactor_case(rows, cols, seed=700 + k)
+        items.append(dict(param=torch.from_numpy(p.astype(np.float32)).cuda(), grad=torch.from_numpy(g.astype(np.float32)).cuda(),
+                          factored=fact, v_row=torch.zeros(rows, device="cuda"), v_col=torch.zeros(cols, device="cuda"),
+                          v_full=torch.zeros(rows, cols, device="cuda")))
+        ref.append(O.adafactor_step(p, g, O.adafactor_zero_state(rows, cols, fact), step=1, lr=0.01, factored=fact)[0])
+    P.adafactor_step_multi(items, step=1, lr=0.01)
+    torch.cuda.synchronize()
+    for k, d in enumerate(items):
+        assert rel_err(to_np(d["param"]), ref[k])[0] <= 1e-5, k
+
+
 def test_adafactor_momentum_and_weight_decay():
     # momentum buffers and decoupled decay through the batched entry point, four steps, against the oracle;
     # weight decay alone also through the single-tensor entry point
