@@ -116,3 +116,25 @@ def test_captured_pass_stays_on_the_callers_stream(overlap):
         assert torch.equal(graph["dx"], eager["dx"]), rep
         for k in eager["grads"]:
             _close(graph["grads"][k], eager["grads"][k], (rep, k))
+
+
+def test_encdec_overlapped_equals_serial(overlap):
+    import test_gpu_parity_stack as TS
+    P = overlap
+    ec = TS.EC_BF16[0]
+    w = SI.make_encdec_weights(ec)
+    SI.make_encdec_random_scales(ec, w)
+    enc_tokens, dec_tokens, targets = SI.make_encdec_tokens(ec, ignore_fraction=0.15)
+    dw, te, td, tg = TS._ec_upload(ec, w, enc_tokens, dec_tokens, targets)
+    l1, g1 = P.t5_encdec_loss_and_grad(ec, te, td, tg, dw)
+    torch.cuda.synchronize()
+    P.t5_wgrad_overlap_enable(False)
+    l0, g0 = P.t5_encdec_loss_and_grad(ec, te, td, tg, dw)
+    torch.cuda.synchronize()
+    assert float(l1.item()) == float(l0.item())
+    for k in [k for k in g0 if not k.endswith("_layers")]:
+        _close(g1[k], g0[k], k)
+    for side in ("enc_layers", "dec_layers"):
+        for l in range(len(g0[side])):
+            for k in g0[side][l]:
+                _close(g1[side][l][k], g0[side][l][k], (side, l, k))
