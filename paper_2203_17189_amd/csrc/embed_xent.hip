@@ -249,8 +249,8 @@ __global__ __launch_bounds__(256) void dropout_keep_kernel(DropSite d, int64_t r
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void dropout_apply_kernel(DropSite d, const T* __restrict__ in, T* __restrict__ out,
-                                                             int64_t rows, int cols) {
+// in and out may be the same buffer (a stack drops its end activations in place): no __restrict__.
+__global__ __launch_bounds__(256) void dropout_apply_kernel(DropSite d, const T* in, T* out, int64_t rows, int cols) {
   const int lane = threadIdx.x & 63;
   for (int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); r < rows; r += (int64_t)gridDim.x * 4) {
     const uint32_t k1 = drop_row_key(d, (uint32_t)r);
