@@ -70,12 +70,13 @@ def test_config_literal_unscaled_logits(name, b0):
         assert e[0] <= TOL_BF16_DW[0] * amp and e[1] <= TOL_BF16_DW[1] * amp, (k, e)
 
 
-def test_bench_workload_full_batch_sampled():
-    """c2_small at its full batch, as bench.py launches it: the first 2 sequences against the oracle,
-    run-to-run determinism of y and dx, and causal-free structure checks."""
+@pytest.mark.parametrize("name,b0", [("c2_small", 2), ("c3_base", 1), ("c4_gpt_causal", 1), ("c5_xl", 1)])
+def test_bench_workload_full_batch_sampled(name, b0):
+    """A workload at its full batch, as bench.py launches it: the first b0 sequences against the oracle
+    (sequences are independent through the block), run-to-run determinism of y and dx, finite gradients and
+    the zero column sums of the bias-table gradient."""
     import paper_2203_17189_amd as P
-    cfg = _scaled(SI.CONFIGS["c2_small"])
-    b0 = 2
+    cfg = _scaled(SI.CONFIGS[name])
     w = SI.make_weights(cfg)
     x, dy = SI.make_activations(cfg)
     small = cfg.with_batch(b0)
@@ -89,7 +90,7 @@ def test_bench_workload_full_batch_sampled():
     gdx2, _ = P.t5_block_bwd(cfg, tdy, tx, dw, stash2)
     torch.cuda.synchronize()
     ey, edx = rel_err(to_np(gy[:b0]), y), rel_err(to_np(gdx[:b0]), dx)
-    print("full batch sample: y", ey, "dx", edx)
+    print(name, "full batch sample: y", ey, "dx", edx)
     assert ey[0] <= TOL_BF16_ACT[0] and ey[1] <= TOL_BF16_ACT[1], ey
     assert edx[0] <= TOL_BF16_DX_NAMED[0] and edx[1] <= TOL_BF16_DX_NAMED[1], edx
     assert torch.equal(gy, gy2) and torch.equal(gdx, gdx2)          # y, dx use no atomics
