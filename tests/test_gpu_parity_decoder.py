@@ -82,6 +82,28 @@ def test_decoder_named_config_reduced_batch():
     _check(cfg, TOL_BF16_ACT, TOL_BF16_DEC_DX_NAMED, TOL_BF16_DENC_NAMED, TOL_BF16_DW_NAMED)
 
 
+def test_decoder_named_config_full_batch_sampled():
+    """c6_dec_base at its full batch, as bench.py launches it: the first sequence's y, dx and denc against the
+    oracle (sequences, each with its own encoder output, are independent through the layer)."""
+    import paper_2203_17189_amd as P
+    cfg = replace(SI.CONFIGS["c6_dec_base"], attn_scale=64 ** -0.5)
+    w, x, enc, dy = make_decoder_case(cfg)
+    small = cfg.with_batch(1)
+    y, saved = O.decoder_block_fwd(small, x[:1], enc[:1], w)
+    dx, denc, _ = O.decoder_block_bwd(small, dy[:1], w, saved)
+    dw = {k: to_dev(v, cfg.dtype) for k, v in w.items()}
+    tx, te, tdy = to_dev(x, cfg.dtype), to_dev(enc, cfg.dtype), to_dev(dy, cfg.dtype)
+    gy, stash = P.t5_decoder_block_fwd(cfg, tx, te, dw)
+    gdx, gdenc, gg = P.t5_decoder_block_bwd(cfg, tdy, tx, te, dw, stash)
+    torch.cuda.synchronize()
+    ey, edx, ede = rel_err(to_np(gy[:1]), y), rel_err(to_np(gdx[:1]), dx), rel_err(to_np(gdenc[:1]), denc)
+    print("c6_dec_base full batch sample: y", ey, "dx", edx, "denc", ede)
+    assert ey[0] <= TOL_BF16_ACT[0] and ey[1] <= TOL_BF16_ACT[1], ey
+    assert edx[0] <= TOL_BF16_DEC_DX_NAMED[0] and edx[1] <= TOL_BF16_DEC_DX_NAMED[1], edx
+    assert ede[0] <= TOL_BF16_DENC_NAMED[0] and ede[1] <= TOL_BF16_DENC_NAMED[1], ede
+    assert all(torch.isfinite(v).all() for v in gg.values())
+
+
 def test_decoder_accumulate_and_determinism():
     import paper_2203_17189_amd as P
     cfg = SMALL_BF16[0]
