@@ -2,7 +2,9 @@
  * t5mi.h - C ABI of the MI355X (gfx950) implementation of one T5.1.1-style
  * Transformer block (encoder layer, decoder-only layer, or encoder-decoder
  * decoder layer with cross-attention): forward, backward, relative-position
- * buckets and the Adafactor update of its weights.
+ * buckets and the Adafactor update of its weights; of whole stacks of such
+ * layers with embedding, final norm, logits and loss (one stack, or the
+ * encoder-decoder pair); and of the dropout mask generator they share.
  *
  * The paper (Sec. 4, "Example models") ships T5.1.1 and a decoder-only model as
  * its reference architectures and Sec. 2.3 describes them as ordinary layer
@@ -17,7 +19,9 @@
  *   - the library allocates nothing: scratch comes from the caller's workspace,
  *     whose size is returned by the *_bytes() queries (0 on an invalid config);
  *   - all device work is enqueued on `stream` (a hipStream_t passed as void*;
- *     NULL = the default stream) and the call returns without synchronising;
+ *     NULL = the default stream) and the call returns without synchronising
+ *     (after t5_wgrad_overlap_enable(1) the backward passes also use one stream
+ *     of the library's own, ordered against `stream` with events);
  *   - arguments are validated before the first HIP call, so error paths can be
  *     exercised on a host without a GPU.
  */
