@@ -337,35 +337,10 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnIO io, const 
 }
 
 // ------------------------------------------------------------------------------------------------
-// dvec[b,h,i] = sum_c dO[b,i,h,c] * O[b,i,h,c].  One wave per 64/DK*... rows: lane handles 8 channels.
-// ------------------------------------------------------------------------------------------------
-template <int DK>
-__global__ __launch_bounds__(256) void attn_dvec_kernel(const bf16* __restrict__ o, const bf16* __restrict__ dout,
-                                                        float* __restrict__ dvec, AttnDims a) {
-  constexpr int LPR = DK / 8;  // lanes per (token, head) row
-  const int64_t rows = (int64_t)a.B * a.S * a.H;
-  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t row = gid / LPR;
-  const int part = (int)(gid % LPR);
-  float s = 0.f;
-  if (row < rows) {
-    const bf16x8 x = *reinterpret_cast<const bf16x8*>(o + row * DK + part * 8);
-    const bf16x8 y = *reinterpret_cast<const bf16x8*>(dout + row * DK + part * 8);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) s += (float)x[e] * (float)y[e];
-  }
-#pragma unroll
-  for (int off = LPR / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-  if (row < rows && part == 0) {
-    const int64_t tok = row / a.H;
-    const int hh = (int)(row % a.H);
-    const int64_t bb = tok / a.S, ii = tok % a.S;
-    dvec[(bb * a.H + hh) * a.S + ii] = s;
-  }
-}
-
-// ------------------------------------------------------------------------------------------------
-// dq and the per-diagonal bias gradient.  Same ownership as the forward (lane = query).
+// dq and the per-diagonal bias gradient.  Same ownership as the forward (lane = query).  The kernel also
+// forms dvec[b,h,i] = sum_c dO[b,i,h,c] * O[b,i,h,c] for its query -- the two lane halves hold the two halves
+// of the dO row as MFMA operands already, so it costs one read of the O row -- and writes it for the
+// dk/dv kernel, which runs after this one.
 //
 // Bias gradient: ddiag[delta] = sum over (b, i) of ds[i, i + delta].  In the MFMA result layout a
 // register holds one key offset for 32 queries, i.e. 32 consecutive diagonals, and a different
@@ -381,10 +356,11 @@ __global__ __launch_bounds__(256) void attn_dvec_kernel(const bf16* __restrict__
 // ------------------------------------------------------------------------------------------------
 template <int DK, bool CAUSAL, bool BIAS, bool DROP>
 __global__ __launch_bounds__(256, DK == 64 && !DROP ? 3 : 2) void attn_bwd_dq_mfma_kernel(AttnIO io,
+                                                               const bf16* __restrict__ o,
                                                                const bf16* __restrict__ dout,
                                                                const float* __restrict__ diag,
                                                                const float* __restrict__ lse,
-                                                               const float* __restrict__ dvec,
+                                                               float* __restrict__ dvec,
                                                                float* __restrict__ ddiag,
                                                                AttnDims a, int far) {
   constexpr int BR = 128, BC = 64, KS = DK / 16, CT = DK / 32;
@@ -414,17 +390,24 @@ __global__ __launch_bounds__(256, DK == 64 && !DROP ? 3 : 2) void attn_bwd_dq_mf
   float* ddgw = ddg_all + (wave * 2 + g) * W + (31 - i_lw);  // this lane's first slot of block m = -nb
 
   bf16x8 qf[KS], dof[KS];
+  float dsum = 0.f;  // this lane half's share of sum_c dO * O
   {
     const bf16* qrow = (const bf16*)io.q + ((size_t)b * S + i) * ldq + h * DK;
     const bf16* drow = dout + ((size_t)b * S + i) * I + h * DK;
+    const bf16* orow = o + ((size_t)b * S + i) * I + h * DK;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
       qf[kk] = *reinterpret_cast<const bf16x8*>(qrow + kk * 16 + g * 8);
       dof[kk] = *reinterpret_cast<const bf16x8*>(drow + kk * 16 + g * 8);
+      const bf16x8 of = *reinterpret_cast<const bf16x8*>(orow + kk * 16 + g * 8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dsum = fmaf((float)of[e], (float)dof[kk][e], dsum);
     }
   }
+  dsum += __shfl_xor(dsum, 32, 64);
   const size_t srow = ((size_t)b * a.H + h) * S + i;
-  const float nlse2 = -lse[srow] * kLog2e, ndv = -dvec[srow];
+  if (g == 0) dvec[srow] = dsum;
+  const float nlse2 = -lse[srow] * kLog2e, ndv = -dsum;
   uint32_t k1 = 0;  // dropout row key of this lane's query
   if constexpr (DROP) k1 = drop_row_key(a.drop, (uint32_t)srow);
   // dP of a kept probability carries the factor 1/(1 - rate); that of a dropped one is zero
@@ -789,16 +772,11 @@ template <int DK, bool CAUSAL, bool BIAS, bool DROP = false>
 hipError_t bwd_launch(const AttnIO& io, const void* c, const void* dc, const float* diag, const float* lse,
                       float* dvec, float* ddiag, const AttnDims& a, int far, int phase, hipStream_t st) {
   hipError_t e = hipSuccess;
-  if (phase == 0) {
-    const int64_t rows = (int64_t)a.B * a.S * a.H;
-    attn_dvec_kernel<DK><<<ceil_div(rows * (DK / 8), 256), 256, 0, st>>>((const bf16*)c, (const bf16*)dc, dvec, a);
-    return hipGetLastError();
-  }
   if (phase == 1) {
     auto kern = attn_bwd_dq_mfma_kernel<DK, CAUSAL, BIAS, DROP>;
     const size_t lds = attn_bwd_dq_lds_bytes(a, far);
     if ((e = set_lds(kern, lds)) != hipSuccess) return e;
-    kern<<<dim3((a.S / 128) * a.H * a.B), 256, lds, st>>>(io, (const bf16*)dc, diag, lse, dvec, ddiag, a, far);
+    kern<<<dim3((a.S / 128) * a.H * a.B), 256, lds, st>>>(io, (const bf16*)c, (const bf16*)dc, diag, lse, dvec, ddiag, a, far);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (phase == 2) {
@@ -856,7 +834,8 @@ hipError_t launch_attn_fwd_mfma(const AttnIO& io, const float* diag, void* c, fl
 hipError_t launch_attn_bwd_mfma(const AttnIO& io, const void* c, const void* dc, const float* diag,
                                 const float* lse, float* dvec, float* ddiag, const AttnDims& a, int far,
                                 int phase, hipStream_t st) {
-  // phase 0: dvec = rowsum(dO * O); phase 1: dq + bias-gradient diagonals (added into ddiag); phase 2: dk, dv.
+  // phase 1: dq, dvec = rowsum(dO * O) and the bias-gradient diagonals (added into ddiag); phase 2: dk, dv
+  // (reads the dvec phase 1 wrote).
   // `far`: smallest distance that falls in the last (saturated) bucket; such offsets need no
   // per-diagonal resolution.  Never below 1, so offset 0 always takes the per-diagonal path.
   if (!attn_mfma_supported(a)) return hipErrorInvalidValue;

@@ -553,7 +553,6 @@ int bwd_cross_attn(const t5_block_cfg* cfg, const Dims& D, const void* enc, cons
   }
   const AttnIO io = cross_io(D, S, &W);
   if (ty == IN_BF16 && attn_mfma_supported(ad)) {
-    T5_STEP("xattn_bwd_prep", launch_attn_bwd_mfma(io, S.cx, W.dc, nullptr, S.lse_x, W.dvec, nullptr, ad, 1, 0, st));
     T5_STEP("xattn_bwd_dq", launch_attn_bwd_mfma(io, S.cx, W.dc, nullptr, S.lse_x, W.dvec, nullptr, ad, 1, 1, st));
     T5_STEP("xattn_bwd_dkv", launch_attn_bwd_mfma(io, S.cx, W.dc, nullptr, S.lse_x, W.dvec, nullptr, ad, 1, 2, st));
   } else {
@@ -620,7 +619,6 @@ int bwd_self_attn(const t5_block_cfg* cfg, const Dims& D, const RelposLut& lut, 
   }
   const AttnIO io = attn_io_packed(S.qkv, W.dqkv, D.I, es);
   if (attn_mfma) {
-    T5_STEP("attn_bwd_prep", launch_attn_bwd_mfma(io, S.c, W.dc, S.diag, S.lse, W.dvec, W.ddiag, ad, far, 0, st));
     T5_STEP("attn_bwd_dq", launch_attn_bwd_mfma(io, S.c, W.dc, S.diag, S.lse, W.dvec, W.ddiag, ad, far, 1, st));
     T5_STEP("attn_bwd_dkv", launch_attn_bwd_mfma(io, S.c, W.dc, S.diag, S.lse, W.dvec, W.ddiag, ad, far, 2, st));
   } else {

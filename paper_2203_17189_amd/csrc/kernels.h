@@ -158,8 +158,8 @@ hipError_t launch_attn_fwd_mfma(const AttnIO& io, const float* diag, void* c, fl
 // Whether the backward kernels take this problem with `far` (smallest distance in the saturated last
 // bucket); otherwise the simple backward is used (same saved tensors).
 bool attn_bwd_mfma_fits(const AttnDims& a, int far);
-// phase 0: dvec = rowsum(dO * O); phase 1: dq and the bias-gradient diagonals, ADDED into ddiag (the
-// caller clears it); phase 2: dk, dv.
+// phase 1: dq, dvec = rowsum(dO * O) and the bias-gradient diagonals, ADDED into ddiag (the caller clears
+// it); phase 2: dk, dv (reads dvec, so it runs after phase 1).
 hipError_t launch_attn_bwd_mfma(const AttnIO& io, const void* c, const void* dc, const float* diag,
                                 const float* lse, float* dvec, float* ddiag, const AttnDims& a, int far,
                                 int phase, hipStream_t st);
