@@ -329,6 +329,11 @@ def main() -> int:
         flops = {k: v for k, v in flops.items() if k.startswith(("gemm_x", "xattn", "gemm_dx", "gemm_dcx", "gemm_denc",
                                                                  "gemm_dnx", "gemm_logits", "gemm_dnf", "gemm_dlogits"))}
     per_kernel = {k: {"avg_ms": v[0] / v[1], "launches_per_step": v[1] / n_prof} for k, v in timing.items()}
+    # a stack launches the weight-gradient GEMMs of all its layers together: one launch does n_layers problems
+    n_lay = sc.n_layers if sc is not None else (ec.n_dec_layers if ec is not None else 1)
+    for k in ("gemm_dwo_ff", "gemm_dwi", "gemm_dwo", "gemm_dwqkv", "gemm_dxo", "gemm_dxq", "gemm_dxkv"):
+        if k in flops and k in per_kernel and n_lay > 1 and per_kernel[k]["launches_per_step"] < n_lay:
+            flops[k] *= n_lay / per_kernel[k]["launches_per_step"]
     step_ms = {k: v["avg_ms"] * v["launches_per_step"] for k, v in per_kernel.items()}
     fwd_names = {"relpos_diag", "rmsnorm_fwd", "pack_weights", "gemm_qkv", "attn_fwd", "gemm_o", "gemm_wi_geglu",
                  "gemm_wi", "geglu_fwd", "gemm_wo", "gemm_xq", "gemm_xkv", "xattn_fwd", "gemm_xo"}

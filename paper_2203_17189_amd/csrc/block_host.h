@@ -184,6 +184,9 @@ inline hipStream_t wgrad_stream(const Fork& f) { return f.on ? f.side : f.main; 
 
 struct BwdWs {
   Fork fork;
+  // set by a stack that launches the weight-gradient GEMMs of all its layers together after the sweep: the
+  // layer functions then skip theirs and leave the operands (duw, dh_lp / dh1_lp, dqkv, dqx, dkvx) in place
+  bool defer_wgrad = false;
   float *dn, *dh, *dvec, *ddiag, *dg_partial;
   void *dh_lp, *duw, *dc, *dqkv;  // duw: [T][2F], du in columns 0..F-1, dw in F..2F-1
   // cross-attention sublayer: dh/dh_lp hold the gradient of h2, dh1/dh1_lp that of h
@@ -470,7 +473,7 @@ int bwd_mlp(const Dims& D, const void* dy, const float* hin, const t5_block_weig
     T5_STEP("dropout_dy", launch_dropout_apply(drop_site(D, DROP_MLP_OUT), dy, W.dmask, ty, T, D.d, st));
     dy = W.dmask;
   }
-  {  // dWo_ff = a^T dy
+  if (!W.defer_wgrad) {  // dWo_ff = a^T dy
     T5_TRY(fork_sync(W.fork));
     hipStream_t st = wgrad_stream(W.fork);
     GemmDesc g = gemm1(D.F, D.d, T, S.a, D.F, 0, dy, D.d, 0, ty);
@@ -485,7 +488,7 @@ int bwd_mlp(const Dims& D, const void* dy, const float* hin, const t5_block_weig
       e.aux0 = S.a; e.aux_type = ty; e.aux_mask = 1; e.drop = drop_site(D, DROP_MLP_HIDDEN);
       T5_STEP("gemm_da_relu_bwd", run_gemm(g, e, st));
     }
-    {  // dWi0 = n2^T du
+    if (!W.defer_wgrad) {  // dWi0 = n2^T du
       T5_TRY(fork_sync(W.fork));
       hipStream_t st = wgrad_stream(W.fork);
       GemmDesc g = gemm1(D.d, D.F, T, S.n2, D.d, 0, du_p, D.F, 0, ty);
@@ -504,7 +507,7 @@ int bwd_mlp(const Dims& D, const void* dy, const float* hin, const t5_block_weig
       e.out1 = dw_p; e.aux0 = S.gp; e.aux1 = S.gl; e.aux_type = ty; e.ld_aux = D.F;
       T5_STEP("gemm_da_geglu_bwd", run_gemm(g, e, st));
     }
-    {  // dWi0 | dWi1 = n2^T [du | dw]
+    if (!W.defer_wgrad) {  // dWi0 | dWi1 = n2^T [du | dw]
       T5_TRY(fork_sync(W.fork));
       hipStream_t st = wgrad_stream(W.fork);
       GemmDesc g = gemm1(D.d, 2 * D.F, T, S.n2, D.d, 0, du_p, 2 * D.F, 0, ty);
@@ -539,7 +542,7 @@ int bwd_cross_attn(const t5_block_cfg* cfg, const Dims& D, const void* enc, cons
     T5_STEP("dropout_dh", launch_dropout_apply(drop_site(D, DROP_CROSS_OUT), dh_op, W.dmask, ty, T, D.d, st));
     dh_op = W.dmask;
   }
-  {  // dXo = cx^T dh2
+  if (!W.defer_wgrad) {  // dXo = cx^T dh2
     T5_TRY(fork_sync(W.fork));
     hipStream_t st = wgrad_stream(W.fork);
     GemmDesc g = gemm1(D.I, D.d, T, S.cx, D.I, 0, dh_op, D.d, 0, ty);
@@ -558,7 +561,7 @@ int bwd_cross_attn(const t5_block_cfg* cfg, const Dims& D, const void* enc, cons
   } else {
     T5_STEP("xattn_bwd", launch_attn_bwd_simple(io, S.cx, W.dc, ty, nullptr, S.lse_x, W.dvec, nullptr, ad, 0, st));
   }
-  {  // dXq = nx^T dq
+  if (!W.defer_wgrad) {  // dXq = nx^T dq
     T5_TRY(fork_sync(W.fork));
     hipStream_t st = wgrad_stream(W.fork);
     GemmDesc g = gemm1(D.d, D.I, T, S.nx, D.d, 0, W.dqx, D.I, 0, ty);
@@ -566,7 +569,7 @@ int bwd_cross_attn(const t5_block_cfg* cfg, const Dims& D, const void* enc, cons
     e.accumulate = 1;
     T5_STEP("gemm_dxq", run_gemm(g, e, st));
   }
-  {  // dXk | dXv = enc^T [dk | dv]   (ordered after dXq on the side stream: no new fork point needed)
+  if (!W.defer_wgrad) {  // dXk | dXv = enc^T [dk | dv]   (ordered after dXq on the side stream: no new fork point needed)
     hipStream_t st = wgrad_stream(W.fork);
     GemmDesc g = gemm1(D.d, 2 * D.I, Te, enc, D.d, 0, W.dkvx, 2 * D.I, 0, ty);
     GemmEpi e = epi(EPI_SPLIT_F32, dxw->xk, D.I, IN_F32);
@@ -605,7 +608,7 @@ int bwd_self_attn(const t5_block_cfg* cfg, const Dims& D, const RelposLut& lut, 
     T5_STEP("dropout_dh", launch_dropout_apply(drop_site(D, DROP_ATTN_OUT), dh_op, W.dmask, ty, T, D.d, st));
     dh_op = W.dmask;
   }
-  {  // dWo = c^T dh
+  if (!W.defer_wgrad) {  // dWo = c^T dh
     T5_TRY(fork_sync(W.fork));
     hipStream_t st = wgrad_stream(W.fork);
     GemmDesc g = gemm1(D.I, D.d, T, S.c, D.I, 0, dh_op, D.d, 0, ty);
@@ -628,7 +631,7 @@ int bwd_self_attn(const t5_block_cfg* cfg, const Dims& D, const RelposLut& lut, 
   // a stack with a shared table keeps adding into W.ddiag over its layers and folds it once at the end
   if (own_table)
     T5_STEP("relpos_diag_bwd", launch_relpos_diag_bwd(W.ddiag, dw->rel_table, D.S, D.H, cfg->num_buckets, lut, acc, st));
-  {  // dWq | dWk | dWv = n1^T dqkv
+  if (!W.defer_wgrad) {  // dWq | dWk | dWv = n1^T dqkv
     T5_TRY(fork_sync(W.fork));
     hipStream_t st = wgrad_stream(W.fork);
     GemmDesc g = gemm1(D.d, 3 * D.I, T, S.n1, D.d, 0, W.dqkv, 3 * D.I, 0, ty);

@@ -104,11 +104,14 @@ __device__ __forceinline__ void cursor_next(KCursor& c, const char*& abase, cons
 // EPI_T: the epilogue kind, plus EPI_DROP when the result passes a dropout site (a separate instantiation,
 // so that the kernels without dropout keep their register budget).
 constexpr int EPI_DROP = 8;
+// ... plus EPI_GROUP for a grouped launch (several problems of one shape, operands from a pointer table).
+constexpr int EPI_GROUP = 16;
 template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int EPI_T, int NS, int MINW, int BK>
 __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc g, GemmEpi e, int tiles_m,
                                                                 int tiles_n, int split_k) {
   constexpr int EPI = EPI_T & (EPI_DROP - 1);
   constexpr bool DROP = (EPI_T & EPI_DROP) != 0;
+  constexpr bool GROUP = (EPI_T & EPI_GROUP) != 0;
   constexpr int NW = WM * WN;
   constexpr int TMW = BM / WM, TNW = BN / WN;
   constexpr int MI = TMW / 32, NI = TNW / 32;
@@ -131,13 +134,26 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
   // contiguous chunk of the (k-slice, tile) space so that whole k-slices, and compact blocks of
   // tiles inside them, share operand panels through one L2.
   const int nb = tiles_m * tiles_n;
+  const int ngr = GROUP ? g.ngroups : 1;
   int L;
   {
-    const int total = nb * split_k;
+    const int total = nb * split_k * ngr;
     const int bid = blockIdx.x;
     const int xcd = bid & 7, idx = bid >> 3;
     const int nb8 = (total + 7) >> 3, rem = total & 7;
     if (rem == 0 || xcd < rem) L = xcd * nb8 + idx; else L = rem * nb8 + (xcd - rem) * (nb8 - 1) + idx;
+  }
+  // grouped launch: the problem this workgroup belongs to, and its operands and outputs
+  const void *seg_a = g.seg[0].A, *seg_b = g.seg[0].B;
+  void *so0 = e.out0, *so1 = e.out1, *so2 = e.out2;
+  if constexpr (GROUP) {
+    {
+      const int grp = L / (nb * split_k);
+      L -= grp * nb * split_k;
+      const void* const* t = g.groups + (size_t)grp * GEMM_GROUP_PTRS;
+      seg_a = t[0]; seg_b = t[1];
+      so0 = const_cast<void*>(t[2]); so1 = const_cast<void*>(t[3]); so2 = const_cast<void*>(t[4]);
+    }
   }
   const int ks = L / nb;  // split-k slice
   L -= ks * nb;
@@ -212,8 +228,8 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
   kc.ra1 = kc.rb1 = kc.ra2 = kc.rb2 = nullptr;
   kc.rn1 = kc.rn2 = 0;
   if (g.nseg == 1) {
-    kc.ra0 = (const char*)g.seg[0].A + (size_t)kt_begin * kc.step_a;
-    kc.rb0 = (const char*)g.seg[0].B + (size_t)kt_begin * kc.step_b;
+    kc.ra0 = (const char*)seg_a + (size_t)kt_begin * kc.step_a;
+    kc.rb0 = (const char*)seg_b + (size_t)kt_begin * kc.step_b;
     kc.rn0 = nk;
   } else {  // several segments are never split along k
     kc.ra0 = (const char*)g.seg[0].A; kc.rb0 = (const char*)g.seg[0].B; kc.rn0 = g.seg[0].K / BK;
@@ -230,7 +246,16 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
   }
   // Issue DMA instructions [d0, d1) of a k-tile into stage `st`; a tile's DMA_PER_TILE instructions
   // per wave are numbered A slots first, then B slots.
+  // The DMA instructions take their base address from scalar registers.  Addresses that came out of a group
+  // table are the same in every lane but live in vector registers: broadcast them from the first lane.
+  auto uniform = [](const char* q) {
+    const uint64_t v = (uint64_t)q;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (const char*)(((uint64_t)hi << 32) | lo);
+  };
   auto dma_part = [&](const char* abase, const char* bbase, int st, int d0, int d1) {
+    if constexpr (GROUP) { abase = uniform(abase); bbase = uniform(bbase); }
     const uint32_t sa = lds0 + st * STAGE, sb = sa + A_BYTES;
 #pragma unroll
     for (int d = 0; d < DMA_PER_TILE; ++d) {
@@ -334,7 +359,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
       if (interior && split_k > 1) {
         const int cl = lane & 31, rl = (lane >> 5) << 2;
         const int which = nw / e.split_n;
-        float* dst0 = (float*)(which == 0 ? e.out0 : which == 1 ? e.out1 : e.out2) + (nw - which * e.split_n) + cl;
+        float* dst0 = (float*)(which == 0 ? so0 : which == 1 ? so1 : so2) + (nw - which * e.split_n) + cl;
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -413,7 +438,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
         float* split_dst = nullptr;
         if constexpr (EPI == EPI_SPLIT_F32) {
           const int which = nw / e.split_n;
-          split_dst = (float*)(which == 0 ? e.out0 : which == 1 ? e.out1 : e.out2) + (nw - which * e.split_n) + c4 +
+          split_dst = (float*)(which == 0 ? so0 : which == 1 ? so1 : so2) + (nw - which * e.split_n) + c4 +
                       (size_t)(mw + lane / LPR) * e.ld0;
         }
         // The auxiliary operands (residual; saved gated-GELU factors) come from HBM with a latency of a
@@ -578,7 +603,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
             ((bf16*)e.out1)[o] = (bf16)(v * gl);
           } else {  // EPI_SPLIT_F32
             const int which = n / e.split_n, nn = n - which * e.split_n;
-            float* dst = (float*)(which == 0 ? e.out0 : which == 1 ? e.out1 : e.out2) + (size_t)m * e.ld0 + nn;
+            float* dst = (float*)(which == 0 ? so0 : which == 1 ? so1 : so2) + (size_t)m * e.ld0 + nn;
             if (split_k > 1) unsafeAtomicAdd(dst, v);
             else *dst = e.accumulate ? *dst + v : v;
           }
@@ -586,6 +611,11 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
       }
     }
   }
+}
+
+struct PtrChunk { const void* p[64]; };
+__global__ void fill_ptrs_kernel(PtrChunk c, int n, const void** dst) {
+  if ((int)threadIdx.x < n) dst[threadIdx.x] = c.p[threadIdx.x];
 }
 
 __global__ void zero_split_kernel(GemmEpi e, int M, int N) {
@@ -610,7 +640,8 @@ hipError_t launch_cfg(const GemmDesc& g, const GemmEpi& e, int split_k, hipStrea
     attr_set = true;
   }
   const int tiles_m = ceil_div(g.M, BM), tiles_n = ceil_div(g.N, BN);
-  kern<<<tiles_m * tiles_n * split_k, WM * WN * 64, lds, st>>>(g, e, tiles_m, tiles_n, split_k);
+  const int ngr = (EPI & EPI_GROUP) ? g.ngroups : 1;
+  kern<<<tiles_m * tiles_n * split_k * ngr, WM * WN * 64, lds, st>>>(g, e, tiles_m, tiles_n, split_k);
   return hipGetLastError();
 }
 
@@ -619,8 +650,10 @@ hipError_t launch_layout(const GemmDesc& g, const GemmEpi& e, hipStream_t st) {
   constexpr int EPI = EPI_T & (EPI_DROP - 1);
   int nk = 0;
   for (int s = 0; s < g.nseg; ++s) nk += g.seg[s].K / KQ;
-  const int64_t t256 = (int64_t)ceil_div(g.M, 256) * ceil_div(g.N, 256);
-  const int64_t t128 = (int64_t)ceil_div(g.M, 128) * ceil_div(g.N, 128);
+  // a grouped launch (weight gradients of several layers) counts the tiles of all its problems
+  const int ngr = (EPI_T & EPI_GROUP) ? g.ngroups : 1;
+  const int64_t t256 = (int64_t)ceil_div(g.M, 256) * ceil_div(g.N, 256) * ngr;
+  const int64_t t128 = (int64_t)ceil_div(g.M, 128) * ceil_div(g.N, 128) * ngr;
   bool big = t256 >= 192;
   int split_k = 1;
   if constexpr (EPI == EPI_SPLIT_F32) {
@@ -641,6 +674,7 @@ hipError_t launch_layout(const GemmDesc& g, const GemmEpi& e, hipStream_t st) {
       const double eff = (double)wgs / (double)(((wgs + slots - 1) / slots) * slots) - 0.012 * sp;
       if (eff > best) { best = eff; split_k = sp; }
     }
+    if (ngr > 1 && !e.accumulate) return hipErrorInvalidValue;  // grouped outputs are cleared by the caller
     if (split_k > 1 && !e.accumulate) {
       zero_split_kernel<<<ceil_div((int64_t)g.M * g.N, 256), 256, 0, st>>>(e, g.M, g.N);
       hipError_t err = hipGetLastError();
@@ -696,10 +730,23 @@ bool gemm_mfma_supported(const GemmDesc& g, const GemmEpi& e) {
     case EPI_GEGLU_FWD:
       return g.a_kc == 1 && g.N % 64 == 0 && e.out_type == IN_BF16;
     case EPI_SPLIT_F32:
+      if (g.ngroups > 1 && (!g.groups || !e.accumulate)) return false;
       return g.a_kc == 0 && g.nseg == 1;  // k may be split into slices: one segment only
     default:
       return false;
   }
+}
+
+hipError_t launch_fill_ptrs(const void* const* ptrs, int n, const void** dst, hipStream_t st) {
+  for (int i0 = 0; i0 < n; i0 += 64) {
+    PtrChunk c;
+    const int m = n - i0 < 64 ? n - i0 : 64;
+    for (int i = 0; i < 64; ++i) c.p[i] = i < m ? ptrs[i0 + i] : nullptr;
+    fill_ptrs_kernel<<<1, 64, 0, st>>>(c, m, dst + i0);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+  }
+  return hipSuccess;
 }
 
 hipError_t launch_gemm_mfma(const GemmDesc& g, const GemmEpi& e, hipStream_t st) {
@@ -714,7 +761,9 @@ hipError_t launch_gemm_mfma(const GemmDesc& g, const GemmEpi& e, hipStream_t st)
       return e.drop.on ? launch_layout<true, true, EPI_GEGLU_FWD | EPI_DROP>(g, e, st)
                        : launch_layout<true, true, EPI_GEGLU_FWD>(g, e, st);
     case EPI_GEGLU_BWD: return launch_layout<true, true, EPI_GEGLU_BWD>(g, e, st);
-    case EPI_SPLIT_F32: return launch_layout<false, false, EPI_SPLIT_F32>(g, e, st);
+    case EPI_SPLIT_F32:
+      return g.ngroups > 1 ? launch_layout<false, false, EPI_SPLIT_F32 | EPI_GROUP>(g, e, st)
+                           : launch_layout<false, false, EPI_SPLIT_F32>(g, e, st);
     default: return hipErrorInvalidValue;
   }
 }

@@ -74,7 +74,16 @@ struct GemmDesc {
   GemmSeg seg[3];
   int a_kc, b_kc;
   int in_type;  // element type of A and B
+  // Several problems of one shape in one launch (EPI_SPLIT_F32 with accumulate, one segment, MFMA kernel only):
+  // groups is a DEVICE array of ngroups x GEMM_GROUP_PTRS pointers {A, B, out0, out1, out2}, which replace
+  // seg[0].A / .B and the epilogue's outputs for the workgroups of that problem.  ngroups <= 1: one problem.
+  const void* const* groups;
+  int ngroups;
 };
+constexpr int GEMM_GROUP_PTRS = 5;
+// dst[i] = ptrs[i] for i < n: builds such a table (or any other) in device memory from host values, by kernel
+// (no host-to-device copy: callers may be recording a graph).
+hipError_t launch_fill_ptrs(const void* const* ptrs, int n, const void** dst, hipStream_t st);
 // Simple LDS-tiled FMA kernel: any shape, float32 or bf16 inputs.  Reference-grade speed.
 hipError_t launch_gemm_simple(const GemmDesc& g, const GemmEpi& e, hipStream_t st);
 // bf16 MFMA kernel.  Requires in_type == IN_BF16, every K % 64 == 0, lda/ldb % 8 == 0, N % 64 == 0

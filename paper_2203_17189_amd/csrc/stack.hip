@@ -33,11 +33,54 @@ struct Layers {
   float *diag = nullptr, *ddiag = nullptr;
   void* block_ws = nullptr;
   void *dxa = nullptr, *dxb = nullptr;
+  // Weight gradients of all layers in grouped launches after the backward sweep (see wgrads_grouped_ok):
+  // every layer then keeps its own backward workspace and incoming gradient until the sweep is over.
+  bool grouped = false;
+  void* layer_ws = nullptr;   // L - 1 more backward workspaces (layer L-1 uses block_ws)
+  size_t bwd_ws_each = 0;
+  void* dx_more = nullptr;    // L - 1 more gradient buffers
+  const void** ptr_tab = nullptr;
 
   size_t xbytes() const { return (size_t)D.T * D.d * D.es; }
   void* x_of(int l) const { return (char*)xs + (size_t)l * xbytes(); }
   void* stash_of(int l) const { return (char*)stash + (remat ? 0 : (size_t)l * stash_each); }
 };
+
+// The weight-gradient GEMMs of one layer reduce over that layer's tokens only; at 16 k tokens and less they
+// are short split-k problems that leave the chip half idle.  Launched for all layers at once (same shapes,
+// a pointer table per problem) they fill it without splitting.  That needs every layer's operands alive
+// until the end of the sweep: its saved activations (so: no remat) and its backward workspace.
+constexpr int kWgradKinds = 7;  // wo_ff, wi, wo, wqkv; decoder layers: xo, xq, xkv
+GemmDesc wgrad_desc(const Dims& D, int kind, const void* A, const void* B) {
+  const int T = (int)D.T, Te = (int)D.Te, nf = D.mlp == ACT_RELU ? 1 : 2;
+  switch (kind) {
+    case 0: return gemm1(D.F, D.d, T, A, D.F, 0, B, D.d, 0, D.ty);            // dWo_ff = a^T dy
+    case 1: return gemm1(D.d, nf * D.F, T, A, D.d, 0, B, nf * D.F, 0, D.ty);  // dWi0 | dWi1 = n2^T [du | dw]
+    case 2: return gemm1(D.I, D.d, T, A, D.I, 0, B, D.d, 0, D.ty);            // dWo = c^T dh
+    case 3: return gemm1(D.d, 3 * D.I, T, A, D.d, 0, B, 3 * D.I, 0, D.ty);    // dWq | dWk | dWv = n1^T dqkv
+    case 4: return gemm1(D.I, D.d, T, A, D.I, 0, B, D.d, 0, D.ty);            // dXo = cx^T dh2
+    case 5: return gemm1(D.d, D.I, T, A, D.d, 0, B, D.I, 0, D.ty);            // dXq = nx^T dq
+    default: return gemm1(D.d, 2 * D.I, Te, A, D.d, 0, B, 2 * D.I, 0, D.ty);  // dXk | dXv = enc^T [dk | dv]
+  }
+}
+GemmEpi wgrad_epi(const Dims& D, int kind, float* o0, float* o1, float* o2) {
+  const int ld = kind == 0 || kind == 2 || kind == 4 ? D.d : kind == 1 ? D.F : D.I;
+  GemmEpi e = epi(EPI_SPLIT_F32, o0, ld, IN_F32);
+  e.out1 = o1; e.out2 = o2; e.accumulate = 1;
+  if (kind == 1 && D.mlp != ACT_RELU) e.split_n = D.F;
+  if (kind == 3 || kind == 6) e.split_n = D.I;
+  return e;
+}
+bool wgrads_grouped_ok(const Dims& D, int L, bool remat) {
+  if (D.ty != IN_BF16 || remat || D.drop > 0.f || L < 2 || L > 256) return false;
+  static const long long dummy[4] = {0, 0, 0, 0};
+  for (int kind = 0; kind < (D.Sk > 0 ? kWgradKinds : 4); ++kind) {
+    GemmDesc g = wgrad_desc(D, kind, dummy, dummy);
+    g.groups = (const void* const*)dummy; g.ngroups = L;
+    if (!gemm_mfma_supported(g, wgrad_epi(D, kind, (float*)dummy, (float*)dummy, (float*)dummy))) return false;
+  }
+  return true;
+}
 
 void carve_layers(Carver& cv, Layers& s) {
   const Dims& D = s.D;
@@ -50,6 +93,13 @@ void carve_layers(Carver& cv, Layers& s) {
   s.block_ws = cv.take(f > b ? f : b);
   s.dxa = cv.take(s.xbytes());
   s.dxb = cv.take(s.xbytes());
+  s.grouped = wgrads_grouped_ok(D, s.L, s.remat);
+  if (s.grouped) {
+    s.bwd_ws_each = b;
+    s.layer_ws = cv.take(b * (size_t)(s.L - 1));
+    s.dx_more = cv.take(s.xbytes() * (size_t)(s.L - 1));
+    s.ptr_tab = cv.take<const void*>(sizeof(void*) * kWgradKinds * GEMM_GROUP_PTRS * (size_t)s.L);
+  }
 }
 
 // Copies the caller's per-layer pointer structs, pointing every layer at the stack's shared table.
@@ -132,10 +182,20 @@ int layers_backward(const Layers& s, const void* enc_out, float* denc_acc, int a
   const Dims& D = s.D;
   const int ty = D.ty;
   const bool dec = D.Sk > 0;
-  BwdWs BW;
-  carve_bwd(D, s.block_ws, &BW);
-  BW.ddiag = s.ddiag;
-  BW.fork = fork_begin(st, D.drop == 0.f);
+  // one backward workspace, or (grouped weight gradients) one per layer; likewise the gradient buffers
+  const int nws = s.grouped ? s.L : 1;
+  std::vector<BwdWs> bws(nws);
+  for (int i = 0; i < nws; ++i) {
+    carve_bwd(D, i == 0 ? s.block_ws : (void*)((char*)s.layer_ws + (size_t)(i - 1) * s.bwd_ws_each), &bws[i]);
+    bws[i].ddiag = s.ddiag;
+    bws[i].defer_wgrad = s.grouped;
+    if (!s.grouped) bws[i].fork = fork_begin(st, D.drop == 0.f);
+  }
+  const int nring = s.grouped ? s.L + 1 : 2;
+  auto ring = [&](int i) -> void* {
+    const int q = i % nring;
+    return q == 0 ? s.dxa : q == 1 ? s.dxb : (void*)((char*)s.dx_more + (size_t)(q - 2) * s.xbytes());
+  };
   {
     ZeroList z;
     std::memset(&z, 0, sizeof(z));
@@ -145,9 +205,11 @@ int layers_backward(const Layers& s, const void* enc_out, float* denc_acc, int a
   const AttnDims ad = self_dims(s.bc, D);
   const int far = s.lut.n_thr > 0 ? s.lut.thr[s.lut.n_thr - 1] : s.lut.max_exact;
   const bool attn_mfma = ty == IN_BF16 && attn_mfma_supported(ad) && attn_bwd_mfma_fits(ad, far);
-  void* dy = s.dxa;
-  void* dx = s.dxb;
   for (int l = s.L - 1; l >= 0; --l) {
+    const int n = s.L - 1 - l;  // layers processed so far
+    BwdWs& BW = bws[s.grouped ? n : 0];
+    void* dy = ring(n);
+    void* dx = ring(n + 1);
     if (s.remat) T5_SUB(layer_forward(s, l, enc_out, st));  // rebuilds layer l's saved activations
     t5_block_cfg bc;
     Dims D;  // this layer's (its dropout seed differs from the stack's)
@@ -168,11 +230,48 @@ int layers_backward(const Layers& s, const void* enc_out, float* denc_acc, int a
     }
     // the next layer rewrites the workspace (and, with remat, the stash) the side GEMMs read
     T5_TRY(fork_join(BW.fork));
-    std::swap(dy, dx);
+  }
+  if (s.grouped) {
+    // one launch per kind of weight over all layers: problem n is layer L-1-n
+    std::vector<const void*> tab((size_t)kWgradKinds * s.L * GEMM_GROUP_PTRS, nullptr);
+    const int kinds = dec ? kWgradKinds : 4;
+    for (int n = 0; n < s.L; ++n) {
+      const int l = s.L - 1 - n;
+      Stash S;
+      carve_stash(D, s.stash_of(l), &S);
+      const BwdWs& W = bws[n];
+      const t5_block_grads& g = s.lg[l];
+      auto put = [&](int kind, const void* A, const void* B, float* o0, float* o1, float* o2) {
+        const void** t = &tab[((size_t)kind * s.L + n) * GEMM_GROUP_PTRS];
+        t[0] = A; t[1] = B; t[2] = o0; t[3] = o1; t[4] = o2;
+      };
+      put(0, S.a, ring(n), g.wo_ff, nullptr, nullptr);
+      put(1, S.n2, W.duw, g.wi0, D.mlp == ACT_RELU ? nullptr : g.wi1, nullptr);
+      put(2, S.c, dec ? W.dh1_lp : W.dh_lp, g.wo, nullptr, nullptr);
+      put(3, S.n1, W.dqkv, g.wq, g.wk, g.wv);
+      if (dec) {
+        const t5_cross_grads& x = s.xg[l];
+        put(4, S.cx, W.dh_lp, x.xo, nullptr, nullptr);
+        put(5, S.nx, W.dqx, x.xq, nullptr, nullptr);
+        put(6, enc_out, W.dkvx, x.xk, x.xv, nullptr);
+      }
+    }
+    T5_STEP("wgrad_table", launch_fill_ptrs(tab.data(), kinds * s.L * GEMM_GROUP_PTRS, s.ptr_tab, st));
+    static const char* const names[kWgradKinds] = {"gemm_dwo_ff", "gemm_dwi", "gemm_dwo", "gemm_dwqkv",
+                                                   "gemm_dxo", "gemm_dxq", "gemm_dxkv"};
+    for (int kind = 0; kind < kinds; ++kind) {
+      const void** t = &tab[(size_t)kind * s.L * GEMM_GROUP_PTRS];
+      GemmDesc g = wgrad_desc(D, kind, t[0], t[1]);
+      g.groups = s.ptr_tab + (size_t)kind * s.L * GEMM_GROUP_PTRS;
+      g.ngroups = s.L;
+      const GemmEpi e = wgrad_epi(D, kind, (float*)t[2], (float*)t[3], (float*)t[4]);
+      if (!gemm_mfma_supported(g, e)) return T5_ERR_UNSUPPORTED;  // checked for the shapes when the plan was made
+      T5_STEP(names[kind], launch_gemm_mfma(g, e, st));
+    }
   }
   T5_STEP("relpos_diag_bwd",
           launch_relpos_diag_bwd(s.ddiag, s.d_rel_table, D.S, D.H, s.bc->num_buckets, s.lut, acc, st));
-  *dx0 = dy;
+  *dx0 = ring(s.L);
   return T5_OK;
 }
 
