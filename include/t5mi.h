@@ -204,9 +204,12 @@ int t5_decoder_block_bwd(const t5_block_cfg* cfg, int32_t enc_seq, const void* d
  *   logits = nf Wout                              tied_logits != 0: logits = d_model^-1/2 nf E^T
  *   loss = mean over positions with 0 <= target < vocab of
  *          lse - logits[target] + z_loss lse^2,   lse = log sum_v exp(logits_v)
- * remat == 0 keeps every layer's saved activations between the forward and the backward sweep;
+ * remat == 0 keeps every layer's saved activations between the forward and the backward sweep, and
+ * (bf16 stacks without dropout) every layer's backward workspace until the sweep is over, so that the
+ * weight gradients of all layers are computed by one grouped GEMM per kind of weight afterwards;
  * remat != 0 keeps the layer inputs only and recomputes each layer's forward inside the backward
- * sweep (one extra forward per layer for 1/n_layers of the activation memory). */
+ * sweep (one extra forward per layer and per-layer weight-gradient GEMMs, for a fraction of the
+ * memory: t5_stack_workspace_bytes() tells). */
 typedef struct {
   t5_block_cfg block; /* per-layer shapes; block.batch x block.seq tokens per step */
   int32_t n_layers;
