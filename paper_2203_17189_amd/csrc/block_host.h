@@ -192,7 +192,9 @@ struct BwdWs {
   // cross-attention sublayer: dh/dh_lp hold the gradient of h2, dh1/dh1_lp that of h
   float* dh1;
   void *dh1_lp, *dqx, *dkvx;  // dqx [T, I]; dkvx [Te, 2I]
-  void* dmask;                // [T, d]: a sublayer's output gradient times its dropout multiplier (dropout only)
+  // [T, d] each (dropout only): a sublayer's output gradient times its dropout multiplier, one buffer per
+  // sublayer (feed-forward, self-attention, cross-attention) so that all three outlive the layer's pass
+  void *dmask, *dmask_a, *dmask_x;
 };
 size_t carve_bwd(const Dims& D, void* base, BwdWs* w) {
   Carver cv(base);
@@ -207,11 +209,13 @@ size_t carve_bwd(const Dims& D, void* base, BwdWs* w) {
   t.dc = cv.take((size_t)D.T * D.I * D.es);
   t.dqkv = cv.take((size_t)D.T * 3 * D.I * D.es);
   t.dmask = cv.take(D.drop > 0.f ? (size_t)D.T * D.d * D.es : 0);
+  t.dmask_a = cv.take(D.drop > 0.f ? (size_t)D.T * D.d * D.es : 0);
   if (D.Sk > 0) {
     t.dh1 = cv.take<float>((size_t)D.T * D.d * 4);
     t.dh1_lp = cv.take(D.ty == IN_BF16 ? (size_t)D.T * D.d * D.es : 0);
     t.dqx = cv.take((size_t)D.T * D.I * D.es);
     t.dkvx = cv.take((size_t)D.Te * 2 * D.I * D.es);
+    t.dmask_x = cv.take(D.drop > 0.f ? (size_t)D.T * D.d * D.es : 0);
   }
   if (w) *w = t;
   return cv.off;
@@ -539,8 +543,8 @@ int bwd_cross_attn(const t5_block_cfg* cfg, const Dims& D, const void* enc, cons
   const AttnDims ad = cross_dims(cfg, D);
   const void* dh_op = ty == IN_BF16 ? (const void*)W.dh_lp : (const void*)W.dh;
   if (D.drop > 0.f) {
-    T5_STEP("dropout_dh", launch_dropout_apply(drop_site(D, DROP_CROSS_OUT), dh_op, W.dmask, ty, T, D.d, st));
-    dh_op = W.dmask;
+    T5_STEP("dropout_dh", launch_dropout_apply(drop_site(D, DROP_CROSS_OUT), dh_op, W.dmask_x, ty, T, D.d, st));
+    dh_op = W.dmask_x;
   }
   if (!W.defer_wgrad) {  // dXo = cx^T dh2
     T5_TRY(fork_sync(W.fork));
@@ -605,8 +609,8 @@ int bwd_self_attn(const t5_block_cfg* cfg, const Dims& D, const RelposLut& lut, 
   const AttnDims ad = self_dims(cfg, D);
   const void* dh_op = ty == IN_BF16 ? dh_lp : (const void*)dh;
   if (D.drop > 0.f) {
-    T5_STEP("dropout_dh", launch_dropout_apply(drop_site(D, DROP_ATTN_OUT), dh_op, W.dmask, ty, T, D.d, st));
-    dh_op = W.dmask;
+    T5_STEP("dropout_dh", launch_dropout_apply(drop_site(D, DROP_ATTN_OUT), dh_op, W.dmask_a, ty, T, D.d, st));
+    dh_op = W.dmask_a;
   }
   if (!W.defer_wgrad) {  // dWo = c^T dh
     T5_TRY(fork_sync(W.fork));

@@ -72,7 +72,7 @@ GemmEpi wgrad_epi(const Dims& D, int kind, float* o0, float* o1, float* o2) {
   return e;
 }
 bool wgrads_grouped_ok(const Dims& D, int L, bool remat) {
-  if (D.ty != IN_BF16 || remat || D.drop > 0.f || L < 2 || L > 256) return false;
+  if (D.ty != IN_BF16 || remat || L < 2 || L > 256) return false;
   static const long long dummy[4] = {0, 0, 0, 0};
   for (int kind = 0; kind < (D.Sk > 0 ? kWgradKinds : 4); ++kind) {
     GemmDesc g = wgrad_desc(D, kind, dummy, dummy);
@@ -245,13 +245,15 @@ int layers_backward(const Layers& s, const void* enc_out, float* denc_acc, int a
         const void** t = &tab[((size_t)kind * s.L + n) * GEMM_GROUP_PTRS];
         t[0] = A; t[1] = B; t[2] = o0; t[3] = o1; t[4] = o2;
       };
-      put(0, S.a, ring(n), g.wo_ff, nullptr, nullptr);
+      // with dropout the GEMMs of a dropped sublayer output read its masked gradient copy
+      const bool drop = D.drop > 0.f;
+      put(0, S.a, drop ? W.dmask : ring(n), g.wo_ff, nullptr, nullptr);
       put(1, S.n2, W.duw, g.wi0, D.mlp == ACT_RELU ? nullptr : g.wi1, nullptr);
-      put(2, S.c, dec ? W.dh1_lp : W.dh_lp, g.wo, nullptr, nullptr);
+      put(2, S.c, drop ? W.dmask_a : (dec ? W.dh1_lp : W.dh_lp), g.wo, nullptr, nullptr);
       put(3, S.n1, W.dqkv, g.wq, g.wk, g.wv);
       if (dec) {
         const t5_cross_grads& x = s.xg[l];
-        put(4, S.cx, W.dh_lp, x.xo, nullptr, nullptr);
+        put(4, S.cx, drop ? W.dmask_x : W.dh_lp, x.xo, nullptr, nullptr);
         put(5, S.nx, W.dqx, x.xq, nullptr, nullptr);
         put(6, enc_out, W.dkvx, x.xk, x.xv, nullptr);
       }
