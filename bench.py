@@ -320,7 +320,7 @@ def main() -> int:
     P.t5_step_timing_enable(False)
     flops = gemm_step_flops(cfg)
     if sc is not None or ec is not None:
-        chunk = min(cfg.tokens, 8192)
+        chunk = min(cfg.tokens, 16384)
         for name in ("gemm_logits", "gemm_dnf", "gemm_dlogits_w"):
             flops[name] = 2.0 * chunk * cfg.d_model * (sc or ec).vocab
     if ec is not None:

@@ -6,7 +6,7 @@
 
 namespace {
 
-constexpr int kLogitChunk = 8192;  // tokens whose logits exist at a time
+constexpr int kLogitChunk = 16384;  // tokens whose logits exist at a time
 
 // ------------------------------------------------------------------------------------------------
 // One stack of identical layers.  Layer l reads x_l and writes x_{l+1} (storage type); its saved

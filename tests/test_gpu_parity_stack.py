@@ -118,8 +118,8 @@ BF16_CASES = [
     SI.StackConfig("stack_bf16_t5_vocab", replace(BF_BLK, index=66, batch=1, d_model=64, n_heads=1, d_ff=128),
                    n_layers=1, vocab=32128),
     SI.StackConfig("stack_bf16_relu_tied", replace(BF_BLK, index=69, mlp="relu"), n_layers=2, vocab=512, tied_logits=True),
-    # more tokens than one logits chunk (8192) and not a multiple of it: two launches of the head, the second short
-    SI.StackConfig("stack_bf16_two_chunks", replace(BF_BLK, index=59, batch=66, seq=128, d_model=64, n_heads=1, d_ff=64),
+    # more tokens than one logits chunk (16384) and not a multiple of it: two launches of the head, the second short
+    SI.StackConfig("stack_bf16_two_chunks", replace(BF_BLK, index=59, batch=130, seq=128, d_model=64, n_heads=1, d_ff=64),
                    n_layers=1, vocab=256),
     SI.StackConfig("stack_bf16_ragged", SI.BlockConfig("stack_bf16_ragged", 67, batch=1, seq=50, d_model=72, n_heads=3,
                                                         d_kv=24, d_ff=136, causal=True, attn_scale=24 ** -0.5),
