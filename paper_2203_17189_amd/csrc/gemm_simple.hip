@@ -130,36 +130,44 @@ __global__ void geglu_fwd_kernel(T* __restrict__ u, T* __restrict__ w, T* __rest
   }
 }
 
-// dst[n][k] for a 32x32 tile staged through LDS; see launch_pack_transpose_bf16.  blockIdx.z picks
-// the job; blocks outside a job's tile range leave at once.
+// dst[n][k] for a 64x64 tile staged through LDS; see launch_pack_transpose_bf16.  blockIdx.z picks the
+// job; blocks outside a job's tile range leave at once.  Each thread moves two adjacent elements, so
+// a row of the tile is one 128-byte line on the way in and on the way out.
 __global__ __launch_bounds__(256) void pack_transpose_kernel(PackJobs jobs) {
-  __shared__ bf16 tile[32][33];
+  __shared__ bf16 tile[64][66];
   const PackJob& jb = jobs.j[blockIdx.z];
   const int nsrc = jb.nsrc, K = jb.K, n_each = jb.n_each, interleave = jb.interleave;
   const int n_total = nsrc * n_each;
-  const int n0 = blockIdx.x * 32, k0 = blockIdx.y * 32;
+  const int n0 = blockIdx.x * 64, k0 = blockIdx.y * 64;
   if (n0 >= n_total || k0 >= K) return;
-  const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;  // 32 x 8
-  // interleave and n_each are multiples of 32 (or interleave == 0), so a 32-wide tile of packed
-  // rows comes from one source and 32 consecutive source columns.
+  const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;  // 32 column pairs x 8 rows
+  // interleave and n_each are multiples of 32 (or interleave == 0), so each 32-wide half of the tile's packed
+  // rows comes from one source and 32 consecutive source columns; a thread's pair lies inside one half.
+  const int c = 2 * tx, nh = n0 + (c & 32);  // first packed row of this thread's half
   int which, col0;
   if (interleave > 0) {
-    which = (n0 / interleave) % nsrc;
-    col0 = (n0 / (interleave * nsrc)) * interleave + n0 % interleave;
+    which = (nh / interleave) % nsrc;
+    col0 = (nh / (interleave * nsrc)) * interleave + nh % interleave;
   } else {
-    which = n0 / n_each;
-    col0 = n0 % n_each;
+    which = nh / n_each;
+    col0 = nh % n_each;
   }
-  const bf16* src = (const bf16*)jb.src[which];
+  const bool in_n = nh < n_total;
+  const bf16* src = (const bf16*)jb.src[in_n ? which : 0];
   bf16* dst = (bf16*)jb.dst;
-  for (int r = ty; r < 32; r += 8) {
+  for (int r = ty; r < 64; r += 8) {
     const int k = k0 + r;
-    tile[r][tx] = (k < K && n0 + tx < n_total) ? src[(size_t)k * n_each + col0 + tx] : (bf16)0.f;
+    uint32_t v = 0;
+    if (in_n && k < K) v = *reinterpret_cast<const uint32_t*>(src + (size_t)k * n_each + col0 + (c & 31));
+    *reinterpret_cast<uint32_t*>(&tile[r][c]) = v;
   }
   __syncthreads();
-  for (int r = ty; r < 32; r += 8) {
-    const int n = n0 + r, k = k0 + tx;
-    if (n < n_total && k < K) dst[(size_t)n * K + k] = tile[tx][r];
+  for (int r = ty; r < 64; r += 8) {
+    const int n = n0 + r, k = k0 + c;
+    if (n < n_total && k < K) {  // K is even: the pair (k, k + 1) is inside or outside together
+      const uint32_t lo = __builtin_bit_cast(uint16_t, tile[c][r]), hi = __builtin_bit_cast(uint16_t, tile[c + 1][r]);
+      *reinterpret_cast<uint32_t*>(dst + (size_t)n * K + k) = lo | (hi << 16);
+    }
   }
 }
 
@@ -205,10 +213,11 @@ hipError_t launch_pack_transpose_multi(const PackJobs& jobs, hipStream_t st) {
   int gx = 0, gy = 0;
   for (int q = 0; q < jobs.count; ++q) {
     const PackJob& jb = jobs.j[q];
-    if (jb.nsrc < 1 || jb.nsrc > 3 || jb.n_each % 32 != 0 || (jb.interleave > 0 && jb.interleave % 32 != 0))
+    if (jb.nsrc < 1 || jb.nsrc > 3 || jb.n_each % 32 != 0 || (jb.interleave > 0 && jb.interleave % 32 != 0) ||
+        jb.K % 2 != 0)
       return hipErrorInvalidValue;
-    gx = std::max(gx, jb.nsrc * jb.n_each / 32);
-    gy = std::max(gy, ceil_div(jb.K, 32));
+    gx = std::max(gx, ceil_div(jb.nsrc * jb.n_each, 64));
+    gy = std::max(gy, ceil_div(jb.K, 64));
   }
   pack_transpose_kernel<<<dim3(gx, gy, jobs.count), 256, 0, st>>>(jobs);
   return hipGetLastError();
