@@ -49,12 +49,15 @@ def test_block_step_in_a_graph_matches_eager():
             assert np.abs(to_np(graph["grads"][k]) - a).max() <= 1e-4 * (np.abs(a).max() + 1e-30), (rep, k)
 
 
-def test_stack_step_in_a_graph_matches_eager():
+@pytest.mark.parametrize("remat", [True, False])
+def test_stack_step_in_a_graph_matches_eager(remat):
+    # remat: per-layer weight-gradient launches; without it the grouped launches, whose pointer tables are
+    # written by kernels inside the captured step
     import paper_2203_17189_amd as P
     from paper_2203_17189_amd import binding as B
     blk = SI.BlockConfig("graph_stack", 91, batch=2, seq=128, d_model=128, n_heads=2, d_kv=64, d_ff=256, causal=True,
                          attn_scale=64 ** -0.5)
-    sc = SI.StackConfig("graph_stack", blk, n_layers=2, vocab=512, remat=True)
+    sc = SI.StackConfig("graph_stack", blk, n_layers=2, vocab=512, remat=remat)
     w = SI.make_stack_weights(sc)
     dw = {k: to_dev(v, blk.dtype) for k, v in w.items() if k != "layers"}
     dw["layers"] = [{k: to_dev(v, blk.dtype) for k, v in lw.items()} for lw in w["layers"]]
