@@ -665,6 +665,9 @@ hipError_t launch_layout(const GemmDesc& g, const GemmEpi& e, hipStream_t st) {
     // dWi 3x16 tiles -18 % at 65536 and -10 % at 16384 tokens; dWo_ff 8x3 and dWqkv 3x9 tiles -14 % at 65536
     // tokens but +10..18 % at 16384, where a workgroup's share of k no longer pays for the larger epilogue)
     big = t256 >= 48 || (t256 >= 24 && nk * KQ >= 49152);
+    // grouped small outputs (12 x 768 x 768: 432 tiles of 128x128): one round of small tiles over the whole
+    // reduction, no split and no atomics, beats 256x256 tiles split seven ways (0.20 -> 0.17 ms at 4096 tokens)
+    if (ngr > 1 && t128 <= 512) big = false;
     const int64_t tiles = big ? t256 : t128;
     const int per_cu = big ? 1 : 2;  // concurrent workgroups per compute unit (LDS-limited)
     double best = -1.0;
