@@ -132,6 +132,25 @@ def test_stack_bf16_small(sc):
     _compare(sc, 5e-4, *relu_aware(sc.block, stack_bf16_tol(sc.n_layers)))
 
 
+def test_stack_bf16_accumulate_with_grouped_weight_gradients():
+    """A second call with accumulate adds to the gradients of the first, also where the weight gradients of
+    all layers come from the grouped launches (bf16, activations kept)."""
+    import paper_2203_17189_amd as P
+    sc = replace(BF16_CASES[0], n_layers=3)
+    w, tokens, targets = _case(sc)
+    dw, tt, tg = _upload(sc, w, tokens, targets)
+    _, g1 = P.t5_stack_loss_and_grad(sc, tt, tg, dw)
+    g2 = {k: ([{n: t.clone() for n, t in d.items()} for d in v] if k == "layers" else v.clone()) for k, v in g1.items()}
+    P.t5_stack_loss_and_grad(sc, tt, tg, dw, grads=g2, accumulate=True)
+    torch.cuda.synchronize()
+    close = lambda a, b, what: np.testing.assert_allclose(to_np(a), 2 * to_np(b), rtol=0, atol=1e-4 * float(b.abs().max()) + 1e-12, err_msg=str(what))
+    for k in ("embedding", "rel_table", "final_scale", "logits_w"):
+        close(g2[k], g1[k], k)
+    for l in range(sc.n_layers):
+        for n in g1["layers"][l]:
+            close(g2["layers"][l][n], g1["layers"][l][n], (l, n))
+
+
 def test_stack_bf16_remat_matches_stashed():
     """Recomputing each layer inside the backward sweep gives the same loss bit for bit and the same
     gradients up to the order of the float32 atomic additions."""
