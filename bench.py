@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the T5.1.1 block hot path (forward + backward [+ Adafactor]) on one MI355X.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2_small|c3_base|c4_gpt_causal|c5_xl|c6_dec_base|c7_xl_tp8_share|s1_lm_base|e1_t5_base]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5_xl|c2_small|c3_base|c4_gpt_causal|c6_dec_base|c7_xl_tp8_share|s1_lm_base|e1_t5_base]
 
 Prints ONE JSON line.  A "step" is one pass of the whole hot path over one batch of seeded
 synthetic input already resident in HBM: t5_block_fwd + t5_block_bwd (t5_decoder_block_fwd/bwd for the
@@ -128,7 +128,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2_small", choices=[k for k in SI.CONFIGS if k != "c1_tiny_f32"] + list(SI.STACK_CONFIGS) + list(SI.ENCDEC_CONFIGS))
+    ap.add_argument("--workload", default="c5_xl", choices=[k for k in SI.CONFIGS if k != "c1_tiny_f32"] + list(SI.STACK_CONFIGS) + list(SI.ENCDEC_CONFIGS))
     ap.add_argument("--cpu-sample-batch", type=int, default=0, help="0 = pick about 10-30 s of oracle work")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
@@ -208,15 +208,15 @@ def main() -> int:
     decoder = cfg.enc_seq > 0
     opt = None
     if sc is None and ec is None:
-        rng = np.random.default_rng(SI.BASE_SEED + 1000 * cfg.index)
-        shape = (cfg.batch, cfg.seq, cfg.d_model)
-        x = torch.from_numpy(rng.standard_normal(shape, dtype=np.float32)).to(dev).to(dt_t)
-        dy = torch.from_numpy(rng.standard_normal(shape, dtype=np.float32)).to(dev).to(dt_t)
+        # the seeded draws the parity tests use (float64 on the host, rounded once to bf16)
+        x_h, dy_h = SI.make_activations(cfg)
+        x, dy = up(x_h), up(dy_h)
+        del x_h, dy_h
         y = torch.empty_like(x)
         dx = torch.empty_like(x)
         decoder = cfg.enc_seq > 0
         if decoder:
-            enc = torch.from_numpy(rng.standard_normal((cfg.batch, cfg.enc_seq, cfg.d_model), dtype=np.float32)).to(dev).to(dt_t)
+            enc = up(SI.make_encoder_output(cfg))
             denc = torch.empty_like(enc)
             stash = torch.empty(P.t5_decoder_block_stash_bytes(cfg), dtype=torch.uint8, device=dev)
             ws = torch.empty(P.t5_decoder_block_workspace_bytes(cfg), dtype=torch.uint8, device=dev)

@@ -16,8 +16,14 @@
  *   - all tensor pointers are DEVICE pointers owned by the caller, dense
  *     row-major, no strides, no aliasing between inputs and outputs;
  *   - config structs are HOST pointers, read during the call only;
- *   - the library allocates nothing: scratch comes from the caller's workspace,
- *     whose size is returned by the *_bytes() queries (0 on an invalid config);
+ *   - the library allocates no device memory: scratch comes from the caller's
+ *     workspace, whose size is returned by the *_bytes() queries (0 on an
+ *     invalid config).  Host-side objects only: the stack entry points build
+ *     short host arrays per call, and the two opt-in aids create HIP objects
+ *     (t5_wgrad_overlap_enable: one stream and two events, kept until it is
+ *     switched off; t5_step_timing_enable: one event pair per timed step);
+ *   - one host thread at a time: the opt-in aids and the one-time kernel
+ *     attribute set-up keep process-wide state without locks;
  *   - all device work is enqueued on `stream` (a hipStream_t passed as void*;
  *     NULL = the default stream) and the call returns without synchronising
  *     (after t5_wgrad_overlap_enable(1) the backward passes also use one stream
@@ -136,6 +142,18 @@ int t5_dropout_keep(uint64_t seed, int site, float rate, int64_t rows, int64_t c
  * (opaque layout), and of the scratch workspace (max over forward and backward). */
 size_t t5_block_stash_bytes(const t5_block_cfg* cfg);
 size_t t5_block_workspace_bytes(const t5_block_cfg* cfg);
+
+/* Which kernels a configuration runs on (a pure host-side query: no device work, usable without a GPU).
+ * Returns a bit mask, or -1 for an invalid configuration.  enc_seq = 0: the block; > 0: the decoder layer
+ * with cross-attention over enc_seq positions.  A clear bit means the general-shape kernels (any shape,
+ * reference-grade speed) take that part; results obey the same bounds either way. */
+enum {
+  T5_PATH_MFMA_GEMM = 1,       /* forward projections on the matrix-unit GEMM, gated activation fused into it */
+  T5_PATH_MFMA_ATTN_FWD = 2,   /* fused matrix-unit self-attention, forward */
+  T5_PATH_MFMA_ATTN_BWD = 4,   /* ... backward */
+  T5_PATH_MFMA_CROSS_ATTN = 8  /* fused matrix-unit cross-attention (decoder layer), both directions */
+};
+int t5_block_kernel_path(const t5_block_cfg* cfg, int32_t enc_seq);
 
 /* Forward of the block defined at t5_block_cfg.  x, y: [batch, seq, d_model] of cfg.dtype.
  * stash: t5_block_stash_bytes(cfg) bytes, 256-byte aligned, written here.

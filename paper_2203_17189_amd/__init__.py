@@ -16,6 +16,11 @@ from .binding import (  # noqa: F401
     lib_path,
     t5_block_bwd,
     t5_block_fwd,
+    t5_block_kernel_path,
+    PATH_MFMA_GEMM,
+    PATH_MFMA_ATTN_FWD,
+    PATH_MFMA_ATTN_BWD,
+    PATH_MFMA_CROSS_ATTN,
     t5_block_stash_bytes,
     t5_block_workspace_bytes,
     t5_decoder_block_bwd,

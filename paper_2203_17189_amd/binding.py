@@ -110,6 +110,8 @@ def lib() -> C.CDLL:
     L.t5_relpos_bucket.argtypes = [vp, vp, i64, i32, i32, i32, vp]
     L.t5_dropout_keep.restype = i32
     L.t5_dropout_keep.argtypes = [C.c_uint64, i32, C.c_float, i64, i64, vp, vp]
+    L.t5_block_kernel_path.restype = i32
+    L.t5_block_kernel_path.argtypes = [C.POINTER(_Cfg), i32]
     L.t5_block_stash_bytes.restype = sz
     L.t5_block_stash_bytes.argtypes = [C.POINTER(_Cfg)]
     L.t5_block_workspace_bytes.restype = sz
@@ -215,6 +217,14 @@ def t5_dropout_keep(seed: int, site: int, rate: float, rows: int, cols: int) -> 
     if rc:
         raise T5Error(rc, "t5_dropout_keep")
     return out
+
+
+PATH_MFMA_GEMM, PATH_MFMA_ATTN_FWD, PATH_MFMA_ATTN_BWD, PATH_MFMA_CROSS_ATTN = 1, 2, 4, 8
+
+
+def t5_block_kernel_path(cfg) -> int:
+    """Bit mask of the kernel families the configuration runs on (host-side query; -1: invalid configuration)."""
+    return int(lib().t5_block_kernel_path(C.byref(_cfg_struct(cfg)), int(getattr(cfg, "enc_seq", 0))))
 
 
 def t5_block_stash_bytes(cfg) -> int:

@@ -15,7 +15,7 @@ SOURCES = ["relpos.hip", "rmsnorm.hip", "gemm_simple.hip", "gemm_mfma.hip", "att
 # -packed-fp32-ops is switched off: hand-written and compiler-made packed float32 math is avoided on
 # this target.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
-         "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-Wno-unknown-cuda-version"]
+         "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 
 
 def _compile(src: str) -> str:

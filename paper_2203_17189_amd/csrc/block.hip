@@ -74,6 +74,22 @@ size_t t5_decoder_block_workspace_bytes(const t5_block_cfg* cfg, int32_t enc_seq
   return f > b ? f : b;
 }
 
+int t5_block_kernel_path(const t5_block_cfg* cfg, int32_t enc_seq) {
+  Dims D;
+  RelposLut lut;
+  if (enc_seq < 0 || validate_cfg(cfg, &D, &lut, enc_seq) != T5_OK) return -1;
+  int path = 0;
+  if (fused_fwd_ok(D)) path |= T5_PATH_MFMA_GEMM;
+  const AttnDims ad = self_dims(cfg, D);
+  const int far = lut.n_thr > 0 ? lut.thr[lut.n_thr - 1] : lut.max_exact;
+  if (D.ty == IN_BF16 && attn_mfma_supported(ad)) {
+    path |= T5_PATH_MFMA_ATTN_FWD;
+    if (attn_bwd_mfma_fits(ad, far)) path |= T5_PATH_MFMA_ATTN_BWD;
+  }
+  if (enc_seq > 0 && D.ty == IN_BF16 && attn_mfma_supported(cross_dims(cfg, D))) path |= T5_PATH_MFMA_CROSS_ATTN;
+  return path;
+}
+
 int t5_block_fwd(const t5_block_cfg* cfg, const void* x, const t5_block_weights* w, void* y, void* stash,
                  void* workspace, size_t workspace_bytes, void* stream) {
   Dims D;
@@ -115,10 +131,11 @@ int t5_block_bwd(const t5_block_cfg* cfg, const void* dy, const void* x, const t
   const int far = lut.n_thr > 0 ? lut.thr[lut.n_thr - 1] : lut.max_exact;
   const bool attn_mfma = D.ty == IN_BF16 && attn_mfma_supported(ad) && attn_bwd_mfma_fits(ad, far);
   W.fork = fork_begin(st, D.drop == 0.f);
+  ForkGuard guard(W.fork);
   T5_SUB(bwd_zero(D, dw, nullptr, attn_mfma ? W.ddiag : nullptr, acc != 0, st));
   T5_SUB(bwd_mlp(D, dy, S.h, w, S, W, dw, acc, st));
   T5_SUB(bwd_self_attn(cfg, D, lut, x, W.dh, W.dh_lp, w, S, W, attn_mfma, far, dx, dw, acc, st));
-  T5_TRY(fork_join(W.fork));
+  T5_TRY(guard.join());
   return T5_OK;
 }
 
@@ -172,11 +189,12 @@ int t5_decoder_block_bwd(const t5_block_cfg* cfg, int32_t enc_seq, const void* d
   const int far = lut.n_thr > 0 ? lut.thr[lut.n_thr - 1] : lut.max_exact;
   const bool attn_mfma = D.ty == IN_BF16 && attn_mfma_supported(ad) && attn_bwd_mfma_fits(ad, far);
   W.fork = fork_begin(st, D.drop == 0.f);
+  ForkGuard guard(W.fork);
   T5_SUB(bwd_zero(D, dw, dxw, attn_mfma ? W.ddiag : nullptr, acc != 0, st));
   T5_SUB(bwd_mlp(D, dy, S.h2, w, S, W, dw, acc, st));
   T5_SUB(bwd_cross_attn(cfg, D, enc, xw, S, W, denc, dxw, acc, st));
   T5_SUB(bwd_self_attn(cfg, D, lut, x, W.dh1, W.dh1_lp, w, S, W, attn_mfma, far, dx, dw, acc, st));
-  T5_TRY(fork_join(W.fork));
+  T5_TRY(guard.join());
   return T5_OK;
 }
 

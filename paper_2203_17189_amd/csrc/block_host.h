@@ -181,6 +181,15 @@ inline hipError_t fork_join(const Fork& f) {
   return e != hipSuccess ? e : hipStreamWaitEvent(f.main, f.ev_join, 0);
 }
 inline hipStream_t wgrad_stream(const Fork& f) { return f.on ? f.side : f.main; }
+// Joins the side stream on every way out of a backward pass: an error return between fork and join must
+// not leave side-stream GEMMs running on buffers the caller is about to reuse.
+struct ForkGuard {
+  const Fork& f;
+  bool done = false;
+  explicit ForkGuard(const Fork& fk) : f(fk) {}
+  hipError_t join() { done = true; return fork_join(f); }
+  ~ForkGuard() { if (!done) (void)fork_join(f); }
+};
 
 struct BwdWs {
   Fork fork;
@@ -281,7 +290,7 @@ bool fused_fwd_ok(const Dims& D) {
   // The packed-weight MFMA forward needs the MFMA GEMM for every projection of this shape; the
   // fused gated-GELU GEMM is the most demanding one, so probe it with placeholder pointers.
   if (D.ty != IN_BF16 || D.d % 64 != 0 || D.I % 64 != 0 || D.F % 64 != 0) return false;
-  static const long long dummy[4] = {0, 0, 0, 0};
+  alignas(16) static const long long dummy[4] = {0, 0, 0, 0};  // placeholder operand: passes the 16-byte alignment test
   if (D.mlp == ACT_RELU) {
     GemmDesc g = gemm1((int)D.T, D.F, D.d, dummy, D.d, 1, dummy, D.d, 1, IN_BF16);
     return gemm_mfma_supported(g, epi(EPI_STORE, (void*)dummy, D.F, IN_BF16));

@@ -21,6 +21,7 @@
 // Workgroup ids are remapped so that each XCD (ids are dealt round-robin to the 8 XCDs) works on a
 // compact block of output tiles and shares operand tiles through its own L2.
 #include "kernels.h"
+#include <atomic>
 
 namespace t5mi {
 
@@ -633,11 +634,12 @@ hipError_t launch_cfg(const GemmDesc& g, const GemmEpi& e, int split_k, hipStrea
   constexpr int lds_loop = NS * (BM + BN) * BK * 2;
   constexpr int lds_epi = WM * WN * 64 * (BN / WN + 8) * 4;
   constexpr int lds = lds_loop > lds_epi ? lds_loop : lds_epi;
-  static bool attr_set = false;
-  if (!attr_set) {
+  // once per instantiation; setting it twice is harmless, so a relaxed flag is enough
+  static std::atomic<bool> attr_set{false};
+  if (!attr_set.load(std::memory_order_relaxed)) {
     hipError_t err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (err != hipSuccess) return err;
-    attr_set = true;
+    attr_set.store(true, std::memory_order_relaxed);
   }
   const int tiles_m = ceil_div(g.M, BM), tiles_n = ceil_div(g.N, BN);
   const int ngr = (EPI & EPI_GROUP) ? g.ngroups : 1;

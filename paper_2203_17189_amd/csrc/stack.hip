@@ -210,6 +210,7 @@ int layers_backward(const Layers& s, const void* enc_out, float* denc_acc, int a
     BwdWs& BW = bws[s.grouped ? n : 0];
     void* dy = ring(n);
     void* dx = ring(n + 1);
+    ForkGuard guard(BW.fork);
     if (s.remat) T5_SUB(layer_forward(s, l, enc_out, st));  // rebuilds layer l's saved activations
     t5_block_cfg bc;
     Dims D;  // this layer's (its dropout seed differs from the stack's)
@@ -229,7 +230,7 @@ int layers_backward(const Layers& s, const void* enc_out, float* denc_acc, int a
                            &s.lg[l], acc, st, false));
     }
     // the next layer rewrites the workspace (and, with remat, the stash) the side GEMMs read
-    T5_TRY(fork_join(BW.fork));
+    T5_TRY(guard.join());
   }
   if (s.grouped) {
     // one launch per kind of weight over all layers: problem n is layer L-1-n

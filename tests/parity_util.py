@@ -2,65 +2,143 @@
 binding, and measure the error against the float64 oracle."""
 from __future__ import annotations
 
+import json
+import os
+
 import numpy as np
 import torch
 
 import synth_inputs as SI
 
-# Tolerances, keyed by storage dtype: (max, mean) of the per-element error
-#   e_i = |gpu_i - ref_i| / max(|ref_i|, RMS(ref))
+# Tolerances.  Per-element error of a tensor: e_i = |gpu_i - ref_i| / max(|ref_i|, RMS(ref)); (max, mean) over i.
 TOL_F32 = (1e-4, 1e-4)
-TOL_BF16_ACT = (2e-2, 2e-3)      # y of the bf16 block (stated target)
-TOL_BF16_DX = (3e-2, 2.5e-3)     # dx: one more chain of bf16 MFMA-operand roundings than y
-TOL_BF16_DW = (6e-2, 6e-3)       # weight gradients
-# At the shapes of the named workload configurations (thousands of tokens per reduction) the measured
-# errors sit lower, and the mean of dx meets the stated 2e-3:
-TOL_BF16_DX_NAMED = (3e-2, 2e-3)
-TOL_BF16_DW_NAMED = (5e-2, 5e-3)
-# denc = dk Xk^T + dv Xv^T has no residual term (dx = dh + ... is dominated by the float32 residual
-# path): all of it passes through the bf16 roundings of P and dS as MFMA operands and of dk, dv as
-# stored, the chain of the weight gradients dWk and dWv, so it gets their bound.
-TOL_BF16_DENC = TOL_BF16_DW
-# The decoder layer adds a third sublayer to the float32 residual stream; each sublayer contributes
-# an independent bf16-rounded term of similar size, so the error of y and dx grows by about
-# sqrt(3/2) over the two-sublayer block.  Mean bounds scaled by that factor, maxima unchanged.
-TOL_BF16_DEC_ACT = (2e-2, 2.5e-3)
-TOL_BF16_DEC_DX = (3e-2, 3.1e-3)
-TOL_BF16_DEC_DX_NAMED = (3e-2, 2.5e-3)   # the named-workload dx bound times sqrt(3/2); y meets the stated 2e-3
-TOL_BF16_DENC_NAMED = TOL_BF16_DW_NAMED
+# bf16: the stated target, asserted wherever ideal bf16-operand arithmetic can meet it at all.
+STATED_BF16 = (2e-2, 2e-3)
+# Where it cannot -- the floor that tests/bf16_model.py computes for the very case under test (same seeded
+# inputs, float64 everywhere except the tensors the device rounds to bf16) lies above the stated value --
+# the bound is that floor times a margin.  The floor is ONE realisation of the rounding noise and the device
+# produces ANOTHER: float32 accumulation order flips a small fraction of the first bf16 roundings and the
+# flips spread down the chain of roundings, so by the end of the backward pass the two error patterns are
+# independent samples of one distribution (tests/test_bf16_floor.py measures the spread between such
+# samples).  The margins are therefore those of comparing two samples:
+#   mean over n elements: MARGIN = 1.25 (what the model leaves out: float32 accumulation, the hardware exp2)
+#     plus three standard deviations of the ratio of two n-element means of half-normal-like values,
+#     3 * sqrt(2) * 0.756 / sqrt(n) = 3.2 / sqrt(n)  (n = 64 for a 32 x 2 bias table: 1.65; n >= 1e5: 1.26);
+#   maximum: an extreme value, dominated by a handful of elements; between two samples it differs by up to
+#     a factor of about two (measured), so MARGIN_MAX = 2.
+MARGIN = 1.25
+MARGIN_MAX = 2.0
+# Ungated ReLU feed-forward: a pre-activation within rounding distance of zero takes one branch on the
+# device and the other in float64, and each such unit changes its gradient by its full size.  The error of
+# every gradient upstream of the activation is a sum over these discrete events (about 0.3 % of the units);
+# which units flip differs between two samples, so the mean gets 1.5 instead of 1.25.
+MARGIN_RELU_MEAN = 1.5
 
 
-# ReLU feed-forward in bf16: the derivative of max(u, 0) jumps at u = 0, and the sign of a pre-activation
-# is decided by the kernel's arithmetic (bf16 operands) on one side and by float64 on the other.  With
-# u ~ N(0, 1) and an operand-rounding error of about 3e-3 in u, roughly 0.3 % of the units take the other
-# branch; each such unit changes du by its full size, which is an 8 % error in that token's dn2 and about
-# 1 % (mean) in every gradient upstream of the feed-forward.  The forward is continuous and keeps its
-# bound; the gradients are held to a mean bound only (float32 runs check the mask logic to 1e-4).
-TOL_BF16_RELU_GRAD = (1.0, 3e-2)
+def mean_margin(n: int, relu: bool = False) -> float:
+    return (MARGIN_RELU_MEAN if relu else MARGIN) + 3.2 / float(max(n, 1)) ** 0.5
 
 
-def relu_aware(cfg, tol):
-    return TOL_BF16_RELU_GRAD if getattr(cfg, "mlp", "") == "relu" and cfg.dtype == "bf16" else tol
+def tol_from_floor(floor, n: int = 1 << 30, relu: bool = False):
+    """(max, mean) bound for an n-element tensor whose ideal-bf16 floor is `floor`: the stated value where
+    the floor (times the margin of the maximum) is at or under it, else floor x margin."""
+    tmax = max(STATED_BF16[0], MARGIN_MAX * floor[0])
+    tmean = STATED_BF16[1] if floor[1] <= STATED_BF16[1] else mean_margin(n, relu) * floor[1]
+    return tmax, tmean
 
 
-def drop_tol(tol, rate: float, backward: bool):
-    """bf16 bounds of a block with dropout at rate p.  A sublayer's output f carries the bf16 rounding error
-    eps * rms(f); the kept elements (a fraction 1 - p) are multiplied by 1 / (1 - p), so the error that reaches
-    the residual stream has RMS eps * rms(f) / sqrt(1 - p) while the exact skip term is unchanged: forward
-    bounds grow by at most (1 - p)^-1/2.  In the backward the gradient passes the same multiplier once more
-    and meets operands that already carry the forward factor: (1 - p)^-1."""
-    f = (1.0 - rate) ** (-1.0 if backward else -0.5)
-    return tol[0] * f, tol[1] * f
+def _record(label, name, err, floor, tol, n):
+    """One line per checked tensor: printed (pytest -rP shows it) and, when T5MI_PARITY_LOG names a file,
+    appended to it, so that the measured errors can be quoted beside their bounds."""
+    status = "stated" if tol == STATED_BF16 else "floor"
+    line = {"case": label, "tensor": name, "n": int(n), "err": [float(f"{err[0]:.4g}"), float(f"{err[1]:.4g}")],
+            "floor": [float(f"{floor[0]:.4g}"), float(f"{floor[1]:.4g}")],
+            "tol": [float(f"{tol[0]:.4g}"), float(f"{tol[1]:.4g}")], "bound": status}
+    print(json.dumps(line))
+    path = os.environ.get("T5MI_PARITY_LOG")
+    if path:
+        try:
+            with open(path, "a") as fh:
+                fh.write(json.dumps(line) + "\n")
+        except OSError:
+            pass
 
 
-def stack_bf16_tol(n_layers: int):
-    """Weight-gradient bound of an n_layers-deep bf16 stack.  The gradient that reaches a layer has
-    crossed the bf16-rounded operands of every layer above it (and the activations those of every
-    layer below); the per-layer errors are independent, so they add in quadrature: the block's bound
-    times sqrt(n_layers).  The loss itself is a mean over all positions of values computed from
-    bf16 logits: 5e-4 relative."""
+def check_bf16(label, errs: dict, floors: dict, relu=False, scale=1.0, only=None):
+    """Assert every tensor of errs ({name: (max, mean)}) against the bound derived from its floor.
+    Each error carries the element count of its tensor (rel_err attaches it).
+    relu: the case has the ungated ReLU feed-forward (affects every gradient upstream of it; y and the
+    output projection's gradient a^T dy do not pass through the activation's derivative).
+    scale: widens the derived bounds (comparisons of two device runs: sqrt(2))."""
+    failures = []
+    for name, err in errs.items():
+        if only is not None and name not in only:
+            continue
+        n = getattr(err, "n", 1 << 30)
+        t = tol_from_floor(floors[name], n, relu and name not in ("y", "wo_ff"))
+        t = (t[0] * scale, t[1] * scale) if scale != 1.0 else t
+        _record(label, name, err, floors[name], t, n)
+        if not (err[0] <= t[0] and err[1] <= t[1]):
+            failures.append((name, err, t))
+    assert not failures, (label, failures)
+
+
+def general_mlp_path(cfg) -> bool:
+    """True when the configuration's forward projections run on the general-shape kernels, which store the
+    two feed-forward input projections in bf16 before the activation (the floor model mirrors that)."""
+    import paper_2203_17189_amd as P
+    path = P.t5_block_kernel_path(cfg)
+    assert path >= 0, cfg
+    return cfg.dtype == "bf16" and not (path & P.PATH_MFMA_GEMM)
+
+
+def is_relu(cfg):
+    return getattr(cfg, "mlp", "") == "relu"
+
+
+def block_floors(cfg, w, x, dy, ref):
+    """Floors of one block case; ref = the oracle's (y, dx, grads) for it."""
+    import bf16_model as M
+    return M.block_floor(cfg, x, w, dy, ref=ref, round_uw=general_mlp_path(cfg))
+
+
+def decoder_floors(cfg, w, x, enc, dy, ref):
+    import bf16_model as M
+    return M.decoder_block_floor(cfg, x, enc, w, dy, ref=ref, round_uw=general_mlp_path(cfg))
+
+
+def stack_bf16_tol(blocks, n_layers: int):
+    """(max, mean) bound for every gradient of an n_layers-deep bf16 stack.  The gradient that reaches a
+    layer has crossed the bf16-rounded operands of every layer above it (and the activations those of every
+    layer below); the per-layer errors are independent, so they add in quadrature: the largest
+    weight-gradient floor of one layer of the stack's own shape (block or decoder layer, at batch 1, from
+    tests/bf16_model.py) times sqrt(n_layers), then the rule of tol_from_floor with the margin of the
+    smallest tensor a stack has (a bias table of 32 x n_heads entries).
+    blocks: the layer configurations that occur in the stack (one, or encoder and decoder)."""
+    import bf16_model as M
+    fmax, fmean, relu, n_min = 0.0, 0.0, False, 1 << 30
+    for cfg in blocks:
+        c = cfg.with_batch(1)
+        w = SI.make_weights(c)
+        x, dy = SI.make_activations(c)
+        kw = dict(round_uw=general_mlp_path(c))
+        if c.enc_seq > 0:
+            fl = M.decoder_block_floor(c, x, SI.make_encoder_output(c), w, dy, **kw)
+        else:
+            fl = M.block_floor(c, x, w, dy, **kw)
+        for name, f in fl.items():
+            if name in ("y",):
+                continue
+            fmax, fmean = max(fmax, f[0]), max(fmean, f[1])
+        relu = relu or is_relu(cfg)
+        n_min = min(n_min, cfg.num_buckets * cfg.n_heads)
     f = float(n_layers) ** 0.5
-    return TOL_BF16_DW[0] * f, TOL_BF16_DW[1] * f
+    return tol_from_floor((fmax * f, fmean * f), n_min, relu)
+
+
+class Err(tuple):
+    """(max, mean) of a tensor's per-element error, with the tensor's element count in .n."""
+    n = 1 << 30
 
 
 def rel_err(gpu: np.ndarray, ref: np.ndarray, rms: float | None = None):
@@ -71,9 +149,12 @@ def rel_err(gpu: np.ndarray, ref: np.ndarray, rms: float | None = None):
     if rms is None:
         rms = float(np.sqrt(np.mean(ref * ref)))
     if rms == 0.0:
-        return float(np.abs(gpu).max()), float(np.abs(gpu).mean())
-    e = np.abs(gpu - ref) / np.maximum(np.abs(ref), rms)
-    return float(e.max()), float(e.mean())
+        out = Err((float(np.abs(gpu).max()), float(np.abs(gpu).mean())))
+    else:
+        e = np.abs(gpu - ref) / np.maximum(np.abs(ref), rms)
+        out = Err((float(e.max()), float(e.mean())))
+    out.n = int(ref.size)
+    return out
 
 
 def to_dev(a: np.ndarray, dtype: str) -> torch.Tensor:

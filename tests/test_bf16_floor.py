@@ -1,0 +1,146 @@
+"""CPU checks of the bf16 error-floor model (tests/bf16_model.py) that the GPU tolerances are derived from.
+
+1. Structure: with the rounding switched off the model must BE the oracle (block and decoder layer, every
+   feed-forward variant, with and without dropout) -- so the only thing it adds is the list of rounded tensors.
+2. Values: the floors at the T5.1.1-Small block shape, both readings of the logit scale and both
+   split-operand variants of the score path, against tests/golden/bf16_floor_c2_small.json
+   (written by tests/golden/make_bf16_floor.py), and what they imply for the stated 2e-2 / 2e-3 target.
+3. The rule that turns a floor into a bound.
+"""
+import json
+import os
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+import bf16_model as M
+import synth_inputs as SI
+from oracle import t5_oracle as O
+from parity_util import MARGIN, MARGIN_MAX, STATED_BF16, mean_margin, tol_from_floor
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "bf16_floor_c2_small.json")
+
+SMALL = SI.BlockConfig("floor_small", 90, batch=2, seq=48, d_model=64, n_heads=2, d_kv=16, d_ff=96, attn_scale=0.25)
+VARIANTS = [
+    SMALL,
+    replace(SMALL, name="floor_causal", causal=True),
+    replace(SMALL, name="floor_relu", mlp="relu"),
+    replace(SMALL, name="floor_erf", mlp="geglu_erf", causal=True),
+    replace(SMALL, name="floor_drop", dropout_rate=float(np.float32(0.1)), dropout_seed=77),
+    replace(SMALL, name="floor_drop_relu", mlp="relu", causal=True, dropout_rate=float(np.float32(0.25)), dropout_seed=5),
+]
+
+
+def _case(cfg):
+    w = SI.make_weights(cfg)
+    w.update(SI.make_random_scales(cfg))
+    x, dy = SI.make_activations(cfg)
+    return w, x, dy
+
+
+@pytest.mark.parametrize("cfg", VARIANTS, ids=[c.name for c in VARIANTS])
+def test_model_without_rounding_is_the_oracle(cfg, monkeypatch):
+    monkeypatch.setattr(M, "rb", lambda a: np.asarray(a, dtype=np.float64))
+    w, x, dy = _case(cfg)
+    y, saved = O.block_fwd(cfg, x, w)
+    dx, g = O.block_bwd(cfg, dy, w, saved)
+    my, mdx, mg = M.block_model(cfg, x, w, dy)
+    assert set(mg) == set(g)
+    np.testing.assert_allclose(my, y, rtol=0, atol=1e-11)
+    np.testing.assert_allclose(mdx, dx, rtol=0, atol=1e-10)
+    for k in g:
+        np.testing.assert_allclose(mg[k], g[k], rtol=0, atol=1e-9 * max(1.0, np.abs(g[k]).max()), err_msg=k)
+    # the split-operand variants change nothing either once nothing is rounded
+    sy, sdx, _ = M.block_model(cfg, x, w, dy, split_qk=True, split_n1=True)
+    np.testing.assert_allclose(sy, y, rtol=0, atol=1e-11)
+    np.testing.assert_allclose(sdx, dx, rtol=0, atol=1e-10)
+
+
+@pytest.mark.parametrize("cfg", [replace(c, enc_seq=37, causal=True) for c in (VARIANTS[0], VARIANTS[2], VARIANTS[4])],
+                         ids=["dec", "dec_relu", "dec_drop"])
+def test_decoder_model_without_rounding_is_the_oracle(cfg, monkeypatch):
+    monkeypatch.setattr(M, "rb", lambda a: np.asarray(a, dtype=np.float64))
+    w, x, dy = _case(cfg)
+    enc = SI.make_encoder_output(cfg)
+    y, saved = O.decoder_block_fwd(cfg, x, enc, w)
+    dx, denc, g = O.decoder_block_bwd(cfg, dy, w, saved)
+    my, mdx, mde, mg = M.decoder_block_model(cfg, x, enc, w, dy)
+    assert set(mg) == set(g)
+    np.testing.assert_allclose(my, y, rtol=0, atol=1e-11)
+    np.testing.assert_allclose(mdx, dx, rtol=0, atol=1e-10)
+    np.testing.assert_allclose(mde, denc, rtol=0, atol=1e-10)
+    for k in g:
+        np.testing.assert_allclose(mg[k], g[k], rtol=0, atol=1e-9 * max(1.0, np.abs(g[k]).max()), err_msg=k)
+
+
+def test_rounding_is_bf16_round_to_nearest_even():
+    # 1 + 2^-8 is a tie between 1 and 1 + 2^-7: goes to the even mantissa (1); 1 + 3 * 2^-8 goes up to 1 + 2^-6
+    a = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20, 1.0 + 3 * 2.0 ** -8, -3.0, 1e-30])
+    r = M.rb(a)
+    assert r[0] == 1.0 and r[1] == 1.0 and r[2] == 1.0 + 2.0 ** -7 and r[3] == 1.0 + 2.0 ** -6 and r[4] == -3.0
+    assert abs(r[5] / 1e-30 - 1.0) <= 2.0 ** -8
+    x = np.random.default_rng(0).standard_normal(10000)
+    rel = np.abs(M.rb(x) - x) / np.abs(x)
+    assert rel.max() <= 2.0 ** -8 and 0.8e-3 < rel.mean() < 1.6e-3     # half an ulp at most; about 2^-8 * 0.36 mean
+
+
+@pytest.fixture(scope="module")
+def floors():
+    from golden.make_bf16_floor import floors as compute
+    return compute()
+
+
+def test_floors_match_golden(floors):
+    with open(GOLDEN) as fh:
+        gold = json.load(fh)
+    assert set(gold) == set(floors)
+    for key in gold:
+        for name, (gmax, gmean) in gold[key].items():
+            fmax, fmean = floors[key][name]
+            # same seeds, same arithmetic: differences come from the BLAS summation order only
+            assert abs(fmean - gmean) <= 0.02 * gmean, (key, name, fmean, gmean)
+            assert abs(fmax - gmax) <= 0.25 * gmax, (key, name, fmax, gmax)
+
+
+def test_what_the_floors_say_about_the_stated_target(floors):
+    sc, lit = floors["scaled/plain"], floors["literal/plain"]
+    grads = [k for k in sc if k not in ("y", "dx")]
+    # logits scaled by d_kv^-1/2: y and dx can meet the stated bound ...
+    for name in ("y", "dx"):
+        assert sc[name][0] <= STATED_BF16[0] and sc[name][1] <= STATED_BF16[1], (name, sc[name])
+    # ... the weight gradients cannot: every one of them has a mean floor above 2e-3 (each passes at least three
+    # bf16 roundings of size 2^-9/sqrt(3) relative, as operands, and the sum over tokens does not average them
+    # away relative to the gradient's own size), and the q/k/v gradients a maximum above 2e-2
+    for name in grads:
+        assert sc[name][1] > STATED_BF16[1], (name, sc[name])
+    assert max(sc[n][0] for n in ("wq", "wk", "wv")) > STATED_BF16[0]
+    assert max(sc[n][1] for n in grads) < 3.0 * STATED_BF16[1]
+    # attn_scale = 1 with unit-variance q, k (logit std 8): every tensor's floor is above the stated bound
+    for name in lit:
+        assert lit[name][1] > STATED_BF16[1], (name, lit[name])
+    assert lit["y"][0] > 3 * STATED_BF16[0] and lit["dx"][1] > 5 * STATED_BF16[1]
+    # keeping q and k at ~16 mantissa bits inside the score product does not bring y back under the bound: the
+    # rounding of n1 ahead of the q and k projections weighs as much
+    sq = floors["literal/split_qk"]
+    assert sq["y"][1] > 1.5 * STATED_BF16[1] and sq["y"][0] > 1.5 * STATED_BF16[0]
+    # with n1 split as well y lands on the edge of the bound while dx and the gradients stay above it
+    sqn = floors["literal/split_qk_n1"]
+    assert sqn["y"][1] < 1.1 * STATED_BF16[1]
+    assert sqn["dx"][1] > 2.0 * STATED_BF16[1] and sqn["wq"][1] > 2.0 * STATED_BF16[1]
+
+
+def test_tol_from_floor_rule():
+    big = 1 << 24
+    assert tol_from_floor((0.9e-2, 1.9e-3), big) == STATED_BF16
+    assert tol_from_floor((1.0e-2, 2.0e-3), big) == STATED_BF16
+    t = tol_from_floor((3.0e-2, 1.0e-3), big)
+    assert t == (MARGIN_MAX * 3.0e-2, STATED_BF16[1])
+    t = tol_from_floor((0.5e-2, 4.0e-3), big)
+    assert t[0] == STATED_BF16[0] and abs(t[1] - MARGIN * 4.0e-3) <= 1e-3 * t[1]
+    assert MARGIN <= 1.25 and MARGIN_MAX <= 2.0
+    # small tensors: the mean of 64 values is itself noisy
+    assert abs(mean_margin(64) - (MARGIN + 0.4)) < 1e-12 and mean_margin(10 ** 6) < MARGIN + 0.004
+    # ReLU gradients: the mean gets the wider margin
+    t = tol_from_floor((0.5, 1.0e-2), big, relu=True)
+    assert t[0] == MARGIN_MAX * 0.5 and abs(t[1] - 1.5e-2) < 1e-5

@@ -6,11 +6,12 @@ that the weight-gradient sums match.  In addition, at the full batch of the conf
 bench.py times, the first b0 sequences of y and dx are compared with the oracle (the batch only
 adds independent rows), and properties that hold at any size are checked.
 
-Tolerances (error e_i = |gpu_i - ref_i| / max(|ref_i|, RMS(ref)), max and mean per tensor):
-  y: the stated 2e-2 / 2e-3.  dx and weight gradients: bounds derived from the bf16 MFMA-operand
-  rounding chain (see parity_util).  With attn_scale = 1 and unit-variance q, k the logits have
-  standard deviation sqrt(d_kv); every bf16 rounding of q and k is multiplied by that factor inside
-  the softmax, so that reading is checked against a correspondingly wider bound.
+Tolerances (error e_i = |gpu_i - ref_i| / max(|ref_i|, RMS(ref)), max and mean per tensor): the stated
+2e-2 / 2e-3 for every tensor whose ideal bf16-operand floor (tests/bf16_model.py, evaluated for the same
+case) is at or under it, floor x 1.25 for the others (parity_util.tol_from_floor).  With attn_scale = 1
+and unit-variance q, k the logits have standard deviation sqrt(d_kv); every bf16 rounding of n1, q and k is
+multiplied by that factor inside the softmax, and the floor of that reading lies above the stated bound
+for every tensor.
 """
 from dataclasses import replace
 
@@ -20,9 +21,7 @@ import torch
 
 import synth_inputs as SI
 from oracle import t5_oracle as O
-from parity_util import (TOL_BF16_ACT, TOL_BF16_DW, TOL_BF16_DW_NAMED, TOL_BF16_DX, TOL_BF16_DX_NAMED, make_case,
-                         rel_err, run_block_gpu, to_dev,
-                         to_np)
+from parity_util import block_floors, check_bf16, make_case, rel_err, run_block_gpu, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -40,18 +39,13 @@ def test_config_reduced_batch_scaled_logits(name, b0):
     y, saved = O.block_fwd(cfg, x, w)
     dx, g = O.block_bwd(cfg, dy, w, saved)
     gy, gdx, gg = run_block_gpu(cfg, w, x, dy)
-    ey, edx = rel_err(gy, y), rel_err(gdx, dx)
-    print(name, "y", ey, "dx", edx, {k: tuple(round(v, 5) for v in rel_err(gg[k], g[k])) for k in g})
-    assert ey[0] <= TOL_BF16_ACT[0] and ey[1] <= TOL_BF16_ACT[1], ("y", ey)
-    assert edx[0] <= TOL_BF16_DX_NAMED[0] and edx[1] <= TOL_BF16_DX_NAMED[1], ("dx", edx)
-    for k in g:
-        e = rel_err(gg[k], g[k])
-        assert e[0] <= TOL_BF16_DW_NAMED[0] and e[1] <= TOL_BF16_DW_NAMED[1], (k, e)
+    errs = {"y": rel_err(gy, y), "dx": rel_err(gdx, dx), **{k: rel_err(gg[k], g[k]) for k in g}}
+    check_bf16(name + " scaled", errs, block_floors(cfg, w, x, dy, (y, dx, g)))
     # the bias-table gradient sums to zero over buckets for every head (softmax Jacobian rows sum to 0)
     assert np.abs(gg["rel_table"].sum(0)).max() <= 1e-3 * np.abs(gg["rel_table"]).max() * 32
 
 
-@pytest.mark.parametrize("name,b0", [("c2_small", 2), ("c4_gpt_causal", 1)])
+@pytest.mark.parametrize("name,b0", [("c2_small", 2), ("c3_base", 2), ("c4_gpt_causal", 1), ("c5_xl", 1)])
 def test_config_literal_unscaled_logits(name, b0):
     """attn_scale = 1 (no 1/sqrt(d_kv)) with unit-variance q, k: logits of std sqrt(d_kv)."""
     cfg = SI.CONFIGS[name].with_batch(b0)
@@ -60,14 +54,8 @@ def test_config_literal_unscaled_logits(name, b0):
     y, saved = O.block_fwd(cfg, x, w)
     dx, g = O.block_bwd(cfg, dy, w, saved)
     gy, gdx, gg = run_block_gpu(cfg, w, x, dy)
-    amp = cfg.d_kv ** 0.5
-    ey, edx = rel_err(gy, y), rel_err(gdx, dx)
-    print(name, "unscaled y", ey, "dx", edx)
-    assert ey[0] <= TOL_BF16_ACT[0] * amp and ey[1] <= TOL_BF16_ACT[1] * amp, ("y", ey)
-    assert edx[0] <= TOL_BF16_DX[0] * amp and edx[1] <= TOL_BF16_DX[1] * amp, ("dx", edx)
-    for k in g:
-        e = rel_err(gg[k], g[k])
-        assert e[0] <= TOL_BF16_DW[0] * amp and e[1] <= TOL_BF16_DW[1] * amp, (k, e)
+    errs = {"y": rel_err(gy, y), "dx": rel_err(gdx, dx), **{k: rel_err(gg[k], g[k]) for k in g}}
+    check_bf16(name + " literal", errs, block_floors(cfg, w, x, dy, (y, dx, g)))
 
 
 @pytest.mark.parametrize("name,b0", [("c2_small", 2), ("c3_base", 1), ("c4_gpt_causal", 1), ("c5_xl", 1)])
@@ -81,7 +69,7 @@ def test_bench_workload_full_batch_sampled(name, b0):
     x, dy = SI.make_activations(cfg)
     small = cfg.with_batch(b0)
     y, saved = O.block_fwd(small, x[:b0], w)
-    dx, _ = O.block_bwd(small, dy[:b0], w, saved)
+    dx, g_small = O.block_bwd(small, dy[:b0], w, saved)
     dw = {k: to_dev(v, cfg.dtype) for k, v in w.items()}
     tx, tdy = to_dev(x, cfg.dtype), to_dev(dy, cfg.dtype)
     gy, stash = P.t5_block_fwd(cfg, tx, dw)
@@ -89,10 +77,11 @@ def test_bench_workload_full_batch_sampled(name, b0):
     gy2, stash2 = P.t5_block_fwd(cfg, tx, dw)
     gdx2, _ = P.t5_block_bwd(cfg, tdy, tx, dw, stash2)
     torch.cuda.synchronize()
-    ey, edx = rel_err(to_np(gy[:b0]), y), rel_err(to_np(gdx[:b0]), dx)
-    print(name, "full batch sample: y", ey, "dx", edx)
-    assert ey[0] <= TOL_BF16_ACT[0] and ey[1] <= TOL_BF16_ACT[1], ey
-    assert edx[0] <= TOL_BF16_DX_NAMED[0] and edx[1] <= TOL_BF16_DX_NAMED[1], edx
+    errs = {"y": rel_err(to_np(gy[:b0]), y), "dx": rel_err(to_np(gdx[:b0]), dx)}
+    # y and dx of a sequence do not depend on the other sequences: the floor of the sampled rows is the floor
+    # of the same rows run alone
+    check_bf16(name + " full batch sample", errs, block_floors(small, w, x[:b0], dy[:b0], (y, dx, g_small)),
+               only=("y", "dx"))
     assert torch.equal(gy, gy2) and torch.equal(gdx, gdx2)          # y, dx use no atomics
     assert all(torch.isfinite(v).all() for v in gg.values())
     tab = to_np(gg["rel_table"])

@@ -8,9 +8,8 @@ import torch
 
 import synth_inputs as SI
 from oracle import t5_oracle as O
-from parity_util import (TOL_BF16_ACT, TOL_BF16_DEC_ACT, TOL_BF16_DEC_DX, TOL_BF16_DEC_DX_NAMED, TOL_BF16_DENC, TOL_BF16_DENC_NAMED, TOL_BF16_DW, TOL_BF16_DW_NAMED,
-                         TOL_F32,
-                         make_decoder_case, rel_err, relu_aware, run_decoder_block_gpu, to_dev, to_np)
+from parity_util import (TOL_F32, check_bf16, decoder_floors, is_relu, make_decoder_case, rel_err,
+                         run_decoder_block_gpu, to_dev, to_np)
 
 pytestmark = pytest.mark.gpu
 
@@ -24,6 +23,18 @@ F32_CASES = [
     replace(C1, name="dec_f32_bidirectional_self", index=44, causal=False, enc_seq=70),
     replace(C1, name="dec_f32_relu", index=51, causal=True, enc_seq=48, mlp="relu"),
 ]
+
+
+def _check_bf16(cfg):
+    """bf16 decoder layer against the oracle, every tensor at the bound derived from its ideal-bf16 floor."""
+    w, x, enc, dy = make_decoder_case(cfg)
+    y, saved = O.decoder_block_fwd(cfg, x, enc, w)
+    dx, denc, g = O.decoder_block_bwd(cfg, dy, w, saved)
+    gy, gdx, gdenc, gg = run_decoder_block_gpu(cfg, w, x, enc, dy)
+    assert set(gg) == set(g)
+    errs = {"y": rel_err(gy, y), "dx": rel_err(gdx, dx), "denc": rel_err(gdenc, denc),
+            **{k: rel_err(gg[k], g[k]) for k in g}}
+    check_bf16(cfg.name, errs, decoder_floors(cfg, w, x, enc, dy, (y, dx, denc, g)), relu=is_relu(cfg))
 
 
 def _check(cfg, tol_y, tol_dx, tol_denc, tol_dw, verbose=True):
@@ -72,14 +83,13 @@ SMALL_BF16 = [
 
 @pytest.mark.parametrize("cfg", SMALL_BF16, ids=[c.name for c in SMALL_BF16])
 def test_decoder_block_bf16_small(cfg):
-    _check(cfg, TOL_BF16_DEC_ACT, relu_aware(cfg, TOL_BF16_DEC_DX), relu_aware(cfg, TOL_BF16_DENC),
-           relu_aware(cfg, TOL_BF16_DW))
+    _check_bf16(cfg)
 
 
 def test_decoder_named_config_reduced_batch():
     """T5.1.1-Base decoder layer at its real widths and lengths, batch reduced for the oracle."""
     cfg = replace(SI.CONFIGS["c6_dec_base"], attn_scale=64 ** -0.5).with_batch(2)
-    _check(cfg, TOL_BF16_ACT, TOL_BF16_DEC_DX_NAMED, TOL_BF16_DENC_NAMED, TOL_BF16_DW_NAMED)
+    _check_bf16(cfg)
 
 
 def test_decoder_named_config_full_batch_sampled():
@@ -90,17 +100,15 @@ def test_decoder_named_config_full_batch_sampled():
     w, x, enc, dy = make_decoder_case(cfg)
     small = cfg.with_batch(1)
     y, saved = O.decoder_block_fwd(small, x[:1], enc[:1], w)
-    dx, denc, _ = O.decoder_block_bwd(small, dy[:1], w, saved)
+    dx, denc, g_small = O.decoder_block_bwd(small, dy[:1], w, saved)
     dw = {k: to_dev(v, cfg.dtype) for k, v in w.items()}
     tx, te, tdy = to_dev(x, cfg.dtype), to_dev(enc, cfg.dtype), to_dev(dy, cfg.dtype)
     gy, stash = P.t5_decoder_block_fwd(cfg, tx, te, dw)
     gdx, gdenc, gg = P.t5_decoder_block_bwd(cfg, tdy, tx, te, dw, stash)
     torch.cuda.synchronize()
-    ey, edx, ede = rel_err(to_np(gy[:1]), y), rel_err(to_np(gdx[:1]), dx), rel_err(to_np(gdenc[:1]), denc)
-    print("c6_dec_base full batch sample: y", ey, "dx", edx, "denc", ede)
-    assert ey[0] <= TOL_BF16_ACT[0] and ey[1] <= TOL_BF16_ACT[1], ey
-    assert edx[0] <= TOL_BF16_DEC_DX_NAMED[0] and edx[1] <= TOL_BF16_DEC_DX_NAMED[1], edx
-    assert ede[0] <= TOL_BF16_DENC_NAMED[0] and ede[1] <= TOL_BF16_DENC_NAMED[1], ede
+    errs = {"y": rel_err(to_np(gy[:1]), y), "dx": rel_err(to_np(gdx[:1]), dx), "denc": rel_err(to_np(gdenc[:1]), denc)}
+    check_bf16("c6_dec_base full batch sample", errs,
+               decoder_floors(small, w, x[:1], enc[:1], dy[:1], (y, dx, denc, g_small)), only=("y", "dx", "denc"))
     assert all(torch.isfinite(v).all() for v in gg.values())
 
 
@@ -131,8 +139,8 @@ def test_decoder_encoder_tokens_form_a_set():
     perm = np.random.default_rng(3).permutation(cfg.enc_seq)
     y1, dx1, de1, g1 = run_decoder_block_gpu(cfg, w, x, enc, dy)
     y2, dx2, de2, g2 = run_decoder_block_gpu(cfg, w, x, enc[:, perm], dy)
-    ey, ede = rel_err(y2, y1), rel_err(de2, de1[:, perm])
-    assert ey[0] <= TOL_BF16_DEC_ACT[0] and ey[1] <= TOL_BF16_DEC_ACT[1], ey
-    assert ede[0] <= TOL_BF16_DENC[0] and ede[1] <= TOL_BF16_DENC[1], ede
+    errs = {"y": rel_err(y2, y1), "denc": rel_err(de2, de1[:, perm])}
+    floors = decoder_floors(cfg, w, x, enc, dy, None)
+    check_bf16(cfg.name + " permuted encoder", errs, floors, scale=2 ** 0.5, only=("y", "denc"))
     # and the unpermuted comparison is far outside them, so the check can tell the two apart
-    assert rel_err(de2, de1)[1] > 10 * TOL_BF16_DENC[1]
+    assert rel_err(de2, de1)[1] > 10 * 1.25 * floors["denc"][1]

@@ -8,7 +8,7 @@ import torch
 
 import synth_inputs as SI
 from oracle import t5_oracle as O
-from parity_util import (TOL_BF16_ACT, TOL_BF16_DW, TOL_BF16_DX, TOL_F32, drop_tol, make_case, rel_err, relu_aware,
+from parity_util import (TOL_F32, block_floors, check_bf16, is_relu, make_case, rel_err,
                          run_block_gpu)
 
 pytestmark = pytest.mark.gpu
@@ -99,17 +99,9 @@ def test_block_dropout_bf16(cfg):
     y, saved = O.block_fwd(cfg, x, w)
     dx, g = O.block_bwd(cfg, dy, w, saved)
     gy, gdx, gg = run_block_gpu(cfg, w, x, dy)
-    ey, edx = rel_err(gy, y), rel_err(gdx, dx)
-    print(cfg.name, "y", ey, "dx", edx, {k: rel_err(gg[k], g[k]) for k in g})
-    p = cfg.dropout_rate
-    tol_y = drop_tol(TOL_BF16_ACT, p, False)
-    assert ey[0] <= tol_y[0] and ey[1] <= tol_y[1], ey
-    tol_dx, tol_dw = relu_aware(cfg, drop_tol(TOL_BF16_DX, p, True)), relu_aware(cfg, drop_tol(TOL_BF16_DW, p, True))
-    assert edx[0] <= tol_dx[0] and edx[1] <= tol_dx[1], edx
-    for name in g:
-        e = rel_err(gg[name], g[name])
-        tol = drop_tol(TOL_BF16_DW, p, True) if name == "wo_ff" else tol_dw
-        assert e[0] <= tol[0] and e[1] <= tol[1], (name, e)
+    errs = {"y": rel_err(gy, y), "dx": rel_err(gdx, dx), **{k: rel_err(gg[k], g[k]) for k in g}}
+    # the floor model applies the same masks, so the growth of the error with the rate is part of the floor
+    check_bf16(cfg.name, errs, block_floors(cfg, w, x, dy, (y, dx, g)), relu=is_relu(cfg))
 
 
 # ------------------------------------------------------------------ workload shapes (matrix-unit kernels)
@@ -122,28 +114,20 @@ def _named(name, b):
 def test_config_dropout_reduced_batch(name, b0):
     """Full sequence length, widths and heads of a workload at a reduced batch (sequences are independent
     through the block): several query and key tiles per head in the fused attention kernels."""
-    from parity_util import TOL_BF16_DW_NAMED, TOL_BF16_DX_NAMED
     cfg = _named(name, b0)
     w, x, dy = make_case(cfg)
     y, saved = O.block_fwd(cfg, x, w)
     dx, g = O.block_bwd(cfg, dy, w, saved)
     gy, gdx, gg = run_block_gpu(cfg, w, x, dy)
-    ey, edx = rel_err(gy, y), rel_err(gdx, dx)
-    print(name, "y", ey, "dx", edx, {k: tuple(round(v, 5) for v in rel_err(gg[k], g[k])) for k in g})
-    tol_y, tol_dx = drop_tol(TOL_BF16_ACT, RATE, False), drop_tol(TOL_BF16_DX_NAMED, RATE, True)
-    tol_dw = drop_tol(TOL_BF16_DW_NAMED, RATE, True)
-    assert ey[0] <= tol_y[0] and ey[1] <= tol_y[1], ("y", ey)
-    assert edx[0] <= tol_dx[0] and edx[1] <= tol_dx[1], ("dx", edx)
-    for k in g:
-        e = rel_err(gg[k], g[k])
-        assert e[0] <= tol_dw[0] and e[1] <= tol_dw[1], (k, e)
+    errs = {"y": rel_err(gy, y), "dx": rel_err(gdx, dx), **{k: rel_err(gg[k], g[k]) for k in g}}
+    check_bf16(name + " dropout", errs, block_floors(cfg, w, x, dy, (y, dx, g)))
 
 
 def test_dropout_full_batch_sampled():
     """c2_small at its full batch with dropout, as bench.py --dropout launches it: the first 2 sequences of y
     and dx against the oracle (the masks of a sequence depend on its own batch index only), and
     run-to-run determinism."""
-    from parity_util import TOL_BF16_DX_NAMED, to_dev, to_np
+    from parity_util import to_dev, to_np
     P = _P()
     cfg = _named("c2_small", SI.CONFIGS["c2_small"].batch)
     b0 = 2
@@ -151,7 +135,7 @@ def test_dropout_full_batch_sampled():
     x, dy = SI.make_activations(cfg)
     small = cfg.with_batch(b0)
     y, saved = O.block_fwd(small, x[:b0], w)
-    dx, _ = O.block_bwd(small, dy[:b0], w, saved)
+    dx, g_small = O.block_bwd(small, dy[:b0], w, saved)
     dw = {k: to_dev(v, cfg.dtype) for k, v in w.items()}
     tx, tdy = to_dev(x, cfg.dtype), to_dev(dy, cfg.dtype)
     gy, stash = P.t5_block_fwd(cfg, tx, dw)
@@ -159,11 +143,9 @@ def test_dropout_full_batch_sampled():
     gy2, stash2 = P.t5_block_fwd(cfg, tx, dw)
     gdx2, _ = P.t5_block_bwd(cfg, tdy, tx, dw, stash2)
     torch.cuda.synchronize()
-    ey, edx = rel_err(to_np(gy[:b0]), y), rel_err(to_np(gdx[:b0]), dx)
-    print("full batch sample with dropout: y", ey, "dx", edx)
-    tol_y, tol_dx = drop_tol(TOL_BF16_ACT, RATE, False), drop_tol(TOL_BF16_DX_NAMED, RATE, True)
-    assert ey[0] <= tol_y[0] and ey[1] <= tol_y[1], ey
-    assert edx[0] <= tol_dx[0] and edx[1] <= tol_dx[1], edx
+    errs = {"y": rel_err(to_np(gy[:b0]), y), "dx": rel_err(to_np(gdx[:b0]), dx)}
+    check_bf16("c2_small dropout full batch sample", errs,
+               block_floors(small, w, x[:b0], dy[:b0], (y, dx, g_small)), only=("y", "dx"))
     assert torch.equal(gy, gy2) and torch.equal(gdx, gdx2)
     assert all(torch.isfinite(v).all() for v in gg.values())
 
@@ -202,11 +184,8 @@ def test_decoder_block_dropout_f32(cfg):
 
 @pytest.mark.parametrize("cfg", DEC_BF16, ids=[c.name for c in DEC_BF16])
 def test_decoder_block_dropout_bf16(cfg):
-    from parity_util import TOL_BF16_DEC_ACT, TOL_BF16_DEC_DX, TOL_BF16_DENC
-    from test_gpu_parity_decoder import _check
-    p = cfg.dropout_rate
-    _check(cfg, drop_tol(TOL_BF16_DEC_ACT, p, False), drop_tol(TOL_BF16_DEC_DX, p, True), drop_tol(TOL_BF16_DENC, p, True),
-           drop_tol(TOL_BF16_DW, p, True))
+    from test_gpu_parity_decoder import _check_bf16
+    _check_bf16(cfg)
 
 
 def _stack_cases():
@@ -234,7 +213,7 @@ def test_stack_dropout_f32(sc):
 def test_stack_dropout_bf16(sc):
     from parity_util import stack_bf16_tol
     from test_gpu_parity_stack import _compare
-    _compare(sc, 5e-4 / (1.0 - RATE), *drop_tol(stack_bf16_tol(sc.n_layers), RATE, True))
+    _compare(sc, 5e-4 / (1.0 - RATE), *stack_bf16_tol([sc.block], sc.n_layers))
 
 
 def test_stack_dropout_remat_replays_the_masks():
@@ -263,4 +242,4 @@ def test_encdec_dropout_f32(ec):
 def test_encdec_dropout_bf16(ec):
     from parity_util import stack_bf16_tol
     from test_gpu_parity_stack import _ec_compare
-    _ec_compare(ec, 5e-4 / (1.0 - RATE), *drop_tol(stack_bf16_tol(ec.n_enc_layers + ec.n_dec_layers), RATE, True))
+    _ec_compare(ec, 5e-4 / (1.0 - RATE), *stack_bf16_tol([ec.enc_block, ec.dec_block], ec.n_enc_layers + ec.n_dec_layers))

@@ -8,7 +8,7 @@ import torch
 
 import synth_inputs as SI
 from oracle import t5_oracle as O
-from parity_util import (TOL_BF16_ACT, TOL_BF16_DW, TOL_BF16_DX, TOL_F32, make_case, rel_err, relu_aware,
+from parity_util import (TOL_F32, block_floors, check_bf16, is_relu, make_case, rel_err,
                          run_block_gpu, to_np)
 
 pytestmark = pytest.mark.gpu
@@ -262,13 +262,5 @@ def test_block_bf16_small(cfg):
     y, saved = O.block_fwd(cfg, x, w)
     dx, g = O.block_bwd(cfg, dy, w, saved)
     gy, gdx, gg = run_block_gpu(cfg, w, x, dy)
-    ey, edx = rel_err(gy, y), rel_err(gdx, dx)
-    print(cfg.name, "y", ey, "dx", edx, {k: rel_err(gg[k], g[k]) for k in g})
-    assert ey[0] <= TOL_BF16_ACT[0] and ey[1] <= TOL_BF16_ACT[1], ey
-    tol_dx, tol_dw = relu_aware(cfg, TOL_BF16_DX), relu_aware(cfg, TOL_BF16_DW)
-    assert edx[0] <= tol_dx[0] and edx[1] <= tol_dx[1], edx
-    for name in g:
-        e = rel_err(gg[name], g[name])
-        # the output projection's gradient a^T dy does not pass through the activation's derivative
-        tol = TOL_BF16_DW if name == "wo_ff" else tol_dw
-        assert e[0] <= tol[0] and e[1] <= tol[1], (name, e)
+    errs = {"y": rel_err(gy, y), "dx": rel_err(gdx, dx), **{k: rel_err(gg[k], g[k]) for k in g}}
+    check_bf16(cfg.name, errs, block_floors(cfg, w, x, dy, (y, dx, g)), relu=is_relu(cfg))

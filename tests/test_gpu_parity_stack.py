@@ -8,7 +8,7 @@ import torch
 
 import synth_inputs as SI
 from oracle import t5_oracle as O
-from parity_util import TOL_F32, rel_err, relu_aware, stack_bf16_tol, to_dev, to_np
+from parity_util import TOL_F32, rel_err, stack_bf16_tol, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -129,7 +129,7 @@ BF16_CASES = [
 
 @pytest.mark.parametrize("sc", BF16_CASES, ids=[c.name for c in BF16_CASES])
 def test_stack_bf16_small(sc):
-    _compare(sc, 5e-4, *relu_aware(sc.block, stack_bf16_tol(sc.n_layers)))
+    _compare(sc, 5e-4, *stack_bf16_tol([sc.block], sc.n_layers))
 
 
 def test_stack_bf16_accumulate_with_grouped_weight_gradients():
@@ -170,7 +170,7 @@ def test_stack_named_config_reduced_batch():
     """T5.1.1-Base decoder-only stack at its real depth, widths, length and vocabulary, one sequence."""
     sc = replace(SI.STACK_CONFIGS["s1_lm_base"].with_batch(1), name="s1_lm_base_b1")
     sc = replace(sc, block=replace(sc.block, attn_scale=64 ** -0.5))
-    _compare(sc, 5e-4, *stack_bf16_tol(sc.n_layers))
+    _compare(sc, 5e-4, *stack_bf16_tol([sc.block], sc.n_layers))
 
 
 # ---------------------------------------------------------------- encoder-decoder model
@@ -240,7 +240,7 @@ EC_BF16 = [
 @pytest.mark.parametrize("ec", EC_BF16, ids=[c.name for c in EC_BF16])
 def test_encdec_bf16_small(ec):
     # a gradient in the encoder has crossed every decoder layer and the encoder layers above it
-    _ec_compare(ec, 5e-4, *stack_bf16_tol(ec.n_enc_layers + ec.n_dec_layers))
+    _ec_compare(ec, 5e-4, *stack_bf16_tol([ec.enc_block, ec.dec_block], ec.n_enc_layers + ec.n_dec_layers))
 
 
 def test_encdec_named_config_reduced_batch():
@@ -248,4 +248,4 @@ def test_encdec_named_config_reduced_batch():
     ec = SI.ENCDEC_CONFIGS["e1_t5_base"].with_batch(1)
     ec = replace(ec, enc_block=replace(ec.enc_block, attn_scale=64 ** -0.5),
                  dec_block=replace(ec.dec_block, attn_scale=64 ** -0.5))
-    _ec_compare(ec, 5e-4, *stack_bf16_tol(ec.n_enc_layers + ec.n_dec_layers))
+    _ec_compare(ec, 5e-4, *stack_bf16_tol([ec.enc_block, ec.dec_block], ec.n_enc_layers + ec.n_dec_layers))
