@@ -357,6 +357,19 @@ int adafactor_step(float* param, const float* grad, float* v_row, float* v_col, 
                    int64_t rows, int64_t cols, int factored, const adafactor_cfg* cfg,
                    void* bf16_copy_out, void* workspace, size_t workspace_bytes, void* stream);
 
+/* adafactor_step for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving or training loops, harnesses that forbid allocation.  Same arguments, results and
+ * errors as adafactor_step, without workspace / workspace_bytes: the scratch is a fixed device array of
+ * ADAFACTOR_STATIC_SCRATCH_BYTES inside the library (each GPU the library runs on holds its own copy until
+ * the process ends).  A tensor whose adafactor_workspace_bytes() exceeds that size is refused with
+ * T5_ERR_WORKSPACE before any device work.  The call allocates nothing and frees nothing.  All calls on one GPU
+ * share that GPU's array: calls that may overlap on one GPU (different streams, different host threads) race
+ * and must be serialised by the caller; calls in stream order on one stream are safe. */
+#define ADAFACTOR_STATIC_SCRATCH_BYTES (4u << 20)
+int adafactor_step_static(float* param, const float* grad, float* v_row, float* v_col, float* v_full,
+                          int64_t rows, int64_t cols, int factored, const adafactor_cfg* cfg,
+                          void* bf16_copy_out, void* stream);
+
 /* The same update for several tensors at once (the ten parameter tensors of a block): one sequence
  * of five launches for the whole set instead of five per tensor, which is what the step costs at
  * T5.1.1-Small/Base sizes.  Each entry is what adafactor_step takes for one tensor; every tensor

@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     WEIGHT_NAMES,
     adafactor_step,
     adafactor_step_multi,
+    adafactor_step_static,
     adafactor_multi_workspace_bytes,
     adafactor_workspace_bytes,
     lib,

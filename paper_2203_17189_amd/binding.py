@@ -146,6 +146,8 @@ def lib() -> C.CDLL:
     L.adafactor_workspace_bytes.argtypes = [i64, i64, i32]
     L.adafactor_step.restype = i32
     L.adafactor_step.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, C.POINTER(_AfCfg), vp, vp, sz, vp]
+    L.adafactor_step_static.restype = i32
+    L.adafactor_step_static.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, C.POINTER(_AfCfg), vp, vp]
     L.adafactor_multi_workspace_bytes.restype = sz
     L.adafactor_multi_workspace_bytes.argtypes = [C.POINTER(_AfTensor), i32]
     L.adafactor_step_multi.restype = i32
@@ -591,6 +593,29 @@ def adafactor_step(param, grad, *, step, lr, factored, v_row=None, v_col=None, v
                               workspace.numel(), _stream())
     if rc:
         raise T5Error(rc, "adafactor_step")
+    return param
+
+
+def adafactor_step_static(param, grad, *, step, lr, factored, v_row=None, v_col=None, v_full=None, decay_pow=0.8,
+                          eps1=1e-30, eps2=1e-3, clip=1.0, scale_by_param=True, bf16_copy_out=None,
+                          weight_decay=0.0):
+    """adafactor_step through the entry point that allocates nothing: no workspace argument, the scratch is a
+    fixed device array inside the library (tensors beyond its size are refused)."""
+    rows, cols = (param.shape[0], param.numel() // param.shape[0]) if param.dim() >= 2 else (1, param.numel())
+    _check_tensor(param, torch.float32, rows * cols, "param")
+    _check_tensor(grad, torch.float32, rows * cols, "grad")
+    if factored:
+        _check_tensor(v_row, torch.float32, rows, "v_row")
+        _check_tensor(v_col, torch.float32, cols, "v_col")
+    else:
+        _check_tensor(v_full, torch.float32, rows * cols, "v_full")
+    if bf16_copy_out is not None:
+        _check_tensor(bf16_copy_out, torch.bfloat16, rows * cols, "bf16_copy_out")
+    cfg = _AfCfg(lr, decay_pow, eps1, eps2, clip, int(bool(scale_by_param)), int(step), 0.0, float(weight_decay))
+    rc = lib().adafactor_step_static(_ptr(param), _ptr(grad), _ptr(v_row), _ptr(v_col), _ptr(v_full), rows, cols,
+                                     int(bool(factored)), C.byref(cfg), _ptr(bf16_copy_out), _stream())
+    if rc:
+        raise T5Error(rc, "adafactor_step_static")
     return param
 
 

@@ -411,3 +411,43 @@ hipError_t launch_adafactor(float* param, const float* grad, float* v_row, float
 }
 
 }  // namespace t5mi
+
+// ------------------------------------------------------------------------------------------------
+// adafactor_step_static: the single-tensor update for callers that cannot allocate.  Its scratch
+// (the tile partial sums and factors that adafactor_step takes from the caller's workspace) is this
+// file-scope device array; every GPU holds its own copy at its own address, looked up once per device.
+// ------------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[ADAFACTOR_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each GPU, set on first use there
+}  // namespace
+
+extern "C" int adafactor_step_static(float* param, const float* grad, float* v_row, float* v_col, float* v_full,
+                                     int64_t rows, int64_t cols, int factored, const adafactor_cfg* cfg,
+                                     void* bf16_copy_out, void* stream) {
+  using namespace t5mi;
+  if (!cfg) return T5_ERR_NULL;
+  if (rows < 1 || cols < 1 || cfg->step < 1 || !(cfg->clip > 0.f) || !(cfg->eps1 >= 0.f)) return T5_ERR_SHAPE;
+  if (!(cfg->beta1 >= 0.f && cfg->beta1 < 1.f) || !(cfg->weight_decay >= 0.f)) return T5_ERR_SHAPE;
+  if (cfg->beta1 > 0.f) return T5_ERR_UNSUPPORTED;
+  if (rows > (1 << 24) || cols > (1 << 24)) return T5_ERR_UNSUPPORTED;
+  if (!param || !grad) return T5_ERR_NULL;
+  if (factored ? (!v_row || !v_col) : !v_full) return T5_ERR_NULL;
+  if (adafactor_ws_bytes(rows, cols, factored) > (size_t)ADAFACTOR_STATIC_SCRATCH_BYTES) return T5_ERR_WORKSPACE;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return T5_ERR_DEVICE;
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return T5_ERR_DEVICE;
+    g_scratch_ptr[dev] = p;
+  }
+  // Nothing in the scratch has to start at zero: every partial sum, factor and scalar a kernel of this
+  // update reads was written by an earlier kernel of the same update.
+  if (launch_adafactor(param, grad, v_row, v_col, v_full, rows, cols, factored, *cfg, bf16_copy_out,
+                       g_scratch_ptr[dev], (hipStream_t)stream) != hipSuccess)
+    return T5_ERR_DEVICE;
+  return T5_OK;
+}
+
