@@ -22,6 +22,7 @@
 // compact block of output tiles and shares operand tiles through its own L2.
 #include "kernels.h"
 #include <atomic>
+#include <type_traits>
 
 namespace t5mi {
 
@@ -62,44 +63,60 @@ __device__ __forceinline__ bf16x8 load_frag(const char* stage, int base, int kk,
   }
 }
 
-// Position in a workgroup's sequence of k-tiles, in scalar registers: global base addresses of the
-// next tile and the number of tiles left in the current run.  A k-slice is at most three runs of
-// consecutive tiles (one per segment); the runs are kept as a list that is rotated when the first
-// one is used up, so nothing is indexed by a run number.  Advancing costs two adds per tile --
-// recomputing the position from the tile number (a modulo, a segment search through the kernel
-// arguments) cost some forty scalar instructions and a scalar load per k-tile.
+// Position in a workgroup's sequence of k-tiles, in scalar registers: global base addresses of the next
+// tile and the number of tiles left in the current run.  A k-slice is at most three runs of consecutive
+// tiles (one per segment).  A wave issues one instruction every four cycles and a matrix instruction
+// occupies its pipe for 32: seven other instructions fit between two of them for free, and every one
+// beyond that is a bubble in the matrix pipe.  The cursor therefore advances without branches, in a few
+// scalar and/or/add steps (a conditional expression on the fields compiles to a select of addresses,
+// which puts the cursor into memory, or to branches), and the main loop calls the two halves of the
+// update in two different gaps.  Past the end of the last run the cursor stays on the last tile: the
+// pipeline requests NS - 1 tiles more than it uses, and those refetch valid data.
 struct KCursor {
-  const char *a, *b;  // bases of the next tile
+  uint64_t a, b;      // bases of the next tile
   int rem;            // tiles left in the current run, this one included
-  const char *ra0, *rb0, *ra1, *rb1, *ra2, *rb2;
-  int rn0, rn1, rn2, nruns;
-  size_t step_a, step_b;
+  uint64_t step_a, step_b;
+  // runs after the current one (MULTI only): what to add to a / b at the switch instead of the step
+  // (start of that run minus last tile of the one before), and the run lengths (0: no such run)
+  uint64_t da1, db1, da2, db2;
+  int rn1, rn2;
+  // masks of the update in progress: all ones when the run has another tile / when the next run starts
+  uint64_t m_stay, m_sw;
 };
-__device__ __forceinline__ void cursor_rotate(KCursor& c) {
-  if (c.nruns == 2) {
-    const char* ta = c.ra0; const char* tb = c.rb0; const int tn = c.rn0;
-    c.ra0 = c.ra1; c.rb0 = c.rb1; c.rn0 = c.rn1;
-    c.ra1 = ta; c.rb1 = tb; c.rn1 = tn;
-  } else if (c.nruns == 3) {
-    const char* ta = c.ra0; const char* tb = c.rb0; const int tn = c.rn0;
-    c.ra0 = c.ra1; c.rb0 = c.rb1; c.rn0 = c.rn1;
-    c.ra1 = c.ra2; c.rb1 = c.rb2; c.rn1 = c.rn2;
-    c.ra2 = ta; c.rb2 = tb; c.rn2 = tn;
+// first half: hands out the current tile and moves the bases on
+template <bool MULTI>
+__device__ __forceinline__ void cursor_bases(KCursor& c, const char*& abase, const char*& bbase) {
+  abase = (const char*)c.a;
+  bbase = (const char*)c.b;
+  c.m_stay = (uint64_t)(int64_t)(c.rem > 1 ? -1 : 0);
+  if constexpr (MULTI) {
+    c.m_sw = (uint64_t)(int64_t)((c.rem <= 1 && c.rn1 > 0) ? -1 : 0);
+    c.a += (c.step_a & c.m_stay) | (c.da1 & c.m_sw);
+    c.b += (c.step_b & c.m_stay) | (c.db1 & c.m_sw);
+  } else {
+    c.a += c.step_a & c.m_stay;
+    c.b += c.step_b & c.m_stay;
   }
 }
-// Returns the bases of the next tile and moves on; the sequence wraps around at the end.
-__device__ __forceinline__ void cursor_next(KCursor& c, const char*& abase, const char*& bbase) {
-  abase = c.a;
-  bbase = c.b;
-  if (--c.rem > 0) {
-    c.a += c.step_a;
-    c.b += c.step_b;
+// second half: the run counters
+template <bool MULTI>
+__device__ __forceinline__ void cursor_counts(KCursor& c) {
+  const int i_stay = (int)c.m_stay;
+  if constexpr (MULTI) {
+    const int i_sw = (int)c.m_sw;
+    c.rem = ((c.rem - 1) & i_stay) | (c.rn1 & i_sw) | (1 & ~(i_stay | i_sw));
+    c.da1 = (c.da2 & c.m_sw) | (c.da1 & ~c.m_sw);
+    c.db1 = (c.db2 & c.m_sw) | (c.db1 & ~c.m_sw);
+    c.rn1 = (c.rn2 & i_sw) | (c.rn1 & ~i_sw);
+    c.rn2 = c.rn2 & ~i_sw;
   } else {
-    cursor_rotate(c);
-    c.a = c.ra0;
-    c.b = c.rb0;
-    c.rem = c.rn0;
+    c.rem += i_stay;  // counts down to 1 and stays there
   }
+}
+template <bool MULTI>
+__device__ __forceinline__ void cursor_next(KCursor& c, const char*& abase, const char*& bbase) {
+  cursor_bases<MULTI>(c, abase, bbase);
+  cursor_counts<MULTI>(c);
 }
 
 // EPI_T: the epilogue kind, plus EPI_DROP when the result passes a dropout site (a separate instantiation,
@@ -174,7 +191,6 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
   const int kt_end = (kt_begin + per) < nk_total ? (kt_begin + per) : nk_total;
   const int nk = kt_end - kt_begin;
   const int lda = g.seg[0].lda, ldb = g.seg[0].ldb;
-  const int k_skew = nk > 0 ? (tm * 4 + tn) % nk : 0;
 
   // ---- per-lane byte offsets of this wave's DMA slots (loop invariant)
   uint32_t a_off[A_DMA], b_off[B_DMA];
@@ -218,44 +234,39 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
   }
   const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)smem;
 
-  // Workgroups start their k loop at different phases (rotated by a multiple of the tile
-  // coordinates) so that concurrently running tiles do not all stream the same 256-byte-interleaved
-  // L2 channel; the sequence wraps around, and tiles requested past the end refetch valid data that
-  // is never used.
   KCursor kc;
-  kc.step_a = A_KC ? (size_t)BK * 2 : (size_t)BK * (size_t)lda * 2;
-  kc.step_b = B_KC ? (size_t)BK * 2 : (size_t)BK * (size_t)ldb * 2;
-  kc.nruns = g.nseg;
-  kc.ra1 = kc.rb1 = kc.ra2 = kc.rb2 = nullptr;
+  kc.step_a = A_KC ? (uint64_t)BK * 2 : (uint64_t)BK * (uint64_t)lda * 2;
+  kc.step_b = B_KC ? (uint64_t)BK * 2 : (uint64_t)BK * (uint64_t)ldb * 2;
+  kc.da1 = kc.db1 = kc.da2 = kc.db2 = 0;
   kc.rn1 = kc.rn2 = 0;
+  kc.m_stay = kc.m_sw = 0;
   if (g.nseg == 1) {
-    kc.ra0 = (const char*)seg_a + (size_t)kt_begin * kc.step_a;
-    kc.rb0 = (const char*)seg_b + (size_t)kt_begin * kc.step_b;
-    kc.rn0 = nk;
+    kc.a = (uint64_t)seg_a + (uint64_t)kt_begin * kc.step_a;
+    kc.b = (uint64_t)seg_b + (uint64_t)kt_begin * kc.step_b;
+    kc.rem = nk;
   } else {  // several segments are never split along k
-    kc.ra0 = (const char*)g.seg[0].A; kc.rb0 = (const char*)g.seg[0].B; kc.rn0 = g.seg[0].K / BK;
-    kc.ra1 = (const char*)g.seg[1].A; kc.rb1 = (const char*)g.seg[1].B; kc.rn1 = g.seg[1].K / BK;
-    if (g.nseg > 2) { kc.ra2 = (const char*)g.seg[2].A; kc.rb2 = (const char*)g.seg[2].B; kc.rn2 = g.seg[2].K / BK; }
-  }
-  {
-    int o = k_skew;  // < nk = rn0 + rn1 + rn2
-    if (kc.nruns > 1 && o >= kc.rn0) { o -= kc.rn0; cursor_rotate(kc); }
-    if (kc.nruns > 2 && o >= kc.rn0) { o -= kc.rn0; cursor_rotate(kc); }
-    kc.a = kc.ra0 + (size_t)o * kc.step_a;
-    kc.b = kc.rb0 + (size_t)o * kc.step_b;
-    kc.rem = kc.rn0 - o;
+    const int n0 = g.seg[0].K / BK, n1 = g.seg[1].K / BK;
+    kc.a = (uint64_t)g.seg[0].A; kc.b = (uint64_t)g.seg[0].B; kc.rem = n0;
+    kc.da1 = (uint64_t)g.seg[1].A - (kc.a + (uint64_t)(n0 - 1) * kc.step_a);
+    kc.db1 = (uint64_t)g.seg[1].B - (kc.b + (uint64_t)(n0 - 1) * kc.step_b);
+    kc.rn1 = n1;
+    if (g.nseg > 2) {
+      kc.da2 = (uint64_t)g.seg[2].A - ((uint64_t)g.seg[1].A + (uint64_t)(n1 - 1) * kc.step_a);
+      kc.db2 = (uint64_t)g.seg[2].B - ((uint64_t)g.seg[1].B + (uint64_t)(n1 - 1) * kc.step_b);
+      kc.rn2 = g.seg[2].K / BK;
+    }
   }
   // Issue DMA instructions [d0, d1) of a k-tile into stage `st`; a tile's DMA_PER_TILE instructions
   // per wave are numbered A slots first, then B slots.
   // The DMA instructions take their base address from scalar registers.  Addresses that came out of a group
   // table are the same in every lane but live in vector registers: broadcast them from the first lane.
-  auto uniform = [](const char* q) {
+  auto uniform = [](const char* q) __attribute__((always_inline)) {
     const uint64_t v = (uint64_t)q;
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
     const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
     return (const char*)(((uint64_t)hi << 32) | lo);
   };
-  auto dma_part = [&](const char* abase, const char* bbase, int st, int d0, int d1) {
+  auto dma_part = [&](const char* abase, const char* bbase, int st, int d0, int d1) __attribute__((always_inline)) {
     if constexpr (GROUP) { abase = uniform(abase); bbase = uniform(bbase); }
     const uint32_t sa = lds0 + st * STAGE, sb = sa + A_BYTES;
 #pragma unroll
@@ -275,7 +286,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   bf16x8 fa[2][MI], fb[2][NI];
-  auto load_frags = [&](int st, int kk, int slot) {
+  auto load_frags = [&](int st, int kk, int slot) __attribute__((always_inline)) {
     const char* sa = smem + st * STAGE;
     const char* sb = sa + A_BYTES;
 #pragma unroll
@@ -287,59 +298,84 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
   // of a k-tile into stage dst, fetches its share of the next k-step's fragments (stage ld_st,
   // k-step ld_kk, into register set nxt) and runs the MFMAs of accumulator row i from register set
   // cur.  The DMA instructions are spread out because a wave that issues them back to back sits in
-  // the memory pipeline's issue queue instead of feeding the matrix unit.
+  // the memory pipeline's issue queue instead of feeding the matrix unit.  The fragment reads all go
+  // into the first MI - 1 chunks, in the order the next k-step consumes them (its first chunk needs
+  // A row 0 and every B column): the last chunk's MFMAs then cover their latency, so that neither the
+  // next k-step's first MFMA nor the wait before a barrier finds a read still in flight.
   auto kstep = [&](int cur, int ld_st, int ld_kk, int nxt, const char* abase, const char* bbase, int dst,
-                   int dbase, int dcount) {
+                   int dbase, int dcount, auto&& gap) __attribute__((always_inline)) {
     const char* sa = smem + ld_st * STAGE;
     const char* sb = sa + A_BYTES;
+    constexpr int NLD = MI + NI;              // fragment reads of one k-step
+    constexpr int LCH = MI > 1 ? MI - 1 : 1;  // chunks that carry them
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
       if (dcount > 0) dma_part(abase, bbase, dst, dbase + i * dcount / MI, dbase + (i + 1) * dcount / MI);
-      fa[nxt][i] = load_frag<BM, A_KC, BK>(sa, wm * TMW + i * 32, ld_kk, lane);
 #pragma unroll
-      for (int j = 0; j < NI; ++j)
-        if (j >= i * NI / MI && j < (i + 1) * NI / MI)
-          fb[nxt][j] = load_frag<BN, B_KC, BK>(sb, wn * TNW + j * 32, ld_kk, lane);
+      for (int q = 0; q < NLD; ++q) {  // read q: A row 0, B columns 0 .. NI-1, A rows 1 .. MI-1
+        if (q * LCH / NLD != i) continue;
+        if (q == 0) fa[nxt][0] = load_frag<BM, A_KC, BK>(sa, wm * TMW, ld_kk, lane);
+        else if (q <= NI) fb[nxt][q - 1] = load_frag<BN, B_KC, BK>(sb, wn * TNW + (q - 1) * 32, ld_kk, lane);
+        else fa[nxt][q - NI] = load_frag<BM, A_KC, BK>(sa, wm * TMW + (q - NI) * 32, ld_kk, lane);
+      }
 #pragma unroll
-      for (int j = 0; j < NI; ++j)
+      for (int j = 0; j < NI; ++j) {
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
+        if (j == 0) gap(i);  // scalar bookkeeping of the caller, in the shadow of the MFMA just issued
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
   };
+  auto no_gap = [](int) __attribute__((always_inline)) {};
   constexpr int H0 = NS == 2 ? DMA_PER_TILE : DMA_PER_TILE / 2;  // a tile's DMA is issued in two parts: [0, H0) and [H0, DMA_PER_TILE)
 
-  if (nk > 0) {
+  // The k loop, compiled twice: for one run of tiles (one segment) and for several.
+  auto k_loop = [&](auto multi_tag) __attribute__((always_inline)) {
+    constexpr bool MULTI = decltype(multi_tag)::value;
     // Prologue: fill stages 0 .. NS-2 and the first part of stage NS-1, wait for tile 0.
     const char *ab, *bb;
 #pragma unroll
     for (int s = 0; s + 1 < NS; ++s) {
-      cursor_next(kc, ab, bb);
+      cursor_next<MULTI>(kc, ab, bb);
       dma_part(ab, bb, s, 0, DMA_PER_TILE);
     }
-    cursor_next(kc, ab, bb);
+    cursor_next<MULTI>(kc, ab, bb);
     dma_part(ab, bb, NS - 1, 0, H0);
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((NS - 2) * DMA_PER_TILE + H0) : "memory");
     load_frags(0, 0, 0);
-    for (int base = 0; base < nk; base += NS) {
+    // One k-tile out of stage s.  k-step 0 also issues the second part of tile t+NS-1 (its stage was
+    // released at the previous barrier) and, in two of its gaps, works out the addresses of tile t+NS:
+    // whatever stands between the barrier and the next MFMA is a bubble in the matrix pipe.  k-steps
+    // 1 .. KSTEPS-2 issue nothing.  At the barrier tile t+1 has landed (this wave's part) and all of
+    // this wave's reads of stage s are done; after it that holds for every wave, so the last k-step
+    // refills stage s with the first part of tile t+NS.
+    auto ktile = [&](int s) __attribute__((always_inline)) {
+      const char *an = ab, *bn = bb;
+      kstep(0, s, 1, 1, ab, bb, (s + NS - 1) % NS, H0, DMA_PER_TILE - H0, [&](int i) __attribute__((always_inline)) {
+        if (i == 0) cursor_bases<MULTI>(kc, an, bn);
+        if (i == 1) cursor_counts<MULTI>(kc);
+      });
 #pragma unroll
-      for (int s = 0; s < NS; ++s) {
-        const int t = base + s;
-        if (t < nk) {
-          // k-step 0 also issues the second part of tile t+NS-1 (its stage was released at the
-          // previous barrier); k-steps 1 .. KSTEPS-2 issue none
-          kstep(0, s, 1, 1, ab, bb, (s + NS - 1) % NS, H0, DMA_PER_TILE - H0);
+      for (int kk = 1; kk + 1 < KSTEPS; ++kk) kstep(kk & 1, s, kk + 1, (kk + 1) & 1, ab, bb, 0, 0, 0, no_gap);
+      ab = an; bb = bn;  // tile t + NS
+      asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((NS - 2) * DMA_PER_TILE) : "memory");
+      kstep((KSTEPS - 1) & 1, (s + 1) % NS, 0, 0, ab, bb, s, 0, H0, no_gap);
+    };
+    // whole rounds of the stage ring run without a test per tile; the last, partial round tests
+    int t = 0;
+    for (; t + NS <= nk; t += NS) {
 #pragma unroll
-          for (int kk = 1; kk + 1 < KSTEPS; ++kk) kstep(kk & 1, s, kk + 1, (kk + 1) & 1, ab, bb, 0, 0, 0);
-          // tile t+1 has landed (this wave's part) and all of this wave's reads of stage s are done;
-          // after the barrier that holds for every wave, so stage s can be refilled.
-          asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((NS - 2) * DMA_PER_TILE) : "memory");
-          cursor_next(kc, ab, bb);  // tile t + NS
-          kstep((KSTEPS - 1) & 1, (s + 1) % NS, 0, 0, ab, bb, s, 0, H0);
-        }
-      }
+      for (int s = 0; s < NS; ++s) ktile(s);
     }
+#pragma unroll
+    for (int s = 0; s + 1 < NS; ++s)
+      if (t + s < nk) ktile(s);
     // drain DMA that was issued past the end before LDS is released
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  };
+  if (nk > 0) {
+    if (g.nseg == 1) k_loop(std::false_type{});
+    else k_loop(std::true_type{});
   }
 
   // ---- epilogue.  acc[i][j][r]: row = (r/4)*8 + (lane/32)*4 + r%4, col = lane%32 of the 32x32 tile.
