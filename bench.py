@@ -139,6 +139,8 @@ def main() -> int:
                     help="run the weight-gradient GEMMs of the backward on the library's second stream")
     ap.add_argument("--dropout", type=float, default=0.0,
                     help="dropout rate at every site of the workload (0 = the paper's pre-training recipe)")
+    ap.add_argument("--deterministic", action="store_true",
+                    help="weight and bias-table gradients summed in a fixed order (bit-reproducible backward)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run three 1 GiB device-to-device copies (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -165,6 +167,14 @@ def main() -> int:
         if ec is not None:
             ec = dataclasses.replace(ec, enc_block=drop(ec.enc_block), dec_block=drop(ec.dec_block))
         cfg = sc.block if sc is not None else (ec.dec_block if ec is not None else drop(cfg))
+    if args.deterministic:
+        import dataclasses
+        det = lambda c: dataclasses.replace(c, deterministic=True)
+        if sc is not None:
+            sc = dataclasses.replace(sc, block=det(sc.block))
+        if ec is not None:
+            ec = dataclasses.replace(ec, enc_block=det(ec.enc_block), dec_block=det(ec.dec_block))
+        cfg = sc.block if sc is not None else (ec.dec_block if ec is not None else det(cfg))
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     if args.calibrate_copy:
@@ -419,7 +429,7 @@ def main() -> int:
         "launch": ("hip graph replay" if args.graph else "eager") + (", weight gradients on a second stream" if args.overlap else ""),
         "config": {"workload": args.workload, "batch": cfg.batch, "seq_len": cfg.seq, "d_model": cfg.d_model,
                    "n_heads": cfg.n_heads, "d_kv": cfg.d_kv, "d_ff": cfg.d_ff, "causal": cfg.causal,
-                   "enc_seq_len": cfg.enc_seq, "dropout_rate": cfg.dropout_rate,
+                   "enc_seq_len": cfg.enc_seq, "dropout_rate": cfg.dropout_rate, "deterministic": bool(cfg.deterministic), "attn_scale": cfg.attn_scale,
                    "adafactor": cfg.adafactor, "passes": "fwd+bwd" + ("+adafactor" if cfg.adafactor or (args.optimizer and (sc is not None or ec is not None)) else ""),
                    **({"n_layers": sc.n_layers, "vocab": sc.vocab, "tied_logits": sc.tied_logits, "remat": sc.remat,
                        "z_loss": sc.z_loss} if sc is not None else {}),
@@ -432,9 +442,9 @@ def main() -> int:
     if not args.no_cpu_baseline:
         sb = args.cpu_sample_batch
         if sb <= 0:
-            # float64 numpy sustains very roughly 50 GFLOP/s on a handful of cores; aim near 15 s
+            # float64 numpy sustains very roughly 150 GFLOP/s on the box's 16 host cores; aim near 15 s
             per_seq = total_model_flops / cfg.batch
-            sb = int(max(1, min(cfg.batch, 15.0 * 50e9 / per_seq)))
+            sb = int(max(1, min(cfg.batch, 15.0 * 150e9 / per_seq)))
         out["cpu_baseline"] = (cpu_baseline_stack(sc, sb) if sc is not None else
                                cpu_baseline_encdec(ec, sb) if ec is not None else cpu_baseline(cfg, sb))
     print(json.dumps(out))

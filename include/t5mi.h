@@ -77,6 +77,12 @@ typedef struct {
   int32_t mlp_kind;     /* T5_MLP_*; 0 = the T5.1.1 gated tanh-GELU */
   float dropout_rate;   /* 0 = none (pre-training of T5.1.1); in (0, 1): training-time dropout, see t5_dropout_keep */
   uint32_t dropout_seed_lo, dropout_seed_hi; /* 64-bit seed; a caller changes it per step and per layer */
+  int32_t deterministic; /* 0: the partial sums of the weight gradients (reduction over all tokens, split across
+                            workgroups) and of the bias-table gradient meet in float32 atomics: results are
+                            reproducible to float32 rounding.  1: they are written out and added in a fixed order
+                            by a second pass: every output of the backward pass is bit-reproducible, for a larger
+                            workspace (the *_workspace_bytes() queries account for it) and a few percent of time.
+                            Applies to the matrix-unit kernels; y, dx (and denc) are bit-reproducible either way. */
 } t5_block_cfg;
 
 /* Weights, device pointers, element type cfg.dtype, row-major [in, out]. */

@@ -26,7 +26,8 @@ class _Cfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("batch", "seq", "d_model", "n_heads", "d_kv", "d_ff", "num_buckets",
                                          "max_distance", "causal", "dtype")] + \
                [("rms_eps", C.c_float), ("attn_scale", C.c_float), ("mlp_kind", C.c_int32),
-                ("dropout_rate", C.c_float), ("dropout_seed_lo", C.c_uint32), ("dropout_seed_hi", C.c_uint32)]
+                ("dropout_rate", C.c_float), ("dropout_seed_lo", C.c_uint32), ("dropout_seed_hi", C.c_uint32),
+                ("deterministic", C.c_int32)]
 
 
 class _Weights(C.Structure):
@@ -177,7 +178,8 @@ def _cfg_struct(cfg) -> _Cfg:
     return _Cfg(cfg.batch, cfg.seq, cfg.d_model, cfg.n_heads, cfg.d_kv, cfg.d_ff, cfg.num_buckets,
                 cfg.max_distance, int(bool(cfg.causal)), int(dt), float(cfg.rms_eps), float(cfg.attn_scale),
                 MLP_KINDS[getattr(cfg, "mlp", "geglu_tanh")], float(getattr(cfg, "dropout_rate", 0.0)),
-                int(getattr(cfg, "dropout_seed", 0)) & 0xFFFFFFFF, (int(getattr(cfg, "dropout_seed", 0)) >> 32) & 0xFFFFFFFF)
+                int(getattr(cfg, "dropout_seed", 0)) & 0xFFFFFFFF, (int(getattr(cfg, "dropout_seed", 0)) >> 32) & 0xFFFFFFFF,
+                int(bool(getattr(cfg, "deterministic", False))))
 
 
 def _torch_dtype(cfg):

@@ -175,6 +175,9 @@ __host__ __device__ inline int attn_dq_window_blocks(int S, int far) {
   const int nb = (far + 30) / 32, cap = S / 32 - 1;
   return nb < cap ? nb : cap;
 }
+// Floats per workgroup row of the reproducible bias-gradient buffer: a window is at most 2 S entries wide
+// (+ 4 for the upper lane half) and two sums of the saturated buckets follow it.
+__host__ __device__ inline int attn_ddiag_part_stride(int S) { return 2 * S + 8; }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // ------------------------------------------------------------------------------------------------
@@ -362,6 +365,7 @@ __global__ __launch_bounds__(256, DK == 64 && !DROP ? 3 : 2) void attn_bwd_dq_mf
                                                                const float* __restrict__ lse,
                                                                float* __restrict__ dvec,
                                                                float* __restrict__ ddiag,
+                                                               float* __restrict__ ddiag_part,
                                                                AttnDims a, int far) {
   constexpr int BR = 128, BC = 64, KS = DK / 16, CT = DK / 32;
   constexpr int TILE = BC * DK * 2, STG = 2 * TILE;  // a stage holds a K tile then a V tile
@@ -526,9 +530,12 @@ __global__ __launch_bounds__(256, DK == 64 && !DROP ? 3 : 2) void attn_bwd_dq_mf
       }
   }
   if constexpr (!BIAS) return;
-  // ---- flush: add the eight windows up (the upper lane half's diagonals sit 4 higher) and issue one
-  // global atomic per diagonal of this workgroup
+  // ---- flush: add the eight windows up (the upper lane half's diagonals sit 4 higher) and either issue one
+  // global atomic per diagonal of this workgroup or, for a reproducible result, write the summed window to
+  // this workgroup's row of ddiag_part (attn_ddiag_reduce_kernel adds the rows up in a fixed order)
   float* ddh = ddiag + (size_t)h * (2 * S - 1);
+  float* part = nullptr;
+  if (ddiag_part) part = ddiag_part + (((size_t)b * a.H + h) * (S / BR) + qt) * (size_t)attn_ddiag_part_stride(S);
   __syncthreads();
   for (int t = tid; t < W + 4; t += 256) {
     float v = 0.f;
@@ -541,13 +548,71 @@ __global__ __launch_bounds__(256, DK == 64 && !DROP ? 3 : 2) void attn_bwd_dq_mf
     // the waves' first queries are 32 apart -- but so are their windows' origins (m counts from the
     // wave's own queries), so the entry means the same diagonal for every wave
     const int idx = t - 32 * nb - 31 + (S - 1);
-    if (v != 0.f && idx >= 0 && idx < 2 * S - 1) unsafeAtomicAdd(&ddh[idx], v);
+    if (part) part[t] = v;
+    else if (v != 0.f && idx >= 0 && idx < 2 * S - 1) unsafeAtomicAdd(&ddh[idx], v);
   }
   far_neg = wave_sum(far_neg);
   far_pos = wave_sum(far_pos);
-  if (lane == 0) {
+  if (part) {
+    // per-wave sums, added by one lane in wave order
+    float* fs = ddg_all;  // the windows have been read
+    __syncthreads();
+    if (lane == 0) { fs[wave * 2] = far_neg; fs[wave * 2 + 1] = far_pos; }
+    __syncthreads();
+    if (tid == 0) {
+      part[W + 4] = (fs[0] + fs[2]) + (fs[4] + fs[6]);
+      part[W + 5] = (fs[1] + fs[3]) + (fs[5] + fs[7]);
+    }
+  } else if (lane == 0) {
     if (far_neg != 0.f) unsafeAtomicAdd(&ddh[0], far_neg);
     if (far_pos != 0.f) unsafeAtomicAdd(&ddh[2 * S - 2], far_pos);
+  }
+}
+
+// ddiag[h][..] += the window rows that the dq workgroups of head h wrote, always in the same order: a thread
+// owns one window entry (or one of the two saturated-bucket sums behind the window), four threads share the
+// rows (row r goes to thread group r % 4) and their sums are added in group order.  Where the window reaches an
+// end diagonal, the saturated-bucket sum of that end lands on the same address: the window entry's thread adds
+// both, so no two threads ever update one address.
+__global__ __launch_bounds__(256) void attn_ddiag_reduce_kernel(const float* __restrict__ part,
+                                                              float* __restrict__ ddiag, int B, int H, int S,
+                                                              int nb) {
+  __shared__ float red[2][4][64];
+  const int nch = gridDim.x / H;
+  const int h = blockIdx.x / nch, chunk = blockIdx.x % nch;
+  const int nt = S / 128, W = 32 * (2 * nb + 2), rows = B * nt;
+  const size_t stride = (size_t)attn_ddiag_part_stride(S);
+  const int tl = threadIdx.x & 63, grp = threadIdx.x >> 6;
+  const int t = chunk * 64 + tl;                      // entry: [0, W+4) window, W+4 / W+5 the two sums
+  const int last = 2 * S - 2;
+  int idx = -1;
+  if (t < W + 4) idx = t - 32 * nb - 31 + (S - 1);
+  else if (t == W + 4) idx = 0;
+  else if (t == W + 5) idx = last;
+  const bool valid = idx >= 0 && idx <= last;
+  // does a window entry own this end?  (entry t0 maps to diagonal 0, entry t1 to the last one)
+  const int t0 = 32 * nb + 31 - (S - 1), t1 = t0 + last;
+  const bool win0 = t0 >= 0 && t0 < W + 4, win1 = t1 >= 0 && t1 < W + 4;
+  int extra = -1;                                      // second column this thread adds
+  if (t < W + 4 && idx == 0) extra = W + 4;
+  if (t < W + 4 && idx == last) extra = W + 5;
+  const bool skip = (t == W + 4 && win0) || (t == W + 5 && win1);
+  float s = 0.f, s2 = 0.f;
+  if (valid && !skip) {
+    // rows of head h: (b, q) -> ((b*H + h)*nt + q)
+    for (int r = grp; r < rows; r += 4) {
+      const size_t base = (((size_t)(r / nt) * H + h) * nt + r % nt) * stride;
+      s += part[base + t];
+      if (extra >= 0) s2 += part[base + extra];
+    }
+  }
+  red[0][grp][tl] = s;
+  red[1][grp][tl] = s2;
+  __syncthreads();
+  if (grp == 0 && valid && !skip) {
+    const float tot = ((red[0][0][tl] + red[0][1][tl]) + (red[0][2][tl] + red[0][3][tl])) +
+                      ((red[1][0][tl] + red[1][1][tl]) + (red[1][2][tl] + red[1][3][tl]));
+    ddiag[(size_t)h * (2 * S - 1) + idx] += tot;
   }
 }
 
@@ -770,14 +835,22 @@ hipError_t fwd_launch(const AttnIO& io, const float* diag, void* c, float* lse, 
 
 template <int DK, bool CAUSAL, bool BIAS, bool DROP = false>
 hipError_t bwd_launch(const AttnIO& io, const void* c, const void* dc, const float* diag, const float* lse,
-                      float* dvec, float* ddiag, const AttnDims& a, int far, int phase, hipStream_t st) {
+                      float* dvec, float* ddiag, float* ddiag_part, const AttnDims& a, int far, int phase,
+                      hipStream_t st) {
   hipError_t e = hipSuccess;
   if (phase == 1) {
     auto kern = attn_bwd_dq_mfma_kernel<DK, CAUSAL, BIAS, DROP>;
     const size_t lds = attn_bwd_dq_lds_bytes(a, far);
     if ((e = set_lds(kern, lds)) != hipSuccess) return e;
-    kern<<<dim3((a.S / 128) * a.H * a.B), 256, lds, st>>>(io, (const bf16*)c, (const bf16*)dc, diag, lse, dvec, ddiag, a, far);
+    kern<<<dim3((a.S / 128) * a.H * a.B), 256, lds, st>>>(io, (const bf16*)c, (const bf16*)dc, diag, lse, dvec, ddiag,
+                                                          BIAS ? ddiag_part : nullptr, a, far);
     if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (BIAS && ddiag_part) {
+      const int nb = attn_dq_window_blocks(a.S, far);
+      attn_ddiag_reduce_kernel<<<a.H * ceil_div(32 * (2 * nb + 2) + 6, 64), 256, 0, st>>>(ddiag_part, ddiag, a.B, a.H,
+                                                                                         a.S, nb);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
   }
   if (phase == 2) {
     auto kern = attn_bwd_dkv_mfma_kernel<DK, CAUSAL, BIAS, DROP>;
@@ -831,9 +904,13 @@ hipError_t launch_attn_fwd_mfma(const AttnIO& io, const float* diag, void* c, fl
   return fwd_launch<128, false, false>(io, diag, c, lse, a, st);
 }
 
+size_t attn_ddiag_part_bytes(const AttnDims& a) {
+  return (size_t)a.B * a.H * (a.S / 128) * (size_t)attn_ddiag_part_stride(a.S) * sizeof(float);
+}
+
 hipError_t launch_attn_bwd_mfma(const AttnIO& io, const void* c, const void* dc, const float* diag,
                                 const float* lse, float* dvec, float* ddiag, const AttnDims& a, int far,
-                                int phase, hipStream_t st) {
+                                int phase, hipStream_t st, float* ddiag_part) {
   // phase 1: dq, dvec = rowsum(dO * O) and the bias-gradient diagonals (added into ddiag); phase 2: dk, dv
   // (reads the dvec phase 1 wrote).
   // `far`: smallest distance that falls in the last (saturated) bucket; such offsets need no
@@ -843,22 +920,22 @@ hipError_t launch_attn_bwd_mfma(const AttnIO& io, const void* c, const void* dc,
   const int mode = attn_mode(a);
   if (a.drop.on) {
     if (a.dk == 64) {
-      if (mode == 0) return bwd_launch<64, false, true, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
-      if (mode == 1) return bwd_launch<64, true, true, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
-      return bwd_launch<64, false, false, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
+      if (mode == 0) return bwd_launch<64, false, true, true>(io, c, dc, diag, lse, dvec, ddiag, ddiag_part, a, far, phase, st);
+      if (mode == 1) return bwd_launch<64, true, true, true>(io, c, dc, diag, lse, dvec, ddiag, ddiag_part, a, far, phase, st);
+      return bwd_launch<64, false, false, true>(io, c, dc, diag, lse, dvec, ddiag, ddiag_part, a, far, phase, st);
     }
-    if (mode == 0) return bwd_launch<128, false, true, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
-    if (mode == 1) return bwd_launch<128, true, true, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
-    return bwd_launch<128, false, false, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
+    if (mode == 0) return bwd_launch<128, false, true, true>(io, c, dc, diag, lse, dvec, ddiag, ddiag_part, a, far, phase, st);
+    if (mode == 1) return bwd_launch<128, true, true, true>(io, c, dc, diag, lse, dvec, ddiag, ddiag_part, a, far, phase, st);
+    return bwd_launch<128, false, false, true>(io, c, dc, diag, lse, dvec, ddiag, ddiag_part, a, far, phase, st);
   }
   if (a.dk == 64) {
-    if (mode == 0) return bwd_launch<64, false, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
-    if (mode == 1) return bwd_launch<64, true, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
-    return bwd_launch<64, false, false>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
+    if (mode == 0) return bwd_launch<64, false, true>(io, c, dc, diag, lse, dvec, ddiag, ddiag_part, a, far, phase, st);
+    if (mode == 1) return bwd_launch<64, true, true>(io, c, dc, diag, lse, dvec, ddiag, ddiag_part, a, far, phase, st);
+    return bwd_launch<64, false, false>(io, c, dc, diag, lse, dvec, ddiag, ddiag_part, a, far, phase, st);
   }
-  if (mode == 0) return bwd_launch<128, false, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
-  if (mode == 1) return bwd_launch<128, true, true>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
-  return bwd_launch<128, false, false>(io, c, dc, diag, lse, dvec, ddiag, a, far, phase, st);
+  if (mode == 0) return bwd_launch<128, false, true>(io, c, dc, diag, lse, dvec, ddiag, ddiag_part, a, far, phase, st);
+  if (mode == 1) return bwd_launch<128, true, true>(io, c, dc, diag, lse, dvec, ddiag, ddiag_part, a, far, phase, st);
+  return bwd_launch<128, false, false>(io, c, dc, diag, lse, dvec, ddiag, ddiag_part, a, far, phase, st);
 }
 
 }  // namespace t5mi

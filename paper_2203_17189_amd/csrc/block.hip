@@ -130,7 +130,7 @@ int t5_block_bwd(const t5_block_cfg* cfg, const void* dy, const void* x, const t
   const AttnDims ad = self_dims(cfg, D);
   const int far = lut.n_thr > 0 ? lut.thr[lut.n_thr - 1] : lut.max_exact;
   const bool attn_mfma = D.ty == IN_BF16 && attn_mfma_supported(ad) && attn_bwd_mfma_fits(ad, far);
-  W.fork = fork_begin(st, D.drop == 0.f);
+  W.fork = fork_begin(st, D.drop == 0.f && !D.det);
   ForkGuard guard(W.fork);
   T5_SUB(bwd_zero(D, dw, nullptr, attn_mfma ? W.ddiag : nullptr, acc != 0, st));
   T5_SUB(bwd_mlp(D, dy, S.h, w, S, W, dw, acc, st));
@@ -188,7 +188,7 @@ int t5_decoder_block_bwd(const t5_block_cfg* cfg, int32_t enc_seq, const void* d
   const AttnDims ad = self_dims(cfg, D);
   const int far = lut.n_thr > 0 ? lut.thr[lut.n_thr - 1] : lut.max_exact;
   const bool attn_mfma = D.ty == IN_BF16 && attn_mfma_supported(ad) && attn_bwd_mfma_fits(ad, far);
-  W.fork = fork_begin(st, D.drop == 0.f);
+  W.fork = fork_begin(st, D.drop == 0.f && !D.det);
   ForkGuard guard(W.fork);
   T5_SUB(bwd_zero(D, dw, dxw, attn_mfma ? W.ddiag : nullptr, acc != 0, st));
   T5_SUB(bwd_mlp(D, dy, S.h2, w, S, W, dw, acc, st));

@@ -37,6 +37,7 @@ struct Dims {
   int64_t Te; // B * Sk
   float drop;     // dropout rate; 0: none
   uint64_t seed;  // dropout seed
+  int det;        // 1: weight and bias-table gradients are summed in a fixed order
 };
 // Generator parameters of one of the block's dropout sites (off when the rate is 0).
 inline DropSite drop_site(const Dims& D, int site) { return make_drop_site(D.seed, site, D.drop); }
@@ -50,6 +51,7 @@ int validate_cfg(const t5_block_cfg* c, Dims* o, RelposLut* lut, int enc_seq = 0
     return T5_ERR_UNSUPPORTED;
   if (!(c->rms_eps >= 0.f) || !std::isfinite(c->attn_scale)) return T5_ERR_SHAPE;
   if (!(c->dropout_rate >= 0.f && c->dropout_rate < 1.f)) return T5_ERR_SHAPE;
+  if (c->deterministic != 0 && c->deterministic != 1) return T5_ERR_SHAPE;
   const int64_t T = (int64_t)c->batch * c->seq;
   const int64_t Te = (int64_t)c->batch * enc_seq;
   const int64_t I = (int64_t)c->n_heads * c->d_kv;
@@ -70,6 +72,7 @@ int validate_cfg(const t5_block_cfg* c, Dims* o, RelposLut* lut, int enc_seq = 0
     o->mlp = c->mlp_kind;
     o->drop = c->dropout_rate;
     o->seed = ((uint64_t)c->dropout_seed_hi << 32) | c->dropout_seed_lo;
+    o->det = c->deterministic;
     static_assert(T5_MLP_GEGLU_TANH == ACT_GELU_TANH && T5_MLP_RELU == ACT_RELU && T5_MLP_GEGLU_ERF == ACT_GELU_ERF,
                   "the config values are the kernels' activation codes");
   }
@@ -204,7 +207,12 @@ struct BwdWs {
   // [T, d] each (dropout only): a sublayer's output gradient times its dropout multiplier, one buffer per
   // sublayer (feed-forward, self-attention, cross-attention) so that all three outlive the layer's pass
   void *dmask, *dmask_a, *dmask_x;
+  // reproducible mode (D.det): room for the k-slices' partial sums of the largest weight-gradient GEMM of the
+  // layer (the GEMMs run one after the other and share it), and for the bias-gradient windows of the
+  // attention backward's workgroups
+  float *wg_partials, *ddiag_part;
 };
+size_t wgrad_partials_bytes(const Dims& D);  // defined below, after the GEMM descriptor helpers
 size_t carve_bwd(const Dims& D, void* base, BwdWs* w) {
   Carver cv(base);
   BwdWs t = {};
@@ -225,6 +233,13 @@ size_t carve_bwd(const Dims& D, void* base, BwdWs* w) {
     t.dqx = cv.take((size_t)D.T * D.I * D.es);
     t.dkvx = cv.take((size_t)D.Te * 2 * D.I * D.es);
     t.dmask_x = cv.take(D.drop > 0.f ? (size_t)D.T * D.d * D.es : 0);
+  }
+  if (D.det && D.ty == IN_BF16) {
+    t.wg_partials = cv.take<float>(wgrad_partials_bytes(D));
+    AttnDims ad;
+    std::memset(&ad, 0, sizeof(ad));
+    ad.B = D.B; ad.S = D.S; ad.H = D.H;
+    t.ddiag_part = cv.take<float>(D.S % 128 == 0 ? attn_ddiag_part_bytes(ad) : 0);
   }
   if (w) *w = t;
   return cv.off;
@@ -247,6 +262,27 @@ GemmEpi epi(int kind, void* out0, int ld0, int out_type) {
   std::memset(&e, 0, sizeof(e));
   e.kind = kind; e.out0 = out0; e.ld0 = ld0; e.out_type = out_type; e.split_n = 1 << 30;
   return e;
+}
+
+// Room for the partial sums of the layer's largest split weight-gradient GEMM (reproducible mode).
+size_t wgrad_partials_bytes(const Dims& D) {
+  alignas(16) static const long long dummy[4] = {0, 0, 0, 0};
+  const int T = (int)D.T, Te = (int)D.Te;
+  size_t need = 0;
+  auto probe = [&](int M, int N, int K) {
+    GemmDesc g = gemm1(M, N, K, dummy, M, 0, dummy, N, 0, IN_BF16);
+    const size_t b = gemm_split_partials_bytes(g, epi(EPI_SPLIT_F32, (void*)dummy, N, IN_F32));
+    need = b > need ? b : need;
+  };
+  probe(D.F, D.d, T);                                   // dWo_ff
+  probe(D.d, D.mlp == ACT_RELU ? D.F : 2 * D.F, T);     // dWi0 | dWi1
+  probe(D.I, D.d, T);                                   // dWo (and dXo)
+  probe(D.d, 3 * D.I, T);                               // dWq | dWk | dWv
+  if (D.Sk > 0) {
+    probe(D.d, D.I, T);                                 // dXq
+    probe(D.d, 2 * D.I, Te);                            // dXk | dXv
+  }
+  return need;
 }
 
 hipError_t run_gemm(const GemmDesc& g, const GemmEpi& e, hipStream_t st) {
@@ -491,7 +527,7 @@ int bwd_mlp(const Dims& D, const void* dy, const float* hin, const t5_block_weig
     hipStream_t st = wgrad_stream(W.fork);
     GemmDesc g = gemm1(D.F, D.d, T, S.a, D.F, 0, dy, D.d, 0, ty);
     GemmEpi e = epi(EPI_SPLIT_F32, dw->wo_ff, D.d, IN_F32);
-    e.accumulate = 1;
+    e.accumulate = 1; e.aux0 = W.wg_partials;
     T5_STEP("gemm_dwo_ff", run_gemm(g, e, st));
   }
   if (D.mlp == ACT_RELU) {
@@ -506,7 +542,7 @@ int bwd_mlp(const Dims& D, const void* dy, const float* hin, const t5_block_weig
       hipStream_t st = wgrad_stream(W.fork);
       GemmDesc g = gemm1(D.d, D.F, T, S.n2, D.d, 0, du_p, D.F, 0, ty);
       GemmEpi e = epi(EPI_SPLIT_F32, dw->wi0, D.F, IN_F32);
-      e.accumulate = 1;
+      e.accumulate = 1; e.aux0 = W.wg_partials;
       T5_STEP("gemm_dwi", run_gemm(g, e, st));
     }
     {  // dn2 = du Wi0^T
@@ -525,7 +561,7 @@ int bwd_mlp(const Dims& D, const void* dy, const float* hin, const t5_block_weig
       hipStream_t st = wgrad_stream(W.fork);
       GemmDesc g = gemm1(D.d, 2 * D.F, T, S.n2, D.d, 0, du_p, 2 * D.F, 0, ty);
       GemmEpi e = epi(EPI_SPLIT_F32, dw->wi0, D.F, IN_F32);
-      e.out1 = dw->wi1; e.split_n = D.F; e.accumulate = 1;
+      e.out1 = dw->wi1; e.split_n = D.F; e.accumulate = 1; e.aux0 = W.wg_partials;
       T5_STEP("gemm_dwi", run_gemm(g, e, st));
     }
     {  // dn2 = du Wi0^T + dw Wi1^T
@@ -560,7 +596,7 @@ int bwd_cross_attn(const t5_block_cfg* cfg, const Dims& D, const void* enc, cons
     hipStream_t st = wgrad_stream(W.fork);
     GemmDesc g = gemm1(D.I, D.d, T, S.cx, D.I, 0, dh_op, D.d, 0, ty);
     GemmEpi e = epi(EPI_SPLIT_F32, dxw->xo, D.d, IN_F32);
-    e.accumulate = 1;
+    e.accumulate = 1; e.aux0 = W.wg_partials;
     T5_STEP("gemm_dxo", run_gemm(g, e, st));
   }
   {  // dcx = dh2 Xo^T
@@ -579,14 +615,14 @@ int bwd_cross_attn(const t5_block_cfg* cfg, const Dims& D, const void* enc, cons
     hipStream_t st = wgrad_stream(W.fork);
     GemmDesc g = gemm1(D.d, D.I, T, S.nx, D.d, 0, W.dqx, D.I, 0, ty);
     GemmEpi e = epi(EPI_SPLIT_F32, dxw->xq, D.I, IN_F32);
-    e.accumulate = 1;
+    e.accumulate = 1; e.aux0 = W.wg_partials;
     T5_STEP("gemm_dxq", run_gemm(g, e, st));
   }
   if (!W.defer_wgrad) {  // dXk | dXv = enc^T [dk | dv]   (ordered after dXq on the side stream: no new fork point needed)
     hipStream_t st = wgrad_stream(W.fork);
     GemmDesc g = gemm1(D.d, 2 * D.I, Te, enc, D.d, 0, W.dkvx, 2 * D.I, 0, ty);
     GemmEpi e = epi(EPI_SPLIT_F32, dxw->xk, D.I, IN_F32);
-    e.out1 = dxw->xv; e.split_n = D.I; e.accumulate = 1;
+    e.out1 = dxw->xv; e.split_n = D.I; e.accumulate = 1; e.aux0 = W.wg_partials;
     T5_STEP("gemm_dxkv", run_gemm(g, e, st));
   }
   {  // denc = dk Xk^T + dv Xv^T
@@ -626,7 +662,7 @@ int bwd_self_attn(const t5_block_cfg* cfg, const Dims& D, const RelposLut& lut, 
     hipStream_t st = wgrad_stream(W.fork);
     GemmDesc g = gemm1(D.I, D.d, T, S.c, D.I, 0, dh_op, D.d, 0, ty);
     GemmEpi e = epi(EPI_SPLIT_F32, dw->wo, D.d, IN_F32);
-    e.accumulate = 1;
+    e.accumulate = 1; e.aux0 = W.wg_partials;
     T5_STEP("gemm_dwo", run_gemm(g, e, st));
   }
   {  // dc = dh Wo^T
@@ -635,7 +671,8 @@ int bwd_self_attn(const t5_block_cfg* cfg, const Dims& D, const RelposLut& lut, 
   }
   const AttnIO io = attn_io_packed(S.qkv, W.dqkv, D.I, es);
   if (attn_mfma) {
-    T5_STEP("attn_bwd_dq", launch_attn_bwd_mfma(io, S.c, W.dc, S.diag, S.lse, W.dvec, W.ddiag, ad, far, 1, st));
+    T5_STEP("attn_bwd_dq", launch_attn_bwd_mfma(io, S.c, W.dc, S.diag, S.lse, W.dvec, W.ddiag, ad, far, 1, st,
+                                                W.ddiag_part));
     T5_STEP("attn_bwd_dkv", launch_attn_bwd_mfma(io, S.c, W.dc, S.diag, S.lse, W.dvec, W.ddiag, ad, far, 2, st));
   } else {
     T5_STEP("attn_bwd", launch_attn_bwd_simple(io, S.c, W.dc, ty, S.diag, S.lse, W.dvec, W.ddiag, ad,
@@ -649,7 +686,7 @@ int bwd_self_attn(const t5_block_cfg* cfg, const Dims& D, const RelposLut& lut, 
     hipStream_t st = wgrad_stream(W.fork);
     GemmDesc g = gemm1(D.d, 3 * D.I, T, S.n1, D.d, 0, W.dqkv, 3 * D.I, 0, ty);
     GemmEpi e = epi(EPI_SPLIT_F32, dw->wq, D.I, IN_F32);
-    e.out1 = dw->wk; e.out2 = dw->wv; e.split_n = D.I; e.accumulate = 1;
+    e.out1 = dw->wk; e.out2 = dw->wv; e.split_n = D.I; e.accumulate = 1; e.aux0 = W.wg_partials;
     T5_STEP("gemm_dwqkv", run_gemm(g, e, st));
   }
   {  // dn1 = dq Wq^T + dk Wk^T + dv Wv^T

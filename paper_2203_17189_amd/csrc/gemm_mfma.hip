@@ -267,7 +267,10 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
     return (const char*)(((uint64_t)hi << 32) | lo);
   };
   auto dma_part = [&](const char* abase, const char* bbase, int st, int d0, int d1) __attribute__((always_inline)) {
-    if constexpr (GROUP) { abase = uniform(abase); bbase = uniform(bbase); }
+    // (also without a group table: where the compiler keeps a cursor value in vector registers across a
+    // barrier this moves it back; on a value that is already scalar it folds away)
+    abase = uniform(abase);
+    bbase = uniform(bbase);
     const uint32_t sa = lds0 + st * STAGE, sb = sa + A_BYTES;
 #pragma unroll
     for (int d = 0; d < DMA_PER_TILE; ++d) {
@@ -378,6 +381,19 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
     else k_loop(std::true_type{});
   }
 
+  // Output placement of the epilogue, in locals: the reproducible split reduction redirects it.  There this
+  // k-slice stores its partial sums, as a plain M x N float32 matrix of its own, instead of adding them into the
+  // output; splitk_reduce_kernel adds the slices up afterwards.
+  int ep_ld0 = e.ld0, ep_split_n = e.split_n, ep_acc = e.accumulate, ep_sk = split_k;
+  if constexpr (EPI == EPI_SPLIT_F32 && !GROUP) {
+    if (e.aux0 != nullptr && split_k > 1) {
+      so0 = (float*)const_cast<void*>(e.aux0) + (size_t)ks * (size_t)g.M * (size_t)g.N;
+      ep_ld0 = g.N;
+      ep_split_n = 1 << 30;
+      ep_acc = 0;
+      ep_sk = 1;
+    }
+  }
   // ---- epilogue.  acc[i][j][r]: row = (r/4)*8 + (lane/32)*4 + r%4, col = lane%32 of the 32x32 tile.
   // Interior wave tiles (the common case) are transposed through LDS, 64 rows at a time, so that
   // each lane ends up with 4 consecutive columns of one row: auxiliary loads and the stores are
@@ -387,21 +403,21 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
   {
     constexpr int EP_LD = TNW + 8;  // floats per staged row
     const int mw = m0 + wm * TMW, nw = n0 + wn * TNW;
-    bool interior = (mw + TMW <= g.M) && (nw + TNW <= g.N) && (e.ld0 % 8 == 0) && (e.ld_aux % 8 == 0);
+    bool interior = (mw + TMW <= g.M) && (nw + TNW <= g.N) && (ep_ld0 % 8 == 0) && (e.ld_aux % 8 == 0);
     if constexpr (EPI == EPI_SPLIT_F32)
-      interior = interior && (nw / e.split_n == (nw + TNW - 1) / e.split_n) && (e.split_n % 4 == 0);
+      interior = interior && (nw / ep_split_n == (nw + TNW - 1) / ep_split_n) && (ep_split_n % 4 == 0);
     if constexpr (EPI == EPI_SPLIT_F32) {
       // split-k partial sums go out as float atomics straight from the accumulator registers
       // (32 consecutive floats per half-wave and row)
-      if (interior && split_k > 1) {
+      if (interior && ep_sk > 1) {
         const int cl = lane & 31, rl = (lane >> 5) << 2;
-        const int which = nw / e.split_n;
-        float* dst0 = (float*)(which == 0 ? so0 : which == 1 ? so1 : so2) + (nw - which * e.split_n) + cl;
+        const int which = nw / ep_split_n;
+        float* dst0 = (float*)(which == 0 ? so0 : which == 1 ? so1 : so2) + (nw - which * ep_split_n) + cl;
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            float* rowp = dst0 + (size_t)(mw + i * 32 + ((r >> 2) << 3) + rl + (r & 3)) * e.ld0;
+            float* rowp = dst0 + (size_t)(mw + i * 32 + ((r >> 2) << 3) + rl + (r & 3)) * ep_ld0;
 #pragma unroll
             for (int j = 0; j < NI; ++j) unsafeAtomicAdd(rowp + j * 32, acc[i][j][r]);
           }
@@ -452,7 +468,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
               glb[q] = (bf16)(gl * mk[q]);
               ab[q] = (bf16)(gl * ww[q] * mk[q]);
             }
-            const size_t o = (size_t)(mh + rloc) * e.ld0 + f;
+            const size_t o = (size_t)(mh + rloc) * ep_ld0 + f;
             st_stream(reinterpret_cast<bf16x4*>((bf16*)e.out0 + o), gpb);
             st_stream(reinterpret_cast<bf16x4*>((bf16*)e.out1 + o), glb);
             st_stream(reinterpret_cast<bf16x4*>((bf16*)e.out2 + o), ab);
@@ -469,14 +485,14 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
         static_assert(NIT % BT == 0, "batching");
         const int c4 = (lane % LPR) * 4;
         // element offset of this lane in instruction `it` of half `half`: o0 + (half*64 + it*RPI) * ld0
-        const size_t o0 = (size_t)(mw + lane / LPR) * e.ld0 + nw + c4;
-        const int ld_aux = e.ld_aux ? e.ld_aux : e.ld0;
+        const size_t o0 = (size_t)(mw + lane / LPR) * ep_ld0 + nw + c4;
+        const int ld_aux = e.ld_aux ? e.ld_aux : ep_ld0;
         const size_t a0 = (size_t)(mw + lane / LPR) * ld_aux + nw + c4;  // same, in the auxiliary operands
         float* split_dst = nullptr;
         if constexpr (EPI == EPI_SPLIT_F32) {
-          const int which = nw / e.split_n;
-          split_dst = (float*)(which == 0 ? so0 : which == 1 ? so1 : so2) + (nw - which * e.split_n) + c4 +
-                      (size_t)(mw + lane / LPR) * e.ld0;
+          const int which = nw / ep_split_n;
+          split_dst = (float*)(which == 0 ? so0 : which == 1 ? so1 : so2) + (nw - which * ep_split_n) + c4 +
+                      (size_t)(mw + lane / LPR) * ep_ld0;
         }
         // The auxiliary operands (residual; saved gated-GELU factors) come from HBM with a latency of a
         // microsecond or more.  They are fetched in batches of BT instructions, one batch ahead of the
@@ -517,14 +533,14 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
               const int it = b * BT + q;
               const int rloc = it * RPI + lane / LPR;
               f32x4 v = *reinterpret_cast<const f32x4*>(stg + rloc * EP_LD + c4);
-              const size_t o = o0 + (size_t)(half * 64 + it * RPI) * e.ld0;
+              const size_t o = o0 + (size_t)(half * 64 + it * RPI) * ep_ld0;
               if constexpr (EPI == EPI_SPLIT_F32) {
-                float* d = split_dst + (size_t)(half * 64 + it * RPI) * e.ld0;
-                if (split_k > 1) {
+                float* d = split_dst + (size_t)(half * 64 + it * RPI) * ep_ld0;
+                if (ep_sk > 1) {
 #pragma unroll
                   for (int qq = 0; qq < 4; ++qq) unsafeAtomicAdd(d + qq, v[qq]);
                 } else {
-                  if (e.accumulate) {
+                  if (ep_acc) {
                     const f32x4 old = *reinterpret_cast<const f32x4*>(d);
 #pragma unroll
                     for (int qq = 0; qq < 4; ++qq) v[qq] += old[qq];
@@ -608,7 +624,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
           const float uu = acc[i][j][r], ww = acc[i][j + 1][r];
           float gl, dgl;
           gelu_both(e.act, uu, gl, dgl);
-          const size_t o = (size_t)m * e.ld0 + f;
+          const size_t o = (size_t)m * ep_ld0 + f;
           const float mk = DROP ? drop_mult(e.drop, drop_row_key(e.drop, (uint32_t)m), (uint32_t)f) : 1.f;
           ((bf16*)e.out0)[o] = (bf16)(ww * dgl * mk);
           ((bf16*)e.out1)[o] = (bf16)(gl * mk);
@@ -620,7 +636,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
           const int n = n0 + wn * TNW + j * 32 + col_l;
           if (n >= g.N) continue;
           float v = acc[i][j][r];
-          const size_t o = (size_t)m * e.ld0 + n;
+          const size_t o = (size_t)m * ep_ld0 + n;
           float mk = 1.f;
           if constexpr (EPI == EPI_STORE || EPI == EPI_RESID)
             if constexpr (DROP) mk = drop_mult(e.drop, drop_row_key(e.drop, (uint32_t)m), (uint32_t)n);
@@ -629,20 +645,20 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
             v *= mk;
             if (e.out_type == IN_BF16) ((bf16*)e.out0)[o] = (bf16)v; else ((float*)e.out0)[o] = v;
           } else if constexpr (EPI == EPI_RESID) {
-            const size_t oa = (size_t)m * (e.ld_aux ? e.ld_aux : e.ld0) + n;
+            const size_t oa = (size_t)m * (e.ld_aux ? e.ld_aux : ep_ld0) + n;
             const float a = e.aux_type == IN_BF16 ? (float)((const bf16*)e.aux0)[oa] : ((const float*)e.aux0)[oa];
             const float r = e.aux_mask ? (a > 0.f ? v * (DROP ? e.drop.scale : 1.f) : 0.f) : fmaf(v, mk, a);
             if (e.out_type == IN_BF16) ((bf16*)e.out0)[o] = (bf16)r; else ((float*)e.out0)[o] = r;
           } else if constexpr (EPI == EPI_GEGLU_BWD) {
-            const size_t oa = (size_t)m * (e.ld_aux ? e.ld_aux : e.ld0) + n;
+            const size_t oa = (size_t)m * (e.ld_aux ? e.ld_aux : ep_ld0) + n;
             const float gp = (float)((const bf16*)e.aux0)[oa], gl = (float)((const bf16*)e.aux1)[oa];
             ((bf16*)e.out0)[o] = (bf16)(v * gp);
             ((bf16*)e.out1)[o] = (bf16)(v * gl);
           } else {  // EPI_SPLIT_F32
-            const int which = n / e.split_n, nn = n - which * e.split_n;
-            float* dst = (float*)(which == 0 ? so0 : which == 1 ? so1 : so2) + (size_t)m * e.ld0 + nn;
-            if (split_k > 1) unsafeAtomicAdd(dst, v);
-            else *dst = e.accumulate ? *dst + v : v;
+            const int which = n / ep_split_n, nn = n - which * ep_split_n;
+            float* dst = (float*)(which == 0 ? so0 : which == 1 ? so1 : so2) + (size_t)m * ep_ld0 + nn;
+            if (ep_sk > 1) unsafeAtomicAdd(dst, v);
+            else *dst = ep_acc ? *dst + v : v;
           }
         }
       }
@@ -662,6 +678,61 @@ __global__ void zero_split_kernel(GemmEpi e, int M, int N) {
   const int which = n / e.split_n, nn = n - which * e.split_n;
   float* dst = (float*)(which == 0 ? e.out0 : which == 1 ? e.out1 : e.out2);
   dst[(size_t)m * e.ld0 + nn] = 0.f;
+}
+
+// out[m][n] (+)= partials[0][m][n] + partials[1][m][n] + ... in that order; out as in EPI_SPLIT_F32.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmEpi e, int M, int N, int slices) {
+  const int64_t idx = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;  // N % 4 == 0 (checked by the launcher)
+  if (idx >= (int64_t)M * N) return;
+  const size_t mn = (size_t)M * N;
+  const float* partials = (const float*)e.aux0;
+  f32x4 acc = *reinterpret_cast<const f32x4*>(partials + idx);
+  for (int s = 1; s < slices; ++s) {
+    const f32x4 v = *reinterpret_cast<const f32x4*>(partials + (size_t)s * mn + idx);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[q] += v[q];
+  }
+  const int m = (int)(idx / N), n = (int)(idx % N);
+  const int which = n / e.split_n, nn = n - which * e.split_n;  // split_n % 4 == 0: the four columns share an output
+  float* dst = (float*)(which == 0 ? e.out0 : which == 1 ? e.out1 : e.out2) + (size_t)m * e.ld0 + nn;
+  if (e.accumulate) {
+    const f32x4 old = *reinterpret_cast<const f32x4*>(dst);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[q] += old[q];
+  }
+  *reinterpret_cast<f32x4*>(dst) = acc;
+}
+
+// Tile size and k split of a weight-gradient GEMM (EPI_SPLIT_F32): few output tiles, very long k.
+// Small outputs take 128x128 tiles (fewer k-slices, hence fewer partial sums per output element); k is split
+// so that the workgroups fill whole rounds of the 256 compute units.
+void wgrad_plan(const GemmDesc& g, const GemmEpi& e, int ngr, bool& big, int& split_k) {
+  int nk = 0;
+  for (int s = 0; s < g.nseg; ++s) nk += g.seg[s].K / KQ;
+  const int64_t t256 = (int64_t)ceil_div(g.M, 256) * ceil_div(g.N, 256) * ngr;
+  const int64_t t128 = (int64_t)ceil_div(g.M, 128) * ceil_div(g.N, 128) * ngr;
+  // 256x256 tiles from 48 output tiles on, and from 24 when the reduction is long (measured at d_model 768:
+  // dWi 3x16 tiles -18 % at 65536 and -10 % at 16384 tokens; dWo_ff 8x3 and dWqkv 3x9 tiles -14 % at 65536
+  // tokens but +10..18 % at 16384, where a workgroup's share of k no longer pays for the larger epilogue)
+  big = t256 >= 48 || (t256 >= 24 && nk * KQ >= 49152);
+  // grouped small outputs (12 x 768 x 768: 432 tiles of 128x128): one round of small tiles over the whole
+  // reduction, no split and no atomics, beats 256x256 tiles split seven ways (0.20 -> 0.17 ms at 4096 tokens)
+  if (ngr > 1 && t128 <= 512) big = false;
+  const int64_t tiles = big ? t256 : t128;
+  const int per_cu = big ? 1 : 2;  // concurrent workgroups per compute unit (LDS-limited)
+  double best = -1.0;
+  split_k = 1;
+  for (int sp = 1; sp <= 32; ++sp) {
+    if (sp > 1 && nk / sp < 8) break;
+    const int64_t wgs = tiles * sp, slots = 256 * per_cu;
+    const double eff = (double)wgs / (double)(((wgs + slots - 1) / slots) * slots) - 0.012 * sp;
+    if (eff > best) { best = eff; split_k = sp; }
+  }
+  (void)e;
+}
+// whether the reproducible two-pass reduction applies to this problem
+bool split_partials_ok(const GemmDesc& g, const GemmEpi& e) {
+  return e.aux0 != nullptr && g.ngroups <= 1 && g.N % 4 == 0 && e.split_n % 4 == 0 && e.ld0 % 4 == 0;
 }
 
 template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int EPI, int NS = 4, int MINW = 1, int BK = 32>
@@ -694,33 +765,31 @@ hipError_t launch_layout(const GemmDesc& g, const GemmEpi& e, hipStream_t st) {
   const int64_t t128 = (int64_t)ceil_div(g.M, 128) * ceil_div(g.N, 128) * ngr;
   bool big = t256 >= 192;
   int split_k = 1;
+  bool two_pass = false;  // reproducible split reduction through the partial-sum buffer in GemmEpi::aux0
   if constexpr (EPI == EPI_SPLIT_F32) {
-    // Weight-gradient GEMMs: few output tiles, very long k.  Small outputs take 128x128 tiles (fewer
-    // k-slices, hence fewer float atomics per output element); k is split so that the workgroups
-    // fill whole rounds of the 256 compute units.  Partial sums meet in float32 atomics on a zeroed
-    // output.
-    // 256x256 tiles from 48 output tiles on, and from 24 when the reduction is long (measured at d_model 768:
-    // dWi 3x16 tiles -18 % at 65536 and -10 % at 16384 tokens; dWo_ff 8x3 and dWqkv 3x9 tiles -14 % at 65536
-    // tokens but +10..18 % at 16384, where a workgroup's share of k no longer pays for the larger epilogue)
-    big = t256 >= 48 || (t256 >= 24 && nk * KQ >= 49152);
-    // grouped small outputs (12 x 768 x 768: 432 tiles of 128x128): one round of small tiles over the whole
-    // reduction, no split and no atomics, beats 256x256 tiles split seven ways (0.20 -> 0.17 ms at 4096 tokens)
-    if (ngr > 1 && t128 <= 512) big = false;
-    const int64_t tiles = big ? t256 : t128;
-    const int per_cu = big ? 1 : 2;  // concurrent workgroups per compute unit (LDS-limited)
-    double best = -1.0;
-    for (int sp = 1; sp <= 32; ++sp) {
-      if (sp > 1 && nk / sp < 8) break;
-      const int64_t wgs = tiles * sp, slots = 256 * per_cu;
-      const double eff = (double)wgs / (double)(((wgs + slots - 1) / slots) * slots) - 0.012 * sp;
-      if (eff > best) { best = eff; split_k = sp; }
-    }
+    // Partial sums of the k-slices meet in float32 atomics on a zeroed output, or, when the caller provides
+    // room for them, in a second pass that adds them up in a fixed order.
+    wgrad_plan(g, e, ngr, big, split_k);
     if (ngr > 1 && !e.accumulate) return hipErrorInvalidValue;  // grouped outputs are cleared by the caller
-    if (split_k > 1 && !e.accumulate) {
+    two_pass = split_k > 1 && split_partials_ok(g, e);
+    if (split_k > 1 && !e.accumulate && !two_pass) {
       zero_split_kernel<<<ceil_div((int64_t)g.M * g.N, 256), 256, 0, st>>>(e, g.M, g.N);
       hipError_t err = hipGetLastError();
       if (err != hipSuccess) return err;
     }
+  }
+  GemmEpi ee = e;
+  if constexpr (EPI == EPI_SPLIT_F32) {
+    if (!two_pass) ee.aux0 = nullptr;
+  }
+  auto finish = [&](hipError_t err) {
+    if (err != hipSuccess || !two_pass) return err;
+    splitk_reduce_kernel<<<ceil_div((int64_t)g.M * g.N / 4, 256), 256, 0, st>>>(ee, g.M, g.N, split_k);
+    return hipGetLastError();
+  };
+  if constexpr (EPI == EPI_SPLIT_F32) {
+    if (big) return finish(launch_cfg<256, 256, 2, 2, A_KC, B_KC, EPI_T, 5, 1>(g, ee, split_k, st));
+    return finish(launch_cfg<128, 128, 2, 2, A_KC, B_KC, EPI_T, 4, 1>(g, ee, split_k, st));
   }
   if (big) {
     // short k loops: two 256x128 workgroups per compute unit hide each other's prologue/epilogue
@@ -776,6 +845,14 @@ bool gemm_mfma_supported(const GemmDesc& g, const GemmEpi& e) {
     default:
       return false;
   }
+}
+
+size_t gemm_split_partials_bytes(const GemmDesc& g, const GemmEpi& e) {
+  if (e.kind != EPI_SPLIT_F32 || g.ngroups > 1) return 0;
+  bool big;
+  int split_k;
+  wgrad_plan(g, e, 1, big, split_k);
+  return split_k > 1 ? (size_t)split_k * (size_t)g.M * (size_t)g.N * sizeof(float) : 0;
 }
 
 hipError_t launch_fill_ptrs(const void* const* ptrs, int n, const void** dst, hipStream_t st) {

@@ -53,6 +53,10 @@ struct GemmEpi {
   void* out0;
   void* out1;
   void* out2;
+  // EPI_SPLIT_F32 with a split reduction (MFMA kernel only) reads no auxiliary operand and uses aux0 for
+  // something else: when it is set, the k-slices write their partial sums to aux0[slice][m][n] (float32,
+  // M x N each, at least gemm_split_partials_bytes()) and a second launch adds the slices up in a fixed order --
+  // bit-reproducible, where the default meets in float atomics on the output.
   const void* aux0;
   const void* aux1;
   int ld0;       // leading dimension of out0/out1/out2
@@ -90,6 +94,8 @@ hipError_t launch_gemm_simple(const GemmDesc& g, const GemmEpi& e, hipStream_t s
 // and 16-byte aligned pointers; gemm_mfma_supported() checks this.
 bool gemm_mfma_supported(const GemmDesc& g, const GemmEpi& e);
 hipError_t launch_gemm_mfma(const GemmDesc& g, const GemmEpi& e, hipStream_t st);
+// Bytes of the partial-sum buffer (GemmEpi::aux0) that launch_gemm_mfma would use for this EPI_SPLIT_F32 problem (0: no split).
+size_t gemm_split_partials_bytes(const GemmDesc& g, const GemmEpi& e);
 
 // Sets up to 12 float arrays to zero in one launch (the weight gradients, before the split-k GEMMs add
 // their partial sums into them, and the bias-gradient diagonals).
@@ -169,9 +175,13 @@ hipError_t launch_attn_fwd_mfma(const AttnIO& io, const float* diag, void* c, fl
 bool attn_bwd_mfma_fits(const AttnDims& a, int far);
 // phase 1: dq, dvec = rowsum(dO * O) and the bias-gradient diagonals, ADDED into ddiag (the caller clears
 // it); phase 2: dk, dv (reads dvec, so it runs after phase 1).
+// ddiag_part (phase 1, with bias; nullable): when given, at least attn_ddiag_part_bytes(); the workgroups then
+// write their bias-gradient windows there and a second kernel adds them into ddiag in a fixed order
+// (bit-reproducible) instead of meeting in float atomics.
+size_t attn_ddiag_part_bytes(const AttnDims& a);
 hipError_t launch_attn_bwd_mfma(const AttnIO& io, const void* c, const void* dc, const float* diag,
                                 const float* lse, float* dvec, float* ddiag, const AttnDims& a, int far,
-                                int phase, hipStream_t st);
+                                int phase, hipStream_t st, float* ddiag_part = nullptr);
 
 // ------------------------------------------------------------------ ends of the layer stack
 // x[r, :] = E[tokens[r], :] (storage type); ids outside [0, vocab) are clamped into it.

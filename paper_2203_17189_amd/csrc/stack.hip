@@ -72,8 +72,9 @@ GemmEpi wgrad_epi(const Dims& D, int kind, float* o0, float* o1, float* o2) {
   return e;
 }
 bool wgrads_grouped_ok(const Dims& D, int L, bool remat) {
-  if (D.ty != IN_BF16 || remat || L < 2 || L > 256) return false;
-  static const long long dummy[4] = {0, 0, 0, 0};
+  // (the reproducible mode keeps the per-layer launches: their split reductions go through the two-pass form)
+  if (D.ty != IN_BF16 || remat || L < 2 || L > 256 || D.det) return false;
+  alignas(16) static const long long dummy[4] = {0, 0, 0, 0};
   for (int kind = 0; kind < (D.Sk > 0 ? kWgradKinds : 4); ++kind) {
     GemmDesc g = wgrad_desc(D, kind, dummy, dummy);
     g.groups = (const void* const*)dummy; g.ngroups = L;
@@ -189,7 +190,7 @@ int layers_backward(const Layers& s, const void* enc_out, float* denc_acc, int a
     carve_bwd(D, i == 0 ? s.block_ws : (void*)((char*)s.layer_ws + (size_t)(i - 1) * s.bwd_ws_each), &bws[i]);
     bws[i].ddiag = s.ddiag;
     bws[i].defer_wgrad = s.grouped;
-    if (!s.grouped) bws[i].fork = fork_begin(st, D.drop == 0.f);
+    if (!s.grouped) bws[i].fork = fork_begin(st, D.drop == 0.f && !D.det);
   }
   const int nring = s.grouped ? s.L + 1 : 2;
   auto ring = [&](int i) -> void* {

@@ -48,6 +48,7 @@ class BlockConfig:
     mlp: str = "geglu_tanh"   # feed-forward: "geglu_tanh" (T5.1.1) | "geglu_erf" | "relu" (original T5, no gate)
     dropout_rate: float = 0.0 # > 0: training-time dropout at the four T5 sites of the block
     dropout_seed: int = 0     # 64-bit seed of the counter-based generator (a caller varies it per step and layer)
+    deterministic: bool = False  # True: weight and bias-table gradients summed in a fixed order (bit-reproducible)
     enc_seq: int = 0          # > 0: decoder block, with a cross-attention sublayer over an encoder
                               # output of this length between self-attention and the MLP
 
