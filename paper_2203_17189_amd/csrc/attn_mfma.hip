@@ -16,6 +16,10 @@
 // query tile in LDS beside -lse and -dvec.  The factor 1/(1 - rate) of the kept probabilities is applied
 // to the finished O and dV accumulators, and to dP before dvec is subtracted.
 //
+// Sequence lengths need not be multiples of the tile sizes: tiles are rounded up, rows past the end are
+// fetched from the last valid row, keys past the end are masked like causal ones, and queries past the end
+// are neither stored nor counted in the bias gradient.
+//
 // The bias is Toeplitz: bias[h,i,j] = diag[h][j - i + S - 1].  Each workgroup stages the slice of
 // the per-head diagonal vector it can touch (S + tile - 1 floats) in LDS.
 #include "kernels.h"
@@ -66,13 +70,16 @@ template <int DK, int ROWS>
 struct TileDma {
   static constexpr int PER_WAVE = ROWS * DK * 2 / 1024 / 4;
   uint32_t voff[PER_WAVE];
-  __device__ __forceinline__ void init(int wave, int lane, size_t ld_elems) {
+  // valid: rows of the tile that exist; the others fetch the last valid row again (their values are masked
+  // or never stored), so that a ragged last tile reads nothing outside the operand
+  __device__ __forceinline__ void init(int wave, int lane, size_t ld_elems, int valid = ROWS) {
     constexpr int CPR = DK / 8;
 #pragma unroll
     for (int i = 0; i < PER_WAVE; ++i) {
       const int slot = (wave + i * 4) * 64 + lane;
       const int row = slot / CPR, pch = slot % CPR;
-      voff[i] = (uint32_t)(row * ld_elems * 2) + (uint32_t)((pch ^ row_swz<DK>(row)) << 4);
+      const int src = row < valid ? row : valid - 1;
+      voff[i] = (uint32_t)(src * ld_elems * 2) + (uint32_t)((pch ^ row_swz<DK>(row)) << 4);
     }
   }
   __device__ __forceinline__ void issue(uint32_t lds_addr, const void* sbase, int wave) const {
@@ -172,12 +179,12 @@ __device__ __forceinline__ void diag_accum(const f32x16& ds, int lp, float& lo, 
 // Number of 32-key blocks on each side of a wave's queries whose diagonals are resolved one by one in
 // the dq kernel: offsets up to far + 30 can fall into a sub-tile that is not entirely saturated.
 __host__ __device__ inline int attn_dq_window_blocks(int S, int far) {
-  const int nb = (far + 30) / 32, cap = S / 32 - 1;
+  const int nb = (far + 30) / 32, cap = (S + 31) / 32 - 1;
   return nb < cap ? nb : cap;
 }
-// Floats per workgroup row of the reproducible bias-gradient buffer: a window is at most 2 S entries wide
-// (+ 4 for the upper lane half) and two sums of the saturated buckets follow it.
-__host__ __device__ inline int attn_ddiag_part_stride(int S) { return 2 * S + 8; }
+// Floats per workgroup row of the reproducible bias-gradient buffer: a window is at most 64 * ceil(S / 32)
+// entries wide (+ 4 for the upper lane half) and two sums of the saturated buckets follow it.
+__host__ __device__ inline int attn_ddiag_part_stride(int S) { return 64 * ((S + 31) / 32) + 8; }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // ------------------------------------------------------------------------------------------------
@@ -197,8 +204,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnIO io, const 
   const int S = a.S, Sk = a.Sk, I = a.H * DK;
   const size_t ldq = (size_t)io.ldq, ld = (size_t)io.ldkv;
   int qt, h, b;
-  decode_block(S / BR, a.H, a.B, qt, h, b);
-  if (CAUSAL) qt = S / BR - 1 - qt;  // heavy causal tiles first
+  decode_block((S + BR - 1) / BR, a.H, a.B, qt, h, b);
+  if (CAUSAL) qt = (S + BR - 1) / BR - 1 - qt;  // heavy causal tiles first
   const int i0 = qt * BR;
   const int i_loc = wave * 32 + (lane & 31);
   const int i = i0 + i_loc;
@@ -231,24 +238,28 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnIO io, const 
     for (int r = 0; r < 16; ++r) oT[ct][r] = 0.f;
   float m = -INFINITY, l = 0.f;
 
-  int n_kv = Sk / BC;
+  int n_kv = (Sk + BC - 1) / BC;
   if (CAUSAL) {
     const int last = (i0 + BR < S ? i0 + BR : S);
     n_kv = (last + BC - 1) / BC;
   }
-  // K/V tiles are double buffered: tile jt+1 is in flight (DMA) while tile jt is used.
-  TileDma<DK, BC> td;
+  // K/V tiles are double buffered: tile jt+1 is in flight (DMA) while tile jt is used.  td_tail fetches the
+  // last tile of a key sequence whose length is not a multiple of the tile.
+  TileDma<DK, BC> td, td_tail;
   td.init(wave, lane, ld);
+  td_tail.init(wave, lane, ld, Sk % BC ? Sk % BC : BC);
+  const int jt_tail = Sk % BC ? Sk / BC : -1;  // index of the ragged tile, if there is one
   const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)smem;
-  td.issue(lds0, kbase, wave);
-  td.issue(lds0 + TILE, vbase, wave);
+  (jt_tail == 0 ? td_tail : td).issue(lds0, kbase, wave);
+  (jt_tail == 0 ? td_tail : td).issue(lds0 + TILE, vbase, wave);
   for (int jt = 0; jt < n_kv; ++jt) {
     const int j0 = jt * BC;
     dma_wait_barrier();  // tile jt landed; every wave is done with the other stage
     if (jt + 1 < n_kv) {
       const uint32_t nxt = lds0 + ((jt + 1) & 1) * STG;
-      td.issue(nxt, kbase + (size_t)(j0 + BC) * ld, wave);
-      td.issue(nxt + TILE, vbase + (size_t)(j0 + BC) * ld, wave);
+      const TileDma<DK, BC>& tn = jt + 1 == jt_tail ? td_tail : td;
+      tn.issue(nxt, kbase + (size_t)(j0 + BC) * ld, wave);
+      tn.issue(nxt + TILE, vbase + (size_t)(j0 + BC) * ld, wave);
     }
     const char* Kt = smem + (jt & 1) * STG;
     const char* Vt = Kt + TILE;
@@ -265,15 +276,18 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnIO io, const 
     }
     float mx = -INFINITY;
     // only tiles that reach above the diagonal of this wave's queries pay for the mask (wave-uniform)
-    const bool on_diag = CAUSAL && j0 + BC - 1 > i0 + wave * 32;
+    // (and the tile that reaches past the last key)
+    const bool on_diag = (CAUSAL && j0 + BC - 1 > i0 + wave * 32) || j0 + BC > Sk;
     if (on_diag) {
 #pragma unroll
       for (int kt = 0; kt < BC / 32; ++kt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int j = j0 + kt * 32 + ((r >> 2) << 3) + (g << 2) + (r & 3);
-          float s = BIAS ? fmaf(sT[kt][r], sc, dg[dg_base + j]) : sT[kt][r] * sc;
-          if (j > i) s = -INFINITY;
+          // (a masked key's bias slot may lie outside the slice: clamp the index, the value is discarded)
+          const int jb = j < Sk ? j : Sk - 1;
+          float s = BIAS ? fmaf(sT[kt][r], sc, dg[dg_base + jb]) : sT[kt][r] * sc;
+          if ((CAUSAL && j > i) || j >= Sk) s = -INFINITY;
           sT[kt][r] = s;
           mx = fmaxf(mx, s);
         }
@@ -382,13 +396,15 @@ __global__ __launch_bounds__(256, DK == 64 && !DROP ? 3 : 2) void attn_bwd_dq_mf
   const int S = a.S, Sk = a.Sk, I = a.H * DK;
   const size_t ldq = (size_t)io.ldq, ld = (size_t)io.ldkv;
   int qt, h, b;
-  decode_block(S / BR, a.H, a.B, qt, h, b);
-  if (CAUSAL) qt = S / BR - 1 - qt;
+  decode_block((S + BR - 1) / BR, a.H, a.B, qt, h, b);
+  if (CAUSAL) qt = (S + BR - 1) / BR - 1 - qt;
   const int i0 = qt * BR;
   const int i_w0 = i0 + wave * 32;         // first query of this wave
   const int i_lw = lane & 31;              // query index inside the wave
   const int i_loc = wave * 32 + i_lw;
   const int i = i0 + i_loc;
+  const int i_ld = i < S ? i : S - 1;      // queries past the end read the last row; their ds is forced to zero
+  const bool q_ok = i < S;
   const bf16* kbase = (const bf16*)io.k + (size_t)b * Sk * ld + h * DK;
   const bf16* vbase = (const bf16*)io.v + (size_t)b * Sk * ld + h * DK;
   float* ddgw = ddg_all + (wave * 2 + g) * W + (31 - i_lw);  // this lane's first slot of block m = -nb
@@ -396,9 +412,9 @@ __global__ __launch_bounds__(256, DK == 64 && !DROP ? 3 : 2) void attn_bwd_dq_mf
   bf16x8 qf[KS], dof[KS];
   float dsum = 0.f;  // this lane half's share of sum_c dO * O
   {
-    const bf16* qrow = (const bf16*)io.q + ((size_t)b * S + i) * ldq + h * DK;
-    const bf16* drow = dout + ((size_t)b * S + i) * I + h * DK;
-    const bf16* orow = o + ((size_t)b * S + i) * I + h * DK;
+    const bf16* qrow = (const bf16*)io.q + ((size_t)b * S + i_ld) * ldq + h * DK;
+    const bf16* drow = dout + ((size_t)b * S + i_ld) * I + h * DK;
+    const bf16* orow = o + ((size_t)b * S + i_ld) * I + h * DK;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
       qf[kk] = *reinterpret_cast<const bf16x8*>(qrow + kk * 16 + g * 8);
@@ -409,8 +425,8 @@ __global__ __launch_bounds__(256, DK == 64 && !DROP ? 3 : 2) void attn_bwd_dq_mf
     }
   }
   dsum += __shfl_xor(dsum, 32, 64);
-  const size_t srow = ((size_t)b * a.H + h) * S + i;
-  if (g == 0) dvec[srow] = dsum;
+  const size_t srow = ((size_t)b * a.H + h) * S + i_ld;
+  if (g == 0 && q_ok) dvec[srow] = dsum;
   const float nlse2 = -lse[srow] * kLog2e, ndv = -dsum;
   uint32_t k1 = 0;  // dropout row key of this lane's query
   if constexpr (DROP) k1 = drop_row_key(a.drop, (uint32_t)srow);
@@ -421,7 +437,10 @@ __global__ __launch_bounds__(256, DK == 64 && !DROP ? 3 : 2) void attn_bwd_dq_mf
   };
   if constexpr (BIAS) {
     const float* dgh = diag + (size_t)h * (2 * S - 1);
-    fill_bias_slice(dg, dgh, S + BR - 1, tid, [&](int t) { return t - (i0 + BR - 1) + (S - 1); });
+    fill_bias_slice(dg, dgh, S + BR - 1, tid, [&](int t) {
+      const int idx = t - (i0 + BR - 1) + (S - 1);  // delta + S - 1
+      return idx < 0 ? 0 : idx;                     // only reachable by queries past the end
+    });
     for (int t = tid; t < 8 * W; t += 256) ddg_all[t] = 0.f;
   }
   const float sc = a.scale * kLog2e;
@@ -434,19 +453,22 @@ __global__ __launch_bounds__(256, DK == 64 && !DROP ? 3 : 2) void attn_bwd_dq_mf
 #pragma unroll
     for (int r = 0; r < 16; ++r) dqT[ct][r] = 0.f;
 
-  const int n_kv = CAUSAL ? (i0 + BR) / BC : Sk / BC;
-  TileDma<DK, BC> td;
+  const int n_kv = ((CAUSAL && i0 + BR < Sk ? i0 + BR : Sk) + BC - 1) / BC;
+  TileDma<DK, BC> td, td_tail;  // td_tail: the last tile of a key sequence that does not fill it
   td.init(wave, lane, ld);
+  td_tail.init(wave, lane, ld, Sk % BC ? Sk % BC : BC);
+  const int jt_tail = Sk % BC ? Sk / BC : -1;
   const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)smem;
-  td.issue(lds0, kbase, wave);
-  td.issue(lds0 + TILE, vbase, wave);
+  (jt_tail == 0 ? td_tail : td).issue(lds0, kbase, wave);
+  (jt_tail == 0 ? td_tail : td).issue(lds0 + TILE, vbase, wave);
   for (int jt = 0; jt < n_kv; ++jt) {
     const int j0 = jt * BC;
     dma_wait_barrier();  // tile jt landed; every wave is done with the other stage
     if (jt + 1 < n_kv) {
       const uint32_t nxt = lds0 + ((jt + 1) & 1) * STG;
-      td.issue(nxt, kbase + (size_t)(j0 + BC) * ld, wave);
-      td.issue(nxt + TILE, vbase + (size_t)(j0 + BC) * ld, wave);
+      const TileDma<DK, BC>& tn = jt + 1 == jt_tail ? td_tail : td;
+      tn.issue(nxt, kbase + (size_t)(j0 + BC) * ld, wave);
+      tn.issue(nxt + TILE, vbase + (size_t)(j0 + BC) * ld, wave);
     }
     const char* Kt = smem + (jt & 1) * STG;
     const char* Vt = Kt + TILE;
@@ -454,6 +476,7 @@ __global__ __launch_bounds__(256, DK == 64 && !DROP ? 3 : 2) void attn_bwd_dq_mf
     for (int kt = 0; kt < BC / 32; ++kt) {
       const int j0s = j0 + kt * 32;
       if (CAUSAL && j0s > i_w0 + 31) continue;  // whole sub-tile masked for this wave
+      if (j0s >= Sk || i_w0 >= S) continue;     // whole sub-tile past the last key, or no query of this wave exists
       // The bias values are requested before the MFMAs (and the scheduler may not sink them): read at
       // first use, each one stalls the softmax arithmetic for an LDS round trip.  Prefetching the
       // MFMA operands as well, or seeding the accumulators with -lse and -dvec, costs more registers
@@ -461,7 +484,10 @@ __global__ __launch_bounds__(256, DK == 64 && !DROP ? 3 : 2) void attn_bwd_dq_mf
       float bias[16];
       if constexpr (BIAS) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) bias[r] = dg[dg_base + j0s + ((r >> 2) << 3) + (g << 2) + (r & 3)];
+        for (int r = 0; r < 16; ++r) {
+          const int j = j0s + ((r >> 2) << 3) + (g << 2) + (r & 3);
+          bias[r] = dg[dg_base + (j < Sk ? j : Sk - 1)];  // (keys past the end are masked below)
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
       f32x16 sT, dpT;
@@ -472,12 +498,14 @@ __global__ __launch_bounds__(256, DK == 64 && !DROP ? 3 : 2) void attn_bwd_dq_mf
         sT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Kt, kt * 32, kk, lane), qf[kk], sT, 0, 0, 0);
         dpT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Vt, kt * 32, kk, lane), dof[kk], dpT, 0, 0, 0);
       }
-      if (CAUSAL && j0s + 31 > i_w0) {  // sub-tile reaches above the diagonal (wave-uniform)
+      // sub-tile reaches above the diagonal, past the last key, or this wave holds queries past the end
+      // (all wave-uniform)
+      if ((CAUSAL && j0s + 31 > i_w0) || j0s + 32 > Sk || i_w0 + 32 > S) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int j = j0s + ((r >> 2) << 3) + (g << 2) + (r & 3);
           float p = BIAS ? fast_exp2(fmaf(sT[r], sc, bias[r]) + nlse2) : fast_exp2(fmaf(sT[r], sc, nlse2));
-          if (j > i) p = 0.f;
+          if ((CAUSAL && j > i) || j >= Sk || !q_ok) p = 0.f;
           sT[r] = p * (dp_masked(dpT[r], j) + ndv);
         }
       } else {
@@ -517,7 +545,7 @@ __global__ __launch_bounds__(256, DK == 64 && !DROP ? 3 : 2) void attn_bwd_dq_mf
       }
     }
   }
-  {
+  if (q_ok) {
     bf16* qrow = (bf16*)io.dq + ((size_t)b * S + i) * (size_t)io.lddq + h * DK;
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct)
@@ -535,7 +563,7 @@ __global__ __launch_bounds__(256, DK == 64 && !DROP ? 3 : 2) void attn_bwd_dq_mf
   // this workgroup's row of ddiag_part (attn_ddiag_reduce_kernel adds the rows up in a fixed order)
   float* ddh = ddiag + (size_t)h * (2 * S - 1);
   float* part = nullptr;
-  if (ddiag_part) part = ddiag_part + (((size_t)b * a.H + h) * (S / BR) + qt) * (size_t)attn_ddiag_part_stride(S);
+  if (ddiag_part) part = ddiag_part + (((size_t)b * a.H + h) * ((S + BR - 1) / BR) + qt) * (size_t)attn_ddiag_part_stride(S);
   __syncthreads();
   for (int t = tid; t < W + 4; t += 256) {
     float v = 0.f;
@@ -580,7 +608,7 @@ __global__ __launch_bounds__(256) void attn_ddiag_reduce_kernel(const float* __r
   __shared__ float red[2][4][64];
   const int nch = gridDim.x / H;
   const int h = blockIdx.x / nch, chunk = blockIdx.x % nch;
-  const int nt = S / 128, W = 32 * (2 * nb + 2), rows = B * nt;
+  const int nt = (S + 127) / 128, W = 32 * (2 * nb + 2), rows = B * nt;
   const size_t stride = (size_t)attn_ddiag_part_stride(S);
   const int tl = threadIdx.x & 63, grp = threadIdx.x >> 6;
   const int t = chunk * 64 + tl;                      // entry: [0, W+4) window, W+4 / W+5 the two sums
@@ -641,7 +669,7 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
   const int S = a.S, Sk = a.Sk, I = a.H * DK;
   const size_t ld = (size_t)io.ldq, ldkv = (size_t)io.ldkv;
   int kt_, h, b;
-  decode_block(Sk / BCK, a.H, a.B, kt_, h, b);
+  decode_block((Sk + BCK - 1) / BCK, a.H, a.B, kt_, h, b);
   const int j0 = kt_ * BCK;
   const int j_loc = wave * 32 + (lane & 31);
   const int j = j0 + j_loc;
@@ -679,18 +707,23 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
   const int it_begin = CAUSAL ? (j0 / BQ) : 0;
   const size_t srow = ((size_t)b * a.H + h) * S;
   // Q/dO tiles (DMA) and the matching lse / dvec slices are double buffered.
-  TileDma<DK, BQ> tq, tdo;
+  // tq_tail / tdo_tail: the last tile of a query sequence that does not fill it
+  TileDma<DK, BQ> tq, tdo, tq_tail, tdo_tail;
   tq.init(wave, lane, ld);
   tdo.init(wave, lane, (size_t)I);
+  tq_tail.init(wave, lane, ld, S % BQ ? S % BQ : BQ);
+  tdo_tail.init(wave, lane, (size_t)I, S % BQ ? S % BQ : BQ);
+  const int it_tail = S % BQ ? S / BQ : -1;
   const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)smem;
-  const int n_it = S / BQ;
-  tq.issue(lds0, base + (size_t)it_begin * BQ * ld, wave);
-  tdo.issue(lds0 + TILE, dobase + (size_t)it_begin * BQ * I, wave);
+  const int n_it = (S + BQ - 1) / BQ;
+  (it_begin == it_tail ? tq_tail : tq).issue(lds0, base + (size_t)it_begin * BQ * ld, wave);
+  (it_begin == it_tail ? tdo_tail : tdo).issue(lds0 + TILE, dobase + (size_t)it_begin * BQ * I, wave);
   const float neg_inv_scale = -1.f / a.scale;
   if (tid < BQ) {
-    lse_all[tid] = lse[srow + it_begin * BQ + tid] * neg_inv_scale;
-    dv_all[tid] = -dvec[srow + it_begin * BQ + tid];
-    if constexpr (DROP) key_all[tid] = drop_row_key(a.drop, (uint32_t)(srow + it_begin * BQ + tid));
+    const int qi = it_begin * BQ + tid < S ? it_begin * BQ + tid : S - 1;  // (rows past the end are masked)
+    lse_all[tid] = lse[srow + qi] * neg_inv_scale;
+    dv_all[tid] = -dvec[srow + qi];
+    if constexpr (DROP) key_all[tid] = drop_row_key(a.drop, (uint32_t)(srow + qi));
   }
   for (int it = it_begin; it < n_it; ++it) {
     const int q0 = it * BQ;
@@ -701,12 +734,13 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
     const bool more = it + 1 < n_it;
     if (more) {
       const uint32_t nxt = lds0 + (st ^ 1) * STG;
-      tq.issue(nxt, base + (size_t)(q0 + BQ) * ld, wave);
-      tdo.issue(nxt + TILE, dobase + (size_t)(q0 + BQ) * I, wave);
+      (it + 1 == it_tail ? tq_tail : tq).issue(nxt, base + (size_t)(q0 + BQ) * ld, wave);
+      (it + 1 == it_tail ? tdo_tail : tdo).issue(nxt + TILE, dobase + (size_t)(q0 + BQ) * I, wave);
       if (tid < BQ) {
-        nl = lse[srow + q0 + BQ + tid] * neg_inv_scale;
-        nd = -dvec[srow + q0 + BQ + tid];
-        if constexpr (DROP) nkey = drop_row_key(a.drop, (uint32_t)(srow + q0 + BQ + tid));
+        const int qi = q0 + BQ + tid < S ? q0 + BQ + tid : S - 1;
+        nl = lse[srow + qi] * neg_inv_scale;
+        nd = -dvec[srow + qi];
+        if constexpr (DROP) nkey = drop_row_key(a.drop, (uint32_t)(srow + qi));
       }
     }
     const char* Qt = smem + st * STG;
@@ -725,7 +759,10 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
       if constexpr (HOIST) {
 #pragma unroll
         for (int r = 0; r < 16; ++r)
-          bias[r] = dg[j_loc + (S - 1 - (q0 + qb * 32 + ((r >> 2) << 3) + (g << 2) + (r & 3)))];
+        {
+          const int i = q0 + qb * 32 + ((r >> 2) << 3) + (g << 2) + (r & 3);
+          bias[r] = dg[j_loc + (S - 1 - (i < S ? i : S - 1))];
+        }
       }
       f32x16 s, dp;
 #pragma unroll
@@ -743,13 +780,15 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Dt, qb * 32, kk, lane), vf[kk], dp, 0, 0, 0);
       }
       // with 64 channels the second copy of the loop costs a wave per SIMD in registers: mask always
-      if (CAUSAL && (DK == 64 || j0 + wave * 32 + 31 > q0 + qb * 32)) {  // some key here lies after some query
+      // some key here lies after some query, or the tile reaches past the last query (both wave-uniform)
+      if ((CAUSAL && (DK == 64 || j0 + wave * 32 + 31 > q0 + qb * 32)) || q0 + BQ > S) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int il = qb * 32 + ((r >> 2) << 3) + (g << 2) + (r & 3);
           const int i = q0 + il;
-          float p = BIAS ? fast_exp2(fmaf(s[r], sc, HOIST ? bias[r] : dg[j_loc + (S - 1 - i)])) : fast_exp2(s[r] * sc);
-          if (j > i) p = 0.f;
+          const int ib = i < S ? i : S - 1;  // (a masked query's bias slot may lie outside the slice)
+          float p = BIAS ? fast_exp2(fmaf(s[r], sc, HOIST ? bias[r] : dg[j_loc + (S - 1 - ib)])) : fast_exp2(s[r] * sc);
+          if ((CAUSAL && j > i) || i >= S) p = 0.f;
           if constexpr (DROP) {
             const bool keep = mix32(key_s[il] ^ (uint32_t)j) >= a.drop.thr;
             s[r] = keep ? p : 0.f;
@@ -829,7 +868,7 @@ hipError_t fwd_launch(const AttnIO& io, const float* diag, void* c, float* lse, 
   const size_t lds = 4 * 64 * DK * 2 + (BIAS ? sizeof(float) * (a.S + 127) : 0);
   hipError_t e = set_lds(kern, lds);
   if (e != hipSuccess) return e;
-  kern<<<dim3((a.S / 128) * a.H * a.B), 256, lds, st>>>(io, diag, (bf16*)c, lse, a);
+  kern<<<dim3(((a.S + 127) / 128) * a.H * a.B), 256, lds, st>>>(io, diag, (bf16*)c, lse, a);
   return hipGetLastError();
 }
 
@@ -842,7 +881,7 @@ hipError_t bwd_launch(const AttnIO& io, const void* c, const void* dc, const flo
     auto kern = attn_bwd_dq_mfma_kernel<DK, CAUSAL, BIAS, DROP>;
     const size_t lds = attn_bwd_dq_lds_bytes(a, far);
     if ((e = set_lds(kern, lds)) != hipSuccess) return e;
-    kern<<<dim3((a.S / 128) * a.H * a.B), 256, lds, st>>>(io, (const bf16*)c, (const bf16*)dc, diag, lse, dvec, ddiag,
+    kern<<<dim3(((a.S + 127) / 128) * a.H * a.B), 256, lds, st>>>(io, (const bf16*)c, (const bf16*)dc, diag, lse, dvec, ddiag,
                                                           BIAS ? ddiag_part : nullptr, a, far);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (BIAS && ddiag_part) {
@@ -856,7 +895,7 @@ hipError_t bwd_launch(const AttnIO& io, const void* c, const void* dc, const flo
     auto kern = attn_bwd_dkv_mfma_kernel<DK, CAUSAL, BIAS, DROP>;
     const size_t lds = 4 * 64 * DK * 2 + sizeof(float) * (256 + (DROP ? 128 : 0) + (BIAS ? a.S + 127 : 0));
     if ((e = set_lds(kern, lds)) != hipSuccess) return e;
-    kern<<<dim3((a.Sk / 128) * a.H * a.B), 256, lds, st>>>(io, (const bf16*)dc, diag, lse, dvec, a);
+    kern<<<dim3(((a.Sk + 127) / 128) * a.H * a.B), 256, lds, st>>>(io, (const bf16*)dc, diag, lse, dvec, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   return hipSuccess;
@@ -873,9 +912,9 @@ bool attn_bwd_mfma_fits(const AttnDims& a, int far) {
 }
 
 bool attn_mfma_supported(const AttnDims& a) {
-  // S, Sk % 128: query/key tiles of 128 without ragged edges; LDS holds the diagonal slice (S + 127
-  // floats).  Without the bias only the unmasked form exists; bias and mask need square scores.
-  if (!(a.dk == 64 || a.dk == 128) || a.S % 128 != 0 || a.Sk % 128 != 0 || a.S > 8192 || a.Sk > 65536) return false;
+  // Any lengths from 32 up (tiles are rounded up and their tails masked); LDS holds the diagonal slice
+  // (S + 127 floats).  Without the bias only the unmasked form exists; bias and mask need square scores.
+  if (!(a.dk == 64 || a.dk == 128) || a.S < 32 || a.Sk < 32 || a.S > 8192 || a.Sk > 65536) return false;
   if (a.bias) return a.Sk == a.S;
   return !a.causal;
 }
@@ -905,7 +944,7 @@ hipError_t launch_attn_fwd_mfma(const AttnIO& io, const float* diag, void* c, fl
 }
 
 size_t attn_ddiag_part_bytes(const AttnDims& a) {
-  return (size_t)a.B * a.H * (a.S / 128) * (size_t)attn_ddiag_part_stride(a.S) * sizeof(float);
+  return (size_t)a.B * a.H * ((a.S + 127) / 128) * (size_t)attn_ddiag_part_stride(a.S) * sizeof(float);
 }
 
 hipError_t launch_attn_bwd_mfma(const AttnIO& io, const void* c, const void* dc, const float* diag,

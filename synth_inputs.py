@@ -272,9 +272,8 @@ def _encdec(name, index, batch, enc_seq, dec_seq, d, h, dk, f, le, ld, vocab, **
 
 
 ENCDEC_CONFIGS = {
-    # T5.1.1-Base: 12 + 12 layers, 512 encoder positions, 114 decoder positions in pre-training; the decoder
-    # length is rounded to 128 here so that its attention runs on the matrix-unit kernels
-    "e1_t5_base": _encdec("e1_t5_base", 8, 32, 512, 128, 768, 12, 64, 2048, 12, 12, 32128),
+    # T5.1.1-Base: 12 + 12 layers, 512 encoder positions, 114 decoder positions in pre-training
+    "e1_t5_base": _encdec("e1_t5_base", 8, 32, 512, 114, 768, 12, 64, 2048, 12, 12, 32128),
 }
 
 

@@ -170,8 +170,9 @@ def cross_attn_fwd(cfg, h1, enc, w):
     return h2, dict(h1=h1, enc=enc, nx=nx, rx=rx, q=q, k=k, v=v, keep_p=keep_p, keep_o=keep_o, c_h=c_h, c=c)
 
 
-def cross_attn_bwd(cfg, dh2, w, sv, g):
-    """(dh1 unrounded, denc rounded) from dh2; adds xq, xk, xv, xo, lnx_scale to g."""
+def cross_attn_bwd(cfg, dh2, w, sv, g, round_denc=True):
+    """(dh1 unrounded, denc) from dh2; adds xq, xk, xv, xo, lnx_scale to g.  denc is rounded to bf16 as the
+    decoder layer's entry point stores it; a stack sums the layers' contributions in float32 (round_denc=False)."""
     nh, dk = cfg.n_heads, cfg.d_kv
     dao = rb(dh2)
     if sv["keep_o"] is not None:
@@ -183,7 +184,9 @@ def cross_attn_bwd(cfg, dh2, w, sv, g):
     g["xq"] = _flat(sv["nx"]).T @ _flat(dqf)
     g["xk"] = _flat(sv["enc"]).T @ _flat(dkf)
     g["xv"] = _flat(sv["enc"]).T @ _flat(dvf)
-    denc = rb(dkf @ w["xk"].T + dvf @ w["xv"].T)
+    denc = dkf @ w["xk"].T + dvf @ w["xv"].T
+    if round_denc:
+        denc = rb(denc)
     dh1_norm, g["lnx_scale"] = O.rmsnorm_bwd(sv["h1"], w["lnx_scale"], sv["rx"], dqf @ w["xq"].T)
     return dh2 + dh1_norm, denc
 
@@ -256,6 +259,133 @@ def decoder_block_model(cfg, x, enc, w, dy, round_uw=False):
     dh1, denc = cross_attn_bwd(cfg, dh2, w, sx, g)
     dx = rb(self_attn_bwd(cfg, dh1, w, sa, g))
     return y, dx, denc, g
+
+
+# ------------------------------------------------------------------------------ stacks
+def _layer_fwd(cfg, x, w, enc, round_uw):
+    h, sa = self_attn_fwd(cfg, x, w)
+    sx = None
+    if enc is not None:
+        h, sx = cross_attn_fwd(cfg, h, enc, w)
+    y, sm = mlp_fwd(cfg, h, w, round_uw)
+    return y, (sa, sx, sm)
+
+
+def _layer_bwd(cfg, dy, w, saved):
+    """(dx rounded to bf16 -- the residual stream crosses layer boundaries in the storage type --,
+    denc unrounded or None, gradients)."""
+    sa, sx, sm = saved
+    g = {}
+    dh = mlp_bwd(cfg, dy, w, sm, g)
+    denc = None
+    if sx is not None:
+        dh, denc = cross_attn_bwd(cfg, dh, w, sx, g, round_denc=False)
+    return rb(self_attn_bwd(cfg, dh, w, sa, g)), denc, g
+
+
+def _head(cfg, x_last, final_scale, emb_or_w, tied, targets, z_loss, site):
+    """Final norm, logits, loss and the gradients of the head.  Returns (loss, dx_last rounded, dfinal_scale,
+    dW of the output matrix (or of the tied embedding), nf)."""
+    s = cfg.d_model ** -0.5 if tied else 1.0
+    gf = rb(final_scale * s) if tied else final_scale          # tied: the factor rides on the (stored) scale
+    nf, rf = O.rmsnorm_fwd(x_last, gf, cfg.rms_eps)
+    m_final = O._token_scale(cfg, site, nf.shape)
+    nf = rb(rb(nf) * m_final) if not np.isscalar(m_final) else rb(nf)
+    wmat = emb_or_w.T if tied else emb_or_w                    # [d, V]
+    logits = rb(nf @ wmat)
+    loss, lse, n = O.xent_zloss(logits, targets, z_loss)
+    dlogits = rb(O.xent_zloss_grad(logits, targets, lse, z_loss, n))
+    dw = _flat(nf).T @ _flat(dlogits)                          # [d, V]
+    dnf = dlogits @ wmat.T
+    dx, dgf = O.rmsnorm_bwd(x_last, gf, rf, dnf * m_final)
+    return loss, rb(dx), dgf * s, (dw.T if tied else dw)
+
+
+def stack_model(sc, tokens, targets, w, round_uw=False):
+    """(loss, gradients nested like the oracle's stack_loss_grad) under ideal bf16-operand arithmetic."""
+    cfg = sc.block
+    x = w["embedding"][tokens]
+    m_embed = O._token_scale(cfg, O.DROP_EMBED, x.shape)
+    if not np.isscalar(m_embed):
+        x = rb(x * m_embed)
+    saved = []
+    for l, lw in enumerate(w["layers"]):
+        wl = dict(lw, rel_table=w["rel_table"])
+        x, sv = _layer_fwd(O._with_layer_seed(cfg, l), x, wl, None, round_uw)
+        saved.append(sv)
+    loss, dx, dgf, dw = _head(cfg, x, w["final_scale"], w["embedding"] if sc.tied_logits else w["logits_w"],
+                              sc.tied_logits, targets, sc.z_loss, O.DROP_FINAL)
+    g = {"layers": [None] * sc.n_layers, "embedding": np.zeros_like(w["embedding"]), "final_scale": dgf,
+         "rel_table": np.zeros_like(w["rel_table"])}
+    if sc.tied_logits:
+        g["embedding"] += dw
+    else:
+        g["logits_w"] = dw
+    for l in range(sc.n_layers - 1, -1, -1):
+        wl = dict(w["layers"][l], rel_table=w["rel_table"])
+        dx, _, gl = _layer_bwd(O._with_layer_seed(cfg, l), dx, wl, saved[l])
+        g["rel_table"] += gl.pop("rel_table")
+        g["layers"][l] = gl
+    if not np.isscalar(m_embed):
+        dx = rb(dx * m_embed)
+    np.add.at(g["embedding"], tokens.reshape(-1), _flat(dx))
+    return loss, g
+
+
+def encdec_model(ec, enc_tokens, dec_tokens, targets, w, round_uw=False):
+    """(loss, gradients nested like the oracle's encdec_loss_grad) under ideal bf16-operand arithmetic."""
+    e, d = ec.enc_block, ec.dec_block
+    x = w["embedding"][enc_tokens]
+    me_embed = O._token_scale(e, O.DROP_EMBED, x.shape)
+    if not np.isscalar(me_embed):
+        x = rb(x * me_embed)
+    enc_saved = []
+    for l, lw in enumerate(w["enc_layers"]):
+        x, sv = _layer_fwd(O._with_layer_seed(e, l), x, dict(lw, rel_table=w["enc_rel_table"]), None, round_uw)
+        enc_saved.append(sv)
+    xe_last = x
+    enc_out, enc_rf = O.rmsnorm_fwd(x, w["enc_final_scale"], e.rms_eps)
+    me_final = O._token_scale(e, O.DROP_FINAL, enc_out.shape)
+    enc_out = rb(rb(enc_out) * me_final) if not np.isscalar(me_final) else rb(enc_out)
+    x = w["embedding"][dec_tokens]
+    md_embed = O._token_scale(d, O.DROP_DEC_EMBED, x.shape)
+    if not np.isscalar(md_embed):
+        x = rb(x * md_embed)
+    dec_saved = []
+    for l, lw in enumerate(w["dec_layers"]):
+        x, sv = _layer_fwd(O._with_layer_seed(d, ec.n_enc_layers + l), x, dict(lw, rel_table=w["dec_rel_table"]),
+                           enc_out, round_uw)
+        dec_saved.append(sv)
+    loss, dx, dgf, dw = _head(d, x, w["dec_final_scale"], w["embedding"] if ec.tied_logits else w["logits_w"],
+                              ec.tied_logits, targets, ec.z_loss, O.DROP_DEC_FINAL)
+    g = {"embedding": np.zeros_like(w["embedding"]), "enc_layers": [None] * ec.n_enc_layers,
+         "dec_layers": [None] * ec.n_dec_layers, "dec_final_scale": dgf,
+         "dec_rel_table": np.zeros_like(w["dec_rel_table"]), "enc_rel_table": np.zeros_like(w["enc_rel_table"])}
+    if ec.tied_logits:
+        g["embedding"] += dw
+    else:
+        g["logits_w"] = dw
+    denc_out = 0.0
+    for l in range(ec.n_dec_layers - 1, -1, -1):
+        wl = dict(w["dec_layers"][l], rel_table=w["dec_rel_table"])
+        dx, denc_l, gl = _layer_bwd(O._with_layer_seed(d, ec.n_enc_layers + l), dx, wl, dec_saved[l])
+        denc_out = denc_out + denc_l
+        g["dec_rel_table"] += gl.pop("rel_table")
+        g["dec_layers"][l] = gl
+    if not np.isscalar(md_embed):
+        dx = rb(dx * md_embed)
+    np.add.at(g["embedding"], dec_tokens.reshape(-1), _flat(dx))
+    dx, g["enc_final_scale"] = O.rmsnorm_bwd(xe_last, w["enc_final_scale"], enc_rf, denc_out * me_final)
+    dx = rb(dx)
+    for l in range(ec.n_enc_layers - 1, -1, -1):
+        wl = dict(w["enc_layers"][l], rel_table=w["enc_rel_table"])
+        dx, _, gl = _layer_bwd(O._with_layer_seed(e, l), dx, wl, enc_saved[l])
+        g["enc_rel_table"] += gl.pop("rel_table")
+        g["enc_layers"][l] = gl
+    if not np.isscalar(me_embed):
+        dx = rb(dx * me_embed)
+    np.add.at(g["embedding"], enc_tokens.reshape(-1), _flat(dx))
+    return loss, g
 
 
 def rel_err(a: np.ndarray, ref: np.ndarray):

@@ -74,6 +74,40 @@ def test_decoder_model_without_rounding_is_the_oracle(cfg, monkeypatch):
         np.testing.assert_allclose(mg[k], g[k], rtol=0, atol=1e-9 * max(1.0, np.abs(g[k]).max()), err_msg=k)
 
 
+def _max_diff(a, b):
+    if isinstance(a, dict):
+        return max(_max_diff(a[k], b[k]) for k in b)
+    if isinstance(a, list):
+        return max(_max_diff(x, y) for x, y in zip(a, b))
+    return float(np.abs(np.asarray(a) - np.asarray(b)).max())
+
+
+@pytest.mark.parametrize("tied,rate", [(False, 0.0), (True, 0.0), (False, 0.2), (True, 0.2)])
+def test_stack_models_without_rounding_are_the_oracle(tied, rate, monkeypatch):
+    monkeypatch.setattr(M, "rb", lambda a: np.asarray(a, dtype=np.float64))
+    blk = SI.BlockConfig("floor_stack", 95, batch=2, seq=24, d_model=32, n_heads=2, d_kv=8, d_ff=48, causal=True,
+                         attn_scale=0.3, dropout_rate=float(np.float32(rate)), dropout_seed=7)
+    sc = SI.StackConfig("floor_stack", blk, n_layers=2, vocab=37, tied_logits=tied, z_loss=1e-2)
+    w = SI.make_stack_weights(sc)
+    SI.make_stack_random_scales(sc, w)
+    tokens, targets = SI.make_tokens(sc, ignore_fraction=0.2)
+    loss, saved = O.stack_loss(sc, tokens, targets, w)
+    g = O.stack_loss_grad(sc, w, saved)
+    ml, mg = M.stack_model(sc, tokens, targets, w)
+    assert abs(ml - loss) <= 1e-12 and _max_diff(mg, g) <= 1e-12
+    ec = SI._encdec("floor_ec", 96, 2, 20, 12, 32, 2, 8, 48, 2, 2, 37, z_loss=1e-2, block=dict(dtype="f32"))
+    ec = replace(ec, tied_logits=tied,
+                 enc_block=replace(ec.enc_block, dropout_rate=float(np.float32(rate)), dropout_seed=3),
+                 dec_block=replace(ec.dec_block, dropout_rate=float(np.float32(rate)), dropout_seed=4))
+    w = SI.make_encdec_weights(ec)
+    SI.make_encdec_random_scales(ec, w)
+    et, dt, tg = SI.make_encdec_tokens(ec, ignore_fraction=0.15)
+    loss, saved = O.encdec_loss(ec, et, dt, tg, w)
+    g = O.encdec_loss_grad(ec, w, saved)
+    ml, mg = M.encdec_model(ec, et, dt, tg, w)
+    assert abs(ml - loss) <= 1e-12 and _max_diff(mg, g) <= 1e-12
+
+
 def test_rounding_is_bf16_round_to_nearest_even():
     # 1 + 2^-8 is a tie between 1 and 1 + 2^-7: goes to the even mantissa (1); 1 + 3 * 2^-8 goes up to 1 + 2^-6
     a = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20, 1.0 + 3 * 2.0 ** -8, -3.0, 1e-30])
@@ -138,8 +172,7 @@ def test_tol_from_floor_rule():
     assert abs(t[0] - max_margin(big) * 3.0e-2) < 1e-12 and t[1] == STATED_BF16[1]
     t = tol_from_floor((0.5e-2, 4.0e-3), big)
     assert t[0] == STATED_BF16[0] and abs(t[1] - MARGIN * 4.0e-3) <= 1e-3 * t[1]
-    assert MARGIN <= 1.25 and max_margin(1) == 2.0 and max_margin(64) == 2.0
-    assert abs(max_margin(10 ** 4) - 1.75) < 1e-9 and max_margin(10 ** 6) < 1.41 and max_margin(big) < 1.28
+    assert MARGIN <= 1.25 and max_margin(1) == 2.0 and max_margin(big) == 2.0
     # small tensors: the mean of 64 values is itself noisy
     assert abs(mean_margin(64) - (MARGIN + 0.4)) < 1e-12 and mean_margin(10 ** 6) < MARGIN + 0.004
     # ReLU gradients: wider margins for both statistics
@@ -153,7 +186,7 @@ def test_spread_between_two_samples_of_the_rounding_noise(monkeypatch):
     with every value perturbed by 3e-7 (relative, Gaussian) before it is rounded.  Only roundings that sit
     on a tie flip at first, but the flips spread down the chain: the six floors of a tensor agree closely in
     the mean of a large tensor, scatter in the mean of a small one, and scatter by tens of percent in the
-    maximum -- more than a flat 1.25 allows, within the size-dependent margins of parity_util."""
+    maximum -- more than a flat 1.25 allows, within the margins of parity_util."""
     cfg = SI.BlockConfig("floor_spread", 91, batch=2, seq=256, d_model=128, n_heads=2, d_kv=64, d_ff=256,
                          attn_scale=0.125)
     w, x, dy = _case(cfg)
@@ -173,8 +206,7 @@ def test_spread_between_two_samples_of_the_rounding_noise(monkeypatch):
         mx = np.array([f[name][0] for f in floors])
         mn = np.array([f[name][1] for f in floors])
         n = sizes[name]
-        # the extremes of six samples are further apart than two samples usually are: 10 % on top
-        assert mx.max() / mx.min() <= 1.1 * max_margin(n), (name, n, mx)
+        assert mx.max() / mx.min() <= max_margin(n), (name, n, mx)
         assert mn.max() / mn.min() <= 1.0 + 3.2 / n ** 0.5 + 0.02, (name, n, mn)
         worst_max = max(worst_max, mx.max() / mx.min())
         if n >= 16384:

@@ -70,15 +70,29 @@ SMALL_BF16 = [
     # three heads: workgroups are not dealt in groups of eight
     SI.BlockConfig("dec_bf16_h3", 48, batch=1, seq=128, d_model=192, n_heads=3, d_kv=64, d_ff=192, causal=True,
                    attn_scale=64 ** -0.5, enc_seq=128),
-    # encoder length not a multiple of 128: the simple cross-attention kernels with MFMA self-attention
+    # encoder length not a multiple of the attention tiles: ragged key tiles in the fused cross-attention
     SI.BlockConfig("dec_bf16_ragged_enc", 49, batch=2, seq=128, d_model=128, n_heads=2, d_kv=64, d_ff=256, causal=True,
                    attn_scale=64 ** -0.5, enc_seq=100),
+    # T5's own lengths: 114 decoder positions over 512 encoder positions, and a ragged pair
+    SI.BlockConfig("dec_bf16_s114", 53, batch=2, seq=114, d_model=128, n_heads=2, d_kv=64, d_ff=256, causal=True,
+                   attn_scale=64 ** -0.5, enc_seq=512),
+    SI.BlockConfig("dec_bf16_s200_e77", 54, batch=1, seq=200, d_model=128, n_heads=2, d_kv=128, d_ff=256, causal=True,
+                   attn_scale=128 ** -0.5, enc_seq=77),
     SI.BlockConfig("dec_bf16_relu", 52, batch=2, seq=128, d_model=128, n_heads=2, d_kv=64, d_ff=256, causal=True,
                    attn_scale=64 ** -0.5, enc_seq=128, mlp="relu"),
     # nothing a multiple of anything: simple kernels throughout
     SI.BlockConfig("dec_bf16_ragged", 50, batch=1, seq=100, d_model=72, n_heads=3, d_kv=24, d_ff=136, causal=True,
                    attn_scale=24 ** -0.5, enc_seq=61),
 ]
+
+
+def test_ragged_lengths_run_the_fused_attention_kernels():
+    import paper_2203_17189_amd as P
+    want = P.PATH_MFMA_ATTN_FWD | P.PATH_MFMA_ATTN_BWD | P.PATH_MFMA_CROSS_ATTN
+    for cfg in SMALL_BF16:
+        if cfg.d_kv in (64, 128):
+            assert P.t5_block_kernel_path(cfg) & want == want, (cfg.name, P.t5_block_kernel_path(cfg))
+    assert P.t5_block_kernel_path(SMALL_BF16[-1]) & want == 0      # 24 channels per head: general-shape kernels
 
 
 @pytest.mark.parametrize("cfg", SMALL_BF16, ids=[c.name for c in SMALL_BF16])

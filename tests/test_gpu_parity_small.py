@@ -266,7 +266,26 @@ SMALL_BF16 = [
                    attn_scale=24 ** -0.5, mlp="relu"),
     SI.BlockConfig("bf16_enc_b64_d1000", 39, batch=1, seq=384, d_model=128, n_heads=2, d_kv=64, d_ff=128,
                    num_buckets=64, max_distance=1000, attn_scale=64 ** -0.5),
+    # sequence lengths that are not multiples of the attention tiles, on the matrix-unit attention kernels
+    # (RAGGED_MFMA below asserts the path): T5's 114 decoder positions (shorter than one query tile), 200
+    # (ragged 64-key and 128-query tiles), 1000 (eight tiles, the last one ragged), both directions and widths
+    SI.BlockConfig("bf16_enc_s114", 20, batch=2, seq=114, d_model=128, n_heads=2, d_kv=64, d_ff=256,
+                   attn_scale=64 ** -0.5),
+    SI.BlockConfig("bf16_dec_s114", 21, batch=2, seq=114, d_model=128, n_heads=2, d_kv=64, d_ff=256, causal=True,
+                   attn_scale=64 ** -0.5),
+    SI.BlockConfig("bf16_enc_s200_dk128", 22, batch=1, seq=200, d_model=256, n_heads=2, d_kv=128, d_ff=320,
+                   attn_scale=128 ** -0.5),
+    SI.BlockConfig("bf16_dec_s200", 23, batch=2, seq=200, d_model=128, n_heads=3, d_kv=64, d_ff=256, causal=True,
+                   attn_scale=64 ** -0.5),
+    SI.BlockConfig("bf16_enc_s1000", 24, batch=1, seq=1000, d_model=64, n_heads=1, d_kv=64, d_ff=64,
+                   attn_scale=64 ** -0.5),
+    SI.BlockConfig("bf16_dec_s1000_dk128", 25, batch=1, seq=1000, d_model=128, n_heads=1, d_kv=128, d_ff=128, causal=True,
+                   attn_scale=128 ** -0.5),
+    SI.BlockConfig("bf16_enc_s33_b8_d20", 19, batch=2, seq=33, d_model=64, n_heads=1, d_kv=64, d_ff=64,
+                   num_buckets=8, max_distance=20, attn_scale=64 ** -0.5),
 ]
+RAGGED_MFMA = ("bf16_enc_s114", "bf16_dec_s114", "bf16_enc_s200_dk128", "bf16_dec_s200", "bf16_enc_s1000",
+               "bf16_dec_s1000_dk128", "bf16_enc_s33_b8_d20")
 
 
 def test_block_bf16_accumulate_flag():
@@ -294,6 +313,10 @@ def test_block_bf16_accumulate_flag():
 
 @pytest.mark.parametrize("cfg", SMALL_BF16, ids=[c.name for c in SMALL_BF16])
 def test_block_bf16_small(cfg):
+    if cfg.name in RAGGED_MFMA:   # these must run the fused matrix-unit attention, forward and backward
+        P = _P()
+        assert P.t5_block_kernel_path(cfg) & (P.PATH_MFMA_ATTN_FWD | P.PATH_MFMA_ATTN_BWD) == \
+            (P.PATH_MFMA_ATTN_FWD | P.PATH_MFMA_ATTN_BWD), P.t5_block_kernel_path(cfg)
     w, x, dy = make_case(cfg)
     y, saved = O.block_fwd(cfg, x, w)
     dx, g = O.block_bwd(cfg, dy, w, saved)
