@@ -330,7 +330,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
     }
   };
   auto no_gap = [](int) __attribute__((always_inline)) {};
-  constexpr int H0 = NS == 2 ? DMA_PER_TILE : DMA_PER_TILE / 2;  // a tile's DMA is issued in two parts: [0, H0) and [H0, DMA_PER_TILE)
+  constexpr int H0 = DMA_PER_TILE / 2;  // a tile's DMA is issued in two parts: [0, H0) and [H0, DMA_PER_TILE)
 
   // The k loop, compiled twice: for one run of tiles (one segment) and for several.
   auto k_loop = [&](auto multi_tag) __attribute__((always_inline)) {
@@ -801,6 +801,7 @@ hipError_t launch_layout(const GemmDesc& g, const GemmEpi& e, hipStream_t st) {
     // (-4..9 %)
     if (EPI_T == EPI_RESID && g.N < 1024 && nk > 8) {
       if (nk <= 12) return launch_cfg<128, 128, 2, 2, A_KC, B_KC, EPI_T, 4, 1>(g, e, split_k, st);
+      if constexpr (A_KC) return launch_cfg<256, 256, 2, 2, A_KC, B_KC, EPI_T, 2, 1, 64>(g, e, split_k, st);
       return launch_cfg<256, 256, 2, 2, A_KC, B_KC, EPI_T, 5, 1>(g, e, split_k, st);
     }
     // the residual epilogue with dropout does not fit the 256x256 tile's register budget (it would spill)
@@ -808,6 +809,15 @@ hipError_t launch_layout(const GemmDesc& g, const GemmEpi& e, hipStream_t st) {
     if (EPI != EPI_SPLIT_F32 && (nk <= 16 || (EPI == EPI_GEGLU_FWD && nk < 24) || EPI == EPI_GEGLU_BWD ||
                                  (EPI == EPI_RESID && nk <= 32)))
       return launch_cfg<256, 128, 2, 2, A_KC, B_KC, EPI_T, 3, 2>(g, e, split_k, st);
+    // k-contiguous operands: k-tiles of 64 in two stages.  A DMA instruction then covers eight whole 128-byte
+    // rows instead of sixteen half rows (the L1 processes a line per request whatever part of it is used, and
+    // at 64 bytes per row that path, not the matrix unit, sets the pace), and there is one barrier per 64 MFMAs
+    // instead of per 32.  Measured on the T5.1.1-XL GEMMs against five stages of 32: +7 to +12 %, once a tile's
+    // sixteen DMA instructions per wave are issued two per chunk over two k-steps instead of four per chunk over
+    // one (issued four at a time they stall the wave in the memory pipeline's queue and the gain is lost).
+    // The weight-gradient GEMMs (rows of 512 bytes already) and the 256x128 two-workgroup configuration lose
+    // with k-tiles of 64 (-4 % and -25 %) and keep 32.
+    if constexpr (A_KC) return launch_cfg<256, 256, 2, 2, A_KC, B_KC, EPI_T, 2, 1, 64>(g, e, split_k, st);
     return launch_cfg<256, 256, 2, 2, A_KC, B_KC, EPI_T, 5, 1>(g, e, split_k, st);
   }
   // too few 256x256 tiles to fill the chip, but a long reduction: 256x128 tiles, two per compute unit
