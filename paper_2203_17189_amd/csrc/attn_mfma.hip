@@ -748,6 +748,7 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
     const float* lse_s = lse_all + st * BQ;
     const float* dv_s = dv_all + st * BQ;
     const uint32_t* key_s = key_all + st * BQ;
+    bf16x8 qr[KS], dr[KS];
 #pragma unroll
     for (int qb = 0; qb < BQ / 32; ++qb) {
       // bias values and accumulator seeds are requested before the MFMAs so that their LDS latency
@@ -765,6 +766,9 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
         }
       }
       f32x16 s, dp;
+      // likewise the row operands of the tile's second sub-tile, requested before the dV / dK products of
+      // the first
+      constexpr bool ROWS_AHEAD = DK == 128;
 #pragma unroll
       for (int rq = 0; rq < 4; ++rq) {
         const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_s + qb * 32 + rq * 8 + g * 4);
@@ -776,8 +780,23 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
       if constexpr (HOIST) __builtin_amdgcn_sched_group_barrier(0x100, 12, 0);  // 8 bias + 4 seed reads first
 #pragma unroll
       for (int kk = 0; kk < KS; ++kk) {
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Qt, qb * 32, kk, lane), kf[kk], s, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Dt, qb * 32, kk, lane), vf[kk], dp, 0, 0, 0);
+        const bool pre = ROWS_AHEAD && qb == 1;
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pre ? qr[kk] : frag_rows<DK>(Qt, qb * 32, kk, lane), kf[kk], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pre ? dr[kk] : frag_rows<DK>(Dt, qb * 32, kk, lane), vf[kk], dp, 0, 0, 0);
+      }
+      // with 128 channels (one wave per SIMD, registers to spare) the transposed Q and dO operands of the
+      // dV / dK products are requested before the softmax arithmetic, which then covers their LDS
+      // latency; with 64 channels the second wave on the SIMD covers it and the registers are not there
+      constexpr bool TR_AHEAD = DK == 128;
+      bf16x8 dtr[2][CT], qtr[2][CT];
+      if constexpr (TR_AHEAD) {
+#pragma unroll
+        for (int mm = 0; mm < 2; ++mm)
+#pragma unroll
+          for (int ct = 0; ct < CT; ++ct) {
+            dtr[mm][ct] = frag_cols_tr<DK>(Dt, qb * 32 + mm * 16, ct * 32, lane);
+            qtr[mm][ct] = frag_cols_tr<DK>(Qt, qb * 32 + mm * 16, ct * 32, lane);
+          }
       }
       // with 64 channels the second copy of the loop costs a wave per SIMD in registers: mask always
       // some key here lies after some query, or the tile reaches past the last query (both wave-uniform)
@@ -814,15 +833,24 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
           }
         }
       }
+      if constexpr (ROWS_AHEAD) {
+        if (qb == 0) {
+#pragma unroll
+          for (int kk = 0; kk < KS; ++kk) {
+            qr[kk] = frag_rows<DK>(Qt, 32, kk, lane);
+            dr[kk] = frag_rows<DK>(Dt, 32, kk, lane);
+          }
+        }
+      }
 #pragma unroll
       for (int mm = 0; mm < 2; ++mm) {
         const bf16x8 pf = pack8(s, mm * 8), dsf = pack8(dp, mm * 8);
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) {
           dvT[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              frag_cols_tr<DK>(Dt, qb * 32 + mm * 16, ct * 32, lane), pf, dvT[ct], 0, 0, 0);
+              TR_AHEAD ? dtr[mm][ct] : frag_cols_tr<DK>(Dt, qb * 32 + mm * 16, ct * 32, lane), pf, dvT[ct], 0, 0, 0);
           dkT[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              frag_cols_tr<DK>(Qt, qb * 32 + mm * 16, ct * 32, lane), dsf, dkT[ct], 0, 0, 0);
+              TR_AHEAD ? qtr[mm][ct] : frag_cols_tr<DK>(Qt, qb * 32 + mm * 16, ct * 32, lane), dsf, dkT[ct], 0, 0, 0);
         }
       }
     }
