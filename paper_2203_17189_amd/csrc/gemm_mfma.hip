@@ -2,8 +2,10 @@
 //
 //   C[m,n] = sum_s sum_k A_s(m,k) B_s(n,k)
 //
-// Tiling: workgroup tile BM x BN, k-tiles of 32, WM x WN wavefronts, each wave owns
-// (BM/WM) x (BN/WN) as 32x32 MFMA tiles.
+// Tiling: workgroup tile BM x BN, k-tiles of BK, WM x WN wavefronts, each wave owns
+// (BM/WM) x (BN/WN) as 32x32 MFMA tiles.  BK = 64 in two stages for the large k-contiguous problems (a
+// DMA request then covers a whole 128-byte line of a row; with 64-byte rows the L1 still spends a
+// line's worth of time per request), BK = 32 in three to five stages elsewhere.
 //
 // Data path: global -> LDS directly (global_load_lds_dwordx4: every lane fetches 16 bytes, a wave
 // fills 1 KB of contiguous LDS), NS stages deep.  Global load latency on this part is on the order
@@ -12,7 +14,7 @@
 // Because the DMA writes LDS linearly, the bank-conflict swizzle is applied on the global side: the
 // lane that owns LDS slot (row, physical chunk) fetches the logical chunk that belongs there.
 // Two operand layouts:
-//   k-contiguous (A[m][k]):  LDS rows of 32 k (64 B, 4 chunks), read with ds_read_b128;
+//   k-contiguous (A[m][k]):  LDS rows of BK k (64 or 128 B: 4 or 8 chunks), read with ds_read_b128;
 //   m-contiguous (A[k][m]):  LDS rows of BM m, 32-byte granules swizzled by k, read with the LDS
 //                            transpose load ds_read_b64_tr_b16 (two per MFMA operand).
 // The compiler does not see these DMA writes; ordering is explicit: s_waitcnt vmcnt(n) + s_barrier
