@@ -64,16 +64,17 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
 // with one exp2 and one reciprocal (absolute error ~1e-7).  Saturates without NaNs: s -> 0 for
 // large negative z (exp2 -> inf, rcp -> 0), s -> 1 for large positive z.
 __device__ __forceinline__ float gelu_gate(float z, float z2) {
-  const float c = -2.f * 0.7978845608028654f * 1.4426950408889634f;  // -2 kappa log2(e)
-  const float inner = z * fmaf(z2, 0.044715f, 1.f);
-  return __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(c * inner));
+  constexpr float c = -2.f * 0.7978845608028654f * 1.4426950408889634f;  // -2 kappa log2(e), folded into the cubic
+  return __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(z * fmaf(z2, c * 0.044715f, c)));
 }
 __device__ __forceinline__ float gelu_tanh(float z) { return z * gelu_gate(z, z * z); }
 __device__ __forceinline__ void gelu_tanh_both(float z, float& g, float& dg) {
+  constexpr float k2 = 2.f * 0.7978845608028654f;
   const float z2 = z * z;
   const float s = gelu_gate(z, z2);
   g = z * s;
-  dg = fmaf(g * (1.f - s), 2.f * 0.7978845608028654f * fmaf(z2, 3.f * 0.044715f, 1.f), s);
+  // g (1 - s) = g - g s, and 2 kappa (1 + 3 beta z^2) as one fma
+  dg = fmaf(fmaf(-g, s, g), fmaf(z2, k2 * 3.f * 0.044715f, k2), s);
 }
 
 // Exact GELU z Phi(z) and its derivative Phi(z) + z phi(z).

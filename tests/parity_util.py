@@ -27,18 +27,26 @@ STATED_BF16 = (2e-2, 2e-3)
 #     standard deviations of the ratio of two n-element means of half-normal-like values,
 #     3 * sqrt(2) * 0.756 / sqrt(n) = 3.2 / sqrt(n)  (n = 64 for a 32 x 2 bias table: 1.65; n >= 1e5: 1.26);
 #   maximum: an extreme value, set by the handful of elements with the largest noise, so it differs between
-#     two samples by tens of percent whatever the tensor's size (CPU: 1.5 to 1.7 between six samples at 64 and
-#     at 65536 elements; device / floor over some 1500 checked tensors of blocks, decoder layers and stacks:
-#     median 1.00, 99th percentile 1.5, largest 1.9): MARGIN_MAX = 2.
+#     two samples by tens of percent (CPU: 1.5 to 1.7 between six samples at 64 and at 65536 elements).
+#     Device / floor over 1487 checked tensors of blocks, decoder layers and stacks: median 1.00 throughout;
+#     tensors of 1e5 elements or more: 99th percentile 1.37, largest 1.49; smaller ones (scales, tables, the
+#     weights of the small test shapes): 99th percentile 1.64, largest 1.94 -- close to log-normal with
+#     sigma = 0.21, for which a margin of 2 lies 3.3 sigma out: with some 500 such checks per run one of them
+#     crosses it in every few new realisations of the noise (it happened: a change of rounding order in the
+#     GELU moved one 768-element scale gradient of a 12-layer stack from 1.73 to 2.2).  Hence MARGIN_MAX = 2 for
+#     n >= 1e5 (5 sigma of the tighter spread there) and 2.5 below (4.4 sigma: one false alarm in a few hundred
+#     runs).  The mean margins are what holds the kernels to the floor.
 MARGIN = 1.25
 MARGIN_MAX = 2.0
+MARGIN_MAX_SMALL = 2.5   # tensors of fewer than 1e5 elements
 # Ungated ReLU feed-forward: a pre-activation within rounding distance of zero takes one branch on the
 # device and the other in float64, and each such unit changes its gradient by its full size.  The error of
 # every gradient upstream of the activation is a sum over these discrete events (about 0.3 % of the units);
 # which units flip differs between two samples: the mean gets 1.5 instead of 1.25, the maximum (a single
-# flipped unit) 2.5.
+# flipped unit) half a unit more than without it.
 MARGIN_RELU_MEAN = 1.5
 MARGIN_RELU_MAX = 2.5
+MARGIN_RELU_MAX_SMALL = 3.0
 
 
 def mean_margin(n: int, relu: bool = False) -> float:
@@ -46,7 +54,9 @@ def mean_margin(n: int, relu: bool = False) -> float:
 
 
 def max_margin(n: int, relu: bool = False) -> float:
-    return MARGIN_RELU_MAX if relu else MARGIN_MAX
+    if n >= 100000:
+        return MARGIN_RELU_MAX if relu else MARGIN_MAX
+    return MARGIN_RELU_MAX_SMALL if relu else MARGIN_MAX_SMALL
 
 
 def tol_from_floor(floor, n: int = 1 << 30, relu: bool = False):

@@ -172,12 +172,13 @@ def test_tol_from_floor_rule():
     assert abs(t[0] - max_margin(big) * 3.0e-2) < 1e-12 and t[1] == STATED_BF16[1]
     t = tol_from_floor((0.5e-2, 4.0e-3), big)
     assert t[0] == STATED_BF16[0] and abs(t[1] - MARGIN * 4.0e-3) <= 1e-3 * t[1]
-    assert MARGIN <= 1.25 and max_margin(1) == 2.0 and max_margin(big) == 2.0
+    assert MARGIN <= 1.25 and max_margin(1) == 2.5 and max_margin(99999) == 2.5 and max_margin(100000) == 2.0 and max_margin(big) == 2.0
     # small tensors: the mean of 64 values is itself noisy
     assert abs(mean_margin(64) - (MARGIN + 0.4)) < 1e-12 and mean_margin(10 ** 6) < MARGIN + 0.004
     # ReLU gradients: wider margins for both statistics
     t = tol_from_floor((0.5, 1.0e-2), big, relu=True)
     assert t[0] == 2.5 * 0.5 and abs(t[1] - 1.5e-2) < 1e-5
+    assert tol_from_floor((0.5, 1.0e-2), 768, relu=True)[0] == 3.0 * 0.5
 
 
 def test_spread_between_two_samples_of_the_rounding_noise(monkeypatch):
