@@ -555,16 +555,32 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_mfma_kernel(GemmDesc 
             }
           }
         } else {
-          // plain store: one copy with its two properties read at run time.  Without auxiliary loads to wait for,
-          // the straight-line copies let the compiler pull every staged read to the front, which spills
-          // (measured: 9 % slower), while the per-instruction tests cost this short epilogue nothing.
+          // plain store
+          if (e.act == ACT_RELU) {
 #define T5MI_EPI_AF 0
 #define T5MI_EPI_OB 2
-#define T5MI_EPI_SP 2
+#define T5MI_EPI_SP 1
 #include "gemm_epilogue_rows.inc"
 #undef T5MI_EPI_AF
 #undef T5MI_EPI_OB
 #undef T5MI_EPI_SP
+          } else if (e.out_type == IN_BF16) {
+#define T5MI_EPI_AF 0
+#define T5MI_EPI_OB 1
+#define T5MI_EPI_SP 0
+#include "gemm_epilogue_rows.inc"
+#undef T5MI_EPI_AF
+#undef T5MI_EPI_OB
+#undef T5MI_EPI_SP
+          } else {
+#define T5MI_EPI_AF 0
+#define T5MI_EPI_OB 0
+#define T5MI_EPI_SP 0
+#include "gemm_epilogue_rows.inc"
+#undef T5MI_EPI_AF
+#undef T5MI_EPI_OB
+#undef T5MI_EPI_SP
+          }
         }
       }
       return;
