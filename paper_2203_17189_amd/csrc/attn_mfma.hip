@@ -89,6 +89,13 @@ struct TileDma {
 };
 
 // All DMA issued so far has landed, this wave's LDS traffic is complete, and every wave is here.
+// 64 floats global -> LDS, one per lane (global_load_lds_dword): lane L fetches 4 bytes at sbase + voff and they
+// land at LDS address lds_addr + 4*L.  Same ordering rules as the 1 KB form.
+__device__ __forceinline__ void dma_64f(uint32_t lds_addr, const void* sbase, uint32_t voff) {
+  lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_addr), "v"(voff), "s"(sbase));
+}
+
 __device__ __forceinline__ void dma_wait_barrier() {
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
@@ -218,6 +225,10 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnIO io, const 
     const bf16* qrow = (const bf16*)io.q + ((size_t)b * S + i_ld) * ldq + h * DK;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qrow + kk * 16 + g * 8);
+    // (an empty use: the wait for these loads belongs here, not at their first use inside the loop, where it
+    // would also wait for the tile DMA of every iteration -- see the dk/dv kernel)
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) asm volatile("" ::"v"(qf[kk]));
   }
   if constexpr (BIAS) {
     const float* dgh = diag + (size_t)h * (2 * S - 1);
@@ -423,11 +434,19 @@ __global__ __launch_bounds__(256, DK == 64 && !DROP ? 3 : 2) void attn_bwd_dq_mf
 #pragma unroll
       for (int e = 0; e < 8; ++e) dsum = fmaf((float)of[e], (float)dof[kk][e], dsum);
     }
+    // (an empty use: see the forward kernel)
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) asm volatile("" ::"v"(qf[kk]), "v"(dof[kk]));
   }
   dsum += __shfl_xor(dsum, 32, 64);
   const size_t srow = ((size_t)b * a.H + h) * S + i_ld;
-  if (g == 0 && q_ok) dvec[srow] = dsum;
-  const float nlse2 = -lse[srow] * kLog2e, ndv = -dsum;
+  // for the dk/dv kernel, which stages them per query tile by DMA: -dvec, and behind it -lse / scale
+  const float lse_q = lse[srow];
+  if (g == 0 && q_ok) {
+    dvec[srow] = -dsum;
+    dvec[(size_t)a.B * a.H * S + srow] = lse_q * (-1.f / a.scale);
+  }
+  const float nlse2 = -lse_q * kLog2e, ndv = -dsum;
   uint32_t k1 = 0;  // dropout row key of this lane's query
   if constexpr (DROP) k1 = drop_row_key(a.drop, (uint32_t)srow);
   // dP of a kept probability carries the factor 1/(1 - rate); that of a dropped one is zero
@@ -686,6 +705,12 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
       kf[kk] = *reinterpret_cast<const bf16x8*>(krow + kk * 16 + g * 8);
       vf[kk] = *reinterpret_cast<const bf16x8*>(vrow + kk * 16 + g * 8);
     }
+    // The compiler waits for these loads where they are first used, and that is inside the loop: its
+    // s_waitcnt vmcnt(n) there would run in every iteration and, since the counter also counts the tile DMA
+    // issued at the top of the iteration, stall the first matrix instructions until the whole DMA has landed.
+    // An empty use here moves the wait in front of the loop.
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) asm volatile("" ::"v"(kf[kk]), "v"(vf[kk]));
   }
   if constexpr (BIAS) {
     // dg[t] = bias(delta) for delta = t + j0 - (S - 1), t in [0, S + BCK - 1)
@@ -718,29 +743,41 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
   const int n_it = (S + BQ - 1) / BQ;
   (it_begin == it_tail ? tq_tail : tq).issue(lds0, base + (size_t)it_begin * BQ * ld, wave);
   (it_begin == it_tail ? tdo_tail : tdo).issue(lds0 + TILE, dobase + (size_t)it_begin * BQ * I, wave);
-  const float neg_inv_scale = -1.f / a.scale;
-  if (tid < BQ) {
-    const int qi = it_begin * BQ + tid < S ? it_begin * BQ + tid : S - 1;  // (rows past the end are masked)
-    lse_all[tid] = lse[srow + qi] * neg_inv_scale;
-    dv_all[tid] = -dvec[srow + qi];
-    if constexpr (DROP) key_all[tid] = drop_row_key(a.drop, (uint32_t)(srow + qi));
+  // The -lse / scale and -dvec slices of a query tile (written by the dq kernel) travel by DMA as well, one
+  // instruction each from waves 0 and 1.  Fetched with ordinary loads they put compiler-made vmcnt waits into
+  // the loop, and since those count the tile DMA issued just before them, every iteration waited out the
+  // whole DMA latency at its first matrix instruction.
+  const float* ndvec = dvec + srow;
+  const float* nlse = dvec + (size_t)a.B * a.H * S + srow;
+  const uint32_t lds_lse = lds0 + 2 * STG, lds_dv = lds_lse + 2 * BQ * 4;
+  auto issue_rows = [&](int stage, int q_first) __attribute__((always_inline)) {
+    const int qi = q_first + lane < S ? q_first + lane : S - 1;  // (rows past the end are masked)
+    if (wave == 0) dma_64f(lds_lse + stage * BQ * 4, nlse, (uint32_t)qi * 4u);
+    if (wave == 1) dma_64f(lds_dv + stage * BQ * 4, ndvec, (uint32_t)qi * 4u);
+  };
+  issue_rows(0, it_begin * BQ);
+  if constexpr (DROP) {
+    if (tid < BQ) {
+      const int qi = it_begin * BQ + tid < S ? it_begin * BQ + tid : S - 1;
+      key_all[tid] = drop_row_key(a.drop, (uint32_t)(srow + qi));
+    }
   }
   for (int it = it_begin; it < n_it; ++it) {
     const int q0 = it * BQ;
     const int st = (it - it_begin) & 1;
-    dma_wait_barrier();  // tile `it` landed, its lse/dvec slice is written; other stage is free
-    float nl = 0.f, nd = 0.f;
+    dma_wait_barrier();  // tile `it` and its lse / dvec slices landed; other stage is free
     uint32_t nkey = 0;
     const bool more = it + 1 < n_it;
     if (more) {
       const uint32_t nxt = lds0 + (st ^ 1) * STG;
       (it + 1 == it_tail ? tq_tail : tq).issue(nxt, base + (size_t)(q0 + BQ) * ld, wave);
       (it + 1 == it_tail ? tdo_tail : tdo).issue(nxt + TILE, dobase + (size_t)(q0 + BQ) * I, wave);
-      if (tid < BQ) {
-        const int qi = q0 + BQ + tid < S ? q0 + BQ + tid : S - 1;
-        nl = lse[srow + qi] * neg_inv_scale;
-        nd = -dvec[srow + qi];
-        if constexpr (DROP) nkey = drop_row_key(a.drop, (uint32_t)(srow + qi));
+      issue_rows(st ^ 1, q0 + BQ);
+      if constexpr (DROP) {
+        if (tid < BQ) {
+          const int qi = q0 + BQ + tid < S ? q0 + BQ + tid : S - 1;
+          nkey = drop_row_key(a.drop, (uint32_t)(srow + qi));
+        }
       }
     }
     const char* Qt = smem + st * STG;
@@ -784,6 +821,7 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pre ? qr[kk] : frag_rows<DK>(Qt, qb * 32, kk, lane), kf[kk], s, 0, 0, 0);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pre ? dr[kk] : frag_rows<DK>(Dt, qb * 32, kk, lane), vf[kk], dp, 0, 0, 0);
       }
+
       // with 128 channels (one wave per SIMD, registers to spare) the transposed Q and dO operands of the
       // dV / dK products are requested before the softmax arithmetic, which then covers their LDS
       // latency; with 64 channels the second wave on the SIMD covers it and the registers are not there
@@ -854,10 +892,8 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
         }
       }
     }
-    if (more && tid < BQ) {
-      lse_all[(st ^ 1) * BQ + tid] = nl;
-      dv_all[(st ^ 1) * BQ + tid] = nd;
-      if constexpr (DROP) key_all[(st ^ 1) * BQ + tid] = nkey;
+    if constexpr (DROP) {
+      if (more && tid < BQ) key_all[(st ^ 1) * BQ + tid] = nkey;
     }
   }
   if (j < Sk) {

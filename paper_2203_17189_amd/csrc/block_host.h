@@ -218,7 +218,7 @@ size_t carve_bwd(const Dims& D, void* base, BwdWs* w) {
   BwdWs t = {};
   t.dn = cv.take<float>((size_t)D.T * D.d * 4);
   t.dh = cv.take<float>((size_t)D.T * D.d * 4);
-  t.dvec = cv.take<float>((size_t)D.B * D.H * D.S * 4);
+  t.dvec = cv.take<float>((size_t)2 * D.B * D.H * D.S * 4);  // rowsum(dO * O), and the forward's lse rescaled, per query
   t.ddiag = cv.take<float>((size_t)D.H * (2 * D.S - 1) * 4);
   t.dg_partial = cv.take<float>((size_t)rmsnorm_bwd_partial_rows((int)D.T) * D.d * 4);
   t.dh_lp = cv.take(D.ty == IN_BF16 ? (size_t)D.T * D.d * D.es : 0);

@@ -173,8 +173,9 @@ hipError_t launch_attn_fwd_mfma(const AttnIO& io, const float* diag, void* c, fl
 // Whether the backward kernels take this problem with `far` (smallest distance in the saturated last
 // bucket); otherwise the simple backward is used (same saved tensors).
 bool attn_bwd_mfma_fits(const AttnDims& a, int far);
-// phase 1: dq, dvec = rowsum(dO * O) and the bias-gradient diagonals, ADDED into ddiag (the caller clears
-// it); phase 2: dk, dv (reads dvec, so it runs after phase 1).
+// phase 1: dq, the per-query scratch and the bias-gradient diagonals, ADDED into ddiag (the caller clears
+// it); phase 2: dk, dv (reads the scratch, so it runs after phase 1).  dvec here is 2 x [B,H,S] floats:
+// -rowsum(dO * O), then -lse / scale, the two per-query constants the dk/dv kernel stages by DMA.
 // ddiag_part (phase 1, with bias; nullable): when given, at least attn_ddiag_part_bytes(); the workgroups then
 // write their bias-gradient windows there and a second kernel adds them into ddiag in a fixed order
 // (bit-reproducible) instead of meeting in float atomics.
