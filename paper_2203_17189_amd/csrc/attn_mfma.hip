@@ -171,16 +171,31 @@ __device__ __forceinline__ void fill_bias_slice(float* dg, const float* __restri
 // Registers R.. of a 32x32 ds sub-tile (S^T layout), each rotated across the 32 lanes of its half by
 // its key offset, summed into `tot`; `lo` gets the part whose source query did not wrap around
 // (lp = 31 - query index of the receiving lane).  The rotation amount must be an immediate.
+// The rotations are issued in groups of eight before any of their results is used: one at a time, each
+// is followed by a wait for its trip through the LDS crossbar.
 template <int R>
-__device__ __forceinline__ void diag_accum(const f32x16& ds, int lp, float& lo, float& tot) {
-  if constexpr (R < 16) {
-    constexpr int kj0 = ((R >> 2) << 3) + (R & 3);  // key offset of register R (without the half's + 4)
-    const float x = ds[R];  // (a plain float first: bit-casting the vector element itself picks element 0)
-    const float v = __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, x), 0xC000 | (kj0 << 5)));
-    lo += lp >= kj0 ? v : 0.f;
-    tot += v;
-    diag_accum<R + 1>(ds, lp, lo, tot);
+__device__ __forceinline__ float diag_rot(const f32x16& ds) {
+  constexpr int kj0 = ((R >> 2) << 3) + (R & 3);  // key offset of register R (without the half's + 4)
+  const float x = ds[R];  // (a plain float first: bit-casting the vector element itself picks element 0)
+  return __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, x), 0xC000 | (kj0 << 5)));
+}
+template <int R0>
+__device__ __forceinline__ void diag_accum8(const f32x16& ds, int lp, float& lo, float& tot) {
+  const float v0 = diag_rot<R0>(ds), v1 = diag_rot<R0 + 1>(ds), v2 = diag_rot<R0 + 2>(ds), v3 = diag_rot<R0 + 3>(ds);
+  const float v4 = diag_rot<R0 + 4>(ds), v5 = diag_rot<R0 + 5>(ds), v6 = diag_rot<R0 + 6>(ds), v7 = diag_rot<R0 + 7>(ds);
+  __builtin_amdgcn_sched_barrier(0);
+  const float v[8] = {v0, v1, v2, v3, v4, v5, v6, v7};
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    const int r = R0 + q;
+    const int kj0 = ((r >> 2) << 3) + (r & 3);
+    lo += lp >= kj0 ? v[q] : 0.f;
+    tot += v[q];
   }
+}
+__device__ __forceinline__ void diag_accum(const f32x16& ds, int lp, float& lo, float& tot) {
+  diag_accum8<0>(ds, lp, lo, tot);
+  diag_accum8<8>(ds, lp, lo, tot);
 }
 
 // Number of 32-key blocks on each side of a wave's queries whose diagonals are resolved one by one in
@@ -502,10 +517,18 @@ __global__ __launch_bounds__(256, DK == 64 && !DROP ? 3 : 2) void attn_bwd_dq_mf
       // than the third wave per SIMD they displace is worth (measured).
       float bias[16];
       if constexpr (BIAS) {
+        if (j0s + 32 <= Sk) {
+          // every key of the sub-tile exists: one address per lane and sixteen constant offsets (with the
+          // clamp below each value costs four address instructions, a third of the kernel's vector work)
+          const float* bp = dg + (dg_base + j0s + (g << 2));
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int j = j0s + ((r >> 2) << 3) + (g << 2) + (r & 3);
-          bias[r] = dg[dg_base + (j < Sk ? j : Sk - 1)];  // (keys past the end are masked below)
+          for (int r = 0; r < 16; ++r) bias[r] = bp[((r >> 2) << 3) + (r & 3)];
+        } else {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int j = j0s + ((r >> 2) << 3) + (g << 2) + (r & 3);
+            bias[r] = dg[dg_base + (j < Sk ? j : Sk - 1)];  // (keys past the end are masked below)
+          }
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -549,7 +572,7 @@ __global__ __launch_bounds__(256, DK == 64 && !DROP ? 3 : 2) void attn_bwd_dq_mf
         far_pos += t;
       } else {
         float lo = 0.f, tot = 0.f;
-        diag_accum<0>(sT, 31 - i_lw, lo, tot);
+        diag_accum(sT, 31 - i_lw, lo, tot);
         float* slot = ddgw + ((j0s - i_w0) / 32 + nb) * 32;
         slot[0] += lo;
         slot[32] += tot - lo;
