@@ -704,7 +704,9 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
   float* lse_all = reinterpret_cast<float*>(smem + 2 * STG);  // [2 stages][BQ]  -lse / scale
   float* dv_all = lse_all + 2 * BQ;                           // [2 stages][BQ]  -dvec
   uint32_t* key_all = reinterpret_cast<uint32_t*>(dv_all + 2 * BQ);  // [2 stages][BQ] dropout row keys (DROP only)
-  float* dg = dv_all + 2 * BQ + (DROP ? 2 * BQ : 0);          // [S + BCK - 1] log2 units (BIAS only)
+  // [-BQ, S + BCK - 1) log2 units (BIAS only); the BQ entries in front are only ever read for queries past the
+  // end of a ragged last tile, whose probabilities are set to zero
+  float* dg = dv_all + 2 * BQ + (DROP ? 2 * BQ : 0) + BQ;
 
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -743,6 +745,7 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
       idx = idx > 2 * S - 2 ? 2 * S - 2 : idx;
       dg[t] = dgh[idx] * kLog2e;
     }
+    if (tid < BQ) dg[tid - BQ] = 0.f;
   }
   const float sc = a.scale * kLog2e;
   // dg index of (query i, key j): (j - i) - (j0 - (S-1)) = j_loc + (S - 1 - i)
@@ -817,13 +820,14 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
       // channels the extra live registers would cost the third wave per SIMD, which hides more)
       constexpr bool HOIST = BIAS && DK == 128;
       float bias[16];
+      // Bias of (query i, key j) sits at dg[j_loc + S - 1 - i].  Where every query of the tile exists the sixteen
+      // values of a lane are one pointer and constant offsets: register r belongs to query
+      // q0 + qb*32 + 4g + c_r with c_r = 8*(r/4) + r%4 <= 27, so bq[27 - c_r] with bq 27 below the first.
+      // (a query past the end of a ragged tile reads at most BQ - 1 entries below dg[0]: the padding)
+      const float* bq = dg + (j_loc + S - 1 - q0 - qb * 32 - (g << 2) - 27);
       if constexpr (HOIST) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-        {
-          const int i = q0 + qb * 32 + ((r >> 2) << 3) + (g << 2) + (r & 3);
-          bias[r] = dg[j_loc + (S - 1 - (i < S ? i : S - 1))];
-        }
+        for (int r = 0; r < 16; ++r) bias[r] = bq[27 - (((r >> 2) << 3) + (r & 3))];
       }
       f32x16 s, dp;
       // likewise the row operands of the tile's second sub-tile, requested before the dV / dK products of
@@ -866,8 +870,8 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
         for (int r = 0; r < 16; ++r) {
           const int il = qb * 32 + ((r >> 2) << 3) + (g << 2) + (r & 3);
           const int i = q0 + il;
-          const int ib = i < S ? i : S - 1;  // (a masked query's bias slot may lie outside the slice)
-          float p = BIAS ? fast_exp2(fmaf(s[r], sc, HOIST ? bias[r] : dg[j_loc + (S - 1 - ib)])) : fast_exp2(s[r] * sc);
+          float p = BIAS ? fast_exp2(fmaf(s[r], sc, HOIST ? bias[r] : bq[27 - (((r >> 2) << 3) + (r & 3))]))
+                         : fast_exp2(s[r] * sc);
           if ((CAUSAL && j > i) || i >= S) p = 0.f;
           if constexpr (DROP) {
             const bool keep = mix32(key_s[il] ^ (uint32_t)j) >= a.drop.thr;
@@ -883,7 +887,8 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
         for (int r = 0; r < 16; ++r) {
           const int il = qb * 32 + ((r >> 2) << 3) + (g << 2) + (r & 3);
           const int i = q0 + il;
-          const float p = BIAS ? fast_exp2(fmaf(s[r], sc, HOIST ? bias[r] : dg[j_loc + (S - 1 - i)])) : fast_exp2(s[r] * sc);
+          const float p = BIAS ? fast_exp2(fmaf(s[r], sc, HOIST ? bias[r] : bq[27 - (((r >> 2) << 3) + (r & 3))]))
+                               : fast_exp2(s[r] * sc);
           if constexpr (DROP) {
             const bool keep = mix32(key_s[il] ^ (uint32_t)j) >= a.drop.thr;
             s[r] = keep ? p : 0.f;
@@ -980,7 +985,7 @@ hipError_t bwd_launch(const AttnIO& io, const void* c, const void* dc, const flo
   }
   if (phase == 2) {
     auto kern = attn_bwd_dkv_mfma_kernel<DK, CAUSAL, BIAS, DROP>;
-    const size_t lds = 4 * 64 * DK * 2 + sizeof(float) * (256 + (DROP ? 128 : 0) + (BIAS ? a.S + 127 : 0));
+    const size_t lds = 4 * 64 * DK * 2 + sizeof(float) * (256 + (DROP ? 128 : 0) + (BIAS ? 64 + a.S + 127 : 0));
     if ((e = set_lds(kern, lds)) != hipSuccess) return e;
     kern<<<dim3(((a.Sk + 127) / 128) * a.H * a.B), 256, lds, st>>>(io, (const bf16*)dc, diag, lse, dvec, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
