@@ -704,7 +704,15 @@ void wgrad_plan(const GemmDesc& g, const GemmEpi& e, int ngr, bool& big, int& sp
   for (int sp = 1; sp <= 32; ++sp) {
     if (sp > 1 && nk / sp < 8) break;
     const int64_t wgs = tiles * sp, slots = 256 * per_cu;
-    const double eff = (double)wgs / (double)(((wgs + slots - 1) / slots) * slots) - 0.012 * sp;
+    const int64_t rounds = (wgs + slots - 1) / slots;
+    double eff;
+    if (big) {
+      // time = rounds x (a workgroup's k-tiles + its epilogue); the epilogue of a 256x256 slice (65536 float
+      // atomics beside those of 255 other workgroups) costs about as much as 12 k-tiles of 64 (measured)
+      eff = 1.0 / ((double)rounds * ((double)nk / sp + 12.0));
+    } else {
+      eff = (double)wgs / (double)(rounds * slots) - 0.012 * sp;
+    }
     if (eff > best) { best = eff; split_k = sp; }
   }
   (void)e;
