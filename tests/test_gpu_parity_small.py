@@ -283,9 +283,13 @@ SMALL_BF16 = [
                    attn_scale=128 ** -0.5),
     SI.BlockConfig("bf16_enc_s33_b8_d20", 19, batch=2, seq=33, d_model=64, n_heads=1, d_kv=64, d_ff=64,
                    num_buckets=8, max_distance=20, attn_scale=64 ** -0.5),
+    # the longest sequence the fused attention takes, less one: every tile count at its maximum, and a ragged tail
+    # (the oracle and the floor model materialise 8191 x 8191 scores: about a minute on the host)
+    SI.BlockConfig("bf16_dec_s8191", 18, batch=1, seq=8191, d_model=64, n_heads=1, d_kv=64, d_ff=64, causal=True,
+                   dtype="bf16", attn_scale=64 ** -0.5),
 ]
 RAGGED_MFMA = ("bf16_enc_s114", "bf16_dec_s114", "bf16_enc_s200_dk128", "bf16_dec_s200", "bf16_enc_s1000",
-               "bf16_dec_s1000_dk128", "bf16_enc_s33_b8_d20")
+               "bf16_dec_s1000_dk128", "bf16_enc_s33_b8_d20", "bf16_dec_s8191")
 
 
 def test_block_bf16_accumulate_flag():
