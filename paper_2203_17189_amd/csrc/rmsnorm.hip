@@ -42,7 +42,10 @@ __device__ __forceinline__ void store_vec(T* __restrict__ p, const float (&v)[VE
 
 constexpr int kNormWaves = 4;
 
-template <typename TX, typename TO, int VEC>
+// NV > 0: the row (NV vectors of VEC columns per lane, d <= 64 * VEC * NV) stays in registers between the sum of
+// squares and the scaling, so that it is read once; read a second time it came from the fabric again (the counters
+// showed twice the algorithmic bytes).  NV == 0: any width, two passes over the row.
+template <typename TX, typename TO, int VEC, int NV>
 __global__ __launch_bounds__(kNormWaves * 64) void rmsnorm_fwd_kernel(
     const TX* __restrict__ x, const TO* __restrict__ g, TO* __restrict__ n, float* __restrict__ r, int T,
     int d, float eps) {
@@ -51,24 +54,51 @@ __global__ __launch_bounds__(kNormWaves * 64) void rmsnorm_fwd_kernel(
   const float inv_d = 1.f / (float)d;
   for (int row = blockIdx.x * kNormWaves + wave; row < T; row += gridDim.x * kNormWaves) {
     const TX* xr = x + (size_t)row * d;
-    float ss = 0.f;
-    for (int c = lane * VEC; c < d; c += 64 * VEC) {
-      float v[VEC];
-      load_vec<TX, VEC>(xr + c, v);
-#pragma unroll
-      for (int i = 0; i < VEC; ++i) ss += v[i] * v[i];
-    }
-    ss = wave_sum(ss);
-    const float rr = rsqrtf(ss * inv_d + eps);
-    if (lane == 0) r[row] = rr;
     TO* nr = n + (size_t)row * d;
-    for (int c = lane * VEC; c < d; c += 64 * VEC) {
-      float v[VEC], gg[VEC], o[VEC];
-      load_vec<TX, VEC>(xr + c, v);
-      load_vec<TO, VEC>(g + c, gg);
+    float ss = 0.f;
+    if constexpr (NV > 0) {
+      float xv[NV][VEC];
 #pragma unroll
-      for (int i = 0; i < VEC; ++i) o[i] = v[i] * rr * gg[i];
-      store_vec<TO, VEC>(nr + c, o);
+      for (int j = 0; j < NV; ++j) {
+        const int c = (j * 64 + lane) * VEC;
+        if (c < d) {
+          load_vec<TX, VEC>(xr + c, xv[j]);
+#pragma unroll
+          for (int i = 0; i < VEC; ++i) ss += xv[j][i] * xv[j][i];
+        }
+      }
+      ss = wave_sum(ss);
+      const float rr = rsqrtf(ss * inv_d + eps);
+      if (lane == 0) r[row] = rr;
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        const int c = (j * 64 + lane) * VEC;
+        if (c < d) {
+          float gg[VEC], o[VEC];
+          load_vec<TO, VEC>(g + c, gg);
+#pragma unroll
+          for (int i = 0; i < VEC; ++i) o[i] = xv[j][i] * rr * gg[i];
+          store_vec<TO, VEC>(nr + c, o);
+        }
+      }
+    } else {
+      for (int c = lane * VEC; c < d; c += 64 * VEC) {
+        float v[VEC];
+        load_vec<TX, VEC>(xr + c, v);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) ss += v[i] * v[i];
+      }
+      ss = wave_sum(ss);
+      const float rr = rsqrtf(ss * inv_d + eps);
+      if (lane == 0) r[row] = rr;
+      for (int c = lane * VEC; c < d; c += 64 * VEC) {
+        float v[VEC], gg[VEC], o[VEC];
+        load_vec<TX, VEC>(xr + c, v);
+        load_vec<TO, VEC>(g + c, gg);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) o[i] = v[i] * rr * gg[i];
+        store_vec<TO, VEC>(nr + c, o);
+      }
     }
   }
 }
@@ -96,6 +126,8 @@ __global__ __launch_bounds__(kNormWaves * 64) void rmsnorm_bwd_kernel(
     const float* dnr = dn + (size_t)row * d;
     const float rr = r[row];
     float dot = 0.f;
+    // x * r and dn * g of the row stay in registers for the second pass: x and dn are read once
+    float xh[NV][VEC], dgn[NV][VEC];
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       const int c = (j * 64 + lane) * VEC;
@@ -106,9 +138,10 @@ __global__ __launch_bounds__(kNormWaves * 64) void rmsnorm_bwd_kernel(
         load_vec<TG, VEC>(g + c, gv);
 #pragma unroll
         for (int i = 0; i < VEC; ++i) {
-          const float xh = xv[i] * rr;
-          dgacc[j][i] += dv[i] * xh;
-          dot += dv[i] * gv[i] * xh;
+          xh[j][i] = xv[i] * rr;
+          dgn[j][i] = dv[i] * gv[i];
+          dgacc[j][i] += dv[i] * xh[j][i];
+          dot += dgn[j][i] * xh[j][i];
         }
       }
     }
@@ -117,10 +150,7 @@ __global__ __launch_bounds__(kNormWaves * 64) void rmsnorm_bwd_kernel(
     for (int j = 0; j < NV; ++j) {
       const int c = (j * 64 + lane) * VEC;
       if (c < d) {
-        float xv[VEC], dv[VEC], gv[VEC], rv[VEC], o[VEC];
-        load_vec<TX, VEC>(xr + c, xv);
-        load_vec<float, VEC>(dnr + c, dv);
-        load_vec<TG, VEC>(g + c, gv);
+        float rv[VEC], o[VEC];
         if (resid) {
           load_vec<TR, VEC>(resid + (size_t)row * d + c, rv);
         } else {
@@ -128,7 +158,7 @@ __global__ __launch_bounds__(kNormWaves * 64) void rmsnorm_bwd_kernel(
           for (int i = 0; i < VEC; ++i) rv[i] = 0.f;
         }
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) o[i] = rv[i] + rr * (dv[i] * gv[i] - xv[i] * rr * dot);
+        for (int i = 0; i < VEC; ++i) o[i] = rv[i] + rr * (dgn[j][i] - xh[j][i] * dot);
         if (out_f32) store_vec<float, VEC>(out_f32 + (size_t)row * d + c, o);
         if (out_lp) store_vec<TL, VEC>(out_lp + (size_t)row * d + c, o);
       }
@@ -183,12 +213,20 @@ hipError_t fwd_dispatch(const void* x, const void* g, void* n, float* r, int T, 
                         hipStream_t st) {
   int grid = ceil_div(T, kNormWaves);
   if (grid > 8192) grid = 8192;
-  if (d % 8 == 0)
-    rmsnorm_fwd_kernel<TX, TO, 8><<<grid, kNormWaves * 64, 0, st>>>((const TX*)x, (const TO*)g, (TO*)n, r, T,
-                                                                     d, eps);
-  else
-    rmsnorm_fwd_kernel<TX, TO, 1><<<grid, kNormWaves * 64, 0, st>>>((const TX*)x, (const TO*)g, (TO*)n, r, T,
-                                                                     d, eps);
+#define T5MI_FWD(VEC, NV)                                                                                          \
+  rmsnorm_fwd_kernel<TX, TO, VEC, NV><<<grid, kNormWaves * 64, 0, st>>>((const TX*)x, (const TO*)g, (TO*)n, r, T, d, \
+                                                                      eps)
+  if (d % 8 == 0) {
+    const int nv = ceil_div(d, 512);
+    if (nv <= 1) T5MI_FWD(8, 1);
+    else if (nv <= 2) T5MI_FWD(8, 2);
+    else if (nv <= 4) T5MI_FWD(8, 4);
+    else if (nv <= 8) T5MI_FWD(8, 8);
+    else T5MI_FWD(8, 0);
+  } else {
+    T5MI_FWD(1, 0);
+  }
+#undef T5MI_FWD
   return hipGetLastError();
 }
 
