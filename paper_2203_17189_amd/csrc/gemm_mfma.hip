@@ -782,7 +782,7 @@ hipError_t launch_layout(const GemmDesc& g, const GemmEpi& e, hipStream_t st) {
     // short k loops: two 256x128 workgroups per compute unit hide each other's prologue/epilogue
     // and so do the epilogue-heavy gated-GELU kernels (three outputs, or two inputs and two outputs);
     // the gated-GELU forward goes back to one 256x256 tile once k is long enough (measured: better
-    // from K = 2048, worse at K = 768) because the smaller tiles re-stream more operand data
+    // from K = 768, worse at K = 512) because the smaller tiles re-stream more operand data
     // residual epilogues into a narrow output (N < 1024: T5.1.1-Small/Base widths), measured per shape:
     // K <= 512 as below (256x128), 128x128 tiles for K up to 768 (-6..15 % at N = 768), 256x256 beyond
     // (-4..9 %)
@@ -793,7 +793,10 @@ hipError_t launch_layout(const GemmDesc& g, const GemmEpi& e, hipStream_t st) {
     }
     // the residual epilogue with dropout does not fit the 256x256 tile's register budget (it would spill)
     if (EPI_T == (EPI_RESID | EPI_DROP)) return launch_cfg<256, 128, 2, 2, A_KC, B_KC, EPI_T, 3, 2>(g, e, split_k, st);
-    if (EPI != EPI_SPLIT_F32 && (nk <= 16 || (EPI == EPI_GEGLU_FWD && nk < 24) || EPI == EPI_GEGLU_BWD ||
+    // (thresholds in units of 64 along k, measured per epilogue: plain stores and the gated-GELU forward gain
+    // 10-12 % from the 256x256 tile at K = 768 and lose 7-20 % at K = 512; the residual epilogue is indifferent
+    // up to K = 2048)
+    if (EPI != EPI_SPLIT_F32 && (((EPI == EPI_STORE || EPI == EPI_GEGLU_FWD) && nk < 12) || EPI == EPI_GEGLU_BWD ||
                                  (EPI == EPI_RESID && nk <= 32)))
       return launch_cfg<256, 128, 2, 2, A_KC, B_KC, EPI_T, 3, 2>(g, e, split_k, st);
     // k-contiguous operands: k-tiles of 64 in two stages.  A DMA instruction then covers eight whole 128-byte
