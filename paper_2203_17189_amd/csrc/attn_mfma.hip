@@ -300,6 +300,16 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnIO io, const 
         sT[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Kt, kt * 32, kk, lane), qf[kk], sT[kt],
                                                         0, 0, 0);
     }
+    if constexpr (DK == 128) {
+      // K operands requested two contraction steps ahead of the products that use them
+      __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+#pragma unroll
+      for (int q = 0; q + 3 < (BC / 32) * KS; ++q) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);
+    }
     float mx = -INFINITY;
     // only tiles that reach above the diagonal of this wave's queries pay for the mask (wave-uniform)
     // (and the tile that reaches past the last key)
@@ -540,6 +550,15 @@ __global__ __launch_bounds__(256, DK == 64 && !DROP ? 3 : 2) void attn_bwd_dq_mf
         sT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Kt, kt * 32, kk, lane), qf[kk], sT, 0, 0, 0);
         dpT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DK>(Vt, kt * 32, kk, lane), dof[kk], dpT, 0, 0, 0);
       }
+      // the K / V operands of a contraction step are requested one step ahead of the products that use them
+      // (left alone the compiler reads them right before, and every pair of products waits out an LDS round trip)
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+      for (int kk = 0; kk + 2 < KS; ++kk) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
       // sub-tile reaches above the diagonal, past the last key, or this wave holds queries past the end
       // (all wave-uniform)
       if ((CAUSAL && j0s + 31 > i_w0) || j0s + 32 > Sk || i_w0 + 32 > S) {
