@@ -442,9 +442,9 @@ def main() -> int:
     if not args.no_cpu_baseline:
         sb = args.cpu_sample_batch
         if sb <= 0:
-            # float64 numpy sustains very roughly 150 GFLOP/s on the box's 16 host cores; aim near 15 s
+            # float64 numpy sustains roughly 270 GFLOP/s on the box's 16 host cores (measured: c5_xl at batch 6 takes 8.3 s); aim near 15 s
             per_seq = total_model_flops / cfg.batch
-            sb = int(max(1, min(cfg.batch, 15.0 * 150e9 / per_seq)))
+            sb = int(max(1, min(cfg.batch, 15.0 * 270e9 / per_seq)))
         out["cpu_baseline"] = (cpu_baseline_stack(sc, sb) if sc is not None else
                                cpu_baseline_encdec(ec, sb) if ec is not None else cpu_baseline(cfg, sb))
     print(json.dumps(out))
