@@ -82,7 +82,9 @@ typedef struct {
                             reproducible to float32 rounding.  1: they are written out and added in a fixed order
                             by a second pass: every output of the backward pass is bit-reproducible, for a larger
                             workspace (the *_workspace_bytes() queries account for it) and a few percent of time.
-                            Applies to the matrix-unit kernels; y, dx (and denc) are bit-reproducible either way. */
+                            Applies to the matrix-unit kernels; y, dx (and denc) are bit-reproducible either way.
+                            In a stack it also covers the output-matrix gradient and the embedding gradient (formed
+                            per vocabulary row in position order instead of with atomics). */
 } t5_block_cfg;
 
 /* Weights, device pointers, element type cfg.dtype, row-major [in, out]. */

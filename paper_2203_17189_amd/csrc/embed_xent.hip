@@ -46,6 +46,42 @@ __global__ __launch_bounds__(256) void embed_bwd_kernel(const int32_t* __restric
   }
 }
 
+// The same sum in a fixed order: a wave owns kEmbRows consecutive vocabulary rows, scans the token ids 64 at a time
+// and, row by row, adds the rows of the positions that hold that id, lowest position first.  No other wave writes
+// those rows, so plain read-modify-write is enough and the result does not depend on timing.  The scan costs every
+// wave a pass over the ids (from L2) and one compare per owned row and chunk; it is the price of the reproducible
+// mode only.
+constexpr int kEmbRows = 8;
+template <typename T>
+__global__ __launch_bounds__(256) void embed_bwd_ordered_kernel(const int32_t* __restrict__ tok,
+                                                                const T* __restrict__ dx, float* __restrict__ dE,
+                                                                int rows, int d, int vocab) {
+  const int lane = threadIdx.x & 63;
+  const int v0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * kEmbRows;
+  if (v0 >= vocab) return;
+  for (int r0 = 0; r0 < rows; r0 += 64) {
+    const int r = r0 + lane;
+    int id = -1;
+    if (r < rows) {
+      id = tok[r];
+      id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
+    }
+    // (most chunks hold none of this wave's rows: one test for all of them first)
+    if (__ballot((unsigned)(id - v0) < (unsigned)kEmbRows) == 0) continue;
+#pragma unroll
+    for (int q = 0; q < kEmbRows; ++q) {
+      unsigned long long hit = __ballot(id == v0 + q);
+      while (hit) {
+        const int k = __ffsll((long long)hit) - 1;
+        hit &= hit - 1;
+        float* dst = dE + (size_t)(v0 + q) * d;
+        const T* src = dx + (size_t)(r0 + k) * d;
+        for (int c = lane; c < d; c += 64) dst[c] += to_f32(src[c]);
+      }
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------------------
 // Number of positions that carry a loss (0 <= target < vocab), as a float, by one workgroup in a
 // fixed order.
@@ -292,7 +328,16 @@ hipError_t launch_embed_fwd(const int32_t* tokens, const void* E, void* x, int t
 }
 
 hipError_t launch_embed_bwd(const int32_t* tokens, const void* dx, int type, float* dE, int64_t rows, int d,
-                            int vocab, hipStream_t st) {
+                            int vocab, int ordered, hipStream_t st) {
+  if (ordered) {
+    if (rows > (int64_t)1 << 30) return hipErrorInvalidValue;
+    const int grid_v = (vocab + 4 * kEmbRows - 1) / (4 * kEmbRows);
+    if (type == IN_BF16)
+      embed_bwd_ordered_kernel<bf16><<<grid_v, 256, 0, st>>>(tokens, (const bf16*)dx, dE, (int)rows, d, vocab);
+    else
+      embed_bwd_ordered_kernel<float><<<grid_v, 256, 0, st>>>(tokens, (const float*)dx, dE, (int)rows, d, vocab);
+    return hipGetLastError();
+  }
   const int grid = (int)std::min<int64_t>((rows + 3) / 4, 16384);
   if (type == IN_BF16) embed_bwd_kernel<bf16><<<grid, 256, 0, st>>>(tokens, (const bf16*)dx, dE, rows, d, vocab);
   else embed_bwd_kernel<float><<<grid, 256, 0, st>>>(tokens, (const float*)dx, dE, rows, d, vocab);

@@ -188,9 +188,11 @@ hipError_t launch_attn_bwd_mfma(const AttnIO& io, const void* c, const void* dc,
 // x[r, :] = E[tokens[r], :] (storage type); ids outside [0, vocab) are clamped into it.
 hipError_t launch_embed_fwd(const int32_t* tokens, const void* E, void* x, int type, int64_t rows, int d, int vocab,
                             hipStream_t st);
-// dE[tokens[r], :] += dx[r, :] with float32 atomics; the caller clears dE.
+// dE[tokens[r], :] += dx[r, :]; the caller clears dE.  ordered == 0: float32 atomics, one wave per token row.
+// ordered != 0: one wave per vocabulary row, which adds the rows of its tokens in position order (bit-reproducible;
+// every wave scans all the tokens).
 hipError_t launch_embed_bwd(const int32_t* tokens, const void* dx, int type, float* dE, int64_t rows, int d,
-                            int vocab, hipStream_t st);
+                            int vocab, int ordered, hipStream_t st);
 // *n_valid = number of rows with 0 <= target < vocab, as a float.
 hipError_t launch_xent_count(const int32_t* targets, int64_t rows, int vocab, float* n_valid, hipStream_t st);
 // Per row of logits [rows, ld] (V used columns): loss_rows[r] = lse - logit[target] + z_loss lse^2 (0 when

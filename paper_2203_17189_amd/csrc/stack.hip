@@ -293,7 +293,21 @@ struct Head {
   void *nf = nullptr, *logits = nullptr, *wout_t = nullptr, *scale_s = nullptr;
   float *rf = nullptr, *loss_rows = nullptr, *n_valid = nullptr, *dnf = nullptr, *dg_tmp = nullptr,
         *dg_partial = nullptr;
+  float* wg_partials = nullptr;  // reproducible mode: partial sums of the output-matrix gradient's k-slices
 };
+
+// The gradient GEMM of the output matrix (or of the tied embedding) for one chunk of tokens.
+void head_wgrad_gemm(const Head& h, const Dims& D, int tc, const void* nf_c, GemmDesc& g, GemmEpi& e) {
+  if (h.tied) {  // dE += dlogits^T nf'
+    g = gemm1(h.V, D.d, tc, h.logits, h.V, 0, nf_c, D.d, 0, D.ty);
+    e = epi(EPI_SPLIT_F32, h.d_embedding, D.d, IN_F32);
+  } else {  // dWout += nf^T dlogits
+    g = gemm1(D.d, h.V, tc, nf_c, D.d, 0, h.logits, h.V, 0, D.ty);
+    e = epi(EPI_SPLIT_F32, h.d_logits_w, h.V, IN_F32);
+  }
+  e.accumulate = 1;
+  e.aux0 = h.wg_partials;  // null unless the reproducible mode carved it
+}
 
 void carve_head(Carver& cv, Head& h, const Dims& D) {
   h.nf = cv.take((size_t)D.T * D.d * D.es);
@@ -306,6 +320,13 @@ void carve_head(Carver& cv, Head& h, const Dims& D) {
   h.dnf = cv.take<float>((size_t)D.T * D.d * 4);
   h.dg_tmp = cv.take<float>((size_t)D.d * 4);
   h.dg_partial = cv.take<float>((size_t)rmsnorm_bwd_partial_rows((int)D.T) * D.d * 4);
+  h.wg_partials = nullptr;
+  if (D.det && D.ty == IN_BF16) {
+    GemmDesc g;
+    GemmEpi e;
+    head_wgrad_gemm(h, D, h.chunk, h.nf, g, e);
+    h.wg_partials = cv.take<float>(gemm_split_partials_bytes(g, e));
+  }
 }
 
 int head_loss_and_grad(const Head& h, const Dims& D, float rms_eps, const void* x_last, const int32_t* targets,
@@ -355,15 +376,10 @@ int head_loss_and_grad(const Head& h, const Dims& D, float rms_eps, const void* 
       else g = gemm1(tc, D.d, V, h.logits, V, 1, h.embedding, D.d, 0, ty);
       T5_STEP("gemm_dnf", run_gemm(g, epi(EPI_STORE, h.dnf + (size_t)t0 * D.d, D.d, IN_F32), st));
     }
-    if (h.tied) {  // dE += dlogits^T nf'
-      GemmDesc g = gemm1(V, D.d, tc, h.logits, V, 0, nf_c, D.d, 0, ty);
-      GemmEpi e = epi(EPI_SPLIT_F32, h.d_embedding, D.d, IN_F32);
-      e.accumulate = 1;
-      T5_STEP("gemm_dlogits_w", run_gemm(g, e, st));
-    } else {  // dWout += nf^T dlogits
-      GemmDesc g = gemm1(D.d, V, tc, nf_c, D.d, 0, h.logits, V, 0, ty);
-      GemmEpi e = epi(EPI_SPLIT_F32, h.d_logits_w, V, IN_F32);
-      e.accumulate = 1;
+    {
+      GemmDesc g;
+      GemmEpi e;
+      head_wgrad_gemm(h, D, tc, nf_c, g, e);
       T5_STEP("gemm_dlogits_w", run_gemm(g, e, st));
     }
   }
@@ -502,7 +518,7 @@ int t5_stack_loss_and_grad(const t5_stack_cfg* cfg, const int32_t* tokens, const
   void* dx0 = nullptr;
   T5_SUB(layers_backward(p.S, nullptr, nullptr, acc, &dx0, st));
   T5_SUB(end_dropout(D, DROP_EMBED, dx0, D.ty, st));
-  T5_STEP("embed_bwd", launch_embed_bwd(tokens, dx0, D.ty, grads->embedding, D.T, D.d, V, st));
+  T5_STEP("embed_bwd", launch_embed_bwd(tokens, dx0, D.ty, grads->embedding, D.T, D.d, V, D.det, st));
   return T5_OK;
 }
 
@@ -560,7 +576,7 @@ int t5_encdec_loss_and_grad(const t5_encdec_cfg* cfg, const int32_t* enc_tokens,
   void* dx0 = nullptr;
   T5_SUB(layers_backward(p.Dc, p.enc_out, p.denc, acc, &dx0, st));
   T5_SUB(end_dropout(D, DROP_DEC_EMBED, dx0, ty, st));
-  T5_STEP("embed_bwd", launch_embed_bwd(dec_tokens, dx0, ty, grads->embedding, D.T, D.d, V, st));
+  T5_STEP("embed_bwd", launch_embed_bwd(dec_tokens, dx0, ty, grads->embedding, D.T, D.d, V, D.det, st));
   T5_SUB(end_dropout(E, DROP_FINAL, p.denc, IN_F32, st));
   // encoder: final norm backward (no residual term), layers, embedding
   T5_STEP("rmsnorm_bwd", launch_rmsnorm_bwd(p.E.x_of(p.E.L), ty, w->enc_final_scale, ty, p.enc_rf, p.denc, nullptr,
@@ -569,7 +585,7 @@ int t5_encdec_loss_and_grad(const t5_encdec_cfg* cfg, const int32_t* enc_tokens,
                                             p.enc_dg_partial, acc, (int)E.T, E.d, st));
   T5_SUB(layers_backward(p.E, nullptr, nullptr, acc, &dx0, st));
   T5_SUB(end_dropout(E, DROP_EMBED, dx0, ty, st));
-  T5_STEP("embed_bwd", launch_embed_bwd(enc_tokens, dx0, ty, grads->embedding, E.T, E.d, V, st));
+  T5_STEP("embed_bwd", launch_embed_bwd(enc_tokens, dx0, ty, grads->embedding, E.T, E.d, V, E.det, st));
   return T5_OK;
 }
 

@@ -73,19 +73,30 @@ def test_decoder_layer_gradients_bit_reproducible():
         assert torch.equal(outs[0][2][k], outs[1][2][k]), k
 
 
-def test_stack_layer_gradients_bit_reproducible():
-    """A stack in the reproducible mode: every layer's weight gradients, the shared bias table's and the final
-    norm's are bit-identical between two runs (the embedding gradient still meets in float atomics)."""
+@pytest.mark.parametrize("tied", [False, True], ids=["untied", "tied"])
+def test_stack_gradients_bit_reproducible(tied):
+    """A stack in the reproducible mode: every gradient -- the layers' weights, the shared bias table, the final
+    norm's scale, the output matrix (k-slices of its GEMM summed in a fixed order, chunk after chunk) and the
+    embedding (one wave per vocabulary row adds the rows of its tokens in position order; with tied logits on top
+    of the output-matrix term) -- is bit-identical between two runs, and agrees with the default mode."""
     import paper_2203_17189_amd as P
     import test_gpu_parity_stack as TS
-    sc = SI.StackConfig("stack_det", replace(TS.BF_BLK, index=58, batch=16, seq=256, deterministic=True), n_layers=3,
-                        vocab=512)
+    blk = replace(TS.BF_BLK, index=58, batch=16, seq=256, deterministic=True)
+    sc = SI.StackConfig("stack_det", blk, n_layers=3, vocab=512, tied_logits=tied)
     w, tokens, targets = TS._case(sc)
     l1, g1 = TS._run(sc, w, tokens, targets)
     l2, g2 = TS._run(sc, w, tokens, targets)
     assert l1 == l2
-    for k in ("rel_table", "final_scale"):
+    top = [k for k in g1 if k != "layers"]
+    assert "embedding" in top and ("logits_w" in top) == (not tied), top
+    for k in top:
         assert torch.equal(g1[k], g2[k]), k
     for l in range(sc.n_layers):
         for n in g1["layers"][l]:
             assert torch.equal(g1["layers"][l][n], g2["layers"][l][n]), (l, n)
+    # same sums as the default mode, in another order
+    sd = SI.StackConfig("stack_det", replace(blk, deterministic=False), n_layers=3, vocab=512, tied_logits=tied)
+    _, g0 = TS._run(sd, w, tokens, targets)
+    for k in top:
+        a, b = g1[k].float(), g0[k].float()
+        assert (a - b).abs().max().item() <= 2e-5 * (b.abs().max().item() + 1e-30), k
