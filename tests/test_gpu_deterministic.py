@@ -100,3 +100,29 @@ def test_stack_gradients_bit_reproducible(tied):
     for k in top:
         a, b = g1[k].float(), g0[k].float()
         assert (a - b).abs().max().item() <= 2e-5 * (b.abs().max().item() + 1e-30), k
+
+
+def test_encdec_gradients_bit_reproducible():
+    """The encoder-decoder pair in the reproducible mode: both token streams add into one embedding gradient (the
+    decoder's first, then the encoder's, each in position order), and every gradient is bit-identical between runs."""
+    import paper_2203_17189_amd as P
+    import test_gpu_parity_stack as TS
+    ec = SI._encdec("ec_det", 79, 2, 256, 128, 128, 2, 64, 256, 2, 2, 512,
+                    block=dict(attn_scale=64 ** -0.5, deterministic=True))
+    w = SI.make_encdec_weights(ec)
+    enc_tokens, dec_tokens, targets = SI.make_encdec_tokens(ec, ignore_fraction=0.15)
+    dw, te, td, tg = TS._ec_upload(ec, w, enc_tokens, dec_tokens, targets)
+    outs = []
+    for _ in range(2):
+        loss, g = P.t5_encdec_loss_and_grad(ec, te, td, tg, dw)
+        torch.cuda.synchronize()
+        outs.append((float(loss.item()), g))
+    assert outs[0][0] == outs[1][0]
+    g1, g2 = outs[0][1], outs[1][1]
+    for k in g1:
+        if k.endswith("_layers"):
+            for l in range(len(g1[k])):
+                for n in g1[k][l]:
+                    assert torch.equal(g1[k][l][n], g2[k][l][n]), (k, l, n)
+        else:
+            assert torch.equal(g1[k], g2[k]), k
