@@ -208,6 +208,17 @@ __host__ __device__ inline int attn_dq_window_blocks(int S, int far) {
 // entries wide (+ 4 for the upper lane half) and two sums of the saturated buckets follow it.
 __host__ __device__ inline int attn_ddiag_part_stride(int S) { return 64 * ((S + 31) / 32) + 8; }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+// max(x of this lane, x of the lane 32 away).  v_permlane32_swap exchanges lanes 32..63 of its first operand with
+// lanes 0..31 of its second: started from two copies of x, every lane then holds its own value in one of the two
+// registers and its partner's in the other.  One vector instruction through no memory, where the generic shuffle
+// is an LDS round trip (ds_bpermute) on the dependent chain of every key tile.  (The s_nop covers the wait states
+// between a vector write of the operands and the swap; the compiler's builtin for this instruction returned the
+// same half in both results when tried here, hence the assembly.)
+__device__ __forceinline__ float max_across_halves(float x) {
+  float a = x, b = x;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+  return fmaxf(a, b);
+}
 
 // ------------------------------------------------------------------------------------------------
 // Forward.  grid (ceil(S/128), H, B), 256 threads; wave w owns queries i0 + 32w + lane%32.
@@ -338,7 +349,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnIO io, const 
           mx = fmaxf(mx, s);
         }
     }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    mx = max_across_halves(mx);
     const float m_new = fmaxf(m, mx);
     const float alpha = fast_exp2(m - m_new);
     m = m_new;
