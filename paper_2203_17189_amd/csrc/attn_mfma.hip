@@ -845,10 +845,10 @@ __global__ __launch_bounds__(256, DK == 64 ? 2 : 1) void attn_bwd_dkv_mfma_kerne
 #pragma unroll
     for (int qb = 0; qb < BQ / 32; ++qb) {
       // bias values and accumulator seeds are requested before the MFMAs so that their LDS latency
-      // is hidden behind the matrix work instead of stalling the softmax arithmetic
-      // (done for 128 channels, where one wave per SIMD leaves nothing else to hide it; with 64
-      // channels the extra live registers would cost the third wave per SIMD, which hides more)
-      constexpr bool HOIST = BIAS && DK == 128;
+      // is hidden behind the matrix work instead of stalling the softmax arithmetic (read at first use they
+      // put an LDS round trip on every sub-tile's dependent chain: 651 -> 635 us at 64 channels, the sixteen
+      // registers are there at two waves per SIMD)
+      constexpr bool HOIST = BIAS;
       float bias[16];
       // Bias of (query i, key j) sits at dg[j_loc + S - 1 - i].  Where every query of the tile exists the sixteen
       // values of a lane are one pointer and constant offsets: register r belongs to query
